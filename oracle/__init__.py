@@ -1,0 +1,146 @@
+"""ctypes front end of the CPU oracle (oracle/knn_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+cpu_baseline leg of bench.py.  The GPU package never imports this module and
+this module never imports the GPU package.
+
+The oracle evaluates the plain definition of brute-force kNN (paper section
+5.2) with naive difference-form squared distances in fp64 (section 4.1) and a
+(distance, index) lexicographic order.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "knn_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_knn.so")
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, no fast-math, no FMA contraction)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        fp = ctypes.POINTER(ctypes.c_float)
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        dp = ctypes.POINTER(ctypes.c_double)
+        common = [fp, ctypes.c_int64, fp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                  ctypes.c_int32, i64p, ctypes.c_int64, i64p, dp, dp]
+        lib.oracle_knn.argtypes = common + [ctypes.c_int32]
+        lib.oracle_knn.restype = ctypes.c_int
+        lib.oracle_knn_fullsort.argtypes = common
+        lib.oracle_knn_fullsort.restype = ctypes.c_int
+        lib.oracle_sqdist.argtypes = [fp, fp, ctypes.c_int32]
+        lib.oracle_sqdist.restype = ctypes.c_double
+        lib.oracle_sqdist_expanded.argtypes = [fp, fp, ctypes.c_int32]
+        lib.oracle_sqdist_expanded.restype = ctypes.c_double
+        lib.oracle_threads_used.argtypes = [ctypes.c_int32]
+        lib.oracle_threads_used.restype = ctypes.c_int32
+        _lib = lib
+    return _lib
+
+
+def default_threads() -> int:
+    try:
+        return max(1, len(os.sched_getaffinity(0)))
+    except AttributeError:  # pragma: no cover
+        return max(1, os.cpu_count() or 1)
+
+
+def threads_used(nthreads: int | None = None) -> int:
+    return int(_load().oracle_threads_used(int(nthreads or default_threads())))
+
+
+def _as_f32_2d(a) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if a.ndim != 2:
+        raise ValueError("expected a 2-D array")
+    return a
+
+
+def _run(fn, Q, X, k, rows, extra):
+    Q = _as_f32_2d(Q)
+    X = _as_f32_2d(X)
+    if Q.shape[1] != X.shape[1]:
+        raise ValueError("Q and X differ in dimension")
+    n, d = X.shape
+    if rows is None:
+        rows_arr = None
+        nrows = Q.shape[0]
+    else:
+        rows_arr = np.ascontiguousarray(rows, dtype=np.int64)
+        nrows = rows_arr.shape[0]
+        if nrows and (rows_arr.min() < 0 or rows_arr.max() >= Q.shape[0]):
+            raise ValueError("row index out of range")
+    idx = np.empty((nrows, k), dtype=np.int64)
+    dist = np.empty((nrows, k), dtype=np.float64)
+    nxt = np.empty((nrows,), dtype=np.float64)
+    fp = ctypes.POINTER(ctypes.c_float)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = fn(Q.ctypes.data_as(fp), Q.shape[1], X.ctypes.data_as(fp), d, n, d, int(k),
+            rows_arr.ctypes.data_as(i64p) if rows_arr is not None else None, nrows,
+            idx.ctypes.data_as(i64p), dist.ctypes.data_as(dp), nxt.ctypes.data_as(dp), *extra)
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments (need 1 <= k <= n, d >= 1)")
+    return idx, dist, nxt
+
+
+def knn(Q, X, k, rows=None, nthreads: int | None = None):
+    """Heap-selection oracle.  Returns (idx int64[r,k], dist fp64[r,k], next fp64[r])."""
+    return _run(_load().oracle_knn, Q, X, k, rows, (int(nthreads or default_threads()),))
+
+
+def knn_fullsort(Q, X, k, rows=None):
+    """Definition written out: all distances, one full sort, first k."""
+    return _run(_load().oracle_knn_fullsort, Q, X, k, rows, ())
+
+
+def sqdist(q, x) -> float:
+    q = np.ascontiguousarray(q, dtype=np.float32).ravel()
+    x = np.ascontiguousarray(x, dtype=np.float32).ravel()
+    fp = ctypes.POINTER(ctypes.c_float)
+    return float(_load().oracle_sqdist(q.ctypes.data_as(fp), x.ctypes.data_as(fp), q.shape[0]))
+
+
+def sqdist_expanded(q, x) -> float:
+    q = np.ascontiguousarray(q, dtype=np.float32).ravel()
+    x = np.ascontiguousarray(x, dtype=np.float32).ravel()
+    fp = ctypes.POINTER(ctypes.c_float)
+    return float(_load().oracle_sqdist_expanded(q.ctypes.data_as(fp), x.ctypes.data_as(fp),
+                                                q.shape[0]))
+
+
+def sqdist_pairs(Q, X, qi, xj) -> np.ndarray:
+    """fp64 difference-form distance of the listed (query, point) pairs."""
+    Q = _as_f32_2d(Q)
+    X = _as_f32_2d(X)
+    qi = np.asarray(qi, dtype=np.int64).ravel()
+    xj = np.asarray(xj, dtype=np.int64).ravel()
+    out = np.empty(qi.shape[0], dtype=np.float64)
+    lib = _load()
+    fp = ctypes.POINTER(ctypes.c_float)
+    d = Q.shape[1]
+    qb = Q.ctypes.data
+    xb = X.ctypes.data
+    for p in range(qi.shape[0]):
+        out[p] = lib.oracle_sqdist(ctypes.cast(qb + 4 * d * int(qi[p]), fp),
+                                   ctypes.cast(xb + 4 * d * int(xj[p]), fp), d)
+    return out

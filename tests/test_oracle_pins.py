@@ -1,0 +1,184 @@
+"""Pins for the CPU oracle: each test checks it against something other than itself.
+
+The paper (section 5.2) gives only the definition of the result, so the pins are
+closed forms, brute force through numpy/torch library routines on tiny inputs,
+and invariants of the definition.  A dropped term, a wrong sign, a transposed
+operand, a broken tie-break or an off-by-one in the heap fails at least one.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+
+
+def np_bruteforce(Q, X, k):
+    """numpy: broadcast differences in fp64, stable argsort (ties -> lower index)."""
+    Qd = Q.astype(np.float64)
+    Xd = X.astype(np.float64)
+    D = ((Qd[:, None, :] - Xd[None, :, :]) ** 2).sum(axis=2)
+    order = np.argsort(D, axis=1, kind="stable")[:, :k]
+    return order, np.take_along_axis(D, order, axis=1), D
+
+
+@pytest.mark.parametrize("seed,m,n,d", [(0, 7, 13, 1), (1, 5, 64, 3), (2, 9, 33, 8), (3, 4, 50, 5)])
+def test_bruteforce_every_k(oracle, seed, m, n, d):
+    Q, X = W.random_case(seed, m, n, d)
+    for k in range(1, n + 1):
+        ref_idx, ref_dist, D = np_bruteforce(Q, X, k)
+        for fn in (oracle.knn, oracle.knn_fullsort):
+            idx, dist, nxt = fn(Q, X, k)
+            assert np.array_equal(idx, ref_idx), (fn.__name__, k)
+            np.testing.assert_allclose(dist, ref_dist, rtol=1e-13, atol=0)
+            if k < n:
+                ref_next = np.sort(D, axis=1)[:, k]
+                np.testing.assert_allclose(nxt, ref_next, rtol=1e-13)
+            else:
+                assert np.all(np.isinf(nxt))
+
+
+def test_ties_on_integer_grid_match_stable_argsort(oracle):
+    # small integer coordinates: distances are exact integers with many ties
+    Q, X = W.random_case(11, 20, 200, 3, kind="grid")
+    for k in (1, 2, 7, 50, 200):
+        ref_idx, ref_dist, _ = np_bruteforce(Q, X, k)
+        for fn in (oracle.knn, oracle.knn_fullsort):
+            idx, dist, _ = fn(Q, X, k)
+            assert np.array_equal(idx, ref_idx)
+            assert np.array_equal(dist, ref_dist)  # integers: exact
+
+
+def integer_line_expected(i, n, k):
+    """d=1, X[j]=j, query i: neighbours i, i-1, i+1, i-2, ... (lower index first on ties)."""
+    out = [(0, i)]
+    for step in range(1, n):
+        for j in (i - step, i + step):
+            if 0 <= j < n:
+                out.append((step * step, j))
+    out = out[:k]
+    return [j for _, j in out], [float(dd) for dd, _ in out]
+
+
+def test_closed_form_integer_line(oracle):
+    n = 41
+    X = np.arange(n, dtype=np.float32).reshape(n, 1)
+    for k in (1, 2, 3, 6, 9, n):
+        idx, dist, _ = oracle.knn(X, X, k)
+        idx2, dist2, _ = oracle.knn_fullsort(X, X, k)
+        for i in range(n):
+            e_idx, e_dist = integer_line_expected(i, n, k)
+            assert idx[i].tolist() == e_idx
+            assert dist[i].tolist() == e_dist
+            assert idx2[i].tolist() == e_idx and dist2[i].tolist() == e_dist
+
+
+def test_closed_form_scaled_orthogonal_basis(oracle):
+    # X[j] = a_j e_j  =>  D[i][j] = a_i^2 + a_j^2 (i != j), 0 (i == j)
+    n = 12
+    a = np.array([3, 1, 4, 1.5, 5, 9, 2, 6, 5.5, 3.5, 8, 7], dtype=np.float32)
+    X = np.diag(a).astype(np.float32)
+    idx, dist, _ = oracle.knn(X, X, n)
+    for i in range(n):
+        expect = sorted(((0.0 if j == i else float(a[i]) ** 2 + float(a[j]) ** 2), j) for j in range(n))
+        assert idx[i].tolist() == [j for _, j in expect]
+        np.testing.assert_allclose(dist[i], [v for v, _ in expect], rtol=1e-15)
+
+
+def test_duplicated_points_come_in_index_pairs(oracle):
+    Q, X = W.random_case(5, 6, 40, 4)
+    X2 = np.repeat(X, 2, axis=0)  # rows 2j and 2j+1 are the same point
+    k = 11
+    idx, dist, _ = oracle.knn(Q, X2, k)
+    base_idx, base_dist, _ = oracle.knn(Q, X, (k + 1) // 2)
+    for i in range(Q.shape[0]):
+        for p in range(k):
+            assert idx[i, p] == 2 * base_idx[i, p // 2] + (p % 2)
+            assert dist[i, p] == base_dist[i, p // 2]
+
+
+def test_k1_is_argmin_and_kn_is_stable_argsort(oracle):
+    Q, X = W.random_case(6, 30, 300, 6)
+    _, _, D = np_bruteforce(Q, X, 1)
+    idx, dist, _ = oracle.knn(Q, X, 1)
+    assert np.array_equal(idx[:, 0], np.argmin(D, axis=1))
+    idx, dist, _ = oracle.knn(Q, X, 300)
+    assert np.array_equal(idx, np.argsort(D, axis=1, kind="stable"))
+
+
+def test_against_torch_cdist(oracle):
+    # library routine, different code: cdist in fp64, squared, stable argsort
+    w = W.scaled(1, m=200, n=3000)
+    Q, X = W.make(w)
+    D = torch.cdist(torch.from_numpy(Q).double(), torch.from_numpy(X).double()) ** 2
+    order = torch.argsort(D, dim=1, stable=True)[:, : w.k].numpy()
+    idx, dist, nxt = oracle.knn(Q, X, w.k)
+    assert np.array_equal(idx, order)
+    np.testing.assert_allclose(dist, np.take_along_axis(D.numpy(), order, 1), rtol=1e-9)
+
+
+def test_difference_form_equals_norm_expansion(oracle):
+    # section 4.1: sum (x-y)^2 == sum x^2 + y^2 - 2xy, each side in fp64
+    Q, X = W.random_case(8, 50, 50, 16)
+    for i in range(50):
+        a = oracle.sqdist(Q[i], X[i])
+        b = oracle.sqdist_expanded(Q[i], X[i])
+        assert abs(a - b) <= 1e-12 * max(a, 1.0)
+    # and a hand-computed value
+    assert oracle.sqdist([1, 2, 3], [4, 6, 3]) == 25.0
+    assert oracle.sqdist([0.5], [-0.25]) == 0.5625
+
+
+def test_rows_sorted_and_self_distance_zero(oracle):
+    w = W.scaled(2, n=2000)
+    Q, X = W.make(w)
+    idx, dist, nxt = oracle.knn(Q, X, w.k)
+    assert np.all(np.diff(dist, axis=1) >= 0)
+    assert np.all(dist[:, 0] == 0.0)
+    assert np.array_equal(idx[:, 0], np.arange(2000))  # no duplicates in continuous data
+    assert np.all(nxt >= dist[:, -1])
+    assert np.all(dist >= 0)
+
+
+def test_permuting_points_permutes_indices(oracle):
+    Q, X = W.random_case(9, 25, 400, 5)
+    perm = np.random.Generator(np.random.PCG64(99)).permutation(400)
+    idx, dist, _ = oracle.knn(Q, X, 12)
+    idx_p, dist_p, _ = oracle.knn(Q, X[perm], 12)
+    # continuous data: no ties, so the mapped indices agree position by position
+    assert np.array_equal(perm[idx_p], idx)
+    assert np.array_equal(dist_p, dist)
+
+
+def test_translation_invariance(oracle):
+    # shift by a value exactly representable next to the data: results identical
+    Q, X = W.random_case(10, 20, 300, 4, kind="grid")
+    shift = np.float32(8.0)
+    idx, dist, _ = oracle.knn(Q, X, 9)
+    idx_s, dist_s, _ = oracle.knn(Q + shift, X + shift, 9)
+    assert np.array_equal(idx, idx_s)
+    assert np.array_equal(dist, dist_s)
+
+
+def test_row_subset_matches_full(oracle):
+    Q, X = W.random_case(12, 40, 500, 7)
+    rows = np.array([3, 3, 39, 0, 17], dtype=np.int64)
+    idx, dist, nxt = oracle.knn(Q, X, 5)
+    idx_r, dist_r, nxt_r = oracle.knn(Q, X, 5, rows=rows)
+    assert np.array_equal(idx_r, idx[rows])
+    assert np.array_equal(dist_r, dist[rows])
+    assert np.array_equal(nxt_r, nxt[rows])
+    # thread count must not change anything
+    idx_1, dist_1, _ = oracle.knn(Q, X, 5, nthreads=1)
+    assert np.array_equal(idx_1, idx) and np.array_equal(dist_1, dist)
+
+
+def test_argument_errors(oracle):
+    Q, X = W.random_case(13, 3, 10, 2)
+    with pytest.raises(ValueError):
+        oracle.knn(Q, X, 11)  # k > n
+    with pytest.raises(ValueError):
+        oracle.knn(Q, X, 0)
+    with pytest.raises(ValueError):
+        oracle.knn(Q, X[:, :1], 2)  # dimension mismatch
+    with pytest.raises(ValueError):
+        oracle.knn(Q, X, 2, rows=[5])

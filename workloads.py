@@ -1,0 +1,163 @@
+"""Seeded synthetic inputs shaped like the paper's kNN workloads.
+
+This module only draws random numbers (numpy PCG64) and names sizes.  It holds
+none of the method's arithmetic: no distances, no norms, no selection.  Both the
+CPU oracle's callers and the GPU path's callers take their inputs from here so
+that the two sides see identical bits.
+
+The five workloads follow the paper's experiment grid (section 5.2 and the
+appendix table: random data with n in {1e4, 1e6, 1e7} and d in {3, 10, 100},
+image vectors with d = 784, word-embedding-like vectors with d in 50..200) and
+the memory-limit sweep of section 5.1 / figure 1.  The image and embedding data
+sets themselves are not available; value distributions of the same structure
+(sparse non-negative pixels, clustered embeddings) stand in for them.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+
+import numpy as np
+
+SEED_BASE = 220614148
+MB = 10 ** 6  # decimal units: the paper's worked example has 125e6 fp64 values = "1GB"
+GB = 10 ** 9
+
+
+@dataclass(frozen=True)
+class Workload:
+    cfg: int
+    name: str
+    m: int
+    n: int
+    d: int
+    k: int
+    mem_limit: int
+    kind: str            # value distribution
+    q_is_x: bool = False  # queries are the data points themselves (kNN graph)
+    sweep: tuple = ()     # extra memory limits (config 5)
+
+    @property
+    def pairs(self) -> int:
+        return self.m * self.n
+
+
+WORKLOADS = {
+    1: Workload(1, "c1_random_d16", 1_000, 10_000, 16, 10, 64 * MB, "normal"),
+    2: Workload(2, "c2_pointcloud_d3", 1_000_000, 1_000_000, 3, 16, 1 * GB, "uniform", q_is_x=True),
+    3: Workload(3, "c3_imagelike_d784", 10_000, 1_000_000, 784, 10, 2 * GB, "sparse"),
+    4: Workload(4, "c4_clustered_d128", 100_000, 10_000_000, 128, 100, 8 * GB, "gmm"),
+    5: Workload(5, "c5_memsweep_d256", 50_000, 2_000_000, 256, 32, 1 * GB, "normal",
+                sweep=(128 * MB, 1 * GB, 8 * GB, 64 * GB)),
+}
+
+
+def scaled(cfg: int, m: int | None = None, n: int | None = None, **kw) -> Workload:
+    """Same distribution and d as config `cfg`, other sizes."""
+    w = WORKLOADS[cfg]
+    if w.q_is_x:
+        size = n if n is not None else (m if m is not None else w.n)
+        m = n = size
+    else:
+        m = w.m if m is None else m
+        n = w.n if n is None else n
+    return replace(w, m=m, n=n, **kw)
+
+
+def _rng(cfg: int, stream: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(SEED_BASE + 1000 * cfg + stream))
+
+
+_CHUNK = 1 << 22  # values drawn per call, bounds temporary memory
+
+
+def _fill_normal(rng, out):
+    flat = out.reshape(-1)
+    for s in range(0, flat.size, _CHUNK):
+        e = min(flat.size, s + _CHUNK)
+        rng.standard_normal(e - s, dtype=np.float32, out=flat[s:e])
+
+
+def _fill_uniform(rng, out):
+    flat = out.reshape(-1)
+    for s in range(0, flat.size, _CHUNK):
+        e = min(flat.size, s + _CHUNK)
+        rng.random(e - s, dtype=np.float32, out=flat[s:e])
+
+
+def _fill_sparse(rng, out):
+    """Entry is 0 with probability 0.8, else uniform in (0, 1]."""
+    flat = out.reshape(-1)
+    for s in range(0, flat.size, _CHUNK):
+        e = min(flat.size, s + _CHUNK)
+        keep = rng.random(e - s, dtype=np.float32) < np.float32(0.2)
+        val = np.float32(1.0) - rng.random(e - s, dtype=np.float32)
+        flat[s:e] = np.where(keep, val, np.float32(0.0))
+
+
+def _fill_gmm(rng, out, centres):
+    """Uniform mixture weights; point = centre + unit isotropic noise."""
+    rows = out.shape[0]
+    step = max(1, _CHUNK // out.shape[1])
+    for s in range(0, rows, step):
+        e = min(rows, s + step)
+        lab = rng.integers(0, centres.shape[0], size=e - s)
+        noise = rng.standard_normal((e - s, out.shape[1]), dtype=np.float32)
+        out[s:e] = centres[lab] + noise
+
+
+def gmm_centres(cfg: int, d: int, comps: int = 1000) -> np.ndarray:
+    """Component centres ~ N(0, 4 I), i.e. standard deviation 2 per coordinate."""
+    c = _rng(cfg, 2).standard_normal((comps, d), dtype=np.float32)
+    return (np.float32(2.0) * c).astype(np.float32)
+
+
+def make(w: Workload):
+    """Returns (Q, X) as C-contiguous float32 arrays; Q is X itself when q_is_x."""
+    X = np.empty((w.n, w.d), dtype=np.float32)
+    if w.kind == "normal":
+        _fill_normal(_rng(w.cfg, 0), X)
+    elif w.kind == "uniform":
+        _fill_uniform(_rng(w.cfg, 0), X)
+    elif w.kind == "sparse":
+        _fill_sparse(_rng(w.cfg, 0), X)
+    elif w.kind == "gmm":
+        centres = gmm_centres(w.cfg, w.d)
+        _fill_gmm(_rng(w.cfg, 0), X, centres)
+    else:
+        raise ValueError(w.kind)
+    if w.q_is_x:
+        return X, X
+    Q = np.empty((w.m, w.d), dtype=np.float32)
+    if w.kind == "normal":
+        _fill_normal(_rng(w.cfg, 1), Q)
+    elif w.kind == "uniform":
+        _fill_uniform(_rng(w.cfg, 1), Q)
+    elif w.kind == "sparse":
+        _fill_sparse(_rng(w.cfg, 1), Q)
+    else:
+        _fill_gmm(_rng(w.cfg, 1), Q, centres)
+    return Q, X
+
+
+def sample_rows(w: Workload, count: int) -> np.ndarray:
+    """Seeded subset of query rows (sorted, distinct) for row-level checks."""
+    count = min(count, w.m)
+    r = _rng(w.cfg, 3).choice(w.m, size=count, replace=False)
+    return np.sort(r).astype(np.int64)
+
+
+def random_case(seed: int, m: int, n: int, d: int, kind: str = "normal"):
+    """Small free-form case for the edge-case tests."""
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 7_000_000 + seed))
+    if kind == "normal":
+        X = rng.standard_normal((n, d), dtype=np.float32)
+        Q = rng.standard_normal((m, d), dtype=np.float32)
+    elif kind == "uniform":
+        X = rng.random((n, d), dtype=np.float32)
+        Q = rng.random((m, d), dtype=np.float32)
+    elif kind == "grid":  # many exact ties: small integer coordinates
+        X = rng.integers(0, 4, size=(n, d)).astype(np.float32)
+        Q = rng.integers(0, 4, size=(m, d)).astype(np.float32)
+    else:
+        raise ValueError(kind)
+    return Q, X
