@@ -1,0 +1,145 @@
+/*
+ * knn.h - C ABI of the MI355X (gfx950) exact brute-force k-nearest-neighbour
+ * library with a caller-given device-memory limit.
+ *
+ * Operation (paper section 5.2, "K-Nearest Neighbours"): for each of m query
+ * points select the k closest of n data points.  Distances are squared
+ * Euclidean, evaluated through the expansion of section 4.1
+ * (sum x^2 + y^2 - 2xy, whose largest operand is m x n instead of m x n x d);
+ * the m x n matrix itself is never stored: it is produced tile by tile and
+ * reduced on the fly to each query's k smallest, in the spirit of the
+ * generator / reducer loop of section 4.3 (figure 2, algorithm 1).  All
+ * library-owned device memory is one workspace whose size never exceeds the
+ * caller's limit; section 4.4 notes that a limit-unaware allocator can still
+ * overflow, so this library allocates nothing itself.
+ *
+ * Conventions shared by every entry point
+ *   - Row-major fp32 matrices with a leading dimension in ELEMENTS (ld >= d).
+ *   - "DEVICE" pointers are HIP device memory of the current device; "HOST"
+ *     pointers are ordinary process memory.  The library never takes ownership
+ *     of, frees or reallocates a pointer it is given.
+ *   - Byte sizes with unit suffixes are DECIMAL (1GB = 1e9 bytes), as the
+ *     paper's appendix example implies (125e6 fp64 values = "1GB").
+ *   - Result rows are ascending by (distance, index): equal distances are
+ *     ordered by the lower point index.  The paper leaves ties unspecified.
+ *   - Inputs must be finite; behaviour for NaN/Inf entries is unspecified.
+ */
+#ifndef KNN_MI355X_H
+#define KNN_MI355X_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KNN_OK = 0,
+    KNN_ERR_INVALID_ARG = 1,         /* null pointer, m<0, n<1, d<1, k<1, k>n, ld<d */
+    KNN_ERR_MEM_LIMIT_TOO_SMALL = 2, /* limit below knn_plan_t.min_limit_bytes      */
+    KNN_ERR_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes < plan.workspace_bytes      */
+    KNN_ERR_UNSUPPORTED = 4,         /* n >= 2^31 (int32 indices) or k > KNN_MAX_K  */
+    KNN_ERR_HIP = 5                  /* a HIP call or kernel launch failed          */
+} knn_status;
+
+#define KNN_MAX_K 1024
+
+/* kernel families (knn_plan_t.path) */
+#define KNN_PATH_LOWD 0 /* d <= 8: difference-form distances on the vector ALU  */
+#define KNN_PATH_MFMA 1 /* d  > 8: fp32 matrix-core tile of -2 Q X^T plus norms */
+
+/*
+ * The plan: how the call is cut into pieces (section 4.3: split the largest
+ * splittable axis so that each piece stays under the limit; the loop body
+ * produces a slice of the final result).  Queries are processed in q_chunks
+ * chunks of at most chunk_rows rows; inside a chunk the points are cut into
+ * n_splits ranges that are searched concurrently and merged afterwards.
+ */
+typedef struct {
+    int64_t m, n;
+    int32_t d, k;
+    int32_t path;        /* KNN_PATH_*                                          */
+    int32_t tile_q;      /* query rows per workgroup                            */
+    int32_t tile_x;      /* data points per inner tile                          */
+    int32_t n_splits;    /* ranges the point axis is cut into                   */
+    int64_t chunk_rows;  /* query rows per chunk (multiple of tile_q, or m)     */
+    int64_t q_chunks;    /* ceil(m / chunk_rows); 0 when m == 0                 */
+    int32_t streams;     /* HIP streams used (1: the caller's)                  */
+    int32_t reserved;
+    uint64_t norms_bytes;     /* workspace: per-point squared norms (MFMA path) */
+    uint64_t lists_bytes;     /* workspace: partial k-lists of one chunk        */
+    uint64_t workspace_bytes; /* total device workspace needed, <= mem_limit    */
+    uint64_t min_limit_bytes; /* smallest limit any plan for this shape fits in */
+} knn_plan_t;
+
+/*
+ * knn_plan - pure host arithmetic, no HIP call; usable without a GPU.
+ * Fills *out for the shape and limit given.  On KNN_ERR_MEM_LIMIT_TOO_SMALL
+ * *out still carries min_limit_bytes.  m == 0 gives an empty plan and KNN_OK.
+ */
+knn_status knn_plan(int64_t m, int64_t n, int32_t d, int32_t k,
+                    uint64_t mem_limit_bytes, knn_plan_t *out /* HOST */);
+
+/* workspace_bytes of the plan above, or 0 if there is none (error or m == 0). */
+uint64_t knn_workspace_bytes(int64_t m, int64_t n, int32_t d, int32_t k,
+                             uint64_t mem_limit_bytes);
+
+/*
+ * knn_search - the whole path: norms, tiled distances, running top-k, merge of
+ * the point ranges, exact re-evaluation of the winners, output.
+ *
+ *   Q [m, d], ldq      DEVICE in, row-major fp32 queries
+ *   X [n, d], ldx      DEVICE in, row-major fp32 data points (Q may alias X)
+ *   k                  neighbours per query, 1 <= k <= min(n, KNN_MAX_K)
+ *   mem_limit_bytes    upper bound for library-owned device memory.  It covers
+ *                      the workspace only, not Q, X, idx, dist (the caller's).
+ *   workspace          DEVICE scratch of workspace_bytes >= plan.workspace_bytes,
+ *                      256-byte aligned, caller-allocated, contents undefined
+ *                      before and after.  The library touches no byte beyond
+ *                      plan.workspace_bytes and allocates nothing itself.
+ *   idx  [m, k]        DEVICE out, int32, contiguous; point indices
+ *   dist [m, k]        DEVICE out, fp32, contiguous; squared distances >= 0,
+ *                      the fp64 difference-form value rounded to fp32
+ *   hip_stream         hipStream_t (NULL = default stream).  All work is
+ *                      enqueued there; outputs are valid once the caller has
+ *                      synchronised it.
+ *
+ * Argument and plan errors are returned synchronously and leave the outputs
+ * untouched.  The result does not depend on mem_limit_bytes: every limit that
+ * admits a plan gives bit-identical idx and dist.
+ */
+knn_status knn_search(const float *Q, int64_t ldq, const float *X, int64_t ldx,
+                      int64_t m, int64_t n, int32_t d, int32_t k,
+                      uint64_t mem_limit_bytes,
+                      void *workspace, uint64_t workspace_bytes,
+                      int32_t *idx, float *dist, void *hip_stream);
+
+/* Plan and workspace size of this thread's last successful knn_search. */
+knn_status knn_last_stats(knn_plan_t *plan_out /* HOST */,
+                          uint64_t *peak_workspace_bytes /* HOST */);
+
+/* Static string for a status code. */
+const char *knn_status_string(knn_status s);
+
+/*
+ * knn_parse_size - "64MB", "1GB", "500KB", "123" -> bytes, DECIMAL multipliers
+ * (KB = 1e3, MB = 1e6, GB = 1e9, TB = 1e12), matching the size options of the
+ * paper's section 4.3 listing as read through the appendix example.
+ * Returns KNN_ERR_INVALID_ARG for anything else.
+ */
+knn_status knn_parse_size(const char *text /* HOST */, uint64_t *bytes_out /* HOST */);
+
+/*
+ * knn_chunk_rows - rows of row_bytes each that fit in limit_bytes:
+ * floor(limit_bytes / row_bytes), the chunk length rule of algorithm 1 as it
+ * appears in the appendix example (1GB / (1e6 * 8 B) = 125 rows).
+ */
+int64_t knn_chunk_rows(uint64_t limit_bytes, uint64_t row_bytes);
+
+/* Last HIP error text seen by this thread ("" if none). */
+const char *knn_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KNN_MI355X_H */

@@ -1,0 +1,193 @@
+"""ctypes binding of libknn_mi355x.so: argument marshalling only.
+
+Every step of the search runs in the library's HIP kernels; PyTorch is used for device
+memory (inputs, outputs, the workspace) and for the current stream, nothing else.  There is
+no CPU fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+from . import build as _build
+
+KNN_OK = 0
+KNN_ERR_INVALID_ARG = 1
+KNN_ERR_MEM_LIMIT_TOO_SMALL = 2
+KNN_ERR_WORKSPACE_TOO_SMALL = 3
+KNN_ERR_UNSUPPORTED = 4
+KNN_ERR_HIP = 5
+KNN_MAX_K = 1024
+KNN_PATH_LOWD = 0
+KNN_PATH_MFMA = 1
+
+EXPORTED_SYMBOLS = (
+    "knn_plan", "knn_workspace_bytes", "knn_search", "knn_last_stats", "knn_status_string",
+    "knn_parse_size", "knn_chunk_rows", "knn_last_hip_error",
+)
+
+
+class PlanStruct(ctypes.Structure):
+    _fields_ = [
+        ("m", ctypes.c_int64), ("n", ctypes.c_int64),
+        ("d", ctypes.c_int32), ("k", ctypes.c_int32),
+        ("path", ctypes.c_int32), ("tile_q", ctypes.c_int32),
+        ("tile_x", ctypes.c_int32), ("n_splits", ctypes.c_int32),
+        ("chunk_rows", ctypes.c_int64), ("q_chunks", ctypes.c_int64),
+        ("streams", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("norms_bytes", ctypes.c_uint64), ("lists_bytes", ctypes.c_uint64),
+        ("workspace_bytes", ctypes.c_uint64), ("min_limit_bytes", ctypes.c_uint64),
+    ]
+
+
+@dataclass(frozen=True)
+class Plan:
+    m: int
+    n: int
+    d: int
+    k: int
+    path: int
+    tile_q: int
+    tile_x: int
+    n_splits: int
+    chunk_rows: int
+    q_chunks: int
+    streams: int
+    norms_bytes: int
+    lists_bytes: int
+    workspace_bytes: int
+    min_limit_bytes: int
+
+
+class KnnError(RuntimeError):
+    def __init__(self, status: int, message: str, min_limit_bytes: int = 0):
+        super().__init__(f"knn status {status}: {message}")
+        self.status = status
+        self.min_limit_bytes = min_limit_bytes
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB_PATH
+
+
+def load():
+    """Loads the built library; builds it first only if it does not exist at all."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build()
+    lib = ctypes.CDLL(_build.LIB_PATH)
+    i64, i32, u64, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_void_p
+    lib.knn_plan.argtypes = [i64, i64, i32, i32, u64, ctypes.POINTER(PlanStruct)]
+    lib.knn_plan.restype = ctypes.c_int
+    lib.knn_workspace_bytes.argtypes = [i64, i64, i32, i32, u64]
+    lib.knn_workspace_bytes.restype = u64
+    lib.knn_search.argtypes = [vp, i64, vp, i64, i64, i64, i32, i32, u64, vp, u64, vp, vp, vp]
+    lib.knn_search.restype = ctypes.c_int
+    lib.knn_last_stats.argtypes = [ctypes.POINTER(PlanStruct), ctypes.POINTER(u64)]
+    lib.knn_last_stats.restype = ctypes.c_int
+    lib.knn_status_string.argtypes = [ctypes.c_int]
+    lib.knn_status_string.restype = ctypes.c_char_p
+    lib.knn_parse_size.argtypes = [ctypes.c_char_p, ctypes.POINTER(u64)]
+    lib.knn_parse_size.restype = ctypes.c_int
+    lib.knn_chunk_rows.argtypes = [u64, u64]
+    lib.knn_chunk_rows.restype = i64
+    lib.knn_last_hip_error.argtypes = []
+    lib.knn_last_hip_error.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def knn_status_string(status: int) -> str:
+    return load().knn_status_string(int(status)).decode()
+
+
+def _plan_from_struct(ps: PlanStruct) -> Plan:
+    return Plan(ps.m, ps.n, ps.d, ps.k, ps.path, ps.tile_q, ps.tile_x, ps.n_splits,
+                ps.chunk_rows, ps.q_chunks, ps.streams, ps.norms_bytes, ps.lists_bytes,
+                ps.workspace_bytes, ps.min_limit_bytes)
+
+
+def knn_plan(m: int, n: int, d: int, k: int, mem_limit_bytes: int) -> Plan:
+    ps = PlanStruct()
+    st = load().knn_plan(m, n, d, k, mem_limit_bytes, ctypes.byref(ps))
+    if st != KNN_OK:
+        raise KnnError(st, knn_status_string(st), int(ps.min_limit_bytes))
+    return _plan_from_struct(ps)
+
+
+def knn_workspace_bytes(m: int, n: int, d: int, k: int, mem_limit_bytes: int) -> int:
+    return int(load().knn_workspace_bytes(m, n, d, k, mem_limit_bytes))
+
+
+def knn_parse_size(text: str) -> int:
+    out = ctypes.c_uint64(0)
+    st = load().knn_parse_size(text.encode(), ctypes.byref(out))
+    if st != KNN_OK:
+        raise KnnError(st, f"cannot parse size {text!r}")
+    return int(out.value)
+
+
+def knn_chunk_rows(limit_bytes: int, row_bytes: int) -> int:
+    return int(load().knn_chunk_rows(limit_bytes, row_bytes))
+
+
+def knn_last_stats():
+    ps = PlanStruct()
+    peak = ctypes.c_uint64(0)
+    st = load().knn_last_stats(ctypes.byref(ps), ctypes.byref(peak))
+    if st != KNN_OK:
+        raise KnnError(st, "no successful knn_search on this thread yet")
+    return _plan_from_struct(ps), int(peak.value)
+
+
+def knn_search_raw(q_ptr, ldq, x_ptr, ldx, m, n, d, k, mem_limit_bytes, ws_ptr, ws_bytes,
+                   idx_ptr, dist_ptr, stream_ptr) -> int:
+    """Direct call, raw integers for pointers; returns the status code."""
+    return int(load().knn_search(q_ptr, ldq, x_ptr, ldx, m, n, d, k, mem_limit_bytes, ws_ptr,
+                                 ws_bytes, idx_ptr, dist_ptr, stream_ptr))
+
+
+def knn_search(Q, X, k: int, mem_limit_bytes: int, workspace=None, out=None):
+    """knn_search(Q[m,d], X[n,d], k, mem_limit_bytes) -> (idx int32[m,k], dist fp32[m,k]).
+
+    Q and X are fp32 CUDA(HIP) tensors, row-major (a row stride larger than d is allowed).
+    The workspace (a uint8 tensor of plan.workspace_bytes) is allocated here unless given.
+    Work is enqueued on torch's current stream; no synchronisation is done.
+    """
+    import torch
+
+    if not (Q.is_cuda and X.is_cuda):
+        raise KnnError(KNN_ERR_INVALID_ARG, "Q and X must be device tensors (no CPU path exists)")
+    if Q.dtype != torch.float32 or X.dtype != torch.float32 or Q.dim() != 2 or X.dim() != 2:
+        raise KnnError(KNN_ERR_INVALID_ARG, "Q and X must be 2-D float32")
+    if Q.shape[1] != X.shape[1] or Q.stride(1) != 1 or X.stride(1) != 1:
+        raise KnnError(KNN_ERR_INVALID_ARG, "Q and X must share d and have unit column stride")
+    m, d = Q.shape
+    n = X.shape[0]
+    plan = knn_plan(m, n, d, k, mem_limit_bytes)
+    if workspace is None:
+        workspace = torch.empty(max(int(plan.workspace_bytes), 256), dtype=torch.uint8,
+                                device=Q.device)
+    if out is None:
+        idx = torch.empty((m, k), dtype=torch.int32, device=Q.device)
+        dist = torch.empty((m, k), dtype=torch.float32, device=Q.device)
+    else:
+        idx, dist = out
+    stream = torch.cuda.current_stream(Q.device).cuda_stream
+    ldq = Q.stride(0) if m > 1 else max(d, Q.stride(0))
+    ldx = X.stride(0) if n > 1 else max(d, X.stride(0))
+    st = knn_search_raw(Q.data_ptr(), ldq, X.data_ptr(), ldx, m, n, d, k, mem_limit_bytes,
+                        workspace.data_ptr(), workspace.numel(), idx.data_ptr(),
+                        dist.data_ptr(), stream)
+    if st != KNN_OK:
+        detail = knn_status_string(st)
+        if st == KNN_ERR_HIP:
+            detail += " (" + load().knn_last_hip_error().decode() + ")"
+        raise KnnError(st, detail)
+    return idx, dist

@@ -1,0 +1,95 @@
+// C ABI entry points that touch the GPU (see include/knn.h for the contract).
+//
+// knn_search is the loop of paper section 4.3 written by hand: the query axis is cut into
+// chunks whose partial lists fit the workspace, each chunk is one "generator + reducer"
+// launch over all point ranges followed by the merge that writes a slice of the final
+// result.  Nothing is allocated here: the only device memory the library uses is the
+// caller's workspace, so its footprint is bounded by the limit by construction (the
+// limit-unaware allocator is the overflow risk section 4.4 describes).
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/knn.h"
+#include "knn_config.h"
+#include "knn_kernels.h"
+
+namespace {
+
+thread_local knn_plan_t g_last_plan;
+thread_local uint64_t g_last_peak = 0;
+thread_local bool g_have_last = false;
+thread_local char g_hip_error[256] = "";
+
+knn_status hip_fail(hipError_t e, const char* what) {
+    snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
+    return KNN_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" const char* knn_last_hip_error(void) { return g_hip_error; }
+
+extern "C" knn_status knn_last_stats(knn_plan_t* plan_out, uint64_t* peak_workspace_bytes) {
+    if (!g_have_last) return KNN_ERR_INVALID_ARG;
+    if (plan_out) *plan_out = g_last_plan;
+    if (peak_workspace_bytes) *peak_workspace_bytes = g_last_peak;
+    return KNN_OK;
+}
+
+extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, int64_t ldx,
+                                 int64_t m, int64_t n, int32_t d, int32_t k,
+                                 uint64_t mem_limit_bytes, void* workspace,
+                                 uint64_t workspace_bytes, int32_t* idx, float* dist,
+                                 void* hip_stream) {
+    using namespace knn;
+    if (m < 0 || n < 1 || d < 1 || k < 1 || (int64_t)k > n) return KNN_ERR_INVALID_ARG;
+    if (ldq < d || ldx < d) return KNN_ERR_INVALID_ARG;
+    if (!X) return KNN_ERR_INVALID_ARG;
+    if (m > 0 && (!Q || !idx || !dist)) return KNN_ERR_INVALID_ARG;
+    knn_plan_t plan;
+    knn_status st = knn_plan(m, n, d, k, mem_limit_bytes, &plan);
+    if (st != KNN_OK) return st;
+    if (m == 0) {
+        g_last_plan = plan;
+        g_last_peak = 0;
+        g_have_last = true;
+        return KNN_OK;
+    }
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0)
+        return KNN_ERR_INVALID_ARG;
+    if (workspace_bytes < plan.workspace_bytes) return KNN_ERR_WORKSPACE_TOO_SMALL;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    float* xn = reinterpret_cast<float*>(ws);
+    float* lk = reinterpret_cast<float*>(ws + plan.norms_bytes);
+    int* li = reinterpret_cast<int*>(ws + plan.norms_bytes + plan.lists_bytes / 2);
+    const int S = plan.n_splits;
+
+    hipError_t e;
+    if (plan.path == KNN_PATH_MFMA) {
+        e = launch_row_norms(X, ldx, n, d, xn, stream);
+        if (e != hipSuccess) return hip_fail(e, "row norms launch");
+    }
+    for (int64_t c = 0; c < plan.q_chunks; ++c) {
+        const int64_t row0 = c * plan.chunk_rows;
+        const int64_t rows = (m - row0 < plan.chunk_rows) ? (m - row0) : plan.chunk_rows;
+        const float* Qc = Q + row0 * ldq;
+        if (plan.path == KNN_PATH_LOWD) {
+            e = launch_lowd(Qc, ldq, X, ldx, rows, n, d, k, S, lk, li, stream);
+            if (e != hipSuccess) return hip_fail(e, "low-d search launch");
+        } else {
+            e = launch_mfma(Qc, ldq, X, ldx, xn, rows, n, d, k, S, lk, li, stream);
+            if (e != hipSuccess) return hip_fail(e, "mfma search launch");
+        }
+        e = launch_merge_refine(Qc, ldq, X, ldx, rows, n, d, k, S, lk, li, idx + row0 * k,
+                                dist + row0 * k, stream);
+        if (e != hipSuccess) return hip_fail(e, "merge/refine launch");
+    }
+    g_last_plan = plan;
+    g_last_peak = plan.workspace_bytes;
+    g_have_last = true;
+    return KNN_OK;
+}

@@ -1,0 +1,32 @@
+// Compile-time shape constants shared by the host planner and the gfx950 kernels.
+#pragma once
+#include <cstdint>
+
+namespace knn {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr int kNumCU = 256;          // MI355X compute units (8 XCDs x 32)
+
+// d <= kLowdMaxD: one query per lane, difference-form distances on the vector ALU.
+constexpr int kLowdMaxD = 8;
+constexpr int kLowdWaves = 4;                    // waves per workgroup
+constexpr int kLowdTileQ = kLowdWaves * kWave;   // 256 query rows per workgroup
+constexpr int kLowdUnroll = 8;                   // points examined per filter test
+constexpr int kLowdCand = 16;                    // candidate slots per query (LDS)
+
+// d > kLowdMaxD: fp32 MFMA tile, 4 waves, each wave owns 32 queries x 128 points.
+constexpr int kMfmaTileQ = 128;
+constexpr int kMfmaTileX = 128;
+constexpr int kMfmaKC = 16;          // K columns staged in LDS per pipeline step
+constexpr int kMfmaRowStride = 20;   // floats per staged row (16 + 4 pad, keeps 16 B alignment)
+constexpr int kMfmaCand = 32;        // candidate slots per query (LDS)
+
+constexpr int kTargetWorkgroups = 2048;  // launch width the planner aims for
+constexpr int kMaxSplits = 64;
+constexpr int64_t kMaxChunkRows = 1 << 22;  // keeps per-launch row counts and grids in int range
+constexpr int kMinSplitPoints = 2048;    // a point range shorter than this is not worth a split
+
+constexpr uint64_t kAlign = 256;
+constexpr inline uint64_t align_up(uint64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+}  // namespace knn

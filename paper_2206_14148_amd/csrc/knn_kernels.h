@@ -1,0 +1,32 @@
+// Internal launcher interface between the C ABI (api.hip) and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace knn {
+
+// Partial k-lists of one query chunk live in the workspace as two arrays of
+// rows * S * k entries: keys (fp32) and point indices (int32).  The list of chunk row r
+// and point range s starts at ((r * S) + s) * k and is ascending by (key, index).
+
+// xn[j] = sum_t X[j][t]^2 in fp32 (the sum x^2 term of paper section 4.1).
+hipError_t launch_row_norms(const float* X, int64_t ldx, int64_t n, int d, float* xn,
+                            hipStream_t stream);
+
+// d <= kLowdMaxD: key = fp32 difference-form squared distance.
+hipError_t launch_lowd(const float* Q, int64_t ldq, const float* X, int64_t ldx, int64_t rows,
+                       int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream);
+
+// d > kLowdMaxD: key = xn[j] - 2 q.x from fp32 MFMA tiles (rank-equivalent to the distance).
+hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx, const float* xn,
+                       int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
+                       hipStream_t stream);
+
+// Merge the S lists of each row, re-evaluate the k winners in fp64 difference form,
+// order by (distance, index) and write idx / dist rows.
+hipError_t launch_merge_refine(const float* Q, int64_t ldq, const float* X, int64_t ldx,
+                               int64_t rows, int64_t n, int d, int k, int S, const float* lk,
+                               const int* li, int32_t* idx, float* dist, hipStream_t stream);
+
+}  // namespace knn

@@ -1,0 +1,670 @@
+// gfx950 (CDNA4, MI355X) kernels for exact brute-force kNN under a memory limit.
+//
+// Paper section 5.2 defines the result (k closest of n points for each of m queries);
+// section 4.1 gives the distance expansion sum x^2 + y^2 - 2xy; section 4.3 (figure 2)
+// gives the shape of the computation: a generator (distance tile), a reducer (top-k) and a
+// loop over slices, with the big intermediate alive only inside one iteration.  Here the
+// intermediate lives in registers: a tile of keys is produced, compared against each
+// query's current k-th best and dropped.  The rare survivors go through a small per-query
+// candidate buffer in LDS and are merged by one wavefront into the query's sorted list in
+// the workspace.
+//
+// Ordering rule everywhere: (key, index) lexicographic, lower index first on equal keys.
+#include <hip/hip_runtime.h>
+
+#include <climits>
+#include <cmath>
+#include <cstdint>
+
+#include "knn_config.h"
+#include "knn_kernels.h"
+
+namespace knn {
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr float kInf = __builtin_huge_valf();
+constexpr int kNoIdx = INT_MAX;
+
+__device__ __forceinline__ bool before(float ka, int ia, float kb, int ib) {
+    return ka < kb || (ka == kb && ia < ib);
+}
+
+__device__ __forceinline__ bool before64(double ka, int ia, double kb, int ib) {
+    return ka < kb || (ka == kb && ia < ib);
+}
+
+// Make this wave's earlier LDS/global writes visible to its other lanes.
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) v = fminf(v, __shfl_xor(v, s));
+    return v;
+}
+
+// Ascending bitonic sort of one (key, idx) per lane across the 64 lanes of a wave.
+__device__ __forceinline__ void wave_sort64(float& key, int& idx, int lane) {
+#pragma unroll
+    for (int size = 2; size <= 64; size <<= 1) {
+#pragma unroll
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            const float ok = __shfl_xor(key, stride);
+            const int oi = __shfl_xor(idx, stride);
+            const bool ascending = (lane & size) == 0;
+            const bool low_lane = (lane & stride) == 0;
+            const bool keep_min = ascending == low_lane;
+            const bool take = keep_min ? before(ok, oi, key, idx) : before(key, idx, ok, oi);
+            key = take ? ok : key;
+            idx = take ? oi : idx;
+        }
+    }
+}
+
+// Per-wave LDS scratch used while merging candidates into a list.
+struct MergeScratch {
+    float* list_key;  // [k]   staged copy of the list
+    int* list_idx;    // [k]
+    float* cand_key;  // [64]  sorted candidates
+    int* cand_idx;    // [64]
+};
+
+// Merge up to 64 candidates (one per lane; lanes without one pass (+inf, kNoIdx)) into the
+// ascending list gk/gi of k entries in global memory.  Returns the key at position k-1 of
+// the merged list, i.e. the new acceptance threshold.  All 64 lanes must call it together.
+__device__ float wave_merge(float* __restrict__ gk, int* __restrict__ gi, int k, float ckey,
+                            int cidx, const MergeScratch& sc, int lane) {
+    wave_sync();  // earlier uses of the scratch are finished
+    __threadfence();
+    wave_sort64(ckey, cidx, lane);
+    sc.cand_key[lane] = ckey;
+    sc.cand_idx[lane] = cidx;
+    for (int p = lane; p < k; p += kWave) {
+        sc.list_key[p] = gk[p];
+        sc.list_idx[p] = gi[p];
+    }
+    wave_sync();
+    float tau = kInf;
+    // list entries move right by the number of candidates that come before them
+    for (int p = lane; p < k; p += kWave) {
+        const float ek = sc.list_key[p];
+        const int ei = sc.list_idx[p];
+        int cnt = 0;
+#pragma unroll
+        for (int step = 32; step > 0; step >>= 1) {
+            const int probe = cnt + step - 1;
+            if (before(sc.cand_key[probe], sc.cand_idx[probe], ek, ei)) cnt += step;
+        }
+        if (before(sc.cand_key[cnt], sc.cand_idx[cnt], ek, ei)) cnt += 1;  // cnt <= 63 here
+        const int pos = p + cnt;
+        if (pos < k) {
+            gk[pos] = ek;
+            gi[pos] = ei;
+            if (pos == k - 1) tau = ek;
+        }
+    }
+    // candidate c lands after the c candidates before it and the list entries <= it
+    {
+        int lo = 0, hi = k;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (!before(ckey, cidx, sc.list_key[mid], sc.list_idx[mid])) lo = mid + 1;
+            else hi = mid;
+        }
+        const int pos = lane + lo;
+        if (pos < k) {
+            gk[pos] = ckey;
+            gi[pos] = cidx;
+            if (pos == k - 1) tau = ckey;
+        }
+    }
+    tau = wave_min(tau);
+    __threadfence();
+    return tau;
+}
+
+// ---------------------------------------------------------------------------------------
+// Row norms (section 4.1, the sum x^2 term): one wave per row, fixed summation order.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void knn_row_norms_kernel(const float* __restrict__ X,
+                                                            int64_t ldx, int64_t n, int d,
+                                                            float* __restrict__ xn) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t j = wave; j < n; j += nwaves) {
+        const float* row = X + j * ldx;
+        float acc = 0.f;
+        for (int t = lane; t < d; t += kWave) acc = fmaf(row[t], row[t], acc);
+#pragma unroll
+        for (int s = 32; s > 0; s >>= 1) acc += __shfl_xor(acc, s);
+        if (lane == 0) xn[j] = acc;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Low-dimensional path: one query per lane, points streamed through uniform (scalar) loads,
+// difference-form distance in fp32 on the vector ALU.
+// ---------------------------------------------------------------------------------------
+template <int D, bool CONTIG>
+__global__ __launch_bounds__(kLowdTileQ) void knn_lowd_kernel(
+    const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx_arg,
+    int rows, int n, int k, int S, int split_len, float* __restrict__ lk, int* __restrict__ li) {
+    constexpr int U = kLowdUnroll;  // points per filter test
+    constexpr int H = 4;            // points pushed between two overflow checks
+    constexpr int C = kLowdCand;
+    constexpr int CP = C + 1;  // padded row of the candidate buffer
+    static_assert(U % H == 0 && C > H, "candidate buffer must hold one push group");
+    // rows of X that follow each other without gaps let a whole group be one wide load
+    const int64_t ldx = CONTIG ? (int64_t)D : ldx_arg;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const size_t per_wave = (size_t)(2 * kWave * CP + 2 * k + 2 * kWave) * 4;
+    unsigned char* base = smem + (size_t)wave * per_wave;
+    float* ck = reinterpret_cast<float*>(base);         // [64][CP]
+    int* ci = reinterpret_cast<int*>(ck + kWave * CP);  // [64][CP]
+    MergeScratch sc;
+    sc.list_key = reinterpret_cast<float*>(ci + kWave * CP);
+    sc.list_idx = reinterpret_cast<int*>(sc.list_key + k);
+    sc.cand_key = reinterpret_cast<float*>(sc.list_idx + k);
+    sc.cand_idx = reinterpret_cast<int*>(sc.cand_key + kWave);
+
+    const int s = blockIdx.y;
+    const int wave_row0 = (blockIdx.x * kLowdWaves + wave) * kWave;
+    if (wave_row0 >= rows) return;  // whole wave idle; no workgroup barrier is used below
+    const int r = wave_row0 + lane;
+    const bool active = r < rows;
+
+    // start every list of this wave as k sentinels
+    {
+        const int nq = min(kWave, rows - wave_row0);
+        for (int qq = 0; qq < nq; ++qq) {
+            const size_t lb = ((size_t)(wave_row0 + qq) * S + s) * k;
+            for (int p = lane; p < k; p += kWave) {
+                lk[lb + p] = kInf;
+                li[lb + p] = kNoIdx;
+            }
+        }
+    }
+
+    float q[D];
+#pragma unroll
+    for (int t = 0; t < D; ++t) q[t] = active ? Q[(int64_t)r * ldq + t] : 0.f;
+    float tau = active ? kInf : -kInf;  // idle lanes never accept anything
+    int cnt = 0;
+
+    auto flush = [&](uint64_t mask) {
+        while (mask) {
+            const int L = __builtin_ctzll(mask);
+            mask &= mask - 1;
+            wave_sync();
+            const int c = __shfl(cnt, L);
+            float key = kInf;
+            int id = kNoIdx;
+            if (lane < c) {
+                key = ck[L * CP + lane];
+                id = ci[L * CP + lane];
+            }
+            const size_t lb = ((size_t)(wave_row0 + L) * S + s) * k;
+            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane);
+            if (lane == L) {
+                tau = t_new;
+                cnt = 0;
+            }
+        }
+    };
+    auto sqdist = [&](const float* __restrict__ xp) {
+        float df = q[0] - xp[0];
+        float acc = df * df;
+#pragma unroll
+        for (int t = 1; t < D; ++t) {
+            df = q[t] - xp[t];
+            acc = fmaf(df, df, acc);
+        }
+        return acc;
+    };
+
+    const int j0 = s * split_len;
+    const int j1 = min(n, j0 + split_len);
+    int j = j0;
+    const float* xp = X + (int64_t)j0 * ldx;  // uniform: the compiler reads it with scalar loads
+    for (; j + U <= j1; j += U, xp += U * ldx) {
+        float dd[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) dd[u] = sqdist(xp + u * ldx);
+        float mn = dd[0];
+#pragma unroll
+        for (int u = 1; u < U; ++u) mn = fminf(mn, dd[u]);
+        if (__builtin_amdgcn_ballot_w64(mn < tau) != 0) {
+#pragma unroll
+            for (int g = 0; g < U / H; ++g) {
+#pragma unroll
+                for (int u = g * H; u < (g + 1) * H; ++u) {
+                    if (dd[u] < tau) {
+                        ck[lane * CP + cnt] = dd[u];
+                        ci[lane * CP + cnt] = j + u;
+                        ++cnt;
+                    }
+                }
+                const uint64_t full = __builtin_amdgcn_ballot_w64(cnt > C - H);
+                if (full) flush(full);
+            }
+        }
+    }
+    for (; j < j1; ++j, xp += ldx) {
+        const float acc = sqdist(xp);
+        if (acc < tau) {
+            ck[lane * CP + cnt] = acc;
+            ci[lane * CP + cnt] = j;
+            ++cnt;
+        }
+        const uint64_t full = __builtin_amdgcn_ballot_w64(cnt > C - H);
+        if (full) flush(full);
+    }
+    const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0);
+    if (rest) flush(rest);
+}
+
+// ---------------------------------------------------------------------------------------
+// Matrix-core path: a workgroup of 4 waves owns 128 queries and walks its point range in
+// tiles of 128 points.  Data points are the M side and queries the N side of
+// v_mfma_f32_32x32x2_f32, so the 16 accumulator values a lane holds per 32x32 block all
+// belong to ONE query (column = lane % 32): its threshold is one register and the filter
+// is a per-lane compare.  The accumulators start at ||x||^2 and receive (-2 q) . x, which
+// gives the key  ||x||^2 - 2 q.x  (the distance minus the per-query constant ||q||^2).
+// ---------------------------------------------------------------------------------------
+template <bool ALIGNED>
+__device__ __forceinline__ f32x4 load_row4(const float* __restrict__ base, int64_t ld,
+                                           int64_t row, int64_t nrows, int col, int d) {
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (row < nrows && col < d) {
+        const float* p = base + row * ld + col;
+        if (ALIGNED && col + 4 <= d) {
+            v = *reinterpret_cast<const f32x4*>(p);
+        } else {
+            v[0] = p[0];
+            if (col + 1 < d) v[1] = p[1];
+            if (col + 2 < d) v[2] = p[2];
+            if (col + 3 < d) v[3] = p[3];
+        }
+    }
+    return v;
+}
+
+template <bool ALIGNED>
+__global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
+    const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
+    const float* __restrict__ xn, int rows, int n, int d, int k, int S, int split_len,
+    float* __restrict__ lk, int* __restrict__ li) {
+    constexpr int TQ = kMfmaTileQ, TX = kMfmaTileX, KC = kMfmaKC, RS = kMfmaRowStride;
+    constexpr int C = kMfmaCand;
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* xs = reinterpret_cast<float*>(smem);        // [2][TX][RS]
+    float* qs = xs + 2 * TX * RS;                      // [2][TQ][RS]
+    float* xns = qs + 2 * TQ * RS;                     // [2][TX]
+    float* ck = xns + 2 * TX;                          // [TQ][C]
+    int* ci = reinterpret_cast<int*>(ck + TQ * C);     // [TQ][C]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    MergeScratch sc;
+    {
+        float* pw = reinterpret_cast<float*>(ci + TQ * C) + (size_t)wave * (2 * kWave + 2 * k);
+        sc.cand_key = pw;
+        sc.cand_idx = reinterpret_cast<int*>(pw + kWave);
+        sc.list_key = pw + 2 * kWave;
+        sc.list_idx = reinterpret_cast<int*>(pw + 2 * kWave + k);
+    }
+    const int i32 = lane & 31;  // query column / point row inside a 32x32 block
+    const int h = lane >> 5;    // which half of the wave
+    const int s = blockIdx.y;
+    const int wg_row0 = blockIdx.x * TQ;
+    const int my_q = wave * 32 + i32;  // query inside the workgroup tile
+    const int r = wg_row0 + my_q;
+    const bool active = r < rows;
+
+    // lists of this wave's 32 queries start as k sentinels
+    for (int qq = 0; qq < 32; ++qq) {
+        const int rr = wg_row0 + wave * 32 + qq;
+        if (rr >= rows) break;
+        const size_t lb = ((size_t)rr * S + s) * k;
+        for (int p = lane; p < k; p += kWave) {
+            lk[lb + p] = kInf;
+            li[lb + p] = kNoIdx;
+        }
+    }
+
+    float tau = active ? kInf : -kInf;
+    int cnt = 0;  // candidates buffered for this lane's query (same value in both halves)
+
+    const int j0 = s * split_len;
+    const int j1 = min(n, j0 + split_len);
+    const int ntiles = (j1 > j0) ? (j1 - j0 + TX - 1) / TX : 0;
+    const int nch = (d + KC - 1) / KC;
+    const int total = ntiles * nch;
+
+    // staging role of this thread: rows srow and srow + 64, four columns at scol
+    const int srow = tid >> 2;
+    const int scol = (tid & 3) * 4;
+
+    f32x4 gx0, gx1, gq0, gq1;
+    float gxn = kInf;
+    auto fetch = [&](int step) {
+        const int tile = step / nch;
+        const int c = step - tile * nch;
+        const int col = c * KC + scol;
+        const int64_t jr = (int64_t)j0 + (int64_t)tile * TX + srow;
+        gx0 = load_row4<ALIGNED>(X, ldx, jr, j1, col, d);
+        gx1 = load_row4<ALIGNED>(X, ldx, jr + 64, j1, col, d);
+        gq0 = load_row4<ALIGNED>(Q, ldq, (int64_t)wg_row0 + srow, rows, col, d) * -2.f;
+        gq1 = load_row4<ALIGNED>(Q, ldq, (int64_t)wg_row0 + srow + 64, rows, col, d) * -2.f;
+        if (c == 0 && tid < TX) {
+            const int64_t jj = (int64_t)j0 + (int64_t)tile * TX + tid;
+            gxn = jj < j1 ? xn[jj] : kInf;  // rows past the range can never be accepted
+        }
+    };
+    auto stash = [&](int step) {
+        const int tile = step / nch;
+        const int c = step - tile * nch;
+        const int buf = step & 1;
+        float* xb = xs + buf * TX * RS;
+        float* qb = qs + buf * TQ * RS;
+        *reinterpret_cast<f32x4*>(xb + srow * RS + scol) = gx0;
+        *reinterpret_cast<f32x4*>(xb + (srow + 64) * RS + scol) = gx1;
+        *reinterpret_cast<f32x4*>(qb + srow * RS + scol) = gq0;
+        *reinterpret_cast<f32x4*>(qb + (srow + 64) * RS + scol) = gq1;
+        if (c == 0 && tid < TX) xns[(tile & 1) * TX + tid] = gxn;
+    };
+
+    auto flush = [&](uint64_t mask) {  // bits 0..31: queries of this wave to merge
+        while (mask) {
+            const int L = __builtin_ctzll(mask);
+            mask &= mask - 1;
+            wave_sync();
+            const int c = __shfl(cnt, L);
+            float key = kInf;
+            int id = kNoIdx;
+            if (lane < c) {
+                key = ck[(wave * 32 + L) * C + lane];
+                id = ci[(wave * 32 + L) * C + lane];
+            }
+            const size_t lb = ((size_t)(wg_row0 + wave * 32 + L) * S + s) * k;
+            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane);
+            if (i32 == L) {
+                tau = t_new;
+                cnt = 0;
+            }
+        }
+    };
+
+    f32x16 acc[4];
+
+    if (total > 0) {
+        fetch(0);
+        stash(0);
+    }
+    __syncthreads();
+
+    for (int step = 0; step < total; ++step) {
+        const int tile = step / nch;
+        const int c = step - tile * nch;
+        const int buf = step & 1;
+        if (step + 1 < total) fetch(step + 1);
+
+        if (c == 0) {
+            const float* xt = xns + (tile & 1) * TX;
+#pragma unroll
+            for (int pb = 0; pb < 4; ++pb) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(xt + pb * 32 + g * 8 + h * 4);
+                    acc[pb][g * 4 + 0] = v[0];
+                    acc[pb][g * 4 + 1] = v[1];
+                    acc[pb][g * 4 + 2] = v[2];
+                    acc[pb][g * 4 + 3] = v[3];
+                }
+            }
+        }
+        {
+            const float* xb = xs + buf * TX * RS;
+            const float* qb = qs + buf * TQ * RS;
+#pragma unroll
+            for (int g = 0; g < KC / 8; ++g) {
+                const int col = g * 8 + h * 4;
+                const f32x4 b = *reinterpret_cast<const f32x4*>(qb + my_q * RS + col);
+                f32x4 a[4];
+#pragma unroll
+                for (int pb = 0; pb < 4; ++pb)
+                    a[pb] = *reinterpret_cast<const f32x4*>(xb + (pb * 32 + i32) * RS + col);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                    for (int pb = 0; pb < 4; ++pb)
+                        acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[pb][e], b[e], acc[pb], 0, 0, 0);
+                }
+            }
+        }
+
+        if (c == nch - 1) {
+            // filter: does any of this lane's 64 keys beat its query's threshold?
+            float mn = acc[0][0];
+#pragma unroll
+            for (int pb = 0; pb < 4; ++pb) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) mn = fminf(mn, acc[pb][e]);
+            }
+            if (__builtin_amdgcn_ballot_w64(mn < tau) != 0) {
+                const int tile_base = j0 + tile * TX;
+#pragma unroll
+                for (int pb = 0; pb < 4; ++pb) {
+                    int own = 0;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) own += (acc[pb][e] < tau) ? 1 : 0;
+                    int oth = __shfl_xor(own, 32);
+                    const uint64_t need =
+                        __builtin_amdgcn_ballot_w64(cnt + own + oth > C) & 0xffffffffull;
+                    if (need) {
+                        flush(need);
+                        own = 0;
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) own += (acc[pb][e] < tau) ? 1 : 0;
+                        oth = __shfl_xor(own, 32);
+                    }
+                    int slot = my_q * C + cnt + (h ? oth : 0);
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        if (acc[pb][e] < tau) {
+                            ck[slot] = acc[pb][e];
+                            ci[slot] = tile_base + pb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+                            ++slot;
+                        }
+                    }
+                    cnt += own + oth;
+                }
+            }
+        }
+
+        if (step + 1 < total) stash(step + 1);
+        __syncthreads();
+    }
+    const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0) & 0xffffffffull;
+    if (rest) flush(rest);
+}
+
+// ---------------------------------------------------------------------------------------
+// Merge of the S partial lists, exact re-evaluation, final order.  One wave per query.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ double exact_sqdist(const float* __restrict__ q,
+                                               const float* __restrict__ x, int d) {
+#pragma clang fp contract(off)
+    double acc = 0.0;
+    for (int t = 0; t < d; ++t) {
+        const double diff = (double)q[t] - (double)x[t];
+        acc = acc + diff * diff;
+    }
+    return acc;
+}
+
+__global__ __launch_bounds__(256) void knn_merge_refine_kernel(
+    const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx, int rows,
+    int n, int d, int k, int S, const float* __restrict__ lk, const int* __restrict__ li,
+    int32_t* __restrict__ idx_out, float* __restrict__ dist_out) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int r = blockIdx.x * 4 + wave;
+    if (r >= rows) return;  // no workgroup barrier below
+    double* wd = reinterpret_cast<double*>(smem) + (size_t)wave * k;
+    int* wi = reinterpret_cast<int*>(reinterpret_cast<double*>(smem) + (size_t)4 * k) + (size_t)wave * k;
+
+    const size_t rb = (size_t)r * S * k;
+    if (S == 1) {
+        for (int p = lane; p < k; p += kWave) wi[p] = li[rb + p];
+    } else {
+        // rank of an entry = its position in its own list + entries of the other lists
+        // that come before it; indices are distinct, so ranks are too
+        const int total = S * k;
+        for (int e = lane; e < total; e += kWave) {
+            const int se = e / k;
+            const int p = e - se * k;
+            const float key = lk[rb + e];
+            const int id = li[rb + e];
+            int rank = p;
+            for (int s2 = 0; s2 < S && rank < k; ++s2) {
+                if (s2 == se) continue;
+                const float* k2 = lk + rb + (size_t)s2 * k;
+                const int* i2 = li + rb + (size_t)s2 * k;
+                int lo = 0, hi = k;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (before(k2[mid], i2[mid], key, id)) lo = mid + 1;
+                    else hi = mid;
+                }
+                rank += lo;
+            }
+            if (rank < k) wi[rank] = id;
+        }
+    }
+    wave_sync();
+    for (int w = lane; w < k; w += kWave) {
+        const int j = wi[w];
+        double dist = __builtin_huge_val();
+        if ((unsigned)j < (unsigned)n)
+            dist = exact_sqdist(Q + (int64_t)r * ldq, X + (int64_t)j * ldx, d);
+        wd[w] = dist;
+    }
+    wave_sync();
+    for (int w = lane; w < k; w += kWave) {
+        const double dw = wd[w];
+        const int jw = wi[w];
+        int rank = 0;
+        for (int v = 0; v < k; ++v) rank += before64(wd[v], wi[v], dw, jw) ? 1 : 0;
+        idx_out[(size_t)r * k + rank] = jw;
+        dist_out[(size_t)r * k + rank] = (float)dw;
+    }
+}
+
+template <typename F>
+hipError_t raise_lds_limit(F kernel, size_t bytes) {
+    if (bytes <= 48 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+}  // namespace
+
+hipError_t launch_row_norms(const float* X, int64_t ldx, int64_t n, int d, float* xn,
+                            hipStream_t stream) {
+    int64_t blocks = (n + 3) / 4;
+    if (blocks > 16384) blocks = 16384;
+    knn_row_norms_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(X, ldx, n, d, xn);
+    return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_lowd_d(const float* Q, int64_t ldq, const float* X, int64_t ldx,
+                                int64_t rows, int64_t n, int k, int S, float* lk, int* li,
+                                hipStream_t stream) {
+    const size_t per_wave = (size_t)(2 * kWave * (kLowdCand + 1) + 2 * k + 2 * kWave) * 4;
+    const size_t lds = per_wave * kLowdWaves;
+    int64_t split_len = (n + S - 1) / S;
+    split_len = (split_len + kLowdUnroll - 1) / kLowdUnroll * kLowdUnroll;
+    dim3 grid((unsigned)((rows + kLowdTileQ - 1) / kLowdTileQ), (unsigned)S);
+    hipError_t e;
+    if (ldx == D) {
+        e = raise_lds_limit(knn_lowd_kernel<D, true>, lds);
+        if (e != hipSuccess) return e;
+        knn_lowd_kernel<D, true><<<grid, dim3(kLowdTileQ), lds, stream>>>(
+            Q, ldq, X, ldx, (int)rows, (int)n, k, S, (int)split_len, lk, li);
+    } else {
+        e = raise_lds_limit(knn_lowd_kernel<D, false>, lds);
+        if (e != hipSuccess) return e;
+        knn_lowd_kernel<D, false><<<grid, dim3(kLowdTileQ), lds, stream>>>(
+            Q, ldq, X, ldx, (int)rows, (int)n, k, S, (int)split_len, lk, li);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_lowd(const float* Q, int64_t ldq, const float* X, int64_t ldx, int64_t rows,
+                       int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream) {
+    switch (d) {
+        case 1: return launch_lowd_d<1>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 2: return launch_lowd_d<2>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 3: return launch_lowd_d<3>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 4: return launch_lowd_d<4>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 5: return launch_lowd_d<5>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 6: return launch_lowd_d<6>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 7: return launch_lowd_d<7>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 8: return launch_lowd_d<8>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx, const float* xn,
+                       int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
+                       hipStream_t stream) {
+    const size_t lds = (size_t)(2 * kMfmaTileX * kMfmaRowStride + 2 * kMfmaTileQ * kMfmaRowStride +
+                                2 * kMfmaTileX + 2 * kMfmaTileQ * kMfmaCand +
+                                4 * (2 * kWave + 2 * k)) * 4;
+    int64_t split_len = (n + S - 1) / S;
+    split_len = (split_len + kMfmaTileX - 1) / kMfmaTileX * kMfmaTileX;
+    dim3 grid((unsigned)((rows + kMfmaTileQ - 1) / kMfmaTileQ), (unsigned)S);
+    const bool aligned = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldq % 4 == 0) &&
+                         (ldx % 4 == 0);
+    hipError_t e;
+    if (aligned) {
+        e = raise_lds_limit(knn_mfma_kernel<true>, lds);
+        if (e != hipSuccess) return e;
+        knn_mfma_kernel<true><<<grid, dim3(256), lds, stream>>>(
+            Q, ldq, X, ldx, xn, (int)rows, (int)n, d, k, S, (int)split_len, lk, li);
+    } else {
+        e = raise_lds_limit(knn_mfma_kernel<false>, lds);
+        if (e != hipSuccess) return e;
+        knn_mfma_kernel<false><<<grid, dim3(256), lds, stream>>>(
+            Q, ldq, X, ldx, xn, (int)rows, (int)n, d, k, S, (int)split_len, lk, li);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_merge_refine(const float* Q, int64_t ldq, const float* X, int64_t ldx,
+                               int64_t rows, int64_t n, int d, int k, int S, const float* lk,
+                               const int* li, int32_t* idx, float* dist, hipStream_t stream) {
+    const size_t lds = (size_t)4 * k * (sizeof(double) + sizeof(int));
+    hipError_t e = raise_lds_limit(knn_merge_refine_kernel, lds);
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned)((rows + 3) / 4));
+    knn_merge_refine_kernel<<<grid, dim3(256), lds, stream>>>(Q, ldq, X, ldx, (int)rows, (int)n, d,
+                                                              k, S, lk, li, idx, dist);
+    return hipGetLastError();
+}
+
+}  // namespace knn

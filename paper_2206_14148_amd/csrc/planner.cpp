@@ -1,0 +1,144 @@
+// Host-side planner: turns (m, n, d, k, mem_limit) into tile, split and chunk sizes.
+//
+// Paper section 4.3 / algorithm 1: the largest splittable axis is cut so that each piece
+// stays under the size limit and the loop body yields a slice of the result.  For kNN the
+// query axis is freely splittable (rows are independent) and the point axis becomes
+// splittable because the reduction is a mergeable running top-k instead of a sort.
+// Section 4.4: every concurrently live buffer counts, so the plan sums all library-owned
+// device memory (norms + every partial list of a chunk) and keeps the sum under the limit.
+#include <cctype>
+#include <cstdlib>
+#include <cstring>
+
+#include "../../include/knn.h"
+#include "knn_config.h"
+
+using namespace knn;
+
+extern "C" int64_t knn_chunk_rows(uint64_t limit_bytes, uint64_t row_bytes) {
+    if (row_bytes == 0) return 0;
+    uint64_t rows = limit_bytes / row_bytes;
+    return rows > (uint64_t)INT64_MAX ? INT64_MAX : (int64_t)rows;
+}
+
+extern "C" knn_status knn_parse_size(const char* text, uint64_t* bytes_out) {
+    if (!text || !bytes_out) return KNN_ERR_INVALID_ARG;
+    while (*text && isspace((unsigned char)*text)) ++text;
+    if (!isdigit((unsigned char)*text)) return KNN_ERR_INVALID_ARG;
+    uint64_t value = 0;
+    while (isdigit((unsigned char)*text)) {
+        uint64_t digit = (uint64_t)(*text - '0');
+        if (value > (UINT64_MAX - digit) / 10) return KNN_ERR_INVALID_ARG;
+        value = value * 10 + digit;
+        ++text;
+    }
+    char unit[4] = {0, 0, 0, 0};
+    int len = 0;
+    while (*text && !isspace((unsigned char)*text)) {
+        if (len >= 2) return KNN_ERR_INVALID_ARG;
+        unit[len++] = (char)toupper((unsigned char)*text++);
+    }
+    while (*text && isspace((unsigned char)*text)) ++text;
+    if (*text) return KNN_ERR_INVALID_ARG;
+    uint64_t mult;
+    if (len == 0 || !strcmp(unit, "B")) mult = 1ull;
+    else if (!strcmp(unit, "KB")) mult = 1000ull;
+    else if (!strcmp(unit, "MB")) mult = 1000000ull;
+    else if (!strcmp(unit, "GB")) mult = 1000000000ull;
+    else if (!strcmp(unit, "TB")) mult = 1000000000000ull;
+    else return KNN_ERR_INVALID_ARG;
+    if (value > UINT64_MAX / mult) return KNN_ERR_INVALID_ARG;
+    *bytes_out = value * mult;
+    return KNN_OK;
+}
+
+extern "C" const char* knn_status_string(knn_status s) {
+    switch (s) {
+        case KNN_OK: return "ok";
+        case KNN_ERR_INVALID_ARG: return "invalid argument";
+        case KNN_ERR_MEM_LIMIT_TOO_SMALL: return "memory limit below the smallest feasible plan";
+        case KNN_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than the plan requires";
+        case KNN_ERR_UNSUPPORTED: return "unsupported size (n >= 2^31 or k > KNN_MAX_K)";
+        case KNN_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+namespace {
+
+// bytes of the two list arrays (keys fp32, indices int32) for `rows` queries and S ranges
+uint64_t lists_bytes_for(uint64_t rows, uint64_t S, uint64_t k) {
+    return 2 * align_up(rows * S * k * 4);
+}
+
+// largest row count whose lists fit in `avail` bytes with S ranges
+int64_t rows_fitting(uint64_t avail, uint64_t S, uint64_t k) {
+    // 2 * align_up(x) <= avail  <=>  x <= floor(floor(avail / 2) / kAlign) * kAlign
+    uint64_t usable = avail / 2 / kAlign * kAlign;
+    return knn_chunk_rows(usable, S * k * 4);
+}
+
+}  // namespace
+
+extern "C" knn_status knn_plan(int64_t m, int64_t n, int32_t d, int32_t k,
+                               uint64_t mem_limit_bytes, knn_plan_t* out) {
+    if (!out) return KNN_ERR_INVALID_ARG;
+    memset(out, 0, sizeof(*out));
+    if (m < 0 || n < 1 || d < 1 || k < 1 || (int64_t)k > n) return KNN_ERR_INVALID_ARG;
+    if (n >= (int64_t)1 << 31 || k > KNN_MAX_K) return KNN_ERR_UNSUPPORTED;
+    out->m = m;
+    out->n = n;
+    out->d = d;
+    out->k = k;
+    out->streams = 1;
+    const bool lowd = d <= kLowdMaxD;
+    out->path = lowd ? KNN_PATH_LOWD : KNN_PATH_MFMA;
+    out->tile_q = lowd ? kLowdTileQ : kMfmaTileQ;
+    out->tile_x = lowd ? kLowdUnroll : kMfmaTileX;
+    out->norms_bytes = lowd ? 0 : align_up((uint64_t)n * 4);
+    const int64_t tile = out->tile_q;
+    const int64_t min_rows = m < tile ? (m > 0 ? m : 1) : tile;
+    out->min_limit_bytes = out->norms_bytes + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k);
+    if (m == 0) return KNN_OK;
+    if (mem_limit_bytes < out->min_limit_bytes) return KNN_ERR_MEM_LIMIT_TOO_SMALL;
+    const uint64_t avail = mem_limit_bytes - out->norms_bytes;
+
+    const int64_t tiles_total = (m + tile - 1) / tile;
+    int64_t s_max = n / kMinSplitPoints;
+    if (s_max < 1) s_max = 1;
+    if (s_max > kMaxSplits) s_max = kMaxSplits;
+    int64_t s_want = (kTargetWorkgroups + tiles_total - 1) / tiles_total;
+    if (s_want < 1) s_want = 1;
+    if (s_want > s_max) s_want = s_max;
+
+    // smallest S whose launch reaches the target width; otherwise the widest launch
+    int64_t best_s = 0, best_rows = 0, best_wgs = -1;
+    for (int64_t S = 1; S <= s_want; ++S) {
+        int64_t rows = rows_fitting(avail, (uint64_t)S, (uint64_t)k);
+        if (rows > kMaxChunkRows) rows = kMaxChunkRows;
+        if (rows >= m) rows = m;
+        else rows = rows / tile * tile;
+        if (rows < 1) continue;
+        int64_t wgs = (rows + tile - 1) / tile * S;
+        int64_t score = wgs < kTargetWorkgroups ? wgs : kTargetWorkgroups;
+        if (score > best_wgs) {
+            best_wgs = score;
+            best_s = S;
+            best_rows = rows;
+        }
+    }
+    if (best_s == 0) return KNN_ERR_MEM_LIMIT_TOO_SMALL;
+    out->n_splits = (int32_t)best_s;
+    out->chunk_rows = best_rows;
+    out->q_chunks = (m + best_rows - 1) / best_rows;
+    out->lists_bytes = lists_bytes_for((uint64_t)best_rows, (uint64_t)best_s, (uint64_t)k);
+    out->workspace_bytes = out->norms_bytes + out->lists_bytes;
+    return KNN_OK;
+}
+
+extern "C" uint64_t knn_workspace_bytes(int64_t m, int64_t n, int32_t d, int32_t k,
+                                        uint64_t mem_limit_bytes) {
+    knn_plan_t p;
+    if (knn_plan(m, n, d, k, mem_limit_bytes, &p) != KNN_OK) return 0;
+    return p.workspace_bytes;
+}

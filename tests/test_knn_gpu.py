@@ -1,0 +1,234 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle.
+
+Sizes are small enough for the oracle to finish in seconds yet span several tiles, several
+point ranges and ragged tails on both kernel families (d <= 8 and d > 8).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import workloads as W
+from parity import check
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def K():
+    import paper_2206_14148_amd as K
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    K.load()
+    return K
+
+
+def run_gpu(K, Q, X, k, limit, q_is_x=False):
+    Xd = torch.from_numpy(X).cuda()
+    Qd = Xd if q_is_x else torch.from_numpy(Q).cuda()
+    idx, dist = K.knn_search(Qd, Xd, k, limit)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), dist.cpu().numpy()
+
+
+def parity(K, oracle, Q, X, k, limit=64 * W.MB, q_is_x=False, rows=None):
+    idx, dist = run_gpu(K, Q, X, k, limit, q_is_x)
+    o_idx, o_dist, o_next = oracle.knn(Q, X, k, rows=rows)
+    if rows is not None:
+        idx, dist = idx[rows], dist[rows]
+    sel = np.arange(Q.shape[0]) if rows is None else rows
+
+    def pair_dist(cols):
+        qi = np.repeat(sel, cols.shape[1])
+        return oracle.sqdist_pairs(Q, X, qi, cols.ravel()).reshape(cols.shape)
+
+    stats = check(idx, dist, o_idx, o_dist, o_next, X.shape[0],
+                  pair_dist if Q.shape[0] * k <= 20000 else None)
+    say("   parity", stats)
+    return stats, idx, dist
+
+
+# (seed, m, n, d, k, kind)
+SMALL = [
+    (0, 1, 1, 1, 1, "normal"),          # smallest possible call
+    (1, 3, 5, 3, 5, "normal"),          # k == n on the low-d path
+    (2, 300, 5000, 3, 16, "uniform"),   # low-d, two point ranges, ragged query tile
+    (3, 257, 1003, 8, 7, "normal"),     # low-d widest d, one query past a tile
+    (4, 70, 9001, 2, 33, "uniform"),    # low-d, k > 32, many ranges
+    (5, 5, 129, 9, 129, "normal"),      # matrix path, k == n, one point past a tile
+    (6, 64, 300, 17, 1, "normal"),      # matrix path, k == 1, d not a multiple of 4
+    (7, 130, 4100, 100, 100, "normal"),  # matrix path, k = 100, ragged everything
+    (8, 1000, 10000, 16, 10, "normal"),  # shape of config 1
+    (9, 200, 3000, 784, 10, "sparse0"),  # d = 784 as in config 3 (small n)
+    (10, 33, 20000, 128, 64, "normal"),  # many point ranges, k = 64
+    (11, 129, 2500, 10, 12, "normal"),   # unaligned rows (d = 10)
+]
+
+
+@pytest.mark.parametrize("seed,m,n,d,k,kind", SMALL)
+def test_parity_small(K, oracle, seed, m, n, d, k, kind):
+    say(f"\ncase seed={seed} m={m} n={n} d={d} k={k} kind={kind}")
+    if kind == "sparse0":
+        Q, X = W.make(W.scaled(3, m=m, n=n))
+    else:
+        Q, X = W.random_case(100 + seed, m, n, d, kind)
+    stats, _, _ = parity(K, oracle, Q, X, k)
+    assert stats["strict_rows"] >= 0.98 * stats["rows"]
+
+
+@pytest.mark.parametrize("d", [1])
+def test_integer_line_closed_form(K, d):
+    # X[j] = j on a line: neighbours of i are i, i-1, i+1, i-2, ... with exact integer
+    # distances and every +-step tie resolved to the lower index
+    n = 700
+    X = np.arange(n, dtype=np.float32).reshape(n, 1)
+    k = 9
+    idx, dist = run_gpu(K, X, X, k, 64 * W.MB, q_is_x=True)
+    for i in (0, 1, 3, 4, 5, 350, 695, 698, 699):
+        want = [(0, i)]
+        for step in range(1, n):
+            for j in (i - step, i + step):
+                if 0 <= j < n:
+                    want.append((step * step, j))
+        want = want[:k]
+        assert idx[i].tolist() == [j for _, j in want], i
+        assert dist[i].tolist() == [float(v) for v, _ in want], i
+
+
+@pytest.mark.parametrize("d,n", [(3, 3000), (16, 3000), (40, 2600)])
+def test_duplicated_points_keep_index_order(K, oracle, d, n):
+    # every point twice: rows 2j and 2j+1 are identical, so results come in (2j, 2j+1) pairs
+    Q, X = W.random_case(200 + d, 150, n // 2, d)
+    X2 = np.repeat(X, 2, axis=0)
+    k = 11
+    idx, dist = run_gpu(K, Q, X2, k, 64 * W.MB)
+    o_idx, o_dist, _ = oracle.knn(Q, X2, k)
+    assert np.array_equal(idx, o_idx)
+    pairs = idx[:, : k - 1].reshape(idx.shape[0], -1, 2)
+    assert np.all(pairs[:, :, 0] % 2 == 0) and np.all(pairs[:, :, 1] == pairs[:, :, 0] + 1)
+    assert np.all(idx[:, k - 1] % 2 == 0)  # the odd one out is the lower twin
+    np.testing.assert_allclose(dist, o_dist, rtol=1e-6, atol=1e-7)
+
+
+@pytest.mark.parametrize("d", [3, 12])
+def test_exact_ties_on_integer_grid(K, oracle, d):
+    # small integer coordinates: all arithmetic is exact in fp32 and fp64, ties are massive,
+    # so the result is unique under the (distance, index) order and must match bit for bit
+    Q, X = W.random_case(300 + d, 260, 6000, d, kind="grid")
+    for k in (1, 8, 50):
+        idx, dist = run_gpu(K, Q, X, k, 64 * W.MB)
+        o_idx, o_dist, _ = oracle.knn(Q, X, k)
+        assert np.array_equal(idx, o_idx), (d, k)
+        assert np.array_equal(dist.astype(np.float64), o_dist), (d, k)
+
+
+def test_self_distance_zero_when_queries_are_the_points(K, oracle):
+    w = W.scaled(2, n=30000)
+    Q, X = W.make(w)
+    stats, idx, dist = parity(K, oracle, Q, X, w.k, q_is_x=True,
+                              rows=W.sample_rows(w, 600))
+    idx_all, dist_all = run_gpu(K, X, X, w.k, w.mem_limit, q_is_x=True)
+    assert np.array_equal(idx_all[:, 0], np.arange(30000))
+    assert np.all(dist_all[:, 0] == 0.0)
+    assert stats["strict_rows"] == stats["rows"]
+
+
+@pytest.mark.parametrize("m,n,d,k", [(3000, 9000, 3, 10), (700, 12000, 32, 20)])
+def test_result_does_not_depend_on_the_memory_limit(K, m, n, d, k):
+    # same answer, bit for bit, whatever the limit forces the plan to be (chunks, ranges)
+    Q, X = W.random_case(400 + d, m, n, d)
+    lo = K.knn_plan(m, n, d, k, 1 << 40).min_limit_bytes
+    limits = [lo, lo + 70_000, lo + 500_000, 64 * W.MB, 8 * W.GB]
+    plans = [K.knn_plan(m, n, d, k, lim) for lim in limits]
+    say("   plans", [(p.q_chunks, p.n_splits, p.workspace_bytes) for p in plans])
+    assert len({(p.q_chunks, p.n_splits) for p in plans}) >= 3  # the plans really differ
+    ref = None
+    for lim in limits:
+        idx, dist = run_gpu(K, Q, X, k, lim)
+        if ref is None:
+            ref = (idx, dist)
+        else:
+            assert np.array_equal(idx, ref[0]) and np.array_equal(dist, ref[1]), lim
+
+
+@pytest.mark.parametrize("m,n,d,k", [(1500, 8000, 3, 16), (400, 9000, 24, 10)])
+def test_workspace_bound_is_respected(K, m, n, d, k):
+    # guard bytes right behind the planned workspace must survive the call
+    Q, X = W.random_case(500 + d, m, n, d)
+    Qd, Xd = torch.from_numpy(Q).cuda(), torch.from_numpy(X).cuda()
+    limit = K.knn_plan(m, n, d, k, 1 << 40).min_limit_bytes + 100_000
+    plan = K.knn_plan(m, n, d, k, limit)
+    assert plan.workspace_bytes <= limit
+    guard = 4096
+    ws = torch.full((plan.workspace_bytes + guard,), 0xA5, dtype=torch.uint8, device="cuda")
+    idx, dist = K.knn_search(Qd, Xd, k, limit, workspace=ws[: plan.workspace_bytes])
+    torch.cuda.synchronize()
+    assert bool((ws[plan.workspace_bytes:] == 0xA5).all())
+    last_plan, peak = K.knn_last_stats()
+    assert peak == plan.workspace_bytes <= limit and last_plan.q_chunks == plan.q_chunks
+    ref_idx, ref_dist = run_gpu(K, Q, X, k, 8 * W.GB)
+    assert np.array_equal(idx.cpu().numpy(), ref_idx)
+    assert np.array_equal(dist.cpu().numpy(), ref_dist)
+
+
+def test_row_strides_larger_than_d(K, oracle):
+    for d, ld in ((3, 5), (20, 24), (20, 23)):
+        Q, X = W.random_case(600 + ld, 90, 2100, d)
+        Xp = torch.zeros((2100, ld), device="cuda")
+        Qp = torch.zeros((90, ld), device="cuda")
+        Xp[:, :d] = torch.from_numpy(X).cuda()
+        Qp[:, :d] = torch.from_numpy(Q).cuda()
+        Xp[:, d:] = 1e30  # padding must never be read as data
+        idx, dist = K.knn_search(Qp[:, :d], Xp[:, :d], 6, 64 * W.MB)
+        torch.cuda.synchronize()
+        o_idx, o_dist, o_next = oracle.knn(Q, X, 6)
+        check(idx.cpu().numpy(), dist.cpu().numpy(), o_idx, o_dist, o_next, 2100)
+
+
+def test_errors_leave_outputs_untouched(K):
+    Q, X = W.random_case(700, 10, 50, 4)
+    Qd, Xd = torch.from_numpy(Q).cuda(), torch.from_numpy(X).cuda()
+    idx = torch.full((10, 3), -7, dtype=torch.int32, device="cuda")
+    dist = torch.full((10, 3), -7.0, device="cuda")
+    with pytest.raises(K.KnnError) as ei:
+        K.knn_search(Qd, Xd, 3, 100, out=(idx, dist))  # limit far too small
+    assert ei.value.status == K.KNN_ERR_MEM_LIMIT_TOO_SMALL
+    with pytest.raises(K.KnnError) as ei:
+        K.knn_search(Qd, Xd, 51, 64 * W.MB)  # k > n
+    assert ei.value.status == K.KNN_ERR_INVALID_ARG
+    ws = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(K.KnnError) as ei:
+        K.knn_search(Qd, Xd, 3, 64 * W.MB, workspace=ws[:8], out=(idx, dist))
+    assert ei.value.status == K.KNN_ERR_WORKSPACE_TOO_SMALL
+    with pytest.raises(K.KnnError):
+        K.knn_search(Qd.cpu(), Xd.cpu(), 3, 64 * W.MB)  # no CPU path
+    torch.cuda.synchronize()
+    assert bool((idx == -7).all()) and bool((dist == -7.0).all())
+    e_idx, e_dist = K.knn_search(Qd[:0], Xd, 3, 64 * W.MB)  # m == 0
+    assert e_idx.shape == (0, 3) and e_dist.shape == (0, 3)
+
+
+def test_two_runs_are_bit_identical_and_streams_are_honoured(K):
+    Q, X = W.random_case(800, 500, 7000, 48)
+    Qd, Xd = torch.from_numpy(Q).cuda(), torch.from_numpy(X).cuda()
+    a_idx, a_dist = K.knn_search(Qd, Xd, 25, 64 * W.MB)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        b_idx, b_dist = K.knn_search(Qd, Xd, 25, 64 * W.MB)
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(a_idx, b_idx) and torch.equal(a_dist, b_dist)
+
+
+def test_large_k(K, oracle):
+    Q, X = W.random_case(900, 40, 3000, 5)
+    parity(K, oracle, Q, X, 1000)
+    Q, X = W.random_case(901, 40, 3000, 20)
+    parity(K, oracle, Q, X, 1024)

@@ -1,0 +1,148 @@
+"""CPU-only tests: the C-ABI library loads, exports every declared symbol, and the host
+planner's arithmetic holds (no GPU call is made)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2206_14148_amd as K
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "knn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(knn_[a-z_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = K.load()
+    names = declared_symbols()
+    assert set(names) == set(K.EXPORTED_SYMBOLS)
+    for name in names:
+        assert getattr(lib, name) is not None
+    raw = ctypes.CDLL(K.library_path())
+    for name in names:
+        getattr(raw, name)  # AttributeError if missing
+
+
+def test_worked_example_from_the_paper_appendix():
+    # golden fixture: 1GB threshold, rows of 1e6 fp64 entries -> 125 rows
+    path = os.path.join(ROOT, "tests", "golden", "planner_worked_example.txt")
+    rows = [ln.split() for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    assert rows
+    for limit_text, entries, width, expected in rows:
+        limit = K.knn_parse_size(limit_text)
+        assert limit == 10 ** 9
+        assert K.knn_chunk_rows(limit, int(entries) * int(width)) == int(expected)
+
+
+@pytest.mark.parametrize("text,val", [("64MB", 64 * 10 ** 6), ("1GB", 10 ** 9), ("500MB", 5 * 10 ** 8),
+                                      ("2kb", 2000), ("123", 123), ("7B", 7), ("3TB", 3 * 10 ** 12),
+                                      (" 8GB ", 8 * 10 ** 9)])
+def test_parse_size_decimal(text, val):
+    assert K.knn_parse_size(text) == val
+
+
+@pytest.mark.parametrize("text", ["", "GB", "1.5GB", "1GiB", "-1MB", "1 GB x", "99999999999999999999999"])
+def test_parse_size_rejects(text):
+    with pytest.raises(K.KnnError):
+        K.knn_parse_size(text)
+
+
+def test_chunk_rows_floor():
+    assert K.knn_chunk_rows(999, 1000) == 0
+    assert K.knn_chunk_rows(1000, 1000) == 1
+    assert K.knn_chunk_rows(1999, 1000) == 1
+    assert K.knn_chunk_rows(5, 0) == 0
+
+
+CONFIGS = [
+    (1_000, 10_000, 16, 10, 64 * 10 ** 6),
+    (1_000_000, 1_000_000, 3, 16, 10 ** 9),
+    (10_000, 1_000_000, 784, 10, 2 * 10 ** 9),
+    (100_000, 10_000_000, 128, 100, 8 * 10 ** 9),
+    (50_000, 2_000_000, 256, 32, 128 * 10 ** 6),
+    (50_000, 2_000_000, 256, 32, 10 ** 9),
+    (50_000, 2_000_000, 256, 32, 8 * 10 ** 9),
+    (50_000, 2_000_000, 256, 32, 64 * 10 ** 9),
+]
+
+
+@pytest.mark.parametrize("m,n,d,k,limit", CONFIGS)
+def test_every_baseline_config_has_a_plan_under_its_limit(m, n, d, k, limit):
+    p = K.knn_plan(m, n, d, k, limit)
+    assert p.workspace_bytes <= limit
+    assert p.workspace_bytes == p.norms_bytes + p.lists_bytes
+    assert p.path == (K.KNN_PATH_LOWD if d <= 8 else K.KNN_PATH_MFMA)
+    assert p.q_chunks * p.chunk_rows >= m
+    assert p.chunk_rows == m or p.chunk_rows % p.tile_q == 0
+    # every concurrently live list is counted: rows x ranges x k x (key + index)
+    assert p.lists_bytes >= p.chunk_rows * p.n_splits * k * 8
+    assert K.knn_workspace_bytes(m, n, d, k, limit) == p.workspace_bytes
+
+
+def test_min_limit_is_exact_boundary():
+    for (m, n, d, k) in [(1000, 10000, 16, 10), (5000, 20000, 3, 16), (7, 50, 4, 50), (100000, 10 ** 7, 128, 100)]:
+        p = K.knn_plan(m, n, d, k, 1 << 40)
+        lo = p.min_limit_bytes
+        q = K.knn_plan(m, n, d, k, lo)
+        assert q.workspace_bytes <= lo and q.n_splits == 1
+        with pytest.raises(K.KnnError) as ei:
+            K.knn_plan(m, n, d, k, lo - 1)
+        assert ei.value.status == K.KNN_ERR_MEM_LIMIT_TOO_SMALL
+        assert ei.value.min_limit_bytes == lo
+
+
+def test_small_limits_cut_queries_into_chunks_and_never_exceed_the_limit():
+    m, n, d, k = 50_000, 2_000_000, 256, 32
+    prev_chunks = None
+    for limit in [8_100_000, 8_500_000, 9_000_000, 12_000_000, 20_000_000, 50_000_000, 128_000_000, 10 ** 9]:
+        p = K.knn_plan(m, n, d, k, limit)
+        assert p.workspace_bytes <= limit
+        assert p.chunk_rows >= p.tile_q or p.chunk_rows == m
+        if prev_chunks is not None:
+            assert p.q_chunks <= prev_chunks  # more memory never means more passes
+        prev_chunks = p.q_chunks
+    assert K.knn_plan(m, n, d, k, 8_100_000).q_chunks > 1
+
+
+def test_plan_argument_errors():
+    bad = [(-1, 10, 3, 1), (5, 0, 3, 1), (5, 10, 0, 1), (5, 10, 3, 0), (5, 10, 3, 11)]
+    for m, n, d, k in bad:
+        with pytest.raises(K.KnnError) as ei:
+            K.knn_plan(m, n, d, k, 10 ** 9)
+        assert ei.value.status == K.KNN_ERR_INVALID_ARG
+    with pytest.raises(K.KnnError) as ei:
+        K.knn_plan(5, 1 << 31, 3, 1, 10 ** 12)
+    assert ei.value.status == K.KNN_ERR_UNSUPPORTED
+    with pytest.raises(K.KnnError) as ei:
+        K.knn_plan(5, 5000, 3, K.KNN_MAX_K + 1, 10 ** 12)
+    assert ei.value.status == K.KNN_ERR_UNSUPPORTED
+    p = K.knn_plan(0, 10, 3, 2, 0)  # no queries: empty plan, nothing needed
+    assert p.q_chunks == 0 and p.workspace_bytes == 0
+
+
+def test_status_strings_are_distinct():
+    texts = {K.knn_status_string(s) for s in range(6)}
+    assert len(texts) == 6
+
+
+def test_host_entry_points_reject_bad_arguments_without_a_gpu():
+    # knn_search validates before it touches HIP: these return synchronously on any machine
+    st = K.knn_search_raw(0, 3, 0, 3, 5, 10, 3, 11, 10 ** 9, 0, 0, 0, 0, 0)  # k > n
+    assert st == K.KNN_ERR_INVALID_ARG
+    st = K.knn_search_raw(0, 3, 0, 3, 5, 10, 3, 2, 10 ** 9, 0, 0, 0, 0, 0)  # null X
+    assert st == K.KNN_ERR_INVALID_ARG
+    st = K.knn_search_raw(256, 2, 256, 3, 5, 10, 3, 2, 10 ** 9, 256, 1 << 20, 256, 256, 0)  # ldq < d
+    assert st == K.KNN_ERR_INVALID_ARG
+    st = K.knn_search_raw(256, 3, 256, 3, 5, 10, 3, 2, 16, 256, 1 << 20, 256, 256, 0)  # limit too small
+    assert st == K.KNN_ERR_MEM_LIMIT_TOO_SMALL
+    st = K.knn_search_raw(256, 3, 256, 3, 5, 10, 3, 2, 10 ** 9, 256, 8, 256, 256, 0)  # workspace too small
+    assert st == K.KNN_ERR_WORKSPACE_TOO_SMALL
+    st = K.knn_search_raw(256, 3, 256, 3, 5, 10, 3, 2, 10 ** 9, 257, 1 << 20, 256, 256, 0)  # misaligned ws
+    assert st == K.KNN_ERR_INVALID_ARG
+    st = K.knn_search_raw(0, 3, 256, 3, 0, 10, 3, 2, 0, 0, 0, 0, 0, 0)  # m == 0: nothing to do
+    assert st == K.KNN_OK
