@@ -81,8 +81,10 @@ struct MergeScratch {
 // the merged list, i.e. the new acceptance threshold.  All 64 lanes must call it together.
 __device__ float wave_merge(float* __restrict__ gk, int* __restrict__ gi, int k, float ckey,
                             int cidx, const MergeScratch& sc, int lane) {
+    // A list is read and written only by the wave that owns its query, so wave-level
+    // ordering is enough; wave_sync() also orders this wave's earlier global stores to the
+    // list before the loads below (same compute unit, same vector L1).
     wave_sync();  // earlier uses of the scratch are finished
-    __threadfence();
     wave_sort64(ckey, cidx, lane);
     sc.cand_key[lane] = ckey;
     sc.cand_idx[lane] = cidx;
@@ -126,7 +128,7 @@ __device__ float wave_merge(float* __restrict__ gk, int* __restrict__ gi, int k,
         }
     }
     tau = wave_min(tau);
-    __threadfence();
+    wave_sync();
     return tau;
 }
 
