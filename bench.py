@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole kNN hot path on one MI355X.
+
+A "step" is one knn_search call (norms, tiled distances + running top-k, merge, exact
+re-evaluation) over one synthetic workload whose inputs are already resident in HBM.
+Default workload: the point-cloud kNN graph (m = n = 1e6, d = 3, k = 16, 1 GB limit).
+
+Prints ONE JSON line: pairs/s for the whole job, the roofline of the dominant kernel
+(measured live with HIP events on the launch stream) and the CPU oracle timed on the host
+cores on a bounded sample of the same workload (reported baseline, also a parity check).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+# published MI355X peaks
+PEAK_FP32_MATRIX_TFLOPS = 157.3
+PEAK_FP32_VECTOR_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per search-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/*_pmc.txt), scaled by the copy-kernel calibration stated there.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c2", help="c1..c5 (default c2, the metric's workload)")
+    ap.add_argument("--mem-limit", default=None, help="e.g. 128MB, 1GB (decimal); default: the workload's")
+    ap.add_argument("--m", type=int, default=None, help="override the query count (testing)")
+    ap.add_argument("--n", type=int, default=None, help="override the point count (testing)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle time budget; 0 skips it")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 "
+              "(sharding over GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2206_14148_amd as K
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    K.load()
+    cfg = int(args.workload.lstrip("c"))
+    w = W.scaled(cfg, m=args.m, n=args.n) if (args.m or args.n) else W.WORKLOADS[cfg]
+    limit = K.knn_parse_size(args.mem_limit) if args.mem_limit else w.mem_limit
+
+    t0 = time.time()
+    Q, X = W.make(w)
+    log(f"[bench] inputs {w.name}: m={w.m} n={w.n} d={w.d} k={w.k} generated in {time.time()-t0:.1f}s")
+    dev = torch.device("cuda:0")
+    Xd = torch.from_numpy(X).to(dev)
+    Qd = Xd if w.q_is_x else torch.from_numpy(Q).to(dev)
+    plan = K.knn_plan(w.m, w.n, w.d, w.k, limit)
+    assert plan.workspace_bytes <= limit
+    ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
+    idx = torch.empty((w.m, w.k), dtype=torch.int32, device=dev)
+    dist = torch.empty((w.m, w.k), dtype=torch.float32, device=dev)
+    log(f"[bench] plan: path={'lowd' if plan.path == 0 else 'mfma'} chunks={plan.q_chunks} "
+        f"ranges={plan.n_splits} workspace={plan.workspace_bytes} B (limit {limit} B)")
+
+    def step():
+        K.knn_search(Qd, Xd, w.k, limit, workspace=ws, out=(idx, dist))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    K.knn_profile_enable(True)
+    K.knn_profile_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    norms_ms, search_ms, refine_ms, launches = K.knn_profile_read()
+    K.knn_profile_enable(False)
+    ms_per_step = elapsed * 1e3 / args.steps
+    pairs = float(w.m) * float(w.n)
+    value = pairs * args.steps / elapsed
+    log(f"[bench] {ms_per_step:.2f} ms/step, {value:.3e} pairs/s; kernels per step: "
+        f"norms {norms_ms/args.steps:.3f} ms, search {search_ms/args.steps:.3f} ms "
+        f"({launches // max(args.steps,1)} launch), merge+refine {refine_ms/args.steps:.3f} ms")
+
+    # roofline of the dominant kernel (the search kernel), per launch
+    avg_launch_s = (search_ms / max(launches, 1)) * 1e-3
+    pairs_per_launch = pairs * args.steps / max(launches, 1)
+    traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
+    if plan.path == K.KNN_PATH_MFMA:
+        flops = 2.0 * w.d * pairs_per_launch  # the -2 Q X^T contraction
+        achieved = flops / avg_launch_s / 1e12
+        roofline = {"bound": "mfma", "kernel": "knn_mfma_kernel", "achieved": achieved,
+                    "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_FP32_MATRIX_TFLOPS, "traffic": traffic,
+                    "flops_per_pair": 2 * w.d}
+    else:
+        # difference form: d subtractions, d multiplications, d-1 additions per pair
+        flops = (3.0 * w.d - 1.0) * pairs_per_launch
+        achieved = flops / avg_launch_s / 1e12
+        roofline = {"bound": "alu", "kernel": "knn_lowd_kernel", "achieved": achieved,
+                    "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_FP32_VECTOR_TFLOPS, "traffic": traffic,
+                    "flops_per_pair": 3 * w.d - 1,
+                    # what a design that stores the distance tile would move: 4 B out + 4 B in
+                    "hbm_equiv_frac": (pairs_per_launch / avg_launch_s) * 8.0 / (PEAK_HBM_GBS * 1e9)}
+    roofline["avg_launch_ms"] = avg_launch_s * 1e3
+
+    cpu_baseline = None
+    parity = None
+    if args.cpu_seconds > 0:
+        import oracle
+        from parity import check
+
+        threads = oracle.threads_used()
+        probe_rows = W.sample_rows(w, min(w.m, 4 * threads))
+        t0 = time.perf_counter()
+        oracle.knn(Q, X, w.k, rows=probe_rows)
+        probe_rate = len(probe_rows) / max(time.perf_counter() - t0, 1e-6)
+        nrows = int(max(len(probe_rows), min(w.m, probe_rate * args.cpu_seconds)))
+        rows = W.sample_rows(w, nrows)
+        t0 = time.perf_counter()
+        o_idx, o_dist, o_next = oracle.knn(Q, X, w.k, rows=rows)
+        dt = time.perf_counter() - t0
+        cpu_baseline = {"value": len(rows) * float(w.n) / dt, "unit": "pairs/s", "cores": threads,
+                        "kind": "oracle",
+                        "sample": f"{len(rows)} seeded query rows x all {w.n} points of {w.name}, {dt:.1f} s"}
+        rows_t = torch.from_numpy(rows).to(dev)
+        parity = check(idx[rows_t].cpu().numpy(), dist[rows_t].cpu().numpy(), o_idx, o_dist, o_next, w.n)
+        log(f"[bench] oracle: {cpu_baseline['value']:.3e} pairs/s on {threads} threads; parity {parity}")
+
+    out = {
+        "metric": "query-point pairs per second, exact brute-force kNN (m*n/s)",
+        "value": value, "unit": "pairs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "m": w.m, "n": w.n, "d": w.d, "k": w.k,
+                   "mem_limit_bytes": limit, "workspace_bytes": plan.workspace_bytes,
+                   "q_chunks": plan.q_chunks, "point_ranges": plan.n_splits,
+                   "path": "lowd" if plan.path == 0 else "mfma"},
+        "kernel_ms_per_step": {"norms": norms_ms / args.steps, "search": search_ms / args.steps,
+                               "merge_refine": refine_ms / args.steps},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

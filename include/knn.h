@@ -136,6 +136,19 @@ knn_status knn_parse_size(const char *text /* HOST */, uint64_t *bytes_out /* HO
  */
 int64_t knn_chunk_rows(uint64_t limit_bytes, uint64_t row_bytes);
 
+/*
+ * Kernel timing for benchmarks (section 5 reports elapsed time next to memory use).
+ * knn_profile_enable(1) makes every later knn_search on this thread bracket its kernels
+ * with HIP events recorded on the caller's stream: [norms] [search] [merge+refine] per
+ * query chunk.  knn_profile_read waits for those events, adds the elapsed milliseconds of
+ * all searches since the last read into the three HOST outputs (any may be NULL), stores
+ * the number of search-kernel launches, and resets the tally.  Events are host objects; no
+ * device memory is allocated.  Off by default; knn_profile_enable(0) frees the events.
+ */
+knn_status knn_profile_enable(int32_t on);
+knn_status knn_profile_read(float *norms_ms /* HOST */, float *search_ms /* HOST */,
+                            float *refine_ms /* HOST */, int64_t *search_launches /* HOST */);
+
 /* Last HIP error text seen by this thread ("" if none). */
 const char *knn_last_hip_error(void);
 

@@ -24,7 +24,8 @@ KNN_PATH_MFMA = 1
 
 EXPORTED_SYMBOLS = (
     "knn_plan", "knn_workspace_bytes", "knn_search", "knn_last_stats", "knn_status_string",
-    "knn_parse_size", "knn_chunk_rows", "knn_last_hip_error",
+    "knn_parse_size", "knn_chunk_rows", "knn_last_hip_error", "knn_profile_enable",
+    "knn_profile_read",
 )
 
 
@@ -97,6 +98,10 @@ def load():
     lib.knn_parse_size.restype = ctypes.c_int
     lib.knn_chunk_rows.argtypes = [u64, u64]
     lib.knn_chunk_rows.restype = i64
+    lib.knn_profile_enable.argtypes = [i32]
+    lib.knn_profile_enable.restype = ctypes.c_int
+    lib.knn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float)] * 3 + [ctypes.POINTER(i64)]
+    lib.knn_profile_read.restype = ctypes.c_int
     lib.knn_last_hip_error.argtypes = []
     lib.knn_last_hip_error.restype = ctypes.c_char_p
     _lib = lib
@@ -144,6 +149,21 @@ def knn_last_stats():
     if st != KNN_OK:
         raise KnnError(st, "no successful knn_search on this thread yet")
     return _plan_from_struct(ps), int(peak.value)
+
+
+def knn_profile_enable(on: bool) -> None:
+    load().knn_profile_enable(1 if on else 0)
+
+
+def knn_profile_read():
+    """(norms_ms, search_ms, refine_ms, search_launches) summed since the last read."""
+    a, b, c = ctypes.c_float(0), ctypes.c_float(0), ctypes.c_float(0)
+    launches = ctypes.c_int64(0)
+    st = load().knn_profile_read(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
+                                 ctypes.byref(launches))
+    if st != KNN_OK:
+        raise KnnError(st, knn_status_string(st))
+    return float(a.value), float(b.value), float(c.value), int(launches.value)
 
 
 def knn_search_raw(q_ptr, ldq, x_ptr, ldx, m, n, d, k, mem_limit_bytes, ws_ptr, ws_bytes,

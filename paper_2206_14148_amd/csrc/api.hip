@@ -10,6 +10,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "../../include/knn.h"
 #include "knn_config.h"
@@ -22,6 +23,47 @@ thread_local uint64_t g_last_peak = 0;
 thread_local bool g_have_last = false;
 thread_local char g_hip_error[256] = "";
 
+// Event brackets of the profiled searches since the last knn_profile_read.
+struct Bracket {
+    hipEvent_t begin, end;
+    int kind;  // 0 norms, 1 search, 2 merge+refine
+};
+thread_local bool g_profile = false;
+thread_local std::vector<Bracket> g_brackets;
+thread_local std::vector<hipEvent_t> g_event_pool;
+
+hipEvent_t take_event() {
+    hipEvent_t ev = nullptr;
+    if (!g_event_pool.empty()) {
+        ev = g_event_pool.back();
+        g_event_pool.pop_back();
+    } else if (hipEventCreate(&ev) != hipSuccess) {
+        ev = nullptr;
+    }
+    return ev;
+}
+
+// Records an event on the stream when profiling is on; returns nullptr otherwise.
+hipEvent_t mark(hipStream_t stream) {
+    if (!g_profile) return nullptr;
+    hipEvent_t ev = take_event();
+    if (ev && hipEventRecord(ev, stream) != hipSuccess) {
+        g_event_pool.push_back(ev);
+        ev = nullptr;
+    }
+    return ev;
+}
+
+void close_bracket(hipEvent_t begin, hipStream_t stream, int kind) {
+    if (!begin) return;
+    hipEvent_t end = mark(stream);
+    if (!end) {
+        g_event_pool.push_back(begin);
+        return;
+    }
+    g_brackets.push_back({begin, end, kind});
+}
+
 knn_status hip_fail(hipError_t e, const char* what) {
     snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
     return KNN_ERR_HIP;
@@ -30,6 +72,43 @@ knn_status hip_fail(hipError_t e, const char* what) {
 }  // namespace
 
 extern "C" const char* knn_last_hip_error(void) { return g_hip_error; }
+
+extern "C" knn_status knn_profile_enable(int32_t on) {
+    g_profile = on != 0;
+    if (!g_profile) {
+        for (auto& b : g_brackets) {
+            g_event_pool.push_back(b.begin);
+            g_event_pool.push_back(b.end);
+        }
+        g_brackets.clear();
+        for (hipEvent_t ev : g_event_pool) (void)hipEventDestroy(ev);
+        g_event_pool.clear();
+    }
+    return KNN_OK;
+}
+
+extern "C" knn_status knn_profile_read(float* norms_ms, float* search_ms, float* refine_ms,
+                                       int64_t* search_launches) {
+    float sum[3] = {0.f, 0.f, 0.f};
+    int64_t launches = 0;
+    knn_status st = KNN_OK;
+    for (auto& b : g_brackets) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(b.end);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, b.begin, b.end);
+        if (e != hipSuccess) st = hip_fail(e, "profile event");
+        else sum[b.kind] += ms;
+        if (b.kind == 1) ++launches;
+        g_event_pool.push_back(b.begin);
+        g_event_pool.push_back(b.end);
+    }
+    g_brackets.clear();
+    if (norms_ms) *norms_ms = sum[0];
+    if (search_ms) *search_ms = sum[1];
+    if (refine_ms) *refine_ms = sum[2];
+    if (search_launches) *search_launches = launches;
+    return st;
+}
 
 extern "C" knn_status knn_last_stats(knn_plan_t* plan_out, uint64_t* peak_workspace_bytes) {
     if (!g_have_last) return KNN_ERR_INVALID_ARG;
@@ -70,13 +149,16 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
 
     hipError_t e;
     if (plan.path == KNN_PATH_MFMA) {
+        hipEvent_t t0 = mark(stream);
         e = launch_row_norms(X, ldx, n, d, xn, stream);
         if (e != hipSuccess) return hip_fail(e, "row norms launch");
+        close_bracket(t0, stream, 0);
     }
     for (int64_t c = 0; c < plan.q_chunks; ++c) {
         const int64_t row0 = c * plan.chunk_rows;
         const int64_t rows = (m - row0 < plan.chunk_rows) ? (m - row0) : plan.chunk_rows;
         const float* Qc = Q + row0 * ldq;
+        hipEvent_t t1 = mark(stream);
         if (plan.path == KNN_PATH_LOWD) {
             e = launch_lowd(Qc, ldq, X, ldx, rows, n, d, k, S, lk, li, stream);
             if (e != hipSuccess) return hip_fail(e, "low-d search launch");
@@ -84,9 +166,12 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
             e = launch_mfma(Qc, ldq, X, ldx, xn, rows, n, d, k, S, lk, li, stream);
             if (e != hipSuccess) return hip_fail(e, "mfma search launch");
         }
+        close_bracket(t1, stream, 1);
+        hipEvent_t t2 = mark(stream);
         e = launch_merge_refine(Qc, ldq, X, ldx, rows, n, d, k, S, lk, li, idx + row0 * k,
                                 dist + row0 * k, stream);
         if (e != hipSuccess) return hip_fail(e, "merge/refine launch");
+        close_bracket(t2, stream, 2);
     }
     g_last_plan = plan;
     g_last_peak = plan.workspace_bytes;
