@@ -46,6 +46,9 @@ def main() -> int:
     ap.add_argument("--m", type=int, default=None, help="override the query count (testing)")
     ap.add_argument("--n", type=int, default=None, help="override the point count (testing)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle time budget; 0 skips it")
+    ap.add_argument("--calibrate-copy-mb", type=int, default=0,
+                    help="also run one plain elementwise copy of this many MB (read + write) before "
+                         "the timed region, as the known-size reference for rocprofv3 --pmc byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 "
@@ -83,6 +86,13 @@ def main() -> int:
     def step():
         K.knn_search(Qd, Xd, w.k, limit, workspace=ws, out=(idx, dist))
 
+    if args.calibrate_copy_mb > 0:
+        src = torch.ones(args.calibrate_copy_mb * 250_000, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)  # one elementwise kernel: reads and writes calibrate_copy_mb MB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
