@@ -21,7 +21,10 @@ constexpr int kMfmaKC = 16;          // K columns staged in LDS per pipeline ste
 constexpr int kMfmaRowStride = 20;   // floats per staged row (16 + 4 pad, keeps 16 B alignment)
 constexpr int kMfmaCand = 32;        // candidate slots per query (LDS)
 
-constexpr int kTargetWorkgroups = 2048;  // launch width the planner aims for
+// Workgroups the chip holds at once (LDS-limited): the planner sizes launches in rounds of these.
+constexpr int kLowdResidentWorkgroups = 4 * kNumCU;
+constexpr int kMfmaResidentWorkgroups = 2 * kNumCU;
+constexpr int kWarmupPointsPerK = 64;     // list warm-up of one point range, in point-equivalents per k
 constexpr int kMaxSplits = 64;
 constexpr int64_t kMaxChunkRows = 1 << 22;  // keeps per-launch row counts and grids in int range
 constexpr int kMinSplitPoints = 2048;    // a point range shorter than this is not worth a split

@@ -283,21 +283,27 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_lowd_kernel(
 // is a per-lane compare.  The accumulators start at ||x||^2 and receive (-2 q) . x, which
 // gives the key  ||x||^2 - 2 q.x  (the distance minus the per-query constant ||q||^2).
 // ---------------------------------------------------------------------------------------
+// Four consecutive columns of one row, loaded from an address clamped into the matrix so that
+// the loads of a pipeline step issue back to back without control flow; mask_row4 zeroes
+// what was out of range once the data is used.  ALIGNED: rows are 16-byte aligned and d is
+// a multiple of 4, so one vector load covers the four columns.
 template <bool ALIGNED>
 __device__ __forceinline__ f32x4 load_row4(const float* __restrict__ base, int64_t ld,
                                            int64_t row, int64_t nrows, int col, int d) {
-    f32x4 v = {0.f, 0.f, 0.f, 0.f};
-    if (row < nrows && col < d) {
-        const float* p = base + row * ld + col;
-        if (ALIGNED && col + 4 <= d) {
-            v = *reinterpret_cast<const f32x4*>(p);
-        } else {
-            v[0] = p[0];
-            if (col + 1 < d) v[1] = p[1];
-            if (col + 2 < d) v[2] = p[2];
-            if (col + 3 < d) v[3] = p[3];
-        }
+    const float* p = base + (row < nrows ? row : nrows - 1) * ld;
+    f32x4 v;
+    if (ALIGNED) {
+        v = *reinterpret_cast<const f32x4*>(p + (col < d ? col : 0));
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = p[col + e < d ? col + e : 0];
     }
+    return v;
+}
+
+__device__ __forceinline__ f32x4 mask_row4(f32x4 v, bool row_ok, int col, int d, float scale) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = (row_ok && col + e < d) ? v[e] * scale : 0.f;
     return v;
 }
 
@@ -305,7 +311,7 @@ template <bool ALIGNED>
 __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
     const float* __restrict__ xn, int rows, int n, int d, int k, int S, int split_len,
-    float* __restrict__ lk, int* __restrict__ li) {
+    int BQ, int BS, float* __restrict__ lk, int* __restrict__ li) {
     constexpr int TQ = kMfmaTileQ, TX = kMfmaTileX, KC = kMfmaKC, RS = kMfmaRowStride;
     constexpr int C = kMfmaCand;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -327,8 +333,33 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
     }
     const int i32 = lane & 31;  // query column / point row inside a 32x32 block
     const int h = lane >> 5;    // which half of the wave
-    const int s = blockIdx.y;
-    const int wg_row0 = blockIdx.x * TQ;
+
+    // Workgroup -> (query tile, point range).  Consecutive workgroup ids go round-robin to
+    // the 8 XCDs, each with its own L2.  The (tile, range) grid is cut into blocks of
+    // BQ tiles x BS ranges; a block is handed to one XCD as BQ*BS consecutive workgroups of
+    // that XCD, so the workgroups resident there together re-use BQ query tiles and BS point
+    // streams out of its L2 instead of fetching BQ*BS private ones.
+    int s, wg_row0;
+    {
+        const int T = (rows + TQ - 1) / TQ;
+        const int nQB = (T + BQ - 1) / BQ;
+        const int nSB = S / BS;  // BS divides S
+        const int xcd = blockIdx.x & 7;
+        const int slot = blockIdx.x >> 3;
+        const int per_block = BQ * BS;
+        const int bseq = slot / per_block;
+        const int within = slot - bseq * per_block;
+        const int b = bseq * 8 + xcd;
+        if (b >= nQB * nSB) return;  // padding workgroup (before any barrier)
+        const int sb = b / nQB;
+        const int qb = b - sb * nQB;
+        const int si = within / BQ;
+        const int qi = within - si * BQ;
+        const int qtile = qb * BQ + qi;
+        if (qtile >= T) return;
+        s = sb * BS + si;
+        wg_row0 = qtile * TQ;
+    }
     const int my_q = wave * 32 + i32;  // query inside the workgroup tile
     const int r = wg_row0 + my_q;
     const bool active = r < rows;
@@ -357,33 +388,45 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
     const int srow = tid >> 2;
     const int scol = (tid & 3) * 4;
 
-    f32x4 gx0, gx1, gq0, gq1;
-    float gxn = kInf;
-    auto fetch = [&](int step) {
+    // Global -> register -> LDS staging runs one pipeline step ahead of the MFMA loop.
+    struct Staged {
+        f32x4 x0, x1, q0, q1;
+        float xnv;
+    };
+    auto fetch = [&](int step, Staged& g) {
         const int tile = step / nch;
         const int c = step - tile * nch;
         const int col = c * KC + scol;
         const int64_t jr = (int64_t)j0 + (int64_t)tile * TX + srow;
-        gx0 = load_row4<ALIGNED>(X, ldx, jr, j1, col, d);
-        gx1 = load_row4<ALIGNED>(X, ldx, jr + 64, j1, col, d);
-        gq0 = load_row4<ALIGNED>(Q, ldq, (int64_t)wg_row0 + srow, rows, col, d) * -2.f;
-        gq1 = load_row4<ALIGNED>(Q, ldq, (int64_t)wg_row0 + srow + 64, rows, col, d) * -2.f;
+        g.x0 = load_row4<ALIGNED>(X, ldx, jr, j1, col, d);
+        g.x1 = load_row4<ALIGNED>(X, ldx, jr + 64, j1, col, d);
+        g.q0 = load_row4<ALIGNED>(Q, ldq, (int64_t)wg_row0 + srow, rows, col, d);
+        g.q1 = load_row4<ALIGNED>(Q, ldq, (int64_t)wg_row0 + srow + 64, rows, col, d);
         if (c == 0 && tid < TX) {
             const int64_t jj = (int64_t)j0 + (int64_t)tile * TX + tid;
-            gxn = jj < j1 ? xn[jj] : kInf;  // rows past the range can never be accepted
+            g.xnv = xn[jj < j1 ? jj : j1 - 1];
         }
     };
-    auto stash = [&](int step) {
+    auto stash = [&](int step, const Staged& g) {
         const int tile = step / nch;
         const int c = step - tile * nch;
         const int buf = step & 1;
+        const int col = c * KC + scol;
+        const int64_t jr = (int64_t)j0 + (int64_t)tile * TX + srow;
         float* xb = xs + buf * TX * RS;
         float* qb = qs + buf * TQ * RS;
-        *reinterpret_cast<f32x4*>(xb + srow * RS + scol) = gx0;
-        *reinterpret_cast<f32x4*>(xb + (srow + 64) * RS + scol) = gx1;
-        *reinterpret_cast<f32x4*>(qb + srow * RS + scol) = gq0;
-        *reinterpret_cast<f32x4*>(qb + (srow + 64) * RS + scol) = gq1;
-        if (c == 0 && tid < TX) xns[(tile & 1) * TX + tid] = gxn;
+        *reinterpret_cast<f32x4*>(xb + srow * RS + scol) = mask_row4(g.x0, jr < j1, col, d, 1.f);
+        *reinterpret_cast<f32x4*>(xb + (srow + 64) * RS + scol) =
+            mask_row4(g.x1, jr + 64 < j1, col, d, 1.f);
+        *reinterpret_cast<f32x4*>(qb + srow * RS + scol) =
+            mask_row4(g.q0, wg_row0 + srow < rows, col, d, -2.f);
+        *reinterpret_cast<f32x4*>(qb + (srow + 64) * RS + scol) =
+            mask_row4(g.q1, wg_row0 + srow + 64 < rows, col, d, -2.f);
+        if (c == 0 && tid < TX) {
+            const int64_t jj = (int64_t)j0 + (int64_t)tile * TX + tid;
+            // rows past the range get +inf: they can never be accepted
+            xns[(tile & 1) * TX + tid] = jj < j1 ? g.xnv : kInf;
+        }
     };
 
     auto flush = [&](uint64_t mask) {  // bits 0..31: queries of this wave to merge
@@ -409,9 +452,10 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
 
     f32x16 acc[4];
 
+    Staged near;  // data of the next step
     if (total > 0) {
-        fetch(0);
-        stash(0);
+        fetch(0, near);
+        stash(0, near);
     }
     __syncthreads();
 
@@ -419,7 +463,7 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
         const int tile = step / nch;
         const int c = step - tile * nch;
         const int buf = step & 1;
-        if (step + 1 < total) fetch(step + 1);
+        if (step + 1 < total) fetch(step + 1, near);
 
         if (c == 0) {
             const float* xt = xns + (tile & 1) * TX;
@@ -494,7 +538,7 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
             }
         }
 
-        if (step + 1 < total) stash(step + 1);
+        if (step + 1 < total) stash(step + 1, near);
         __syncthreads();
     }
     const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0) & 0xffffffffull;
@@ -638,21 +682,39 @@ hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx,
                                 4 * (2 * kWave + 2 * k)) * 4;
     int64_t split_len = (n + S - 1) / S;
     split_len = (split_len + kMfmaTileX - 1) / kMfmaTileX * kMfmaTileX;
-    dim3 grid((unsigned)((rows + kMfmaTileQ - 1) / kMfmaTileQ), (unsigned)S);
+    // block shape for the XCD-aware mapping: BS = a divisor of S, BQ query tiles whose rows
+    // (BQ * 128 * d floats) stay within about half of one XCD's 4 MB L2, BQ * BS <= 64
+    // (the workgroups one XCD holds at a time)
+    const int T = (int)((rows + kMfmaTileQ - 1) / kMfmaTileQ);
+    int bq_cap = (int)(2 * 1024 * 1024 / ((int64_t)kMfmaTileQ * d * 4));
+    if (bq_cap < 1) bq_cap = 1;
+    if (bq_cap > 64) bq_cap = 64;
+    const int bs_cap = (64 / bq_cap) > 8 ? (64 / bq_cap) : 8;
+    int BS = 1;
+    for (int v = 1; v <= S && v <= bs_cap; ++v)
+        if (S % v == 0) BS = v;
+    int BQ = 64 / BS;
+    if (BQ > bq_cap) BQ = bq_cap;
+    if (BQ > T) BQ = T;
+    if (BQ < 1) BQ = 1;
+    const int nQB = (T + BQ - 1) / BQ;
+    const int blocks = nQB * (S / BS);
+    const unsigned grid_x = (unsigned)((blocks + 7) / 8 * 8 * BQ * BS);
+    dim3 grid(grid_x);
     const bool aligned = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldq % 4 == 0) &&
-                         (ldx % 4 == 0);
+                         (ldx % 4 == 0) && (d % 4 == 0);
     hipError_t e;
     if (aligned) {
         e = raise_lds_limit(knn_mfma_kernel<true>, lds);
         if (e != hipSuccess) return e;
         knn_mfma_kernel<true><<<grid, dim3(256), lds, stream>>>(
-            Q, ldq, X, ldx, xn, (int)rows, (int)n, d, k, S, (int)split_len, lk, li);
+            Q, ldq, X, ldx, xn, (int)rows, (int)n, d, k, S, (int)split_len, BQ, BS, lk, li);
     } else {
         e = raise_lds_limit(knn_mfma_kernel<false>, lds);
         if (e != hipSuccess) return e;
         knn_mfma_kernel<false><<<grid, dim3(256), lds, stream>>>(
-            Q, ldq, X, ldx, xn, (int)rows, (int)n, d, k, S, (int)split_len, lk, li);
+            Q, ldq, X, ldx, xn, (int)rows, (int)n, d, k, S, (int)split_len, BQ, BS, lk, li);
     }
     return hipGetLastError();
 }

@@ -103,26 +103,29 @@ extern "C" knn_status knn_plan(int64_t m, int64_t n, int32_t d, int32_t k,
     if (mem_limit_bytes < out->min_limit_bytes) return KNN_ERR_MEM_LIMIT_TOO_SMALL;
     const uint64_t avail = mem_limit_bytes - out->norms_bytes;
 
-    const int64_t tiles_total = (m + tile - 1) / tile;
+    // Number of point ranges S.  More ranges mean more workgroups (tiles x S), each walking
+    // n / S points, but also more list warm-up and merge work.  Estimated run time of a
+    // plan: chunks x rounds of resident workgroups x points per workgroup (+ a warm-up
+    // allowance); a larger S must beat a smaller one by 10 %.
     int64_t s_max = n / kMinSplitPoints;
     if (s_max < 1) s_max = 1;
     if (s_max > kMaxSplits) s_max = kMaxSplits;
-    int64_t s_want = (kTargetWorkgroups + tiles_total - 1) / tiles_total;
-    if (s_want < 1) s_want = 1;
-    if (s_want > s_max) s_want = s_max;
-
-    // smallest S whose launch reaches the target width; otherwise the widest launch
-    int64_t best_s = 0, best_rows = 0, best_wgs = -1;
-    for (int64_t S = 1; S <= s_want; ++S) {
+    const int64_t slots = lowd ? kLowdResidentWorkgroups : kMfmaResidentWorkgroups;
+    int64_t best_s = 0, best_rows = 0;
+    double best_cost = 0.0;
+    for (int64_t S = 1; S <= s_max; S = (S < 8 ? S + 1 : S + 8)) {
         int64_t rows = rows_fitting(avail, (uint64_t)S, (uint64_t)k);
         if (rows > kMaxChunkRows) rows = kMaxChunkRows;
         if (rows >= m) rows = m;
         else rows = rows / tile * tile;
         if (rows < 1) continue;
-        int64_t wgs = (rows + tile - 1) / tile * S;
-        int64_t score = wgs < kTargetWorkgroups ? wgs : kTargetWorkgroups;
-        if (score > best_wgs) {
-            best_wgs = score;
+        const int64_t chunks = (m + rows - 1) / rows;
+        const int64_t wgs = (rows + tile - 1) / tile * S;
+        const int64_t rounds = (wgs + slots - 1) / slots;
+        const double per_wg = (double)((n + S - 1) / S) + (double)kWarmupPointsPerK * (double)k;
+        const double cost = (double)chunks * (double)rounds * per_wg;
+        if (best_s == 0 || cost < 0.9 * best_cost) {
+            best_cost = cost;
             best_s = S;
             best_rows = rows;
         }
