@@ -47,6 +47,8 @@ typedef enum {
 /* kernel families (knn_plan_t.path) */
 #define KNN_PATH_LOWD 0 /* d <= 8: difference-form distances on the vector ALU  */
 #define KNN_PATH_MFMA 1 /* d  > 8: fp32 matrix-core tile of -2 Q X^T plus norms */
+#define KNN_PATH_LOWD_MFMA 2 /* d <= 3 and room for 16 n bytes of packed points:
+                                matrix-core filter + the same exact test as path 0 */
 
 /*
  * The plan: how the call is cut into pieces (section 4.3: split the largest
@@ -66,7 +68,8 @@ typedef struct {
     int64_t q_chunks;    /* ceil(m / chunk_rows); 0 when m == 0                 */
     int32_t streams;     /* HIP streams used (1: the caller's)                  */
     int32_t reserved;
-    uint64_t norms_bytes;     /* workspace: per-point squared norms (MFMA path) */
+    uint64_t norms_bytes;     /* workspace: per-point squared norms (path 1) or packed
+                                 points [x0 x1 x2 |x|^2] (path 2); 0 on path 0       */
     uint64_t lists_bytes;     /* workspace: partial k-lists of one chunk        */
     uint64_t workspace_bytes; /* total device workspace needed, <= mem_limit    */
     uint64_t min_limit_bytes; /* smallest limit any plan for this shape fits in */

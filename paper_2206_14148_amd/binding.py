@@ -21,6 +21,7 @@ KNN_ERR_HIP = 5
 KNN_MAX_K = 1024
 KNN_PATH_LOWD = 0
 KNN_PATH_MFMA = 1
+KNN_PATH_LOWD_MFMA = 2
 
 EXPORTED_SYMBOLS = (
     "knn_plan", "knn_workspace_bytes", "knn_search", "knn_last_stats", "knn_status_string",

@@ -24,6 +24,8 @@ def build(verbose: bool = False) -> str:
     cmd = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
            # packed fp32 VALU forms are kept out of the generated code on purpose
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # MFMA results go to ordinary VGPRs so the filter reads them without copies
+           "-mllvm", "-amdgpu-mfma-vgpr-form=1",
            "-Wno-unused-command-line-argument",
            "-o", LIB_PATH] + [os.path.join(CSRC, f) for f in SOURCES]
     if verbose:

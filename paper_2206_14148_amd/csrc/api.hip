@@ -153,6 +153,11 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
         e = launch_row_norms(X, ldx, n, d, xn, stream);
         if (e != hipSuccess) return hip_fail(e, "row norms launch");
         close_bracket(t0, stream, 0);
+    } else if (plan.path == KNN_PATH_LOWD_MFMA) {
+        hipEvent_t t0 = mark(stream);
+        e = launch_lowd_mfma(Q, ldq, X, ldx, ws, 0, n, d, k, S, true, lk, li, stream);
+        if (e != hipSuccess) return hip_fail(e, "point packing launch");
+        close_bracket(t0, stream, 0);
     }
     for (int64_t c = 0; c < plan.q_chunks; ++c) {
         const int64_t row0 = c * plan.chunk_rows;
@@ -162,6 +167,9 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
         if (plan.path == KNN_PATH_LOWD) {
             e = launch_lowd(Qc, ldq, X, ldx, rows, n, d, k, S, lk, li, stream);
             if (e != hipSuccess) return hip_fail(e, "low-d search launch");
+        } else if (plan.path == KNN_PATH_LOWD_MFMA) {
+            e = launch_lowd_mfma(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, lk, li, stream);
+            if (e != hipSuccess) return hip_fail(e, "low-d matrix-core search launch");
         } else {
             e = launch_mfma(Qc, ldq, X, ldx, xn, rows, n, d, k, S, lk, li, stream);
             if (e != hipSuccess) return hip_fail(e, "mfma search launch");

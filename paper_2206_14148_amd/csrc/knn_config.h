@@ -14,6 +14,12 @@ constexpr int kLowdTileQ = kLowdWaves * kWave;   // 256 query rows per workgroup
 constexpr int kLowdUnroll = 8;                   // points examined per filter test
 constexpr int kLowdCand = 16;                    // candidate slots per query (LDS)
 
+// d <= kPmMaxD (and workspace room for packed points): MFMA filter + exact test, 4 waves, each
+// wave owns 32 queries.
+constexpr int kPmMaxD = 3;
+constexpr int kPmTileQ = 128;
+constexpr int kPmCand = 16;                      // candidate slots per query (LDS)
+
 // d > kLowdMaxD: fp32 MFMA tile, 4 waves, each wave owns 32 queries x 128 points.
 constexpr int kMfmaTileQ = 128;
 constexpr int kMfmaTileX = 128;

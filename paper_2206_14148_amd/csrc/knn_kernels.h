@@ -18,6 +18,13 @@ hipError_t launch_row_norms(const float* X, int64_t ldx, int64_t n, int d, float
 hipError_t launch_lowd(const float* Q, int64_t ldq, const float* X, int64_t ldx, int64_t rows,
                        int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream);
 
+// d <= kPmMaxD with room for the packed points: the same keys as launch_lowd, found through an
+// MFMA filter.  `packed` = kAlign bytes (max ||x||^2 word) + 16 n bytes ([x0 x1 x2 ||x||^2] per
+// point); pack = true (re)builds it from X first; rows == 0 only packs.
+hipError_t launch_lowd_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx, void* packed,
+                            int64_t rows, int64_t n, int d, int k, int S, bool pack, float* lk,
+                            int* li, hipStream_t stream);
+
 // d > kLowdMaxD: key = xn[j] - 2 q.x from fp32 MFMA tiles (rank-equivalent to the distance).
 hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx, const float* xn,
                        int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,

@@ -79,7 +79,7 @@ struct MergeScratch {
 // Merge up to 64 candidates (one per lane; lanes without one pass (+inf, kNoIdx)) into the
 // ascending list gk/gi of k entries in global memory.  Returns the key at position k-1 of
 // the merged list, i.e. the new acceptance threshold.  All 64 lanes must call it together.
-__device__ float wave_merge(float* __restrict__ gk, int* __restrict__ gi, int k, float ckey,
+__device__ __noinline__ float wave_merge(float* __restrict__ gk, int* __restrict__ gi, int k, float ckey,
                             int cidx, const MergeScratch& sc, int lane) {
     // A list is read and written only by the wave that owns its query, so wave-level
     // ordering is enough; wave_sync() also orders this wave's earlier global stores to the
@@ -272,6 +272,214 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_lowd_kernel(
         if (full) flush(full);
     }
     const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0);
+    if (rest) flush(rest);
+}
+
+// ---------------------------------------------------------------------------------------
+// Low-dimensional path on the matrix cores (d <= 3).  The expansion of section 4.1 is used
+// only as a FILTER: with points packed as [x0 x1 x2 ||x||^2] and queries as
+// [-2q0 -2q1 -2q2 1], two v_mfma_f32_32x32x2_f32 give 32 x 32 keys ||x||^2 - 2 q.x.  A key
+// that could still belong to a pair closer than the query's threshold (allowing for the
+// rounding of the expansion) sends the pair to the exact test: the same fp32
+// difference-form distance as knn_lowd_kernel, compared against the same threshold.  The
+// accepted set, the keys and therefore the result are identical to the vector-ALU kernel.
+// ---------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void knn_pack_points_kernel(const float* __restrict__ X,
+                                                              int64_t ldx, int n,
+                                                              f32x4* __restrict__ Xp,
+                                                              unsigned* __restrict__ xn_max_bits) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    float nrm = 0.f;
+    if (j < n) {
+        float v[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < D; ++t) v[t] = X[(int64_t)j * ldx + t];
+        nrm = v[0] * v[0];
+        nrm = fmaf(v[1], v[1], nrm);
+        nrm = fmaf(v[2], v[2], nrm);
+        Xp[j] = f32x4{v[0], v[1], v[2], nrm};
+    }
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) nrm = fmaxf(nrm, __shfl_xor(nrm, s));
+    // non-negative floats order like their bit patterns
+    if ((threadIdx.x & 63) == 0) atomicMax(xn_max_bits, __float_as_uint(nrm));
+}
+
+__global__ void knn_zero_word_kernel(unsigned* __restrict__ w) { *w = 0u; }
+
+template <int D>
+__global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
+    const float* __restrict__ Q, int64_t ldq, const f32x4* __restrict__ Xp,
+    const unsigned* __restrict__ xn_max_bits, int rows, int n, int k, int S, int split_len,
+    float* __restrict__ lk, int* __restrict__ li) {
+    constexpr int C = kPmCand;
+    constexpr int UB = 4;        // 32-point blocks per loop iteration
+    constexpr int PTS = UB * 32; // points per loop iteration
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int i32 = lane & 31;  // query column (B side) / point row (A side) of the 32x32 block
+    const int h = lane >> 5;
+    const size_t per_wave = (size_t)(2 * 32 * C + 16 * kWave + 2 * kWave + 2 * k) * 4;
+    float* ck = reinterpret_cast<float*>(smem + (size_t)wave * per_wave);  // [32][C]
+    int* ci = reinterpret_cast<int*>(ck + 32 * C);                         // [32][C]
+    float* dump = reinterpret_cast<float*>(ci + 32 * C);                   // [16][64]
+    MergeScratch sc;
+    sc.cand_key = dump + 16 * kWave;
+    sc.cand_idx = reinterpret_cast<int*>(sc.cand_key + kWave);
+    sc.list_key = reinterpret_cast<float*>(sc.cand_idx + kWave);
+    sc.list_idx = reinterpret_cast<int*>(sc.list_key + k);
+
+    const int s = blockIdx.y;
+    const int wave_row0 = (blockIdx.x * 4 + wave) * 32;
+    if (wave_row0 >= rows) return;  // whole wave idle; no workgroup barrier is used below
+    const int r = wave_row0 + i32;
+    const bool active = r < rows;
+
+    for (int qq = 0; qq < 32; ++qq) {
+        if (wave_row0 + qq >= rows) break;
+        const size_t lb = ((size_t)(wave_row0 + qq) * S + s) * k;
+        for (int p = lane; p < k; p += kWave) {
+            lk[lb + p] = kInf;
+            li[lb + p] = kNoIdx;
+        }
+    }
+
+    float q[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < D; ++t) q[t] = active ? Q[(int64_t)r * ldq + t] : 0.f;
+    const float qn = fmaf(q[2], q[2], fmaf(q[1], q[1], q[0] * q[0]));
+    // B operand, K order (0, 1 | 2, 3) split over the two halves of the wave
+    const float b0 = h ? -2.f * q[2] : -2.f * q[0];
+    const float b1 = h ? 1.f : -2.f * q[1];
+    const float xmax = __uint_as_float(*xn_max_bits);
+
+    // A pair with exact fp32 distance < tau has key < (tau - qn) + slack: the key and qn each
+    // carry a few roundings relative to (||x||^2 + ||q||^2), the distance a few relative to
+    // itself; 2^-19 of their sum is several times the worst case.
+    float tau = active ? kInf : -kInf;
+    auto key_bound = [&](float t) { return (t - qn) + 0x1p-19f * (xmax + qn + t); };
+    float tauf = key_bound(tau);
+    int cnt = 0;  // candidates buffered for this lane's query (same in both halves)
+
+    auto flush = [&](uint64_t mask) {  // bits 0..31: queries of this wave to merge
+        while (mask) {
+            const int L = __builtin_ctzll(mask);
+            mask &= mask - 1;
+            wave_sync();
+            const int c = __shfl(cnt, L);
+            float key = kInf;
+            int id = kNoIdx;
+            if (lane < c) {
+                key = ck[L * C + lane];
+                id = ci[L * C + lane];
+            }
+            const size_t lb = ((size_t)(wave_row0 + L) * S + s) * k;
+            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane);
+            if (i32 == L) {
+                tau = t_new;
+                tauf = key_bound(t_new);
+                cnt = 0;
+            }
+        }
+    };
+
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2* xp2 = reinterpret_cast<const f32x2*>(Xp);  // point j = entries 2j (x0 x1), 2j+1 (x2 xn)
+    const int j0 = s * split_len;
+    const int j1 = min(n, j0 + split_len);
+
+    // Rare path of one 32-point block: the 16 keys of each lane go through LDS so that the
+    // walk over them is an ordinary loop (one copy of the code, nothing kept in registers
+    // across a list merge).
+    auto examine = [&](const f32x16& keys, int jblock) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) dump[e * kWave + lane] = keys[e];
+        wave_sync();
+        for (int e = 0; e < 16; ++e) {
+            bool c = dump[e * kWave + lane] < tauf;
+            if (__builtin_amdgcn_ballot_w64(c) == 0) continue;
+            const int idx = jblock + (e >> 2) * 8 + h * 4 + (e & 3);
+            float dd = kInf;
+            if (c) {  // exact test, same arithmetic as the vector-ALU kernel
+                const f32x4 xv = Xp[idx];
+                float df = q[0] - xv[0];
+                dd = df * df;
+                if (D > 1) {
+                    df = q[1] - xv[1];
+                    dd = fmaf(df, df, dd);
+                }
+                if (D > 2) {
+                    df = q[2] - xv[2];
+                    dd = fmaf(df, df, dd);
+                }
+                c = dd < tau;
+            }
+            int own = c ? 1 : 0;
+            int oth = __shfl_xor(own, 32);
+            if (__builtin_amdgcn_ballot_w64(c) == 0) continue;
+            const uint64_t need = __builtin_amdgcn_ballot_w64(cnt + own + oth > C) & 0xffffffffull;
+            if (need) {
+                flush(need);
+                c = c && dd < tau;
+                own = c ? 1 : 0;
+                oth = __shfl_xor(own, 32);
+            }
+            if (c) {
+                const int slot = i32 * C + cnt + (h ? oth : 0);
+                ck[slot] = dd;
+                ci[slot] = idx;
+            }
+            cnt += own + oth;
+        }
+    };
+
+    // one iteration: UB blocks of 32 points against this wave's 32 queries
+    auto process = [&](const f32x2 (&a)[UB], int jb) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            f32x16 z;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) z[e] = 0.f;
+            z = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][0], b0, z, 0, 0, 0);
+            z = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][1], b1, z, 0, 0, 0);
+            float m = z[0];
+#pragma unroll
+            for (int e = 1; e < 16; ++e) m = fminf(m, z[e]);
+            if (__builtin_amdgcn_ballot_w64(m < tauf) != 0) examine(z, jb + u * 32);
+        }
+    };
+
+    const int nfull = (j1 > j0) ? (j1 - j0) / PTS : 0;
+    int jb = j0;
+    f32x2 a[UB], an[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) a[u] = an[u] = f32x2{0.f, 0.f};
+    if (nfull > 0) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u) a[u] = xp2[(size_t)(jb + u * 32 + i32) * 2 + h];
+    }
+    for (int it = 0; it < nfull; ++it) {
+        if (it + 1 < nfull) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u) an[u] = xp2[(size_t)(jb + PTS + u * 32 + i32) * 2 + h];
+        }
+        process(a, jb);
+#pragma unroll
+        for (int u = 0; u < UB; ++u) a[u] = an[u];
+        jb += PTS;
+    }
+    if (jb < j1) {  // ragged tail: rows past the range read a valid row and get ||x||^2 = +inf
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const int row = jb + u * 32 + i32;
+            a[u] = xp2[(size_t)(row < j1 ? row : j1 - 1) * 2 + h];
+            if (row >= j1 && h) a[u][1] = kInf;
+        }
+        process(a, jb);
+    }
+    const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0) & 0xffffffffull;
     if (rest) flush(rest);
 }
 
@@ -670,6 +878,43 @@ hipError_t launch_lowd(const float* Q, int64_t ldq, const float* X, int64_t ldx,
         case 6: return launch_lowd_d<6>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
         case 7: return launch_lowd_d<7>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
         case 8: return launch_lowd_d<8>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <int D>
+static hipError_t launch_lowd_mfma_d(const float* Q, int64_t ldq, const float* X, int64_t ldx,
+                                     void* packed, int64_t rows, int64_t n, int k, int S,
+                                     bool pack, float* lk, int* li, hipStream_t stream) {
+    unsigned* xmax = static_cast<unsigned*>(packed);
+    f32x4* Xp = reinterpret_cast<f32x4*>(static_cast<unsigned char*>(packed) + kAlign);
+    if (pack) {
+        knn_zero_word_kernel<<<dim3(1), dim3(1), 0, stream>>>(xmax);
+        knn_pack_points_kernel<D><<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(
+            X, ldx, (int)n, Xp, xmax);
+        hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return e0;
+    }
+    if (rows == 0) return hipSuccess;
+    const size_t per_wave = (size_t)(2 * 32 * kPmCand + 16 * kWave + 2 * kWave + 2 * k) * 4;
+    const size_t lds = per_wave * 4;
+    hipError_t e = raise_lds_limit(knn_lowd_mfma_kernel<D>, lds);
+    if (e != hipSuccess) return e;
+    int64_t split_len = (n + S - 1) / S;
+    split_len = (split_len + 127) / 128 * 128;
+    dim3 grid((unsigned)((rows + kPmTileQ - 1) / kPmTileQ), (unsigned)S);
+    knn_lowd_mfma_kernel<D><<<grid, dim3(256), lds, stream>>>(
+        Q, ldq, Xp, xmax, (int)rows, (int)n, k, S, (int)split_len, lk, li);
+    return hipGetLastError();
+}
+
+hipError_t launch_lowd_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx, void* packed,
+                            int64_t rows, int64_t n, int d, int k, int S, bool pack, float* lk,
+                            int* li, hipStream_t stream) {
+    switch (d) {
+        case 1: return launch_lowd_mfma_d<1>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        case 2: return launch_lowd_mfma_d<2>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        case 3: return launch_lowd_mfma_d<3>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
         default: return hipErrorInvalidValue;
     }
 }

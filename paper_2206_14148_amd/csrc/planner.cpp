@@ -92,15 +92,32 @@ extern "C" knn_status knn_plan(int64_t m, int64_t n, int32_t d, int32_t k,
     out->k = k;
     out->streams = 1;
     const bool lowd = d <= kLowdMaxD;
+    // smallest plan of all: the vector-ALU path (no per-point workspace) or the MFMA path
     out->path = lowd ? KNN_PATH_LOWD : KNN_PATH_MFMA;
     out->tile_q = lowd ? kLowdTileQ : kMfmaTileQ;
     out->tile_x = lowd ? kLowdUnroll : kMfmaTileX;
     out->norms_bytes = lowd ? 0 : align_up((uint64_t)n * 4);
-    const int64_t tile = out->tile_q;
-    const int64_t min_rows = m < tile ? (m > 0 ? m : 1) : tile;
-    out->min_limit_bytes = out->norms_bytes + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k);
+    {
+        const int64_t t0 = out->tile_q;
+        const int64_t min_rows = m < t0 ? (m > 0 ? m : 1) : t0;
+        out->min_limit_bytes =
+            out->norms_bytes + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k);
+    }
     if (m == 0) return KNN_OK;
     if (mem_limit_bytes < out->min_limit_bytes) return KNN_ERR_MEM_LIMIT_TOO_SMALL;
+    if (d <= kPmMaxD) {
+        // the matrix-core filter needs the points packed into the workspace; take it when the
+        // limit has room for that and at least one query tile of lists
+        const uint64_t packed = kAlign + align_up((uint64_t)n * 16);
+        const int64_t min_rows = m < kPmTileQ ? m : kPmTileQ;
+        if (mem_limit_bytes >= packed + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k)) {
+            out->path = KNN_PATH_LOWD_MFMA;
+            out->tile_q = kPmTileQ;
+            out->tile_x = 32;
+            out->norms_bytes = packed;
+        }
+    }
+    const int64_t tile = out->tile_q;
     const uint64_t avail = mem_limit_bytes - out->norms_bytes;
 
     // Number of point ranges S.  More ranges mean more workgroups (tiles x S), each walking

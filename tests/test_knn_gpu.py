@@ -128,6 +128,25 @@ def test_exact_ties_on_integer_grid(K, oracle, d):
         assert np.array_equal(dist.astype(np.float64), o_dist), (d, k)
 
 
+@pytest.mark.parametrize("d", [1, 2, 3])
+def test_low_d_paths_agree_and_survive_data_far_from_the_origin(K, oracle, d):
+    # the matrix-core filter (roomy limit) and the vector kernel (tight limit) must give the
+    # same bits; an offset of 50 makes the expansion's rounding far larger than the
+    # neighbour distances, so the filter passes nearly everything to the exact test
+    Q, X = W.random_case(1000 + d, 700, 9000, d, kind="uniform")
+    for shift in (0.0, 50.0):
+        Qs, Xs = (Q + np.float32(shift)), (X + np.float32(shift))
+        k = 12
+        lo = K.knn_plan(700, 9000, d, k, 1 << 40).min_limit_bytes
+        assert K.knn_plan(700, 9000, d, k, lo + 40_000).path == K.KNN_PATH_LOWD
+        assert K.knn_plan(700, 9000, d, k, 64 * W.MB).path == K.KNN_PATH_LOWD_MFMA
+        a_idx, a_dist = run_gpu(K, Qs, Xs, k, lo + 40_000)
+        b_idx, b_dist = run_gpu(K, Qs, Xs, k, 64 * W.MB)
+        assert np.array_equal(a_idx, b_idx) and np.array_equal(a_dist, b_dist)
+        o_idx, o_dist, o_next = oracle.knn(Qs, Xs, k)
+        say("   shift", shift, check(b_idx, b_dist, o_idx, o_dist, o_next, 9000))
+
+
 def test_self_distance_zero_when_queries_are_the_points(K, oracle):
     w = W.scaled(2, n=30000)
     Q, X = W.make(w)
