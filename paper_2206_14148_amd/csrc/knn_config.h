@@ -18,7 +18,7 @@ constexpr int kLowdCand = 16;                    // candidate slots per query (L
 // wave owns 32 queries.
 constexpr int kPmMaxD = 3;
 constexpr int kPmTileQ = 128;
-constexpr int kPmCand = 16;                      // candidate slots per query (LDS)
+constexpr int kPmCand = 32;                      // candidate slots per query (LDS)
 
 // d > kLowdMaxD: fp32 MFMA tile, 4 waves, each wave owns 32 queries x 128 points.
 constexpr int kMfmaTileQ = 128;

@@ -321,12 +321,11 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
     const int wave = threadIdx.x >> 6;
     const int i32 = lane & 31;  // query column (B side) / point row (A side) of the 32x32 block
     const int h = lane >> 5;
-    const size_t per_wave = (size_t)(2 * 32 * C + 16 * kWave + 2 * kWave + 2 * k) * 4;
+    const size_t per_wave = (size_t)(2 * 32 * C + 2 * kWave + 2 * k) * 4;
     float* ck = reinterpret_cast<float*>(smem + (size_t)wave * per_wave);  // [32][C]
     int* ci = reinterpret_cast<int*>(ck + 32 * C);                         // [32][C]
-    float* dump = reinterpret_cast<float*>(ci + 32 * C);                   // [16][64]
     MergeScratch sc;
-    sc.cand_key = dump + 16 * kWave;
+    sc.cand_key = reinterpret_cast<float*>(ci + 32 * C);
     sc.cand_idx = reinterpret_cast<int*>(sc.cand_key + kWave);
     sc.list_key = reinterpret_cast<float*>(sc.cand_idx + kWave);
     sc.list_idx = reinterpret_cast<int*>(sc.list_key + k);
@@ -390,35 +389,38 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
     const int j0 = s * split_len;
     const int j1 = min(n, j0 + split_len);
 
-    // Rare path of one 32-point block: the 16 keys of each lane go through LDS so that the
-    // walk over them is an ordinary loop (one copy of the code, nothing kept in registers
-    // across a list merge).
-    auto examine = [&](const f32x16& keys, int jblock) {
+    // Rare path of one 32-point block.  Each lane collects the keys that pass the filter in
+    // a 16-bit mask and the lanes then work through their own bits in parallel (usually one
+    // round).  The coordinates of the point come from the A-operand registers of the lanes
+    // that loaded them, not from memory.
+    auto examine = [&](const f32x16& keys, const f32x2& apt, int jblock) {
+        unsigned bits = 0;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) dump[e * kWave + lane] = keys[e];
-        wave_sync();
-        for (int e = 0; e < 16; ++e) {
-            bool c = dump[e * kWave + lane] < tauf;
-            if (__builtin_amdgcn_ballot_w64(c) == 0) continue;
-            const int idx = jblock + (e >> 2) * 8 + h * 4 + (e & 3);
-            float dd = kInf;
-            if (c) {  // exact test, same arithmetic as the vector-ALU kernel
-                const f32x4 xv = Xp[idx];
-                float df = q[0] - xv[0];
-                dd = df * df;
-                if (D > 1) {
-                    df = q[1] - xv[1];
-                    dd = fmaf(df, df, dd);
-                }
-                if (D > 2) {
-                    df = q[2] - xv[2];
-                    dd = fmaf(df, df, dd);
-                }
-                c = dd < tau;
+        for (int e = 0; e < 16; ++e) bits |= (keys[e] < tauf) ? (1u << e) : 0u;
+        while (__builtin_amdgcn_ballot_w64(bits != 0) != 0) {
+            const bool has = bits != 0;
+            const int e = __builtin_ctz(bits | 0x10000u);
+            bits &= bits - 1;
+            const int row = ((e >> 2) * 8 + h * 4 + (e & 3)) & 31;  // point row inside the block
+            float xv[3];
+            xv[0] = __shfl(apt[0], row);
+            xv[1] = __shfl(apt[1], row);
+            xv[2] = __shfl(apt[0], row + 32);
+            // exact test, same arithmetic as the vector-ALU kernel
+            float df = q[0] - xv[0];
+            float dd = df * df;
+            if (D > 1) {
+                df = q[1] - xv[1];
+                dd = fmaf(df, df, dd);
             }
+            if (D > 2) {
+                df = q[2] - xv[2];
+                dd = fmaf(df, df, dd);
+            }
+            bool c = has && dd < tau;
+            if (__builtin_amdgcn_ballot_w64(c) == 0) continue;
             int own = c ? 1 : 0;
             int oth = __shfl_xor(own, 32);
-            if (__builtin_amdgcn_ballot_w64(c) == 0) continue;
             const uint64_t need = __builtin_amdgcn_ballot_w64(cnt + own + oth > C) & 0xffffffffull;
             if (need) {
                 flush(need);
@@ -429,7 +431,7 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
             if (c) {
                 const int slot = i32 * C + cnt + (h ? oth : 0);
                 ck[slot] = dd;
-                ci[slot] = idx;
+                ci[slot] = jblock + row;
             }
             cnt += own + oth;
         }
@@ -447,7 +449,7 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
             float m = z[0];
 #pragma unroll
             for (int e = 1; e < 16; ++e) m = fminf(m, z[e]);
-            if (__builtin_amdgcn_ballot_w64(m < tauf) != 0) examine(z, jb + u * 32);
+            if (__builtin_amdgcn_ballot_w64(m < tauf) != 0) examine(z, a[u], jb + u * 32);
         }
     };
 
@@ -896,7 +898,7 @@ static hipError_t launch_lowd_mfma_d(const float* Q, int64_t ldq, const float* X
         if (e0 != hipSuccess) return e0;
     }
     if (rows == 0) return hipSuccess;
-    const size_t per_wave = (size_t)(2 * 32 * kPmCand + 16 * kWave + 2 * kWave + 2 * k) * 4;
+    const size_t per_wave = (size_t)(2 * 32 * kPmCand + 2 * kWave + 2 * k) * 4;
     const size_t lds = per_wave * 4;
     hipError_t e = raise_lds_limit(knn_lowd_mfma_kernel<D>, lds);
     if (e != hipSuccess) return e;
