@@ -80,7 +80,8 @@ def main() -> int:
     ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
     idx = torch.empty((w.m, w.k), dtype=torch.int32, device=dev)
     dist = torch.empty((w.m, w.k), dtype=torch.float32, device=dev)
-    log(f"[bench] plan: path={'lowd' if plan.path == 0 else 'mfma'} chunks={plan.q_chunks} "
+    path_name = {0: "lowd", 1: "mfma", 2: "lowd_mfma"}[plan.path]
+    log(f"[bench] plan: path={path_name} chunks={plan.q_chunks} "
         f"ranges={plan.n_splits} workspace={plan.workspace_bytes} B (limit {limit} B)")
 
     def step():
@@ -117,6 +118,7 @@ def main() -> int:
     avg_launch_s = (search_ms / max(launches, 1)) * 1e-3
     pairs_per_launch = pairs * args.steps / max(launches, 1)
     traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
+    hbm_equiv = (pairs_per_launch / avg_launch_s) * 8.0 / (PEAK_HBM_GBS * 1e9)
     if plan.path == K.KNN_PATH_MFMA:
         flops = 2.0 * w.d * pairs_per_launch  # the -2 Q X^T contraction
         achieved = flops / avg_launch_s / 1e12
@@ -124,6 +126,16 @@ def main() -> int:
                     "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_FP32_MATRIX_TFLOPS, "traffic": traffic,
                     "flops_per_pair": 2 * w.d}
+    elif plan.path == K.KNN_PATH_LOWD_MFMA:
+        # filter contraction over K = 4: [x0 x1 x2 |x|^2] . [-2q0 -2q1 -2q2 1]
+        flops = 2.0 * 4 * pairs_per_launch
+        achieved = flops / avg_launch_s / 1e12
+        roofline = {"bound": "mfma", "kernel": "knn_lowd_mfma_kernel", "achieved": achieved,
+                    "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_FP32_MATRIX_TFLOPS, "traffic": traffic,
+                    "flops_per_pair": 8,
+                    # what a design that stores the distance tile would move: 4 B out + 4 B in
+                    "hbm_equiv_frac": hbm_equiv}
     else:
         # difference form: d subtractions, d multiplications, d-1 additions per pair
         flops = (3.0 * w.d - 1.0) * pairs_per_launch
@@ -131,9 +143,7 @@ def main() -> int:
         roofline = {"bound": "alu", "kernel": "knn_lowd_kernel", "achieved": achieved,
                     "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_FP32_VECTOR_TFLOPS, "traffic": traffic,
-                    "flops_per_pair": 3 * w.d - 1,
-                    # what a design that stores the distance tile would move: 4 B out + 4 B in
-                    "hbm_equiv_frac": (pairs_per_launch / avg_launch_s) * 8.0 / (PEAK_HBM_GBS * 1e9)}
+                    "flops_per_pair": 3 * w.d - 1, "hbm_equiv_frac": hbm_equiv}
     roofline["avg_launch_ms"] = avg_launch_s * 1e3
 
     cpu_baseline = None
@@ -167,7 +177,7 @@ def main() -> int:
         "config": {"workload": w.name, "m": w.m, "n": w.n, "d": w.d, "k": w.k,
                    "mem_limit_bytes": limit, "workspace_bytes": plan.workspace_bytes,
                    "q_chunks": plan.q_chunks, "point_ranges": plan.n_splits,
-                   "path": "lowd" if plan.path == 0 else "mfma"},
+                   "path": path_name},
         "kernel_ms_per_step": {"norms": norms_ms / args.steps, "search": search_ms / args.steps,
                                "merge_refine": refine_ms / args.steps},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity,

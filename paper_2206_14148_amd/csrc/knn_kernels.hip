@@ -394,9 +394,9 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
     // round).  The coordinates of the point come from the A-operand registers of the lanes
     // that loaded them, not from memory.
     auto examine = [&](const f32x16& keys, const f32x2& apt, int jblock) {
-        unsigned bits = 0;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) bits |= (keys[e] < tauf) ? (1u << e) : 0u;
+        unsigned bits = 0;  // bit e <=> key e passes; shift-in from the top keeps it to
+#pragma unroll          // a compare and an add-with-carry per key
+        for (int e = 15; e >= 0; --e) bits = bits + bits + ((keys[e] < tauf) ? 1u : 0u);
         while (__builtin_amdgcn_ballot_w64(bits != 0) != 0) {
             const bool has = bits != 0;
             const int e = __builtin_ctz(bits | 0x10000u);
@@ -446,9 +446,9 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
             for (int e = 0; e < 16; ++e) z[e] = 0.f;
             z = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][0], b0, z, 0, 0, 0);
             z = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][1], b1, z, 0, 0, 0);
-            float m = z[0];
+            float m = kInf;  // 8 three-input mins over (inf, 16 keys)
 #pragma unroll
-            for (int e = 1; e < 16; ++e) m = fminf(m, z[e]);
+            for (int e = 0; e < 16; ++e) m = fminf(m, z[e]);
             if (__builtin_amdgcn_ballot_w64(m < tauf) != 0) examine(z, a[u], jb + u * 32);
         }
     };
