@@ -29,6 +29,10 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per search-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/*_pmc.txt), scaled by the copy-kernel calibration stated there.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
+    "c2_pointcloud_d3": 8.08e9,    # knn_lowd_mfma_kernel: 6.25 GB fetched + 1.84 GB written
+    "c3_imagelike_d784": 357.2e9,  # knn_mfma_kernel: 357.1 GB fetched + 0.07 GB written
+    "c4_clustered_d128": 4445.4e9,  # knn_mfma_kernel: 4430.9 GB fetched + 14.5 GB written
+    "c5_memsweep_d256": 916.0e9,   # knn_mfma_kernel: 914.9 GB fetched + 1.15 GB written
 }
 
 
