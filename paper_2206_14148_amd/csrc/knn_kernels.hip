@@ -598,11 +598,17 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
     const int srow = tid >> 2;
     const int scol = (tid & 3) * 4;
 
-    // Global -> register -> LDS staging runs one pipeline step ahead of the MFMA loop.
+    // Global -> register -> LDS staging.  Two register sets alternate: the loads of step s+2
+    // are issued at the start of step s and written to LDS at the end of step s+1, so a load
+    // has about two steps to come back from beyond the L2 (the step loop is unrolled by two
+    // so that the sets are named statically and never copied).
     struct Staged {
         f32x4 x0, x1, q0, q1;
         float xnv;
     };
+    // fetch() is branch-free on purpose: every call issues the same five loads, so the
+    // compiler can count how many newer loads may still be in flight when an older set is
+    // written to LDS (a conditional load would force it to wait for everything).
     auto fetch = [&](int step, Staged& g) {
         const int tile = step / nch;
         const int c = step - tile * nch;
@@ -612,10 +618,8 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
         g.x1 = load_row4<ALIGNED>(X, ldx, jr + 64, j1, col, d);
         g.q0 = load_row4<ALIGNED>(Q, ldq, (int64_t)wg_row0 + srow, rows, col, d);
         g.q1 = load_row4<ALIGNED>(Q, ldq, (int64_t)wg_row0 + srow + 64, rows, col, d);
-        if (c == 0 && tid < TX) {
-            const int64_t jj = (int64_t)j0 + (int64_t)tile * TX + tid;
-            g.xnv = xn[jj < j1 ? jj : j1 - 1];
-        }
+        const int64_t jj = (int64_t)j0 + (int64_t)tile * TX + (tid & (TX - 1));
+        g.xnv = xn[jj < j1 ? jj : j1 - 1];
     };
     auto stash = [&](int step, const Staged& g) {
         const int tile = step / nch;
@@ -662,18 +666,20 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
 
     f32x16 acc[4];
 
-    Staged near;  // data of the next step
+    Staged set_even, set_odd;  // staged data of even / odd steps
     if (total > 0) {
-        fetch(0, near);
-        stash(0, near);
+        fetch(0, set_even);
+        stash(0, set_even);
     }
+    if (total > 1) fetch(1, set_odd);
     __syncthreads();
 
-    for (int step = 0; step < total; ++step) {
+    // one pipeline step; `mine` holds step+2 afterwards, `next` holds step+1 on entry
+    auto run_step = [&](int step, Staged& mine, const Staged& next) {
         const int tile = step / nch;
         const int c = step - tile * nch;
         const int buf = step & 1;
-        if (step + 1 < total) fetch(step + 1, near);
+        fetch(step + 2 < total ? step + 2 : total - 1, mine);  // past the end: a harmless re-load
 
         if (c == 0) {
             const float* xt = xns + (tile & 1) * TX;
@@ -690,22 +696,29 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
             }
         }
         {
+            // Both K groups of the step are read up front; the write of the next step's
+            // data to the other LDS buffer sits between the two MFMA groups so that its
+            // LDS traffic and waits overlap with matrix work of this wave.
             const float* xb = xs + buf * TX * RS;
             const float* qb = qs + buf * TQ * RS;
+            f32x4 b[KC / 8], a[KC / 8][4];
 #pragma unroll
             for (int g = 0; g < KC / 8; ++g) {
                 const int col = g * 8 + h * 4;
-                const f32x4 b = *reinterpret_cast<const f32x4*>(qb + my_q * RS + col);
-                f32x4 a[4];
+                b[g] = *reinterpret_cast<const f32x4*>(qb + my_q * RS + col);
 #pragma unroll
                 for (int pb = 0; pb < 4; ++pb)
-                    a[pb] = *reinterpret_cast<const f32x4*>(xb + (pb * 32 + i32) * RS + col);
+                    a[g][pb] = *reinterpret_cast<const f32x4*>(xb + (pb * 32 + i32) * RS + col);
+            }
+#pragma unroll
+            for (int g = 0; g < KC / 8; ++g) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
 #pragma unroll
                     for (int pb = 0; pb < 4; ++pb)
-                        acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[pb][e], b[e], acc[pb], 0, 0, 0);
+                        acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][pb][e], b[g][e], acc[pb], 0, 0, 0);
                 }
+                if (g == 0 && step + 1 < total) stash(step + 1, next);
             }
         }
 
@@ -748,8 +761,11 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
             }
         }
 
-        if (step + 1 < total) stash(step + 1, near);
         __syncthreads();
+    };
+    for (int step = 0; step < total; step += 2) {
+        run_step(step, set_even, set_odd);
+        if (step + 1 < total) run_step(step + 1, set_odd, set_even);
     }
     const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0) & 0xffffffffull;
     if (rest) flush(rest);
