@@ -26,6 +26,8 @@ def build(verbose: bool = False) -> str:
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            # MFMA results go to ordinary VGPRs so the filter reads them without copies
            "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+           # the chunk loop of the register-resident-query kernel must unroll completely
+           "-mllvm", "-pragma-unroll-threshold=100000",
            "-Wno-unused-command-line-argument",
            "-o", LIB_PATH] + [os.path.join(CSRC, f) for f in SOURCES]
     if verbose:

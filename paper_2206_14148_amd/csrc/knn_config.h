@@ -25,6 +25,7 @@ constexpr int kMfmaTileQ = 128;
 constexpr int kMfmaTileX = 128;
 constexpr int kMfmaKC = 16;          // K columns staged in LDS per pipeline step
 constexpr int kMfmaRowStride = 20;   // floats per staged row (16 + 4 pad, keeps 16 B alignment)
+constexpr int kMfmaQregMaxChunks = 16;  // d <= 256: queries stay in registers
 constexpr int kMfmaCand = 32;        // candidate slots per query (LDS)
 
 // Workgroups the chip holds at once (LDS-limited): the planner sizes launches in rounds of these.

@@ -132,6 +132,127 @@ __device__ __noinline__ float wave_merge(float* __restrict__ gk, int* __restrict
     return tau;
 }
 
+// Bookkeeping of the 32 queries one wave owns in the matrix-core kernels: lane % 32 names the
+// query, the two halves of the wave (lane / 32) hold different points of the same query.
+struct WaveLists {
+    float* lk;        // list keys of the chunk, [rows][S][k]
+    int* li;          // list indices
+    int k, S, s;      // list length, ranges, this workgroup's range
+    int row0;         // first query row (inside the chunk) of this wave
+    float* ck;        // candidate keys of this wave, [32][C]
+    int* ci;          // candidate indices
+    MergeScratch sc;
+    int lane;
+};
+
+// Merge the buffered candidates of the queries named by bits 0..31 of `mask` into their lists;
+// lanes of a merged query get the new threshold and an empty buffer.
+template <int C>
+__device__ __forceinline__ void flush_lists(const WaveLists& w, uint64_t mask, float& tau,
+                                            int& cnt) {
+    while (mask) {
+        const int L = __builtin_ctzll(mask);
+        mask &= mask - 1;
+        wave_sync();
+        const int c = __shfl(cnt, L);
+        float key = kInf;
+        int id = kNoIdx;
+        if (w.lane < c) {
+            key = w.ck[L * C + w.lane];
+            id = w.ci[L * C + w.lane];
+        }
+        const size_t lb = ((size_t)(w.row0 + L) * w.S + w.s) * w.k;
+        const float t_new = wave_merge(w.lk + lb, w.li + lb, w.k, key, id, w.sc, w.lane);
+        if ((w.lane & 31) == L) {
+            tau = t_new;
+            cnt = 0;
+        }
+    }
+}
+
+// End of a 128-point tile: acc[pb][e] is the key of query lane % 32 against point
+// tile_base + pb*32 + (e/4)*8 + (lane/32)*4 + e%4.  Keys below the query's threshold are
+// buffered (the two halves of the wave take consecutive slots), full buffers are merged first.
+template <int C>
+__device__ __forceinline__ void tile_epilogue(const f32x16 (&acc)[4], const WaveLists& w,
+                                              int tile_base, float& tau, int& cnt) {
+    float mn = kInf;
+#pragma unroll
+    for (int pb = 0; pb < 4; ++pb) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mn = fminf(mn, acc[pb][e]);
+    }
+    if (__builtin_amdgcn_ballot_w64(mn < tau) == 0) return;
+    const int i32 = w.lane & 31;
+    const int h = w.lane >> 5;
+#pragma unroll
+    for (int pb = 0; pb < 4; ++pb) {
+        int own = 0;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) own += (acc[pb][e] < tau) ? 1 : 0;
+        int oth = __shfl_xor(own, 32);
+        const uint64_t need = __builtin_amdgcn_ballot_w64(cnt + own + oth > C) & 0xffffffffull;
+        if (need) {
+            flush_lists<C>(w, need, tau, cnt);
+            own = 0;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) own += (acc[pb][e] < tau) ? 1 : 0;
+            oth = __shfl_xor(own, 32);
+        }
+        int slot = i32 * C + cnt + (h ? oth : 0);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            if (acc[pb][e] < tau) {
+                w.ck[slot] = acc[pb][e];
+                w.ci[slot] = tile_base + pb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+                ++slot;
+            }
+        }
+        cnt += own + oth;
+    }
+}
+
+// Workgroup -> (query tile, point range).  Consecutive workgroup ids go round-robin to the 8
+// XCDs, each with its own L2.  The (tile, range) grid is cut into blocks of BQ tiles x BS
+// ranges; a block is handed to one XCD as BQ*BS consecutive workgroups of that XCD, so the
+// workgroups resident there together re-use BQ query tiles and BS point streams out of its L2
+// instead of fetching BQ*BS private ones.  Returns false for a padding workgroup.
+__device__ __forceinline__ bool xcd_block_map(int rows, int tile_q, int S, int BQ, int BS, int& s,
+                                              int& wg_row0) {
+    const int T = (rows + tile_q - 1) / tile_q;
+    const int nQB = (T + BQ - 1) / BQ;
+    const int nSB = S / BS;  // BS divides S
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const int per_block = BQ * BS;
+    const int bseq = slot / per_block;
+    const int within = slot - bseq * per_block;
+    const int b = bseq * 8 + xcd;
+    if (b >= nQB * nSB) return false;
+    const int sb = b / nQB;
+    const int qb = b - sb * nQB;
+    const int si = within / BQ;
+    const int qi = within - si * BQ;
+    const int qtile = qb * BQ + qi;
+    if (qtile >= T) return false;
+    s = sb * BS + si;
+    wg_row0 = qtile * tile_q;
+    return true;
+}
+
+// Lists of the 32 queries starting at chunk row `row0` begin as k sentinels.
+__device__ __forceinline__ void init_lists32(float* __restrict__ lk, int* __restrict__ li, int row0,
+                                             int rows, int S, int s, int k, int lane) {
+    for (int qq = 0; qq < 32; ++qq) {
+        if (row0 + qq >= rows) break;
+        const size_t lb = ((size_t)(row0 + qq) * S + s) * k;
+        for (int p = lane; p < k; p += kWave) {
+            lk[lb + p] = kInf;
+            li[lb + p] = kNoIdx;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // Row norms (section 4.1, the sum x^2 term): one wave per row, fixed summation order.
 // ---------------------------------------------------------------------------------------
@@ -544,46 +665,24 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
     const int i32 = lane & 31;  // query column / point row inside a 32x32 block
     const int h = lane >> 5;    // which half of the wave
 
-    // Workgroup -> (query tile, point range).  Consecutive workgroup ids go round-robin to
-    // the 8 XCDs, each with its own L2.  The (tile, range) grid is cut into blocks of
-    // BQ tiles x BS ranges; a block is handed to one XCD as BQ*BS consecutive workgroups of
-    // that XCD, so the workgroups resident there together re-use BQ query tiles and BS point
-    // streams out of its L2 instead of fetching BQ*BS private ones.
     int s, wg_row0;
-    {
-        const int T = (rows + TQ - 1) / TQ;
-        const int nQB = (T + BQ - 1) / BQ;
-        const int nSB = S / BS;  // BS divides S
-        const int xcd = blockIdx.x & 7;
-        const int slot = blockIdx.x >> 3;
-        const int per_block = BQ * BS;
-        const int bseq = slot / per_block;
-        const int within = slot - bseq * per_block;
-        const int b = bseq * 8 + xcd;
-        if (b >= nQB * nSB) return;  // padding workgroup (before any barrier)
-        const int sb = b / nQB;
-        const int qb = b - sb * nQB;
-        const int si = within / BQ;
-        const int qi = within - si * BQ;
-        const int qtile = qb * BQ + qi;
-        if (qtile >= T) return;
-        s = sb * BS + si;
-        wg_row0 = qtile * TQ;
-    }
+    if (!xcd_block_map(rows, TQ, S, BQ, BS, s, wg_row0)) return;  // padding (before any barrier)
     const int my_q = wave * 32 + i32;  // query inside the workgroup tile
     const int r = wg_row0 + my_q;
     const bool active = r < rows;
 
-    // lists of this wave's 32 queries start as k sentinels
-    for (int qq = 0; qq < 32; ++qq) {
-        const int rr = wg_row0 + wave * 32 + qq;
-        if (rr >= rows) break;
-        const size_t lb = ((size_t)rr * S + s) * k;
-        for (int p = lane; p < k; p += kWave) {
-            lk[lb + p] = kInf;
-            li[lb + p] = kNoIdx;
-        }
-    }
+    init_lists32(lk, li, wg_row0 + wave * 32, rows, S, s, k, lane);
+    WaveLists wl;
+    wl.lk = lk;
+    wl.li = li;
+    wl.k = k;
+    wl.S = S;
+    wl.s = s;
+    wl.row0 = wg_row0 + wave * 32;
+    wl.ck = ck + wave * 32 * C;
+    wl.ci = ci + wave * 32 * C;
+    wl.sc = sc;
+    wl.lane = lane;
 
     float tau = active ? kInf : -kInf;
     int cnt = 0;  // candidates buffered for this lane's query (same value in both halves)
@@ -640,27 +739,6 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
             const int64_t jj = (int64_t)j0 + (int64_t)tile * TX + tid;
             // rows past the range get +inf: they can never be accepted
             xns[(tile & 1) * TX + tid] = jj < j1 ? g.xnv : kInf;
-        }
-    };
-
-    auto flush = [&](uint64_t mask) {  // bits 0..31: queries of this wave to merge
-        while (mask) {
-            const int L = __builtin_ctzll(mask);
-            mask &= mask - 1;
-            wave_sync();
-            const int c = __shfl(cnt, L);
-            float key = kInf;
-            int id = kNoIdx;
-            if (lane < c) {
-                key = ck[(wave * 32 + L) * C + lane];
-                id = ci[(wave * 32 + L) * C + lane];
-            }
-            const size_t lb = ((size_t)(wg_row0 + wave * 32 + L) * S + s) * k;
-            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane);
-            if (i32 == L) {
-                tau = t_new;
-                cnt = 0;
-            }
         }
     };
 
@@ -722,44 +800,7 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
             }
         }
 
-        if (c == nch - 1) {
-            // filter: does any of this lane's 64 keys beat its query's threshold?
-            float mn = acc[0][0];
-#pragma unroll
-            for (int pb = 0; pb < 4; ++pb) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) mn = fminf(mn, acc[pb][e]);
-            }
-            if (__builtin_amdgcn_ballot_w64(mn < tau) != 0) {
-                const int tile_base = j0 + tile * TX;
-#pragma unroll
-                for (int pb = 0; pb < 4; ++pb) {
-                    int own = 0;
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) own += (acc[pb][e] < tau) ? 1 : 0;
-                    int oth = __shfl_xor(own, 32);
-                    const uint64_t need =
-                        __builtin_amdgcn_ballot_w64(cnt + own + oth > C) & 0xffffffffull;
-                    if (need) {
-                        flush(need);
-                        own = 0;
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) own += (acc[pb][e] < tau) ? 1 : 0;
-                        oth = __shfl_xor(own, 32);
-                    }
-                    int slot = my_q * C + cnt + (h ? oth : 0);
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        if (acc[pb][e] < tau) {
-                            ck[slot] = acc[pb][e];
-                            ci[slot] = tile_base + pb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-                            ++slot;
-                        }
-                    }
-                    cnt += own + oth;
-                }
-            }
-        }
+        if (c == nch - 1) tile_epilogue<C>(acc, wl, j0 + tile * TX, tau, cnt);
 
         __syncthreads();
     };
@@ -768,7 +809,163 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
         if (step + 1 < total) run_step(step + 1, set_odd, set_even);
     }
     const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0) & 0xffffffffull;
-    if (rest) flush(rest);
+    if (rest) flush_lists<C>(wl, rest, tau, cnt);
+}
+
+// ---------------------------------------------------------------------------------------
+// Matrix-core path for d <= 16 * NCH <= 256: as knn_mfma_kernel, but the queries never go
+// through LDS or the L2 again.  A lane keeps the K values of its query that its half of the
+// wave feeds to the MFMAs (d/2 registers, scaled by -2) for the whole kernel, so only the
+// point stream is staged: half the global requests, half the LDS writes, and the L2 of an XCD
+// holds nothing but the point windows its workgroups share.  The chunk loop of a tile is
+// unrolled (NCH is even), which also names the two prefetch register sets statically.
+// ---------------------------------------------------------------------------------------
+template <int NCH, bool ALIGNED>
+__global__ __launch_bounds__(256, 2) void knn_mfma_qreg_kernel(
+    const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
+    const float* __restrict__ xn, int rows, int n, int d, int k, int S, int split_len,
+    int BQ, int BS, float* __restrict__ lk, int* __restrict__ li) {
+    static_assert(NCH % 2 == 0, "the chunk loop alternates two LDS buffers and register sets");
+    constexpr int TQ = kMfmaTileQ, TX = kMfmaTileX, KC = kMfmaKC, RS = kMfmaRowStride;
+    constexpr int C = kMfmaCand;
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* xs = reinterpret_cast<float*>(smem);     // [2][TX][RS]
+    float* xns = xs + 2 * TX * RS;                  // [2][TX]
+    float* ck = xns + 2 * TX;                       // [TQ][C]
+    int* ci = reinterpret_cast<int*>(ck + TQ * C);  // [TQ][C]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int i32 = lane & 31;
+    const int h = lane >> 5;
+
+    int s, wg_row0;
+    if (!xcd_block_map(rows, TQ, S, BQ, BS, s, wg_row0)) return;  // padding (before any barrier)
+    const int r = wg_row0 + wave * 32 + i32;
+    const bool active = r < rows;
+
+    WaveLists wl;
+    wl.lk = lk;
+    wl.li = li;
+    wl.k = k;
+    wl.S = S;
+    wl.s = s;
+    wl.row0 = wg_row0 + wave * 32;
+    wl.ck = ck + wave * 32 * C;
+    wl.ci = ci + wave * 32 * C;
+    {
+        float* pw = reinterpret_cast<float*>(ci + TQ * C) + (size_t)wave * (2 * kWave + 2 * k);
+        wl.sc.cand_key = pw;
+        wl.sc.cand_idx = reinterpret_cast<int*>(pw + kWave);
+        wl.sc.list_key = pw + 2 * kWave;
+        wl.sc.list_idx = reinterpret_cast<int*>(pw + 2 * kWave + k);
+    }
+    wl.lane = lane;
+    init_lists32(lk, li, wl.row0, rows, S, s, k, lane);
+
+    // B operand of every MFMA of a tile: K columns 8g + 4h .. 8g + 4h + 3 of this lane's query
+    f32x4 qreg[2 * NCH];
+#pragma unroll
+    for (int g = 0; g < 2 * NCH; ++g) {
+        const int col = g * 8 + h * 4;
+        qreg[g] = mask_row4(load_row4<ALIGNED>(Q, ldq, r, rows, col, d), active, col, d, -2.f);
+    }
+
+    float tau = active ? kInf : -kInf;
+    int cnt = 0;
+
+    const int j0 = s * split_len;
+    const int j1 = min(n, j0 + split_len);
+    const int ntiles = (j1 > j0) ? (j1 - j0 + TX - 1) / TX : 0;
+    const int total = ntiles * NCH;
+
+    const int srow = tid >> 2;
+    const int scol = (tid & 3) * 4;
+    struct Staged {
+        f32x4 x0, x1;
+        float xnv;
+    };
+    // branch-free: the same three loads on every call (see knn_mfma_kernel)
+    auto fetch = [&](int step, Staged& g) {
+        const int tile = step / NCH;
+        const int c = step - tile * NCH;
+        const int col = c * KC + scol;
+        const int64_t jr = (int64_t)j0 + (int64_t)tile * TX + srow;
+        g.x0 = load_row4<ALIGNED>(X, ldx, jr, j1, col, d);
+        g.x1 = load_row4<ALIGNED>(X, ldx, jr + 64, j1, col, d);
+        const int64_t jj = (int64_t)j0 + (int64_t)tile * TX + (tid & (TX - 1));
+        g.xnv = xn[jj < j1 ? jj : j1 - 1];
+    };
+    auto stash = [&](int step, const Staged& g) {
+        const int tile = step / NCH;
+        const int c = step - tile * NCH;
+        const int col = c * KC + scol;
+        const int64_t jr = (int64_t)j0 + (int64_t)tile * TX + srow;
+        float* xb = xs + (step & 1) * TX * RS;
+        *reinterpret_cast<f32x4*>(xb + srow * RS + scol) = mask_row4(g.x0, jr < j1, col, d, 1.f);
+        *reinterpret_cast<f32x4*>(xb + (srow + 64) * RS + scol) =
+            mask_row4(g.x1, jr + 64 < j1, col, d, 1.f);
+        if (c == 0 && tid < TX) {
+            const int64_t jj = (int64_t)j0 + (int64_t)tile * TX + tid;
+            xns[(tile & 1) * TX + tid] = jj < j1 ? g.xnv : kInf;  // +inf: never accepted
+        }
+    };
+
+    Staged set_even, set_odd;
+    if (total > 0) {
+        fetch(0, set_even);
+        stash(0, set_even);
+        fetch(total > 1 ? 1 : 0, set_odd);
+    }
+    __syncthreads();
+
+    f32x16 acc[4];
+    for (int tile = 0; tile < ntiles; ++tile) {
+        {
+            const float* xt = xns + (tile & 1) * TX;
+#pragma unroll
+            for (int pb = 0; pb < 4; ++pb) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(xt + pb * 32 + g * 8 + h * 4);
+                    acc[pb][g * 4 + 0] = v[0];
+                    acc[pb][g * 4 + 1] = v[1];
+                    acc[pb][g * 4 + 2] = v[2];
+                    acc[pb][g * 4 + 3] = v[3];
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int step = tile * NCH + c;
+            Staged& mine = (c & 1) ? set_odd : set_even;        // receives step + 2
+            const Staged& next = (c & 1) ? set_even : set_odd;  // holds step + 1
+            fetch(step + 2 < total ? step + 2 : total - 1, mine);
+            const float* xb = xs + (c & 1) * TX * RS;
+            f32x4 a[2][4];
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+#pragma unroll
+                for (int pb = 0; pb < 4; ++pb)
+                    a[g][pb] = *reinterpret_cast<const f32x4*>(xb + (pb * 32 + i32) * RS + g * 8 + h * 4);
+            }
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                    for (int pb = 0; pb < 4; ++pb)
+                        acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][pb][e], qreg[2 * c + g][e],
+                                                                       acc[pb], 0, 0, 0);
+                }
+                if (g == 0 && step + 1 < total) stash(step + 1, next);
+            }
+            if (c == NCH - 1) tile_epilogue<C>(acc, wl, j0 + tile * TX, tau, cnt);
+            __syncthreads();
+        }
+    }
+    const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0) & 0xffffffffull;
+    if (rest) flush_lists<C>(wl, rest, tau, cnt);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -967,6 +1164,33 @@ hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx,
     const bool aligned = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldq % 4 == 0) &&
                          (ldx % 4 == 0) && (d % 4 == 0);
+    if (d <= 16 * kMfmaQregMaxChunks) {
+        // queries held in registers: only the point stream goes through LDS
+        const size_t lds_q = lds - (size_t)2 * kMfmaTileQ * kMfmaRowStride * 4;
+        const int nch = (d + kMfmaKC - 1) / kMfmaKC;
+#define KNN_QREG_LAUNCH(N)                                                                        \
+    do {                                                                                          \
+        if (aligned) {                                                                            \
+            hipError_t e2 = raise_lds_limit(knn_mfma_qreg_kernel<N, true>, lds_q);                \
+            if (e2 != hipSuccess) return e2;                                                      \
+            knn_mfma_qreg_kernel<N, true><<<grid, dim3(256), lds_q, stream>>>(                    \
+                Q, ldq, X, ldx, xn, (int)rows, (int)n, d, k, S, (int)split_len, BQ, BS, lk, li);  \
+        } else {                                                                                  \
+            hipError_t e2 = raise_lds_limit(knn_mfma_qreg_kernel<N, false>, lds_q);               \
+            if (e2 != hipSuccess) return e2;                                                      \
+            knn_mfma_qreg_kernel<N, false><<<grid, dim3(256), lds_q, stream>>>(                   \
+                Q, ldq, X, ldx, xn, (int)rows, (int)n, d, k, S, (int)split_len, BQ, BS, lk, li);  \
+        }                                                                                         \
+    } while (0)
+        if (nch <= 2) KNN_QREG_LAUNCH(2);
+        else if (nch <= 4) KNN_QREG_LAUNCH(4);
+        else if (nch <= 6) KNN_QREG_LAUNCH(6);
+        else if (nch <= 8) KNN_QREG_LAUNCH(8);
+        else if (nch <= 12) KNN_QREG_LAUNCH(12);
+        else KNN_QREG_LAUNCH(16);
+#undef KNN_QREG_LAUNCH
+        return hipGetLastError();
+    }
     hipError_t e;
     if (aligned) {
         e = raise_lds_limit(knn_mfma_kernel<true>, lds);
