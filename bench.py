@@ -49,6 +49,7 @@ def main() -> int:
     ap.add_argument("--mem-limit", default=None, help="e.g. 128MB, 1GB (decimal); default: the workload's")
     ap.add_argument("--m", type=int, default=None, help="override the query count (testing)")
     ap.add_argument("--n", type=int, default=None, help="override the point count (testing)")
+    ap.add_argument("--k", type=int, default=None, help="override the neighbour count (testing)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle time budget; 0 skips it")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="also run one plain elementwise copy of this many MB (read + write) before "
@@ -71,6 +72,8 @@ def main() -> int:
     K.load()
     cfg = int(args.workload.lstrip("c"))
     w = W.scaled(cfg, m=args.m, n=args.n) if (args.m or args.n) else W.WORKLOADS[cfg]
+    if args.k:
+        w = W.scaled(cfg, m=w.m, n=w.n, k=args.k)
     limit = K.knn_parse_size(args.mem_limit) if args.mem_limit else w.mem_limit
 
     t0 = time.time()

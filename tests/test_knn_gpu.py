@@ -68,6 +68,15 @@ SMALL = [
     (9, 200, 3000, 784, 10, "sparse0"),  # d = 784 as in config 3 (small n)
     (10, 33, 20000, 128, 64, "normal"),  # many point ranges, k = 64
     (11, 129, 2500, 10, 12, "normal"),   # unaligned rows (d = 10)
+    # every chunk count of the register-resident-query kernel (d <= 256), aligned and not
+    (12, 140, 2300, 40, 9, "normal"),    # 3 chunks -> 4
+    (13, 140, 2300, 90, 9, "normal"),    # 6 chunks, d % 4 != 0
+    (14, 140, 2300, 128, 9, "normal"),   # 8 chunks
+    (15, 140, 2300, 150, 9, "normal"),   # 10 chunks -> 12, d % 4 != 0
+    (16, 140, 2300, 200, 9, "normal"),   # 13 chunks -> 16
+    (17, 140, 2300, 256, 9, "normal"),   # 16 chunks
+    (18, 140, 2300, 257, 9, "normal"),   # first d of the streamed-query kernel, unaligned
+    (19, 140, 2300, 272, 9, "normal"),   # streamed-query kernel, aligned
 ]
 
 
