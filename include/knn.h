@@ -67,9 +67,10 @@ typedef struct {
     int64_t chunk_rows;  /* query rows per chunk (multiple of tile_q, or m)     */
     int64_t q_chunks;    /* ceil(m / chunk_rows); 0 when m == 0                 */
     int32_t streams;     /* HIP streams used (1: the caller's)                  */
-    int32_t reserved;
-    uint64_t norms_bytes;     /* workspace: per-point squared norms (path 1) or packed
-                                 points [x0 x1 x2 |x|^2] (path 2); 0 on path 0       */
+    int32_t x_blocked;   /* 1: path 1 reads the points from a blocked copy in the workspace */
+    uint64_t norms_bytes;     /* workspace: per-point data. path 1: squared norms, plus the
+                                 blocked copy of X when x_blocked; path 2: packed points
+                                 [x0 x1 x2 |x|^2]; path 0: nothing                    */
     uint64_t lists_bytes;     /* workspace: partial k-lists of one chunk        */
     uint64_t workspace_bytes; /* total device workspace needed, <= mem_limit    */
     uint64_t min_limit_bytes; /* smallest limit any plan for this shape fits in */

@@ -143,6 +143,7 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     float* xn = reinterpret_cast<float*>(ws);
+    void* xblocked = plan.x_blocked ? ws + align_up((uint64_t)n * 4) : nullptr;
     float* lk = reinterpret_cast<float*>(ws + plan.norms_bytes);
     int* li = reinterpret_cast<int*>(ws + plan.norms_bytes + plan.lists_bytes / 2);
     const int S = plan.n_splits;
@@ -152,6 +153,10 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
         hipEvent_t t0 = mark(stream);
         e = launch_row_norms(X, ldx, n, d, xn, stream);
         if (e != hipSuccess) return hip_fail(e, "row norms launch");
+        if (plan.x_blocked) {
+            e = launch_block_points(X, ldx, n, d, xblocked, stream);
+            if (e != hipSuccess) return hip_fail(e, "point blocking launch");
+        }
         close_bracket(t0, stream, 0);
     } else if (plan.path == KNN_PATH_LOWD_MFMA) {
         hipEvent_t t0 = mark(stream);
@@ -171,7 +176,7 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
             e = launch_lowd_mfma(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, lk, li, stream);
             if (e != hipSuccess) return hip_fail(e, "low-d matrix-core search launch");
         } else {
-            e = launch_mfma(Qc, ldq, X, ldx, xn, rows, n, d, k, S, lk, li, stream);
+            e = launch_mfma(Qc, ldq, X, ldx, xn, xblocked, rows, n, d, k, S, lk, li, stream);
             if (e != hipSuccess) return hip_fail(e, "mfma search launch");
         }
         close_bracket(t1, stream, 1);

@@ -26,9 +26,14 @@ hipError_t launch_lowd_mfma(const float* Q, int64_t ldq, const float* X, int64_t
                             int* li, hipStream_t stream);
 
 // d > kLowdMaxD: key = xn[j] - 2 q.x from fp32 MFMA tiles (rank-equivalent to the distance).
+// xblocked: nullptr, or (d <= 256 only) the blocked copy of X made by launch_block_points.
 hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx, const float* xn,
-                       int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
-                       hipStream_t stream);
+                       const void* xblocked, int64_t rows, int64_t n, int d, int k, int S,
+                       float* lk, int* li, hipStream_t stream);
+
+// Blocked copy of X: [ceil(n/128)][ceil(d/16)] contiguous blocks of 128 x 16 floats, zero-filled.
+hipError_t launch_block_points(const float* X, int64_t ldx, int64_t n, int d, void* xblocked,
+                               hipStream_t stream);
 
 // Merge the S lists of each row, re-evaluate the k winners in fp64 difference form,
 // order by (distance, index) and write idx / dist rows.

@@ -813,6 +813,39 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
+// Blocked copy of the points for the register-resident-query kernel: tile t (128 rows) and
+// K chunk c (16 columns) become one contiguous 8 KB block, in the order the kernel reads
+// them, zero-filled past n and past d.  A workgroup's point stream is then one contiguous
+// run (full cache lines, no power-of-two row stride hammering a few L2 sets) that the
+// workgroups sharing a range pull through the L2 once.  Needs 4 * ceil(n/128)*128 *
+// ceil(d/16)*16 bytes of workspace, so the planner uses it only when the limit has room.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void knn_block_points_kernel(const float* __restrict__ X,
+                                                               int64_t ldx, int n, int d,
+                                                               f32x4* __restrict__ Xb) {
+    constexpr int TX = kMfmaTileX, KC = kMfmaKC;
+    const int nch = (d + KC - 1) / KC;
+    const int tile = blockIdx.x;
+    const int srow = threadIdx.x >> 2;
+    const int scol = (threadIdx.x & 3) * 4;
+    for (int c = 0; c < nch; ++c) {
+        const int col = c * KC + scol;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int64_t row = (int64_t)tile * TX + srow + half * 64;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (row < n) {
+                const float* p = X + row * ldx;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (col + e < d) v[e] = p[col + e];
+            }
+            Xb[((size_t)tile * nch + c) * 512 + threadIdx.x + half * 256] = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Matrix-core path for d <= 16 * NCH <= 256: as knn_mfma_kernel, but the queries never go
 // through LDS or the L2 again.  A lane keeps the K values of its query that its half of the
 // wave feeds to the MFMAs (d/2 registers, scaled by -2) for the whole kernel, so only the
@@ -820,11 +853,11 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
 // holds nothing but the point windows its workgroups share.  The chunk loop of a tile is
 // unrolled (NCH is even), which also names the two prefetch register sets statically.
 // ---------------------------------------------------------------------------------------
-template <int NCH, bool ALIGNED>
+template <int NCH, bool ALIGNED, bool BLOCKED>
 __global__ __launch_bounds__(256, 2) void knn_mfma_qreg_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
-    const float* __restrict__ xn, int rows, int n, int d, int k, int S, int split_len,
-    int BQ, int BS, float* __restrict__ lk, int* __restrict__ li) {
+    const f32x4* __restrict__ Xb, const float* __restrict__ xn, int rows, int n, int d, int k,
+    int S, int split_len, int BQ, int BS, float* __restrict__ lk, int* __restrict__ li) {
     static_assert(NCH % 2 == 0, "the chunk loop alternates two LDS buffers and register sets");
     constexpr int TQ = kMfmaTileQ, TX = kMfmaTileX, KC = kMfmaKC, RS = kMfmaRowStride;
     constexpr int C = kMfmaCand;
@@ -886,13 +919,21 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_qreg_kernel(
         float xnv;
     };
     // branch-free: the same three loads on every call (see knn_mfma_kernel)
+    const int nch_real = (d + KC - 1) / KC;  // chunks that exist in the blocked copy
     auto fetch = [&](int step, Staged& g) {
         const int tile = step / NCH;
         const int c = step - tile * NCH;
-        const int col = c * KC + scol;
-        const int64_t jr = (int64_t)j0 + (int64_t)tile * TX + srow;
-        g.x0 = load_row4<ALIGNED>(X, ldx, jr, j1, col, d);
-        g.x1 = load_row4<ALIGNED>(X, ldx, jr + 64, j1, col, d);
+        if (BLOCKED) {
+            // block (tile, chunk): 512 float4, this thread takes entries tid and tid + 256
+            const size_t blk = (size_t)(j0 / TX + tile) * nch_real + (c < nch_real ? c : 0);
+            g.x0 = Xb[blk * 512 + tid];
+            g.x1 = Xb[blk * 512 + tid + 256];
+        } else {
+            const int col = c * KC + scol;
+            const int64_t jr = (int64_t)j0 + (int64_t)tile * TX + srow;
+            g.x0 = load_row4<ALIGNED>(X, ldx, jr, j1, col, d);
+            g.x1 = load_row4<ALIGNED>(X, ldx, jr + 64, j1, col, d);
+        }
         const int64_t jj = (int64_t)j0 + (int64_t)tile * TX + (tid & (TX - 1));
         g.xnv = xn[jj < j1 ? jj : j1 - 1];
     };
@@ -902,9 +943,16 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_qreg_kernel(
         const int col = c * KC + scol;
         const int64_t jr = (int64_t)j0 + (int64_t)tile * TX + srow;
         float* xb = xs + (step & 1) * TX * RS;
-        *reinterpret_cast<f32x4*>(xb + srow * RS + scol) = mask_row4(g.x0, jr < j1, col, d, 1.f);
-        *reinterpret_cast<f32x4*>(xb + (srow + 64) * RS + scol) =
-            mask_row4(g.x1, jr + 64 < j1, col, d, 1.f);
+        if (BLOCKED) {  // the copy is zero-filled already; only a whole missing chunk is masked
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            *reinterpret_cast<f32x4*>(xb + srow * RS + scol) = c < nch_real ? g.x0 : zero;
+            *reinterpret_cast<f32x4*>(xb + (srow + 64) * RS + scol) = c < nch_real ? g.x1 : zero;
+        } else {
+            *reinterpret_cast<f32x4*>(xb + srow * RS + scol) =
+                mask_row4(g.x0, jr < j1, col, d, 1.f);
+            *reinterpret_cast<f32x4*>(xb + (srow + 64) * RS + scol) =
+                mask_row4(g.x1, jr + 64 < j1, col, d, 1.f);
+        }
         if (c == 0 && tid < TX) {
             const int64_t jj = (int64_t)j0 + (int64_t)tile * TX + tid;
             xns[(tile & 1) * TX + tid] = jj < j1 ? g.xnv : kInf;  // +inf: never accepted
@@ -1134,9 +1182,17 @@ hipError_t launch_lowd_mfma(const float* Q, int64_t ldq, const float* X, int64_t
     }
 }
 
+hipError_t launch_block_points(const float* X, int64_t ldx, int64_t n, int d, void* xblocked,
+                               hipStream_t stream) {
+    const unsigned tiles = (unsigned)((n + kMfmaTileX - 1) / kMfmaTileX);
+    knn_block_points_kernel<<<dim3(tiles), dim3(256), 0, stream>>>(
+        X, ldx, (int)n, d, static_cast<f32x4*>(xblocked));
+    return hipGetLastError();
+}
+
 hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx, const float* xn,
-                       int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
-                       hipStream_t stream) {
+                       const void* xblocked, int64_t rows, int64_t n, int d, int k, int S,
+                       float* lk, int* li, hipStream_t stream) {
     const size_t lds = (size_t)(2 * kMfmaTileX * kMfmaRowStride + 2 * kMfmaTileQ * kMfmaRowStride +
                                 2 * kMfmaTileX + 2 * kMfmaTileQ * kMfmaCand +
                                 4 * (2 * kWave + 2 * k)) * 4;
@@ -1168,18 +1224,22 @@ hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx,
         // queries held in registers: only the point stream goes through LDS
         const size_t lds_q = lds - (size_t)2 * kMfmaTileQ * kMfmaRowStride * 4;
         const int nch = (d + kMfmaKC - 1) / kMfmaKC;
+#define KNN_QREG_LAUNCH_AB(N, A, B)                                                               \
+    do {                                                                                          \
+        hipError_t e2 = raise_lds_limit(knn_mfma_qreg_kernel<N, A, B>, lds_q);                    \
+        if (e2 != hipSuccess) return e2;                                                          \
+        knn_mfma_qreg_kernel<N, A, B><<<grid, dim3(256), lds_q, stream>>>(                        \
+            Q, ldq, X, ldx, reinterpret_cast<const f32x4*>(xblocked), xn, (int)rows, (int)n, d,  \
+            k, S, (int)split_len, BQ, BS, lk, li);                                                \
+    } while (0)
 #define KNN_QREG_LAUNCH(N)                                                                        \
     do {                                                                                          \
-        if (aligned) {                                                                            \
-            hipError_t e2 = raise_lds_limit(knn_mfma_qreg_kernel<N, true>, lds_q);                \
-            if (e2 != hipSuccess) return e2;                                                      \
-            knn_mfma_qreg_kernel<N, true><<<grid, dim3(256), lds_q, stream>>>(                    \
-                Q, ldq, X, ldx, xn, (int)rows, (int)n, d, k, S, (int)split_len, BQ, BS, lk, li);  \
+        if (xblocked) {                                                                           \
+            if (aligned) KNN_QREG_LAUNCH_AB(N, true, true);                                       \
+            else KNN_QREG_LAUNCH_AB(N, false, true);                                              \
         } else {                                                                                  \
-            hipError_t e2 = raise_lds_limit(knn_mfma_qreg_kernel<N, false>, lds_q);               \
-            if (e2 != hipSuccess) return e2;                                                      \
-            knn_mfma_qreg_kernel<N, false><<<grid, dim3(256), lds_q, stream>>>(                   \
-                Q, ldq, X, ldx, xn, (int)rows, (int)n, d, k, S, (int)split_len, BQ, BS, lk, li);  \
+            if (aligned) KNN_QREG_LAUNCH_AB(N, true, false);                                      \
+            else KNN_QREG_LAUNCH_AB(N, false, false);                                             \
         }                                                                                         \
     } while (0)
         if (nch <= 2) KNN_QREG_LAUNCH(2);
@@ -1188,6 +1248,7 @@ hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx,
         else if (nch <= 8) KNN_QREG_LAUNCH(8);
         else if (nch <= 12) KNN_QREG_LAUNCH(12);
         else KNN_QREG_LAUNCH(16);
+#undef KNN_QREG_LAUNCH_AB
 #undef KNN_QREG_LAUNCH
         return hipGetLastError();
     }

@@ -153,6 +153,18 @@ extern "C" knn_status knn_plan(int64_t m, int64_t n, int32_t d, int32_t k,
     out->q_chunks = (m + best_rows - 1) / best_rows;
     out->lists_bytes = lists_bytes_for((uint64_t)best_rows, (uint64_t)best_s, (uint64_t)k);
     out->workspace_bytes = out->norms_bytes + out->lists_bytes;
+    if (out->path == KNN_PATH_MFMA && d <= kMfmaKC * kMfmaQregMaxChunks) {
+        // spare room under the limit buys a blocked copy of the points (contiguous 8 KB blocks
+        // in the order the kernel streams them); it never costs a query chunk
+        const uint64_t tiles = ((uint64_t)n + kMfmaTileX - 1) / kMfmaTileX;
+        const uint64_t chunks = ((uint64_t)d + kMfmaKC - 1) / kMfmaKC;
+        const uint64_t blocked = align_up(tiles * chunks * kMfmaTileX * kMfmaKC * 4);
+        if (out->workspace_bytes + blocked <= mem_limit_bytes) {
+            out->x_blocked = 1;
+            out->norms_bytes += blocked;
+            out->workspace_bytes += blocked;
+        }
+    }
     return KNN_OK;
 }
 
