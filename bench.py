@@ -29,10 +29,10 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per search-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/*_pmc.txt), scaled by the copy-kernel calibration stated there.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "c2_pointcloud_d3": 8.08e9,    # knn_lowd_mfma_kernel: 6.25 GB fetched + 1.84 GB written
-    "c3_imagelike_d784": 357.2e9,  # knn_mfma_kernel: 357.1 GB fetched + 0.07 GB written
-    "c4_clustered_d128": 4445.4e9,  # knn_mfma_kernel: 4430.9 GB fetched + 14.5 GB written
-    "c5_memsweep_d256": 916.0e9,   # knn_mfma_kernel: 914.9 GB fetched + 1.15 GB written
+    "c2_pointcloud_d3": 8.07e9,     # knn_lowd_mfma_kernel: 6.24 GB fetched + 1.84 GB written
+    "c3_imagelike_d784": 359.0e9,   # knn_mfma_kernel: 359.0 GB fetched + 0.07 GB written
+    "c4_clustered_d128": 3455.6e9,  # knn_mfma_qreg_kernel: 3443.4 GB fetched + 12.2 GB written
+    "c5_memsweep_d256": 600.0e9,    # knn_mfma_qreg_kernel: 598.9 GB fetched + 1.09 GB written
 }
 
 
@@ -129,7 +129,8 @@ def main() -> int:
     if plan.path == K.KNN_PATH_MFMA:
         flops = 2.0 * w.d * pairs_per_launch  # the -2 Q X^T contraction
         achieved = flops / avg_launch_s / 1e12
-        roofline = {"bound": "mfma", "kernel": "knn_mfma_kernel", "achieved": achieved,
+        kernel = "knn_mfma_qreg_kernel" if w.d <= 256 else "knn_mfma_kernel"
+        roofline = {"bound": "mfma", "kernel": kernel, "achieved": achieved,
                     "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_FP32_MATRIX_TFLOPS, "traffic": traffic,
                     "flops_per_pair": 2 * w.d}
@@ -184,6 +185,7 @@ def main() -> int:
         "config": {"workload": w.name, "m": w.m, "n": w.n, "d": w.d, "k": w.k,
                    "mem_limit_bytes": limit, "workspace_bytes": plan.workspace_bytes,
                    "q_chunks": plan.q_chunks, "point_ranges": plan.n_splits,
+                   "x_blocked": bool(plan.x_blocked),
                    "path": path_name},
         "kernel_ms_per_step": {"norms": norms_ms / args.steps, "search": search_ms / args.steps,
                                "merge_refine": refine_ms / args.steps},
