@@ -177,6 +177,31 @@ def main() -> int:
         parity = check(idx[rows_t].cpu().numpy(), dist[rows_t].cpu().numpy(), o_idx, o_dist, o_next, w.n)
         log(f"[bench] oracle: {cpu_baseline['value']:.3e} pairs/s on {threads} threads; parity {parity}")
 
+    # the memory-limit sweep of the sweep workload (config 5): same inputs, each of its limits
+    sweep = None
+    if w.sweep and not args.mem_limit:
+        sweep = []
+        for lim in w.sweep:
+            p2 = K.knn_plan(w.m, w.n, w.d, w.k, lim)
+            ws2 = torch.empty(max(p2.workspace_bytes, 256), dtype=torch.uint8, device=dev)
+            i2 = torch.empty_like(idx)
+            d2 = torch.empty_like(dist)
+            K.knn_search(Qd, Xd, w.k, lim, workspace=ws2, out=(i2, d2))  # warm-up
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                K.knn_search(Qd, Xd, w.k, lim, workspace=ws2, out=(i2, d2))
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / args.steps
+            sweep.append({"mem_limit_bytes": lim, "workspace_bytes": p2.workspace_bytes,
+                          "q_chunks": p2.q_chunks, "point_ranges": p2.n_splits,
+                          "x_blocked": bool(p2.x_blocked), "ms_per_step": dt * 1e3,
+                          "pairs_per_s": pairs / dt,
+                          "same_result": bool(torch.equal(i2, idx) and torch.equal(d2, dist))})
+            log(f"[bench] sweep limit={lim}: {dt*1e3:.1f} ms, {pairs/dt:.3e} pairs/s, "
+                f"workspace {p2.workspace_bytes} B, same result: {sweep[-1]['same_result']}")
+            del ws2, i2, d2
+
     out = {
         "metric": "query-point pairs per second, exact brute-force kNN (m*n/s)",
         "value": value, "unit": "pairs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -191,6 +216,8 @@ def main() -> int:
                                "merge_refine": refine_ms / args.steps},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity,
     }
+    if sweep is not None:
+        out["mem_limit_sweep"] = sweep
     print(json.dumps(out), flush=True)
     return 0
 
