@@ -38,7 +38,7 @@ typedef enum {
     KNN_ERR_INVALID_ARG = 1,         /* null pointer, m<0, n<1, d<1, k<1, k>n, ld<d */
     KNN_ERR_MEM_LIMIT_TOO_SMALL = 2, /* limit below knn_plan_t.min_limit_bytes      */
     KNN_ERR_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes < plan.workspace_bytes      */
-    KNN_ERR_UNSUPPORTED = 4,         /* n >= 2^31 (int32 indices) or k > KNN_MAX_K  */
+    KNN_ERR_UNSUPPORTED = 4,         /* n > 2^31 - 65536 (int32 indices) or k > KNN_MAX_K */
     KNN_ERR_HIP = 5                  /* a HIP call or kernel launch failed          */
 } knn_status;
 

@@ -54,6 +54,11 @@ hipEvent_t mark(hipStream_t stream) {
     return ev;
 }
 
+// Gives back the opening event of a bracket whose launch failed.
+void drop_bracket(hipEvent_t begin) {
+    if (begin) g_event_pool.push_back(begin);
+}
+
 void close_bracket(hipEvent_t begin, hipStream_t stream, int kind) {
     if (!begin) return;
     hipEvent_t end = mark(stream);
@@ -152,16 +157,20 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
     if (plan.path == KNN_PATH_MFMA) {
         hipEvent_t t0 = mark(stream);
         e = launch_row_norms(X, ldx, n, d, xn, stream);
-        if (e != hipSuccess) return hip_fail(e, "row norms launch");
-        if (plan.x_blocked) {
+        if (e == hipSuccess && plan.x_blocked)
             e = launch_block_points(X, ldx, n, d, xblocked, stream);
-            if (e != hipSuccess) return hip_fail(e, "point blocking launch");
+        if (e != hipSuccess) {
+            drop_bracket(t0);
+            return hip_fail(e, "row norms / point blocking launch");
         }
         close_bracket(t0, stream, 0);
     } else if (plan.path == KNN_PATH_LOWD_MFMA) {
         hipEvent_t t0 = mark(stream);
         e = launch_lowd_mfma(Q, ldq, X, ldx, ws, 0, n, d, k, S, true, lk, li, stream);
-        if (e != hipSuccess) return hip_fail(e, "point packing launch");
+        if (e != hipSuccess) {
+            drop_bracket(t0);
+            return hip_fail(e, "point packing launch");
+        }
         close_bracket(t0, stream, 0);
     }
     for (int64_t c = 0; c < plan.q_chunks; ++c) {
@@ -169,21 +178,24 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
         const int64_t rows = (m - row0 < plan.chunk_rows) ? (m - row0) : plan.chunk_rows;
         const float* Qc = Q + row0 * ldq;
         hipEvent_t t1 = mark(stream);
-        if (plan.path == KNN_PATH_LOWD) {
+        if (plan.path == KNN_PATH_LOWD)
             e = launch_lowd(Qc, ldq, X, ldx, rows, n, d, k, S, lk, li, stream);
-            if (e != hipSuccess) return hip_fail(e, "low-d search launch");
-        } else if (plan.path == KNN_PATH_LOWD_MFMA) {
+        else if (plan.path == KNN_PATH_LOWD_MFMA)
             e = launch_lowd_mfma(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, lk, li, stream);
-            if (e != hipSuccess) return hip_fail(e, "low-d matrix-core search launch");
-        } else {
+        else
             e = launch_mfma(Qc, ldq, X, ldx, xn, xblocked, rows, n, d, k, S, lk, li, stream);
-            if (e != hipSuccess) return hip_fail(e, "mfma search launch");
+        if (e != hipSuccess) {
+            drop_bracket(t1);
+            return hip_fail(e, "search launch");
         }
         close_bracket(t1, stream, 1);
         hipEvent_t t2 = mark(stream);
         e = launch_merge_refine(Qc, ldq, X, ldx, rows, n, d, k, S, lk, li, idx + row0 * k,
                                 dist + row0 * k, stream);
-        if (e != hipSuccess) return hip_fail(e, "merge/refine launch");
+        if (e != hipSuccess) {
+            drop_bracket(t2);
+            return hip_fail(e, "merge/refine launch");
+        }
         close_bracket(t2, stream, 2);
     }
     g_last_plan = plan;

@@ -33,6 +33,7 @@ constexpr int kLowdResidentWorkgroups = 4 * kNumCU;
 constexpr int kMfmaResidentWorkgroups = 2 * kNumCU;
 constexpr int kWarmupPointsPerK = 64;     // list warm-up of one point range, in point-equivalents per k
 constexpr int kMaxSplits = 64;
+constexpr int64_t kMaxPoints = ((int64_t)1 << 31) - 65536;
 constexpr int64_t kMaxChunkRows = 1 << 22;  // keeps per-launch row counts and grids in int range
 constexpr int kMinSplitPoints = 2048;    // a point range shorter than this is not worth a split
 

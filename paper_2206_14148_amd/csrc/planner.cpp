@@ -85,7 +85,8 @@ extern "C" knn_status knn_plan(int64_t m, int64_t n, int32_t d, int32_t k,
     if (!out) return KNN_ERR_INVALID_ARG;
     memset(out, 0, sizeof(*out));
     if (m < 0 || n < 1 || d < 1 || k < 1 || (int64_t)k > n) return KNN_ERR_INVALID_ARG;
-    if (n >= (int64_t)1 << 31 || k > KNN_MAX_K) return KNN_ERR_UNSUPPORTED;
+    // int32 indices, with headroom so that range ends rounded up to a tile stay representable
+    if (n > kMaxPoints || k > KNN_MAX_K) return KNN_ERR_UNSUPPORTED;
     out->m = m;
     out->n = n;
     out->d = d;

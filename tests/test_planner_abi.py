@@ -131,6 +131,10 @@ def test_plan_argument_errors():
         K.knn_plan(5, 1 << 31, 3, 1, 10 ** 12)
     assert ei.value.status == K.KNN_ERR_UNSUPPORTED
     with pytest.raises(K.KnnError) as ei:
+        K.knn_plan(5, (1 << 31) - 65535, 3, 1, 10 ** 12)
+    assert ei.value.status == K.KNN_ERR_UNSUPPORTED
+    assert K.knn_plan(5, (1 << 31) - 65536, 3, 1, 10 ** 12).n == (1 << 31) - 65536
+    with pytest.raises(K.KnnError) as ei:
         K.knn_plan(5, 5000, 3, K.KNN_MAX_K + 1, 10 ** 12)
     assert ei.value.status == K.KNN_ERR_UNSUPPORTED
     p = K.knn_plan(0, 10, 3, 2, 0)  # no queries: empty plan, nothing needed
