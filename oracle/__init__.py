@@ -47,6 +47,12 @@ def _load():
         lib.oracle_knn.restype = ctypes.c_int
         lib.oracle_knn_fullsort.argtypes = common
         lib.oracle_knn_fullsort.restype = ctypes.c_int
+        lib.oracle_knn_metric.argtypes = common + [ctypes.c_int32, ctypes.c_int32]
+        lib.oracle_knn_metric.restype = ctypes.c_int
+        lib.oracle_knn_fullsort_metric.argtypes = common + [ctypes.c_int32]
+        lib.oracle_knn_fullsort_metric.restype = ctypes.c_int
+        lib.oracle_cosdist.argtypes = [fp, fp, ctypes.c_int32]
+        lib.oracle_cosdist.restype = ctypes.c_double
         lib.oracle_sqdist.argtypes = [fp, fp, ctypes.c_int32]
         lib.oracle_sqdist.restype = ctypes.c_double
         lib.oracle_sqdist_expanded.argtypes = [fp, fp, ctypes.c_int32]
@@ -103,14 +109,25 @@ def _run(fn, Q, X, k, rows, extra):
     return idx, dist, nxt
 
 
-def knn(Q, X, k, rows=None, nthreads: int | None = None):
+METRICS = {"l2": 0, "cosine": 1}
+
+
+def knn(Q, X, k, rows=None, nthreads: int | None = None, metric: str = "l2"):
     """Heap-selection oracle.  Returns (idx int64[r,k], dist fp64[r,k], next fp64[r])."""
-    return _run(_load().oracle_knn, Q, X, k, rows, (int(nthreads or default_threads()),))
+    return _run(_load().oracle_knn_metric, Q, X, k, rows,
+                (int(nthreads or default_threads()), METRICS[metric]))
 
 
-def knn_fullsort(Q, X, k, rows=None):
+def knn_fullsort(Q, X, k, rows=None, metric: str = "l2"):
     """Definition written out: all distances, one full sort, first k."""
-    return _run(_load().oracle_knn_fullsort, Q, X, k, rows, ())
+    return _run(_load().oracle_knn_fullsort_metric, Q, X, k, rows, (METRICS[metric],))
+
+
+def cosdist(q, x) -> float:
+    q = np.ascontiguousarray(q, dtype=np.float32).ravel()
+    x = np.ascontiguousarray(x, dtype=np.float32).ravel()
+    fp = ctypes.POINTER(ctypes.c_float)
+    return float(_load().oracle_cosdist(q.ctypes.data_as(fp), x.ctypes.data_as(fp), q.shape[0]))
 
 
 def sqdist(q, x) -> float:
@@ -128,8 +145,8 @@ def sqdist_expanded(q, x) -> float:
                                                 q.shape[0]))
 
 
-def sqdist_pairs(Q, X, qi, xj) -> np.ndarray:
-    """fp64 difference-form distance of the listed (query, point) pairs."""
+def sqdist_pairs(Q, X, qi, xj, metric: str = "l2") -> np.ndarray:
+    """fp64 distance of the listed (query, point) pairs."""
     Q = _as_f32_2d(Q)
     X = _as_f32_2d(X)
     qi = np.asarray(qi, dtype=np.int64).ravel()
@@ -140,7 +157,8 @@ def sqdist_pairs(Q, X, qi, xj) -> np.ndarray:
     d = Q.shape[1]
     qb = Q.ctypes.data
     xb = X.ctypes.data
+    fn = lib.oracle_cosdist if metric == "cosine" else lib.oracle_sqdist
     for p in range(qi.shape[0]):
-        out[p] = lib.oracle_sqdist(ctypes.cast(qb + 4 * d * int(qi[p]), fp),
+        out[p] = fn(ctypes.cast(qb + 4 * d * int(qi[p]), fp),
                                    ctypes.cast(xb + 4 * d * int(xj[p]), fp), d)
     return out

@@ -31,6 +31,12 @@
  * torch.cdist cross-check, the norm-expansion identity of section 4.1,
  * permutation and translation invariance, zero self-distance.
  *
+ * Second metric (the cosine rows of the paper's kNN table, section 5.2 / appendix):
+ *     C[i][j] = max(0, 1 - <q_i, x_j> / (|q_i| |x_j|)),   1 if either vector is zero,
+ * with the three sums accumulated in fp64 in ascending t.  Same selection, same order.
+ * Pins: numpy brute force, orthogonal and antipodal closed forms, exact invariance under
+ * power-of-two scaling, agreement with the Euclidean oracle on unit-normalised data.
+ *
  * Build: gcc -O2 -fopenmp -shared -fPIC (no -ffast-math, no FMA contraction).
  */
 #include <math.h>
@@ -88,6 +94,28 @@ double oracle_sqdist_expanded(const float *q, const float *x, int32_t d)
     return qq + xx - 2.0 * qx;
 }
 
+/* Cosine distance of one pair, fp64: 1 - <q,x> / (|q| |x|), clamped at 0; 1 for a zero vector. */
+double oracle_cosdist(const float *q, const float *x, int32_t d)
+{
+    double qq = 0.0, xx = 0.0, qx = 0.0;
+    for (int32_t t = 0; t < d; ++t) {
+        qq += (double)q[t] * (double)q[t];
+        xx += (double)x[t] * (double)x[t];
+        qx += (double)q[t] * (double)x[t];
+    }
+    if (qq == 0.0 || xx == 0.0) return 1.0;
+    double c = 1.0 - qx / (sqrt(qq) * sqrt(xx));
+    return c < 0.0 ? 0.0 : c;
+}
+
+#define ORACLE_METRIC_L2SQ 0
+#define ORACLE_METRIC_COSINE 1
+
+static double pair_distance(const float *q, const float *x, int32_t d, int32_t metric)
+{
+    return metric == ORACLE_METRIC_COSINE ? oracle_cosdist(q, x, d) : oracle_sqdist(q, x, d);
+}
+
 /* Max-heap on (distance, index): the root is the entry that comes LAST. */
 static void heap_sift_down(pair_t *h, int64_t size, int64_t pos)
 {
@@ -117,12 +145,12 @@ static void heap_sift_up(pair_t *h, int64_t pos)
 
 /* One row, heap selection of the kk = min(k+1, n) first pairs. */
 static void row_select_heap(const float *q, const float *X, int64_t ldx, int64_t n,
-                            int32_t d, int64_t kk, pair_t *heap)
+                            int32_t d, int64_t kk, pair_t *heap, int32_t metric)
 {
     int64_t size = 0;
     for (int64_t j = 0; j < n; ++j) {
         pair_t cur;
-        cur.dist = oracle_sqdist(q, X + j * ldx, d);
+        cur.dist = pair_distance(q, X + j * ldx, d, metric);
         cur.idx = j;
         if (size < kk) {
             heap[size] = cur;
@@ -143,10 +171,11 @@ static void row_select_heap(const float *q, const float *X, int64_t ldx, int64_t
  * (+inf when k == n) so that a caller can measure the gap behind the k-th
  * neighbour.  Returns 0, or -1 on bad arguments / allocation failure.
  */
-int oracle_knn(const float *Q, int64_t ldq, const float *X, int64_t ldx,
-               int64_t n, int32_t d, int32_t k,
-               const int64_t *rows, int64_t nrows,
-               int64_t *idx, double *dist, double *next_dist, int32_t nthreads)
+int oracle_knn_metric(const float *Q, int64_t ldq, const float *X, int64_t ldx,
+                      int64_t n, int32_t d, int32_t k,
+                      const int64_t *rows, int64_t nrows,
+                      int64_t *idx, double *dist, double *next_dist, int32_t nthreads,
+                      int32_t metric)
 {
     if (!Q || !X || !idx || !dist || n < 1 || d < 1 || k < 1 || k > n || nrows < 0 ||
         ldq < d || ldx < d)
@@ -165,7 +194,7 @@ int oracle_knn(const float *Q, int64_t ldq, const float *X, int64_t ldx,
         for (int64_t r = 0; r < nrows; ++r) {
             if (!heap) continue;
             int64_t i = rows ? rows[r] : r;
-            row_select_heap(Q + i * ldq, X, ldx, n, d, kk, heap);
+            row_select_heap(Q + i * ldq, X, ldx, n, d, kk, heap, metric);
             for (int32_t p = 0; p < k; ++p) {
                 idx[r * k + p] = heap[p].idx;
                 dist[r * k + p] = heap[p].dist;
@@ -177,15 +206,24 @@ int oracle_knn(const float *Q, int64_t ldq, const float *X, int64_t ldx,
     return failed ? -1 : 0;
 }
 
+int oracle_knn(const float *Q, int64_t ldq, const float *X, int64_t ldx,
+               int64_t n, int32_t d, int32_t k,
+               const int64_t *rows, int64_t nrows,
+               int64_t *idx, double *dist, double *next_dist, int32_t nthreads)
+{
+    return oracle_knn_metric(Q, ldq, X, ldx, n, d, k, rows, nrows, idx, dist, next_dist, nthreads,
+                             ORACLE_METRIC_L2SQ);
+}
+
 /*
  * oracle_knn_fullsort: the definition written out.  For every requested row
  * all n (distance, index) pairs are formed, sorted once by (distance, index)
  * and the first k are reported.  Single-threaded, O(n log n) per row.
  */
-int oracle_knn_fullsort(const float *Q, int64_t ldq, const float *X, int64_t ldx,
-                        int64_t n, int32_t d, int32_t k,
-                        const int64_t *rows, int64_t nrows,
-                        int64_t *idx, double *dist, double *next_dist)
+int oracle_knn_fullsort_metric(const float *Q, int64_t ldq, const float *X, int64_t ldx,
+                               int64_t n, int32_t d, int32_t k,
+                               const int64_t *rows, int64_t nrows,
+                               int64_t *idx, double *dist, double *next_dist, int32_t metric)
 {
     if (!Q || !X || !idx || !dist || n < 1 || d < 1 || k < 1 || k > n || nrows < 0 ||
         ldq < d || ldx < d)
@@ -195,7 +233,7 @@ int oracle_knn_fullsort(const float *Q, int64_t ldq, const float *X, int64_t ldx
     for (int64_t r = 0; r < nrows; ++r) {
         int64_t i = rows ? rows[r] : r;
         for (int64_t j = 0; j < n; ++j) {
-            all[j].dist = oracle_sqdist(Q + i * ldq, X + j * ldx, d);
+            all[j].dist = pair_distance(Q + i * ldq, X + j * ldx, d, metric);
             all[j].idx = j;
         }
         qsort(all, (size_t)n, sizeof(pair_t), pair_qsort_cmp);
@@ -207,6 +245,15 @@ int oracle_knn_fullsort(const float *Q, int64_t ldq, const float *X, int64_t ldx
     }
     free(all);
     return 0;
+}
+
+int oracle_knn_fullsort(const float *Q, int64_t ldq, const float *X, int64_t ldx,
+                        int64_t n, int32_t d, int32_t k,
+                        const int64_t *rows, int64_t nrows,
+                        int64_t *idx, double *dist, double *next_dist)
+{
+    return oracle_knn_fullsort_metric(Q, ldq, X, ldx, n, d, k, rows, nrows, idx, dist, next_dist,
+                                      ORACLE_METRIC_L2SQ);
 }
 
 /* Number of threads an OpenMP region of the requested width really gets. */

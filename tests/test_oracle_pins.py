@@ -182,3 +182,75 @@ def test_argument_errors(oracle):
         oracle.knn(Q, X[:, :1], 2)  # dimension mismatch
     with pytest.raises(ValueError):
         oracle.knn(Q, X, 2, rows=[5])
+
+
+# ---------------------------------------------------------------------------------------
+# cosine metric (the cosine rows of the paper's kNN table)
+# ---------------------------------------------------------------------------------------
+def np_cosine_bruteforce(Q, X, k):
+    Qd, Xd = Q.astype(np.float64), X.astype(np.float64)
+    qn = np.sqrt((Qd * Qd).sum(1))
+    xn = np.sqrt((Xd * Xd).sum(1))
+    with np.errstate(divide="ignore", invalid="ignore"):
+        C = 1.0 - (Qd @ Xd.T) / (qn[:, None] * xn[None, :])
+    C = np.where((qn[:, None] == 0) | (xn[None, :] == 0), 1.0, C)
+    C = np.maximum(C, 0.0)
+    order = np.argsort(C, axis=1, kind="stable")[:, :k]
+    return order, np.take_along_axis(C, order, axis=1), C
+
+
+@pytest.mark.parametrize("seed,m,n,d", [(20, 6, 40, 2), (21, 5, 64, 7), (22, 4, 33, 20)])
+def test_cosine_bruteforce_every_k(oracle, seed, m, n, d):
+    Q, X = W.random_case(seed, m, n, d)
+    X[3] = 0.0  # a zero vector has distance 1 to everything
+    for k in (1, 2, 5, n // 2, n):
+        ref_idx, ref_dist, C = np_cosine_bruteforce(Q, X, k)
+        for fn in (oracle.knn, oracle.knn_fullsort):
+            idx, dist, nxt = fn(Q, X, k, metric="cosine")
+            # numpy's matmul sums in another order: compare distances, and indices where
+            # the neighbouring distances are not within rounding of each other
+            np.testing.assert_allclose(dist, ref_dist, rtol=0, atol=1e-12)
+            clear = np.ones_like(idx, dtype=bool)
+            srt = np.sort(C, axis=1)
+            gaps = np.diff(srt[:, : k + 1 if k < n else k], axis=1)
+            if k > 1:
+                close = gaps[:, : k - 1] < 1e-11
+                clear[:, 1:] &= ~close
+                clear[:, :-1] &= ~close
+            if k < n:
+                clear[:, -1] &= gaps[:, k - 1] >= 1e-11
+            assert np.array_equal(idx[clear], ref_idx[clear])
+
+
+def test_cosine_closed_forms(oracle):
+    # axis vectors: distance 0 to the same axis (any positive scale), 1 across axes, 2 antipodal
+    X = np.array([[2, 0, 0], [0, 3, 0], [0, 0, 0.5], [-4, 0, 0], [5, 0, 0], [0, 0, 0]], dtype=np.float32)
+    Q = np.array([[1, 0, 0], [0, 0, 7]], dtype=np.float32)
+    idx, dist, _ = oracle.knn(Q, X, 6, metric="cosine")
+    assert idx[0].tolist() == [0, 4, 1, 2, 5, 3]
+    assert dist[0].tolist() == [0.0, 0.0, 1.0, 1.0, 1.0, 2.0]
+    assert idx[1].tolist() == [2, 0, 1, 3, 4, 5]
+    assert dist[1].tolist() == [0.0, 1.0, 1.0, 1.0, 1.0, 1.0]
+    assert oracle.cosdist([1, 1], [1, 0]) == pytest.approx(1 - 1 / np.sqrt(2), abs=1e-15)
+    assert oracle.cosdist([0, 0], [1, 0]) == 1.0
+
+
+def test_cosine_invariant_under_power_of_two_scaling(oracle):
+    # scaling by powers of two is exact in fp32 and fp64, so nothing may change
+    Q, X = W.random_case(23, 15, 300, 9)
+    idx, dist, nxt = oracle.knn(Q, X, 10, metric="cosine")
+    scale = (2.0 ** np.random.Generator(np.random.PCG64(5)).integers(-6, 7, size=(300, 1))).astype(np.float32)
+    idx_s, dist_s, nxt_s = oracle.knn(Q * np.float32(8.0), X * scale, 10, metric="cosine")
+    assert np.array_equal(idx, idx_s) and np.array_equal(dist, dist_s) and np.array_equal(nxt, nxt_s)
+
+
+def test_cosine_matches_euclidean_on_unit_vectors(oracle):
+    # |q - x|^2 = 2 - 2 cos for unit vectors: same neighbours as the Euclidean oracle
+    Q, X = W.random_case(24, 30, 500, 12)
+    Qn = (Q / np.linalg.norm(Q.astype(np.float64), axis=1, keepdims=True)).astype(np.float32)
+    Xn = (X / np.linalg.norm(X.astype(np.float64), axis=1, keepdims=True)).astype(np.float32)
+    c_idx, c_dist, _ = oracle.knn(Qn, Xn, 8, metric="cosine")
+    e_idx, e_dist, _ = oracle.knn(Qn, Xn, 8, metric="l2")
+    assert np.array_equal(c_idx, e_idx)  # continuous data: no ties at this resolution
+    np.testing.assert_allclose(2.0 * c_dist, e_dist, rtol=0, atol=1e-6)  # fp32 normalisation error
+    assert np.all(np.diff(c_dist, axis=1) >= 0)
