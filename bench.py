@@ -45,7 +45,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c2", help="c1..c5 (default c2, the metric's workload)")
+    ap.add_argument("--workload", default="c2", help="c1..c6 (default c2, the metric's workload; c6 is the cosine one)")
     ap.add_argument("--mem-limit", default=None, help="e.g. 128MB, 1GB (decimal); default: the workload's")
     ap.add_argument("--m", type=int, default=None, help="override the query count (testing)")
     ap.add_argument("--n", type=int, default=None, help="override the point count (testing)")
@@ -82,7 +82,7 @@ def main() -> int:
     dev = torch.device("cuda:0")
     Xd = torch.from_numpy(X).to(dev)
     Qd = Xd if w.q_is_x else torch.from_numpy(Q).to(dev)
-    plan = K.knn_plan(w.m, w.n, w.d, w.k, limit)
+    plan = K.knn_plan(w.m, w.n, w.d, w.k, limit, w.metric)
     assert plan.workspace_bytes <= limit
     ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
     idx = torch.empty((w.m, w.k), dtype=torch.int32, device=dev)
@@ -92,7 +92,7 @@ def main() -> int:
         f"ranges={plan.n_splits} workspace={plan.workspace_bytes} B (limit {limit} B)")
 
     def step():
-        K.knn_search(Qd, Xd, w.k, limit, workspace=ws, out=(idx, dist))
+        K.knn_search(Qd, Xd, w.k, limit, workspace=ws, out=(idx, dist), metric=w.metric)
 
     if args.calibrate_copy_mb > 0:
         src = torch.ones(args.calibrate_copy_mb * 250_000, dtype=torch.float32, device=dev)
@@ -163,12 +163,12 @@ def main() -> int:
         threads = oracle.threads_used()
         probe_rows = W.sample_rows(w, min(w.m, 4 * threads))
         t0 = time.perf_counter()
-        oracle.knn(Q, X, w.k, rows=probe_rows)
+        oracle.knn(Q, X, w.k, rows=probe_rows, metric=w.metric)
         probe_rate = len(probe_rows) / max(time.perf_counter() - t0, 1e-6)
         nrows = int(max(len(probe_rows), min(w.m, probe_rate * args.cpu_seconds)))
         rows = W.sample_rows(w, nrows)
         t0 = time.perf_counter()
-        o_idx, o_dist, o_next = oracle.knn(Q, X, w.k, rows=rows)
+        o_idx, o_dist, o_next = oracle.knn(Q, X, w.k, rows=rows, metric=w.metric)
         dt = time.perf_counter() - t0
         cpu_baseline = {"value": len(rows) * float(w.n) / dt, "unit": "pairs/s", "cores": threads,
                         "kind": "oracle",
@@ -182,7 +182,7 @@ def main() -> int:
     if w.sweep and not args.mem_limit:
         sweep = []
         for lim in w.sweep:
-            p2 = K.knn_plan(w.m, w.n, w.d, w.k, lim)
+            p2 = K.knn_plan(w.m, w.n, w.d, w.k, lim, w.metric)
             ws2 = torch.empty(max(p2.workspace_bytes, 256), dtype=torch.uint8, device=dev)
             i2 = torch.empty_like(idx)
             d2 = torch.empty_like(dist)
@@ -207,7 +207,7 @@ def main() -> int:
         "value": value, "unit": "pairs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "m": w.m, "n": w.n, "d": w.d, "k": w.k,
+        "config": {"workload": w.name, "metric": w.metric, "m": w.m, "n": w.n, "d": w.d, "k": w.k,
                    "mem_limit_bytes": limit, "workspace_bytes": plan.workspace_bytes,
                    "q_chunks": plan.q_chunks, "point_ranges": plan.n_splits,
                    "x_blocked": bool(plan.x_blocked),

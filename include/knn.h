@@ -44,6 +44,14 @@ typedef enum {
 
 #define KNN_MAX_K 1024
 
+/*
+ * Distance (section 5.2 and the appendix table report squared-Euclidean, L1 and cosine rows).
+ *   KNN_METRIC_L2SQ    sum_t (q_t - x_t)^2
+ *   KNN_METRIC_COSINE  max(0, 1 - <q, x> / (|q| |x|)); 1 if either vector is zero.
+ *                      Always runs on the matrix-core path (path 1), whatever d.
+ */
+typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1 } knn_metric;
+
 /* kernel families (knn_plan_t.path) */
 #define KNN_PATH_LOWD 0 /* d <= 8: difference-form distances on the vector ALU  */
 #define KNN_PATH_MFMA 1 /* d  > 8: fp32 matrix-core tile of -2 Q X^T plus norms */
@@ -68,6 +76,8 @@ typedef struct {
     int64_t q_chunks;    /* ceil(m / chunk_rows); 0 when m == 0                 */
     int32_t streams;     /* HIP streams used (1: the caller's)                  */
     int32_t x_blocked;   /* 1: path 1 reads the points from a blocked copy in the workspace */
+    int32_t metric;      /* knn_metric                                          */
+    int32_t reserved;
     uint64_t norms_bytes;     /* workspace: per-point data. path 1: squared norms, plus the
                                  blocked copy of X when x_blocked; path 2: packed points
                                  [x0 x1 x2 |x|^2]; path 0: nothing                    */
@@ -83,6 +93,10 @@ typedef struct {
  */
 knn_status knn_plan(int64_t m, int64_t n, int32_t d, int32_t k,
                     uint64_t mem_limit_bytes, knn_plan_t *out /* HOST */);
+
+/* Same for a given metric (knn_plan is the squared-Euclidean case). */
+knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k, knn_metric metric,
+                           uint64_t mem_limit_bytes, knn_plan_t *out /* HOST */);
 
 /* workspace_bytes of the plan above, or 0 if there is none (error or m == 0). */
 uint64_t knn_workspace_bytes(int64_t m, int64_t n, int32_t d, int32_t k,
@@ -117,6 +131,17 @@ knn_status knn_search(const float *Q, int64_t ldq, const float *X, int64_t ldx,
                       uint64_t mem_limit_bytes,
                       void *workspace, uint64_t workspace_bytes,
                       int32_t *idx, float *dist, void *hip_stream);
+
+/*
+ * knn_search_metric - knn_search for a given metric; every other argument as above.  For
+ * KNN_METRIC_COSINE dist holds the fp64 cosine distance rounded to fp32, and the workspace
+ * must satisfy knn_plan_metric(..., KNN_METRIC_COSINE, ...).
+ */
+knn_status knn_search_metric(const float *Q, int64_t ldq, const float *X, int64_t ldx,
+                             int64_t m, int64_t n, int32_t d, int32_t k, knn_metric metric,
+                             uint64_t mem_limit_bytes,
+                             void *workspace, uint64_t workspace_bytes,
+                             int32_t *idx, float *dist, void *hip_stream);
 
 /* Plan and workspace size of this thread's last successful knn_search. */
 knn_status knn_last_stats(knn_plan_t *plan_out /* HOST */,

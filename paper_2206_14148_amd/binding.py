@@ -22,11 +22,14 @@ KNN_MAX_K = 1024
 KNN_PATH_LOWD = 0
 KNN_PATH_MFMA = 1
 KNN_PATH_LOWD_MFMA = 2
+KNN_METRIC_L2SQ = 0
+KNN_METRIC_COSINE = 1
+METRICS = {"l2": KNN_METRIC_L2SQ, "cosine": KNN_METRIC_COSINE}
 
 EXPORTED_SYMBOLS = (
     "knn_plan", "knn_workspace_bytes", "knn_search", "knn_last_stats", "knn_status_string",
     "knn_parse_size", "knn_chunk_rows", "knn_last_hip_error", "knn_profile_enable",
-    "knn_profile_read",
+    "knn_profile_read", "knn_plan_metric", "knn_search_metric",
 )
 
 
@@ -38,6 +41,7 @@ class PlanStruct(ctypes.Structure):
         ("tile_x", ctypes.c_int32), ("n_splits", ctypes.c_int32),
         ("chunk_rows", ctypes.c_int64), ("q_chunks", ctypes.c_int64),
         ("streams", ctypes.c_int32), ("x_blocked", ctypes.c_int32),
+        ("metric", ctypes.c_int32), ("reserved", ctypes.c_int32),
         ("norms_bytes", ctypes.c_uint64), ("lists_bytes", ctypes.c_uint64),
         ("workspace_bytes", ctypes.c_uint64), ("min_limit_bytes", ctypes.c_uint64),
     ]
@@ -57,6 +61,7 @@ class Plan:
     q_chunks: int
     streams: int
     x_blocked: int
+    metric: int
     norms_bytes: int
     lists_bytes: int
     workspace_bytes: int
@@ -88,6 +93,11 @@ def load():
     i64, i32, u64, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_void_p
     lib.knn_plan.argtypes = [i64, i64, i32, i32, u64, ctypes.POINTER(PlanStruct)]
     lib.knn_plan.restype = ctypes.c_int
+    lib.knn_plan_metric.argtypes = [i64, i64, i32, i32, ctypes.c_int, u64, ctypes.POINTER(PlanStruct)]
+    lib.knn_plan_metric.restype = ctypes.c_int
+    lib.knn_search_metric.argtypes = [vp, i64, vp, i64, i64, i64, i32, i32, ctypes.c_int, u64, vp, u64,
+                                      vp, vp, vp]
+    lib.knn_search_metric.restype = ctypes.c_int
     lib.knn_workspace_bytes.argtypes = [i64, i64, i32, i32, u64]
     lib.knn_workspace_bytes.restype = u64
     lib.knn_search.argtypes = [vp, i64, vp, i64, i64, i64, i32, i32, u64, vp, u64, vp, vp, vp]
@@ -116,13 +126,14 @@ def knn_status_string(status: int) -> str:
 
 def _plan_from_struct(ps: PlanStruct) -> Plan:
     return Plan(ps.m, ps.n, ps.d, ps.k, ps.path, ps.tile_q, ps.tile_x, ps.n_splits,
-                ps.chunk_rows, ps.q_chunks, ps.streams, ps.x_blocked, ps.norms_bytes, ps.lists_bytes,
+                ps.chunk_rows, ps.q_chunks, ps.streams, ps.x_blocked, ps.metric, ps.norms_bytes,
+                ps.lists_bytes,
                 ps.workspace_bytes, ps.min_limit_bytes)
 
 
-def knn_plan(m: int, n: int, d: int, k: int, mem_limit_bytes: int) -> Plan:
+def knn_plan(m: int, n: int, d: int, k: int, mem_limit_bytes: int, metric: str = "l2") -> Plan:
     ps = PlanStruct()
-    st = load().knn_plan(m, n, d, k, mem_limit_bytes, ctypes.byref(ps))
+    st = load().knn_plan_metric(m, n, d, k, METRICS[metric], mem_limit_bytes, ctypes.byref(ps))
     if st != KNN_OK:
         raise KnnError(st, knn_status_string(st), int(ps.min_limit_bytes))
     return _plan_from_struct(ps)
@@ -169,15 +180,20 @@ def knn_profile_read():
 
 
 def knn_search_raw(q_ptr, ldq, x_ptr, ldx, m, n, d, k, mem_limit_bytes, ws_ptr, ws_bytes,
-                   idx_ptr, dist_ptr, stream_ptr) -> int:
+                   idx_ptr, dist_ptr, stream_ptr, metric: int = KNN_METRIC_L2SQ) -> int:
     """Direct call, raw integers for pointers; returns the status code."""
-    return int(load().knn_search(q_ptr, ldq, x_ptr, ldx, m, n, d, k, mem_limit_bytes, ws_ptr,
-                                 ws_bytes, idx_ptr, dist_ptr, stream_ptr))
+    if metric == KNN_METRIC_L2SQ:
+        return int(load().knn_search(q_ptr, ldq, x_ptr, ldx, m, n, d, k, mem_limit_bytes, ws_ptr,
+                                     ws_bytes, idx_ptr, dist_ptr, stream_ptr))
+    return int(load().knn_search_metric(q_ptr, ldq, x_ptr, ldx, m, n, d, k, metric,
+                                        mem_limit_bytes, ws_ptr, ws_bytes, idx_ptr, dist_ptr,
+                                        stream_ptr))
 
 
-def knn_search(Q, X, k: int, mem_limit_bytes: int, workspace=None, out=None):
+def knn_search(Q, X, k: int, mem_limit_bytes: int, workspace=None, out=None, metric: str = "l2"):
     """knn_search(Q[m,d], X[n,d], k, mem_limit_bytes) -> (idx int32[m,k], dist fp32[m,k]).
 
+    metric: "l2" (squared Euclidean) or "cosine" (cosine distance).
     Q and X are fp32 CUDA(HIP) tensors, row-major (a row stride larger than d is allowed).
     The workspace (a uint8 tensor of plan.workspace_bytes) is allocated here unless given.
     Work is enqueued on torch's current stream; no synchronisation is done.
@@ -192,7 +208,7 @@ def knn_search(Q, X, k: int, mem_limit_bytes: int, workspace=None, out=None):
         raise KnnError(KNN_ERR_INVALID_ARG, "Q and X must share d and have unit column stride")
     m, d = Q.shape
     n = X.shape[0]
-    plan = knn_plan(m, n, d, k, mem_limit_bytes)
+    plan = knn_plan(m, n, d, k, mem_limit_bytes, metric)
     if workspace is None:
         workspace = torch.empty(max(int(plan.workspace_bytes), 256), dtype=torch.uint8,
                                 device=Q.device)
@@ -206,7 +222,7 @@ def knn_search(Q, X, k: int, mem_limit_bytes: int, workspace=None, out=None):
     ldx = X.stride(0) if n > 1 else max(d, X.stride(0))
     st = knn_search_raw(Q.data_ptr(), ldq, X.data_ptr(), ldx, m, n, d, k, mem_limit_bytes,
                         workspace.data_ptr(), workspace.numel(), idx.data_ptr(),
-                        dist.data_ptr(), stream)
+                        dist.data_ptr(), stream, METRICS[metric])
     if st != KNN_OK:
         detail = knn_status_string(st)
         if st == KNN_ERR_HIP:

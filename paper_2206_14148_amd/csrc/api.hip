@@ -127,13 +127,22 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
                                  uint64_t mem_limit_bytes, void* workspace,
                                  uint64_t workspace_bytes, int32_t* idx, float* dist,
                                  void* hip_stream) {
+    return knn_search_metric(Q, ldq, X, ldx, m, n, d, k, KNN_METRIC_L2SQ, mem_limit_bytes,
+                             workspace, workspace_bytes, idx, dist, hip_stream);
+}
+
+extern "C" knn_status knn_search_metric(const float* Q, int64_t ldq, const float* X, int64_t ldx,
+                                        int64_t m, int64_t n, int32_t d, int32_t k,
+                                        knn_metric metric, uint64_t mem_limit_bytes,
+                                        void* workspace, uint64_t workspace_bytes, int32_t* idx,
+                                        float* dist, void* hip_stream) {
     using namespace knn;
     if (m < 0 || n < 1 || d < 1 || k < 1 || (int64_t)k > n) return KNN_ERR_INVALID_ARG;
     if (ldq < d || ldx < d) return KNN_ERR_INVALID_ARG;
     if (!X) return KNN_ERR_INVALID_ARG;
     if (m > 0 && (!Q || !idx || !dist)) return KNN_ERR_INVALID_ARG;
     knn_plan_t plan;
-    knn_status st = knn_plan(m, n, d, k, mem_limit_bytes, &plan);
+    knn_status st = knn_plan_metric(m, n, d, k, metric, mem_limit_bytes, &plan);
     if (st != KNN_OK) return st;
     if (m == 0) {
         g_last_plan = plan;
@@ -152,11 +161,12 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
     float* lk = reinterpret_cast<float*>(ws + plan.norms_bytes);
     int* li = reinterpret_cast<int*>(ws + plan.norms_bytes + plan.lists_bytes / 2);
     const int S = plan.n_splits;
+    const bool cosine = metric == KNN_METRIC_COSINE;
 
     hipError_t e;
     if (plan.path == KNN_PATH_MFMA) {
         hipEvent_t t0 = mark(stream);
-        e = launch_row_norms(X, ldx, n, d, xn, stream);
+        e = launch_row_norms(X, ldx, n, d, cosine, xn, stream);
         if (e == hipSuccess && plan.x_blocked)
             e = launch_block_points(X, ldx, n, d, xblocked, stream);
         if (e != hipSuccess) {
@@ -183,15 +193,16 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
         else if (plan.path == KNN_PATH_LOWD_MFMA)
             e = launch_lowd_mfma(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, lk, li, stream);
         else
-            e = launch_mfma(Qc, ldq, X, ldx, xn, xblocked, rows, n, d, k, S, lk, li, stream);
+            e = launch_mfma(Qc, ldq, X, ldx, xn, xblocked, cosine, rows, n, d, k, S, lk, li,
+                            stream);
         if (e != hipSuccess) {
             drop_bracket(t1);
             return hip_fail(e, "search launch");
         }
         close_bracket(t1, stream, 1);
         hipEvent_t t2 = mark(stream);
-        e = launch_merge_refine(Qc, ldq, X, ldx, rows, n, d, k, S, lk, li, idx + row0 * k,
-                                dist + row0 * k, stream);
+        e = launch_merge_refine(Qc, ldq, X, ldx, rows, n, d, k, S, cosine, lk, li,
+                                idx + row0 * k, dist + row0 * k, stream);
         if (e != hipSuccess) {
             drop_bracket(t2);
             return hip_fail(e, "merge/refine launch");

@@ -10,8 +10,9 @@ namespace knn {
 // rows * S * k entries: keys (fp32) and point indices (int32).  The list of chunk row r
 // and point range s starts at ((r * S) + s) * k and is ascending by (key, index).
 
-// xn[j] = sum_t X[j][t]^2 in fp32 (the sum x^2 term of paper section 4.1).
-hipError_t launch_row_norms(const float* X, int64_t ldx, int64_t n, int d, float* xn,
+// xn[j] = sum_t X[j][t]^2 in fp32 (the sum x^2 term of paper section 4.1); inverse = true writes
+// 1 / sqrt(that) instead (0 for a zero row), the row scale of the cosine metric.
+hipError_t launch_row_norms(const float* X, int64_t ldx, int64_t n, int d, bool inverse, float* xn,
                             hipStream_t stream);
 
 // d <= kLowdMaxD: key = fp32 difference-form squared distance.
@@ -27,9 +28,10 @@ hipError_t launch_lowd_mfma(const float* Q, int64_t ldq, const float* X, int64_t
 
 // d > kLowdMaxD: key = xn[j] - 2 q.x from fp32 MFMA tiles (rank-equivalent to the distance).
 // xblocked: nullptr, or (d <= 256 only) the blocked copy of X made by launch_block_points.
+// cosine: xn holds 1/|x| and the key is -2 q.x / |x| (rank-equivalent to the cosine distance).
 hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx, const float* xn,
-                       const void* xblocked, int64_t rows, int64_t n, int d, int k, int S,
-                       float* lk, int* li, hipStream_t stream);
+                       const void* xblocked, bool cosine, int64_t rows, int64_t n, int d, int k,
+                       int S, float* lk, int* li, hipStream_t stream);
 
 // Blocked copy of X: [ceil(n/128)][ceil(d/16)] contiguous blocks of 128 x 16 floats, zero-filled.
 hipError_t launch_block_points(const float* X, int64_t ldx, int64_t n, int d, void* xblocked,
@@ -38,7 +40,8 @@ hipError_t launch_block_points(const float* X, int64_t ldx, int64_t n, int d, vo
 // Merge the S lists of each row, re-evaluate the k winners in fp64 difference form,
 // order by (distance, index) and write idx / dist rows.
 hipError_t launch_merge_refine(const float* Q, int64_t ldq, const float* X, int64_t ldx,
-                               int64_t rows, int64_t n, int d, int k, int S, const float* lk,
-                               const int* li, int32_t* idx, float* dist, hipStream_t stream);
+                               int64_t rows, int64_t n, int d, int k, int S, bool cosine,
+                               const float* lk, const int* li, int32_t* idx, float* dist,
+                               hipStream_t stream);
 
 }  // namespace knn

@@ -212,6 +212,22 @@ __device__ __forceinline__ void tile_epilogue(const f32x16 (&acc)[4], const Wave
     }
 }
 
+// Cosine metric: the accumulators hold -2 q.x; multiply each by 1/|x| of its point row (rs is
+// the tile's 128 row scales in LDS) to get the rank-equivalent key -2 q.x / |x|.
+__device__ __forceinline__ void scale_rows(f32x16 (&acc)[4], const float* rs, int h) {
+#pragma unroll
+    for (int pb = 0; pb < 4; ++pb) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(rs + pb * 32 + g * 8 + h * 4);
+            acc[pb][g * 4 + 0] *= v[0];
+            acc[pb][g * 4 + 1] *= v[1];
+            acc[pb][g * 4 + 2] *= v[2];
+            acc[pb][g * 4 + 3] *= v[3];
+        }
+    }
+}
+
 // Workgroup -> (query tile, point range).  Consecutive workgroup ids go round-robin to the 8
 // XCDs, each with its own L2.  The (tile, range) grid is cut into blocks of BQ tiles x BS
 // ranges; a block is handed to one XCD as BQ*BS consecutive workgroups of that XCD, so the
@@ -256,9 +272,10 @@ __device__ __forceinline__ void init_lists32(float* __restrict__ lk, int* __rest
 // ---------------------------------------------------------------------------------------
 // Row norms (section 4.1, the sum x^2 term): one wave per row, fixed summation order.
 // ---------------------------------------------------------------------------------------
+// inverse != 0 writes 1 / sqrt(sum) instead (0 for a zero row): the cosine metric's row scale.
 __global__ __launch_bounds__(256) void knn_row_norms_kernel(const float* __restrict__ X,
                                                             int64_t ldx, int64_t n, int d,
-                                                            float* __restrict__ xn) {
+                                                            int inverse, float* __restrict__ xn) {
     const int lane = threadIdx.x & 63;
     const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * 4;
@@ -268,6 +285,7 @@ __global__ __launch_bounds__(256) void knn_row_norms_kernel(const float* __restr
         for (int t = lane; t < d; t += kWave) acc = fmaf(row[t], row[t], acc);
 #pragma unroll
         for (int s = 32; s > 0; s >>= 1) acc += __shfl_xor(acc, s);
+        if (inverse) acc = acc > 0.f ? 1.f / sqrtf(acc) : 0.f;
         if (lane == 0) xn[j] = acc;
     }
 }
@@ -641,15 +659,16 @@ __device__ __forceinline__ f32x4 mask_row4(f32x4 v, bool row_ok, int col, int d,
 template <bool ALIGNED>
 __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
-    const float* __restrict__ xn, int rows, int n, int d, int k, int S, int split_len,
+    const float* __restrict__ xn, int cosine, int rows, int n, int d, int k, int S, int split_len,
     int BQ, int BS, float* __restrict__ lk, int* __restrict__ li) {
     constexpr int TQ = kMfmaTileQ, TX = kMfmaTileX, KC = kMfmaKC, RS = kMfmaRowStride;
     constexpr int C = kMfmaCand;
     extern __shared__ __align__(16) unsigned char smem[];
     float* xs = reinterpret_cast<float*>(smem);        // [2][TX][RS]
     float* qs = xs + 2 * TX * RS;                      // [2][TQ][RS]
-    float* xns = qs + 2 * TQ * RS;                     // [2][TX]
-    float* ck = xns + 2 * TX;                          // [TQ][C]
+    float* xns = qs + 2 * TQ * RS;                     // [2][TX] accumulator start values
+    float* rns = xns + 2 * TX;                         // [2][TX] row scales (cosine metric)
+    float* ck = rns + 2 * TX;                          // [TQ][C]
     int* ci = reinterpret_cast<int*>(ck + TQ * C);     // [TQ][C]
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -737,8 +756,10 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
             mask_row4(g.q1, wg_row0 + srow + 64 < rows, col, d, -2.f);
         if (c == 0 && tid < TX) {
             const int64_t jj = (int64_t)j0 + (int64_t)tile * TX + tid;
-            // rows past the range get +inf: they can never be accepted
-            xns[(tile & 1) * TX + tid] = jj < j1 ? g.xnv : kInf;
+            // rows past the range get +inf: they can never be accepted.  xn holds |x|^2
+            // (start value) for the Euclidean metric, 1/|x| (final scale) for cosine.
+            xns[(tile & 1) * TX + tid] = jj < j1 ? (cosine ? 0.f : g.xnv) : kInf;
+            rns[(tile & 1) * TX + tid] = (cosine && jj < j1) ? g.xnv : 1.f;
         }
     };
 
@@ -800,7 +821,10 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_kernel(
             }
         }
 
-        if (c == nch - 1) tile_epilogue<C>(acc, wl, j0 + tile * TX, tau, cnt);
+        if (c == nch - 1) {
+            if (cosine) scale_rows(acc, rns + (tile & 1) * TX, h);
+            tile_epilogue<C>(acc, wl, j0 + tile * TX, tau, cnt);
+        }
 
         __syncthreads();
     };
@@ -856,15 +880,16 @@ __global__ __launch_bounds__(256) void knn_block_points_kernel(const float* __re
 template <int NCH, bool ALIGNED, bool BLOCKED>
 __global__ __launch_bounds__(256, 2) void knn_mfma_qreg_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
-    const f32x4* __restrict__ Xb, const float* __restrict__ xn, int rows, int n, int d, int k,
-    int S, int split_len, int BQ, int BS, float* __restrict__ lk, int* __restrict__ li) {
+    const f32x4* __restrict__ Xb, const float* __restrict__ xn, int cosine, int rows, int n, int d,
+    int k, int S, int split_len, int BQ, int BS, float* __restrict__ lk, int* __restrict__ li) {
     static_assert(NCH % 2 == 0, "the chunk loop alternates two LDS buffers and register sets");
     constexpr int TQ = kMfmaTileQ, TX = kMfmaTileX, KC = kMfmaKC, RS = kMfmaRowStride;
     constexpr int C = kMfmaCand;
     extern __shared__ __align__(16) unsigned char smem[];
     float* xs = reinterpret_cast<float*>(smem);     // [2][TX][RS]
-    float* xns = xs + 2 * TX * RS;                  // [2][TX]
-    float* ck = xns + 2 * TX;                       // [TQ][C]
+    float* xns = xs + 2 * TX * RS;                  // [2][TX] accumulator start values
+    float* rns = xns + 2 * TX;                      // [2][TX] row scales (cosine metric)
+    float* ck = rns + 2 * TX;                       // [TQ][C]
     int* ci = reinterpret_cast<int*>(ck + TQ * C);  // [TQ][C]
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -955,7 +980,9 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_qreg_kernel(
         }
         if (c == 0 && tid < TX) {
             const int64_t jj = (int64_t)j0 + (int64_t)tile * TX + tid;
-            xns[(tile & 1) * TX + tid] = jj < j1 ? g.xnv : kInf;  // +inf: never accepted
+            // +inf: never accepted.  xn is |x|^2 (Euclidean) or 1/|x| (cosine), see above.
+            xns[(tile & 1) * TX + tid] = jj < j1 ? (cosine ? 0.f : g.xnv) : kInf;
+            rns[(tile & 1) * TX + tid] = (cosine && jj < j1) ? g.xnv : 1.f;
         }
     };
 
@@ -1008,7 +1035,10 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_qreg_kernel(
                 }
                 if (g == 0 && step + 1 < total) stash(step + 1, next);
             }
-            if (c == NCH - 1) tile_epilogue<C>(acc, wl, j0 + tile * TX, tau, cnt);
+            if (c == NCH - 1) {
+                if (cosine) scale_rows(acc, rns + (tile & 1) * TX, h);
+                tile_epilogue<C>(acc, wl, j0 + tile * TX, tau, cnt);
+            }
             __syncthreads();
         }
     }
@@ -1030,10 +1060,26 @@ __device__ __forceinline__ double exact_sqdist(const float* __restrict__ q,
     return acc;
 }
 
+// Cosine distance in fp64: 1 - <q,x> / (|q| |x|), clamped at 0; 1 if either vector is zero.
+__device__ __forceinline__ double exact_cosdist(const float* __restrict__ q,
+                                                const float* __restrict__ x, int d) {
+#pragma clang fp contract(off)
+    double qq = 0.0, xx = 0.0, qx = 0.0;
+    for (int t = 0; t < d; ++t) {
+        const double a = (double)q[t], b = (double)x[t];
+        qq = qq + a * a;
+        xx = xx + b * b;
+        qx = qx + a * b;
+    }
+    if (qq == 0.0 || xx == 0.0) return 1.0;
+    const double c = 1.0 - __ddiv_rn(qx, __dsqrt_rn(qq) * __dsqrt_rn(xx));
+    return c < 0.0 ? 0.0 : c;
+}
+
 __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx, int rows,
-    int n, int d, int k, int S, const float* __restrict__ lk, const int* __restrict__ li,
-    int32_t* __restrict__ idx_out, float* __restrict__ dist_out) {
+    int n, int d, int k, int S, int cosine, const float* __restrict__ lk,
+    const int* __restrict__ li, int32_t* __restrict__ idx_out, float* __restrict__ dist_out) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -1075,7 +1121,8 @@ __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
         const int j = wi[w];
         double dist = __builtin_huge_val();
         if ((unsigned)j < (unsigned)n)
-            dist = exact_sqdist(Q + (int64_t)r * ldq, X + (int64_t)j * ldx, d);
+            dist = cosine ? exact_cosdist(Q + (int64_t)r * ldq, X + (int64_t)j * ldx, d)
+                          : exact_sqdist(Q + (int64_t)r * ldq, X + (int64_t)j * ldx, d);
         wd[w] = dist;
     }
     wave_sync();
@@ -1098,11 +1145,12 @@ hipError_t raise_lds_limit(F kernel, size_t bytes) {
 
 }  // namespace
 
-hipError_t launch_row_norms(const float* X, int64_t ldx, int64_t n, int d, float* xn,
+hipError_t launch_row_norms(const float* X, int64_t ldx, int64_t n, int d, bool inverse, float* xn,
                             hipStream_t stream) {
     int64_t blocks = (n + 3) / 4;
     if (blocks > 16384) blocks = 16384;
-    knn_row_norms_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(X, ldx, n, d, xn);
+    knn_row_norms_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(X, ldx, n, d,
+                                                                           inverse ? 1 : 0, xn);
     return hipGetLastError();
 }
 
@@ -1191,10 +1239,10 @@ hipError_t launch_block_points(const float* X, int64_t ldx, int64_t n, int d, vo
 }
 
 hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx, const float* xn,
-                       const void* xblocked, int64_t rows, int64_t n, int d, int k, int S,
-                       float* lk, int* li, hipStream_t stream) {
+                       const void* xblocked, bool cosine, int64_t rows, int64_t n, int d, int k,
+                       int S, float* lk, int* li, hipStream_t stream) {
     const size_t lds = (size_t)(2 * kMfmaTileX * kMfmaRowStride + 2 * kMfmaTileQ * kMfmaRowStride +
-                                2 * kMfmaTileX + 2 * kMfmaTileQ * kMfmaCand +
+                                4 * kMfmaTileX + 2 * kMfmaTileQ * kMfmaCand +
                                 4 * (2 * kWave + 2 * k)) * 4;
     int64_t split_len = (n + S - 1) / S;
     split_len = (split_len + kMfmaTileX - 1) / kMfmaTileX * kMfmaTileX;
@@ -1229,8 +1277,8 @@ hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx,
         hipError_t e2 = raise_lds_limit(knn_mfma_qreg_kernel<N, A, B>, lds_q);                    \
         if (e2 != hipSuccess) return e2;                                                          \
         knn_mfma_qreg_kernel<N, A, B><<<grid, dim3(256), lds_q, stream>>>(                        \
-            Q, ldq, X, ldx, reinterpret_cast<const f32x4*>(xblocked), xn, (int)rows, (int)n, d,  \
-            k, S, (int)split_len, BQ, BS, lk, li);                                                \
+            Q, ldq, X, ldx, reinterpret_cast<const f32x4*>(xblocked), xn, cosine ? 1 : 0,         \
+            (int)rows, (int)n, d, k, S, (int)split_len, BQ, BS, lk, li);                          \
     } while (0)
 #define KNN_QREG_LAUNCH(N)                                                                        \
     do {                                                                                          \
@@ -1256,26 +1304,29 @@ hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx,
     if (aligned) {
         e = raise_lds_limit(knn_mfma_kernel<true>, lds);
         if (e != hipSuccess) return e;
-        knn_mfma_kernel<true><<<grid, dim3(256), lds, stream>>>(
-            Q, ldq, X, ldx, xn, (int)rows, (int)n, d, k, S, (int)split_len, BQ, BS, lk, li);
+        knn_mfma_kernel<true><<<grid, dim3(256), lds, stream>>>(Q, ldq, X, ldx, xn, cosine ? 1 : 0,
+                                                                (int)rows, (int)n, d, k, S,
+                                                                (int)split_len, BQ, BS, lk, li);
     } else {
         e = raise_lds_limit(knn_mfma_kernel<false>, lds);
         if (e != hipSuccess) return e;
-        knn_mfma_kernel<false><<<grid, dim3(256), lds, stream>>>(
-            Q, ldq, X, ldx, xn, (int)rows, (int)n, d, k, S, (int)split_len, BQ, BS, lk, li);
+        knn_mfma_kernel<false><<<grid, dim3(256), lds, stream>>>(Q, ldq, X, ldx, xn, cosine ? 1 : 0,
+                                                                 (int)rows, (int)n, d, k, S,
+                                                                 (int)split_len, BQ, BS, lk, li);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_merge_refine(const float* Q, int64_t ldq, const float* X, int64_t ldx,
-                               int64_t rows, int64_t n, int d, int k, int S, const float* lk,
-                               const int* li, int32_t* idx, float* dist, hipStream_t stream) {
+                               int64_t rows, int64_t n, int d, int k, int S, bool cosine,
+                               const float* lk, const int* li, int32_t* idx, float* dist,
+                               hipStream_t stream) {
     const size_t lds = (size_t)4 * k * (sizeof(double) + sizeof(int));
     hipError_t e = raise_lds_limit(knn_merge_refine_kernel, lds);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((rows + 3) / 4));
-    knn_merge_refine_kernel<<<grid, dim3(256), lds, stream>>>(Q, ldq, X, ldx, (int)rows, (int)n, d,
-                                                              k, S, lk, li, idx, dist);
+    knn_merge_refine_kernel<<<grid, dim3(256), lds, stream>>>(
+        Q, ldq, X, ldx, (int)rows, (int)n, d, k, S, cosine ? 1 : 0, lk, li, idx, dist);
     return hipGetLastError();
 }
 

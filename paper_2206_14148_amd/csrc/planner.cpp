@@ -82,8 +82,15 @@ int64_t rows_fitting(uint64_t avail, uint64_t S, uint64_t k) {
 
 extern "C" knn_status knn_plan(int64_t m, int64_t n, int32_t d, int32_t k,
                                uint64_t mem_limit_bytes, knn_plan_t* out) {
+    return knn_plan_metric(m, n, d, k, KNN_METRIC_L2SQ, mem_limit_bytes, out);
+}
+
+extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k, knn_metric metric,
+                                      uint64_t mem_limit_bytes, knn_plan_t* out) {
     if (!out) return KNN_ERR_INVALID_ARG;
     memset(out, 0, sizeof(*out));
+    if (metric != KNN_METRIC_L2SQ && metric != KNN_METRIC_COSINE) return KNN_ERR_INVALID_ARG;
+    out->metric = (int32_t)metric;
     if (m < 0 || n < 1 || d < 1 || k < 1 || (int64_t)k > n) return KNN_ERR_INVALID_ARG;
     // int32 indices, with headroom so that range ends rounded up to a tile stay representable
     if (n > kMaxPoints || k > KNN_MAX_K) return KNN_ERR_UNSUPPORTED;
@@ -92,7 +99,8 @@ extern "C" knn_status knn_plan(int64_t m, int64_t n, int32_t d, int32_t k,
     out->d = d;
     out->k = k;
     out->streams = 1;
-    const bool lowd = d <= kLowdMaxD;
+    // the cosine keys come from the matrix-core kernels only
+    const bool lowd = d <= kLowdMaxD && metric == KNN_METRIC_L2SQ;
     // smallest plan of all: the vector-ALU path (no per-point workspace) or the MFMA path
     out->path = lowd ? KNN_PATH_LOWD : KNN_PATH_MFMA;
     out->tile_q = lowd ? kLowdTileQ : kMfmaTileQ;
@@ -106,7 +114,7 @@ extern "C" knn_status knn_plan(int64_t m, int64_t n, int32_t d, int32_t k,
     }
     if (m == 0) return KNN_OK;
     if (mem_limit_bytes < out->min_limit_bytes) return KNN_ERR_MEM_LIMIT_TOO_SMALL;
-    if (d <= kPmMaxD) {
+    if (d <= kPmMaxD && lowd) {
         // the matrix-core filter needs the points packed into the workspace; take it when the
         // limit has room for that and at least one query tile of lists
         const uint64_t packed = kAlign + align_up((uint64_t)n * 16);

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
-SAMPLE_ROWS = {1: 1000, 2: 2000, 3: 64, 4: 48, 5: 64}
+SAMPLE_ROWS = {1: 1000, 2: 2000, 3: 64, 4: 48, 5: 64, 6: 256}
 
 
 def say(*a):
@@ -30,7 +30,7 @@ def K():
     return K
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5, 6])
 def test_full_size_workload(K, oracle, cfg):
     w = W.WORKLOADS[cfg]
     t0 = time.time()
@@ -41,13 +41,14 @@ def test_full_size_workload(K, oracle, cfg):
     limits = w.sweep if w.sweep else (w.mem_limit,)
     results = []
     for limit in limits:
-        plan = K.knn_plan(w.m, w.n, w.d, w.k, limit)
+        plan = K.knn_plan(w.m, w.n, w.d, w.k, limit, w.metric)
         assert plan.workspace_bytes <= limit
         guard = 4096
         ws = torch.full((plan.workspace_bytes + guard,), 0x5A, dtype=torch.uint8, device="cuda")
         torch.cuda.synchronize()
         t0 = time.time()
-        idx, dist = K.knn_search(Qd, Xd, w.k, limit, workspace=ws[: plan.workspace_bytes])
+        idx, dist = K.knn_search(Qd, Xd, w.k, limit, workspace=ws[: plan.workspace_bytes],
+                                   metric=w.metric)
         torch.cuda.synchronize()
         dt = time.time() - t0
         assert bool((ws[plan.workspace_bytes:] == 0x5A).all()), "wrote past the planned workspace"
@@ -71,7 +72,7 @@ def test_full_size_workload(K, oracle, cfg):
 
     rows = W.sample_rows(w, SAMPLE_ROWS[cfg])
     t0 = time.time()
-    o_idx, o_dist, o_next = oracle.knn(Q, X, w.k, rows=rows)
+    o_idx, o_dist, o_next = oracle.knn(Q, X, w.k, rows=rows, metric=w.metric)
     say(f"   oracle on {len(rows)} rows: {time.time()-t0:.1f}s")
     rt = torch.from_numpy(rows).cuda()
     stats = check(idx[rt].cpu().numpy(), dist[rt].cpu().numpy(), o_idx, o_dist, o_next, w.n)

@@ -29,24 +29,24 @@ def K():
     return K
 
 
-def run_gpu(K, Q, X, k, limit, q_is_x=False):
+def run_gpu(K, Q, X, k, limit, q_is_x=False, metric="l2"):
     Xd = torch.from_numpy(X).cuda()
     Qd = Xd if q_is_x else torch.from_numpy(Q).cuda()
-    idx, dist = K.knn_search(Qd, Xd, k, limit)
+    idx, dist = K.knn_search(Qd, Xd, k, limit, metric=metric)
     torch.cuda.synchronize()
     return idx.cpu().numpy(), dist.cpu().numpy()
 
 
-def parity(K, oracle, Q, X, k, limit=64 * W.MB, q_is_x=False, rows=None):
-    idx, dist = run_gpu(K, Q, X, k, limit, q_is_x)
-    o_idx, o_dist, o_next = oracle.knn(Q, X, k, rows=rows)
+def parity(K, oracle, Q, X, k, limit=64 * W.MB, q_is_x=False, rows=None, metric="l2"):
+    idx, dist = run_gpu(K, Q, X, k, limit, q_is_x, metric)
+    o_idx, o_dist, o_next = oracle.knn(Q, X, k, rows=rows, metric=metric)
     if rows is not None:
         idx, dist = idx[rows], dist[rows]
     sel = np.arange(Q.shape[0]) if rows is None else rows
 
     def pair_dist(cols):
         qi = np.repeat(sel, cols.shape[1])
-        return oracle.sqdist_pairs(Q, X, qi, cols.ravel()).reshape(cols.shape)
+        return oracle.sqdist_pairs(Q, X, qi, cols.ravel(), metric).reshape(cols.shape)
 
     stats = check(idx, dist, o_idx, o_dist, o_next, X.shape[0],
                   pair_dist if Q.shape[0] * k <= 20000 else None)
@@ -260,3 +260,53 @@ def test_large_k(K, oracle):
     parity(K, oracle, Q, X, 1000)
     Q, X = W.random_case(901, 40, 3000, 20)
     parity(K, oracle, Q, X, 1024)
+
+
+# ---------------------------------------------------------------------------------------
+# cosine metric
+# ---------------------------------------------------------------------------------------
+COSINE = [
+    (0, 50, 900, 3, 7),       # low d still runs on the matrix-core path
+    (1, 130, 4100, 20, 16),   # unaligned-free small d, several ranges
+    (2, 140, 2300, 100, 10),  # the table's d = 100
+    (3, 140, 2300, 150, 9),   # d % 4 != 0
+    (4, 90, 2300, 300, 12),   # streamed-query kernel
+    (5, 64, 300, 50, 300),    # k == n
+]
+
+
+@pytest.mark.parametrize("seed,m,n,d,k", COSINE)
+def test_cosine_parity_small(K, oracle, seed, m, n, d, k):
+    say(f"\ncosine case seed={seed} m={m} n={n} d={d} k={k}")
+    Q, X = W.random_case(1100 + seed, m, n, d)
+    X[5] = 0.0  # a zero point: distance 1 to everything
+    Q[2] = 0.0  # a zero query: distance 1 to everything, neighbours are the lowest indices
+    stats, idx, dist = parity(K, oracle, Q, X, k, metric="cosine")
+    assert stats["strict_rows"] >= 0.97 * stats["rows"]
+    assert idx[2].tolist() == list(range(k)) and np.all(dist[2] == 1.0)
+
+
+def test_cosine_result_does_not_depend_on_limit_or_point_layout(K):
+    m, n, d, k = 300, 9000, 64, 15
+    Q, X = W.random_case(1200, m, n, d)
+    lo = K.knn_plan(m, n, d, k, 1 << 40, "cosine").min_limit_bytes
+    limits = [lo, lo + 300_000, 64 * W.MB]
+    plans = [K.knn_plan(m, n, d, k, lim, "cosine") for lim in limits]
+    say("   plans", [(p.q_chunks, p.n_splits, p.x_blocked) for p in plans])
+    assert plans[0].x_blocked == 0 and plans[-1].x_blocked == 1 and plans[0].q_chunks > 1
+    ref = run_gpu(K, Q, X, k, limits[0], metric="cosine")
+    for lim in limits[1:]:
+        idx, dist = run_gpu(K, Q, X, k, lim, metric="cosine")
+        assert np.array_equal(idx, ref[0]) and np.array_equal(dist, ref[1]), lim
+
+
+def test_cosine_on_clustered_embeddings_and_scale_invariance(K, oracle):
+    # the embedding-like mixture of config 4 (the table's cosine rows are word embeddings)
+    w = W.scaled(4, m=400, n=30000)
+    Q, X = W.make(w)
+    stats, idx, dist = parity(K, oracle, Q, X, 20, metric="cosine", rows=W.sample_rows(w, 200))
+    assert stats["strict_rows"] >= 0.97 * stats["rows"]
+    # scaling points by positive factors must not change the neighbours
+    scale = (2.0 ** np.random.Generator(np.random.PCG64(3)).integers(-3, 4, size=(w.n, 1))).astype(np.float32)
+    idx_s, dist_s = run_gpu(K, Q * np.float32(4.0), X * scale, 20, 64 * W.MB, metric="cosine")
+    assert np.array_equal(dist_s, dist_s) and np.mean(idx_s == run_gpu(K, Q, X, 20, 64 * W.MB, metric="cosine")[0]) > 0.999

@@ -35,6 +35,7 @@ class Workload:
     kind: str            # value distribution
     q_is_x: bool = False  # queries are the data points themselves (kNN graph)
     sweep: tuple = ()     # extra memory limits (config 5)
+    metric: str = "l2"    # "l2" (squared Euclidean) or "cosine"
 
     @property
     def pairs(self) -> int:
@@ -48,6 +49,9 @@ WORKLOADS = {
     4: Workload(4, "c4_clustered_d128", 100_000, 10_000_000, 128, 100, 8 * GB, "gmm"),
     5: Workload(5, "c5_memsweep_d256", 50_000, 2_000_000, 256, 32, 1 * GB, "normal",
                 sweep=(128 * MB, 1 * GB, 8 * GB, 64 * GB)),
+    # the cosine rows of the paper's table: word embeddings with n = 1,183,514 and d in
+    # {50, 100, 200}, m = 1e4 queries; the same clustered mixture stands in for them
+    6: Workload(6, "c6_cosine_d100", 10_000, 1_183_514, 100, 10, 1 * GB, "gmm", metric="cosine"),
 }
 
 
