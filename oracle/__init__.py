@@ -53,6 +53,8 @@ def _load():
         lib.oracle_knn_fullsort_metric.restype = ctypes.c_int
         lib.oracle_cosdist.argtypes = [fp, fp, ctypes.c_int32]
         lib.oracle_cosdist.restype = ctypes.c_double
+        lib.oracle_l1dist.argtypes = [fp, fp, ctypes.c_int32]
+        lib.oracle_l1dist.restype = ctypes.c_double
         lib.oracle_sqdist.argtypes = [fp, fp, ctypes.c_int32]
         lib.oracle_sqdist.restype = ctypes.c_double
         lib.oracle_sqdist_expanded.argtypes = [fp, fp, ctypes.c_int32]
@@ -109,7 +111,7 @@ def _run(fn, Q, X, k, rows, extra):
     return idx, dist, nxt
 
 
-METRICS = {"l2": 0, "cosine": 1}
+METRICS = {"l2": 0, "cosine": 1, "l1": 2}
 
 
 def knn(Q, X, k, rows=None, nthreads: int | None = None, metric: str = "l2"):
@@ -128,6 +130,13 @@ def cosdist(q, x) -> float:
     x = np.ascontiguousarray(x, dtype=np.float32).ravel()
     fp = ctypes.POINTER(ctypes.c_float)
     return float(_load().oracle_cosdist(q.ctypes.data_as(fp), x.ctypes.data_as(fp), q.shape[0]))
+
+
+def l1dist(q, x) -> float:
+    q = np.ascontiguousarray(q, dtype=np.float32).ravel()
+    x = np.ascontiguousarray(x, dtype=np.float32).ravel()
+    fp = ctypes.POINTER(ctypes.c_float)
+    return float(_load().oracle_l1dist(q.ctypes.data_as(fp), x.ctypes.data_as(fp), q.shape[0]))
 
 
 def sqdist(q, x) -> float:
@@ -157,7 +166,7 @@ def sqdist_pairs(Q, X, qi, xj, metric: str = "l2") -> np.ndarray:
     d = Q.shape[1]
     qb = Q.ctypes.data
     xb = X.ctypes.data
-    fn = lib.oracle_cosdist if metric == "cosine" else lib.oracle_sqdist
+    fn = {"cosine": lib.oracle_cosdist, "l1": lib.oracle_l1dist}.get(metric, lib.oracle_sqdist)
     for p in range(qi.shape[0]):
         out[p] = fn(ctypes.cast(qb + 4 * d * int(qi[p]), fp),
                                    ctypes.cast(xb + 4 * d * int(xj[p]), fp), d)

@@ -37,6 +37,11 @@
  * Pins: numpy brute force, orthogonal and antipodal closed forms, exact invariance under
  * power-of-two scaling, agreement with the Euclidean oracle on unit-normalised data.
  *
+ * Third metric (the L1 rows of the same table):
+ *     M[i][j] = sum_t |q_it - x_jt|, fp64, ascending t.
+ * Pins: numpy brute force (exact on integer grids), the integer line (distance |i - j|),
+ * scipy's cityblock cdist, the norm inequalities L2 <= L1 <= sqrt(d) L2.
+ *
  * Build: gcc -O2 -fopenmp -shared -fPIC (no -ffast-math, no FMA contraction).
  */
 #include <math.h>
@@ -108,12 +113,23 @@ double oracle_cosdist(const float *q, const float *x, int32_t d)
     return c < 0.0 ? 0.0 : c;
 }
 
+/* L1 (Manhattan) distance of one pair, fp64, ascending t. */
+double oracle_l1dist(const float *q, const float *x, int32_t d)
+{
+    double acc = 0.0;
+    for (int32_t t = 0; t < d; ++t) acc += fabs((double)q[t] - (double)x[t]);
+    return acc;
+}
+
 #define ORACLE_METRIC_L2SQ 0
 #define ORACLE_METRIC_COSINE 1
+#define ORACLE_METRIC_L1 2
 
 static double pair_distance(const float *q, const float *x, int32_t d, int32_t metric)
 {
-    return metric == ORACLE_METRIC_COSINE ? oracle_cosdist(q, x, d) : oracle_sqdist(q, x, d);
+    if (metric == ORACLE_METRIC_COSINE) return oracle_cosdist(q, x, d);
+    if (metric == ORACLE_METRIC_L1) return oracle_l1dist(q, x, d);
+    return oracle_sqdist(q, x, d);
 }
 
 /* Max-heap on (distance, index): the root is the entry that comes LAST. */

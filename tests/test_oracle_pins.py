@@ -254,3 +254,48 @@ def test_cosine_matches_euclidean_on_unit_vectors(oracle):
     assert np.array_equal(c_idx, e_idx)  # continuous data: no ties at this resolution
     np.testing.assert_allclose(2.0 * c_dist, e_dist, rtol=0, atol=1e-6)  # fp32 normalisation error
     assert np.all(np.diff(c_dist, axis=1) >= 0)
+
+
+# ---------------------------------------------------------------------------------------
+# L1 metric (the L1 rows of the paper's kNN table)
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("seed,m,n,d", [(30, 6, 40, 1), (31, 5, 64, 3), (32, 4, 33, 20)])
+def test_l1_bruteforce_every_k(oracle, seed, m, n, d):
+    Q, X = W.random_case(seed, m, n, d, kind="grid")  # integers: every sum is exact
+    M = np.abs(Q.astype(np.float64)[:, None, :] - X.astype(np.float64)[None, :, :]).sum(axis=2)
+    for k in range(1, n + 1):
+        order = np.argsort(M, axis=1, kind="stable")[:, :k]
+        for fn in (oracle.knn, oracle.knn_fullsort):
+            idx, dist, nxt = fn(Q, X, k, metric="l1")
+            assert np.array_equal(idx, order)
+            assert np.array_equal(dist, np.take_along_axis(M, order, axis=1))
+            if k < n:
+                assert np.array_equal(nxt, np.sort(M, axis=1)[:, k])
+
+
+def test_l1_integer_line_and_scipy(oracle):
+    from scipy.spatial.distance import cdist
+    n = 31
+    X = np.arange(n, dtype=np.float32).reshape(n, 1)
+    idx, dist, _ = oracle.knn(X, X, 5, metric="l1")
+    for i in range(n):
+        want = sorted((abs(i - j), j) for j in range(n))[:5]
+        assert idx[i].tolist() == [j for _, j in want]
+        assert dist[i].tolist() == [float(v) for v, _ in want]
+    Q, X = W.random_case(33, 40, 700, 9)
+    M = cdist(Q.astype(np.float64), X.astype(np.float64), metric="cityblock")
+    order = np.argsort(M, axis=1, kind="stable")[:, :12]
+    idx, dist, _ = oracle.knn(Q, X, 12, metric="l1")
+    assert np.array_equal(idx, order)
+    np.testing.assert_allclose(dist, np.take_along_axis(M, order, 1), rtol=1e-13)
+    assert oracle.l1dist([1, -2, 3], [4, 6, 3]) == 11.0
+
+
+def test_l1_norm_inequalities(oracle):
+    # ||v||_2 <= ||v||_1 <= sqrt(d) ||v||_2 for every pair
+    Q, X = W.random_case(34, 10, 50, 7)
+    for i in range(10):
+        for j in range(50):
+            l1 = oracle.l1dist(Q[i], X[j])
+            l2 = np.sqrt(oracle.sqdist(Q[i], X[j]))
+            assert l2 <= l1 * (1 + 1e-12) and l1 <= np.sqrt(7) * l2 * (1 + 1e-12)
