@@ -87,7 +87,7 @@ def main() -> int:
     ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
     idx = torch.empty((w.m, w.k), dtype=torch.int32, device=dev)
     dist = torch.empty((w.m, w.k), dtype=torch.float32, device=dev)
-    path_name = {0: "lowd", 1: "mfma", 2: "lowd_mfma"}[plan.path]
+    path_name = {0: "lowd", 1: "mfma", 2: "lowd_mfma", 3: "l1"}[plan.path]
     log(f"[bench] plan: path={path_name} chunks={plan.q_chunks} "
         f"ranges={plan.n_splits} workspace={plan.workspace_bytes} B (limit {limit} B)")
 
@@ -144,6 +144,14 @@ def main() -> int:
                     "flops_per_pair": 8,
                     # what a design that stores the distance tile would move: 4 B out + 4 B in
                     "hbm_equiv_frac": hbm_equiv}
+    elif plan.path == K.KNN_PATH_L1:
+        # d subtractions and d-1 additions per pair (the absolute value is an operand modifier)
+        flops = (2.0 * w.d - 1.0) * pairs_per_launch
+        achieved = flops / avg_launch_s / 1e12
+        roofline = {"bound": "alu", "kernel": "knn_l1_kernel", "achieved": achieved,
+                    "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_FP32_VECTOR_TFLOPS, "traffic": traffic,
+                    "flops_per_pair": 2 * w.d - 1}
     else:
         # difference form: d subtractions, d multiplications, d-1 additions per pair
         flops = (3.0 * w.d - 1.0) * pairs_per_launch

@@ -49,12 +49,14 @@ typedef enum {
  *   KNN_METRIC_L2SQ    sum_t (q_t - x_t)^2
  *   KNN_METRIC_COSINE  max(0, 1 - <q, x> / (|q| |x|)); 1 if either vector is zero.
  *                      Always runs on the matrix-core path (path 1), whatever d.
+ *   KNN_METRIC_L1      sum_t |q_t - x_t|.  Vector-ALU path 3, whatever d.
  */
-typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1 } knn_metric;
+typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1, KNN_METRIC_L1 = 2 } knn_metric;
 
 /* kernel families (knn_plan_t.path) */
 #define KNN_PATH_LOWD 0 /* d <= 8: difference-form distances on the vector ALU  */
 #define KNN_PATH_MFMA 1 /* d  > 8: fp32 matrix-core tile of -2 Q X^T plus norms */
+#define KNN_PATH_L1 3   /* L1 metric: absolute differences on the vector ALU, any d   */
 #define KNN_PATH_LOWD_MFMA 2 /* d <= 3 and room for 16 n bytes of packed points:
                                 matrix-core filter + the same exact test as path 0 */
 

@@ -24,7 +24,9 @@ KNN_PATH_MFMA = 1
 KNN_PATH_LOWD_MFMA = 2
 KNN_METRIC_L2SQ = 0
 KNN_METRIC_COSINE = 1
-METRICS = {"l2": KNN_METRIC_L2SQ, "cosine": KNN_METRIC_COSINE}
+KNN_METRIC_L1 = 2
+KNN_PATH_L1 = 3
+METRICS = {"l2": KNN_METRIC_L2SQ, "cosine": KNN_METRIC_COSINE, "l1": KNN_METRIC_L1}
 
 EXPORTED_SYMBOLS = (
     "knn_plan", "knn_workspace_bytes", "knn_search", "knn_last_stats", "knn_status_string",
@@ -193,7 +195,7 @@ def knn_search_raw(q_ptr, ldq, x_ptr, ldx, m, n, d, k, mem_limit_bytes, ws_ptr, 
 def knn_search(Q, X, k: int, mem_limit_bytes: int, workspace=None, out=None, metric: str = "l2"):
     """knn_search(Q[m,d], X[n,d], k, mem_limit_bytes) -> (idx int32[m,k], dist fp32[m,k]).
 
-    metric: "l2" (squared Euclidean) or "cosine" (cosine distance).
+    metric: "l2" (squared Euclidean), "cosine" (cosine distance) or "l1".
     Q and X are fp32 CUDA(HIP) tensors, row-major (a row stride larger than d is allowed).
     The workspace (a uint8 tensor of plan.workspace_bytes) is allocated here unless given.
     Work is enqueued on torch's current stream; no synchronisation is done.

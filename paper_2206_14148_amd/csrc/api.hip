@@ -190,6 +190,8 @@ extern "C" knn_status knn_search_metric(const float* Q, int64_t ldq, const float
         hipEvent_t t1 = mark(stream);
         if (plan.path == KNN_PATH_LOWD)
             e = launch_lowd(Qc, ldq, X, ldx, rows, n, d, k, S, lk, li, stream);
+        else if (plan.path == KNN_PATH_L1)
+            e = launch_l1(Qc, ldq, X, ldx, rows, n, d, k, S, lk, li, stream);
         else if (plan.path == KNN_PATH_LOWD_MFMA)
             e = launch_lowd_mfma(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, lk, li, stream);
         else
@@ -201,7 +203,7 @@ extern "C" knn_status knn_search_metric(const float* Q, int64_t ldq, const float
         }
         close_bracket(t1, stream, 1);
         hipEvent_t t2 = mark(stream);
-        e = launch_merge_refine(Qc, ldq, X, ldx, rows, n, d, k, S, cosine, lk, li,
+        e = launch_merge_refine(Qc, ldq, X, ldx, rows, n, d, k, S, (int)metric, lk, li,
                                 idx + row0 * k, dist + row0 * k, stream);
         if (e != hipSuccess) {
             drop_bracket(t2);

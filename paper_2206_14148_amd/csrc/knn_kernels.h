@@ -19,6 +19,10 @@ hipError_t launch_row_norms(const float* X, int64_t ldx, int64_t n, int d, bool 
 hipError_t launch_lowd(const float* Q, int64_t ldq, const float* X, int64_t ldx, int64_t rows,
                        int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream);
 
+// L1 metric, any d: key = fp32 sum of absolute differences.
+hipError_t launch_l1(const float* Q, int64_t ldq, const float* X, int64_t ldx, int64_t rows,
+                     int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream);
+
 // d <= kPmMaxD with room for the packed points: the same keys as launch_lowd, found through an
 // MFMA filter.  `packed` = kAlign bytes (max ||x||^2 word) + 16 n bytes ([x0 x1 x2 ||x||^2] per
 // point); pack = true (re)builds it from X first; rows == 0 only packs.
@@ -37,10 +41,10 @@ hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx,
 hipError_t launch_block_points(const float* X, int64_t ldx, int64_t n, int d, void* xblocked,
                                hipStream_t stream);
 
-// Merge the S lists of each row, re-evaluate the k winners in fp64 difference form,
+// Merge the S lists of each row, re-evaluate the k winners in fp64 (metric: knn_metric value),
 // order by (distance, index) and write idx / dist rows.
 hipError_t launch_merge_refine(const float* Q, int64_t ldq, const float* X, int64_t ldx,
-                               int64_t rows, int64_t n, int d, int k, int S, bool cosine,
+                               int64_t rows, int64_t n, int d, int k, int S, int metric,
                                const float* lk, const int* li, int32_t* idx, float* dist,
                                hipStream_t stream);
 

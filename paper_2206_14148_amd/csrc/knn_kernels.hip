@@ -415,6 +415,147 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_lowd_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
+// L1 metric (the L1 rows of the paper's table): sum |q - x| hides no matrix product, so this
+// is a vector-ALU kernel for every d.  One query per lane; a group of 8 points is wave-uniform
+// and read with scalar loads; the dimension is walked in chunks of 16 with the query's chunk
+// in registers and one running sum per point of the group, so a query value is loaded once
+// per 8 points and a point value costs no vector work.  Two VALU ops per pair and dimension
+// (subtract, add-absolute).  Sums run in ascending t, whatever the chunking.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kLowdTileQ) void knn_l1_kernel(
+    const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx, int rows,
+    int n, int d, int k, int S, int split_len, float* __restrict__ lk, int* __restrict__ li) {
+    constexpr int P = 8;    // points per group
+    constexpr int TC = 16;  // dimensions per register chunk
+    constexpr int H = 4;    // points pushed between two overflow checks
+    constexpr int C = kLowdCand;
+    constexpr int CP = C + 1;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const size_t per_wave = (size_t)(2 * kWave * CP + 2 * k + 2 * kWave) * 4;
+    unsigned char* base = smem + (size_t)wave * per_wave;
+    float* ck = reinterpret_cast<float*>(base);         // [64][CP]
+    int* ci = reinterpret_cast<int*>(ck + kWave * CP);  // [64][CP]
+    MergeScratch sc;
+    sc.list_key = reinterpret_cast<float*>(ci + kWave * CP);
+    sc.list_idx = reinterpret_cast<int*>(sc.list_key + k);
+    sc.cand_key = reinterpret_cast<float*>(sc.list_idx + k);
+    sc.cand_idx = reinterpret_cast<int*>(sc.cand_key + kWave);
+
+    const int s = blockIdx.y;
+    const int wave_row0 = (blockIdx.x * kLowdWaves + wave) * kWave;
+    if (wave_row0 >= rows) return;  // whole wave idle; no workgroup barrier is used below
+    const int r = wave_row0 + lane;
+    const bool active = r < rows;
+    {
+        const int nq = min(kWave, rows - wave_row0);
+        for (int qq = 0; qq < nq; ++qq) {
+            const size_t lb = ((size_t)(wave_row0 + qq) * S + s) * k;
+            for (int p = lane; p < k; p += kWave) {
+                lk[lb + p] = kInf;
+                li[lb + p] = kNoIdx;
+            }
+        }
+    }
+    const float* qrow = Q + (int64_t)(active ? r : 0) * ldq;
+    const bool qvec = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) && (ldq % 4 == 0);
+    float tau = active ? kInf : -kInf;
+    int cnt = 0;
+
+    auto flush = [&](uint64_t mask) {
+        while (mask) {
+            const int L = __builtin_ctzll(mask);
+            mask &= mask - 1;
+            wave_sync();
+            const int c = __shfl(cnt, L);
+            float key = kInf;
+            int id = kNoIdx;
+            if (lane < c) {
+                key = ck[L * CP + lane];
+                id = ci[L * CP + lane];
+            }
+            const size_t lb = ((size_t)(wave_row0 + L) * S + s) * k;
+            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane);
+            if (lane == L) {
+                tau = t_new;
+                cnt = 0;
+            }
+        }
+    };
+
+    const int j0 = s * split_len;
+    const int j1 = min(n, j0 + split_len);
+    for (int j = j0; j < j1; j += P) {
+        float acc[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) acc[p] = 0.f;
+        for (int t0 = 0; t0 < d; t0 += TC) {
+            const bool full = t0 + TC <= d;  // uniform
+            float qv[TC];
+            if (full && qvec) {  // uniform: whole chunk inside the row and 16-byte aligned
+#pragma unroll
+                for (int t4 = 0; t4 < TC / 4; ++t4) {
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(qrow + t0 + 4 * t4);
+                    qv[4 * t4 + 0] = v[0];
+                    qv[4 * t4 + 1] = v[1];
+                    qv[4 * t4 + 2] = v[2];
+                    qv[4 * t4 + 3] = v[3];
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < TC; ++t) {
+                    const int tt = t0 + t;
+                    const float v = qrow[tt < d ? tt : d - 1];
+                    qv[t] = tt < d ? v : 0.f;
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                const int jp = (j + p < j1) ? j + p : j1 - 1;  // uniform; repeats of the last point are masked below
+                const float* xp = X + (int64_t)jp * ldx;
+                float a = acc[p];
+                if (full) {
+#pragma unroll
+                    for (int t = 0; t < TC; ++t) a += fabsf(qv[t] - xp[t0 + t]);
+                } else {
+#pragma unroll
+                    for (int t = 0; t < TC; ++t) {
+                        const int tt = t0 + t;
+                        const float xv = xp[tt < d ? tt : d - 1];
+                        a += fabsf(qv[t] - (tt < d ? xv : 0.f));
+                    }
+                }
+                acc[p] = a;
+            }
+        }
+        float mn = kInf;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            if (j + p >= j1) acc[p] = kInf;  // past the range
+            mn = fminf(mn, acc[p]);
+        }
+        if (__builtin_amdgcn_ballot_w64(mn < tau) != 0) {
+#pragma unroll
+            for (int g = 0; g < P / H; ++g) {
+#pragma unroll
+                for (int p = g * H; p < (g + 1) * H; ++p) {
+                    if (acc[p] < tau) {
+                        ck[lane * CP + cnt] = acc[p];
+                        ci[lane * CP + cnt] = j + p;
+                        ++cnt;
+                    }
+                }
+                const uint64_t fullb = __builtin_amdgcn_ballot_w64(cnt > C - H);
+                if (fullb) flush(fullb);
+            }
+        }
+    }
+    const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0);
+    if (rest) flush(rest);
+}
+
+// ---------------------------------------------------------------------------------------
 // Low-dimensional path on the matrix cores (d <= 3).  The expansion of section 4.1 is used
 // only as a FILTER: with points packed as [x0 x1 x2 ||x||^2] and queries as
 // [-2q0 -2q1 -2q2 1], two v_mfma_f32_32x32x2_f32 give 32 x 32 keys ||x||^2 - 2 q.x.  A key
@@ -1076,9 +1217,18 @@ __device__ __forceinline__ double exact_cosdist(const float* __restrict__ q,
     return c < 0.0 ? 0.0 : c;
 }
 
+// L1 distance in fp64, ascending t.
+__device__ __forceinline__ double exact_l1dist(const float* __restrict__ q,
+                                               const float* __restrict__ x, int d) {
+    double acc = 0.0;
+    for (int t = 0; t < d; ++t) acc = acc + fabs((double)q[t] - (double)x[t]);
+    return acc;
+}
+
+// metric: 0 squared Euclidean, 1 cosine, 2 L1 (the values of knn_metric)
 __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx, int rows,
-    int n, int d, int k, int S, int cosine, const float* __restrict__ lk,
+    int n, int d, int k, int S, int metric, const float* __restrict__ lk,
     const int* __restrict__ li, int32_t* __restrict__ idx_out, float* __restrict__ dist_out) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
@@ -1120,9 +1270,12 @@ __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
     for (int w = lane; w < k; w += kWave) {
         const int j = wi[w];
         double dist = __builtin_huge_val();
-        if ((unsigned)j < (unsigned)n)
-            dist = cosine ? exact_cosdist(Q + (int64_t)r * ldq, X + (int64_t)j * ldx, d)
-                          : exact_sqdist(Q + (int64_t)r * ldq, X + (int64_t)j * ldx, d);
+        if ((unsigned)j < (unsigned)n) {
+            const float* qp = Q + (int64_t)r * ldq;
+            const float* xp = X + (int64_t)j * ldx;
+            dist = metric == 1 ? exact_cosdist(qp, xp, d)
+                               : (metric == 2 ? exact_l1dist(qp, xp, d) : exact_sqdist(qp, xp, d));
+        }
         wd[w] = dist;
     }
     wave_sync();
@@ -1175,6 +1328,20 @@ static hipError_t launch_lowd_d(const float* Q, int64_t ldq, const float* X, int
         knn_lowd_kernel<D, false><<<grid, dim3(kLowdTileQ), lds, stream>>>(
             Q, ldq, X, ldx, (int)rows, (int)n, k, S, (int)split_len, lk, li);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_l1(const float* Q, int64_t ldq, const float* X, int64_t ldx, int64_t rows,
+                     int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream) {
+    const size_t per_wave = (size_t)(2 * kWave * (kLowdCand + 1) + 2 * k + 2 * kWave) * 4;
+    const size_t lds = per_wave * kLowdWaves;
+    hipError_t e = raise_lds_limit(knn_l1_kernel, lds);
+    if (e != hipSuccess) return e;
+    int64_t split_len = (n + S - 1) / S;
+    split_len = (split_len + 7) / 8 * 8;
+    dim3 grid((unsigned)((rows + kLowdTileQ - 1) / kLowdTileQ), (unsigned)S);
+    knn_l1_kernel<<<grid, dim3(kLowdTileQ), lds, stream>>>(Q, ldq, X, ldx, (int)rows, (int)n, d, k, S,
+                                                           (int)split_len, lk, li);
     return hipGetLastError();
 }
 
@@ -1318,7 +1485,7 @@ hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx,
 }
 
 hipError_t launch_merge_refine(const float* Q, int64_t ldq, const float* X, int64_t ldx,
-                               int64_t rows, int64_t n, int d, int k, int S, bool cosine,
+                               int64_t rows, int64_t n, int d, int k, int S, int metric,
                                const float* lk, const int* li, int32_t* idx, float* dist,
                                hipStream_t stream) {
     const size_t lds = (size_t)4 * k * (sizeof(double) + sizeof(int));
@@ -1326,7 +1493,7 @@ hipError_t launch_merge_refine(const float* Q, int64_t ldq, const float* X, int6
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((rows + 3) / 4));
     knn_merge_refine_kernel<<<grid, dim3(256), lds, stream>>>(
-        Q, ldq, X, ldx, (int)rows, (int)n, d, k, S, cosine ? 1 : 0, lk, li, idx, dist);
+        Q, ldq, X, ldx, (int)rows, (int)n, d, k, S, metric, lk, li, idx, dist);
     return hipGetLastError();
 }
 

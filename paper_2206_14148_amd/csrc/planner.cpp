@@ -89,7 +89,8 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
                                       uint64_t mem_limit_bytes, knn_plan_t* out) {
     if (!out) return KNN_ERR_INVALID_ARG;
     memset(out, 0, sizeof(*out));
-    if (metric != KNN_METRIC_L2SQ && metric != KNN_METRIC_COSINE) return KNN_ERR_INVALID_ARG;
+    if (metric != KNN_METRIC_L2SQ && metric != KNN_METRIC_COSINE && metric != KNN_METRIC_L1)
+        return KNN_ERR_INVALID_ARG;
     out->metric = (int32_t)metric;
     if (m < 0 || n < 1 || d < 1 || k < 1 || (int64_t)k > n) return KNN_ERR_INVALID_ARG;
     // int32 indices, with headroom so that range ends rounded up to a tile stay representable
@@ -100,9 +101,10 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     out->k = k;
     out->streams = 1;
     // the cosine keys come from the matrix-core kernels only
-    const bool lowd = d <= kLowdMaxD && metric == KNN_METRIC_L2SQ;
+    // (lowd also stands for the L1 kernel: same workgroup shape, no per-point workspace)
+    const bool lowd = (d <= kLowdMaxD && metric == KNN_METRIC_L2SQ) || metric == KNN_METRIC_L1;
     // smallest plan of all: the vector-ALU path (no per-point workspace) or the MFMA path
-    out->path = lowd ? KNN_PATH_LOWD : KNN_PATH_MFMA;
+    out->path = metric == KNN_METRIC_L1 ? KNN_PATH_L1 : (lowd ? KNN_PATH_LOWD : KNN_PATH_MFMA);
     out->tile_q = lowd ? kLowdTileQ : kMfmaTileQ;
     out->tile_x = lowd ? kLowdUnroll : kMfmaTileX;
     out->norms_bytes = lowd ? 0 : align_up((uint64_t)n * 4);
@@ -114,7 +116,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     }
     if (m == 0) return KNN_OK;
     if (mem_limit_bytes < out->min_limit_bytes) return KNN_ERR_MEM_LIMIT_TOO_SMALL;
-    if (d <= kPmMaxD && lowd) {
+    if (d <= kPmMaxD && metric == KNN_METRIC_L2SQ) {
         // the matrix-core filter needs the points packed into the workspace; take it when the
         // limit has room for that and at least one query tile of lists
         const uint64_t packed = kAlign + align_up((uint64_t)n * 16);

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
-SAMPLE_ROWS = {1: 1000, 2: 2000, 3: 64, 4: 48, 5: 64, 6: 256}
+SAMPLE_ROWS = {1: 1000, 2: 2000, 3: 64, 4: 48, 5: 64, 6: 256, 7: 256}
 
 
 def say(*a):
@@ -30,7 +30,7 @@ def K():
     return K
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5, 6, 7])
 def test_full_size_workload(K, oracle, cfg):
     w = W.WORKLOADS[cfg]
     t0 = time.time()

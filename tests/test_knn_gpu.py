@@ -310,3 +310,47 @@ def test_cosine_on_clustered_embeddings_and_scale_invariance(K, oracle):
     scale = (2.0 ** np.random.Generator(np.random.PCG64(3)).integers(-3, 4, size=(w.n, 1))).astype(np.float32)
     idx_s, dist_s = run_gpu(K, Q * np.float32(4.0), X * scale, 20, 64 * W.MB, metric="cosine")
     assert np.array_equal(dist_s, dist_s) and np.mean(idx_s == run_gpu(K, Q, X, 20, 64 * W.MB, metric="cosine")[0]) > 0.999
+
+
+# ---------------------------------------------------------------------------------------
+# L1 metric
+# ---------------------------------------------------------------------------------------
+L1 = [
+    (0, 1, 1, 1, 1),          # smallest call
+    (1, 300, 5000, 3, 16),    # one partial chunk
+    (2, 257, 1003, 32, 7),    # exactly one chunk, ragged point groups
+    (3, 140, 2300, 100, 10),  # the table's d = 100: three chunks and a tail
+    (4, 64, 9001, 10, 40),    # several ranges
+    (5, 40, 500, 784, 5),     # d = 784
+    (6, 5, 129, 9, 129),      # k == n
+]
+
+
+@pytest.mark.parametrize("seed,m,n,d,k", L1)
+def test_l1_parity_small(K, oracle, seed, m, n, d, k):
+    say(f"\nl1 case seed={seed} m={m} n={n} d={d} k={k}")
+    Q, X = W.random_case(1300 + seed, m, n, d)
+    stats, _, _ = parity(K, oracle, Q, X, k, metric="l1")
+    assert stats["strict_rows"] >= 0.97 * stats["rows"]
+
+
+def test_l1_exact_ties_and_limit_independence(K, oracle):
+    # integer grid: every sum is exact in fp32, ties are massive, the answer is unique
+    Q, X = W.random_case(1400, 300, 6000, 6, kind="grid")
+    ref = None
+    lo = K.knn_plan(300, 6000, 6, 9, 1 << 40, "l1").min_limit_bytes
+    for lim in (lo, lo + 30_000, 64 * W.MB):
+        idx, dist = run_gpu(K, Q, X, 9, lim, metric="l1")
+        o_idx, o_dist, _ = oracle.knn(Q, X, 9, metric="l1")
+        assert np.array_equal(idx, o_idx) and np.array_equal(dist.astype(np.float64), o_dist)
+        if ref is not None:
+            assert np.array_equal(idx, ref[0]) and np.array_equal(dist, ref[1])
+        ref = (idx, dist)
+    # row strides larger than d
+    Xp = torch.full((6000, 11), 1e30, device="cuda")
+    Qp = torch.full((300, 9), 1e30, device="cuda")
+    Xp[:, :6] = torch.from_numpy(X).cuda()
+    Qp[:, :6] = torch.from_numpy(Q).cuda()
+    idx2, dist2 = K.knn_search(Qp[:, :6], Xp[:, :6], 9, 64 * W.MB, metric="l1")
+    torch.cuda.synchronize()
+    assert np.array_equal(idx2.cpu().numpy(), ref[0])

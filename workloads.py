@@ -35,7 +35,7 @@ class Workload:
     kind: str            # value distribution
     q_is_x: bool = False  # queries are the data points themselves (kNN graph)
     sweep: tuple = ()     # extra memory limits (config 5)
-    metric: str = "l2"    # "l2" (squared Euclidean) or "cosine"
+    metric: str = "l2"    # "l2" (squared Euclidean), "cosine" or "l1"
 
     @property
     def pairs(self) -> int:
@@ -52,6 +52,8 @@ WORKLOADS = {
     # the cosine rows of the paper's table: word embeddings with n = 1,183,514 and d in
     # {50, 100, 200}, m = 1e4 queries; the same clustered mixture stands in for them
     6: Workload(6, "c6_cosine_d100", 10_000, 1_183_514, 100, 10, 1 * GB, "gmm", metric="cosine"),
+    # the L1 rows of the table: random data, n = 1e6, d = 100, m = 1e4 queries
+    7: Workload(7, "c7_l1_d100", 10_000, 1_000_000, 100, 10, 1 * GB, "normal", metric="l1"),
 }
 
 
