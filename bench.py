@@ -33,6 +33,8 @@ MEASURED_TRAFFIC_BYTES = {
     "c3_imagelike_d784": 359.0e9,   # knn_mfma_kernel: 359.0 GB fetched + 0.07 GB written
     "c4_clustered_d128": 3455.6e9,  # knn_mfma_qreg_kernel: 3443.4 GB fetched + 12.2 GB written
     "c5_memsweep_d256": 600.0e9,    # knn_mfma_qreg_kernel: 598.9 GB fetched + 1.09 GB written
+    "c6_cosine_d100": 25.05e9,      # knn_mfma_qreg_kernel: 24.99 GB fetched + 0.06 GB written
+    "c7_l1_d100": 11.79e9,          # knn_l1_kernel: 11.37 GB fetched + 0.43 GB written
 }
 
 
