@@ -59,6 +59,10 @@ def _load():
         lib.oracle_sqdist.restype = ctypes.c_double
         lib.oracle_sqdist_expanded.argtypes = [fp, fp, ctypes.c_int32]
         lib.oracle_sqdist_expanded.restype = ctypes.c_double
+        lib.oracle_kmv.argtypes = [fp, ctypes.c_int64, fp, ctypes.c_int64, fp, ctypes.c_int64,
+                                   ctypes.c_int64, ctypes.c_int32, ctypes.c_double, ctypes.c_double,
+                                   i64p, ctypes.c_int64, dp, ctypes.c_int32]
+        lib.oracle_kmv.restype = ctypes.c_int
         lib.oracle_threads_used.argtypes = [ctypes.c_int32]
         lib.oracle_threads_used.restype = ctypes.c_int32
         _lib = lib
@@ -171,3 +175,29 @@ def sqdist_pairs(Q, X, qi, xj, metric: str = "l2") -> np.ndarray:
         out[p] = fn(ctypes.cast(qb + 4 * d * int(qi[p]), fp),
                                    ctypes.cast(xb + 4 * d * int(xj[p]), fp), d)
     return out
+
+
+def kmv(X, Z, v, variance: float, lengthscale: float, rows=None, nthreads: int | None = None):
+    """y = K(X, Z) v for the squared-exponential kernel, fp64 (paper section 5.1)."""
+    X = _as_f32_2d(X)
+    Z = _as_f32_2d(Z)
+    v = np.ascontiguousarray(v, dtype=np.float32).ravel()
+    if X.shape[1] != Z.shape[1] or v.shape[0] != Z.shape[0]:
+        raise ValueError("shape mismatch")
+    if rows is None:
+        rows_arr, nrows = None, X.shape[0]
+    else:
+        rows_arr = np.ascontiguousarray(rows, dtype=np.int64)
+        nrows = rows_arr.shape[0]
+    y = np.empty(nrows, dtype=np.float64)
+    fp = ctypes.POINTER(ctypes.c_float)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    rc = _load().oracle_kmv(X.ctypes.data_as(fp), X.shape[1], Z.ctypes.data_as(fp), Z.shape[1],
+                            v.ctypes.data_as(fp), X.shape[0], Z.shape[0], X.shape[1],
+                            float(variance), float(lengthscale),
+                            rows_arr.ctypes.data_as(i64p) if rows_arr is not None else None, nrows,
+                            y.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                            int(nthreads or default_threads()))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return y

@@ -42,6 +42,12 @@
  * Pins: numpy brute force (exact on integer grids), the integer line (distance |i - j|),
  * scipy's cityblock cdist, the norm inequalities L2 <= L1 <= sqrt(d) L2.
  *
+ * Kernel matrix-vector product (paper section 5.1 and the appendix):
+ *     y_i = sum_j k(x_i, z_j) v_j,   k(x, z) = variance * exp(-0.5 |x - z|^2 / lengthscale^2),
+ * the squared-exponential kernel, distances in the difference form above, everything in
+ * fp64, j ascending.  Pins: dense numpy K @ v, closed forms (one point, two points at a
+ * known distance, huge lengthscale), symmetry v'(Kw) = w'(Kv), linearity in v.
+ *
  * Build: gcc -O2 -fopenmp -shared -fPIC (no -ffast-math, no FMA contraction).
  */
 #include <math.h>
@@ -270,6 +276,30 @@ int oracle_knn_fullsort(const float *Q, int64_t ldq, const float *X, int64_t ldx
 {
     return oracle_knn_fullsort_metric(Q, ldq, X, ldx, n, d, k, rows, nrows, idx, dist, next_dist,
                                       ORACLE_METRIC_L2SQ);
+}
+
+/*
+ * oracle_kmv: y[i] = sum_j variance * exp(-0.5 * |X[i] - Z[j]|^2 / lengthscale^2) * v[j].
+ * X [n, d], Z [m, d] fp32 row-major (leading dimensions in elements), v [m] fp32, y [n] fp64.
+ * rows == NULL: all n rows; else y has nrows entries for the listed rows.
+ */
+int oracle_kmv(const float *X, int64_t ldx, const float *Z, int64_t ldz, const float *v,
+               int64_t n, int64_t m, int32_t d, double variance, double lengthscale,
+               const int64_t *rows, int64_t nrows, double *y, int32_t nthreads)
+{
+    if (!X || !Z || !v || !y || n < 0 || m < 0 || d < 1 || ldx < d || ldz < d || !(lengthscale > 0.0))
+        return -1;
+    if (nthreads < 1) nthreads = 1;
+    const double inv = -0.5 / (lengthscale * lengthscale);
+#pragma omp parallel for num_threads(nthreads) schedule(dynamic, 4)
+    for (int64_t r = 0; r < nrows; ++r) {
+        int64_t i = rows ? rows[r] : r;
+        double acc = 0.0;
+        for (int64_t j = 0; j < m; ++j)
+            acc += variance * exp(inv * oracle_sqdist(X + i * ldx, Z + j * ldz, d)) * (double)v[j];
+        y[r] = acc;
+    }
+    return 0;
 }
 
 /* Number of threads an OpenMP region of the requested width really gets. */
