@@ -35,6 +35,8 @@ MEASURED_TRAFFIC_BYTES = {
     "c5_memsweep_d256": 600.0e9,    # knn_mfma_qreg_kernel: 598.9 GB fetched + 1.09 GB written
     "c6_cosine_d100": 25.05e9,      # knn_mfma_qreg_kernel: 24.99 GB fetched + 0.06 GB written
     "c7_l1_d100": 11.79e9,          # knn_l1_kernel: 11.37 GB fetched + 0.43 GB written
+    "kmv1_d1": 1.84e9,              # kmv_lowd_kernel: 1.83 GB fetched + 0.01 GB written
+    "kmv2_d32": 1.58e9,             # kmv_mfma_kernel: 1.58 GB fetched + 0.002 GB written
 }
 
 
@@ -42,12 +44,133 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def bench_kmv(args) -> int:
+    """--workload kmv1 / kmv2: one step = one kmv_apply call (y = K v, squared-exponential K)."""
+    import numpy as np
+    import torch
+
+    import paper_2206_14148_amd as K
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    K.load()
+    w = W.scaled_kmv(args.workload, n=args.n, m=args.m) if (args.n or args.m) \
+        else W.KMV_WORKLOADS[args.workload]
+    limit = K.knn_parse_size(args.mem_limit) if args.mem_limit else w.mem_limit
+    t0 = time.time()
+    X, Z, v = W.make_kmv(w)
+    log(f"[bench] inputs {w.name}: n={w.n} m={w.m} d={w.d} generated in {time.time()-t0:.1f}s")
+    dev = torch.device("cuda:0")
+    Xd = torch.from_numpy(X).to(dev)
+    Zd = Xd if w.z_is_x else torch.from_numpy(Z).to(dev)
+    vd = torch.from_numpy(v).to(dev)
+    plan = K.kmv_plan(w.n, w.m, w.d, limit)
+    assert plan.workspace_bytes <= limit
+    ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
+    y = torch.empty((w.n,), dtype=torch.float64, device=dev)
+    path_name = {0: "lowd", 1: "mfma"}[plan.path]
+    log(f"[bench] plan: path={path_name} ranges={plan.n_splits} workspace={plan.workspace_bytes} B "
+        f"(limit {limit} B)")
+
+    def step():
+        K.kmv_apply(Xd, Zd, vd, w.variance, w.lengthscale, limit, workspace=ws, out=y)
+
+    if args.calibrate_copy_mb > 0:
+        src = torch.ones(args.calibrate_copy_mb * 250_000, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)  # one elementwise kernel: reads and writes calibrate_copy_mb MB
+        torch.cuda.synchronize()
+        del src, dst
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # kmv_apply launches on torch's current stream, so events recorded there bracket its kernels
+    marks = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+             for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for b, e in marks:
+        b.record()
+        step()
+        e.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    call_ms = sum(b.elapsed_time(e) for b, e in marks) / args.steps
+    ms_per_step = elapsed * 1e3 / args.steps
+    pairs = float(w.n) * float(w.m)
+    value = pairs * args.steps / elapsed
+    log(f"[bench] {ms_per_step:.2f} ms/step, {value:.3e} pairs/s; kernels per call {call_ms:.3f} ms")
+    rate = pairs / (call_ms * 1e-3)
+    if plan.path == K.KMV_PATH_LOWD:
+        # per pair: d subtractions, d multiplications, d-1 additions, the scaling, exp2, and
+        # the multiply-add with v
+        fpp = 3 * w.d + 3
+        # issue slots per pair on a 16-lane SIMD: 2d + 2 full-rate operations and one
+        # half-rate exp2 (measured on this chip: 4 and 8 cycles per wave instruction)
+        slots = 2 * w.d + 2 + 2
+        roofline = {"bound": "alu", "kernel": "kmv_lowd_kernel", "achieved": rate * fpp / 1e12,
+                    "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+                    "frac": rate * fpp / 1e12 / PEAK_FP32_VECTOR_TFLOPS, "traffic": None,
+                    "flops_per_pair": fpp,
+                    "issue_frac": rate * slots / (256 * 4 * 16 * 2.4e9)}
+    else:
+        fpp = 2 * w.d
+        roofline = {"bound": "mfma", "kernel": "kmv_mfma_kernel", "achieved": rate * fpp / 1e12,
+                    "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
+                    "frac": rate * fpp / 1e12 / PEAK_FP32_MATRIX_TFLOPS, "traffic": None,
+                    "flops_per_pair": fpp}
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(w.name)
+    roofline["avg_launch_ms"] = call_ms
+
+    cpu_baseline = None
+    parity = None
+    if args.cpu_seconds > 0:
+        import oracle
+
+        threads = oracle.threads_used()
+        rng = np.random.Generator(np.random.PCG64(11))
+        probe = np.sort(rng.choice(w.n, size=min(w.n, 4 * threads), replace=False))
+        t0 = time.perf_counter()
+        oracle.kmv(X, Z, v, w.variance, w.lengthscale, rows=probe)
+        probe_rate = len(probe) / max(time.perf_counter() - t0, 1e-6)
+        nrows = int(max(len(probe), min(w.n, probe_rate * args.cpu_seconds)))
+        rows = np.sort(rng.choice(w.n, size=nrows, replace=False))
+        t0 = time.perf_counter()
+        ref = oracle.kmv(X, Z, v, w.variance, w.lengthscale, rows=rows)
+        dt = time.perf_counter() - t0
+        cpu_baseline = {"value": len(rows) * float(w.m) / dt, "unit": "pairs/s", "cores": threads,
+                        "kind": "oracle",
+                        "sample": f"{len(rows)} seeded rows of K x all {w.m} points of {w.name}, {dt:.1f} s"}
+        got = y[torch.from_numpy(rows).to(dev)].cpu().numpy()
+        mag = oracle.kmv(X, Z, np.abs(v), w.variance, w.lengthscale, rows=rows)
+        rel = float((np.abs(got - ref) / np.maximum(mag, 1e-300)).max())
+        parity = {"rows": len(rows), "max_abs_err_over_sum_of_magnitudes": rel}
+        log(f"[bench] oracle: {cpu_baseline['value']:.3e} pairs/s on {threads} threads; parity {parity}")
+
+    out = {
+        "metric": "kernel-matrix entries per second, y = K v with a squared-exponential kernel (n*m/s)",
+        "value": value, "unit": "pairs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "m": w.m, "d": w.d, "variance": w.variance,
+                   "lengthscale": w.lengthscale, "mem_limit_bytes": limit,
+                   "workspace_bytes": plan.workspace_bytes, "point_ranges": plan.n_splits,
+                   "path": path_name},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c2", help="c1..c6 (default c2, the metric's workload; c6 is the cosine one)")
+    ap.add_argument("--workload", default="c2", help="c1..c7 (default c2, the metric's workload; c6 cosine, c7 L1), or kmv1 / kmv2: "
+                         "the kernel matrix-vector product")
     ap.add_argument("--mem-limit", default=None, help="e.g. 128MB, 1GB (decimal); default: the workload's")
     ap.add_argument("--m", type=int, default=None, help="override the query count (testing)")
     ap.add_argument("--n", type=int, default=None, help="override the point count (testing)")
@@ -61,6 +184,9 @@ def main() -> int:
         print("bench.py: this build is single-GPU; run with --gpus 1 "
               "(sharding over GPUs is described in DESIGN.md, not built)", file=sys.stderr)
         return 2
+
+    if args.workload.startswith("kmv"):
+        return bench_kmv(args)
 
     import numpy as np
     import torch

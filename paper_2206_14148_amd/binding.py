@@ -32,7 +32,34 @@ EXPORTED_SYMBOLS = (
     "knn_plan", "knn_workspace_bytes", "knn_search", "knn_last_stats", "knn_status_string",
     "knn_parse_size", "knn_chunk_rows", "knn_last_hip_error", "knn_profile_enable",
     "knn_profile_read", "knn_plan_metric", "knn_search_metric",
+    "kmv_plan", "kmv_apply",
 )
+KMV_PATH_LOWD = 0
+KMV_PATH_MFMA = 1
+
+
+class KmvPlanStruct(ctypes.Structure):
+    _fields_ = [
+        ("n", ctypes.c_int64), ("m", ctypes.c_int64),
+        ("d", ctypes.c_int32), ("path", ctypes.c_int32),
+        ("tile_rows", ctypes.c_int32), ("n_splits", ctypes.c_int32),
+        ("norms_bytes", ctypes.c_int64), ("partials_bytes", ctypes.c_int64),
+        ("workspace_bytes", ctypes.c_int64), ("min_limit_bytes", ctypes.c_int64),
+    ]
+
+
+@dataclass(frozen=True)
+class KmvPlan:
+    n: int
+    m: int
+    d: int
+    path: int
+    tile_rows: int
+    n_splits: int
+    norms_bytes: int
+    partials_bytes: int
+    workspace_bytes: int
+    min_limit_bytes: int
 
 
 class PlanStruct(ctypes.Structure):
@@ -118,6 +145,11 @@ def load():
     lib.knn_profile_read.restype = ctypes.c_int
     lib.knn_last_hip_error.argtypes = []
     lib.knn_last_hip_error.restype = ctypes.c_char_p
+    lib.kmv_plan.argtypes = [i64, i64, i32, i64, ctypes.POINTER(KmvPlanStruct)]
+    lib.kmv_plan.restype = ctypes.c_int
+    lib.kmv_apply.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, ctypes.c_double, ctypes.c_double,
+                              i64, vp, i64, vp, vp]
+    lib.kmv_apply.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -231,3 +263,60 @@ def knn_search(Q, X, k: int, mem_limit_bytes: int, workspace=None, out=None, met
             detail += " (" + load().knn_last_hip_error().decode() + ")"
         raise KnnError(st, detail)
     return idx, dist
+
+
+def kmv_plan(n: int, m: int, d: int, mem_limit_bytes: int) -> KmvPlan:
+    ps = KmvPlanStruct()
+    st = int(load().kmv_plan(n, m, d, mem_limit_bytes, ctypes.byref(ps)))
+    if st != KNN_OK:
+        raise KnnError(st, knn_status_string(st) + f" (needs at least {ps.min_limit_bytes} bytes)"
+                       if st == KNN_ERR_MEM_LIMIT_TOO_SMALL else knn_status_string(st))
+    return KmvPlan(*(getattr(ps, f[0]) for f in KmvPlanStruct._fields_))
+
+
+def kmv_apply_raw(x_ptr, ldx, z_ptr, ldz, v_ptr, n, m, d, variance, lengthscale, mem_limit_bytes,
+                  ws_ptr, ws_bytes, y_ptr, stream_ptr) -> int:
+    """Direct call, raw integers for pointers; returns the status code."""
+    return int(load().kmv_apply(x_ptr, ldx, z_ptr, ldz, v_ptr, n, m, d, float(variance),
+                                float(lengthscale), mem_limit_bytes, ws_ptr, ws_bytes, y_ptr,
+                                stream_ptr))
+
+
+def kmv_apply(X, Z, v, variance: float, lengthscale: float, mem_limit_bytes: int, workspace=None,
+              out=None):
+    """kmv_apply(X[n,d], Z[m,d], v[m], variance, lengthscale, mem_limit_bytes) -> y fp64[n].
+
+    y = K(X, Z) v with the squared-exponential kernel.  X, Z, v are fp32 device tensors (rows
+    may be strided).  The workspace (uint8, plan.workspace_bytes) is allocated here unless
+    given.  Work is enqueued on torch's current stream; no synchronisation is done.
+    """
+    import torch
+
+    if not (X.is_cuda and Z.is_cuda and v.is_cuda):
+        raise KnnError(KNN_ERR_INVALID_ARG, "X, Z and v must be device tensors (no CPU path exists)")
+    if X.dtype != torch.float32 or Z.dtype != torch.float32 or v.dtype != torch.float32:
+        raise KnnError(KNN_ERR_INVALID_ARG, "X, Z and v must be float32")
+    if X.dim() != 2 or Z.dim() != 2 or v.dim() != 1 or X.shape[1] != Z.shape[1]:
+        raise KnnError(KNN_ERR_INVALID_ARG, "X and Z must be 2-D with the same d, v 1-D")
+    if v.shape[0] != Z.shape[0] or X.stride(1) != 1 or Z.stride(1) != 1 or \
+            (v.shape[0] > 1 and v.stride(0) != 1):
+        raise KnnError(KNN_ERR_INVALID_ARG, "v must have m contiguous entries; unit column strides")
+    n, d = X.shape
+    m = Z.shape[0]
+    plan = kmv_plan(n, m, d, mem_limit_bytes)
+    if workspace is None:
+        workspace = torch.empty(max(int(plan.workspace_bytes), 256), dtype=torch.uint8,
+                                device=X.device)
+    y = out if out is not None else torch.empty((n,), dtype=torch.float64, device=X.device)
+    stream = torch.cuda.current_stream(X.device).cuda_stream
+    ldx = X.stride(0) if n > 1 else max(d, X.stride(0))
+    ldz = Z.stride(0) if m > 1 else max(d, Z.stride(0))
+    st = kmv_apply_raw(X.data_ptr(), ldx, Z.data_ptr(), ldz, v.data_ptr(), n, m, d, variance,
+                       lengthscale, mem_limit_bytes, workspace.data_ptr(), workspace.numel(),
+                       y.data_ptr(), stream)
+    if st != KNN_OK:
+        detail = knn_status_string(st)
+        if st == KNN_ERR_HIP:
+            detail += " (" + load().knn_last_hip_error().decode() + ")"
+        raise KnnError(st, detail)
+    return y

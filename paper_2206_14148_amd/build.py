@@ -3,12 +3,26 @@ from __future__ import annotations
 
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
+OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libknn_mi355x.so")
-SOURCES = ["planner.cpp", "api.hip", "knn_kernels.hip"]
-HEADERS = ["knn_config.h", "knn_kernels.h", os.path.join("..", "..", "include", "knn.h")]
+SOURCES = ["planner.cpp", "api.hip", "knn_lowd.hip", "knn_mfma.hip", "knn_refine.hip",
+           "kmv_api.hip", "kmv_kernels.hip"]
+HEADERS = ["knn_config.h", "knn_device.h", "knn_kernels.h", "kmv_kernels.h",
+           os.path.join("..", "..", "include", "knn.h"),
+           os.path.join("..", "..", "include", "kmv.h")]
+
+FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
+         # packed fp32 VALU forms are kept out of the generated code on purpose
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA results go to ordinary VGPRs so the filter reads them without copies
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+         # the chunk loop of the register-resident-query kernel must unroll completely
+         "-mllvm", "-pragma-unroll-threshold=100000",
+         "-Wno-unused-command-line-argument"]
 
 
 def is_stale() -> bool:
@@ -19,17 +33,21 @@ def is_stale() -> bool:
 
 
 def build(verbose: bool = False) -> str:
-    """Always compiles; returns the library path."""
+    """Always compiles every source (one hipcc process each), links, returns the library path."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
-           # packed fp32 VALU forms are kept out of the generated code on purpose
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           # MFMA results go to ordinary VGPRs so the filter reads them without copies
-           "-mllvm", "-amdgpu-mfma-vgpr-form=1",
-           # the chunk loop of the register-resident-query kernel must unroll completely
-           "-mllvm", "-pragma-unroll-threshold=100000",
-           "-Wno-unused-command-line-argument",
-           "-o", LIB_PATH] + [os.path.join(CSRC, f) for f in SOURCES]
+    os.makedirs(OBJ_DIR, exist_ok=True)
+
+    def compile_one(name: str) -> str:
+        obj = os.path.join(OBJ_DIR, os.path.splitext(name)[0] + ".o")
+        cmd = [hipcc] + FLAGS + ["-c", os.path.join(CSRC, name), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + objs
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

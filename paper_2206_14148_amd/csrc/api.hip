@@ -76,6 +76,11 @@ knn_status hip_fail(hipError_t e, const char* what) {
 
 }  // namespace
 
+namespace knn {
+// Lets the other C ABI sources of the library record into the same per-thread message.
+void set_last_hip_error(hipError_t e, const char* what) { hip_fail(e, what); }
+}  // namespace knn
+
 extern "C" const char* knn_last_hip_error(void) { return g_hip_error; }
 
 extern "C" knn_status knn_profile_enable(int32_t on) {

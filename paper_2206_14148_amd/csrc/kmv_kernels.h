@@ -1,0 +1,36 @@
+// Internal launcher interface between the kernel matrix-vector C ABI (kmv_api.hip) and its
+// gfx950 kernels.  c2 = log2(e) / (2 lengthscale^2), so K = variance * exp2(-c2 * sqdist).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace kmv {
+
+constexpr int kLowdMaxD = 8;      // difference form on the vector ALU up to here
+constexpr int kLowdTileRows = 256;
+constexpr int kMfmaTileRows = 128;
+constexpr int kGroup = 64;        // points per fp32 partial sum
+constexpr int kMaxSplits = 64;
+
+// zn[j] = -c2 * sum_t Z[j][t]^2 (fp32): the start value of the MFMA accumulators.
+hipError_t launch_scaled_norms(const float* Z, int64_t ldz, int64_t m, int d, float c2, float* zn,
+                               hipStream_t stream);
+
+// d <= kLowdMaxD.  out[s * n + i] = variance * sum over range s of K-without-variance * v.
+hipError_t launch_lowd(const float* X, int64_t ldx, const float* Z, int64_t ldz, const float* v,
+                       int64_t n, int64_t m, int d, float c2, double variance, int S, double* out,
+                       hipStream_t stream);
+
+// d > kLowdMaxD: squared distance through the expansion, X Z^T on fp32 MFMA.
+hipError_t launch_mfma(const float* X, int64_t ldx, const float* Z, int64_t ldz, const float* v,
+                       const float* zn, int64_t n, int64_t m, int d, float c2, double variance, int S,
+                       double* out, hipStream_t stream);
+
+// y[i] = sum_s partials[s * n + i], s ascending.
+hipError_t launch_reduce(const double* partials, int S, int64_t n, double* y, hipStream_t stream);
+
+// y[i] = 0.
+hipError_t launch_zero(double* y, int64_t n, hipStream_t stream);
+
+}  // namespace kmv

@@ -1,0 +1,305 @@
+// Device-side helpers shared by the gfx950 kNN kernels: the (key, index) order, the
+// wave-cooperative sorted-list merge, the candidate buffers of the running top-k, the
+// tile loads of the matrix-core kernels.  Everything sits in an unnamed namespace, so
+// each translation unit that includes this header gets its own copy.
+//
+// Paper section 4.3 (figure 2) gives the shape these serve: a generator (distance tile), a
+// reducer (top-k) and a loop over slices, with the big intermediate alive only inside one
+// iteration.  Here the intermediate lives in registers: a tile of keys is produced,
+// compared against each query's current k-th best and dropped.  The rare survivors go
+// through a small per-query candidate buffer in LDS and are merged by one wavefront into
+// the query's sorted list in the workspace.
+//
+// Ordering rule everywhere: (key, index) lexicographic, lower index first on equal keys.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <climits>
+#include <cmath>
+#include <cstdint>
+
+#include "knn_config.h"
+
+namespace knn {
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr float kInf = __builtin_huge_valf();
+constexpr int kNoIdx = INT_MAX;
+
+__device__ __forceinline__ bool before(float ka, int ia, float kb, int ib) {
+    return ka < kb || (ka == kb && ia < ib);
+}
+
+__device__ __forceinline__ bool before64(double ka, int ia, double kb, int ib) {
+    return ka < kb || (ka == kb && ia < ib);
+}
+
+// Make this wave's earlier LDS/global writes visible to its other lanes.
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) v = fminf(v, __shfl_xor(v, s));
+    return v;
+}
+
+// Ascending bitonic sort of one (key, idx) per lane across the 64 lanes of a wave.
+__device__ __forceinline__ void wave_sort64(float& key, int& idx, int lane) {
+#pragma unroll
+    for (int size = 2; size <= 64; size <<= 1) {
+#pragma unroll
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            const float ok = __shfl_xor(key, stride);
+            const int oi = __shfl_xor(idx, stride);
+            const bool ascending = (lane & size) == 0;
+            const bool low_lane = (lane & stride) == 0;
+            const bool keep_min = ascending == low_lane;
+            const bool take = keep_min ? before(ok, oi, key, idx) : before(key, idx, ok, oi);
+            key = take ? ok : key;
+            idx = take ? oi : idx;
+        }
+    }
+}
+
+// Per-wave LDS scratch used while merging candidates into a list.
+struct MergeScratch {
+    float* list_key;  // [k]   staged copy of the list
+    int* list_idx;    // [k]
+    float* cand_key;  // [64]  sorted candidates
+    int* cand_idx;    // [64]
+};
+
+// Merge up to 64 candidates (one per lane; lanes without one pass (+inf, kNoIdx)) into the
+// ascending list gk/gi of k entries in global memory.  Returns the key at position k-1 of
+// the merged list, i.e. the new acceptance threshold.  All 64 lanes must call it together.
+__device__ __noinline__ float wave_merge(float* __restrict__ gk, int* __restrict__ gi, int k, float ckey,
+                            int cidx, const MergeScratch& sc, int lane) {
+    // A list is read and written only by the wave that owns its query, so wave-level
+    // ordering is enough; wave_sync() also orders this wave's earlier global stores to the
+    // list before the loads below (same compute unit, same vector L1).
+    wave_sync();  // earlier uses of the scratch are finished
+    wave_sort64(ckey, cidx, lane);
+    sc.cand_key[lane] = ckey;
+    sc.cand_idx[lane] = cidx;
+    for (int p = lane; p < k; p += kWave) {
+        sc.list_key[p] = gk[p];
+        sc.list_idx[p] = gi[p];
+    }
+    wave_sync();
+    float tau = kInf;
+    // list entries move right by the number of candidates that come before them
+    for (int p = lane; p < k; p += kWave) {
+        const float ek = sc.list_key[p];
+        const int ei = sc.list_idx[p];
+        int cnt = 0;
+#pragma unroll
+        for (int step = 32; step > 0; step >>= 1) {
+            const int probe = cnt + step - 1;
+            if (before(sc.cand_key[probe], sc.cand_idx[probe], ek, ei)) cnt += step;
+        }
+        if (before(sc.cand_key[cnt], sc.cand_idx[cnt], ek, ei)) cnt += 1;  // cnt <= 63 here
+        const int pos = p + cnt;
+        if (pos < k) {
+            gk[pos] = ek;
+            gi[pos] = ei;
+            if (pos == k - 1) tau = ek;
+        }
+    }
+    // candidate c lands after the c candidates before it and the list entries <= it
+    {
+        int lo = 0, hi = k;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (!before(ckey, cidx, sc.list_key[mid], sc.list_idx[mid])) lo = mid + 1;
+            else hi = mid;
+        }
+        const int pos = lane + lo;
+        if (pos < k) {
+            gk[pos] = ckey;
+            gi[pos] = cidx;
+            if (pos == k - 1) tau = ckey;
+        }
+    }
+    tau = wave_min(tau);
+    wave_sync();
+    return tau;
+}
+
+// Bookkeeping of the 32 queries one wave owns in the matrix-core kernels: lane % 32 names the
+// query, the two halves of the wave (lane / 32) hold different points of the same query.
+struct WaveLists {
+    float* lk;        // list keys of the chunk, [rows][S][k]
+    int* li;          // list indices
+    int k, S, s;      // list length, ranges, this workgroup's range
+    int row0;         // first query row (inside the chunk) of this wave
+    float* ck;        // candidate keys of this wave, [32][C]
+    int* ci;          // candidate indices
+    MergeScratch sc;
+    int lane;
+};
+
+// Merge the buffered candidates of the queries named by bits 0..31 of `mask` into their lists;
+// lanes of a merged query get the new threshold and an empty buffer.
+template <int C>
+__device__ __forceinline__ void flush_lists(const WaveLists& w, uint64_t mask, float& tau,
+                                            int& cnt) {
+    while (mask) {
+        const int L = __builtin_ctzll(mask);
+        mask &= mask - 1;
+        wave_sync();
+        const int c = __shfl(cnt, L);
+        float key = kInf;
+        int id = kNoIdx;
+        if (w.lane < c) {
+            key = w.ck[L * C + w.lane];
+            id = w.ci[L * C + w.lane];
+        }
+        const size_t lb = ((size_t)(w.row0 + L) * w.S + w.s) * w.k;
+        const float t_new = wave_merge(w.lk + lb, w.li + lb, w.k, key, id, w.sc, w.lane);
+        if ((w.lane & 31) == L) {
+            tau = t_new;
+            cnt = 0;
+        }
+    }
+}
+
+// End of a 128-point tile: acc[pb][e] is the key of query lane % 32 against point
+// tile_base + pb*32 + (e/4)*8 + (lane/32)*4 + e%4.  Keys below the query's threshold are
+// buffered (the two halves of the wave take consecutive slots), full buffers are merged first.
+template <int C>
+__device__ __forceinline__ void tile_epilogue(const f32x16 (&acc)[4], const WaveLists& w,
+                                              int tile_base, float& tau, int& cnt) {
+    float mn = kInf;
+#pragma unroll
+    for (int pb = 0; pb < 4; ++pb) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mn = fminf(mn, acc[pb][e]);
+    }
+    if (__builtin_amdgcn_ballot_w64(mn < tau) == 0) return;
+    const int i32 = w.lane & 31;
+    const int h = w.lane >> 5;
+#pragma unroll
+    for (int pb = 0; pb < 4; ++pb) {
+        int own = 0;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) own += (acc[pb][e] < tau) ? 1 : 0;
+        int oth = __shfl_xor(own, 32);
+        const uint64_t need = __builtin_amdgcn_ballot_w64(cnt + own + oth > C) & 0xffffffffull;
+        if (need) {
+            flush_lists<C>(w, need, tau, cnt);
+            own = 0;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) own += (acc[pb][e] < tau) ? 1 : 0;
+            oth = __shfl_xor(own, 32);
+        }
+        int slot = i32 * C + cnt + (h ? oth : 0);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            if (acc[pb][e] < tau) {
+                w.ck[slot] = acc[pb][e];
+                w.ci[slot] = tile_base + pb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+                ++slot;
+            }
+        }
+        cnt += own + oth;
+    }
+}
+
+// Cosine metric: the accumulators hold -2 q.x; multiply each by 1/|x| of its point row (rs is
+// the tile's 128 row scales in LDS) to get the rank-equivalent key -2 q.x / |x|.
+__device__ __forceinline__ void scale_rows(f32x16 (&acc)[4], const float* rs, int h) {
+#pragma unroll
+    for (int pb = 0; pb < 4; ++pb) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(rs + pb * 32 + g * 8 + h * 4);
+            acc[pb][g * 4 + 0] *= v[0];
+            acc[pb][g * 4 + 1] *= v[1];
+            acc[pb][g * 4 + 2] *= v[2];
+            acc[pb][g * 4 + 3] *= v[3];
+        }
+    }
+}
+
+// Workgroup -> (query tile, point range).  Consecutive workgroup ids go round-robin to the 8
+// XCDs, each with its own L2.  The (tile, range) grid is cut into blocks of BQ tiles x BS
+// ranges; a block is handed to one XCD as BQ*BS consecutive workgroups of that XCD, so the
+// workgroups resident there together re-use BQ query tiles and BS point streams out of its L2
+// instead of fetching BQ*BS private ones.  Returns false for a padding workgroup.
+__device__ __forceinline__ bool xcd_block_map(int rows, int tile_q, int S, int BQ, int BS, int& s,
+                                              int& wg_row0) {
+    const int T = (rows + tile_q - 1) / tile_q;
+    const int nQB = (T + BQ - 1) / BQ;
+    const int nSB = S / BS;  // BS divides S
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const int per_block = BQ * BS;
+    const int bseq = slot / per_block;
+    const int within = slot - bseq * per_block;
+    const int b = bseq * 8 + xcd;
+    if (b >= nQB * nSB) return false;
+    const int sb = b / nQB;
+    const int qb = b - sb * nQB;
+    const int si = within / BQ;
+    const int qi = within - si * BQ;
+    const int qtile = qb * BQ + qi;
+    if (qtile >= T) return false;
+    s = sb * BS + si;
+    wg_row0 = qtile * tile_q;
+    return true;
+}
+
+// Lists of the 32 queries starting at chunk row `row0` begin as k sentinels.
+__device__ __forceinline__ void init_lists32(float* __restrict__ lk, int* __restrict__ li, int row0,
+                                             int rows, int S, int s, int k, int lane) {
+    for (int qq = 0; qq < 32; ++qq) {
+        if (row0 + qq >= rows) break;
+        const size_t lb = ((size_t)(row0 + qq) * S + s) * k;
+        for (int p = lane; p < k; p += kWave) {
+            lk[lb + p] = kInf;
+            li[lb + p] = kNoIdx;
+        }
+    }
+}
+
+// Four consecutive columns of one row, loaded from an address clamped into the matrix so that
+// the loads of a pipeline step issue back to back without control flow; mask_row4 zeroes
+// what was out of range once the data is used.  ALIGNED: rows are 16-byte aligned and d is
+// a multiple of 4, so one vector load covers the four columns.
+template <bool ALIGNED>
+__device__ __forceinline__ f32x4 load_row4(const float* __restrict__ base, int64_t ld,
+                                           int64_t row, int64_t nrows, int col, int d) {
+    const float* p = base + (row < nrows ? row : nrows - 1) * ld;
+    f32x4 v;
+    if (ALIGNED) {
+        v = *reinterpret_cast<const f32x4*>(p + (col < d ? col : 0));
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = p[col + e < d ? col + e : 0];
+    }
+    return v;
+}
+
+__device__ __forceinline__ f32x4 mask_row4(f32x4 v, bool row_ok, int col, int d, float scale) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = (row_ok && col + e < d) ? v[e] * scale : 0.f;
+    return v;
+}
+template <typename F>
+hipError_t raise_lds_limit(F kernel, size_t bytes) {
+    if (bytes <= 48 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+}  // namespace
+
+}  // namespace knn

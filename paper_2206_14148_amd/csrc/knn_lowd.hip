@@ -1,0 +1,586 @@
+// gfx950 (CDNA4, MI355X) kNN search kernels for low-dimensional points and for the L1
+// metric: paper section 5.2 defines the result, section 4.1 the squared distance; these
+// kernels evaluate the difference form directly (d <= 8, L1) or use an MFMA filter in
+// front of it (d <= 3 with packed points).
+#include <hip/hip_runtime.h>
+
+#include <climits>
+#include <cmath>
+#include <cstdint>
+
+#include "knn_config.h"
+#include "knn_device.h"
+#include "knn_kernels.h"
+
+namespace knn {
+
+namespace {
+
+// ---------------------------------------------------------------------------------------
+// Low-dimensional path: one query per lane, points streamed through uniform (scalar) loads,
+// difference-form distance in fp32 on the vector ALU.
+// ---------------------------------------------------------------------------------------
+template <int D, bool CONTIG>
+__global__ __launch_bounds__(kLowdTileQ) void knn_lowd_kernel(
+    const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx_arg,
+    int rows, int n, int k, int S, int split_len, float* __restrict__ lk, int* __restrict__ li) {
+    constexpr int U = kLowdUnroll;  // points per filter test
+    constexpr int H = 4;            // points pushed between two overflow checks
+    constexpr int C = kLowdCand;
+    constexpr int CP = C + 1;  // padded row of the candidate buffer
+    static_assert(U % H == 0 && C > H, "candidate buffer must hold one push group");
+    // rows of X that follow each other without gaps let a whole group be one wide load
+    const int64_t ldx = CONTIG ? (int64_t)D : ldx_arg;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const size_t per_wave = (size_t)(2 * kWave * CP + 2 * k + 2 * kWave) * 4;
+    unsigned char* base = smem + (size_t)wave * per_wave;
+    float* ck = reinterpret_cast<float*>(base);         // [64][CP]
+    int* ci = reinterpret_cast<int*>(ck + kWave * CP);  // [64][CP]
+    MergeScratch sc;
+    sc.list_key = reinterpret_cast<float*>(ci + kWave * CP);
+    sc.list_idx = reinterpret_cast<int*>(sc.list_key + k);
+    sc.cand_key = reinterpret_cast<float*>(sc.list_idx + k);
+    sc.cand_idx = reinterpret_cast<int*>(sc.cand_key + kWave);
+
+    const int s = blockIdx.y;
+    const int wave_row0 = (blockIdx.x * kLowdWaves + wave) * kWave;
+    if (wave_row0 >= rows) return;  // whole wave idle; no workgroup barrier is used below
+    const int r = wave_row0 + lane;
+    const bool active = r < rows;
+
+    // start every list of this wave as k sentinels
+    {
+        const int nq = min(kWave, rows - wave_row0);
+        for (int qq = 0; qq < nq; ++qq) {
+            const size_t lb = ((size_t)(wave_row0 + qq) * S + s) * k;
+            for (int p = lane; p < k; p += kWave) {
+                lk[lb + p] = kInf;
+                li[lb + p] = kNoIdx;
+            }
+        }
+    }
+
+    float q[D];
+#pragma unroll
+    for (int t = 0; t < D; ++t) q[t] = active ? Q[(int64_t)r * ldq + t] : 0.f;
+    float tau = active ? kInf : -kInf;  // idle lanes never accept anything
+    int cnt = 0;
+
+    auto flush = [&](uint64_t mask) {
+        while (mask) {
+            const int L = __builtin_ctzll(mask);
+            mask &= mask - 1;
+            wave_sync();
+            const int c = __shfl(cnt, L);
+            float key = kInf;
+            int id = kNoIdx;
+            if (lane < c) {
+                key = ck[L * CP + lane];
+                id = ci[L * CP + lane];
+            }
+            const size_t lb = ((size_t)(wave_row0 + L) * S + s) * k;
+            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane);
+            if (lane == L) {
+                tau = t_new;
+                cnt = 0;
+            }
+        }
+    };
+    auto sqdist = [&](const float* __restrict__ xp) {
+        float df = q[0] - xp[0];
+        float acc = df * df;
+#pragma unroll
+        for (int t = 1; t < D; ++t) {
+            df = q[t] - xp[t];
+            acc = fmaf(df, df, acc);
+        }
+        return acc;
+    };
+
+    const int j0 = s * split_len;
+    const int j1 = min(n, j0 + split_len);
+    int j = j0;
+    const float* xp = X + (int64_t)j0 * ldx;  // uniform: the compiler reads it with scalar loads
+    for (; j + U <= j1; j += U, xp += U * ldx) {
+        float dd[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) dd[u] = sqdist(xp + u * ldx);
+        float mn = dd[0];
+#pragma unroll
+        for (int u = 1; u < U; ++u) mn = fminf(mn, dd[u]);
+        if (__builtin_amdgcn_ballot_w64(mn < tau) != 0) {
+#pragma unroll
+            for (int g = 0; g < U / H; ++g) {
+#pragma unroll
+                for (int u = g * H; u < (g + 1) * H; ++u) {
+                    if (dd[u] < tau) {
+                        ck[lane * CP + cnt] = dd[u];
+                        ci[lane * CP + cnt] = j + u;
+                        ++cnt;
+                    }
+                }
+                const uint64_t full = __builtin_amdgcn_ballot_w64(cnt > C - H);
+                if (full) flush(full);
+            }
+        }
+    }
+    for (; j < j1; ++j, xp += ldx) {
+        const float acc = sqdist(xp);
+        if (acc < tau) {
+            ck[lane * CP + cnt] = acc;
+            ci[lane * CP + cnt] = j;
+            ++cnt;
+        }
+        const uint64_t full = __builtin_amdgcn_ballot_w64(cnt > C - H);
+        if (full) flush(full);
+    }
+    const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0);
+    if (rest) flush(rest);
+}
+
+// ---------------------------------------------------------------------------------------
+// L1 metric (the L1 rows of the paper's table): sum |q - x| hides no matrix product, so this
+// is a vector-ALU kernel for every d.  One query per lane; a group of 8 points is wave-uniform
+// and read with scalar loads; the dimension is walked in chunks of 16 with the query's chunk
+// in registers and one running sum per point of the group, so a query value is loaded once
+// per 8 points and a point value costs no vector work.  Two VALU ops per pair and dimension
+// (subtract, add-absolute).  Sums run in ascending t, whatever the chunking.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kLowdTileQ) void knn_l1_kernel(
+    const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx, int rows,
+    int n, int d, int k, int S, int split_len, float* __restrict__ lk, int* __restrict__ li) {
+    constexpr int P = 8;    // points per group
+    constexpr int TC = 16;  // dimensions per register chunk
+    constexpr int H = 4;    // points pushed between two overflow checks
+    constexpr int C = kLowdCand;
+    constexpr int CP = C + 1;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const size_t per_wave = (size_t)(2 * kWave * CP + 2 * k + 2 * kWave) * 4;
+    unsigned char* base = smem + (size_t)wave * per_wave;
+    float* ck = reinterpret_cast<float*>(base);         // [64][CP]
+    int* ci = reinterpret_cast<int*>(ck + kWave * CP);  // [64][CP]
+    MergeScratch sc;
+    sc.list_key = reinterpret_cast<float*>(ci + kWave * CP);
+    sc.list_idx = reinterpret_cast<int*>(sc.list_key + k);
+    sc.cand_key = reinterpret_cast<float*>(sc.list_idx + k);
+    sc.cand_idx = reinterpret_cast<int*>(sc.cand_key + kWave);
+
+    const int s = blockIdx.y;
+    const int wave_row0 = (blockIdx.x * kLowdWaves + wave) * kWave;
+    if (wave_row0 >= rows) return;  // whole wave idle; no workgroup barrier is used below
+    const int r = wave_row0 + lane;
+    const bool active = r < rows;
+    {
+        const int nq = min(kWave, rows - wave_row0);
+        for (int qq = 0; qq < nq; ++qq) {
+            const size_t lb = ((size_t)(wave_row0 + qq) * S + s) * k;
+            for (int p = lane; p < k; p += kWave) {
+                lk[lb + p] = kInf;
+                li[lb + p] = kNoIdx;
+            }
+        }
+    }
+    const float* qrow = Q + (int64_t)(active ? r : 0) * ldq;
+    const bool qvec = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) && (ldq % 4 == 0);
+    float tau = active ? kInf : -kInf;
+    int cnt = 0;
+
+    auto flush = [&](uint64_t mask) {
+        while (mask) {
+            const int L = __builtin_ctzll(mask);
+            mask &= mask - 1;
+            wave_sync();
+            const int c = __shfl(cnt, L);
+            float key = kInf;
+            int id = kNoIdx;
+            if (lane < c) {
+                key = ck[L * CP + lane];
+                id = ci[L * CP + lane];
+            }
+            const size_t lb = ((size_t)(wave_row0 + L) * S + s) * k;
+            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane);
+            if (lane == L) {
+                tau = t_new;
+                cnt = 0;
+            }
+        }
+    };
+
+    const int j0 = s * split_len;
+    const int j1 = min(n, j0 + split_len);
+    for (int j = j0; j < j1; j += P) {
+        float acc[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) acc[p] = 0.f;
+        for (int t0 = 0; t0 < d; t0 += TC) {
+            const bool full = t0 + TC <= d;  // uniform
+            float qv[TC];
+            if (full && qvec) {  // uniform: whole chunk inside the row and 16-byte aligned
+#pragma unroll
+                for (int t4 = 0; t4 < TC / 4; ++t4) {
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(qrow + t0 + 4 * t4);
+                    qv[4 * t4 + 0] = v[0];
+                    qv[4 * t4 + 1] = v[1];
+                    qv[4 * t4 + 2] = v[2];
+                    qv[4 * t4 + 3] = v[3];
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < TC; ++t) {
+                    const int tt = t0 + t;
+                    const float v = qrow[tt < d ? tt : d - 1];
+                    qv[t] = tt < d ? v : 0.f;
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                const int jp = (j + p < j1) ? j + p : j1 - 1;  // uniform; repeats of the last point are masked below
+                const float* xp = X + (int64_t)jp * ldx;
+                float a = acc[p];
+                if (full) {
+#pragma unroll
+                    for (int t = 0; t < TC; ++t) a += fabsf(qv[t] - xp[t0 + t]);
+                } else {
+#pragma unroll
+                    for (int t = 0; t < TC; ++t) {
+                        const int tt = t0 + t;
+                        const float xv = xp[tt < d ? tt : d - 1];
+                        a += fabsf(qv[t] - (tt < d ? xv : 0.f));
+                    }
+                }
+                acc[p] = a;
+            }
+        }
+        float mn = kInf;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            if (j + p >= j1) acc[p] = kInf;  // past the range
+            mn = fminf(mn, acc[p]);
+        }
+        if (__builtin_amdgcn_ballot_w64(mn < tau) != 0) {
+#pragma unroll
+            for (int g = 0; g < P / H; ++g) {
+#pragma unroll
+                for (int p = g * H; p < (g + 1) * H; ++p) {
+                    if (acc[p] < tau) {
+                        ck[lane * CP + cnt] = acc[p];
+                        ci[lane * CP + cnt] = j + p;
+                        ++cnt;
+                    }
+                }
+                const uint64_t fullb = __builtin_amdgcn_ballot_w64(cnt > C - H);
+                if (fullb) flush(fullb);
+            }
+        }
+    }
+    const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0);
+    if (rest) flush(rest);
+}
+
+// ---------------------------------------------------------------------------------------
+// Low-dimensional path on the matrix cores (d <= 3).  The expansion of section 4.1 is used
+// only as a FILTER: with points packed as [x0 x1 x2 ||x||^2] and queries as
+// [-2q0 -2q1 -2q2 1], two v_mfma_f32_32x32x2_f32 give 32 x 32 keys ||x||^2 - 2 q.x.  A key
+// that could still belong to a pair closer than the query's threshold (allowing for the
+// rounding of the expansion) sends the pair to the exact test: the same fp32
+// difference-form distance as knn_lowd_kernel, compared against the same threshold.  The
+// accepted set, the keys and therefore the result are identical to the vector-ALU kernel.
+// ---------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void knn_pack_points_kernel(const float* __restrict__ X,
+                                                              int64_t ldx, int n,
+                                                              f32x4* __restrict__ Xp,
+                                                              unsigned* __restrict__ xn_max_bits) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    float nrm = 0.f;
+    if (j < n) {
+        float v[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < D; ++t) v[t] = X[(int64_t)j * ldx + t];
+        nrm = v[0] * v[0];
+        nrm = fmaf(v[1], v[1], nrm);
+        nrm = fmaf(v[2], v[2], nrm);
+        Xp[j] = f32x4{v[0], v[1], v[2], nrm};
+    }
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) nrm = fmaxf(nrm, __shfl_xor(nrm, s));
+    // non-negative floats order like their bit patterns
+    if ((threadIdx.x & 63) == 0) atomicMax(xn_max_bits, __float_as_uint(nrm));
+}
+
+__global__ void knn_zero_word_kernel(unsigned* __restrict__ w) { *w = 0u; }
+
+template <int D>
+__global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
+    const float* __restrict__ Q, int64_t ldq, const f32x4* __restrict__ Xp,
+    const unsigned* __restrict__ xn_max_bits, int rows, int n, int k, int S, int split_len,
+    float* __restrict__ lk, int* __restrict__ li) {
+    constexpr int C = kPmCand;
+    constexpr int UB = 4;        // 32-point blocks per loop iteration
+    constexpr int PTS = UB * 32; // points per loop iteration
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int i32 = lane & 31;  // query column (B side) / point row (A side) of the 32x32 block
+    const int h = lane >> 5;
+    const size_t per_wave = (size_t)(2 * 32 * C + 2 * kWave + 2 * k) * 4;
+    float* ck = reinterpret_cast<float*>(smem + (size_t)wave * per_wave);  // [32][C]
+    int* ci = reinterpret_cast<int*>(ck + 32 * C);                         // [32][C]
+    MergeScratch sc;
+    sc.cand_key = reinterpret_cast<float*>(ci + 32 * C);
+    sc.cand_idx = reinterpret_cast<int*>(sc.cand_key + kWave);
+    sc.list_key = reinterpret_cast<float*>(sc.cand_idx + kWave);
+    sc.list_idx = reinterpret_cast<int*>(sc.list_key + k);
+
+    const int s = blockIdx.y;
+    const int wave_row0 = (blockIdx.x * 4 + wave) * 32;
+    if (wave_row0 >= rows) return;  // whole wave idle; no workgroup barrier is used below
+    const int r = wave_row0 + i32;
+    const bool active = r < rows;
+
+    for (int qq = 0; qq < 32; ++qq) {
+        if (wave_row0 + qq >= rows) break;
+        const size_t lb = ((size_t)(wave_row0 + qq) * S + s) * k;
+        for (int p = lane; p < k; p += kWave) {
+            lk[lb + p] = kInf;
+            li[lb + p] = kNoIdx;
+        }
+    }
+
+    float q[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < D; ++t) q[t] = active ? Q[(int64_t)r * ldq + t] : 0.f;
+    const float qn = fmaf(q[2], q[2], fmaf(q[1], q[1], q[0] * q[0]));
+    // B operand, K order (0, 1 | 2, 3) split over the two halves of the wave
+    const float b0 = h ? -2.f * q[2] : -2.f * q[0];
+    const float b1 = h ? 1.f : -2.f * q[1];
+    const float xmax = __uint_as_float(*xn_max_bits);
+
+    // A pair with exact fp32 distance < tau has key < (tau - qn) + slack: the key and qn each
+    // carry a few roundings relative to (||x||^2 + ||q||^2), the distance a few relative to
+    // itself; 2^-19 of their sum is several times the worst case.
+    float tau = active ? kInf : -kInf;
+    auto key_bound = [&](float t) { return (t - qn) + 0x1p-19f * (xmax + qn + t); };
+    float tauf = key_bound(tau);
+    int cnt = 0;  // candidates buffered for this lane's query (same in both halves)
+
+    auto flush = [&](uint64_t mask) {  // bits 0..31: queries of this wave to merge
+        while (mask) {
+            const int L = __builtin_ctzll(mask);
+            mask &= mask - 1;
+            wave_sync();
+            const int c = __shfl(cnt, L);
+            float key = kInf;
+            int id = kNoIdx;
+            if (lane < c) {
+                key = ck[L * C + lane];
+                id = ci[L * C + lane];
+            }
+            const size_t lb = ((size_t)(wave_row0 + L) * S + s) * k;
+            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane);
+            if (i32 == L) {
+                tau = t_new;
+                tauf = key_bound(t_new);
+                cnt = 0;
+            }
+        }
+    };
+
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2* xp2 = reinterpret_cast<const f32x2*>(Xp);  // point j = entries 2j (x0 x1), 2j+1 (x2 xn)
+    const int j0 = s * split_len;
+    const int j1 = min(n, j0 + split_len);
+
+    // Rare path of one 32-point block.  Each lane collects the keys that pass the filter in
+    // a 16-bit mask and the lanes then work through their own bits in parallel (usually one
+    // round).  The coordinates of the point come from the A-operand registers of the lanes
+    // that loaded them, not from memory.
+    auto examine = [&](const f32x16& keys, const f32x2& apt, int jblock) {
+        unsigned bits = 0;  // bit e <=> key e passes; shift-in from the top keeps it to
+#pragma unroll          // a compare and an add-with-carry per key
+        for (int e = 15; e >= 0; --e) bits = bits + bits + ((keys[e] < tauf) ? 1u : 0u);
+        while (__builtin_amdgcn_ballot_w64(bits != 0) != 0) {
+            const bool has = bits != 0;
+            const int e = __builtin_ctz(bits | 0x10000u);
+            bits &= bits - 1;
+            const int row = ((e >> 2) * 8 + h * 4 + (e & 3)) & 31;  // point row inside the block
+            float xv[3];
+            xv[0] = __shfl(apt[0], row);
+            xv[1] = __shfl(apt[1], row);
+            xv[2] = __shfl(apt[0], row + 32);
+            // exact test, same arithmetic as the vector-ALU kernel
+            float df = q[0] - xv[0];
+            float dd = df * df;
+            if (D > 1) {
+                df = q[1] - xv[1];
+                dd = fmaf(df, df, dd);
+            }
+            if (D > 2) {
+                df = q[2] - xv[2];
+                dd = fmaf(df, df, dd);
+            }
+            bool c = has && dd < tau;
+            if (__builtin_amdgcn_ballot_w64(c) == 0) continue;
+            int own = c ? 1 : 0;
+            int oth = __shfl_xor(own, 32);
+            const uint64_t need = __builtin_amdgcn_ballot_w64(cnt + own + oth > C) & 0xffffffffull;
+            if (need) {
+                flush(need);
+                c = c && dd < tau;
+                own = c ? 1 : 0;
+                oth = __shfl_xor(own, 32);
+            }
+            if (c) {
+                const int slot = i32 * C + cnt + (h ? oth : 0);
+                ck[slot] = dd;
+                ci[slot] = jblock + row;
+            }
+            cnt += own + oth;
+        }
+    };
+
+    // one iteration: UB blocks of 32 points against this wave's 32 queries
+    auto process = [&](const f32x2 (&a)[UB], int jb) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            f32x16 z;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) z[e] = 0.f;
+            z = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][0], b0, z, 0, 0, 0);
+            z = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][1], b1, z, 0, 0, 0);
+            float m = kInf;  // 8 three-input mins over (inf, 16 keys)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) m = fminf(m, z[e]);
+            if (__builtin_amdgcn_ballot_w64(m < tauf) != 0) examine(z, a[u], jb + u * 32);
+        }
+    };
+
+    const int nfull = (j1 > j0) ? (j1 - j0) / PTS : 0;
+    int jb = j0;
+    f32x2 a[UB], an[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) a[u] = an[u] = f32x2{0.f, 0.f};
+    if (nfull > 0) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u) a[u] = xp2[(size_t)(jb + u * 32 + i32) * 2 + h];
+    }
+    for (int it = 0; it < nfull; ++it) {
+        if (it + 1 < nfull) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u) an[u] = xp2[(size_t)(jb + PTS + u * 32 + i32) * 2 + h];
+        }
+        process(a, jb);
+#pragma unroll
+        for (int u = 0; u < UB; ++u) a[u] = an[u];
+        jb += PTS;
+    }
+    if (jb < j1) {  // ragged tail: rows past the range read a valid row and get ||x||^2 = +inf
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const int row = jb + u * 32 + i32;
+            a[u] = xp2[(size_t)(row < j1 ? row : j1 - 1) * 2 + h];
+            if (row >= j1 && h) a[u][1] = kInf;
+        }
+        process(a, jb);
+    }
+    const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0) & 0xffffffffull;
+    if (rest) flush(rest);
+}
+
+}  // namespace
+
+template <int D>
+static hipError_t launch_lowd_d(const float* Q, int64_t ldq, const float* X, int64_t ldx,
+                                int64_t rows, int64_t n, int k, int S, float* lk, int* li,
+                                hipStream_t stream) {
+    const size_t per_wave = (size_t)(2 * kWave * (kLowdCand + 1) + 2 * k + 2 * kWave) * 4;
+    const size_t lds = per_wave * kLowdWaves;
+    int64_t split_len = (n + S - 1) / S;
+    split_len = (split_len + kLowdUnroll - 1) / kLowdUnroll * kLowdUnroll;
+    dim3 grid((unsigned)((rows + kLowdTileQ - 1) / kLowdTileQ), (unsigned)S);
+    hipError_t e;
+    if (ldx == D) {
+        e = raise_lds_limit(knn_lowd_kernel<D, true>, lds);
+        if (e != hipSuccess) return e;
+        knn_lowd_kernel<D, true><<<grid, dim3(kLowdTileQ), lds, stream>>>(
+            Q, ldq, X, ldx, (int)rows, (int)n, k, S, (int)split_len, lk, li);
+    } else {
+        e = raise_lds_limit(knn_lowd_kernel<D, false>, lds);
+        if (e != hipSuccess) return e;
+        knn_lowd_kernel<D, false><<<grid, dim3(kLowdTileQ), lds, stream>>>(
+            Q, ldq, X, ldx, (int)rows, (int)n, k, S, (int)split_len, lk, li);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_l1(const float* Q, int64_t ldq, const float* X, int64_t ldx, int64_t rows,
+                     int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream) {
+    const size_t per_wave = (size_t)(2 * kWave * (kLowdCand + 1) + 2 * k + 2 * kWave) * 4;
+    const size_t lds = per_wave * kLowdWaves;
+    hipError_t e = raise_lds_limit(knn_l1_kernel, lds);
+    if (e != hipSuccess) return e;
+    int64_t split_len = (n + S - 1) / S;
+    split_len = (split_len + 7) / 8 * 8;
+    dim3 grid((unsigned)((rows + kLowdTileQ - 1) / kLowdTileQ), (unsigned)S);
+    knn_l1_kernel<<<grid, dim3(kLowdTileQ), lds, stream>>>(Q, ldq, X, ldx, (int)rows, (int)n, d, k, S,
+                                                           (int)split_len, lk, li);
+    return hipGetLastError();
+}
+
+hipError_t launch_lowd(const float* Q, int64_t ldq, const float* X, int64_t ldx, int64_t rows,
+                       int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream) {
+    switch (d) {
+        case 1: return launch_lowd_d<1>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 2: return launch_lowd_d<2>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 3: return launch_lowd_d<3>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 4: return launch_lowd_d<4>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 5: return launch_lowd_d<5>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 6: return launch_lowd_d<6>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 7: return launch_lowd_d<7>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        case 8: return launch_lowd_d<8>(Q, ldq, X, ldx, rows, n, k, S, lk, li, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <int D>
+static hipError_t launch_lowd_mfma_d(const float* Q, int64_t ldq, const float* X, int64_t ldx,
+                                     void* packed, int64_t rows, int64_t n, int k, int S,
+                                     bool pack, float* lk, int* li, hipStream_t stream) {
+    unsigned* xmax = static_cast<unsigned*>(packed);
+    f32x4* Xp = reinterpret_cast<f32x4*>(static_cast<unsigned char*>(packed) + kAlign);
+    if (pack) {
+        knn_zero_word_kernel<<<dim3(1), dim3(1), 0, stream>>>(xmax);
+        knn_pack_points_kernel<D><<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(
+            X, ldx, (int)n, Xp, xmax);
+        hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return e0;
+    }
+    if (rows == 0) return hipSuccess;
+    const size_t per_wave = (size_t)(2 * 32 * kPmCand + 2 * kWave + 2 * k) * 4;
+    const size_t lds = per_wave * 4;
+    hipError_t e = raise_lds_limit(knn_lowd_mfma_kernel<D>, lds);
+    if (e != hipSuccess) return e;
+    int64_t split_len = (n + S - 1) / S;
+    split_len = (split_len + 127) / 128 * 128;
+    dim3 grid((unsigned)((rows + kPmTileQ - 1) / kPmTileQ), (unsigned)S);
+    knn_lowd_mfma_kernel<D><<<grid, dim3(256), lds, stream>>>(
+        Q, ldq, Xp, xmax, (int)rows, (int)n, k, S, (int)split_len, lk, li);
+    return hipGetLastError();
+}
+
+hipError_t launch_lowd_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx, void* packed,
+                            int64_t rows, int64_t n, int d, int k, int S, bool pack, float* lk,
+                            int* li, hipStream_t stream) {
+    switch (d) {
+        case 1: return launch_lowd_mfma_d<1>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        case 2: return launch_lowd_mfma_d<2>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        case 3: return launch_lowd_mfma_d<3>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace knn

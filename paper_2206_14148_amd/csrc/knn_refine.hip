@@ -1,0 +1,135 @@
+// Final step of the gfx950 kNN search: merge the per-range partial lists of each query,
+// re-evaluate the k winners in fp64 with the plain definition of the metric (paper
+// sections 4.1 and 5.2) and write them ordered by (distance, index).
+#include <hip/hip_runtime.h>
+
+#include <climits>
+#include <cmath>
+#include <cstdint>
+
+#include "knn_config.h"
+#include "knn_device.h"
+#include "knn_kernels.h"
+
+namespace knn {
+
+namespace {
+
+// ---------------------------------------------------------------------------------------
+// Merge of the S partial lists, exact re-evaluation, final order.  One wave per query.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ double exact_sqdist(const float* __restrict__ q,
+                                               const float* __restrict__ x, int d) {
+#pragma clang fp contract(off)
+    double acc = 0.0;
+    for (int t = 0; t < d; ++t) {
+        const double diff = (double)q[t] - (double)x[t];
+        acc = acc + diff * diff;
+    }
+    return acc;
+}
+
+// Cosine distance in fp64: 1 - <q,x> / (|q| |x|), clamped at 0; 1 if either vector is zero.
+__device__ __forceinline__ double exact_cosdist(const float* __restrict__ q,
+                                                const float* __restrict__ x, int d) {
+#pragma clang fp contract(off)
+    double qq = 0.0, xx = 0.0, qx = 0.0;
+    for (int t = 0; t < d; ++t) {
+        const double a = (double)q[t], b = (double)x[t];
+        qq = qq + a * a;
+        xx = xx + b * b;
+        qx = qx + a * b;
+    }
+    if (qq == 0.0 || xx == 0.0) return 1.0;
+    const double c = 1.0 - __ddiv_rn(qx, __dsqrt_rn(qq) * __dsqrt_rn(xx));
+    return c < 0.0 ? 0.0 : c;
+}
+
+// L1 distance in fp64, ascending t.
+__device__ __forceinline__ double exact_l1dist(const float* __restrict__ q,
+                                               const float* __restrict__ x, int d) {
+    double acc = 0.0;
+    for (int t = 0; t < d; ++t) acc = acc + fabs((double)q[t] - (double)x[t]);
+    return acc;
+}
+
+// metric: 0 squared Euclidean, 1 cosine, 2 L1 (the values of knn_metric)
+__global__ __launch_bounds__(256) void knn_merge_refine_kernel(
+    const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx, int rows,
+    int n, int d, int k, int S, int metric, const float* __restrict__ lk,
+    const int* __restrict__ li, int32_t* __restrict__ idx_out, float* __restrict__ dist_out) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int r = blockIdx.x * 4 + wave;
+    if (r >= rows) return;  // no workgroup barrier below
+    double* wd = reinterpret_cast<double*>(smem) + (size_t)wave * k;
+    int* wi = reinterpret_cast<int*>(reinterpret_cast<double*>(smem) + (size_t)4 * k) + (size_t)wave * k;
+
+    const size_t rb = (size_t)r * S * k;
+    if (S == 1) {
+        for (int p = lane; p < k; p += kWave) wi[p] = li[rb + p];
+    } else {
+        // rank of an entry = its position in its own list + entries of the other lists
+        // that come before it; indices are distinct, so ranks are too
+        const int total = S * k;
+        for (int e = lane; e < total; e += kWave) {
+            const int se = e / k;
+            const int p = e - se * k;
+            const float key = lk[rb + e];
+            const int id = li[rb + e];
+            int rank = p;
+            for (int s2 = 0; s2 < S && rank < k; ++s2) {
+                if (s2 == se) continue;
+                const float* k2 = lk + rb + (size_t)s2 * k;
+                const int* i2 = li + rb + (size_t)s2 * k;
+                int lo = 0, hi = k;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (before(k2[mid], i2[mid], key, id)) lo = mid + 1;
+                    else hi = mid;
+                }
+                rank += lo;
+            }
+            if (rank < k) wi[rank] = id;
+        }
+    }
+    wave_sync();
+    for (int w = lane; w < k; w += kWave) {
+        const int j = wi[w];
+        double dist = __builtin_huge_val();
+        if ((unsigned)j < (unsigned)n) {
+            const float* qp = Q + (int64_t)r * ldq;
+            const float* xp = X + (int64_t)j * ldx;
+            dist = metric == 1 ? exact_cosdist(qp, xp, d)
+                               : (metric == 2 ? exact_l1dist(qp, xp, d) : exact_sqdist(qp, xp, d));
+        }
+        wd[w] = dist;
+    }
+    wave_sync();
+    for (int w = lane; w < k; w += kWave) {
+        const double dw = wd[w];
+        const int jw = wi[w];
+        int rank = 0;
+        for (int v = 0; v < k; ++v) rank += before64(wd[v], wi[v], dw, jw) ? 1 : 0;
+        idx_out[(size_t)r * k + rank] = jw;
+        dist_out[(size_t)r * k + rank] = (float)dw;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_merge_refine(const float* Q, int64_t ldq, const float* X, int64_t ldx,
+                               int64_t rows, int64_t n, int d, int k, int S, int metric,
+                               const float* lk, const int* li, int32_t* idx, float* dist,
+                               hipStream_t stream) {
+    const size_t lds = (size_t)4 * k * (sizeof(double) + sizeof(int));
+    hipError_t e = raise_lds_limit(knn_merge_refine_kernel, lds);
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned)((rows + 3) / 4));
+    knn_merge_refine_kernel<<<grid, dim3(256), lds, stream>>>(
+        Q, ldq, X, ldx, (int)rows, (int)n, d, k, S, metric, lk, li, idx, dist);
+    return hipGetLastError();
+}
+
+}  // namespace knn

@@ -167,3 +167,68 @@ def random_case(seed: int, m: int, n: int, d: int, kind: str = "normal"):
     else:
         raise ValueError(kind)
     return Q, X
+
+
+# ---------------------------------------------------------------------------------------------
+# Kernel matrix-vector product (paper section 5.1): y = K v with an n x n squared-exponential
+# kernel matrix.  The appendix names 1-dimensional inputs of size 1e6 and the kernel's library
+# defaults (variance 1, lengthscale 1); it does not say how the inputs are distributed, so
+# they are standard normal here.
+# ---------------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class KmvWorkload:
+    name: str
+    n: int               # rows of X = rows of K
+    m: int               # rows of Z = columns of K = length of v
+    d: int
+    variance: float
+    lengthscale: float
+    mem_limit: int
+    z_is_x: bool = True  # square kernel matrix of one point set
+    stream: int = 0
+
+    @property
+    def pairs(self) -> int:
+        return self.n * self.m
+
+
+KMV_WORKLOADS = {
+    "kmv1": KmvWorkload("kmv1_d1", 1_000_000, 1_000_000, 1, 1.0, 1.0, 1 * GB),
+    # a multi-dimensional input set on the matrix-core path, lengthscale of the order sqrt(d)
+    "kmv2": KmvWorkload("kmv2_d32", 200_000, 200_000, 32, 1.0, 6.0, 1 * GB, stream=1),
+}
+
+
+def scaled_kmv(key: str, n: int | None = None, m: int | None = None, **kw) -> KmvWorkload:
+    w = KMV_WORKLOADS[key]
+    if w.z_is_x and "z_is_x" not in kw:
+        size = n if n is not None else (m if m is not None else w.n)
+        n = m = size
+    else:
+        n = w.n if n is None else n
+        m = w.m if m is None else m
+    return replace(w, n=n, m=m, **kw)
+
+
+def make_kmv(w: KmvWorkload):
+    """Returns (X, Z, v): float32 [n,d], [m,d] (X itself when z_is_x) and [m]."""
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 9_000_000 + w.stream))
+    X = np.empty((w.n, w.d), dtype=np.float32)
+    _fill_normal(rng, X)
+    if w.z_is_x:
+        Z = X
+    else:
+        Z = np.empty((w.m, w.d), dtype=np.float32)
+        _fill_normal(rng, Z)
+    v = np.empty((w.m,), dtype=np.float32)
+    _fill_normal(rng, v)
+    return X, Z, v
+
+
+def random_kmv_case(seed: int, n: int, m: int, d: int, spread: float = 1.0):
+    """Small free-form case: normal points with the given spread, normal v."""
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 8_000_000 + seed))
+    X = (np.float32(spread) * rng.standard_normal((n, d), dtype=np.float32)).astype(np.float32)
+    Z = (np.float32(spread) * rng.standard_normal((m, d), dtype=np.float32)).astype(np.float32)
+    v = rng.standard_normal((m,), dtype=np.float32)
+    return X, Z, v
