@@ -63,6 +63,10 @@ def _load():
                                    ctypes.c_int64, ctypes.c_int32, ctypes.c_double, ctypes.c_double,
                                    i64p, ctypes.c_int64, dp, ctypes.c_int32]
         lib.oracle_kmv.restype = ctypes.c_int
+        lib.oracle_kmv_f64.argtypes = [dp, ctypes.c_int64, dp, ctypes.c_int64, dp, ctypes.c_int64,
+                                       ctypes.c_int64, ctypes.c_int32, ctypes.c_double,
+                                       ctypes.c_double, i64p, ctypes.c_int64, dp, ctypes.c_int32]
+        lib.oracle_kmv_f64.restype = ctypes.c_int
         lib.oracle_threads_used.argtypes = [ctypes.c_int32]
         lib.oracle_threads_used.restype = ctypes.c_int32
         _lib = lib
@@ -198,6 +202,31 @@ def kmv(X, Z, v, variance: float, lengthscale: float, rows=None, nthreads: int |
                             rows_arr.ctypes.data_as(i64p) if rows_arr is not None else None, nrows,
                             y.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
                             int(nthreads or default_threads()))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return y
+
+
+def kmv_f64(X, Z, v, variance: float, lengthscale: float, rows=None, nthreads: int | None = None):
+    """The same product on fp64 inputs, all in fp64 (the precision of paper section 5.1)."""
+    X = np.ascontiguousarray(X, dtype=np.float64)
+    Z = np.ascontiguousarray(Z, dtype=np.float64)
+    v = np.ascontiguousarray(v, dtype=np.float64).ravel()
+    if X.ndim != 2 or Z.ndim != 2 or X.shape[1] != Z.shape[1] or v.shape[0] != Z.shape[0]:
+        raise ValueError("shape mismatch")
+    if rows is None:
+        rows_arr, nrows = None, X.shape[0]
+    else:
+        rows_arr = np.ascontiguousarray(rows, dtype=np.int64)
+        nrows = rows_arr.shape[0]
+    y = np.empty(nrows, dtype=np.float64)
+    dp = ctypes.POINTER(ctypes.c_double)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    rc = _load().oracle_kmv_f64(X.ctypes.data_as(dp), X.shape[1], Z.ctypes.data_as(dp), Z.shape[1],
+                                v.ctypes.data_as(dp), X.shape[0], Z.shape[0], X.shape[1],
+                                float(variance), float(lengthscale),
+                                rows_arr.ctypes.data_as(i64p) if rows_arr is not None else None,
+                                nrows, y.ctypes.data_as(dp), int(nthreads or default_threads()))
     if rc != 0:
         raise ValueError("oracle rejected its arguments")
     return y

@@ -302,6 +302,38 @@ int oracle_kmv(const float *X, int64_t ldx, const float *Z, int64_t ldz, const f
     return 0;
 }
 
+/*
+ * oracle_kmv_f64: the same product with fp64 inputs, the precision in which paper section
+ * 5.1 evaluates it.  X [n, d], Z [m, d], v [m] fp64 row-major; everything in fp64, the
+ * squared distance in difference form with t ascending, the sum with j ascending.
+ */
+int oracle_kmv_f64(const double *X, int64_t ldx, const double *Z, int64_t ldz, const double *v,
+                   int64_t n, int64_t m, int32_t d, double variance, double lengthscale,
+                   const int64_t *rows, int64_t nrows, double *y, int32_t nthreads)
+{
+    if (!X || !Z || !v || !y || n < 0 || m < 0 || d < 1 || ldx < d || ldz < d || !(lengthscale > 0.0))
+        return -1;
+    if (nthreads < 1) nthreads = 1;
+    const double inv = -0.5 / (lengthscale * lengthscale);
+#pragma omp parallel for num_threads(nthreads) schedule(dynamic, 4)
+    for (int64_t r = 0; r < nrows; ++r) {
+        int64_t i = rows ? rows[r] : r;
+        const double *x = X + i * ldx;
+        double acc = 0.0;
+        for (int64_t j = 0; j < m; ++j) {
+            const double *z = Z + j * ldz;
+            double sq = 0.0;
+            for (int32_t t = 0; t < d; ++t) {
+                double df = x[t] - z[t];
+                sq += df * df;
+            }
+            acc += variance * exp(inv * sq) * v[j];
+        }
+        y[r] = acc;
+    }
+    return 0;
+}
+
 /* Number of threads an OpenMP region of the requested width really gets. */
 int32_t oracle_threads_used(int32_t nthreads)
 {
