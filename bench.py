@@ -66,11 +66,13 @@ def bench_kmv(args) -> int:
     Xd = torch.from_numpy(X).to(dev)
     Zd = Xd if w.z_is_x else torch.from_numpy(Z).to(dev)
     vd = torch.from_numpy(v).to(dev)
-    plan = K.kmv_plan(w.n, w.m, w.d, limit)
+    plan = K.kmv_plan(w.n, w.m, w.d, limit, w.dtype)
     assert plan.workspace_bytes <= limit
     ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
     y = torch.empty((w.n,), dtype=torch.float64, device=dev)
-    path_name = {0: "lowd", 1: "mfma"}[plan.path]
+    path_name = {0: "lowd", 1: "mfma", 2: "valu"}[plan.path]
+    okmv = (lambda *a, **k: __import__("oracle").kmv_f64(*a, **k)) if w.dtype == "f64" \
+        else (lambda *a, **k: __import__("oracle").kmv(*a, **k))
     log(f"[bench] plan: path={path_name} ranges={plan.n_splits} workspace={plan.workspace_bytes} B "
         f"(limit {limit} B)")
 
@@ -103,7 +105,14 @@ def bench_kmv(args) -> int:
     value = pairs * args.steps / elapsed
     log(f"[bench] {ms_per_step:.2f} ms/step, {value:.3e} pairs/s; kernels per call {call_ms:.3f} ms")
     rate = pairs / (call_ms * 1e-3)
-    if plan.path == K.KMV_PATH_LOWD:
+    if w.dtype == "f64":
+        # per pair: d subtractions, d multiply-adds, the scaling, exp (a polynomial of about 25
+        # fp64 operations in the math library, counted as one flop here) and the multiply-add
+        fpp = 3 * w.d + 3
+        roofline = {"bound": "alu", "kernel": "kmv_lowd_f64_kernel" if w.d <= 8 else "kmv_anyd_f64_kernel",
+                    "achieved": rate * fpp / 1e12, "peak": 78.6, "unit": "TFLOP/s",
+                    "frac": rate * fpp / 1e12 / 78.6, "traffic": None, "flops_per_pair": fpp}
+    elif plan.path == K.KMV_PATH_LOWD:
         # per pair: d subtractions, d multiplications, d-1 additions, the scaling, exp2, and
         # the multiply-add with v
         fpp = 3 * w.d + 3
@@ -133,18 +142,18 @@ def bench_kmv(args) -> int:
         rng = np.random.Generator(np.random.PCG64(11))
         probe = np.sort(rng.choice(w.n, size=min(w.n, 4 * threads), replace=False))
         t0 = time.perf_counter()
-        oracle.kmv(X, Z, v, w.variance, w.lengthscale, rows=probe)
+        okmv(X, Z, v, w.variance, w.lengthscale, rows=probe)
         probe_rate = len(probe) / max(time.perf_counter() - t0, 1e-6)
         nrows = int(max(len(probe), min(w.n, probe_rate * args.cpu_seconds)))
         rows = np.sort(rng.choice(w.n, size=nrows, replace=False))
         t0 = time.perf_counter()
-        ref = oracle.kmv(X, Z, v, w.variance, w.lengthscale, rows=rows)
+        ref = okmv(X, Z, v, w.variance, w.lengthscale, rows=rows)
         dt = time.perf_counter() - t0
         cpu_baseline = {"value": len(rows) * float(w.m) / dt, "unit": "pairs/s", "cores": threads,
                         "kind": "oracle",
                         "sample": f"{len(rows)} seeded rows of K x all {w.m} points of {w.name}, {dt:.1f} s"}
         got = y[torch.from_numpy(rows).to(dev)].cpu().numpy()
-        mag = oracle.kmv(X, Z, np.abs(v), w.variance, w.lengthscale, rows=rows)
+        mag = okmv(X, Z, np.abs(v), w.variance, w.lengthscale, rows=rows)
         rel = float((np.abs(got - ref) / np.maximum(mag, 1e-300)).max())
         parity = {"rows": len(rows), "max_abs_err_over_sum_of_magnitudes": rel}
         log(f"[bench] oracle: {cpu_baseline['value']:.3e} pairs/s on {threads} threads; parity {parity}")
@@ -153,7 +162,7 @@ def bench_kmv(args) -> int:
         "metric": "kernel-matrix entries per second, y = K v with a squared-exponential kernel (n*m/s)",
         "value": value, "unit": "pairs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "m": w.m, "d": w.d, "variance": w.variance,
                    "lengthscale": w.lengthscale, "mem_limit_bytes": limit,
                    "workspace_bytes": plan.workspace_bytes, "point_ranges": plan.n_splits,
@@ -169,7 +178,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c2", help="c1..c7 (default c2, the metric's workload; c6 cosine, c7 L1), or kmv1 / kmv2: "
+    ap.add_argument("--workload", default="c2", help="c1..c7 (default c2, the metric's workload; c6 cosine, c7 L1), or kmv1 / kmv2 / kmv3: "
                          "the kernel matrix-vector product")
     ap.add_argument("--mem-limit", default=None, help="e.g. 128MB, 1GB (decimal); default: the workload's")
     ap.add_argument("--m", type=int, default=None, help="override the query count (testing)")

@@ -12,9 +12,11 @@
  * The n x m matrix K is the big intermediate of section 4.3: it is produced
  * tile by tile in registers, multiplied by the matching piece of v and summed
  * at once, so it never exists in memory.  The paper evaluates the expression
- * in double precision; here the points are fp32, each K entry is evaluated in
- * fp32 (one hardware exp2 per pair) and every sum longer than 64 terms is
- * carried in fp64.  y is fp64.
+ * in double precision.  Two families of entry points: kmv_plan / kmv_apply
+ * take fp32 points, evaluate each K entry in fp32 (one hardware exp2 per pair)
+ * and carry every sum longer than 64 terms in fp64; kmv_plan_f64 /
+ * kmv_apply_f64 take fp64 points and compute in fp64 throughout.  y is fp64
+ * in both.
  */
 #ifndef KMV_MI355X_H
 #define KMV_MI355X_H
@@ -30,6 +32,7 @@ extern "C" {
 /* kernel families (kmv_plan_t.path) */
 #define KMV_PATH_LOWD 0 /* d <= 8: difference-form squared distance on the vector ALU   */
 #define KMV_PATH_MFMA 1 /* d  > 8: section 4.1 expansion, fp32 matrix-core tile of X Z^T */
+#define KMV_PATH_VALU 2 /* fp64 entry points, d > 8: difference form, row re-read in chunks */
 
 /*
  * The plan.  One workgroup owns tile_rows rows of X (one row of K per lane)
@@ -81,6 +84,23 @@ int kmv_plan(int64_t n, int64_t m, int32_t d, int64_t mem_limit_bytes, kmv_plan_
 int kmv_apply(const float* X, int64_t ldx, const float* Z, int64_t ldz, const float* v, int64_t n,
               int64_t m, int32_t d, double variance, double lengthscale, int64_t mem_limit_bytes,
               void* workspace, int64_t workspace_bytes, double* y, void* stream);
+
+/*
+ * The same product in the precision section 5.1 evaluates it in: X, Z, v are
+ * fp64 (DEVICE, row-major, leading dimensions in elements) and every
+ * operation is fp64 - difference-form squared distance with the columns in
+ * ascending order, the math library's exp, one fused multiply-add per point
+ * into a single accumulator with the points in ascending order (per range).
+ * Vector-ALU kernels for every d (path 0 or 2); the workspace holds only the
+ * partial sums of the ranges (norms_bytes == 0).  Otherwise as kmv_plan /
+ * kmv_apply.
+ */
+int kmv_plan_f64(int64_t n, int64_t m, int32_t d, int64_t mem_limit_bytes, kmv_plan_t* out);
+
+int kmv_apply_f64(const double* X, int64_t ldx, const double* Z, int64_t ldz, const double* v,
+                  int64_t n, int64_t m, int32_t d, double variance, double lengthscale,
+                  int64_t mem_limit_bytes, void* workspace, int64_t workspace_bytes, double* y,
+                  void* stream);
 
 #ifdef __cplusplus
 }

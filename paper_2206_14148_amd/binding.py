@@ -32,10 +32,11 @@ EXPORTED_SYMBOLS = (
     "knn_plan", "knn_workspace_bytes", "knn_search", "knn_last_stats", "knn_status_string",
     "knn_parse_size", "knn_chunk_rows", "knn_last_hip_error", "knn_profile_enable",
     "knn_profile_read", "knn_plan_metric", "knn_search_metric",
-    "kmv_plan", "kmv_apply",
+    "kmv_plan", "kmv_apply", "kmv_plan_f64", "kmv_apply_f64",
 )
 KMV_PATH_LOWD = 0
 KMV_PATH_MFMA = 1
+KMV_PATH_VALU = 2
 
 
 class KmvPlanStruct(ctypes.Structure):
@@ -150,6 +151,10 @@ def load():
     lib.kmv_apply.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, ctypes.c_double, ctypes.c_double,
                               i64, vp, i64, vp, vp]
     lib.kmv_apply.restype = ctypes.c_int
+    lib.kmv_plan_f64.argtypes = lib.kmv_plan.argtypes
+    lib.kmv_plan_f64.restype = ctypes.c_int
+    lib.kmv_apply_f64.argtypes = lib.kmv_apply.argtypes
+    lib.kmv_apply_f64.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -265,9 +270,11 @@ def knn_search(Q, X, k: int, mem_limit_bytes: int, workspace=None, out=None, met
     return idx, dist
 
 
-def kmv_plan(n: int, m: int, d: int, mem_limit_bytes: int) -> KmvPlan:
+def kmv_plan(n: int, m: int, d: int, mem_limit_bytes: int, dtype: str = "f32") -> KmvPlan:
+    """dtype "f32": the plan of kmv_apply on fp32 points; "f64": of the all-fp64 entry point."""
     ps = KmvPlanStruct()
-    st = int(load().kmv_plan(n, m, d, mem_limit_bytes, ctypes.byref(ps)))
+    fn = {"f32": load().kmv_plan, "f64": load().kmv_plan_f64}[dtype]
+    st = int(fn(n, m, d, mem_limit_bytes, ctypes.byref(ps)))
     if st != KNN_OK:
         raise KnnError(st, knn_status_string(st) + f" (needs at least {ps.min_limit_bytes} bytes)"
                        if st == KNN_ERR_MEM_LIMIT_TOO_SMALL else knn_status_string(st))
@@ -275,27 +282,28 @@ def kmv_plan(n: int, m: int, d: int, mem_limit_bytes: int) -> KmvPlan:
 
 
 def kmv_apply_raw(x_ptr, ldx, z_ptr, ldz, v_ptr, n, m, d, variance, lengthscale, mem_limit_bytes,
-                  ws_ptr, ws_bytes, y_ptr, stream_ptr) -> int:
+                  ws_ptr, ws_bytes, y_ptr, stream_ptr, dtype: str = "f32") -> int:
     """Direct call, raw integers for pointers; returns the status code."""
-    return int(load().kmv_apply(x_ptr, ldx, z_ptr, ldz, v_ptr, n, m, d, float(variance),
-                                float(lengthscale), mem_limit_bytes, ws_ptr, ws_bytes, y_ptr,
-                                stream_ptr))
+    fn = {"f32": load().kmv_apply, "f64": load().kmv_apply_f64}[dtype]
+    return int(fn(x_ptr, ldx, z_ptr, ldz, v_ptr, n, m, d, float(variance),
+                  float(lengthscale), mem_limit_bytes, ws_ptr, ws_bytes, y_ptr, stream_ptr))
 
 
 def kmv_apply(X, Z, v, variance: float, lengthscale: float, mem_limit_bytes: int, workspace=None,
               out=None):
     """kmv_apply(X[n,d], Z[m,d], v[m], variance, lengthscale, mem_limit_bytes) -> y fp64[n].
 
-    y = K(X, Z) v with the squared-exponential kernel.  X, Z, v are fp32 device tensors (rows
-    may be strided).  The workspace (uint8, plan.workspace_bytes) is allocated here unless
+    y = K(X, Z) v with the squared-exponential kernel.  X, Z, v are device tensors, all fp32
+    or all fp64 (the all-fp64 entry point then runs); rows may be strided.  The workspace (uint8, plan.workspace_bytes) is allocated here unless
     given.  Work is enqueued on torch's current stream; no synchronisation is done.
     """
     import torch
 
     if not (X.is_cuda and Z.is_cuda and v.is_cuda):
         raise KnnError(KNN_ERR_INVALID_ARG, "X, Z and v must be device tensors (no CPU path exists)")
-    if X.dtype != torch.float32 or Z.dtype != torch.float32 or v.dtype != torch.float32:
-        raise KnnError(KNN_ERR_INVALID_ARG, "X, Z and v must be float32")
+    if X.dtype not in (torch.float32, torch.float64) or Z.dtype != X.dtype or v.dtype != X.dtype:
+        raise KnnError(KNN_ERR_INVALID_ARG, "X, Z and v must be all float32 or all float64")
+    dtype = "f32" if X.dtype == torch.float32 else "f64"
     if X.dim() != 2 or Z.dim() != 2 or v.dim() != 1 or X.shape[1] != Z.shape[1]:
         raise KnnError(KNN_ERR_INVALID_ARG, "X and Z must be 2-D with the same d, v 1-D")
     if v.shape[0] != Z.shape[0] or X.stride(1) != 1 or Z.stride(1) != 1 or \
@@ -303,7 +311,7 @@ def kmv_apply(X, Z, v, variance: float, lengthscale: float, mem_limit_bytes: int
         raise KnnError(KNN_ERR_INVALID_ARG, "v must have m contiguous entries; unit column strides")
     n, d = X.shape
     m = Z.shape[0]
-    plan = kmv_plan(n, m, d, mem_limit_bytes)
+    plan = kmv_plan(n, m, d, mem_limit_bytes, dtype)
     if workspace is None:
         workspace = torch.empty(max(int(plan.workspace_bytes), 256), dtype=torch.uint8,
                                 device=X.device)
@@ -313,7 +321,7 @@ def kmv_apply(X, Z, v, variance: float, lengthscale: float, mem_limit_bytes: int
     ldz = Z.stride(0) if m > 1 else max(d, Z.stride(0))
     st = kmv_apply_raw(X.data_ptr(), ldx, Z.data_ptr(), ldz, v.data_ptr(), n, m, d, variance,
                        lengthscale, mem_limit_bytes, workspace.data_ptr(), workspace.numel(),
-                       y.data_ptr(), stream)
+                       y.data_ptr(), stream, dtype)
     if st != KNN_OK:
         detail = knn_status_string(st)
         if st == KNN_ERR_HIP:

@@ -29,7 +29,9 @@ knn_status hip_fail(hipError_t e, const char* what) {
 
 }  // namespace
 
-extern "C" int kmv_plan(int64_t n, int64_t m, int32_t d, int64_t mem_limit_bytes, kmv_plan_t* out) {
+namespace {
+
+int plan_impl(int64_t n, int64_t m, int32_t d, int64_t mem_limit_bytes, bool f64, kmv_plan_t* out) {
     if (!out) return KNN_ERR_INVALID_ARG;
     std::memset(out, 0, sizeof(*out));
     if (n < 0 || m < 0 || d < 1 || mem_limit_bytes < 0) return KNN_ERR_INVALID_ARG;
@@ -37,11 +39,12 @@ extern "C" int kmv_plan(int64_t n, int64_t m, int32_t d, int64_t mem_limit_bytes
     out->n = n;
     out->m = m;
     out->d = d;
-    const bool lowd = d <= kmv::kLowdMaxD;
-    out->path = lowd ? KMV_PATH_LOWD : KMV_PATH_MFMA;
-    out->tile_rows = lowd ? kmv::kLowdTileRows : kmv::kMfmaTileRows;
+    const bool valu = f64 || d <= kmv::kLowdMaxD;  // vector-ALU kernels: one row per lane
+    const bool lowd = valu;
+    out->path = d <= kmv::kLowdMaxD ? KMV_PATH_LOWD : (f64 ? KMV_PATH_VALU : KMV_PATH_MFMA);
+    out->tile_rows = valu ? kmv::kLowdTileRows : kmv::kMfmaTileRows;
     out->n_splits = 1;
-    out->norms_bytes = lowd ? 0 : align_up(4 * m);
+    out->norms_bytes = valu ? 0 : align_up(4 * m);
     out->min_limit_bytes = out->norms_bytes;
     if (mem_limit_bytes < out->min_limit_bytes) return KNN_ERR_MEM_LIMIT_TOO_SMALL;
     // Ranges: double until the launch has enough workgroups for every CU to hold its share
@@ -57,6 +60,17 @@ extern "C" int kmv_plan(int64_t n, int64_t m, int32_t d, int64_t mem_limit_bytes
     out->partials_bytes = S > 1 ? align_up(8 * n * S) : 0;
     out->workspace_bytes = out->norms_bytes + out->partials_bytes;
     return KNN_OK;
+}
+
+}  // namespace
+
+extern "C" int kmv_plan(int64_t n, int64_t m, int32_t d, int64_t mem_limit_bytes, kmv_plan_t* out) {
+    return plan_impl(n, m, d, mem_limit_bytes, false, out);
+}
+
+extern "C" int kmv_plan_f64(int64_t n, int64_t m, int32_t d, int64_t mem_limit_bytes,
+                            kmv_plan_t* out) {
+    return plan_impl(n, m, d, mem_limit_bytes, true, out);
 }
 
 extern "C" int kmv_apply(const float* X, int64_t ldx, const float* Z, int64_t ldz, const float* v,
@@ -100,6 +114,43 @@ extern "C" int kmv_apply(const float* X, int64_t ldx, const float* Z, int64_t ld
         e = kmv::launch_mfma(X, ldx, Z, ldz, v, zn, n, m, d, c2, variance, S, target, stream);
         if (e != hipSuccess) return hip_fail(e, "kmv matrix-core kernel");
     }
+    if (S > 1) {
+        e = kmv::launch_reduce(partials, S, n, y, stream);
+        if (e != hipSuccess) return hip_fail(e, "kmv reduce kernel");
+    }
+    return KNN_OK;
+}
+
+extern "C" int kmv_apply_f64(const double* X, int64_t ldx, const double* Z, int64_t ldz,
+                             const double* v, int64_t n, int64_t m, int32_t d, double variance,
+                             double lengthscale, int64_t mem_limit_bytes, void* workspace,
+                             int64_t workspace_bytes, double* y, void* stream_v) {
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    kmv_plan_t plan;
+    const int rc = kmv_plan_f64(n, m, d, mem_limit_bytes, &plan);
+    if (rc != KNN_OK) return rc;
+    if (!(variance >= 0.0) || !(lengthscale > 0.0) || !std::isfinite(variance) ||
+        !std::isfinite(lengthscale))
+        return KNN_ERR_INVALID_ARG;
+    if (ldx < d || ldz < d) return KNN_ERR_INVALID_ARG;
+    if (n == 0) return KNN_OK;
+    if (!y || !X) return KNN_ERR_INVALID_ARG;
+    if (m > 0 && (!Z || !v)) return KNN_ERR_INVALID_ARG;
+    if (plan.workspace_bytes > 0) {
+        if (!workspace || reinterpret_cast<uintptr_t>(workspace) % knn::kAlign != 0)
+            return KNN_ERR_INVALID_ARG;
+        if (workspace_bytes < plan.workspace_bytes) return KNN_ERR_WORKSPACE_TOO_SMALL;
+    }
+    hipError_t e;
+    if (m == 0) {
+        e = kmv::launch_zero(y, n, stream);
+        return e == hipSuccess ? KNN_OK : hip_fail(e, "kmv zero");
+    }
+    const double negc = -0.5 / (lengthscale * lengthscale);
+    double* partials = static_cast<double*>(workspace);
+    const int S = plan.n_splits;
+    e = kmv::launch_f64(X, ldx, Z, ldz, v, n, m, d, negc, variance, S, S > 1 ? partials : y, stream);
+    if (e != hipSuccess) return hip_fail(e, "kmv fp64 kernel");
     if (S > 1) {
         e = kmv::launch_reduce(partials, S, n, y, stream);
         if (e != hipSuccess) return hip_fail(e, "kmv reduce kernel");

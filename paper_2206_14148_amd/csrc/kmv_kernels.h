@@ -27,6 +27,12 @@ hipError_t launch_mfma(const float* X, int64_t ldx, const float* Z, int64_t ldz,
                        const float* zn, int64_t n, int64_t m, int d, float c2, double variance, int S,
                        double* out, hipStream_t stream);
 
+// fp64 inputs and arithmetic (the precision of paper section 5.1), any d: d <= kLowdMaxD keeps
+// the row in registers, larger d re-reads it in chunks.  negc = -1 / (2 lengthscale^2).
+hipError_t launch_f64(const double* X, int64_t ldx, const double* Z, int64_t ldz, const double* v,
+                      int64_t n, int64_t m, int d, double negc, double variance, int S, double* out,
+                      hipStream_t stream);
+
 // y[i] = sum_s partials[s * n + i], s ascending.
 hipError_t launch_reduce(const double* partials, int S, int64_t n, double* y, hipStream_t stream);
 

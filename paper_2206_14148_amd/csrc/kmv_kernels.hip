@@ -286,6 +286,110 @@ __global__ __launch_bounds__(256, 2) void kmv_mfma_kernel(
     if (active && h == 0) out[(int64_t)s * n + r] = variance * (sum + other);
 }
 
+// ---------------------------------------------------------------------------------------
+// fp64 variant, d <= 8: the low-d kernel with every operation in fp64 and the library's exp.
+// The sum runs over j ascending in one fp64 accumulator.
+// ---------------------------------------------------------------------------------------
+template <int D, bool CONTIG>
+__global__ __launch_bounds__(kLowdTileRows) void kmv_lowd_f64_kernel(
+    const double* __restrict__ X, int64_t ldx, const double* __restrict__ Z, int64_t ldz_arg,
+    const double* __restrict__ v, int n, int m, int split_len, double negc, double variance,
+    double* __restrict__ out) {
+    constexpr int U = 4;
+    const int64_t ldz = CONTIG ? (int64_t)D : ldz_arg;
+    const int s = blockIdx.y;
+    const int i = blockIdx.x * kLowdTileRows + threadIdx.x;
+    const bool active = i < n;
+    double x[D];
+#pragma unroll
+    for (int t = 0; t < D; ++t) x[t] = active ? X[(int64_t)i * ldx + t] : 0.0;
+
+    auto term = [&](const double* __restrict__ zp, double vj, double total) {
+        double df = x[0] - zp[0];
+        double sq = df * df;
+#pragma unroll
+        for (int t = 1; t < D; ++t) {
+            df = x[t] - zp[t];
+            sq = fma(df, df, sq);
+        }
+        return fma(exp(sq * negc), vj, total);
+    };
+
+    const int j0 = s * split_len;
+    const int j1 = min(m, j0 + split_len);
+    const double* zp = Z + (int64_t)j0 * ldz;  // uniform: read with scalar loads
+    const double* vp = v + j0;
+    double total = 0.0;
+    int j = j0;
+    for (; j + U <= j1; j += U, zp += U * ldz, vp += U) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) total = term(zp + u * ldz, vp[u], total);
+    }
+    for (; j < j1; ++j, zp += ldz, ++vp) total = term(zp, vp[0], total);
+    if (active) out[(int64_t)s * n + i] = variance * total;
+}
+
+// ---------------------------------------------------------------------------------------
+// fp64 variant, any d: one row per lane; a group of 8 wave-uniform points (scalar loads)
+// keeps one running squared distance each while the row is walked in chunks of 4 columns,
+// so a row value is loaded once per 8 points.  Columns in ascending order, points in
+// ascending order, one fp64 accumulator.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kLowdTileRows) void kmv_anyd_f64_kernel(
+    const double* __restrict__ X, int64_t ldx, const double* __restrict__ Z, int64_t ldz,
+    const double* __restrict__ v, int n, int m, int d, int split_len, double negc, double variance,
+    double* __restrict__ out) {
+    constexpr int P = 8, TC = 4;
+    const int s = blockIdx.y;
+    const int i = blockIdx.x * kLowdTileRows + threadIdx.x;
+    const bool active = i < n;
+    const double* __restrict__ xrow = X + (int64_t)(active ? i : n - 1) * ldx;  // in bounds for idle lanes
+    const int j0 = s * split_len;
+    const int j1 = min(m, j0 + split_len);
+    const double* zp = Z + (int64_t)j0 * ldz;  // uniform
+    const double* vp = v + j0;
+    double total = 0.0;
+    int j = j0;
+    for (; j + P <= j1; j += P, zp += P * ldz, vp += P) {
+        double sq[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) sq[p] = 0.0;
+        int c = 0;
+        for (; c + TC <= d; c += TC) {
+            double xr[TC];
+#pragma unroll
+            for (int t = 0; t < TC; ++t) xr[t] = xrow[c + t];
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+#pragma unroll
+                for (int t = 0; t < TC; ++t) {
+                    const double df = xr[t] - zp[p * ldz + c + t];
+                    sq[p] = fma(df, df, sq[p]);
+                }
+            }
+        }
+        for (; c < d; ++c) {
+            const double xr = xrow[c];
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                const double df = xr - zp[p * ldz + c];
+                sq[p] = fma(df, df, sq[p]);
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < P; ++p) total = fma(exp(sq[p] * negc), vp[p], total);
+    }
+    for (; j < j1; ++j, zp += ldz, ++vp) {
+        double sq = 0.0;
+        for (int c = 0; c < d; ++c) {
+            const double df = xrow[c] - zp[c];
+            sq = fma(df, df, sq);
+        }
+        total = fma(exp(sq * negc), vp[0], total);
+    }
+    if (active) out[(int64_t)s * n + i] = variance * total;
+}
+
 int64_t split_length(int64_t m, int S, int tile) {
     int64_t len = (m + S - 1) / S;
     return (len + tile - 1) / tile * tile;
@@ -345,6 +449,44 @@ hipError_t launch_lowd(const float* X, int64_t ldx, const float* Z, int64_t ldz,
         case 8: return launch_lowd_d<8>(X, ldx, Z, ldz, v, n, m, c2, variance, S, out, stream);
         default: return hipErrorInvalidValue;
     }
+}
+
+template <int D>
+static hipError_t launch_f64_d(const double* X, int64_t ldx, const double* Z, int64_t ldz,
+                               const double* v, int64_t n, int64_t m, double negc, double variance,
+                               int S, double* out, hipStream_t stream) {
+    const dim3 grid((unsigned)((n + kLowdTileRows - 1) / kLowdTileRows), (unsigned)S);
+    const int split_len = (int)split_length(m, S, kGroup);
+    if (ldz == D) {
+        kmv_lowd_f64_kernel<D, true><<<grid, dim3(kLowdTileRows), 0, stream>>>(
+            X, ldx, Z, ldz, v, (int)n, (int)m, split_len, negc, variance, out);
+    } else {
+        kmv_lowd_f64_kernel<D, false><<<grid, dim3(kLowdTileRows), 0, stream>>>(
+            X, ldx, Z, ldz, v, (int)n, (int)m, split_len, negc, variance, out);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_f64(const double* X, int64_t ldx, const double* Z, int64_t ldz, const double* v,
+                      int64_t n, int64_t m, int d, double negc, double variance, int S, double* out,
+                      hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    switch (d) {
+        case 1: return launch_f64_d<1>(X, ldx, Z, ldz, v, n, m, negc, variance, S, out, stream);
+        case 2: return launch_f64_d<2>(X, ldx, Z, ldz, v, n, m, negc, variance, S, out, stream);
+        case 3: return launch_f64_d<3>(X, ldx, Z, ldz, v, n, m, negc, variance, S, out, stream);
+        case 4: return launch_f64_d<4>(X, ldx, Z, ldz, v, n, m, negc, variance, S, out, stream);
+        case 5: return launch_f64_d<5>(X, ldx, Z, ldz, v, n, m, negc, variance, S, out, stream);
+        case 6: return launch_f64_d<6>(X, ldx, Z, ldz, v, n, m, negc, variance, S, out, stream);
+        case 7: return launch_f64_d<7>(X, ldx, Z, ldz, v, n, m, negc, variance, S, out, stream);
+        case 8: return launch_f64_d<8>(X, ldx, Z, ldz, v, n, m, negc, variance, S, out, stream);
+        default: break;
+    }
+    const dim3 grid((unsigned)((n + kLowdTileRows - 1) / kLowdTileRows), (unsigned)S);
+    const int split_len = (int)split_length(m, S, kGroup);
+    kmv_anyd_f64_kernel<<<grid, dim3(kLowdTileRows), 0, stream>>>(
+        X, ldx, Z, ldz, v, (int)n, (int)m, d, split_len, negc, variance, out);
+    return hipGetLastError();
 }
 
 hipError_t launch_mfma(const float* X, int64_t ldx, const float* Z, int64_t ldz, const float* v,

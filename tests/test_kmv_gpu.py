@@ -10,6 +10,11 @@ Tolerance (derived from the kernels' arithmetic, eps = 2^-24):
                 <= (d+4) eps c (|x_i| + |z_j|)^2 with c = 1 / (2 l^2).
 Hence  |y_i - oracle_i| <= sum_j |K_ij v_j| * (4e-6 + (d+4) eps * e_ij),  e_ij = a_ij or
 c (|x_i|+|z_j|)^2, plus 1e-37 * variance * sum|v| for entries below the smallest normal fp32.
+
+The all-fp64 entry point does what the oracle does in the same precision with other roundings
+(fused multiply-adds, another exp): with eps = 2^-53 an entry differs by <= a (d+4) eps + 2 eps
+relative on each side and a running sum of m terms by <= m eps of the sum of magnitudes on each
+side:  |y_i - oracle_i| <= 2 sum_j |K_ij v_j| * ((m + 8) eps + (d+4) eps a_ij).
 """
 import sys
 
@@ -221,3 +226,110 @@ def test_full_size_sampled_rows(K, oracle, key, count):
     rows = np.sort(np.random.Generator(np.random.PCG64(5)).choice(w.n, count, replace=False))
     parity(K, oracle, X, Z, v, w.variance, w.lengthscale, limit=w.mem_limit, rows=rows,
            z_is_x=w.z_is_x)
+
+
+# ---------------------------------------------------------------------------------------
+# all-fp64 entry point (kmv_apply_f64), against the fp64-input oracle
+# ---------------------------------------------------------------------------------------
+EPS64 = 2.0 ** -53
+
+
+def parity_f64(K, oracle, X, Z, v, variance, lengthscale, limit=64 * W.MB, rows=None, z_is_x=False):
+    Xd = torch.from_numpy(X).cuda()
+    Zd = Xd if z_is_x else torch.from_numpy(Z).cuda()
+    y = K.kmv_apply(Xd, Zd, torch.from_numpy(v).cuda(), variance, lengthscale, limit)
+    torch.cuda.synchronize()
+    y = y.cpu().numpy()
+    assert y.shape == (X.shape[0],) and y.dtype == np.float64 and np.isfinite(y).all()
+    sel = np.arange(X.shape[0]) if rows is None else np.asarray(rows)
+    ref = oracle.kmv_f64(X, Z, v, variance, lengthscale, rows=None if rows is None else sel)
+    m, d = Z.shape
+    c = 0.5 / lengthscale ** 2
+    tol = np.empty(len(sel))
+    for t, i in enumerate(sel):
+        a = c * ((X[i][None, :] - Z) ** 2).sum(1)
+        mag = variance * np.exp(-a) * np.abs(v)
+        tol[t] = 2 * (mag * ((m + 8) * EPS64 + (d + 4) * EPS64 * a)).sum() + 1e-300
+    err = np.abs(y[sel] - ref)
+    worst = float((err / tol).max()) if len(sel) else 0.0
+    say(f"   kmv f64 parity rows={len(sel)} max err/tol={worst:.3g} max|err|={err.max() if len(sel) else 0:.3g}")
+    assert (err <= tol).all(), f"worst err/tol {worst}"
+    return y
+
+
+# (seed, n, m, d, variance, lengthscale, spread)
+SMALL_F64 = [
+    (100, 1, 1, 1, 1.0, 1.0, 1.0),
+    (101, 700, 1513, 1, 1.0, 1.0, 1.0),    # the appendix case, ragged both ways
+    (102, 257, 66, 3, 2.5, 0.7, 1.0),
+    (103, 300, 777, 8, 1.0, 3.0, 1.0),     # last register-resident dimension
+    (104, 300, 1003, 9, 1.0, 3.0, 1.0),    # chunked rows: two chunks and one column, point tail
+    (105, 260, 1111, 11, 1.7, 4.0, 1.0),   # three tail columns
+    (106, 260, 1112, 20, 1.0, 4.0, 1.0),   # whole chunks, whole point groups
+    (107, 140, 700, 300, 1.0, 17.0, 1.0),
+    (108, 400, 800, 2, 1.0, 1.0, 1e4),     # coordinates far from the origin
+]
+
+
+@pytest.mark.parametrize("case", SMALL_F64, ids=lambda c: "s%d_n%d_m%d_d%d" % c[:4])
+def test_f64_small_cases_match_oracle(K, oracle, case):
+    seed, n, m, d, variance, lengthscale, spread = case
+    say("f64 case", case)
+    X, Z, v = W.random_kmv_case(seed, n, m, d, spread, dtype="f64")
+    parity_f64(K, oracle, X, Z, v, variance, lengthscale)
+
+
+@pytest.mark.parametrize("d", [2, 16])
+def test_f64_point_ranges_strides_and_guard(K, oracle, d):
+    n, m = 300, 40000
+    X, Z, v = W.random_kmv_case(120 + d, n, m, d, dtype="f64")
+    ls = 1.0 if d == 2 else 4.0
+    plan = K.kmv_plan(n, m, d, 64 * W.MB, "f64")
+    assert plan.n_splits > 1 and plan.norms_bytes == 0
+    assert K.kmv_plan(n, m, d, 8 * n, "f64").n_splits == 1
+    y1 = parity_f64(K, oracle, X, Z, v, 1.0, ls)
+    y2 = parity_f64(K, oracle, X, Z, v, 1.0, ls, limit=8 * n)
+    assert np.allclose(y1, y2, rtol=1e-12, atol=1e-12)
+    # strided rows, caller-owned workspace with guard bytes behind it
+    Xw = torch.full((n, d + 3), 9.0, dtype=torch.float64, device="cuda")
+    Zw = torch.full((m, d + 1), -9.0, dtype=torch.float64, device="cuda")
+    Xw[:, :d] = torch.from_numpy(X).cuda()
+    Zw[:, :d] = torch.from_numpy(Z).cuda()
+    buf = torch.full((plan.workspace_bytes + 4096,), 0xA5, dtype=torch.uint8, device="cuda")
+    y3 = K.kmv_apply(Xw[:, :d], Zw[:, :d], torch.from_numpy(v).cuda(), 1.0, ls, 64 * W.MB,
+                     workspace=buf[:plan.workspace_bytes])
+    torch.cuda.synchronize()
+    assert np.array_equal(y3.cpu().numpy(), y1)
+    assert (buf[plan.workspace_bytes:] == 0xA5).all()
+
+
+def test_f64_resolves_what_fp32_cannot(K, oracle):
+    # points 1e-9 apart around 1.0, lengthscale 1e-9: in fp32 they would coincide
+    X = 1.0 + 1e-9 * np.arange(500, dtype=np.float64).reshape(-1, 1)
+    v = np.random.Generator(np.random.PCG64(3)).standard_normal(500)
+    y = parity_f64(K, oracle, X, X, v, 1.0, 1e-9, z_is_x=True)
+    assert not np.allclose(y, v.sum(), rtol=1e-3)  # far from the all-ones matrix fp32 would see
+
+
+def test_f64_empty_sides_and_errors(K):
+    X = torch.zeros((300, 3), dtype=torch.float64, device="cuda")
+    y = K.kmv_apply(X, torch.empty((0, 3), dtype=torch.float64, device="cuda"),
+                    torch.empty((0,), dtype=torch.float64, device="cuda"), 1.0, 1.0, 64 * W.MB,
+                    out=torch.full((300,), 7.0, dtype=torch.float64, device="cuda"))
+    torch.cuda.synchronize()
+    assert (y.cpu().numpy() == 0).all()
+    with pytest.raises(K.KnnError) as ei:
+        K.kmv_apply(X, X, torch.zeros(300, dtype=torch.float32, device="cuda"), 1.0, 1.0, 64 * W.MB)
+    assert ei.value.status == K.KNN_ERR_INVALID_ARG  # mixed precisions
+    with pytest.raises(K.KnnError) as ei:
+        K.kmv_apply(X, X, torch.zeros(300, dtype=torch.float64, device="cuda"), 1.0, -2.0, 64 * W.MB)
+    assert ei.value.status == K.KNN_ERR_INVALID_ARG
+
+
+def test_f64_full_size_sampled_rows(K, oracle):
+    w = W.KMV_WORKLOADS["kmv3"]
+    say("full size", w)
+    X, Z, v = W.make_kmv(w)
+    rows = np.sort(np.random.Generator(np.random.PCG64(6)).choice(w.n, 16, replace=False))
+    parity_f64(K, oracle, X, Z, v, w.variance, w.lengthscale, limit=w.mem_limit, rows=rows,
+               z_is_x=True)

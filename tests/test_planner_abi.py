@@ -16,7 +16,7 @@ def declared_symbols():
     for header in ("knn.h", "kmv.h"):
         text = open(os.path.join(ROOT, "include", header)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names |= set(re.findall(r"\b(k(?:nn|mv)_[a-z_]+)\s*\(", text))
+        names |= set(re.findall(r"\b(k(?:nn|mv)_[a-z0-9_]+)\s*\(", text))
     return sorted(names)
 
 

@@ -186,6 +186,7 @@ class KmvWorkload:
     mem_limit: int
     z_is_x: bool = True  # square kernel matrix of one point set
     stream: int = 0
+    dtype: str = "f32"   # "f64": fp64 inputs for the all-fp64 entry point (the paper's precision)
 
     @property
     def pairs(self) -> int:
@@ -196,6 +197,9 @@ KMV_WORKLOADS = {
     "kmv1": KmvWorkload("kmv1_d1", 1_000_000, 1_000_000, 1, 1.0, 1.0, 1 * GB),
     # a multi-dimensional input set on the matrix-core path, lengthscale of the order sqrt(d)
     "kmv2": KmvWorkload("kmv2_d32", 200_000, 200_000, 32, 1.0, 6.0, 1 * GB, stream=1),
+    # the appendix case in the precision the paper evaluates it in
+    "kmv3": KmvWorkload("kmv3_d1_f64", 1_000_000, 1_000_000, 1, 1.0, 1.0, 1 * GB, stream=2,
+                        dtype="f64"),
 }
 
 
@@ -211,8 +215,12 @@ def scaled_kmv(key: str, n: int | None = None, m: int | None = None, **kw) -> Km
 
 
 def make_kmv(w: KmvWorkload):
-    """Returns (X, Z, v): float32 [n,d], [m,d] (X itself when z_is_x) and [m]."""
+    """Returns (X, Z, v): [n,d], [m,d] (X itself when z_is_x) and [m], float32 or float64."""
     rng = np.random.Generator(np.random.PCG64(SEED_BASE + 9_000_000 + w.stream))
+    if w.dtype == "f64":
+        X = rng.standard_normal((w.n, w.d))
+        Z = X if w.z_is_x else rng.standard_normal((w.m, w.d))
+        return X, Z, rng.standard_normal(w.m)
     X = np.empty((w.n, w.d), dtype=np.float32)
     _fill_normal(rng, X)
     if w.z_is_x:
@@ -225,9 +233,12 @@ def make_kmv(w: KmvWorkload):
     return X, Z, v
 
 
-def random_kmv_case(seed: int, n: int, m: int, d: int, spread: float = 1.0):
+def random_kmv_case(seed: int, n: int, m: int, d: int, spread: float = 1.0, dtype: str = "f32"):
     """Small free-form case: normal points with the given spread, normal v."""
     rng = np.random.Generator(np.random.PCG64(SEED_BASE + 8_000_000 + seed))
+    if dtype == "f64":
+        return (spread * rng.standard_normal((n, d)), spread * rng.standard_normal((m, d)),
+                rng.standard_normal(m))
     X = (np.float32(spread) * rng.standard_normal((n, d), dtype=np.float32)).astype(np.float32)
     Z = (np.float32(spread) * rng.standard_normal((m, d), dtype=np.float32)).astype(np.float32)
     v = rng.standard_normal((m,), dtype=np.float32)
