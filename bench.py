@@ -185,6 +185,10 @@ def main() -> int:
     ap.add_argument("--n", type=int, default=None, help="override the point count (testing)")
     ap.add_argument("--k", type=int, default=None, help="override the neighbour count (testing)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle time budget; 0 skips it")
+    ap.add_argument("--host-x", action="store_true",
+                    help="also time knn_search_host_x: the same search with X in pinned host memory, "
+                         "streamed through staging buffers inside the limit (PCIe-inclusive; reported "
+                         "beside the resident figure, never as `value`)")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="also run one plain elementwise copy of this many MB (read + write) before "
                          "the timed region, as the known-size reference for rocprofv3 --pmc byte counters")
@@ -347,6 +351,30 @@ def main() -> int:
                 f"workspace {p2.workspace_bytes} B, same result: {sweep[-1]['same_result']}")
             del ws2, i2, d2
 
+    host_streamed = None
+    if args.host_x:
+        hp = K.knn_plan_host_x(w.m, w.n, w.d, w.k, limit, w.metric)
+        Xp = torch.from_numpy(X).pin_memory()
+        ws3 = torch.empty(max(hp.workspace_bytes, 256), dtype=torch.uint8, device=dev)
+        i3 = torch.empty_like(idx)
+        d3 = torch.empty_like(dist)
+        K.knn_search_host_x(Qd, Xp, w.k, limit, workspace=ws3, out=(i3, d3), metric=w.metric)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            K.knn_search_host_x(Qd, Xp, w.k, limit, workspace=ws3, out=(i3, d3), metric=w.metric)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        host_streamed = {"ms_per_step": dt * 1e3, "pairs_per_s": pairs / dt,
+                         "h2d_GB_per_s": X.nbytes / dt / 1e9, "x_bytes": X.nbytes,
+                         "n_blocks": hp.n_blocks, "block_rows": hp.block_rows,
+                         "workspace_bytes": hp.workspace_bytes,
+                         "same_distances": bool(torch.equal(d3, dist)),
+                         "same_indices_fraction": float((i3 == idx).float().mean())}
+        log(f"[bench] host-streamed X: {dt*1e3:.1f} ms/step, {pairs/dt:.3e} pairs/s, "
+            f"{X.nbytes/dt/1e9:.1f} GB/s over the host link, {hp.n_blocks} blocks of {hp.block_rows}")
+        del ws3, i3, d3, Xp
+
     out = {
         "metric": "query-point pairs per second, exact brute-force kNN (m*n/s)",
         "value": value, "unit": "pairs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -363,6 +391,8 @@ def main() -> int:
     }
     if sweep is not None:
         out["mem_limit_sweep"] = sweep
+    if host_streamed is not None:
+        out["host_streamed_x"] = host_streamed
     print(json.dumps(out), flush=True)
     return 0
 

@@ -180,6 +180,60 @@ knn_status knn_profile_enable(int32_t on);
 knn_status knn_profile_read(float *norms_ms /* HOST */, float *search_ms /* HOST */,
                             float *refine_ms /* HOST */, int64_t *search_launches /* HOST */);
 
+/*
+ * Data points in HOST memory, streamed through the workspace.
+ *
+ * Section 5.1 reports data set sizes "far beyond" the device's memory capacity once every
+ * intermediate is bounded.  Here the n x d matrix X itself may stay in host memory: it is cut
+ * into blocks of block_rows rows; block b+1 is copied host-to-device into one of two staging
+ * buffers (inside the workspace, so they count against the limit) by an internal copy stream
+ * while block b is searched on the caller's stream with the kernels of knn_search; each block's
+ * k best per query (exact fp64 re-evaluation included, done while the block is on the device)
+ * are folded into the running result held in idx / dist.
+ *
+ * The plan: workspace = staging (two buffers of block_rows x d fp32, one if n_blocks == 1)
+ *           + block_out (one block's idx and dist, m x k each) + the workspace of `inner`,
+ *           the knn_plan_metric of one full block under inner_limit_bytes.
+ */
+typedef struct {
+    int64_t m, n;
+    int32_t d, k;
+    int32_t metric, reserved;
+    int64_t block_rows;         /* rows of X per staged block (the last may be shorter) */
+    int64_t n_blocks;
+    uint64_t staging_bytes;
+    uint64_t block_out_bytes;
+    uint64_t inner_limit_bytes; /* limit handed to the plan of a block */
+    uint64_t workspace_bytes;   /* <= mem_limit_bytes */
+    uint64_t min_limit_bytes;
+    knn_plan_t inner;           /* plan of one full block: (m, block_rows, d, min(k, block_rows)) */
+} knn_host_plan_t;
+
+/* HOST.  Errors as knn_plan_metric. */
+knn_status knn_plan_host_x(int64_t m, int64_t n, int32_t d, int32_t k, knn_metric metric,
+                           uint64_t mem_limit_bytes, knn_host_plan_t *out /* HOST */);
+
+/*
+ * knn_search_host_x - knn_search_metric with X in HOST memory.
+ *   X [n, d], ldx   HOST in, row-major fp32; pinned memory (hipHostMalloc) lets the copies
+ *                   overlap the search, pageable memory works but serialises them.  Must stay
+ *                   valid and unchanged until the caller has synchronised hip_stream.
+ *   Q, idx, dist, workspace   DEVICE, as in knn_search; workspace_bytes >=
+ *                   knn_plan_host_x(...).workspace_bytes
+ * Result: the same neighbours and distances as knn_search_metric on a device copy of X.  The
+ * running result is merged on the fp32 distances, so among neighbours of one query whose
+ * distances round to the same fp32 value the order (and, at the k-th place, the choice) follows
+ * the block order, lower block first, rather than the fp64 values.
+ * The call enqueues work on hip_stream and on one internal stream (created on first use, default
+ * priority) ordered against it with events; it returns without waiting for the GPU when X is
+ * pinned.  It allocates no device memory.  Calls of one host thread that share a workspace
+ * must be made on the same hip_stream or be synchronised by the caller.
+ */
+knn_status knn_search_host_x(const float *Q, int64_t ldq, const float *X /* HOST */, int64_t ldx,
+                             int64_t m, int64_t n, int32_t d, int32_t k, knn_metric metric,
+                             uint64_t mem_limit_bytes, void *workspace, uint64_t workspace_bytes,
+                             int32_t *idx, float *dist, void *hip_stream);
+
 /* Last HIP error text seen by this thread ("" if none). */
 const char *knn_last_hip_error(void);
 

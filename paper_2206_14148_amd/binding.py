@@ -33,6 +33,7 @@ EXPORTED_SYMBOLS = (
     "knn_parse_size", "knn_chunk_rows", "knn_last_hip_error", "knn_profile_enable",
     "knn_profile_read", "knn_plan_metric", "knn_search_metric",
     "kmv_plan", "kmv_apply", "kmv_plan_f64", "kmv_apply_f64",
+    "knn_plan_host_x", "knn_search_host_x",
 )
 KMV_PATH_LOWD = 0
 KMV_PATH_MFMA = 1
@@ -75,6 +76,35 @@ class PlanStruct(ctypes.Structure):
         ("norms_bytes", ctypes.c_uint64), ("lists_bytes", ctypes.c_uint64),
         ("workspace_bytes", ctypes.c_uint64), ("min_limit_bytes", ctypes.c_uint64),
     ]
+
+
+class HostPlanStruct(ctypes.Structure):
+    _fields_ = [
+        ("m", ctypes.c_int64), ("n", ctypes.c_int64),
+        ("d", ctypes.c_int32), ("k", ctypes.c_int32),
+        ("metric", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("block_rows", ctypes.c_int64), ("n_blocks", ctypes.c_int64),
+        ("staging_bytes", ctypes.c_uint64), ("block_out_bytes", ctypes.c_uint64),
+        ("inner_limit_bytes", ctypes.c_uint64), ("workspace_bytes", ctypes.c_uint64),
+        ("min_limit_bytes", ctypes.c_uint64), ("inner", PlanStruct),
+    ]
+
+
+@dataclass(frozen=True)
+class HostPlan:
+    m: int
+    n: int
+    d: int
+    k: int
+    metric: int
+    block_rows: int
+    n_blocks: int
+    staging_bytes: int
+    block_out_bytes: int
+    inner_limit_bytes: int
+    workspace_bytes: int
+    min_limit_bytes: int
+    inner: "Plan"
 
 
 @dataclass(frozen=True)
@@ -146,6 +176,11 @@ def load():
     lib.knn_profile_read.restype = ctypes.c_int
     lib.knn_last_hip_error.argtypes = []
     lib.knn_last_hip_error.restype = ctypes.c_char_p
+    lib.knn_plan_host_x.argtypes = [i64, i64, i32, i32, ctypes.c_int, u64,
+                                    ctypes.POINTER(HostPlanStruct)]
+    lib.knn_plan_host_x.restype = ctypes.c_int
+    lib.knn_search_host_x.argtypes = lib.knn_search_metric.argtypes
+    lib.knn_search_host_x.restype = ctypes.c_int
     lib.kmv_plan.argtypes = [i64, i64, i32, i64, ctypes.POINTER(KmvPlanStruct)]
     lib.kmv_plan.restype = ctypes.c_int
     lib.kmv_apply.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, ctypes.c_double, ctypes.c_double,
@@ -328,3 +363,61 @@ def kmv_apply(X, Z, v, variance: float, lengthscale: float, mem_limit_bytes: int
             detail += " (" + load().knn_last_hip_error().decode() + ")"
         raise KnnError(st, detail)
     return y
+
+
+def knn_plan_host_x(m: int, n: int, d: int, k: int, mem_limit_bytes: int,
+                    metric: str = "l2") -> HostPlan:
+    ps = HostPlanStruct()
+    st = int(load().knn_plan_host_x(m, n, d, k, METRICS[metric], mem_limit_bytes, ctypes.byref(ps)))
+    if st != KNN_OK:
+        raise KnnError(st, knn_status_string(st), int(ps.min_limit_bytes))
+    vals = {f[0]: getattr(ps, f[0]) for f in HostPlanStruct._fields_ if f[0] not in ("reserved", "inner")}
+    return HostPlan(inner=_plan_from_struct(ps.inner), **vals)
+
+
+def knn_search_host_x(Q, X_host, k: int, mem_limit_bytes: int, workspace=None, out=None,
+                      metric: str = "l2"):
+    """knn_search with the data points in HOST memory, streamed through the workspace.
+
+    Q: fp32 device tensor [m, d].  X_host: fp32 [n, d] in host memory - a CPU torch tensor
+    (pinned memory lets the copies overlap the search) or a C-contiguous numpy array; it must
+    stay alive and unchanged until the stream has been synchronised.
+    """
+    import numpy as np
+    import torch
+
+    if isinstance(X_host, np.ndarray):
+        if X_host.dtype != np.float32 or X_host.ndim != 2 or not X_host.flags.c_contiguous:
+            raise KnnError(KNN_ERR_INVALID_ARG, "X_host must be a C-contiguous 2-D float32 array")
+        x_ptr, n, d, ldx = X_host.ctypes.data, X_host.shape[0], X_host.shape[1], X_host.shape[1]
+    else:
+        if X_host.is_cuda or X_host.dtype != torch.float32 or X_host.dim() != 2 or \
+                X_host.stride(1) != 1:
+            raise KnnError(KNN_ERR_INVALID_ARG, "X_host must be a 2-D float32 CPU tensor")
+        n, d = X_host.shape
+        x_ptr = X_host.data_ptr()
+        ldx = X_host.stride(0) if n > 1 else max(d, X_host.stride(0))
+    if not Q.is_cuda or Q.dtype != torch.float32 or Q.dim() != 2 or Q.shape[1] != d or \
+            Q.stride(1) != 1:
+        raise KnnError(KNN_ERR_INVALID_ARG, "Q must be a 2-D float32 device tensor with X's d")
+    m = Q.shape[0]
+    plan = knn_plan_host_x(m, n, d, k, mem_limit_bytes, metric)
+    if workspace is None:
+        workspace = torch.empty(max(int(plan.workspace_bytes), 256), dtype=torch.uint8,
+                                device=Q.device)
+    if out is None:
+        idx = torch.empty((m, k), dtype=torch.int32, device=Q.device)
+        dist = torch.empty((m, k), dtype=torch.float32, device=Q.device)
+    else:
+        idx, dist = out
+    stream = torch.cuda.current_stream(Q.device).cuda_stream
+    ldq = Q.stride(0) if m > 1 else max(d, Q.stride(0))
+    st = int(load().knn_search_host_x(Q.data_ptr(), ldq, x_ptr, ldx, m, n, d, k, METRICS[metric],
+                                      mem_limit_bytes, workspace.data_ptr(), workspace.numel(),
+                                      idx.data_ptr(), dist.data_ptr(), stream))
+    if st != KNN_OK:
+        detail = knn_status_string(st)
+        if st == KNN_ERR_HIP:
+            detail += " (" + load().knn_last_hip_error().decode() + ")"
+        raise KnnError(st, detail)
+    return idx, dist

@@ -136,31 +136,14 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
                              workspace, workspace_bytes, idx, dist, hip_stream);
 }
 
-extern "C" knn_status knn_search_metric(const float* Q, int64_t ldq, const float* X, int64_t ldx,
-                                        int64_t m, int64_t n, int32_t d, int32_t k,
-                                        knn_metric metric, uint64_t mem_limit_bytes,
-                                        void* workspace, uint64_t workspace_bytes, int32_t* idx,
-                                        float* dist, void* hip_stream) {
-    using namespace knn;
-    if (m < 0 || n < 1 || d < 1 || k < 1 || (int64_t)k > n) return KNN_ERR_INVALID_ARG;
-    if (ldq < d || ldx < d) return KNN_ERR_INVALID_ARG;
-    if (!X) return KNN_ERR_INVALID_ARG;
-    if (m > 0 && (!Q || !idx || !dist)) return KNN_ERR_INVALID_ARG;
-    knn_plan_t plan;
-    knn_status st = knn_plan_metric(m, n, d, k, metric, mem_limit_bytes, &plan);
-    if (st != KNN_OK) return st;
-    if (m == 0) {
-        g_last_plan = plan;
-        g_last_peak = 0;
-        g_have_last = true;
-        return KNN_OK;
-    }
-    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0)
-        return KNN_ERR_INVALID_ARG;
-    if (workspace_bytes < plan.workspace_bytes) return KNN_ERR_WORKSPACE_TOO_SMALL;
+namespace {
 
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    unsigned char* ws = static_cast<unsigned char*>(workspace);
+// The search of one resident point set under a given plan: norms / packing, then per query
+// chunk the search kernel over all point ranges and the merge + exact re-evaluation.
+knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const float* X,
+                      int64_t ldx, int64_t m, int64_t n, int32_t d, int32_t k, knn_metric metric,
+                      unsigned char* ws, int32_t* idx, float* dist, hipStream_t stream) {
+    using namespace knn;
     float* xn = reinterpret_cast<float*>(ws);
     void* xblocked = plan.x_blocked ? ws + align_up((uint64_t)n * 4) : nullptr;
     float* lk = reinterpret_cast<float*>(ws + plan.norms_bytes);
@@ -216,8 +199,141 @@ extern "C" knn_status knn_search_metric(const float* Q, int64_t ldq, const float
         }
         close_bracket(t2, stream, 2);
     }
+    return KNN_OK;
+}
+
+}  // namespace
+
+extern "C" knn_status knn_search_metric(const float* Q, int64_t ldq, const float* X, int64_t ldx,
+                                        int64_t m, int64_t n, int32_t d, int32_t k,
+                                        knn_metric metric, uint64_t mem_limit_bytes,
+                                        void* workspace, uint64_t workspace_bytes, int32_t* idx,
+                                        float* dist, void* hip_stream) {
+    using namespace knn;
+    if (m < 0 || n < 1 || d < 1 || k < 1 || (int64_t)k > n) return KNN_ERR_INVALID_ARG;
+    if (ldq < d || ldx < d) return KNN_ERR_INVALID_ARG;
+    if (!X) return KNN_ERR_INVALID_ARG;
+    if (m > 0 && (!Q || !idx || !dist)) return KNN_ERR_INVALID_ARG;
+    knn_plan_t plan;
+    knn_status st = knn_plan_metric(m, n, d, k, metric, mem_limit_bytes, &plan);
+    if (st != KNN_OK) return st;
+    if (m == 0) {
+        g_last_plan = plan;
+        g_last_peak = 0;
+        g_have_last = true;
+        return KNN_OK;
+    }
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0)
+        return KNN_ERR_INVALID_ARG;
+    if (workspace_bytes < plan.workspace_bytes) return KNN_ERR_WORKSPACE_TOO_SMALL;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    st = run_search(plan, Q, ldq, X, ldx, m, n, d, k, metric, static_cast<unsigned char*>(workspace),
+                    idx, dist, stream);
+    if (st != KNN_OK) return st;
     g_last_plan = plan;
     g_last_peak = plan.workspace_bytes;
+    g_have_last = true;
+    return KNN_OK;
+}
+
+namespace {
+
+// Copy stream and events of the host-streamed search, one set per host thread and device.
+struct HostStreamState {
+    int device = -1;
+    hipStream_t copy = nullptr;
+    hipEvent_t start = nullptr;
+    hipEvent_t copied[2] = {nullptr, nullptr};
+    hipEvent_t consumed[2] = {nullptr, nullptr};
+};
+thread_local HostStreamState g_host;
+
+hipError_t host_state_init() {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (g_host.copy && g_host.device == dev) return hipSuccess;
+    HostStreamState fresh;
+    fresh.device = dev;
+    e = hipStreamCreateWithFlags(&fresh.copy, hipStreamNonBlocking);
+    if (e != hipSuccess) return e;
+    hipEvent_t* all[5] = {&fresh.start, &fresh.copied[0], &fresh.copied[1], &fresh.consumed[0],
+                          &fresh.consumed[1]};
+    for (hipEvent_t* ev : all) {
+        e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
+        if (e != hipSuccess) return e;
+    }
+    g_host = fresh;  // a set made for another device is left alone: it belongs to that device
+    return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" knn_status knn_search_host_x(const float* Q, int64_t ldq, const float* X, int64_t ldx,
+                                        int64_t m, int64_t n, int32_t d, int32_t k,
+                                        knn_metric metric, uint64_t mem_limit_bytes,
+                                        void* workspace, uint64_t workspace_bytes, int32_t* idx,
+                                        float* dist, void* hip_stream) {
+    using namespace knn;
+    if (m < 0 || n < 1 || d < 1 || k < 1 || (int64_t)k > n) return KNN_ERR_INVALID_ARG;
+    if (ldq < d || ldx < d) return KNN_ERR_INVALID_ARG;
+    if (!X) return KNN_ERR_INVALID_ARG;
+    if (m > 0 && (!Q || !idx || !dist)) return KNN_ERR_INVALID_ARG;
+    knn_host_plan_t hp;
+    knn_status st = knn_plan_host_x(m, n, d, k, metric, mem_limit_bytes, &hp);
+    if (st != KNN_OK) return st;
+    if (m == 0) return KNN_OK;
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % kAlign != 0)
+        return KNN_ERR_INVALID_ARG;
+    if (workspace_bytes < hp.workspace_bytes) return KNN_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = host_state_init();
+    if (e != hipSuccess) return hip_fail(e, "copy stream / events");
+
+    // workspace: [staging 0 | staging 1] [block idx | block dist] [workspace of the block's plan]
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    const uint64_t stage_bytes = hp.staging_bytes / (hp.n_blocks > 1 ? 2 : 1);
+    float* stage[2] = {reinterpret_cast<float*>(ws), reinterpret_cast<float*>(ws + stage_bytes)};
+    int32_t* bidx = reinterpret_cast<int32_t*>(ws + hp.staging_bytes);
+    float* bdist = reinterpret_cast<float*>(ws + hp.staging_bytes + hp.block_out_bytes / 2);
+    unsigned char* inner_ws = ws + hp.staging_bytes + hp.block_out_bytes;
+
+    // the staging buffers may still be in use by earlier work on the caller's stream
+    e = hipEventRecord(g_host.start, stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(g_host.copy, g_host.start, 0);
+    if (e != hipSuccess) return hip_fail(e, "ordering the copy stream");
+
+    const size_t row_bytes = (size_t)d * 4;
+    for (int64_t b = 0; b < hp.n_blocks; ++b) {
+        const int buf = (int)(b & 1);
+        const int64_t j0 = b * hp.block_rows;
+        const int64_t nb = (n - j0 < hp.block_rows) ? (n - j0) : hp.block_rows;
+        const int32_t kb = (int64_t)k < nb ? k : (int32_t)nb;
+        if (b >= 2) {  // the block searched out of this buffer two steps ago must be done with it
+            e = hipStreamWaitEvent(g_host.copy, g_host.consumed[buf], 0);
+            if (e != hipSuccess) return hip_fail(e, "waiting for a staging buffer");
+        }
+        e = hipMemcpy2DAsync(stage[buf], row_bytes, X + j0 * ldx, (size_t)ldx * 4, row_bytes,
+                             (size_t)nb, hipMemcpyHostToDevice, g_host.copy);
+        if (e == hipSuccess) e = hipEventRecord(g_host.copied[buf], g_host.copy);
+        if (e == hipSuccess) e = hipStreamWaitEvent(stream, g_host.copied[buf], 0);
+        if (e != hipSuccess) return hip_fail(e, "host-to-device copy of a block");
+
+        knn_plan_t plan = hp.inner;
+        if (nb != hp.block_rows) {
+            st = knn_plan_metric(m, nb, d, kb, metric, hp.inner_limit_bytes, &plan);
+            if (st != KNN_OK) return st;
+        }
+        st = run_search(plan, Q, ldq, stage[buf], d, m, nb, d, kb, metric, inner_ws, bidx, bdist,
+                        stream);
+        if (st != KNN_OK) return st;
+        e = launch_fold_block(bidx, bdist, kb, j0, b == 0 ? 1 : 0, m, k, idx, dist, stream);
+        if (e == hipSuccess) e = hipEventRecord(g_host.consumed[buf], stream);
+        if (e != hipSuccess) return hip_fail(e, "folding a block into the result");
+    }
+    g_last_plan = hp.inner;
+    g_last_peak = hp.workspace_bytes;
     g_have_last = true;
     return KNN_OK;
 }

@@ -48,4 +48,12 @@ hipError_t launch_merge_refine(const float* Q, int64_t ldq, const float* X, int6
                                const float* lk, const int* li, int32_t* idx, float* dist,
                                hipStream_t stream);
 
+// Running result of a search over blocks of points: idx/dist [rows][k] (ascending by fp32
+// distance) absorb one block's [rows][kb] results, whose indices get `offset` added.  On equal
+// distances the running entries (earlier blocks, lower indices) stay in front.  first != 0:
+// the running result is empty (the block becomes the result, padded with +inf / INT_MAX).
+hipError_t launch_fold_block(const int32_t* bidx, const float* bdist, int kb, int64_t offset,
+                             int first, int64_t rows, int k, int32_t* idx, float* dist,
+                             hipStream_t stream);
+
 }  // namespace knn

@@ -117,7 +117,79 @@ __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
     }
 }
 
+// One wave per query row: both lists are staged in LDS, every element finds its place in the
+// merged order by a binary search over the other list's distances, the first k are written.
+__global__ __launch_bounds__(256) void knn_fold_block_kernel(
+    const int32_t* __restrict__ bidx, const float* __restrict__ bdist, int kb, int offset,
+    int first, int rows, int k, int32_t* __restrict__ idx, float* __restrict__ dist) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    float* ad = reinterpret_cast<float*>(smem) + (size_t)wave * 4 * k;  // running distances [k]
+    int* ai = reinterpret_cast<int*>(ad + k);                           // running indices   [k]
+    float* bd = reinterpret_cast<float*>(ai + k);                       // block distances   [k]
+    int* bi = reinterpret_cast<int*>(bd + k);                           // block indices     [k]
+    const int r = blockIdx.x * 4 + wave;
+    if (r >= rows) return;  // whole wave; no workgroup barrier below
+    const int na = first ? 0 : k;
+    for (int p = lane; p < na; p += kWave) {
+        ad[p] = dist[(size_t)r * k + p];
+        ai[p] = idx[(size_t)r * k + p];
+    }
+    for (int p = lane; p < kb; p += kWave) {
+        bd[p] = bdist[(size_t)r * kb + p];
+        bi[p] = bidx[(size_t)r * kb + p] + offset;
+    }
+    wave_sync();
+    // running element p goes behind the block elements that are strictly closer
+    for (int p = lane; p < na; p += kWave) {
+        const float key = ad[p];
+        int lo = 0, hi = kb;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (bd[mid] < key) lo = mid + 1;
+            else hi = mid;
+        }
+        const int pos = p + lo;
+        if (pos < k) {
+            dist[(size_t)r * k + pos] = key;
+            idx[(size_t)r * k + pos] = ai[p];
+        }
+    }
+    // block element p goes behind the running elements that are closer or equally close
+    for (int p = lane; p < kb; p += kWave) {
+        const float key = bd[p];
+        int lo = 0, hi = na;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (ad[mid] <= key) lo = mid + 1;
+            else hi = mid;
+        }
+        const int pos = p + lo;
+        if (pos < k) {
+            dist[(size_t)r * k + pos] = key;
+            idx[(size_t)r * k + pos] = bi[p];
+        }
+    }
+    // nothing yet for the places beyond the points seen so far
+    for (int p = na + kb + lane; p < k; p += kWave) {
+        dist[(size_t)r * k + p] = kInf;
+        idx[(size_t)r * k + p] = kNoIdx;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_fold_block(const int32_t* bidx, const float* bdist, int kb, int64_t offset,
+                             int first, int64_t rows, int k, int32_t* idx, float* dist,
+                             hipStream_t stream) {
+    const size_t lds = (size_t)4 * 4 * k * 4;
+    hipError_t e = raise_lds_limit(knn_fold_block_kernel, lds);
+    if (e != hipSuccess) return e;
+    knn_fold_block_kernel<<<dim3((unsigned)((rows + 3) / 4)), dim3(256), lds, stream>>>(
+        bidx, bdist, kb, (int)offset, first, (int)rows, k, idx, dist);
+    return hipGetLastError();
+}
 
 hipError_t launch_merge_refine(const float* Q, int64_t ldq, const float* X, int64_t ldx,
                                int64_t rows, int64_t n, int d, int k, int S, int metric,

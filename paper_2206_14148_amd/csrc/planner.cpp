@@ -179,6 +179,82 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     return KNN_OK;
 }
 
+// Host-resident points: the limit pays for two staging buffers, one block's results and the
+// plan of a block.  Staging gets at most half of what is left after the block results, so
+// that the block's own lists keep at least as much; blocks are as long as that allows.
+extern "C" knn_status knn_plan_host_x(int64_t m, int64_t n, int32_t d, int32_t k, knn_metric metric,
+                                      uint64_t mem_limit_bytes, knn_host_plan_t* out) {
+    if (!out) return KNN_ERR_INVALID_ARG;
+    memset(out, 0, sizeof(*out));
+    knn_plan_t probe;
+    // argument checks (and the empty plan for m == 0) are those of the resident search
+    knn_status st = knn_plan_metric(m, n, d, k, metric, UINT64_MAX / 4, &probe);
+    if (st != KNN_OK) return st;
+    out->m = m;
+    out->n = n;
+    out->d = d;
+    out->k = k;
+    out->metric = (int32_t)metric;
+    if (m == 0) return KNN_OK;
+    const uint64_t row = (uint64_t)d * 4;
+    const uint64_t outb = 2 * align_up((uint64_t)m * (uint64_t)k * 4);
+    const int64_t b_floor = n < 1024 ? n : ((int64_t)k > 1024 ? (int64_t)k : 1024);  // shortest block
+    {
+        knn_plan_t smallest;
+        knn_plan_metric(m, b_floor, d, k < b_floor ? k : (int32_t)b_floor, metric, 0, &smallest);
+        const uint64_t bufs = b_floor < n ? 2 : 1;
+        out->min_limit_bytes = outb + bufs * align_up((uint64_t)b_floor * row) + smallest.min_limit_bytes;
+    }
+    out->block_out_bytes = outb;
+    if (mem_limit_bytes < out->min_limit_bytes) return KNN_ERR_MEM_LIMIT_TOO_SMALL;
+    const uint64_t half = (mem_limit_bytes - outb) / 2;
+    // candidate block lengths, longest first: everything at once, what half of the room
+    // stages twice, the shortest block; the first whose block plans fit is taken
+    int64_t cand[3];
+    int ncand = 0;
+    if (align_up((uint64_t)n * row) <= half) cand[ncand++] = n;
+    {
+        int64_t B = (int64_t)(half / 2 / kAlign * kAlign / row);
+        if (B >= 4096) B = B / 4096 * 4096;
+        else if (B >= 128) B = B / 128 * 128;
+        if (B < b_floor) B = b_floor;
+        if (B > n) B = n;
+        if (ncand == 0 || B < cand[ncand - 1]) cand[ncand++] = B;
+    }
+    if (b_floor < cand[ncand - 1]) cand[ncand++] = b_floor;
+    st = KNN_ERR_MEM_LIMIT_TOO_SMALL;
+    uint64_t inner_ws = 0;
+    for (int c = 0; c < ncand; ++c) {
+        const int64_t B = cand[c];
+        const int64_t nb = (n + B - 1) / B;
+        const uint64_t staging = (nb > 1 ? 2 : 1) * align_up((uint64_t)B * row);
+        if (staging + outb > mem_limit_bytes) continue;
+        const uint64_t inner_limit = mem_limit_bytes - outb - staging;
+        knn_plan_t full, tail;
+        if (knn_plan_metric(m, B, d, (int64_t)k < B ? k : (int32_t)B, metric, inner_limit, &full) !=
+            KNN_OK)
+            continue;
+        inner_ws = full.workspace_bytes;
+        const int64_t last = n - (nb - 1) * B;
+        if (last != B) {
+            if (knn_plan_metric(m, last, d, (int64_t)k < last ? k : (int32_t)last, metric,
+                                inner_limit, &tail) != KNN_OK)
+                continue;
+            if (tail.workspace_bytes > inner_ws) inner_ws = tail.workspace_bytes;
+        }
+        out->block_rows = B;
+        out->n_blocks = nb;
+        out->staging_bytes = staging;
+        out->inner_limit_bytes = inner_limit;
+        out->inner = full;
+        st = KNN_OK;
+        break;
+    }
+    if (st != KNN_OK) return st;
+    out->workspace_bytes = out->staging_bytes + outb + inner_ws;
+    return KNN_OK;
+}
+
 extern "C" uint64_t knn_workspace_bytes(int64_t m, int64_t n, int32_t d, int32_t k,
                                         uint64_t mem_limit_bytes) {
     knn_plan_t p;
