@@ -67,6 +67,16 @@ def _load():
                                        ctypes.c_int64, ctypes.c_int32, ctypes.c_double,
                                        ctypes.c_double, i64p, ctypes.c_int64, dp, ctypes.c_int32]
         lib.oracle_kmv_f64.restype = ctypes.c_int
+        lib.oracle_sgpr_accumulate.argtypes = [fp, ctypes.c_int64, fp, ctypes.c_int64, fp,
+                                               ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                               ctypes.c_double, ctypes.c_double, dp, dp,
+                                               ctypes.c_int32]
+        lib.oracle_sgpr_accumulate.restype = ctypes.c_int
+        lib.oracle_sgpr_entries.argtypes = [fp, ctypes.c_int64, fp, ctypes.c_int64, ctypes.c_int64,
+                                            ctypes.c_int64, ctypes.c_int32, ctypes.c_double,
+                                            ctypes.c_double, i64p, i64p, ctypes.c_int64, dp,
+                                            ctypes.c_int32]
+        lib.oracle_sgpr_entries.restype = ctypes.c_int
         lib.oracle_threads_used.argtypes = [ctypes.c_int32]
         lib.oracle_threads_used.restype = ctypes.c_int32
         _lib = lib
@@ -230,3 +240,49 @@ def kmv_f64(X, Z, v, variance: float, lengthscale: float, rows=None, nthreads: i
     if rc != 0:
         raise ValueError("oracle rejected its arguments")
     return y
+
+
+def sgpr_accumulate(U, X, y, variance: float, lengthscale: float, nthreads: int | None = None):
+    """A = K_uf K_fu (fp64 [m,m]) and b = K_uf y (fp64 [m]) of paper section 5.3, the definition
+    written out with K_uf stored whole: small cases only."""
+    U = _as_f32_2d(U)
+    X = _as_f32_2d(X)
+    y = np.ascontiguousarray(y, dtype=np.float32).ravel()
+    if U.shape[1] != X.shape[1] or y.shape[0] != X.shape[0]:
+        raise ValueError("shape mismatch")
+    m = U.shape[0]
+    A = np.empty((m, m), dtype=np.float64)
+    b = np.empty((m,), dtype=np.float64)
+    fp = ctypes.POINTER(ctypes.c_float)
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = _load().oracle_sgpr_accumulate(U.ctypes.data_as(fp), U.shape[1], X.ctypes.data_as(fp),
+                                        X.shape[1], y.ctypes.data_as(fp), m, X.shape[0], U.shape[1],
+                                        float(variance), float(lengthscale), A.ctypes.data_as(dp),
+                                        b.ctypes.data_as(dp), int(nthreads or default_threads()))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return A, b
+
+
+def sgpr_entries(U, X, ii, jj, variance: float, lengthscale: float, nthreads: int | None = None):
+    """The entries A[ii[p], jj[p]] of K_uf K_fu, each summed directly over the data."""
+    U = _as_f32_2d(U)
+    X = _as_f32_2d(X)
+    ii = np.ascontiguousarray(ii, dtype=np.int64).ravel()
+    jj = np.ascontiguousarray(jj, dtype=np.int64).ravel()
+    if U.shape[1] != X.shape[1] or ii.shape != jj.shape:
+        raise ValueError("shape mismatch")
+    if ii.size and (min(ii.min(), jj.min()) < 0 or max(ii.max(), jj.max()) >= U.shape[0]):
+        raise ValueError("entry out of range")
+    out = np.empty(ii.shape[0], dtype=np.float64)
+    fp = ctypes.POINTER(ctypes.c_float)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    rc = _load().oracle_sgpr_entries(U.ctypes.data_as(fp), U.shape[1], X.ctypes.data_as(fp),
+                                     X.shape[1], U.shape[0], X.shape[0], U.shape[1], float(variance),
+                                     float(lengthscale), ii.ctypes.data_as(i64p),
+                                     jj.ctypes.data_as(i64p), ii.shape[0],
+                                     out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                                     int(nthreads or default_threads()))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return out

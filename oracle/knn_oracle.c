@@ -334,6 +334,76 @@ int oracle_kmv_f64(const double *X, int64_t ldx, const double *Z, int64_t ldz, c
     return 0;
 }
 
+/*
+ * oracle_sgpr_accumulate: the two data-sized sums of sparse Gaussian process regression
+ * (paper section 5.3) that a memory-efficient implementation accumulates over the data
+ * instead of storing the m x n matrix K_uf:
+ *     A[i][j] = sum_t K_uf[i][t] * K_uf[j][t]        (A = K_uf K_fu, m x m)
+ *     b[i]    = sum_t K_uf[i][t] * y[t]              (b = K_uf y,    m)
+ * with K_uf[i][t] = variance * exp(-0.5 * |U[i] - X[t]|^2 / lengthscale^2), the squared-
+ * exponential kernel of section 5.1 between the m inducing points U and the n data points X.
+ * Here the definition is written out: K_uf is stored whole (fp64, m * n values - small cases
+ * only) and the sums run over t ascending.  A is m x m row-major.
+ */
+int oracle_sgpr_accumulate(const float *U, int64_t ldu, const float *X, int64_t ldx, const float *y,
+                           int64_t m, int64_t n, int32_t d, double variance, double lengthscale,
+                           double *A, double *b, int32_t nthreads)
+{
+    if (!U || !X || !y || !A || !b || m < 1 || n < 0 || d < 1 || ldu < d || ldx < d ||
+        !(lengthscale > 0.0))
+        return -1;
+    if (nthreads < 1) nthreads = 1;
+    const double inv = -0.5 / (lengthscale * lengthscale);
+    double *K = (double *)malloc(sizeof(double) * (size_t)m * (size_t)(n > 0 ? n : 1));
+    if (!K) return -2;
+#pragma omp parallel for num_threads(nthreads) schedule(static)
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t t = 0; t < n; ++t)
+            K[i * n + t] = variance * exp(inv * oracle_sqdist(U + i * ldu, X + t * ldx, d));
+#pragma omp parallel for num_threads(nthreads) schedule(dynamic, 1)
+    for (int64_t i = 0; i < m; ++i) {
+        for (int64_t j = 0; j < m; ++j) {
+            double acc = 0.0;
+            for (int64_t t = 0; t < n; ++t) acc += K[i * n + t] * K[j * n + t];
+            A[i * m + j] = acc;
+        }
+        double acc = 0.0;
+        for (int64_t t = 0; t < n; ++t) acc += K[i * n + t] * (double)y[t];
+        b[i] = acc;
+    }
+    free(K);
+    return 0;
+}
+
+/*
+ * oracle_sgpr_entries: the listed entries A[ii[p]][jj[p]] of the same matrix, each summed
+ * directly over the data (no stored K_uf), for spot checks at sizes where the full routine
+ * does not fit.
+ */
+int oracle_sgpr_entries(const float *U, int64_t ldu, const float *X, int64_t ldx, int64_t m,
+                        int64_t n, int32_t d, double variance, double lengthscale,
+                        const int64_t *ii, const int64_t *jj, int64_t count, double *out,
+                        int32_t nthreads)
+{
+    if (!U || !X || !ii || !jj || !out || m < 1 || n < 0 || d < 1 || ldu < d || ldx < d ||
+        !(lengthscale > 0.0))
+        return -1;
+    if (nthreads < 1) nthreads = 1;
+    const double inv = -0.5 / (lengthscale * lengthscale);
+#pragma omp parallel for num_threads(nthreads) schedule(dynamic, 1)
+    for (int64_t p = 0; p < count; ++p) {
+        const float *ui = U + ii[p] * ldu, *uj = U + jj[p] * ldu;
+        double acc = 0.0;
+        for (int64_t t = 0; t < n; ++t) {
+            const float *x = X + t * ldx;
+            acc += (variance * exp(inv * oracle_sqdist(ui, x, d))) *
+                   (variance * exp(inv * oracle_sqdist(uj, x, d)));
+        }
+        out[p] = acc;
+    }
+    return 0;
+}
+
 /* Number of threads an OpenMP region of the requested width really gets. */
 int32_t oracle_threads_used(int32_t nthreads)
 {
