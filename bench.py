@@ -37,6 +37,9 @@ MEASURED_TRAFFIC_BYTES = {
     "c7_l1_d100": 11.79e9,          # knn_l1_kernel: 11.37 GB fetched + 0.43 GB written
     "kmv1_d1": 1.84e9,              # kmv_lowd_kernel: 1.83 GB fetched + 0.01 GB written
     "kmv2_d32": 1.58e9,             # kmv_mfma_kernel: 1.58 GB fetched + 0.002 GB written
+    "kmv3_d1_f64": 4.02e9,          # kmv_lowd_f64_kernel: 4.01 GB fetched + 0.01 GB written
+    "sgpr1_road_d3_m10000": 8.97e9,      # sgpr_syrk_kernel, per launch: 8.57 GB fetched + 0.41 GB written
+    "sgpr2_electric_d11_m4000": 1.10e9,  # sgpr_syrk_kernel, per launch: 1.04 GB fetched + 0.07 GB written
 }
 
 
@@ -89,17 +92,16 @@ def bench_kmv(args) -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # kmv_apply launches on torch's current stream, so events recorded there bracket its kernels
-    marks = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-             for _ in range(args.steps)]
+    K.knn_profile_enable(True)  # HIP events around the main kernel, on the launch stream
+    K.knn_profile_read()
     t0 = time.perf_counter()
-    for b, e in marks:
-        b.record()
+    for _ in range(args.steps):
         step()
-        e.record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    call_ms = sum(b.elapsed_time(e) for b, e in marks) / args.steps
+    _, main_ms, _, launches = K.knn_profile_read()
+    K.knn_profile_enable(False)
+    call_ms = main_ms / max(launches, 1)
     ms_per_step = elapsed * 1e3 / args.steps
     pairs = float(w.n) * float(w.m)
     value = pairs * args.steps / elapsed
@@ -173,13 +175,128 @@ def bench_kmv(args) -> int:
     return 0
 
 
+def bench_sgpr(args) -> int:
+    """--workload sgpr1 / sgpr2: one step = one sgpr_accumulate call (A = K_uf K_fu, b = K_uf y)."""
+    import numpy as np
+    import torch
+
+    import paper_2206_14148_amd as K
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    K.load()
+    w = W.SGPR_WORKLOADS[args.workload]
+    if args.m or args.n:
+        from dataclasses import replace
+        w = replace(w, m=args.m or w.m, n=args.n or w.n)
+    limit = K.knn_parse_size(args.mem_limit) if args.mem_limit else w.mem_limit
+    t0 = time.time()
+    U, X, y = W.make_sgpr(w)
+    log(f"[bench] inputs {w.name}: m={w.m} n={w.n} d={w.d} generated in {time.time()-t0:.1f}s")
+    dev = torch.device("cuda:0")
+    Ud, Xd, yd = (torch.from_numpy(a).to(dev) for a in (U, X, y))
+    plan = K.sgpr_plan(w.m, w.n, w.d, limit)
+    assert plan.workspace_bytes <= limit
+    ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
+    A = torch.empty((w.m, w.m), dtype=torch.float64, device=dev)
+    b = torch.empty((w.m,), dtype=torch.float64, device=dev)
+    log(f"[bench] plan: {plan.n_chunks} chunks of {plan.chunk_cols} data points, "
+        f"workspace={plan.workspace_bytes} B (limit {limit} B)")
+
+    def step():
+        K.sgpr_accumulate(Ud, Xd, yd, w.variance, w.lengthscale, limit, workspace=ws, out=(A, b))
+
+    if args.calibrate_copy_mb > 0:
+        src = torch.ones(args.calibrate_copy_mb * 250_000, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)  # one elementwise kernel: reads and writes calibrate_copy_mb MB
+        torch.cuda.synchronize()
+        del src, dst
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    K.knn_profile_enable(True)
+    K.knn_profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kuf_ms, syrk_ms, kufy_ms, launches = K.knn_profile_read()
+    K.knn_profile_enable(False)
+    ms_per_step = elapsed * 1e3 / args.steps
+    pairs = float(w.m) * float(w.n)
+    value = pairs * args.steps / elapsed
+    log(f"[bench] {ms_per_step:.2f} ms/step, {value:.3e} kernel entries/s; kernels per step: K_uf chunks "
+        f"{kuf_ms/args.steps:.2f} ms, chunk products {syrk_ms/args.steps:.2f} ms ({launches // max(args.steps, 1)} "
+        f"launches), times y {kufy_ms/args.steps:.2f} ms")
+    # dominant kernel: the chunk product.  Algorithmic flops: the lower triangle of A once,
+    # n * m * (m + 1) for the whole job, spread over the launches.
+    avg_launch_s = syrk_ms / max(launches, 1) * 1e-3
+    flops_per_launch = float(w.flops) * args.steps / max(launches, 1)
+    achieved = flops_per_launch / avg_launch_s / 1e12
+    roofline = {"bound": "mfma", "kernel": "sgpr_syrk_kernel", "achieved": achieved,
+                "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_FP32_MATRIX_TFLOPS,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                "flops_per_pair": w.m + 1, "avg_launch_ms": avg_launch_s * 1e3}
+
+    cpu_baseline = None
+    parity = None
+    if args.cpu_seconds > 0:
+        import oracle
+
+        threads = oracle.threads_used()
+        g = np.random.Generator(np.random.PCG64(12))
+        count = 4 * threads
+        ii, jj = g.integers(0, w.m, count), g.integers(0, w.m, count)
+        t0 = time.perf_counter()
+        oracle.sgpr_entries(U, X, ii[:threads], jj[:threads], w.variance, w.lengthscale)
+        per_entry = (time.perf_counter() - t0) / 1.0  # one entry per thread in parallel
+        count = int(max(threads, min(4096, threads * args.cpu_seconds / max(per_entry, 1e-6))))
+        ii, jj = g.integers(0, w.m, count), g.integers(0, w.m, count)
+        t0 = time.perf_counter()
+        ref = oracle.sgpr_entries(U, X, ii, jj, w.variance, w.lengthscale)
+        dt = time.perf_counter() - t0
+        # an entry of A costs the oracle 2 n kernel evaluations; its rate in the metric's unit
+        # is the rate at which it would cover the m n entries of K_uf while summing the
+        # (m + 1) / 2 products each of them takes part in
+        entry_rate = count / dt
+        cpu_baseline = {"value": entry_rate * w.n / ((w.m + 1) / 2.0), "unit": "pairs/s",
+                        "cores": threads, "kind": "oracle",
+                        "sample": f"{count} seeded entries of A, each summed over all {w.n} data points of "
+                                  f"{w.name}, {dt:.1f} s; scaled by the m(m+1)/2 entries of the triangle"}
+        got = A[torch.from_numpy(ii).to(dev), torch.from_numpy(jj).to(dev)].cpu().numpy()
+        parity = {"entries": count, "max_rel_err": float((np.abs(got - ref) / ref).max())}
+        log(f"[bench] oracle: {cpu_baseline['value']:.3e} pairs/s on {threads} threads; parity {parity}")
+
+    out = {
+        "metric": "kernel-matrix entries per second through A = K_uf K_fu and b = K_uf y (m*n/s)",
+        "value": value, "unit": "pairs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "m": w.m, "n": w.n, "d": w.d, "variance": w.variance,
+                   "lengthscale": w.lengthscale, "mem_limit_bytes": limit,
+                   "workspace_bytes": plan.workspace_bytes, "chunk_cols": plan.chunk_cols,
+                   "n_chunks": plan.n_chunks},
+        "kernel_ms_per_step": {"kuf": kuf_ms / args.steps, "syrk": syrk_ms / args.steps,
+                               "kufy": kufy_ms / args.steps},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c2", help="c1..c7 (default c2, the metric's workload; c6 cosine, c7 L1), or kmv1 / kmv2 / kmv3: "
-                         "the kernel matrix-vector product")
+                         "the kernel matrix-vector product, or sgpr1 / sgpr2: the SGPR accumulations")
     ap.add_argument("--mem-limit", default=None, help="e.g. 128MB, 1GB (decimal); default: the workload's")
     ap.add_argument("--m", type=int, default=None, help="override the query count (testing)")
     ap.add_argument("--n", type=int, default=None, help="override the point count (testing)")
@@ -200,6 +317,8 @@ def main() -> int:
 
     if args.workload.startswith("kmv"):
         return bench_kmv(args)
+    if args.workload.startswith("sgpr"):
+        return bench_sgpr(args)
 
     import numpy as np
     import torch

@@ -175,6 +175,9 @@ int64_t knn_chunk_rows(uint64_t limit_bytes, uint64_t row_bytes);
  * all searches since the last read into the three HOST outputs (any may be NULL), stores
  * the number of search-kernel launches, and resets the tally.  Events are host objects; no
  * device memory is allocated.  Off by default; knn_profile_enable(0) frees the events.
+ * The other entry points of the library use the same three slots: kmv_apply(_f64) puts its
+ * main kernel into the search slot; sgpr_accumulate puts the kernel-matrix chunks into the
+ * norms slot, the chunk products into the search slot and the products with y into the third.
  */
 knn_status knn_profile_enable(int32_t on);
 knn_status knn_profile_read(float *norms_ms /* HOST */, float *search_ms /* HOST */,

@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     EXPORTED_SYMBOLS, KnnError, Plan, knn_chunk_rows, knn_last_stats, knn_parse_size, knn_plan, knn_profile_enable,
     knn_profile_read,
     KMV_PATH_LOWD, KMV_PATH_MFMA, KMV_PATH_VALU, KmvPlan, kmv_apply, kmv_apply_raw, kmv_plan,
-    HostPlan, knn_plan_host_x, knn_search_host_x,
+    HostPlan, knn_plan_host_x, knn_search_host_x, SgprPlan, sgpr_accumulate, sgpr_plan,
     knn_search, knn_search_raw, knn_status_string, knn_workspace_bytes, library_path, load,
 )

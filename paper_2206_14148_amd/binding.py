@@ -33,7 +33,7 @@ EXPORTED_SYMBOLS = (
     "knn_parse_size", "knn_chunk_rows", "knn_last_hip_error", "knn_profile_enable",
     "knn_profile_read", "knn_plan_metric", "knn_search_metric",
     "kmv_plan", "kmv_apply", "kmv_plan_f64", "kmv_apply_f64",
-    "knn_plan_host_x", "knn_search_host_x",
+    "knn_plan_host_x", "knn_search_host_x", "sgpr_plan", "sgpr_accumulate",
 )
 KMV_PATH_LOWD = 0
 KMV_PATH_MFMA = 1
@@ -48,6 +48,27 @@ class KmvPlanStruct(ctypes.Structure):
         ("norms_bytes", ctypes.c_int64), ("partials_bytes", ctypes.c_int64),
         ("workspace_bytes", ctypes.c_int64), ("min_limit_bytes", ctypes.c_int64),
     ]
+
+
+class SgprPlanStruct(ctypes.Structure):
+    _fields_ = [
+        ("m", ctypes.c_int64), ("n", ctypes.c_int64),
+        ("d", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("chunk_cols", ctypes.c_int64), ("n_chunks", ctypes.c_int64), ("chunk_ld", ctypes.c_int64),
+        ("workspace_bytes", ctypes.c_uint64), ("min_limit_bytes", ctypes.c_uint64),
+    ]
+
+
+@dataclass(frozen=True)
+class SgprPlan:
+    m: int
+    n: int
+    d: int
+    chunk_cols: int
+    n_chunks: int
+    chunk_ld: int
+    workspace_bytes: int
+    min_limit_bytes: int
 
 
 @dataclass(frozen=True)
@@ -181,6 +202,11 @@ def load():
     lib.knn_plan_host_x.restype = ctypes.c_int
     lib.knn_search_host_x.argtypes = lib.knn_search_metric.argtypes
     lib.knn_search_host_x.restype = ctypes.c_int
+    lib.sgpr_plan.argtypes = [i64, i64, i32, u64, ctypes.POINTER(SgprPlanStruct)]
+    lib.sgpr_plan.restype = ctypes.c_int
+    lib.sgpr_accumulate.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, ctypes.c_double,
+                                    ctypes.c_double, u64, vp, u64, vp, i64, vp, vp]
+    lib.sgpr_accumulate.restype = ctypes.c_int
     lib.kmv_plan.argtypes = [i64, i64, i32, i64, ctypes.POINTER(KmvPlanStruct)]
     lib.kmv_plan.restype = ctypes.c_int
     lib.kmv_apply.argtypes = [vp, i64, vp, i64, vp, i64, i64, i32, ctypes.c_double, ctypes.c_double,
@@ -421,3 +447,55 @@ def knn_search_host_x(Q, X_host, k: int, mem_limit_bytes: int, workspace=None, o
             detail += " (" + load().knn_last_hip_error().decode() + ")"
         raise KnnError(st, detail)
     return idx, dist
+
+
+def sgpr_plan(m: int, n: int, d: int, mem_limit_bytes: int) -> SgprPlan:
+    ps = SgprPlanStruct()
+    st = int(load().sgpr_plan(m, n, d, mem_limit_bytes, ctypes.byref(ps)))
+    if st != KNN_OK:
+        raise KnnError(st, knn_status_string(st), int(ps.min_limit_bytes))
+    return SgprPlan(ps.m, ps.n, ps.d, ps.chunk_cols, ps.n_chunks, ps.chunk_ld, ps.workspace_bytes,
+                    ps.min_limit_bytes)
+
+
+def sgpr_accumulate(U, X, y, variance: float, lengthscale: float, mem_limit_bytes: int,
+                    workspace=None, out=None):
+    """sgpr_accumulate(U[m,d], X[n,d], y[n], ...) -> (A fp64[m,m], b fp64[m]).
+
+    A = K_uf K_fu and b = K_uf y for the squared-exponential kernel between the inducing points
+    U and the data X.  fp32 device tensors in, fp64 device tensors out; the workspace (uint8,
+    plan.workspace_bytes) is allocated here unless given.  Work is enqueued on torch's current
+    stream; no synchronisation is done.
+    """
+    import torch
+
+    for t, nd in ((U, 2), (X, 2), (y, 1)):
+        if not t.is_cuda or t.dtype != torch.float32 or t.dim() != nd:
+            raise KnnError(KNN_ERR_INVALID_ARG, "U, X (2-D) and y (1-D) must be float32 device tensors")
+    if U.shape[1] != X.shape[1] or y.shape[0] != X.shape[0] or U.stride(1) != 1 or \
+            X.stride(1) != 1 or (y.shape[0] > 1 and y.stride(0) != 1):
+        raise KnnError(KNN_ERR_INVALID_ARG, "shapes or strides do not fit")
+    m, d = U.shape
+    n = X.shape[0]
+    plan = sgpr_plan(m, n, d, mem_limit_bytes)
+    if workspace is None:
+        workspace = torch.empty(max(int(plan.workspace_bytes), 256), dtype=torch.uint8,
+                                device=U.device)
+    if out is None:
+        A = torch.empty((m, m), dtype=torch.float64, device=U.device)
+        b = torch.empty((m,), dtype=torch.float64, device=U.device)
+    else:
+        A, b = out
+    stream = torch.cuda.current_stream(U.device).cuda_stream
+    ldu = U.stride(0) if m > 1 else max(d, U.stride(0))
+    ldx = X.stride(0) if n > 1 else max(d, X.stride(0))
+    st = int(load().sgpr_accumulate(U.data_ptr(), ldu, X.data_ptr(), ldx, y.data_ptr(), m, n, d,
+                                    float(variance), float(lengthscale), mem_limit_bytes,
+                                    workspace.data_ptr(), workspace.numel(), A.data_ptr(),
+                                    A.stride(0) if m > 1 else m, b.data_ptr(), stream))
+    if st != KNN_OK:
+        detail = knn_status_string(st)
+        if st == KNN_ERR_HIP:
+            detail += " (" + load().knn_last_hip_error().decode() + ")"
+        raise KnnError(st, detail)
+    return A, b

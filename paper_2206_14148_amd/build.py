@@ -10,8 +10,9 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libknn_mi355x.so")
 SOURCES = ["planner.cpp", "api.hip", "knn_lowd.hip", "knn_mfma.hip", "knn_refine.hip",
-           "kmv_api.hip", "kmv_kernels.hip"]
-HEADERS = ["knn_config.h", "knn_device.h", "knn_kernels.h", "kmv_kernels.h",
+           "kmv_api.hip", "kmv_kernels.hip", "sgpr_api.hip", "sgpr_kernels.hip"]
+HEADERS = ["knn_config.h", "knn_device.h", "knn_kernels.h", "kmv_kernels.h", "sgpr_kernels.h",
+           os.path.join("..", "..", "include", "sgpr.h"),
            os.path.join("..", "..", "include", "knn.h"),
            os.path.join("..", "..", "include", "kmv.h")]
 

@@ -77,8 +77,12 @@ knn_status hip_fail(hipError_t e, const char* what) {
 }  // namespace
 
 namespace knn {
-// Lets the other C ABI sources of the library record into the same per-thread message.
+// Lets the other C ABI sources of the library record into the same per-thread message and
+// into the same event brackets (kind 0: preparation, 1: the dominant kernel, 2: the rest).
 void set_last_hip_error(hipError_t e, const char* what) { hip_fail(e, what); }
+hipEvent_t profile_mark(hipStream_t stream) { return mark(stream); }
+void profile_close(hipEvent_t begin, hipStream_t stream, int kind) { close_bracket(begin, stream, kind); }
+void profile_drop(hipEvent_t begin) { drop_bracket(begin); }
 }  // namespace knn
 
 extern "C" const char* knn_last_hip_error(void) { return g_hip_error; }

@@ -14,9 +14,12 @@
 #include "kmv_kernels.h"
 #include "knn_config.h"
 
-namespace knn {
-void set_last_hip_error(hipError_t e, const char* what);  // api.hip
-}
+namespace knn {  // api.hip
+void set_last_hip_error(hipError_t e, const char* what);
+hipEvent_t profile_mark(hipStream_t stream);
+void profile_close(hipEvent_t begin, hipStream_t stream, int kind);
+void profile_drop(hipEvent_t begin);
+}  // namespace knn
 
 namespace {
 
@@ -106,13 +109,23 @@ extern "C" int kmv_apply(const float* X, int64_t ldx, const float* Z, int64_t ld
     const int S = plan.n_splits;
     double* target = S > 1 ? partials : y;
     if (plan.path == KMV_PATH_LOWD) {
+        hipEvent_t t1 = knn::profile_mark(stream);
         e = kmv::launch_lowd(X, ldx, Z, ldz, v, n, m, d, c2, variance, S, target, stream);
-        if (e != hipSuccess) return hip_fail(e, "kmv low-d kernel");
+        if (e != hipSuccess) {
+            knn::profile_drop(t1);
+            return hip_fail(e, "kmv low-d kernel");
+        }
+        knn::profile_close(t1, stream, 1);
     } else {
         e = kmv::launch_scaled_norms(Z, ldz, m, d, c2, zn, stream);
         if (e != hipSuccess) return hip_fail(e, "kmv norms kernel");
+        hipEvent_t t1 = knn::profile_mark(stream);
         e = kmv::launch_mfma(X, ldx, Z, ldz, v, zn, n, m, d, c2, variance, S, target, stream);
-        if (e != hipSuccess) return hip_fail(e, "kmv matrix-core kernel");
+        if (e != hipSuccess) {
+            knn::profile_drop(t1);
+            return hip_fail(e, "kmv matrix-core kernel");
+        }
+        knn::profile_close(t1, stream, 1);
     }
     if (S > 1) {
         e = kmv::launch_reduce(partials, S, n, y, stream);
@@ -149,8 +162,13 @@ extern "C" int kmv_apply_f64(const double* X, int64_t ldx, const double* Z, int6
     const double negc = -0.5 / (lengthscale * lengthscale);
     double* partials = static_cast<double*>(workspace);
     const int S = plan.n_splits;
+    hipEvent_t t1 = knn::profile_mark(stream);
     e = kmv::launch_f64(X, ldx, Z, ldz, v, n, m, d, negc, variance, S, S > 1 ? partials : y, stream);
-    if (e != hipSuccess) return hip_fail(e, "kmv fp64 kernel");
+    if (e != hipSuccess) {
+        knn::profile_drop(t1);
+        return hip_fail(e, "kmv fp64 kernel");
+    }
+    knn::profile_close(t1, stream, 1);
     if (S > 1) {
         e = kmv::launch_reduce(partials, S, n, y, stream);
         if (e != hipSuccess) return hip_fail(e, "kmv reduce kernel");

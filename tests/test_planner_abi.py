@@ -13,10 +13,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def declared_symbols():
     names = set()
-    for header in ("knn.h", "kmv.h"):
+    for header in ("knn.h", "kmv.h", "sgpr.h"):
         text = open(os.path.join(ROOT, "include", header)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names |= set(re.findall(r"\b(k(?:nn|mv)_[a-z0-9_]+)\s*\(", text))
+        names |= set(re.findall(r"\b((?:knn|kmv|sgpr)_[a-z0-9_]+)\s*\(", text))
     return sorted(names)
 
 

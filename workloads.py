@@ -243,3 +243,51 @@ def random_kmv_case(seed: int, n: int, m: int, d: int, spread: float = 1.0, dtyp
     Z = (np.float32(spread) * rng.standard_normal((m, d), dtype=np.float32)).astype(np.float32)
     v = rng.standard_normal((m,), dtype=np.float32)
     return X, Z, v
+
+
+# ---------------------------------------------------------------------------------------------
+# SGPR accumulations (paper section 5.3): A = K_uf K_fu, b = K_uf y.  The paper runs on two
+# regression data sets (n = 434,874 with d = 3, scaled to 1e4 inducing points; n = 2,049,280
+# with d = 11, up to 4000 inducing points in its table); the data sets are not available, so
+# standardised features are drawn as N(0, 1), the inducing points are the first m data
+# points (the usual initialisation) and the targets are N(0, 1).
+# ---------------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class SgprWorkload:
+    name: str
+    m: int   # inducing points
+    n: int   # data points
+    d: int
+    variance: float
+    lengthscale: float
+    mem_limit: int
+    stream: int = 0
+
+    @property
+    def flops(self) -> int:
+        """Multiply-adds of the lower triangle of A, counted as 2 flops each."""
+        return self.n * self.m * (self.m + 1)
+
+
+SGPR_WORKLOADS = {
+    "sgpr1": SgprWorkload("sgpr1_road_d3_m10000", 10_000, 434_874, 3, 1.0, 1.0, 1 * GB),
+    "sgpr2": SgprWorkload("sgpr2_electric_d11_m4000", 4_000, 2_049_280, 11, 1.0, 3.0, 1 * GB, stream=1),
+}
+
+
+def make_sgpr(w: SgprWorkload):
+    """Returns (U, X, y): float32 [m,d] (a copy of the first m data points), [n,d], [n]."""
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 10_000_000 + w.stream))
+    X = np.empty((w.n, w.d), dtype=np.float32)
+    _fill_normal(rng, X)
+    y = np.empty((w.n,), dtype=np.float32)
+    _fill_normal(rng, y)
+    return X[:w.m].copy(), X, y
+
+
+def random_sgpr_case(seed: int, m: int, n: int, d: int):
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 11_000_000 + seed))
+    U = rng.standard_normal((m, d), dtype=np.float32)
+    X = rng.standard_normal((n, d), dtype=np.float32)
+    y = rng.standard_normal((n,), dtype=np.float32)
+    return U, X, y
