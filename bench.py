@@ -347,7 +347,7 @@ def main() -> int:
     ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
     idx = torch.empty((w.m, w.k), dtype=torch.int32, device=dev)
     dist = torch.empty((w.m, w.k), dtype=torch.float32, device=dev)
-    path_name = {0: "lowd", 1: "mfma", 2: "lowd_mfma", 3: "l1"}[plan.path]
+    path_name = {0: "lowd", 1: "mfma", 2: "lowd_mfma", 3: "l1", 4: "lowd_bf16"}[plan.path]
     log(f"[bench] plan: path={path_name} chunks={plan.q_chunks} "
         f"ranges={plan.n_splits} workspace={plan.workspace_bytes} B (limit {limit} B)")
 

@@ -22,6 +22,7 @@ KNN_MAX_K = 1024
 KNN_PATH_LOWD = 0
 KNN_PATH_MFMA = 1
 KNN_PATH_LOWD_MFMA = 2
+KNN_PATH_LOWD_BF16 = 4
 KNN_METRIC_L2SQ = 0
 KNN_METRIC_COSINE = 1
 KNN_METRIC_L1 = 2

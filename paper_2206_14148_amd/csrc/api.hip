@@ -166,9 +166,11 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
             return hip_fail(e, "row norms / point blocking launch");
         }
         close_bracket(t0, stream, 0);
-    } else if (plan.path == KNN_PATH_LOWD_MFMA) {
+    } else if (plan.path == KNN_PATH_LOWD_MFMA || plan.path == KNN_PATH_LOWD_BF16) {
         hipEvent_t t0 = mark(stream);
-        e = launch_lowd_mfma(Q, ldq, X, ldx, ws, 0, n, d, k, S, true, lk, li, stream);
+        e = plan.path == KNN_PATH_LOWD_BF16
+                ? launch_lowd_bf16(Q, ldq, X, ldx, ws, 0, n, d, k, S, true, lk, li, stream)
+                : launch_lowd_mfma(Q, ldq, X, ldx, ws, 0, n, d, k, S, true, lk, li, stream);
         if (e != hipSuccess) {
             drop_bracket(t0);
             return hip_fail(e, "point packing launch");
@@ -186,6 +188,8 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
             e = launch_l1(Qc, ldq, X, ldx, rows, n, d, k, S, lk, li, stream);
         else if (plan.path == KNN_PATH_LOWD_MFMA)
             e = launch_lowd_mfma(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, lk, li, stream);
+        else if (plan.path == KNN_PATH_LOWD_BF16)
+            e = launch_lowd_bf16(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, lk, li, stream);
         else
             e = launch_mfma(Qc, ldq, X, ldx, xn, xblocked, cosine, rows, n, d, k, S, lk, li,
                             stream);

@@ -20,6 +20,12 @@ constexpr int kPmMaxD = 3;
 constexpr int kPmTileQ = 128;
 constexpr int kPmCand = 32;                      // candidate slots per query (LDS)
 
+// the same with a bf16 filter (room for 32 bytes per point): each wave owns kPbSets sets of 32
+// queries, so one load of a block of points feeds kPbSets MFMAs.
+constexpr int kPbSets = 2;
+constexpr int kPbTileQ = 4 * 32 * kPbSets;       // query rows per workgroup
+constexpr int kPbCand = 16;                      // candidate slots per query (LDS)
+
 // d > kLowdMaxD: fp32 MFMA tile, 4 waves, each wave owns 32 queries x 128 points.
 constexpr int kMfmaTileQ = 128;
 constexpr int kMfmaTileX = 128;

@@ -464,14 +464,18 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
     f32x2 a[UB], an[UB];
 #pragma unroll
     for (int u = 0; u < UB; ++u) a[u] = an[u] = f32x2{0.f, 0.f};
+    // wave-uniform base + constant lane offset + immediate: no vector address arithmetic
+    const f32x2* xb = xp2 + (size_t)j0 * 2;
+    const int loff = i32 * 2 + h;
     if (nfull > 0) {
 #pragma unroll
-        for (int u = 0; u < UB; ++u) a[u] = xp2[(size_t)(jb + u * 32 + i32) * 2 + h];
+        for (int u = 0; u < UB; ++u) a[u] = xb[loff + u * 64];
     }
     for (int it = 0; it < nfull; ++it) {
+        xb += PTS * 2;
         if (it + 1 < nfull) {
 #pragma unroll
-            for (int u = 0; u < UB; ++u) an[u] = xp2[(size_t)(jb + PTS + u * 32 + i32) * 2 + h];
+            for (int u = 0; u < UB; ++u) an[u] = xb[loff + u * 64];
         }
         process(a, jb);
 #pragma unroll
@@ -489,6 +493,349 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
     }
     const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0) & 0xffffffffull;
     if (rest) flush(rest);
+}
+
+
+// ---------------------------------------------------------------------------------------
+// Low-dimensional path with a bf16 filter (d <= 3, room for 32 bytes per point).  The filter
+// of the kernel above costs two fp32 MFMAs (128 cycles) per 32 x 32 keys; one
+// v_mfma_f32_32x32x16_bf16 (32 cycles) gives keys that are nearly as sharp if every fp32 value
+// is cut into bf16 pieces and the cross products that matter are spread over the 16 K slots:
+//     x = xh + xl + (|rest| <= 2^-18 |x|),  q = qh + ql + (same),  ||x||^2 = nh + nm + nl exactly
+//     key = sum_t  xh_t (-2 qh_t) + xh_t (-2 ql_t) + xl_t (-2 qh_t)  +  (nh + nm + nl) * 1
+// (12 slots, products of two bf16 values are exact in fp32).  What is left out is at most
+// 6.1 * 2^-18 ||x|| ||q||, which the filter bound allows for.  Points and queries are first
+// moved by the midpoint of the points' bounding box, so that bound scales with the spread of
+// the data, not with its offset from the origin.  The filter only decides which pairs go to
+// the exact test; that test reads the point's original fp32 coordinates from X and is the
+// same arithmetic as knn_lowd_kernel, so keys, accepted sets and results are identical.
+// ---------------------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// round-to-nearest-even bf16 of a finite fp32 value, as its 16 bits
+__device__ __forceinline__ unsigned bf16_bits(float x) {
+    unsigned u = __float_as_uint(x);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ float bf16_value(unsigned bits) { return __uint_as_float(bits << 16); }
+
+// floats <-> unsigned keys with the same order (for atomicMin / atomicMax)
+__device__ __forceinline__ unsigned ordered_bits(float f) {
+    const unsigned u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ordered_value(unsigned k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+// header words of the packed area: 0 max ||x - c||^2 (bits of a non-negative float),
+// 1..3 per-dimension minimum, 4..6 per-dimension maximum (ordered keys)
+__global__ void knn_bbox_init_kernel(unsigned* __restrict__ hdr) {
+    const int t = threadIdx.x;
+    if (t == 0) hdr[0] = 0u;
+    if (t >= 1 && t <= 3) hdr[t] = 0xffffffffu;
+    if (t >= 4 && t <= 6) hdr[t] = 0u;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void knn_bbox_kernel(const float* __restrict__ X, int64_t ldx,
+                                                       int n, unsigned* __restrict__ hdr) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int jc = j < n ? j : n - 1;  // idle lanes repeat the last point
+#pragma unroll
+    for (int t = 0; t < D; ++t) {
+        const float v = X[(int64_t)jc * ldx + t];
+        float lo = v, hi = v;
+#pragma unroll
+        for (int s = 32; s > 0; s >>= 1) {
+            lo = fminf(lo, __shfl_xor(lo, s));
+            hi = fmaxf(hi, __shfl_xor(hi, s));
+        }
+        if ((threadIdx.x & 63) == 0) {
+            atomicMin(hdr + 1 + t, ordered_bits(lo));
+            atomicMax(hdr + 4 + t, ordered_bits(hi));
+        }
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void bbox_centre(const unsigned* __restrict__ hdr, float (&c)[3]) {
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+        c[t] = t < D ? 0.5f * ordered_value(hdr[1 + t]) + 0.5f * ordered_value(hdr[4 + t]) : 0.f;
+}
+
+// 32 bytes per point: 16 for the lanes 0..31 of the MFMA's A operand (K slots 0..7), 16 for the
+// lanes 32..63 (K slots 8..15)
+template <int D>
+__global__ __launch_bounds__(256) void knn_pack_bf16_kernel(const float* __restrict__ X,
+                                                            int64_t ldx, int n,
+                                                            uint4* __restrict__ Xp,
+                                                            unsigned* __restrict__ hdr) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    float c[3];
+    bbox_centre<D>(hdr, c);
+    float nrm = 0.f;
+    if (j < n) {
+        float v[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < D; ++t) v[t] = X[(int64_t)j * ldx + t] - c[t];
+        nrm = v[0] * v[0];
+        nrm = fmaf(v[1], v[1], nrm);
+        nrm = fmaf(v[2], v[2], nrm);
+        unsigned xh[3], xl[3];
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            xh[t] = bf16_bits(v[t]);
+            xl[t] = bf16_bits(v[t] - bf16_value(xh[t]));
+        }
+        const unsigned nh = bf16_bits(nrm);
+        const float r1 = nrm - bf16_value(nh);
+        const unsigned nm = bf16_bits(r1);
+        const unsigned nl = bf16_bits(r1 - bf16_value(nm));
+        Xp[(size_t)j * 2] = uint4{xh[0] | (xh[1] << 16), xh[2] | (xh[0] << 16),
+                                  xh[1] | (xh[2] << 16), nh | (nm << 16)};
+        Xp[(size_t)j * 2 + 1] = uint4{xl[0] | (xl[1] << 16), xl[2] | (nl << 16), 0u, 0u};
+    }
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) nrm = fmaxf(nrm, __shfl_xor(nrm, s));
+    if ((threadIdx.x & 63) == 0) atomicMax(hdr, __float_as_uint(nrm));
+}
+
+template <int D>
+__global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
+    const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
+    const uint4* __restrict__ Xp, const unsigned* __restrict__ hdr, int rows, int n, int k, int S,
+    int split_len, float* __restrict__ lk, int* __restrict__ li) {
+    constexpr int C = kPbCand;
+    constexpr int NS = kPbSets;  // query sets of 32 per wave: one A-operand load feeds NS MFMAs
+    constexpr int UB = 4;        // 32-point blocks per loop iteration
+    constexpr int PTS = UB * 32; // points per loop iteration
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int i32 = lane & 31;  // query column (B side) / point row (A side) of the 32x32 block
+    const int h = lane >> 5;
+    const size_t per_wave = (size_t)(2 * NS * 32 * C + 2 * kWave + 2 * k) * 4;
+    float* ck = reinterpret_cast<float*>(smem + (size_t)wave * per_wave);  // [NS * 32][C]
+    int* ci = reinterpret_cast<int*>(ck + NS * 32 * C);                    // [NS * 32][C]
+    MergeScratch sc;
+    sc.cand_key = reinterpret_cast<float*>(ci + NS * 32 * C);
+    sc.cand_idx = reinterpret_cast<int*>(sc.cand_key + kWave);
+    sc.list_key = reinterpret_cast<float*>(sc.cand_idx + kWave);
+    sc.list_idx = reinterpret_cast<int*>(sc.list_key + k);
+
+    const int s = blockIdx.y;
+    const int wave_row0 = (blockIdx.x * 4 + wave) * (NS * 32);
+    if (wave_row0 >= rows) return;  // whole wave idle; no workgroup barrier is used below
+
+    for (int qq = 0; qq < NS * 32; ++qq) {
+        if (wave_row0 + qq >= rows) break;
+        const size_t lb = ((size_t)(wave_row0 + qq) * S + s) * k;
+        for (int p = lane; p < k; p += kWave) {
+            lk[lb + p] = kInf;
+            li[lb + p] = kNoIdx;
+        }
+    }
+
+    // the filter sees points and queries moved by the midpoint of the points' bounding box
+    float c[3];
+    bbox_centre<D>(hdr, c);
+    const float xmax = __uint_as_float(hdr[0]);
+
+    // per query set: the query (original coordinates, for the exact test), the B operand, the
+    // thresholds and the number of buffered candidates (same value in both halves of the wave)
+    float q[NS][3];
+    bf16x8 bq[NS];
+    float qn[NS], cross[NS], tau[NS], tauf[NS];
+    int cnt[NS];
+    // A pair with exact fp32 distance < tau has a filter key below (tau - qn) + slack: the cross
+    // terms the bf16 pieces leave out (<= 6.1 * 2^-18 ||x'|| ||q'|| < 2^-15 sqrt(xmax qn)), the
+    // fp32 roundings of the accumulation, of qn, of the moved coordinates and of the distance
+    // itself (each a few 2^-24 of ||x'||^2 + ||q'||^2 + tau; 2^-19 of that sum is several times
+    // their total).
+    auto key_bound = [&](int st, float t) {
+        return (t - qn[st]) + (cross[st] + 0x1p-19f * (xmax + qn[st] + t));
+    };
+#pragma unroll
+    for (int st = 0; st < NS; ++st) {
+        const int r = wave_row0 + st * 32 + i32;
+        const bool active = r < rows;
+        float qc[3];
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            q[st][t] = (t < D && active) ? Q[(int64_t)r * ldq + t] : 0.f;
+            qc[t] = (t < D && active) ? q[st][t] - c[t] : 0.f;
+        }
+        qn[st] = fmaf(qc[2], qc[2], fmaf(qc[1], qc[1], qc[0] * qc[0]));
+        cross[st] = 0x1p-15f * sqrtf(xmax * qn[st]);
+        // B operand: K slots 0..7 = -2qh0 -2qh1 -2qh2 -2ql0 -2ql1 -2ql2 1 1, slots 8..15 =
+        // -2qh0 -2qh1 -2qh2 1 0 0 0 0, against the layout written by knn_pack_bf16_kernel
+        unsigned qh[3], ql[3];
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            const unsigned hb = bf16_bits(qc[t]);
+            const float hv = bf16_value(hb);
+            qh[t] = bf16_bits(-2.f * hv);                                 // exact
+            ql[t] = bf16_bits(-2.f * bf16_value(bf16_bits(qc[t] - hv)));  // exact
+        }
+        const unsigned one = 0x3f80u;
+        uint4 w;
+        if (h == 0) w = uint4{qh[0] | (qh[1] << 16), qh[2] | (ql[0] << 16), ql[1] | (ql[2] << 16), one | (one << 16)};
+        else w = uint4{qh[0] | (qh[1] << 16), qh[2] | (one << 16), 0u, 0u};
+        bq[st] = __builtin_bit_cast(bf16x8, w);
+        tau[st] = active ? kInf : -kInf;
+        tauf[st] = key_bound(st, tau[st]);
+        cnt[st] = 0;
+    }
+
+    // bits 0..31 of mask: queries of set st to merge
+    auto flush = [&](int st, uint64_t mask) {
+        while (mask) {
+            const int L = __builtin_ctzll(mask);
+            mask &= mask - 1;
+            wave_sync();
+            const int cc = __shfl(cnt[st], L);
+            float key = kInf;
+            int id = kNoIdx;
+            if (lane < cc) {
+                key = ck[(st * 32 + L) * C + lane];
+                id = ci[(st * 32 + L) * C + lane];
+            }
+            const size_t lb = ((size_t)(wave_row0 + st * 32 + L) * S + s) * k;
+            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane);
+            if (i32 == L) {
+                tau[st] = t_new;
+                tauf[st] = key_bound(st, t_new);
+                cnt[st] = 0;
+            }
+        }
+    };
+
+    const int j0 = s * split_len;
+    const int j1 = min(n, j0 + split_len);
+
+    // Rare path of one 32-point block and one query set (about one block in five at n = 1e6,
+    // k = 16, nearly always for a single key).  Sixteen compares leave one lane mask per
+    // accumulator register in scalar registers; everything that picks the registers with a set
+    // bit is scalar work, and one copy of the exact test handles them one register at a time.
+    // Register e of the lanes' half h holds point row 8 (e / 4) + 4 h + e % 4 of the block; the
+    // point's coordinates are read from X.
+    const int h4 = 4 * h;
+    auto examine = [&](int st, const f32x16& keys, int jblock) {
+        uint64_t pm[16];
+        unsigned nz = 0;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            pm[e] = __builtin_amdgcn_ballot_w64(keys[e] < tauf[st]);
+            nz |= pm[e] ? (1u << e) : 0u;
+        }
+        while (nz) {
+            const int e = __builtin_ctz(nz);
+            nz &= nz - 1;
+            uint64_t mk = 0;
+#pragma unroll
+            for (int t = 0; t < 16; ++t) mk = (e == t) ? pm[t] : mk;  // scalar selects
+            const bool pass = (mk >> lane) & 1;
+            const int row = 8 * (e >> 2) + (e & 3) + h4;
+            const int jj = min(jblock + row, n - 1);  // idle lanes stay in bounds
+            const float* __restrict__ xr = X + (int64_t)jj * ldx;
+            // exact test, same arithmetic as the vector-ALU kernel
+            float df = q[st][0] - xr[0];
+            float dd = df * df;
+            if (D > 1) {
+                df = q[st][1] - xr[1];
+                dd = fmaf(df, df, dd);
+            }
+            if (D > 2) {
+                df = q[st][2] - xr[2];
+                dd = fmaf(df, df, dd);
+            }
+            bool cnd = pass && dd < tau[st];
+            if (__builtin_amdgcn_ballot_w64(cnd) == 0) continue;
+            int own = cnd ? 1 : 0;
+            int oth = __shfl_xor(own, 32);
+            const uint64_t need =
+                __builtin_amdgcn_ballot_w64(cnt[st] + own + oth > C) & 0xffffffffull;
+            if (need) {
+                flush(st, need);
+                cnd = cnd && dd < tau[st];
+                own = cnd ? 1 : 0;
+                oth = __shfl_xor(own, 32);
+            }
+            if (cnd) {
+                const int slot = (st * 32 + i32) * C + cnt[st] + (h ? oth : 0);
+                ck[slot] = dd;
+                ci[slot] = jblock + row;
+            }
+            cnt[st] += own + oth;
+        }
+    };
+
+    auto process = [&](const uint4 (&a)[UB], int jb) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+#pragma unroll
+            for (int st = 0; st < NS; ++st) {
+                f32x16 z;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) z[e] = 0.f;
+                z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[u]), bq[st], z, 0, 0, 0);
+                float m = kInf;  // 8 three-input mins over (inf, 16 keys)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) m = fminf(m, z[e]);
+                if (__builtin_amdgcn_ballot_w64(m < tauf[st]) != 0) examine(st, z, jb + u * 32);
+            }
+        }
+    };
+
+    // Two statically named sets of A operands alternate (the loop is unrolled by two), so the
+    // loads of the next iteration land in registers that are never copied.
+    const int nfull = (j1 > j0) ? (j1 - j0) / PTS : 0;
+    int jb = j0;
+    uint4 a_even[UB], a_odd[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) a_even[u] = a_odd[u] = uint4{0u, 0u, 0u, 0u};
+    // wave-uniform base + constant lane offset + immediate: no vector address arithmetic
+    const uint4* xb = Xp + (size_t)j0 * 2;
+    const int loff = i32 * 2 + h;
+    if (nfull > 0) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u) a_even[u] = xb[loff + u * 64];
+    }
+    for (int it = 0; it < nfull; it += 2) {
+        xb += PTS * 2;
+        if (it + 1 < nfull) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u) a_odd[u] = xb[loff + u * 64];
+        }
+        process(a_even, jb);
+        jb += PTS;
+        if (it + 1 < nfull) {
+            xb += PTS * 2;
+            if (it + 2 < nfull) {
+#pragma unroll
+                for (int u = 0; u < UB; ++u) a_even[u] = xb[loff + u * 64];
+            }
+            process(a_odd, jb);
+            jb += PTS;
+        }
+    }
+    if (jb < j1) {  // ragged tail: rows past the range read a valid row and get ||x||^2 = +inf
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const int row = jb + u * 32 + i32;
+            a_even[u] = Xp[(size_t)(row < j1 ? row : j1 - 1) * 2 + h];
+            if (row >= j1 && !h) a_even[u].w = 0x7f80u;  // nh = +inf, nm = 0
+        }
+        process(a_even, jb);
+    }
+#pragma unroll
+    for (int st = 0; st < NS; ++st) {
+        const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt[st] > 0) & 0xffffffffull;
+        if (rest) flush(st, rest);
+    }
 }
 
 }  // namespace
@@ -570,6 +917,44 @@ static hipError_t launch_lowd_mfma_d(const float* Q, int64_t ldq, const float* X
     knn_lowd_mfma_kernel<D><<<grid, dim3(256), lds, stream>>>(
         Q, ldq, Xp, xmax, (int)rows, (int)n, k, S, (int)split_len, lk, li);
     return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_lowd_bf16_d(const float* Q, int64_t ldq, const float* X, int64_t ldx,
+                                     void* packed, int64_t rows, int64_t n, int k, int S,
+                                     bool pack, float* lk, int* li, hipStream_t stream) {
+    unsigned* hdr = static_cast<unsigned*>(packed);
+    uint4* Xp = reinterpret_cast<uint4*>(static_cast<unsigned char*>(packed) + kAlign);
+    const dim3 pgrid((unsigned)((n + 255) / 256));
+    if (pack) {
+        knn_bbox_init_kernel<<<dim3(1), dim3(64), 0, stream>>>(hdr);
+        knn_bbox_kernel<D><<<pgrid, dim3(256), 0, stream>>>(X, ldx, (int)n, hdr);
+        knn_pack_bf16_kernel<D><<<pgrid, dim3(256), 0, stream>>>(X, ldx, (int)n, Xp, hdr);
+        hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return e0;
+    }
+    if (rows == 0) return hipSuccess;
+    const size_t per_wave = (size_t)(2 * kPbSets * 32 * kPbCand + 2 * kWave + 2 * k) * 4;
+    const size_t lds = per_wave * 4;
+    hipError_t e = raise_lds_limit(knn_lowd_bf16_kernel<D>, lds);
+    if (e != hipSuccess) return e;
+    int64_t split_len = (n + S - 1) / S;
+    split_len = (split_len + 127) / 128 * 128;
+    dim3 grid((unsigned)((rows + kPbTileQ - 1) / kPbTileQ), (unsigned)S);
+    knn_lowd_bf16_kernel<D><<<grid, dim3(256), lds, stream>>>(
+        Q, ldq, X, ldx, Xp, hdr, (int)rows, (int)n, k, S, (int)split_len, lk, li);
+    return hipGetLastError();
+}
+
+hipError_t launch_lowd_bf16(const float* Q, int64_t ldq, const float* X, int64_t ldx, void* packed,
+                            int64_t rows, int64_t n, int d, int k, int S, bool pack, float* lk,
+                            int* li, hipStream_t stream) {
+    switch (d) {
+        case 1: return launch_lowd_bf16_d<1>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        case 2: return launch_lowd_bf16_d<2>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        case 3: return launch_lowd_bf16_d<3>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_lowd_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx, void* packed,

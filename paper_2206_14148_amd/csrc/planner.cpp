@@ -127,6 +127,15 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
             out->tile_x = 32;
             out->norms_bytes = packed;
         }
+        // with 32 bytes per point the filter runs in bf16 pieces, four times cheaper
+        const uint64_t packed16 = kAlign + align_up((uint64_t)n * 32);
+        const int64_t min_rows16 = m < kPbTileQ ? m : kPbTileQ;
+        if (mem_limit_bytes >= packed16 + lists_bytes_for((uint64_t)min_rows16, 1, (uint64_t)k)) {
+            out->path = KNN_PATH_LOWD_BF16;
+            out->tile_q = kPbTileQ;
+            out->tile_x = 32;
+            out->norms_bytes = packed16;
+        }
     }
     const int64_t tile = out->tile_q;
     const uint64_t avail = mem_limit_bytes - out->norms_bytes;

@@ -139,19 +139,23 @@ def test_exact_ties_on_integer_grid(K, oracle, d):
 
 @pytest.mark.parametrize("d", [1, 2, 3])
 def test_low_d_paths_agree_and_survive_data_far_from_the_origin(K, oracle, d):
-    # the matrix-core filter (roomy limit) and the vector kernel (tight limit) must give the
-    # same bits; an offset of 50 makes the expansion's rounding far larger than the
-    # neighbour distances, so the filter passes nearly everything to the exact test
+    # the bf16 matrix-core filter (roomy limit), the fp32 one (room for 16 but not 32 bytes per
+    # point) and the vector kernel (tight limit) must give the same bits; an offset of 50 makes
+    # the expansion's rounding far larger than the neighbour distances, so the fp32 filter
+    # passes nearly everything to the exact test (the bf16 one moves the data first)
     Q, X = W.random_case(1000 + d, 700, 9000, d, kind="uniform")
     for shift in (0.0, 50.0):
         Qs, Xs = (Q + np.float32(shift)), (X + np.float32(shift))
         k = 12
         lo = K.knn_plan(700, 9000, d, k, 1 << 40).min_limit_bytes
         assert K.knn_plan(700, 9000, d, k, lo + 40_000).path == K.KNN_PATH_LOWD
-        assert K.knn_plan(700, 9000, d, k, 64 * W.MB).path == K.KNN_PATH_LOWD_MFMA
+        assert K.knn_plan(700, 9000, d, k, 250_000).path == K.KNN_PATH_LOWD_MFMA
+        assert K.knn_plan(700, 9000, d, k, 64 * W.MB).path == K.KNN_PATH_LOWD_BF16
         a_idx, a_dist = run_gpu(K, Qs, Xs, k, lo + 40_000)
+        c_idx, c_dist = run_gpu(K, Qs, Xs, k, 250_000)
         b_idx, b_dist = run_gpu(K, Qs, Xs, k, 64 * W.MB)
         assert np.array_equal(a_idx, b_idx) and np.array_equal(a_dist, b_dist)
+        assert np.array_equal(a_idx, c_idx) and np.array_equal(a_dist, c_dist)
         o_idx, o_dist, o_next = oracle.knn(Qs, Xs, k)
         say("   shift", shift, check(b_idx, b_dist, o_idx, o_dist, o_next, 9000))
 

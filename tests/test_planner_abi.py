@@ -80,7 +80,7 @@ def test_every_baseline_config_has_a_plan_under_its_limit(m, n, d, k, limit):
     assert p.workspace_bytes <= limit
     assert p.workspace_bytes == p.norms_bytes + p.lists_bytes
     # d <= 3 with room for the packed points takes the matrix-core filter path
-    want = K.KNN_PATH_LOWD_MFMA if d <= 3 else (K.KNN_PATH_LOWD if d <= 8 else K.KNN_PATH_MFMA)
+    want = K.KNN_PATH_LOWD_BF16 if d <= 3 else (K.KNN_PATH_LOWD if d <= 8 else K.KNN_PATH_MFMA)
     assert p.path == want
     assert p.q_chunks * p.chunk_rows >= m
     assert p.chunk_rows == m or p.chunk_rows % p.tile_q == 0
@@ -117,7 +117,10 @@ def test_small_limits_cut_queries_into_chunks_and_never_exceed_the_limit():
 def test_low_d_falls_back_to_the_vector_path_when_packed_points_do_not_fit():
     m, n, d, k = 100_000, 1_000_000, 3, 16
     roomy = K.knn_plan(m, n, d, k, 10 ** 9)
-    assert roomy.path == K.KNN_PATH_LOWD_MFMA and roomy.norms_bytes >= 16 * n
+    assert roomy.path == K.KNN_PATH_LOWD_BF16 and roomy.norms_bytes >= 32 * n
+    mid = K.knn_plan(m, n, d, k, 25 * 10 ** 6)  # 16 bytes per point fit, 32 do not
+    assert mid.path == K.KNN_PATH_LOWD_MFMA and 16 * n <= mid.norms_bytes < 32 * n
+    assert mid.workspace_bytes <= 25 * 10 ** 6
     tight = K.knn_plan(m, n, d, k, 10 ** 7)  # 16 MB of packed points do not fit in 10 MB
     assert tight.path == K.KNN_PATH_LOWD and tight.norms_bytes == 0
     assert tight.workspace_bytes <= 10 ** 7
