@@ -30,8 +30,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr float kInf = __builtin_huge_valf();
 constexpr int kNoIdx = INT_MAX;
 
+// (key, index) order; written without short-circuit operators so that it compiles to
+// compares and mask arithmetic, not branches
 __device__ __forceinline__ bool before(float ka, int ia, float kb, int ib) {
-    return ka < kb || (ka == kb && ia < ib);
+    return (ka < kb) | ((ka == kb) & (ia < ib));
 }
 
 __device__ __forceinline__ bool before64(double ka, int ia, double kb, int ib) {
@@ -51,23 +53,57 @@ __device__ __forceinline__ float wave_min(float v) {
     return v;
 }
 
-// Ascending bitonic sort of one (key, idx) per lane across the 64 lanes of a wave.
-__device__ __forceinline__ void wave_sort64(float& key, int& idx, int lane) {
-#pragma unroll
-    for (int size = 2; size <= 64; size <<= 1) {
-#pragma unroll
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            const float ok = __shfl_xor(key, stride);
-            const int oi = __shfl_xor(idx, stride);
-            const bool ascending = (lane & size) == 0;
-            const bool low_lane = (lane & stride) == 0;
-            const bool keep_min = ascending == low_lane;
-            const bool take = keep_min ? before(ok, oi, key, idx) : before(key, idx, ok, oi);
-            key = take ? ok : key;
-            idx = take ? oi : idx;
-        }
+// Value of lane (lane ^ S).  Strides below 16 stay inside a row of 16 lanes and use DPP
+// (quad permutes; for 4 and 8 a shift left into the low banks and a shift right into the high
+// ones: row_shl:n gives lane i the value of lane i + n), which costs VALU moves instead of a
+// trip through the LDS crossbar.
+template <int S>
+__device__ __forceinline__ int lane_xor(int v) {
+    if constexpr (S == 1) {
+        return __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false);  // quad_perm(1,0,3,2)
+    } else if constexpr (S == 2) {
+        return __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false);  // quad_perm(2,3,0,1)
+    } else if constexpr (S == 4) {
+        const int t = __builtin_amdgcn_update_dpp(v, v, 0x104, 0xF, 0x5, false);  // row_shl:4, banks 0, 2
+        return __builtin_amdgcn_update_dpp(t, v, 0x114, 0xF, 0xA, false);         // row_shr:4, banks 1, 3
+    } else if constexpr (S == 8) {
+        const int t = __builtin_amdgcn_update_dpp(v, v, 0x108, 0xF, 0x3, false);  // row_shl:8, banks 0, 1
+        return __builtin_amdgcn_update_dpp(t, v, 0x118, 0xF, 0xC, false);         // row_shr:8, banks 2, 3
+    } else {
+        return __shfl_xor(v, S);
     }
 }
+template <int S>
+__device__ __forceinline__ float lane_xor(float v) {
+    return __int_as_float(lane_xor<S>(__float_as_int(v)));
+}
+
+template <int SIZE, int STRIDE>
+__device__ __forceinline__ void sort_step(float& key, int& idx, int lane) {
+    const float ok = lane_xor<STRIDE>(key);
+    const int oi = lane_xor<STRIDE>(idx);
+    const bool ascending = (lane & SIZE) == 0;
+    const bool low_lane = (lane & STRIDE) == 0;
+    const bool keep_min = ascending == low_lane;
+    const bool take = keep_min ? before(ok, oi, key, idx) : before(key, idx, ok, oi);
+    key = take ? ok : key;
+    idx = take ? oi : idx;
+}
+template <int SIZE, int STRIDE>
+__device__ __forceinline__ void sort_size(float& key, int& idx, int lane) {
+    sort_step<SIZE, STRIDE>(key, idx, lane);
+    if constexpr (STRIDE > 1) sort_size<SIZE, STRIDE / 2>(key, idx, lane);
+}
+template <int N, int SIZE = 2>
+__device__ __forceinline__ void sort_all(float& key, int& idx, int lane) {
+    sort_size<SIZE, SIZE / 2>(key, idx, lane);
+    if constexpr (SIZE < N) sort_all<N, SIZE * 2>(key, idx, lane);
+}
+
+// Ascending bitonic sort of one (key, idx) per lane: across the 64 lanes of a wave, or inside
+// each group of 16 lanes (group 0 ascending), which needs DPP strides only.
+__device__ __forceinline__ void wave_sort64(float& key, int& idx, int lane) { sort_all<64>(key, idx, lane); }
+__device__ __forceinline__ void wave_sort16(float& key, int& idx, int lane) { sort_all<16>(key, idx, lane); }
 
 // Per-wave LDS scratch used while merging candidates into a list.
 struct MergeScratch {
@@ -79,14 +115,19 @@ struct MergeScratch {
 
 // Merge up to 64 candidates (one per lane; lanes without one pass (+inf, kNoIdx)) into the
 // ascending list gk/gi of k entries in global memory.  Returns the key at position k-1 of
-// the merged list, i.e. the new acceptance threshold.  All 64 lanes must call it together.
-__device__ __noinline__ float wave_merge(float* __restrict__ gk, int* __restrict__ gi, int k, float ckey,
-                            int cidx, const MergeScratch& sc, int lane) {
+// the merged list, i.e. the new acceptance threshold, and its index in tau_idx.  ncand: the
+// candidates sit in lanes 0 .. ncand-1 (wave-uniform; 16 or fewer take a shorter network).
+// All 64 lanes must call it together.
+__device__ __noinline__ float wave_merge_pair(float* __restrict__ gk, int* __restrict__ gi, int k,
+                                              float ckey, int cidx, const MergeScratch& sc, int lane,
+                                              int ncand, int& tau_idx) {
     // A list is read and written only by the wave that owns its query, so wave-level
     // ordering is enough; wave_sync() also orders this wave's earlier global stores to the
     // list before the loads below (same compute unit, same vector L1).
     wave_sync();  // earlier uses of the scratch are finished
-    wave_sort64(ckey, cidx, lane);
+    const bool few = ncand <= 16;
+    if (few) wave_sort16(ckey, cidx, lane);
+    else wave_sort64(ckey, cidx, lane);
     sc.cand_key[lane] = ckey;
     sc.cand_idx[lane] = cidx;
     for (int p = lane; p < k; p += kWave) {
@@ -95,22 +136,28 @@ __device__ __noinline__ float wave_merge(float* __restrict__ gk, int* __restrict
     }
     wave_sync();
     float tau = kInf;
+    int tidx = kNoIdx;
+    bool last = false;  // this lane wrote position k-1 (exactly one lane does)
     // list entries move right by the number of candidates that come before them
     for (int p = lane; p < k; p += kWave) {
         const float ek = sc.list_key[p];
         const int ei = sc.list_idx[p];
         int cnt = 0;
-#pragma unroll
-        for (int step = 32; step > 0; step >>= 1) {
+        for (int step = few ? 8 : 32; step > 0; step >>= 1) {
             const int probe = cnt + step - 1;
             if (before(sc.cand_key[probe], sc.cand_idx[probe], ek, ei)) cnt += step;
         }
-        if (before(sc.cand_key[cnt], sc.cand_idx[cnt], ek, ei)) cnt += 1;  // cnt <= 63 here
+        // cnt <= 15 or 63 here; past the candidates the array holds (+inf, kNoIdx)
+        if (before(sc.cand_key[cnt], sc.cand_idx[cnt], ek, ei)) cnt += 1;
         const int pos = p + cnt;
         if (pos < k) {
             gk[pos] = ek;
             gi[pos] = ei;
-            if (pos == k - 1) tau = ek;
+            if (pos == k - 1) {
+                tau = ek;
+                tidx = ei;
+                last = true;
+            }
         }
     }
     // candidate c lands after the c candidates before it and the list entries <= it
@@ -125,12 +172,25 @@ __device__ __noinline__ float wave_merge(float* __restrict__ gk, int* __restrict
         if (pos < k) {
             gk[pos] = ckey;
             gi[pos] = cidx;
-            if (pos == k - 1) tau = ckey;
+            if (pos == k - 1) {
+                tau = ckey;
+                tidx = cidx;
+                last = true;
+            }
         }
     }
-    tau = wave_min(tau);
+    const int src = __builtin_ctzll(__builtin_amdgcn_ballot_w64(last) | (1ull << 63));
+    tau = __shfl(tau, src);
+    tau_idx = __shfl(tidx, src);
     wave_sync();
     return tau;
+}
+
+__device__ __forceinline__ float wave_merge(float* __restrict__ gk, int* __restrict__ gi, int k,
+                                            float ckey, int cidx, const MergeScratch& sc, int lane,
+                                            int ncand = kWave) {
+    int unused;
+    return wave_merge_pair(gk, gi, k, ckey, cidx, sc, lane, ncand, unused);
 }
 
 // Bookkeeping of the 32 queries one wave owns in the matrix-core kernels: lane % 32 names the
@@ -163,7 +223,7 @@ __device__ __forceinline__ void flush_lists(const WaveLists& w, uint64_t mask, f
             id = w.ci[L * C + w.lane];
         }
         const size_t lb = ((size_t)(w.row0 + L) * w.S + w.s) * w.k;
-        const float t_new = wave_merge(w.lk + lb, w.li + lb, w.k, key, id, w.sc, w.lane);
+        const float t_new = wave_merge(w.lk + lb, w.li + lb, w.k, key, id, w.sc, w.lane, c);
         if ((w.lane & 31) == L) {
             tau = t_new;
             cnt = 0;

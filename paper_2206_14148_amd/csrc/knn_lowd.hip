@@ -81,7 +81,7 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_lowd_kernel(
                 id = ci[L * CP + lane];
             }
             const size_t lb = ((size_t)(wave_row0 + L) * S + s) * k;
-            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane);
+            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane, c);
             if (lane == L) {
                 tau = t_new;
                 cnt = 0;
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_l1_kernel(
                 id = ci[L * CP + lane];
             }
             const size_t lb = ((size_t)(wave_row0 + L) * S + s) * k;
-            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane);
+            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane, c);
             if (lane == L) {
                 tau = t_new;
                 cnt = 0;
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
                 id = ci[L * C + lane];
             }
             const size_t lb = ((size_t)(wave_row0 + L) * S + s) * k;
-            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane);
+            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane, c);
             if (i32 == L) {
                 tau = t_new;
                 tauf = key_bound(t_new);
@@ -704,7 +704,7 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
                 id = ci[(st * 32 + L) * C + lane];
             }
             const size_t lb = ((size_t)(wave_row0 + st * 32 + L) * S + s) * k;
-            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane);
+            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane, cc);
             if (i32 == L) {
                 tau[st] = t_new;
                 tauf[st] = key_bound(st, t_new);
