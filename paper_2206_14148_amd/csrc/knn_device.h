@@ -47,11 +47,7 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
-__device__ __forceinline__ float wave_min(float v) {
-#pragma unroll
-    for (int s = 32; s > 0; s >>= 1) v = fminf(v, __shfl_xor(v, s));
-    return v;
-}
+__device__ __forceinline__ float wave_min(float v);
 
 // Value of lane (lane ^ S).  Strides below 16 stay inside a row of 16 lanes and use DPP
 // (quad permutes; for 4 and 8 a shift left into the low banks and a shift right into the high
@@ -69,6 +65,13 @@ __device__ __forceinline__ int lane_xor(int v) {
     } else if constexpr (S == 8) {
         const int t = __builtin_amdgcn_update_dpp(v, v, 0x108, 0xF, 0x3, false);  // row_shl:8, banks 0, 1
         return __builtin_amdgcn_update_dpp(t, v, 0x118, 0xF, 0xC, false);         // row_shr:8, banks 2, 3
+    } else if constexpr (S == 32) {
+        // v_permlane32_swap exchanges the upper half of its first operand with the lower half
+        // of its second: with both set to v the first result holds the lower half twice and
+        // the second the upper half twice
+        typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+        const u32x2 r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+        return (int)((__lane_id() & 32) ? r.x : r.y);
     } else {
         return __shfl_xor(v, S);
     }
@@ -76,6 +79,16 @@ __device__ __forceinline__ int lane_xor(int v) {
 template <int S>
 __device__ __forceinline__ float lane_xor(float v) {
     return __int_as_float(lane_xor<S>(__float_as_int(v)));
+}
+
+__device__ __forceinline__ float wave_min(float v) {
+    v = fminf(v, lane_xor<32>(v));
+    v = fminf(v, lane_xor<16>(v));
+    v = fminf(v, lane_xor<8>(v));
+    v = fminf(v, lane_xor<4>(v));
+    v = fminf(v, lane_xor<2>(v));
+    v = fminf(v, lane_xor<1>(v));
+    return v;
 }
 
 template <int SIZE, int STRIDE>

@@ -724,45 +724,41 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
     // point's coordinates are read from X.
     const int h4 = 4 * h;
     auto examine = [&](int st, const f32x16& keys, int jblock) {
-        uint64_t pm[16];
-        unsigned nz = 0;
+        unsigned nz = 0;  // registers in which some lane passes the filter
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            pm[e] = __builtin_amdgcn_ballot_w64(keys[e] < tauf[st]);
-            nz |= pm[e] ? (1u << e) : 0u;
-        }
+        for (int e = 0; e < 16; ++e)
+            nz |= __builtin_amdgcn_ballot_w64(keys[e] < tauf[st]) ? (1u << e) : 0u;
         while (nz) {
-            const int e = __builtin_ctz(nz);
+            const int e = __builtin_ctz(nz);  // wave-uniform register number
             nz &= nz - 1;
-            uint64_t mk = 0;
-#pragma unroll
-            for (int t = 0; t < 16; ++t) mk = (e == t) ? pm[t] : mk;  // scalar selects
-            const bool pass = (mk >> lane) & 1;
+            const bool pass = keys[e] < tauf[st];
             const int row = 8 * (e >> 2) + (e & 3) + h4;
-            const int jj = min(jblock + row, n - 1);  // idle lanes stay in bounds
-            const float* __restrict__ xr = X + (int64_t)jj * ldx;
-            // exact test, same arithmetic as the vector-ALU kernel
-            float df = q[st][0] - xr[0];
-            float dd = df * df;
-            if (D > 1) {
-                df = q[st][1] - xr[1];
-                dd = fmaf(df, df, dd);
+            float dd = kInf;
+            if (pass) {  // only these lanes touch X, so no index leaves the matrix
+                const float* __restrict__ xr = X + (int64_t)(jblock + row) * ldx;
+                // exact test, same arithmetic as the vector-ALU kernel
+                float df = q[st][0] - xr[0];
+                dd = df * df;
+                if (D > 1) {
+                    df = q[st][1] - xr[1];
+                    dd = fmaf(df, df, dd);
+                }
+                if (D > 2) {
+                    df = q[st][2] - xr[2];
+                    dd = fmaf(df, df, dd);
+                }
             }
-            if (D > 2) {
-                df = q[st][2] - xr[2];
-                dd = fmaf(df, df, dd);
-            }
-            bool cnd = pass && dd < tau[st];
+            bool cnd = dd < tau[st];
             if (__builtin_amdgcn_ballot_w64(cnd) == 0) continue;
             int own = cnd ? 1 : 0;
-            int oth = __shfl_xor(own, 32);
+            int oth = lane_xor<32>(own);
             const uint64_t need =
                 __builtin_amdgcn_ballot_w64(cnt[st] + own + oth > C) & 0xffffffffull;
             if (need) {
                 flush(st, need);
                 cnd = cnd && dd < tau[st];
                 own = cnd ? 1 : 0;
-                oth = __shfl_xor(own, 32);
+                oth = lane_xor<32>(own);
             }
             if (cnd) {
                 const int slot = (st * 32 + i32) * C + cnt[st] + (h ? oth : 0);
