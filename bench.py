@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per search-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/*_pmc.txt), scaled by the copy-kernel calibration stated there.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "c2_pointcloud_d3": 8.07e9,     # knn_lowd_mfma_kernel: 6.24 GB fetched + 1.84 GB written
+    "c2_pointcloud_d3": 236.95e9,   # knn_lowd_bf16_kernel: 231.31 GB fetched + 5.64 GB written
     "c3_imagelike_d784": 359.0e9,   # knn_mfma_kernel: 359.0 GB fetched + 0.07 GB written
     "c4_clustered_d128": 3455.6e9,  # knn_mfma_qreg_kernel: 3443.4 GB fetched + 12.2 GB written
     "c5_memsweep_d256": 600.0e9,    # knn_mfma_qreg_kernel: 598.9 GB fetched + 1.09 GB written
@@ -402,6 +402,22 @@ def main() -> int:
                     "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_FP32_MATRIX_TFLOPS, "traffic": traffic,
                     "flops_per_pair": 8,
+                    # what a design that stores the distance tile would move: 4 B out + 4 B in
+                    "hbm_equiv_frac": hbm_equiv}
+    elif plan.path == K.KNN_PATH_LOWD_BF16:
+        # Bound: instruction issue of the vector ALU and the matrix core, which share a port on
+        # this chip (their busy cycles add).  Per 32 x 32 keys a wave issues one
+        # v_mfma_f32_32x32x16_bf16 (8 passes = the slot of 8 vector instructions) and 9 vector
+        # instructions (8 three-input minima, 1 compare): 17 slots x 64 lanes / 1024 pairs =
+        # 1.0625 lane-operations per pair against 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz.
+        lane_ops = 17.0 * 64.0 / 1024.0
+        peak = 256 * 4 * 16 * 2.4e9 / 1e12
+        achieved = lane_ops * pairs_per_launch / avg_launch_s / 1e12
+        roofline = {"bound": "alu", "kernel": "knn_lowd_bf16_kernel", "achieved": achieved,
+                    "peak": peak, "unit": "Tlane-op/s", "frac": achieved / peak, "traffic": traffic,
+                    "lane_ops_per_pair": lane_ops,
+                    # the filter contraction alone: 2 x 16 bf16 flops per pair against 2.5 PFLOP/s
+                    "mfma_bf16_frac": 32.0 * pairs_per_launch / avg_launch_s / 2.5e15,
                     # what a design that stores the distance tile would move: 4 B out + 4 B in
                     "hbm_equiv_frac": hbm_equiv}
     elif plan.path == K.KNN_PATH_L1:

@@ -541,20 +541,43 @@ __global__ void knn_bbox_init_kernel(unsigned* __restrict__ hdr) {
 template <int D>
 __global__ __launch_bounds__(256) void knn_bbox_kernel(const float* __restrict__ X, int64_t ldx,
                                                        int n, unsigned* __restrict__ hdr) {
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    const int jc = j < n ? j : n - 1;  // idle lanes repeat the last point
+    // grid-stride over the points, one running box per thread, then wave and workgroup
+    // reductions, so that a workgroup sends 2 D atomics however many points it saw
+    __shared__ float box[4][2 * D];
+    float lo[D], hi[D];
 #pragma unroll
     for (int t = 0; t < D; ++t) {
-        const float v = X[(int64_t)jc * ldx + t];
-        float lo = v, hi = v;
+        lo[t] = kInf;
+        hi[t] = -kInf;
+    }
+    for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < n; j += (int64_t)gridDim.x * 256) {
+#pragma unroll
+        for (int t = 0; t < D; ++t) {
+            const float v = X[j * ldx + t];
+            lo[t] = fminf(lo[t], v);
+            hi[t] = fmaxf(hi[t], v);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < D; ++t) {
 #pragma unroll
         for (int s = 32; s > 0; s >>= 1) {
-            lo = fminf(lo, __shfl_xor(lo, s));
-            hi = fmaxf(hi, __shfl_xor(hi, s));
+            lo[t] = fminf(lo[t], __shfl_xor(lo[t], s));
+            hi[t] = fmaxf(hi[t], __shfl_xor(hi[t], s));
         }
         if ((threadIdx.x & 63) == 0) {
-            atomicMin(hdr + 1 + t, ordered_bits(lo));
-            atomicMax(hdr + 4 + t, ordered_bits(hi));
+            box[threadIdx.x >> 6][t] = lo[t];
+            box[threadIdx.x >> 6][D + t] = hi[t];
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < D) {
+        const int t = threadIdx.x;
+        const float l = fminf(fminf(box[0][t], box[1][t]), fminf(box[2][t], box[3][t]));
+        const float u = fmaxf(fmaxf(box[0][D + t], box[1][D + t]), fmaxf(box[2][D + t], box[3][D + t]));
+        if (l <= u) {  // the workgroup saw at least one point
+            atomicMin(hdr + 1 + t, ordered_bits(l));
+            atomicMax(hdr + 4 + t, ordered_bits(u));
         }
     }
 }
@@ -924,7 +947,8 @@ static hipError_t launch_lowd_bf16_d(const float* Q, int64_t ldq, const float* X
     const dim3 pgrid((unsigned)((n + 255) / 256));
     if (pack) {
         knn_bbox_init_kernel<<<dim3(1), dim3(64), 0, stream>>>(hdr);
-        knn_bbox_kernel<D><<<pgrid, dim3(256), 0, stream>>>(X, ldx, (int)n, hdr);
+        const unsigned bgrid = pgrid.x < 1024u ? pgrid.x : 1024u;
+        knn_bbox_kernel<D><<<dim3(bgrid), dim3(256), 0, stream>>>(X, ldx, (int)n, hdr);
         knn_pack_bf16_kernel<D><<<pgrid, dim3(256), 0, stream>>>(X, ldx, (int)n, Xp, hdr);
         hipError_t e0 = hipGetLastError();
         if (e0 != hipSuccess) return e0;
