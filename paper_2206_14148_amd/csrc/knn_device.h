@@ -128,12 +128,13 @@ struct MergeScratch {
 
 // Merge up to 64 candidates (one per lane; lanes without one pass (+inf, kNoIdx)) into the
 // ascending list gk/gi of k entries in global memory.  Returns the key at position k-1 of
-// the merged list, i.e. the new acceptance threshold, and its index in tau_idx.  ncand: the
-// candidates sit in lanes 0 .. ncand-1 (wave-uniform; 16 or fewer take a shorter network).
-// All 64 lanes must call it together.
-__device__ __noinline__ float wave_merge_pair(float* __restrict__ gk, int* __restrict__ gi, int k,
-                                              float ckey, int cidx, const MergeScratch& sc, int lane,
-                                              int ncand, int& tau_idx) {
+// the merged list, i.e. the new acceptance threshold, together with that entry's index: the
+// key's bits in the low word, the index in the high word (both stay in registers that way).
+// ncand: the candidates sit in lanes 0 .. ncand-1 (wave-uniform; 16 or fewer take a shorter
+// network).  All 64 lanes must call it together.
+__device__ __noinline__ uint64_t wave_merge_pair(float* __restrict__ gk, int* __restrict__ gi, int k,
+                                                 float ckey, int cidx, const MergeScratch& sc,
+                                                 int lane, int ncand) {
     // A list is read and written only by the wave that owns its query, so wave-level
     // ordering is enough; wave_sync() also orders this wave's earlier global stores to the
     // list before the loads below (same compute unit, same vector L1).
@@ -194,16 +195,17 @@ __device__ __noinline__ float wave_merge_pair(float* __restrict__ gk, int* __res
     }
     const int src = __builtin_ctzll(__builtin_amdgcn_ballot_w64(last) | (1ull << 63));
     tau = __shfl(tau, src);
-    tau_idx = __shfl(tidx, src);
+    tidx = __shfl(tidx, src);
     wave_sync();
-    return tau;
+    return ((uint64_t)(unsigned)tidx << 32) | __float_as_uint(tau);
 }
+__device__ __forceinline__ float merged_key(uint64_t r) { return __uint_as_float((unsigned)r); }
+__device__ __forceinline__ int merged_idx(uint64_t r) { return (int)(r >> 32); }
 
 __device__ __forceinline__ float wave_merge(float* __restrict__ gk, int* __restrict__ gi, int k,
                                             float ckey, int cidx, const MergeScratch& sc, int lane,
                                             int ncand = kWave) {
-    int unused;
-    return wave_merge_pair(gk, gi, k, ckey, cidx, sc, lane, ncand, unused);
+    return merged_key(wave_merge_pair(gk, gi, k, ckey, cidx, sc, lane, ncand));
 }
 
 // Bookkeeping of the 32 queries one wave owns in the matrix-core kernels: lane % 32 names the

@@ -360,10 +360,11 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
     const float b1 = h ? 1.f : -2.f * q[1];
     const float xmax = __uint_as_float(*xn_max_bits);
 
-    // A pair with exact fp32 distance < tau has key < (tau - qn) + slack: the key and qn each
+    // A pair with exact fp32 distance <= tau has key < (tau - qn) + slack: the key and qn each
     // carry a few roundings relative to (||x||^2 + ||q||^2), the distance a few relative to
     // itself; 2^-19 of their sum is several times the worst case.
     float tau = active ? kInf : -kInf;
+    int taui = active ? kNoIdx : -1;  // (tau, taui): key and index of the current k-th best
     auto key_bound = [&](float t) { return (t - qn) + 0x1p-19f * (xmax + qn + t); };
     float tauf = key_bound(tau);
     int cnt = 0;  // candidates buffered for this lane's query (same in both halves)
@@ -381,9 +382,11 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
                 id = ci[L * C + lane];
             }
             const size_t lb = ((size_t)(wave_row0 + L) * S + s) * k;
-            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane, c);
+            const uint64_t mr = wave_merge_pair(lk + lb, li + lb, k, key, id, sc, lane, c);
+            const float t_new = merged_key(mr);
             if (i32 == L) {
                 tau = t_new;
+                taui = merged_idx(mr);
                 tauf = key_bound(t_new);
                 cnt = 0;
             }
@@ -423,14 +426,16 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
                 df = q[2] - xv[2];
                 dd = fmaf(df, df, dd);
             }
-            bool c = has && dd < tau;
+            // the halves of the wave hold interleaved runs of four rows, so pairs do not come
+            // in index order: compare on (key, index) with the current k-th best
+            bool c = has && before(dd, jblock + row, tau, taui);
             if (__builtin_amdgcn_ballot_w64(c) == 0) continue;
             int own = c ? 1 : 0;
             int oth = __shfl_xor(own, 32);
             const uint64_t need = __builtin_amdgcn_ballot_w64(cnt + own + oth > C) & 0xffffffffull;
             if (need) {
                 flush(need);
-                c = c && dd < tau;
+                c = c && before(dd, jblock + row, tau, taui);
                 own = c ? 1 : 0;
                 oth = __shfl_xor(own, 32);
             }
@@ -672,8 +677,8 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
     float q[NS][3];
     bf16x8 bq[NS];
     float qn[NS], cross[NS], tau[NS], tauf[NS];
-    int cnt[NS];
-    // A pair with exact fp32 distance < tau has a filter key below (tau - qn) + slack: the cross
+    int taui[NS], cnt[NS];  // (tau, taui): key and index of the query's current k-th best
+    // A pair with exact fp32 distance <= tau has a filter key below (tau - qn) + slack: the cross
     // terms the bf16 pieces leave out (<= 6.1 * 2^-18 ||x'|| ||q'|| < 2^-15 sqrt(xmax qn)), the
     // fp32 roundings of the accumulation, of qn, of the moved coordinates and of the distance
     // itself (each a few 2^-24 of ||x'||^2 + ||q'||^2 + tau; 2^-19 of that sum is several times
@@ -709,6 +714,7 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
         else w = uint4{qh[0] | (qh[1] << 16), qh[2] | (one << 16), 0u, 0u};
         bq[st] = __builtin_bit_cast(bf16x8, w);
         tau[st] = active ? kInf : -kInf;
+        taui[st] = active ? kNoIdx : -1;
         tauf[st] = key_bound(st, tau[st]);
         cnt[st] = 0;
     }
@@ -727,9 +733,11 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
                 id = ci[(st * 32 + L) * C + lane];
             }
             const size_t lb = ((size_t)(wave_row0 + st * 32 + L) * S + s) * k;
-            const float t_new = wave_merge(lk + lb, li + lb, k, key, id, sc, lane, cc);
+            const uint64_t mr = wave_merge_pair(lk + lb, li + lb, k, key, id, sc, lane, cc);
+            const float t_new = merged_key(mr);
             if (i32 == L) {
                 tau[st] = t_new;
+                taui[st] = merged_idx(mr);
                 tauf[st] = key_bound(st, t_new);
                 cnt[st] = 0;
             }
@@ -771,7 +779,10 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
                     dd = fmaf(df, df, dd);
                 }
             }
-            bool cnd = dd < tau[st];
+            // The two halves of the wave hold interleaved runs of four rows, so pairs do not
+            // reach this test in index order: the comparison with the current k-th best is on
+            // (key, index), or a pair could lose a tie against a higher index merged earlier.
+            bool cnd = pass && before(dd, jblock + row, tau[st], taui[st]);
             if (__builtin_amdgcn_ballot_w64(cnd) == 0) continue;
             int own = cnd ? 1 : 0;
             int oth = lane_xor<32>(own);
@@ -779,7 +790,7 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
                 __builtin_amdgcn_ballot_w64(cnt[st] + own + oth > C) & 0xffffffffull;
             if (need) {
                 flush(st, need);
-                cnd = cnd && dd < tau[st];
+                cnd = cnd && before(dd, jblock + row, tau[st], taui[st]);
                 own = cnd ? 1 : 0;
                 oth = lane_xor<32>(own);
             }

@@ -358,3 +358,23 @@ def test_l1_exact_ties_and_limit_independence(K, oracle):
     idx2, dist2 = K.knn_search(Qp[:, :6], Xp[:, :6], 9, 64 * W.MB, metric="l1")
     torch.cuda.synchronize()
     assert np.array_equal(idx2.cpu().numpy(), ref[0])
+
+
+@pytest.mark.parametrize("seed,d,span,n,m,k", [(1, 2, 30, 50_000, 1500, 16), (2, 3, 8, 60_000, 1500, 16),
+                                                (3, 1, 500, 40_000, 1000, 7), (4, 3, 5, 20_000, 1500, 50)])
+def test_exact_ties_keep_the_lower_index_on_every_low_d_path(K, oracle, seed, d, span, n, m, k):
+    # integer coordinates from a small range: dozens of points at exactly the k-th distance.
+    # The matrix-core filter kernels see the two half-waves' rows out of index order, so
+    # their acceptance test compares (key, index); all three low-d paths must reproduce the
+    # oracle's (distance, index) order exactly.
+    g = np.random.Generator(np.random.PCG64(W.SEED_BASE + 12_000_000 + seed))
+    X = g.integers(0, span, size=(n, d)).astype(np.float32)
+    Q = g.integers(0, span, size=(m, d)).astype(np.float32)
+    o_idx, o_dist, _ = oracle.knn(Q, X, k)
+    paths = set()
+    for limit in (64 * W.MB, 16 * n + 300_000, 200_000):
+        paths.add(K.knn_plan(m, n, d, k, limit).path)
+        idx, dist = run_gpu(K, Q, X, k, limit)
+        assert np.array_equal(idx, o_idx), limit
+        assert np.array_equal(dist.astype(np.float64), o_dist), limit
+    assert paths == {K.KNN_PATH_LOWD_BF16, K.KNN_PATH_LOWD_MFMA, K.KNN_PATH_LOWD}
