@@ -263,14 +263,17 @@ __global__ __launch_bounds__(256) void knn_block_points_kernel(const float* __re
 // wave feeds to the MFMAs (d/2 registers, scaled by -2) for the whole kernel, so only the
 // point stream is staged: half the global requests, half the LDS writes, and the L2 of an XCD
 // holds nothing but the point windows its workgroups share.  The chunk loop of a tile is
-// unrolled (NCH is even), which also names the two prefetch register sets statically.
+// unrolled (together with a second tile when NCH is odd), which also names the two prefetch
+// register sets statically.
 // ---------------------------------------------------------------------------------------
 template <int NCH, bool ALIGNED, bool BLOCKED>
 __global__ __launch_bounds__(256, 2) void knn_mfma_qreg_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
     const f32x4* __restrict__ Xb, const float* __restrict__ xn, int cosine, int rows, int n, int d,
     int k, int S, int split_len, int BQ, int BS, float* __restrict__ lk, int* __restrict__ li) {
-    static_assert(NCH % 2 == 0, "the chunk loop alternates two LDS buffers and register sets");
+    // the steps (tile, chunk) alternate two LDS buffers and two register sets; the loops are
+    // unrolled far enough (two tiles when NCH is odd) for the alternation to be static
+    constexpr int TU = (NCH % 2) ? 2 : 1;
     constexpr int TQ = kMfmaTileQ, TX = kMfmaTileX, KC = kMfmaKC, RS = kMfmaRowStride;
     constexpr int C = kMfmaCand;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -383,51 +386,57 @@ __global__ __launch_bounds__(256, 2) void knn_mfma_qreg_kernel(
     __syncthreads();
 
     f32x16 acc[4];
-    for (int tile = 0; tile < ntiles; ++tile) {
-        {
-            const float* xt = xns + (tile & 1) * TX;
+    for (int tile0 = 0; tile0 < ntiles; tile0 += TU) {
 #pragma unroll
-            for (int pb = 0; pb < 4; ++pb) {
+        for (int tt = 0; tt < TU; ++tt) {
+            const int tile = tile0 + tt;
+            if (tile >= ntiles) break;  // uniform
+            {
+                const float* xt = xns + (tile & 1) * TX;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const f32x4 v = *reinterpret_cast<const f32x4*>(xt + pb * 32 + g * 8 + h * 4);
-                    acc[pb][g * 4 + 0] = v[0];
-                    acc[pb][g * 4 + 1] = v[1];
-                    acc[pb][g * 4 + 2] = v[2];
-                    acc[pb][g * 4 + 3] = v[3];
+                for (int pb = 0; pb < 4; ++pb) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const f32x4 v = *reinterpret_cast<const f32x4*>(xt + pb * 32 + g * 8 + h * 4);
+                        acc[pb][g * 4 + 0] = v[0];
+                        acc[pb][g * 4 + 1] = v[1];
+                        acc[pb][g * 4 + 2] = v[2];
+                        acc[pb][g * 4 + 3] = v[3];
+                    }
                 }
             }
-        }
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            const int step = tile * NCH + c;
-            Staged& mine = (c & 1) ? set_odd : set_even;        // receives step + 2
-            const Staged& next = (c & 1) ? set_even : set_odd;  // holds step + 1
-            fetch(step + 2 < total ? step + 2 : total - 1, mine);
-            const float* xb = xs + (c & 1) * TX * RS;
-            f32x4 a[2][4];
+            for (int c = 0; c < NCH; ++c) {
+                const int step = tile * NCH + c;
+                const int par = (tt * NCH + c) & 1;  // == step & 1, known at compile time
+                Staged& mine = par ? set_odd : set_even;        // receives step + 2
+                const Staged& next = par ? set_even : set_odd;  // holds step + 1
+                fetch(step + 2 < total ? step + 2 : total - 1, mine);
+                const float* xb = xs + par * TX * RS;
+                f32x4 a[2][4];
 #pragma unroll
-            for (int g = 0; g < 2; ++g) {
-#pragma unroll
-                for (int pb = 0; pb < 4; ++pb)
-                    a[g][pb] = *reinterpret_cast<const f32x4*>(xb + (pb * 32 + i32) * RS + g * 8 + h * 4);
-            }
-#pragma unroll
-            for (int g = 0; g < 2; ++g) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
+                for (int g = 0; g < 2; ++g) {
 #pragma unroll
                     for (int pb = 0; pb < 4; ++pb)
-                        acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][pb][e], qreg[2 * c + g][e],
-                                                                       acc[pb], 0, 0, 0);
+                        a[g][pb] = *reinterpret_cast<const f32x4*>(xb + (pb * 32 + i32) * RS + g * 8 + h * 4);
                 }
-                if (g == 0 && step + 1 < total) stash(step + 1, next);
+#pragma unroll
+                for (int g = 0; g < 2; ++g) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                        for (int pb = 0; pb < 4; ++pb)
+                            acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][pb][e], qreg[2 * c + g][e],
+                                                                           acc[pb], 0, 0, 0);
+                    }
+                    if (g == 0 && step + 1 < total) stash(step + 1, next);
+                }
+                if (c == NCH - 1) {
+                    if (cosine) scale_rows(acc, rns + (tile & 1) * TX, h);
+                    tile_epilogue<C>(acc, wl, j0 + tile * TX, tau, cnt);
+                }
+                __syncthreads();
             }
-            if (c == NCH - 1) {
-                if (cosine) scale_rows(acc, rns + (tile & 1) * TX, h);
-                tile_epilogue<C>(acc, wl, j0 + tile * TX, tau, cnt);
-            }
-            __syncthreads();
         }
     }
     const uint64_t rest = __builtin_amdgcn_ballot_w64(cnt > 0) & 0xffffffffull;
@@ -504,7 +513,8 @@ hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx,
             else KNN_QREG_LAUNCH_AB(N, false, false);                                             \
         }                                                                                         \
     } while (0)
-        if (nch <= 2) KNN_QREG_LAUNCH(2);
+        if (nch <= 1) KNN_QREG_LAUNCH(1);
+        else if (nch <= 2) KNN_QREG_LAUNCH(2);
         else if (nch <= 4) KNN_QREG_LAUNCH(4);
         else if (nch <= 6) KNN_QREG_LAUNCH(6);
         else if (nch <= 8) KNN_QREG_LAUNCH(8);

@@ -77,6 +77,8 @@ SMALL = [
     (17, 140, 2300, 256, 9, "normal"),   # 16 chunks
     (18, 140, 2300, 257, 9, "normal"),   # first d of the streamed-query kernel, unaligned
     (19, 140, 2300, 272, 9, "normal"),   # streamed-query kernel, aligned
+    (20, 70, 300, 12, 5, "normal"),      # one chunk (d <= 16), an odd number of point tiles
+    (21, 70, 128, 16, 5, "normal"),      # one chunk, a single tile
 ]
 
 
