@@ -59,8 +59,9 @@ typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1, KNN_METRIC_L1 = 2 } k
 #define KNN_PATH_L1 3   /* L1 metric: absolute differences on the vector ALU, any d   */
 #define KNN_PATH_LOWD_MFMA 2 /* d <= 3 and room for 16 n bytes of packed points:
                                 matrix-core filter + the same exact test as path 0 */
-#define KNN_PATH_LOWD_BF16 4 /* d <= 3 and room for 32 n bytes: the filter in bf16 pieces on
-                                points moved by their bounding box's midpoint, same exact test */
+#define KNN_PATH_LOWD_BF16 4 /* d <= 8 and room for 32 n bytes (d <= 4) or 64 n bytes: the filter
+                                in bf16 pieces on points moved by their bounding box's midpoint,
+                                same exact test */
 
 /*
  * The plan: how the call is cut into pieces (section 4.3: split the largest

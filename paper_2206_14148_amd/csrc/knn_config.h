@@ -20,8 +20,10 @@ constexpr int kPmMaxD = 3;
 constexpr int kPmTileQ = 128;
 constexpr int kPmCand = 32;                      // candidate slots per query (LDS)
 
-// the same with a bf16 filter (room for 32 bytes per point): each wave owns kPbSets sets of 32
-// queries, so one load of a block of points feeds kPbSets MFMAs.
+// the same with a bf16 filter, d <= kPbMaxD (room for 32 bytes per point up to d = 4, 64 above):
+// each wave owns kPbSets sets of 32 queries, so one load of a block of points feeds kPbSets
+// MFMAs per 16 K slots.
+constexpr int kPbMaxD = 8;
 constexpr int kPbSets = 2;
 constexpr int kPbTileQ = 4 * 32 * kPbSets;       // query rows per workgroup
 constexpr int kPbCand = 16;                      // candidate slots per query (LDS)

@@ -30,9 +30,10 @@ hipError_t launch_lowd_mfma(const float* Q, int64_t ldq, const float* X, int64_t
                             int64_t rows, int64_t n, int d, int k, int S, bool pack, float* lk,
                             int* li, hipStream_t stream);
 
-// d <= kPmMaxD with room for 32 n bytes: the same keys again, found through a bf16 MFMA filter on
-// points and queries moved by the midpoint of the points' bounding box.  `packed` = kAlign bytes
-// (header: max moved norm, bounding box) + 32 n bytes; pack / rows == 0 as above.
+// d <= kPbMaxD with room for 32 n bytes (d <= 4) or 64 n bytes: the same keys again, found through
+// a bf16 MFMA filter on points and queries moved by the midpoint of the points' bounding box.
+// `packed` = kAlign bytes (header: max moved norm, bounding box) + the packed points; pack /
+// rows == 0 as above.
 hipError_t launch_lowd_bf16(const float* Q, int64_t ldq, const float* X, int64_t ldx, void* packed,
                             int64_t rows, int64_t n, int d, int k, int S, bool pack, float* lk,
                             int* li, hipStream_t stream);

@@ -535,12 +535,12 @@ __device__ __forceinline__ float ordered_value(unsigned k) {
 }
 
 // header words of the packed area: 0 max ||x - c||^2 (bits of a non-negative float),
-// 1..3 per-dimension minimum, 4..6 per-dimension maximum (ordered keys)
+// 1 .. kPbMaxD per-dimension minimum, kPbMaxD + 1 .. 2 kPbMaxD per-dimension maximum (ordered keys)
 __global__ void knn_bbox_init_kernel(unsigned* __restrict__ hdr) {
     const int t = threadIdx.x;
     if (t == 0) hdr[0] = 0u;
-    if (t >= 1 && t <= 3) hdr[t] = 0xffffffffu;
-    if (t >= 4 && t <= 6) hdr[t] = 0u;
+    if (t >= 1 && t <= kPbMaxD) hdr[t] = 0xffffffffu;
+    if (t > kPbMaxD && t <= 2 * kPbMaxD) hdr[t] = 0u;
 }
 
 template <int D>
@@ -582,49 +582,89 @@ __global__ __launch_bounds__(256) void knn_bbox_kernel(const float* __restrict__
         const float u = fmaxf(fmaxf(box[0][D + t], box[1][D + t]), fmaxf(box[2][D + t], box[3][D + t]));
         if (l <= u) {  // the workgroup saw at least one point
             atomicMin(hdr + 1 + t, ordered_bits(l));
-            atomicMax(hdr + 4 + t, ordered_bits(u));
+            atomicMax(hdr + 1 + kPbMaxD + t, ordered_bits(u));
         }
     }
 }
 
 template <int D>
-__device__ __forceinline__ void bbox_centre(const unsigned* __restrict__ hdr, float (&c)[3]) {
+__device__ __forceinline__ void bbox_centre(const unsigned* __restrict__ hdr, float (&c)[D]) {
 #pragma unroll
-    for (int t = 0; t < 3; ++t)
-        c[t] = t < D ? 0.5f * ordered_value(hdr[1 + t]) + 0.5f * ordered_value(hdr[4 + t]) : 0.f;
+    for (int t = 0; t < D; ++t)
+        c[t] = 0.5f * ordered_value(hdr[1 + t]) + 0.5f * ordered_value(hdr[1 + kPbMaxD + t]);
 }
 
-// 32 bytes per point: 16 for the lanes 0..31 of the MFMA's A operand (K slots 0..7), 16 for the
-// lanes 32..63 (K slots 8..15)
+// K slots of the filter's contraction for dimension D (3 D + 3 of them, padded with zeros to
+// NM MFMAs of 16 slots): slot s < D pairs xh_s with -2 qh_s, D <= s < 2D pairs xh with -2 ql,
+// 2D <= s < 3D pairs xl with -2 qh, and the three pieces of the squared norm meet 1.
+template <int D>
+struct FilterSlots {
+    static constexpr int kUsed = 3 * D + 3;
+    static constexpr int kMfmas = (kUsed + 15) / 16;  // 1 for D <= 4, 2 for D <= 8
+};
+
+// A-operand piece of slot s: xh / xl are the bf16 pieces of the moved coordinates, np the three
+// pieces of the squared norm
+template <int D>
+__device__ __forceinline__ unsigned slot_a(int s, const unsigned (&xh)[D], const unsigned (&xl)[D],
+                                           const unsigned (&np)[3]) {
+    if (s < 2 * D) return xh[s < D ? s : s - D];
+    if (s < 3 * D) return xl[s - 2 * D];
+    if (s < 3 * D + 3) return np[s - 3 * D];
+    return 0u;
+}
+// B-operand piece of slot s: qh / ql hold the bf16 bits of -2 qh_t and -2 ql_t
+template <int D>
+__device__ __forceinline__ unsigned slot_b(int s, const unsigned (&qh)[D], const unsigned (&ql)[D]) {
+    if (s < D) return qh[s];
+    if (s < 2 * D) return ql[s - D];
+    if (s < 3 * D) return qh[s - 2 * D];
+    if (s < 3 * D + 3) return 0x3f80u;  // 1.0
+    return 0u;
+}
+
+// 32 bytes per point and MFMA: 16 for the lanes 0..31 of the A operand (K slots 0..7 of that
+// MFMA), 16 for the lanes 32..63 (slots 8..15).  Record (j, i, half) is Xp[(j * NM + i) * 2 + half].
 template <int D>
 __global__ __launch_bounds__(256) void knn_pack_bf16_kernel(const float* __restrict__ X,
                                                             int64_t ldx, int n,
                                                             uint4* __restrict__ Xp,
                                                             unsigned* __restrict__ hdr) {
+    constexpr int NM = FilterSlots<D>::kMfmas;
     const int j = blockIdx.x * 256 + threadIdx.x;
-    float c[3];
+    float c[D];
     bbox_centre<D>(hdr, c);
     float nrm = 0.f;
     if (j < n) {
-        float v[3] = {0.f, 0.f, 0.f};
+        float v[D];
 #pragma unroll
         for (int t = 0; t < D; ++t) v[t] = X[(int64_t)j * ldx + t] - c[t];
         nrm = v[0] * v[0];
-        nrm = fmaf(v[1], v[1], nrm);
-        nrm = fmaf(v[2], v[2], nrm);
-        unsigned xh[3], xl[3];
 #pragma unroll
-        for (int t = 0; t < 3; ++t) {
+        for (int t = 1; t < D; ++t) nrm = fmaf(v[t], v[t], nrm);
+        unsigned xh[D], xl[D], np[3];
+#pragma unroll
+        for (int t = 0; t < D; ++t) {
             xh[t] = bf16_bits(v[t]);
             xl[t] = bf16_bits(v[t] - bf16_value(xh[t]));
         }
-        const unsigned nh = bf16_bits(nrm);
-        const float r1 = nrm - bf16_value(nh);
-        const unsigned nm = bf16_bits(r1);
-        const unsigned nl = bf16_bits(r1 - bf16_value(nm));
-        Xp[(size_t)j * 2] = uint4{xh[0] | (xh[1] << 16), xh[2] | (xh[0] << 16),
-                                  xh[1] | (xh[2] << 16), nh | (nm << 16)};
-        Xp[(size_t)j * 2 + 1] = uint4{xl[0] | (xl[1] << 16), xl[2] | (nl << 16), 0u, 0u};
+        np[0] = bf16_bits(nrm);
+        const float r1 = nrm - bf16_value(np[0]);
+        np[1] = bf16_bits(r1);
+        np[2] = bf16_bits(r1 - bf16_value(np[1]));
+#pragma unroll
+        for (int i = 0; i < NM; ++i) {
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                unsigned w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int s0 = 16 * i + 8 * half + 2 * e;
+                    w[e] = slot_a<D>(s0, xh, xl, np) | (slot_a<D>(s0 + 1, xh, xl, np) << 16);
+                }
+                Xp[((size_t)j * NM + i) * 2 + half] = uint4{w[0], w[1], w[2], w[3]};
+            }
+        }
     }
 #pragma unroll
     for (int s = 32; s > 0; s >>= 1) nrm = fmaxf(nrm, __shfl_xor(nrm, s));
@@ -632,13 +672,14 @@ __global__ __launch_bounds__(256) void knn_pack_bf16_kernel(const float* __restr
 }
 
 template <int D>
-__global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
+__global__ __launch_bounds__(256, FilterSlots<D>::kMfmas == 1 ? 4 : 3) void knn_lowd_bf16_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
     const uint4* __restrict__ Xp, const unsigned* __restrict__ hdr, int rows, int n, int k, int S,
     int split_len, float* __restrict__ lk, int* __restrict__ li) {
     constexpr int C = kPbCand;
     constexpr int NS = kPbSets;  // query sets of 32 per wave: one A-operand load feeds NS MFMAs
-    constexpr int UB = 4;        // 32-point blocks per loop iteration
+    constexpr int NM = FilterSlots<D>::kMfmas;  // MFMAs (of 16 K slots) per 32 x 32 keys
+    constexpr int UB = 4 / NM;   // 32-point blocks per loop iteration
     constexpr int PTS = UB * 32; // points per loop iteration
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
@@ -668,14 +709,14 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
     }
 
     // the filter sees points and queries moved by the midpoint of the points' bounding box
-    float c[3];
+    float c[D];
     bbox_centre<D>(hdr, c);
     const float xmax = __uint_as_float(hdr[0]);
 
-    // per query set: the query (original coordinates, for the exact test), the B operand, the
+    // per query set: the query (original coordinates, for the exact test), the B operands, the
     // thresholds and the number of buffered candidates (same value in both halves of the wave)
-    float q[NS][3];
-    bf16x8 bq[NS];
+    float q[NS][D];
+    bf16x8 bq[NS][NM];
     float qn[NS], cross[NS], tau[NS], tauf[NS];
     int taui[NS], cnt[NS];  // (tau, taui): key and index of the query's current k-th best
     // A pair with exact fp32 distance <= tau has a filter key below (tau - qn) + slack: the cross
@@ -690,29 +731,38 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
     for (int st = 0; st < NS; ++st) {
         const int r = wave_row0 + st * 32 + i32;
         const bool active = r < rows;
-        float qc[3];
+        float qc[D];
 #pragma unroll
-        for (int t = 0; t < 3; ++t) {
-            q[st][t] = (t < D && active) ? Q[(int64_t)r * ldq + t] : 0.f;
-            qc[t] = (t < D && active) ? q[st][t] - c[t] : 0.f;
+        for (int t = 0; t < D; ++t) {
+            q[st][t] = active ? Q[(int64_t)r * ldq + t] : 0.f;
+            qc[t] = active ? q[st][t] - c[t] : 0.f;
         }
-        qn[st] = fmaf(qc[2], qc[2], fmaf(qc[1], qc[1], qc[0] * qc[0]));
-        cross[st] = 0x1p-15f * sqrtf(xmax * qn[st]);
-        // B operand: K slots 0..7 = -2qh0 -2qh1 -2qh2 -2ql0 -2ql1 -2ql2 1 1, slots 8..15 =
-        // -2qh0 -2qh1 -2qh2 1 0 0 0 0, against the layout written by knn_pack_bf16_kernel
-        unsigned qh[3], ql[3];
+        qn[st] = qc[0] * qc[0];
 #pragma unroll
-        for (int t = 0; t < 3; ++t) {
+        for (int t = 1; t < D; ++t) qn[st] = fmaf(qc[t], qc[t], qn[st]);
+        cross[st] = 0x1p-15f * sqrtf(xmax * qn[st]);
+        // B operands: the pieces -2 qh, -2 ql and 1 in the slot order of FilterSlots; a lane of
+        // half h holds slots 8h .. 8h + 7 of each MFMA
+        unsigned qh[D], ql[D];
+#pragma unroll
+        for (int t = 0; t < D; ++t) {
             const unsigned hb = bf16_bits(qc[t]);
             const float hv = bf16_value(hb);
             qh[t] = bf16_bits(-2.f * hv);                                 // exact
             ql[t] = bf16_bits(-2.f * bf16_value(bf16_bits(qc[t] - hv)));  // exact
         }
-        const unsigned one = 0x3f80u;
-        uint4 w;
-        if (h == 0) w = uint4{qh[0] | (qh[1] << 16), qh[2] | (ql[0] << 16), ql[1] | (ql[2] << 16), one | (one << 16)};
-        else w = uint4{qh[0] | (qh[1] << 16), qh[2] | (one << 16), 0u, 0u};
-        bq[st] = __builtin_bit_cast(bf16x8, w);
+#pragma unroll
+        for (int i = 0; i < NM; ++i) {
+            unsigned w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int s0 = 16 * i + 2 * e;  // slot of the lower half-wave
+                const unsigned lo = slot_b<D>(s0, qh, ql) | (slot_b<D>(s0 + 1, qh, ql) << 16);
+                const unsigned hi = slot_b<D>(s0 + 8, qh, ql) | (slot_b<D>(s0 + 9, qh, ql) << 16);
+                w[e] = h ? hi : lo;
+            }
+            bq[st][i] = __builtin_bit_cast(bf16x8, uint4{w[0], w[1], w[2], w[3]});
+        }
         tau[st] = active ? kInf : -kInf;
         taui[st] = active ? kNoIdx : -1;
         tauf[st] = key_bound(st, tau[st]);
@@ -770,12 +820,9 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
                 // exact test, same arithmetic as the vector-ALU kernel
                 float df = q[st][0] - xr[0];
                 dd = df * df;
-                if (D > 1) {
-                    df = q[st][1] - xr[1];
-                    dd = fmaf(df, df, dd);
-                }
-                if (D > 2) {
-                    df = q[st][2] - xr[2];
+#pragma unroll
+                for (int t = 1; t < D; ++t) {
+                    df = q[st][t] - xr[t];
                     dd = fmaf(df, df, dd);
                 }
             }
@@ -803,7 +850,7 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
         }
     };
 
-    auto process = [&](const uint4 (&a)[UB], int jb) {
+    auto process = [&](const uint4 (&a)[UB][NM], int jb) {
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
 #pragma unroll
@@ -811,7 +858,10 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
                 f32x16 z;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) z[e] = 0.f;
-                z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[u]), bq[st], z, 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < NM; ++i)
+                    z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[u][i]),
+                                                                bq[st][i], z, 0, 0, 0);
                 float m = kInf;  // 8 three-input mins over (inf, 16 keys)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) m = fminf(m, z[e]);
@@ -824,40 +874,50 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_bf16_kernel(
     // loads of the next iteration land in registers that are never copied.
     const int nfull = (j1 > j0) ? (j1 - j0) / PTS : 0;
     int jb = j0;
-    uint4 a_even[UB], a_odd[UB];
+    uint4 a_even[UB][NM], a_odd[UB][NM];
 #pragma unroll
-    for (int u = 0; u < UB; ++u) a_even[u] = a_odd[u] = uint4{0u, 0u, 0u, 0u};
-    // wave-uniform base + constant lane offset + immediate: no vector address arithmetic
-    const uint4* xb = Xp + (size_t)j0 * 2;
-    const int loff = i32 * 2 + h;
-    if (nfull > 0) {
+    for (int u = 0; u < UB; ++u)
 #pragma unroll
-        for (int u = 0; u < UB; ++u) a_even[u] = xb[loff + u * 64];
-    }
+        for (int i = 0; i < NM; ++i) a_even[u][i] = a_odd[u][i] = uint4{0u, 0u, 0u, 0u};
+    // wave-uniform base + constant lane offset + immediate: no vector address arithmetic.
+    // Record (point, MFMA i, half) sits at uint4 index (point * NM + i) * 2 + half.
+    const uint4* xb = Xp + (size_t)j0 * (2 * NM);
+    const int loff = i32 * (2 * NM) + h;
+    auto fetch = [&](uint4 (&dst)[UB][NM]) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u)
+#pragma unroll
+            for (int i = 0; i < NM; ++i) dst[u][i] = xb[loff + u * (64 * NM) + 2 * i];
+    };
+    if (nfull > 0) fetch(a_even);
     for (int it = 0; it < nfull; it += 2) {
-        xb += PTS * 2;
-        if (it + 1 < nfull) {
-#pragma unroll
-            for (int u = 0; u < UB; ++u) a_odd[u] = xb[loff + u * 64];
-        }
+        xb += PTS * 2 * NM;
+        if (it + 1 < nfull) fetch(a_odd);
         process(a_even, jb);
         jb += PTS;
         if (it + 1 < nfull) {
-            xb += PTS * 2;
-            if (it + 2 < nfull) {
-#pragma unroll
-                for (int u = 0; u < UB; ++u) a_even[u] = xb[loff + u * 64];
-            }
+            xb += PTS * 2 * NM;
+            if (it + 2 < nfull) fetch(a_even);
             process(a_odd, jb);
             jb += PTS;
         }
     }
     if (jb < j1) {  // ragged tail: rows past the range read a valid row and get ||x||^2 = +inf
+        constexpr int kNormSlot = 3 * D;  // slot of the leading piece of the squared norm
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
             const int row = jb + u * 32 + i32;
-            a_even[u] = Xp[(size_t)(row < j1 ? row : j1 - 1) * 2 + h];
-            if (row >= j1 && !h) a_even[u].w = 0x7f80u;  // nh = +inf, nm = 0
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                uint4 v = Xp[((size_t)(row < j1 ? row : j1 - 1) * NM + i) * 2 + h];
+                if (row >= j1 && i == kNormSlot / 16 && h == (kNormSlot % 16) / 8) {
+                    unsigned* w = reinterpret_cast<unsigned*>(&v);
+                    constexpr int e = kNormSlot % 8;
+                    w[e / 2] = (e % 2) ? ((w[e / 2] & 0x0000ffffu) | 0x7f800000u)
+                                       : ((w[e / 2] & 0xffff0000u) | 0x00007f80u);
+                }
+                a_even[u][i] = v;
+            }
         }
         process(a_even, jb);
     }
@@ -984,6 +1044,11 @@ hipError_t launch_lowd_bf16(const float* Q, int64_t ldq, const float* X, int64_t
         case 1: return launch_lowd_bf16_d<1>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
         case 2: return launch_lowd_bf16_d<2>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
         case 3: return launch_lowd_bf16_d<3>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        case 4: return launch_lowd_bf16_d<4>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        case 5: return launch_lowd_bf16_d<5>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        case 6: return launch_lowd_bf16_d<6>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        case 7: return launch_lowd_bf16_d<7>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        case 8: return launch_lowd_bf16_d<8>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
         default: return hipErrorInvalidValue;
     }
 }

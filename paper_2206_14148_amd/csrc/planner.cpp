@@ -116,19 +116,23 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     }
     if (m == 0) return KNN_OK;
     if (mem_limit_bytes < out->min_limit_bytes) return KNN_ERR_MEM_LIMIT_TOO_SMALL;
-    if (d <= kPmMaxD && metric == KNN_METRIC_L2SQ) {
-        // the matrix-core filter needs the points packed into the workspace; take it when the
+    if (d <= kPbMaxD && metric == KNN_METRIC_L2SQ) {
+        // the matrix-core filters need the points packed into the workspace; take one when the
         // limit has room for that and at least one query tile of lists
-        const uint64_t packed = kAlign + align_up((uint64_t)n * 16);
-        const int64_t min_rows = m < kPmTileQ ? m : kPmTileQ;
-        if (mem_limit_bytes >= packed + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k)) {
-            out->path = KNN_PATH_LOWD_MFMA;
-            out->tile_q = kPmTileQ;
-            out->tile_x = 32;
-            out->norms_bytes = packed;
+        if (d <= kPmMaxD) {
+            const uint64_t packed = kAlign + align_up((uint64_t)n * 16);
+            const int64_t min_rows = m < kPmTileQ ? m : kPmTileQ;
+            if (mem_limit_bytes >= packed + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k)) {
+                out->path = KNN_PATH_LOWD_MFMA;
+                out->tile_q = kPmTileQ;
+                out->tile_x = 32;
+                out->norms_bytes = packed;
+            }
         }
-        // with 32 bytes per point the filter runs in bf16 pieces, four times cheaper
-        const uint64_t packed16 = kAlign + align_up((uint64_t)n * 32);
+        // with 32 bytes per point and 16 K slots (one MFMA up to d = 4, two up to d = 8) the
+        // filter runs in bf16 pieces, four times cheaper per MFMA
+        const uint64_t per_point = 32ull * ((3 * (uint64_t)d + 3 + 15) / 16);
+        const uint64_t packed16 = kAlign + align_up((uint64_t)n * per_point);
         const int64_t min_rows16 = m < kPbTileQ ? m : kPbTileQ;
         if (mem_limit_bytes >= packed16 + lists_bytes_for((uint64_t)min_rows16, 1, (uint64_t)k)) {
             out->path = KNN_PATH_LOWD_BF16;

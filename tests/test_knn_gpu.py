@@ -162,6 +162,23 @@ def test_low_d_paths_agree_and_survive_data_far_from_the_origin(K, oracle, d):
         say("   shift", shift, check(b_idx, b_dist, o_idx, o_dist, o_next, 9000))
 
 
+@pytest.mark.parametrize("d", [4, 5, 6, 7, 8])
+def test_bf16_filter_and_vector_kernel_agree_for_d_4_to_8(K, oracle, d):
+    # one MFMA of 16 K slots up to d = 4, two above; same exact keys as the vector kernel
+    Q, X = W.random_case(1100 + d, 520, 9000, d, kind="uniform")
+    for shift in (0.0, 50.0):
+        Qs, Xs = (Q + np.float32(shift)), (X + np.float32(shift))
+        k = 12
+        lo = K.knn_plan(520, 9000, d, k, 1 << 40).min_limit_bytes
+        assert K.knn_plan(520, 9000, d, k, lo + 40_000).path == K.KNN_PATH_LOWD
+        assert K.knn_plan(520, 9000, d, k, 64 * W.MB).path == K.KNN_PATH_LOWD_BF16
+        a_idx, a_dist = run_gpu(K, Qs, Xs, k, lo + 40_000)
+        b_idx, b_dist = run_gpu(K, Qs, Xs, k, 64 * W.MB)
+        assert np.array_equal(a_idx, b_idx) and np.array_equal(a_dist, b_dist)
+        o_idx, o_dist, o_next = oracle.knn(Qs, Xs, k)
+        say("   d", d, "shift", shift, check(b_idx, b_dist, o_idx, o_dist, o_next, 9000))
+
+
 def test_self_distance_zero_when_queries_are_the_points(K, oracle):
     w = W.scaled(2, n=30000)
     Q, X = W.make(w)

@@ -80,7 +80,7 @@ def test_every_baseline_config_has_a_plan_under_its_limit(m, n, d, k, limit):
     assert p.workspace_bytes <= limit
     assert p.workspace_bytes == p.norms_bytes + p.lists_bytes
     # d <= 3 with room for the packed points takes the matrix-core filter path
-    want = K.KNN_PATH_LOWD_BF16 if d <= 3 else (K.KNN_PATH_LOWD if d <= 8 else K.KNN_PATH_MFMA)
+    want = K.KNN_PATH_LOWD_BF16 if d <= 8 else K.KNN_PATH_MFMA
     assert p.path == want
     assert p.q_chunks * p.chunk_rows >= m
     assert p.chunk_rows == m or p.chunk_rows % p.tile_q == 0
@@ -124,7 +124,12 @@ def test_low_d_falls_back_to_the_vector_path_when_packed_points_do_not_fit():
     tight = K.knn_plan(m, n, d, k, 10 ** 7)  # 16 MB of packed points do not fit in 10 MB
     assert tight.path == K.KNN_PATH_LOWD and tight.norms_bytes == 0
     assert tight.workspace_bytes <= 10 ** 7
-    assert K.knn_plan(m, n, 4, k, 10 ** 9).path == K.KNN_PATH_LOWD
+    # d in 4..8: bf16 filter (32 bytes per point up to d = 4, 64 above) or the vector kernel
+    assert K.knn_plan(m, n, 4, k, 10 ** 9).norms_bytes == 256 + 32 * n
+    assert K.knn_plan(m, n, 8, k, 10 ** 9).path == K.KNN_PATH_LOWD_BF16
+    assert K.knn_plan(m, n, 8, k, 10 ** 9).norms_bytes == 256 + 64 * n
+    assert K.knn_plan(m, n, 8, k, 60 * 10 ** 6).path == K.KNN_PATH_LOWD
+    assert K.knn_plan(m, n, 9, k, 10 ** 9).path == K.KNN_PATH_MFMA
 
 
 def test_plan_argument_errors():
