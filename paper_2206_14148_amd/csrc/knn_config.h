@@ -40,6 +40,11 @@ constexpr int kMfmaCand = 32;        // candidate slots per query (LDS)
 constexpr int kLowdResidentWorkgroups = 4 * kNumCU;
 constexpr int kMfmaResidentWorkgroups = 2 * kNumCU;
 constexpr int kWarmupPointsPerK = 64;     // list warm-up of one point range, in point-equivalents per k
+// the same for the low-d filter kernels, per k and per unit of 1 + ln(range / k): measured
+// ~370 cycles per accepted pair against ~5 (bf16, 64 queries per wave) or ~7 (fp32 filter, 32
+// queries per wave) cycles per scanned point and wave
+constexpr int kWarmupPointsPerKBf16 = 4700;
+constexpr int kWarmupPointsPerKFilter = 1800;
 constexpr int kMaxSplits = 64;
 constexpr int64_t kMaxPoints = ((int64_t)1 << 31) - 65536;
 constexpr int64_t kMaxChunkRows = 1 << 22;  // keeps per-launch row counts and grids in int range

@@ -7,6 +7,7 @@
 // Section 4.4: every concurrently live buffer counts, so the plan sums all library-owned
 // device memory (norms + every partial list of a chunk) and keeps the sum under the limit.
 #include <cctype>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 
@@ -163,7 +164,18 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
         const int64_t chunks = (m + rows - 1) / rows;
         const int64_t wgs = (rows + tile - 1) / tile * S;
         const int64_t rounds = (wgs + slots - 1) / slots;
-        const double per_wg = (double)((n + S - 1) / S) + (double)kWarmupPointsPerK * (double)k;
+        const double range = (double)((n + S - 1) / S);
+        double warm = (double)kWarmupPointsPerK * (double)k;
+        if (out->path == KNN_PATH_LOWD_BF16 || out->path == KNN_PATH_LOWD_MFMA) {
+            // The filter kernels scan a point in a few cycles per wave, while every accepted
+            // pair (about k (1 + ln(range / k)) per query and range) costs a few hundred, so a
+            // range's list warm-up is worth on the order of a million scanned points there.
+            const double per_k = out->path == KNN_PATH_LOWD_BF16 ? kWarmupPointsPerKBf16
+                                                                 : kWarmupPointsPerKFilter;
+            const double ratio = range > (double)k ? range / (double)k : 1.0;
+            warm = per_k * (double)k * (1.0 + log(ratio));
+        }
+        const double per_wg = range + warm;
         const double cost = (double)chunks * (double)rounds * per_wg;
         if (best_s == 0 || cost < 0.9 * best_cost) {
             best_cost = cost;
