@@ -29,12 +29,12 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per search-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/*_pmc.txt), scaled by the copy-kernel calibration stated there.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "c2_pointcloud_d3": 236.95e9,   # knn_lowd_bf16_kernel: 231.31 GB fetched + 5.64 GB written
-    "c3_imagelike_d784": 359.0e9,   # knn_mfma_kernel: 359.0 GB fetched + 0.07 GB written
+    "c2_pointcloud_d3": 227.34e9,   # knn_lowd_bf16_kernel: 224.72 GB fetched + 2.62 GB written
+    "c3_imagelike_d784": 351.5e9,   # knn_mfma_kernel: 351.4 GB fetched + 0.07 GB written
     "c4_clustered_d128": 3455.6e9,  # knn_mfma_qreg_kernel: 3443.4 GB fetched + 12.2 GB written
-    "c5_memsweep_d256": 600.0e9,    # knn_mfma_qreg_kernel: 598.9 GB fetched + 1.09 GB written
-    "c6_cosine_d100": 25.05e9,      # knn_mfma_qreg_kernel: 24.99 GB fetched + 0.06 GB written
-    "c7_l1_d100": 11.79e9,          # knn_l1_kernel: 11.37 GB fetched + 0.43 GB written
+    "c5_memsweep_d256": 577.5e9,    # knn_mfma_qreg_kernel: 576.4 GB fetched + 1.05 GB written
+    "c6_cosine_d100": 20.75e9,      # knn_mfma_qreg_kernel: 20.69 GB fetched + 0.06 GB written
+    "c7_l1_d100": 10.08e9,          # knn_l1_kernel: 9.66 GB fetched + 0.42 GB written
     "kmv1_d1": 1.84e9,              # kmv_lowd_kernel: 1.83 GB fetched + 0.01 GB written
     "kmv2_d32": 1.58e9,             # kmv_mfma_kernel: 1.58 GB fetched + 0.002 GB written
     "kmv3_d1_f64": 4.02e9,          # kmv_lowd_f64_kernel: 4.01 GB fetched + 0.01 GB written
