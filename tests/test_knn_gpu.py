@@ -397,3 +397,30 @@ def test_exact_ties_keep_the_lower_index_on_every_low_d_path(K, oracle, seed, d,
         assert np.array_equal(idx, o_idx), limit
         assert np.array_equal(dist.astype(np.float64), o_dist), limit
     assert paths == {K.KNN_PATH_LOWD_BF16, K.KNN_PATH_LOWD_MFMA, K.KNN_PATH_LOWD}
+
+
+def test_seeded_random_shapes_and_limits(K, oracle):
+    # a seeded sweep over shapes, k, metrics and limits (from the smallest feasible one up):
+    # whatever plan comes out - path, chunks, ranges - the result passes the parity rule
+    g = np.random.Generator(np.random.PCG64(W.SEED_BASE + 13_000_000))
+    seen = set()
+    for case in range(48):
+        d = int(g.choice([1, 2, 3, 4, 5, 8, 9, 12, 16, 17, 31, 64, 100, 260]))
+        m = int(g.choice([1, 7, 63, 129, 300, 700]))
+        n = int(g.choice([1, 5, 64, 127, 500, 2049, 6000]))
+        k = int(min(n, g.choice([1, 2, 9, 16, 33, 100])))
+        metric = str(g.choice(["l2", "l2", "l2", "cosine", "l1"]))
+        kind = str(g.choice(["normal", "uniform", "grid"]))
+        if kind == "grid" and metric == "cosine":
+            kind = "normal"  # zero vectors and exact cosine ties are covered by their own tests
+        lo = K.knn_plan(m, n, d, k, 1 << 40, metric).min_limit_bytes
+        limit = int(g.choice([lo, lo + 3000, 4 * lo + 100_000, 64 * W.MB]))
+        plan = K.knn_plan(m, n, d, k, limit, metric)
+        assert plan.workspace_bytes <= limit
+        seen.add((plan.path, plan.q_chunks > 1, plan.n_splits > 1))
+        say("fuzz", case, (m, n, d, k, metric, kind, limit), "plan", (plan.path, plan.q_chunks, plan.n_splits))
+        Q, X = W.random_case(5000 + case, m, n, d, kind)
+        idx, dist = run_gpu(K, Q, X, k, limit, metric=metric)
+        o_idx, o_dist, o_next = oracle.knn(Q, X, k, metric=metric)
+        check(idx, dist, o_idx, o_dist, o_next, n)
+    assert len({p for p, _, _ in seen}) >= 4  # several kernel families were exercised
