@@ -14,7 +14,10 @@
  * procedure the section refers to sums over the data in chunks and needs O(m^2).  Here the
  * data axis is cut into chunks of chunk_cols points (section 4.3: the largest splittable
  * axis); one chunk of K_uf lives in the workspace, is multiplied by its own transpose on the
- * fp32 matrix cores and added to A in fp64, and is dropped.
+ * fp32 matrix cores and added to A in fp64, and is dropped.  When m is small (few 128 x 128
+ * tiles of A for 256 compute units) and the limit has room, the columns of a chunk are cut
+ * into col_groups groups whose products run concurrently into partial copies of A kept in
+ * the workspace; the copies are added in a fixed order at the end.
  */
 #ifndef SGPR_MI355X_H
 #define SGPR_MI355X_H
@@ -31,11 +34,13 @@ extern "C" {
 
 typedef struct {
     int64_t m, n;
-    int32_t d, reserved;
+    int32_t d;
+    int32_t col_groups;       /* column groups of a chunk multiplied concurrently (1, 2, 4, 8) */
     int64_t chunk_cols;       /* data points per chunk (multiple of 16, or n)            */
     int64_t n_chunks;         /* ceil(n / chunk_cols); 0 when n == 0                     */
     int64_t chunk_ld;         /* leading dimension of the K_uf chunk in the workspace    */
-    uint64_t workspace_bytes; /* m * chunk_ld * 4, aligned  <= limit                     */
+    uint64_t workspace_bytes; /* chunk (m * chunk_ld * 4) + (col_groups - 1) partial
+                                 copies of A (m * m * 8 each), aligned  <= limit         */
     uint64_t min_limit_bytes; /* a chunk of 16 points                                    */
 } sgpr_plan_t;
 

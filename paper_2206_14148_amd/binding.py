@@ -54,7 +54,7 @@ class KmvPlanStruct(ctypes.Structure):
 class SgprPlanStruct(ctypes.Structure):
     _fields_ = [
         ("m", ctypes.c_int64), ("n", ctypes.c_int64),
-        ("d", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("d", ctypes.c_int32), ("col_groups", ctypes.c_int32),
         ("chunk_cols", ctypes.c_int64), ("n_chunks", ctypes.c_int64), ("chunk_ld", ctypes.c_int64),
         ("workspace_bytes", ctypes.c_uint64), ("min_limit_bytes", ctypes.c_uint64),
     ]
@@ -65,6 +65,7 @@ class SgprPlan:
     m: int
     n: int
     d: int
+    col_groups: int
     chunk_cols: int
     n_chunks: int
     chunk_ld: int
@@ -455,8 +456,8 @@ def sgpr_plan(m: int, n: int, d: int, mem_limit_bytes: int) -> SgprPlan:
     st = int(load().sgpr_plan(m, n, d, mem_limit_bytes, ctypes.byref(ps)))
     if st != KNN_OK:
         raise KnnError(st, knn_status_string(st), int(ps.min_limit_bytes))
-    return SgprPlan(ps.m, ps.n, ps.d, ps.chunk_cols, ps.n_chunks, ps.chunk_ld, ps.workspace_bytes,
-                    ps.min_limit_bytes)
+    return SgprPlan(ps.m, ps.n, ps.d, ps.col_groups, ps.chunk_cols, ps.n_chunks, ps.chunk_ld,
+                    ps.workspace_bytes, ps.min_limit_bytes)
 
 
 def sgpr_accumulate(U, X, y, variance: float, lengthscale: float, mem_limit_bytes: int,

@@ -49,7 +49,18 @@ extern "C" knn_status sgpr_plan(int64_t m, int64_t n, int32_t d, uint64_t mem_li
     out->chunk_ld = cols;
     out->chunk_cols = cols < n ? cols : n;
     out->n_chunks = n > 0 ? (n + cols - 1) / cols : 0;
-    out->workspace_bytes = knn::align_up((uint64_t)m * (uint64_t)cols * 4);
+    const uint64_t chunk_bytes = knn::align_up((uint64_t)m * (uint64_t)cols * 4);
+    // Few tiles of A: spread a chunk's columns over several groups of workgroups, each with
+    // its own copy of A, while a group keeps at least 256 columns and the copies fit.
+    const int64_t T = (m + 127) / 128;
+    const int64_t tiles = T * (T + 1) / 2;
+    const uint64_t copy_bytes = knn::align_up((uint64_t)m * (uint64_t)m * 8);
+    int G = 1;
+    while (G < 8 && tiles * G < 2048 && cols / (2 * G) >= 256 && (cols / (2 * G)) % 16 == 0 &&
+           chunk_bytes + (uint64_t)(2 * G - 1) * copy_bytes <= mem_limit_bytes)
+        G *= 2;
+    out->col_groups = G;
+    out->workspace_bytes = chunk_bytes + (uint64_t)(G - 1) * copy_bytes;
     return KNN_OK;
 }
 
@@ -74,7 +85,13 @@ extern "C" knn_status sgpr_accumulate(const float* U, int64_t ldu, const float* 
     float* Kc = static_cast<float*>(workspace);
     const float c2 = (float)(0.5 / (lengthscale * lengthscale) * 1.4426950408889634);
 
+    const int G = plan.col_groups;
+    const uint64_t chunk_bytes = knn::align_up((uint64_t)m * (uint64_t)plan.chunk_ld * 4);
+    const uint64_t copy_bytes = knn::align_up((uint64_t)m * (uint64_t)m * 8);
+    double* copies = reinterpret_cast<double*>(static_cast<unsigned char*>(workspace) + chunk_bytes);
     hipError_t e = sgpr::launch_zero(A, lda, b, m, stream);
+    for (int g = 1; g < G && e == hipSuccess; ++g)
+        e = sgpr::launch_zero(copies + (size_t)(g - 1) * (copy_bytes / 8), m, nullptr, m, stream);
     if (e != hipSuccess) return hip_fail(e, "sgpr zero kernel");
     for (int64_t c = 0; c < plan.n_chunks; ++c) {
         const int64_t c0 = c * plan.chunk_cols;
@@ -88,7 +105,8 @@ extern "C" knn_status sgpr_accumulate(const float* U, int64_t ldu, const float* 
         }
         knn::profile_close(t0, stream, 0);
         hipEvent_t t1 = knn::profile_mark(stream);
-        e = sgpr::launch_syrk(Kc, plan.chunk_ld, m, cols, A, lda, stream);
+        e = sgpr::launch_syrk(Kc, plan.chunk_ld, m, cols, G, A, lda, copies, (int64_t)(copy_bytes / 8),
+                              stream);
         if (e != hipSuccess) {
             knn::profile_drop(t1);
             return hip_fail(e, "sgpr chunk product");
@@ -101,6 +119,10 @@ extern "C" knn_status sgpr_accumulate(const float* U, int64_t ldu, const float* 
             return hip_fail(e, "sgpr chunk times y");
         }
         knn::profile_close(t2, stream, 2);
+    }
+    if (G > 1) {
+        e = sgpr::launch_add_copies(A, lda, copies, (int64_t)(copy_bytes / 8), G - 1, m, stream);
+        if (e != hipSuccess) return hip_fail(e, "sgpr add-copies kernel");
     }
     e = sgpr::launch_symmetrize(A, lda, m, stream);
     if (e != hipSuccess) return hip_fail(e, "sgpr symmetrize kernel");

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(256) void sgpr_zero_kernel(double* __restrict__ A, 
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= m) return;
     for (int i = blockIdx.y; i < m; i += gridDim.y) A[(int64_t)i * lda + j] = 0.0;
-    if (blockIdx.y == 0) b[j] = 0.0;
+    if (blockIdx.y == 0 && b) b[j] = 0.0;
 }
 
 // One data point per thread (consecutive threads: consecutive columns of the chunk, so the
@@ -79,6 +79,20 @@ __global__ __launch_bounds__(256) void sgpr_kufy_kernel(const float* __restrict_
     if (lane == 0) b[i] += acc;
 }
 
+__global__ __launch_bounds__(256) void sgpr_add_copies_kernel(double* __restrict__ A, int64_t lda,
+                                                              const double* __restrict__ copies,
+                                                              int64_t copy_stride, int ncopies,
+                                                              int m) {
+    const int i = blockIdx.x * 256 + threadIdx.x;  // column
+    if (i >= m) return;
+    for (int j = blockIdx.y; j < m; j += gridDim.y) {
+        if (i > (j | 127)) continue;  // above the diagonal tile of row j: nothing was summed there
+        double acc = A[(int64_t)j * lda + i];
+        for (int g = 0; g < ncopies; ++g) acc += copies[(int64_t)g * copy_stride + (int64_t)j * m + i];
+        A[(int64_t)j * lda + i] = acc;
+    }
+}
+
 __global__ __launch_bounds__(256) void sgpr_symmetrize_kernel(double* __restrict__ A, int64_t lda,
                                                               int m) {
     // 16 x 16 tile of the strict upper triangle, read from its mirror image through LDS so
@@ -103,9 +117,19 @@ __global__ __launch_bounds__(256) void sgpr_symmetrize_kernel(double* __restrict
 // i = lane % 32, so for a fixed register the 32 lanes of a half wave write 32 consecutive
 // fp64 entries of one row of A.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256, 2) void sgpr_syrk_kernel(const float* __restrict__ Kc,
-                                                           int64_t ldk, int m, int cols,
-                                                           double* __restrict__ A, int64_t lda) {
+__global__ __launch_bounds__(256, 2) void sgpr_syrk_kernel(const float* __restrict__ Kc_all,
+                                                           int64_t ldk, int m, int cols_all,
+                                                           int group_cols,
+                                                           double* __restrict__ A0, int64_t lda0,
+                                                           double* __restrict__ copies,
+                                                           int64_t copy_stride) {
+    // column group blockIdx.y: its run of columns and the matrix its sums go to
+    const int grp = blockIdx.y;
+    const float* __restrict__ Kc = Kc_all + (int64_t)grp * group_cols;
+    const int cols = min(group_cols, cols_all - grp * group_cols);
+    if (cols <= 0) return;  // whole workgroup, before any barrier
+    double* __restrict__ A = grp == 0 ? A0 : copies + (int64_t)(grp - 1) * copy_stride;
+    const int64_t lda = grp == 0 ? lda0 : (int64_t)m;
     constexpr int T = 128, KC = knn::kMfmaKC, RS = knn::kMfmaRowStride;
     extern __shared__ __align__(16) unsigned char smem[];
     float* js = reinterpret_cast<float*>(smem);  // [2][T][RS] rows of tile tj
@@ -233,12 +257,23 @@ hipError_t launch_kuf(const float* U, int64_t ldu, const float* X, int64_t ldx, 
     return hipGetLastError();
 }
 
-hipError_t launch_syrk(const float* Kc, int64_t ldk, int64_t m, int64_t cols, double* A,
-                       int64_t lda, hipStream_t stream) {
+hipError_t launch_syrk(const float* Kc, int64_t ldk, int64_t m, int64_t cols, int groups, double* A,
+                       int64_t lda, double* copies, int64_t copy_stride, hipStream_t stream) {
     const int64_t T = (m + 127) / 128;
     const size_t lds = (size_t)4 * 128 * knn::kMfmaRowStride * 4;
-    sgpr_syrk_kernel<<<dim3((unsigned)(T * (T + 1) / 2)), dim3(256), lds, stream>>>(
-        Kc, ldk, (int)m, (int)cols, A, lda);
+    // equal runs of whole 16-column steps; the last run takes what is left
+    int64_t group_cols = ((cols + groups - 1) / groups + 15) / 16 * 16;
+    if (group_cols < 16) group_cols = 16;
+    sgpr_syrk_kernel<<<dim3((unsigned)(T * (T + 1) / 2), (unsigned)groups), dim3(256), lds, stream>>>(
+        Kc, ldk, (int)m, (int)cols, (int)group_cols, A, lda, copies, copy_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_add_copies(double* A, int64_t lda, const double* copies, int64_t copy_stride,
+                             int ncopies, int64_t m, hipStream_t stream) {
+    const unsigned gy = (unsigned)(m < 4096 ? m : 4096);
+    sgpr_add_copies_kernel<<<dim3((unsigned)((m + 255) / 256), gy), dim3(256), 0, stream>>>(
+        A, lda, copies, copy_stride, ncopies, (int)m);
     return hipGetLastError();
 }
 
