@@ -85,7 +85,8 @@ typedef struct {
     int32_t reserved;
     uint64_t norms_bytes;     /* workspace: per-point data. path 1: squared norms, plus the
                                  blocked copy of X when x_blocked; path 2: packed points
-                                 [x0 x1 x2 |x|^2]; path 0: nothing                    */
+                                 [x0 x1 x2 |x|^2]; path 4: a 256-byte header and 32 bytes
+                                 per point and 16 K slots; paths 0, 3: nothing        */
     uint64_t lists_bytes;     /* workspace: partial k-lists of one chunk        */
     uint64_t workspace_bytes; /* total device workspace needed, <= mem_limit    */
     uint64_t min_limit_bytes; /* smallest limit any plan for this shape fits in */
