@@ -160,6 +160,28 @@ def bench_kmv(args) -> int:
         parity = {"rows": len(rows), "max_abs_err_over_sum_of_magnitudes": rel}
         log(f"[bench] oracle: {cpu_baseline['value']:.3e} pairs/s on {threads} threads; parity {parity}")
 
+    # the memory-limit sweep of the paper's figure 1 (section 5.1), on this product: same inputs,
+    # a range of limits; the workspace stays under each of them
+    sweep = []
+    if not args.mem_limit:
+        for lim in (0 if plan.path != K.KMV_PATH_MFMA else plan.norms_bytes, 10 ** 6, 10 ** 8, 10 ** 9, 32 * 10 ** 9):
+            p2 = K.kmv_plan(w.n, w.m, w.d, lim, w.dtype)
+            ws2 = torch.empty(max(p2.workspace_bytes, 256), dtype=torch.uint8, device=dev)
+            y2 = torch.empty_like(y)
+            K.kmv_apply(Xd, Zd, vd, w.variance, w.lengthscale, lim, workspace=ws2, out=y2)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                K.kmv_apply(Xd, Zd, vd, w.variance, w.lengthscale, lim, workspace=ws2, out=y2)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / args.steps
+            sweep.append({"mem_limit_bytes": lim, "workspace_bytes": p2.workspace_bytes,
+                          "point_ranges": p2.n_splits, "ms_per_step": dt * 1e3,
+                          "max_abs_diff": float((y2 - y).abs().max())})
+            log(f"[bench] sweep limit={lim}: {dt*1e3:.1f} ms, workspace {p2.workspace_bytes} B, "
+                f"ranges {p2.n_splits}")
+            del ws2, y2
+
     out = {
         "metric": "kernel-matrix entries per second, y = K v with a squared-exponential kernel (n*m/s)",
         "value": value, "unit": "pairs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -171,6 +193,8 @@ def bench_kmv(args) -> int:
                    "path": path_name},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity,
     }
+    if sweep:
+        out["mem_limit_sweep"] = sweep
     print(json.dumps(out), flush=True)
     return 0
 
