@@ -82,11 +82,13 @@ typedef struct {
     int32_t streams;     /* HIP streams used (1: the caller's)                  */
     int32_t x_blocked;   /* 1: path 1 reads the points from a blocked copy in the workspace */
     int32_t metric;      /* knn_metric                                          */
-    int32_t reserved;
+    int32_t seed_cells;  /* path 4, d <= 3: cells per axis of the grid the points are counted
+                            into to give every list a finite starting threshold; 0: none */
     uint64_t norms_bytes;     /* workspace: per-point data. path 1: squared norms, plus the
                                  blocked copy of X when x_blocked; path 2: packed points
-                                 [x0 x1 x2 |x|^2]; path 4: a 256-byte header and 32 bytes
-                                 per point and 16 K slots; paths 0, 3: nothing        */
+                                 [x0 x1 x2 |x|^2]; path 4: a 256-byte header, 32 bytes
+                                 per point and 16 K slots, and seed_cells^d counts;
+                                 paths 0, 3: nothing                                   */
     uint64_t lists_bytes;     /* workspace: partial k-lists of one chunk        */
     uint64_t workspace_bytes; /* total device workspace needed, <= mem_limit    */
     uint64_t min_limit_bytes; /* smallest limit any plan for this shape fits in */

@@ -95,7 +95,7 @@ class PlanStruct(ctypes.Structure):
         ("tile_x", ctypes.c_int32), ("n_splits", ctypes.c_int32),
         ("chunk_rows", ctypes.c_int64), ("q_chunks", ctypes.c_int64),
         ("streams", ctypes.c_int32), ("x_blocked", ctypes.c_int32),
-        ("metric", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("metric", ctypes.c_int32), ("seed_cells", ctypes.c_int32),
         ("norms_bytes", ctypes.c_uint64), ("lists_bytes", ctypes.c_uint64),
         ("workspace_bytes", ctypes.c_uint64), ("min_limit_bytes", ctypes.c_uint64),
     ]
@@ -145,6 +145,7 @@ class Plan:
     streams: int
     x_blocked: int
     metric: int
+    seed_cells: int
     norms_bytes: int
     lists_bytes: int
     workspace_bytes: int
@@ -228,8 +229,8 @@ def knn_status_string(status: int) -> str:
 
 def _plan_from_struct(ps: PlanStruct) -> Plan:
     return Plan(ps.m, ps.n, ps.d, ps.k, ps.path, ps.tile_q, ps.tile_x, ps.n_splits,
-                ps.chunk_rows, ps.q_chunks, ps.streams, ps.x_blocked, ps.metric, ps.norms_bytes,
-                ps.lists_bytes,
+                ps.chunk_rows, ps.q_chunks, ps.streams, ps.x_blocked, ps.metric, ps.seed_cells,
+                ps.norms_bytes, ps.lists_bytes,
                 ps.workspace_bytes, ps.min_limit_bytes)
 
 

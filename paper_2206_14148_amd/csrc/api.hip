@@ -169,7 +169,7 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     } else if (plan.path == KNN_PATH_LOWD_MFMA || plan.path == KNN_PATH_LOWD_BF16) {
         hipEvent_t t0 = mark(stream);
         e = plan.path == KNN_PATH_LOWD_BF16
-                ? launch_lowd_bf16(Q, ldq, X, ldx, ws, 0, n, d, k, S, true, lk, li, stream)
+                ? launch_lowd_bf16(Q, ldq, X, ldx, ws, 0, n, d, k, S, true, plan.seed_cells, lk, li, stream)
                 : launch_lowd_mfma(Q, ldq, X, ldx, ws, 0, n, d, k, S, true, lk, li, stream);
         if (e != hipSuccess) {
             drop_bracket(t0);
@@ -189,7 +189,8 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
         else if (plan.path == KNN_PATH_LOWD_MFMA)
             e = launch_lowd_mfma(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, lk, li, stream);
         else if (plan.path == KNN_PATH_LOWD_BF16)
-            e = launch_lowd_bf16(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, lk, li, stream);
+            e = launch_lowd_bf16(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, plan.seed_cells, lk,
+                                 li, stream);
         else
             e = launch_mfma(Qc, ldq, X, ldx, xn, xblocked, cosine, rows, n, d, k, S, lk, li,
                             stream);

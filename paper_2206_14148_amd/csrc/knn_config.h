@@ -27,6 +27,11 @@ constexpr int kPbMaxD = 8;
 constexpr int kPbSets = 2;
 constexpr int kPbTileQ = 4 * 32 * kPbSets;       // query rows per workgroup
 constexpr int kPbCand = 16;                      // candidate slots per query (LDS)
+// threshold seed of that path, d <= kSeedMaxD: the points are counted into a grid of at most
+// kSeedMaxCells cells (about kSeedPointsPerCellPerK * k points per cell)
+constexpr int kSeedMaxD = 3;
+constexpr int kSeedMaxCells = 32768;
+constexpr int kSeedPointsPerCellPerK = 2;
 
 // d > kLowdMaxD: fp32 MFMA tile, 4 waves, each wave owns 32 queries x 128 points.
 constexpr int kMfmaTileQ = 128;

@@ -33,10 +33,12 @@ hipError_t launch_lowd_mfma(const float* Q, int64_t ldq, const float* X, int64_t
 // d <= kPbMaxD with room for 32 n bytes (d <= 4) or 64 n bytes: the same keys again, found through
 // a bf16 MFMA filter on points and queries moved by the midpoint of the points' bounding box.
 // `packed` = kAlign bytes (header: max moved norm, bounding box) + the packed points; pack /
-// rows == 0 as above.
+// rows == 0 as above.  seed_cells > 0 (d <= kSeedMaxD only): the area continues with
+// seed_cells^d ints, the points counted into a grid of that many cells per axis, from which
+// every query's list gets a finite starting threshold.
 hipError_t launch_lowd_bf16(const float* Q, int64_t ldq, const float* X, int64_t ldx, void* packed,
-                            int64_t rows, int64_t n, int d, int k, int S, bool pack, float* lk,
-                            int* li, hipStream_t stream);
+                            int64_t rows, int64_t n, int d, int k, int S, bool pack, int seed_cells,
+                            float* lk, int* li, hipStream_t stream);
 
 // d > kLowdMaxD: key = xn[j] - 2 q.x from fp32 MFMA tiles (rank-equivalent to the distance).
 // xblocked: nullptr, or (d <= 256 only) the blocked copy of X made by launch_block_points.

@@ -594,6 +594,105 @@ __device__ __forceinline__ void bbox_centre(const unsigned* __restrict__ hdr, fl
         c[t] = 0.5f * ordered_value(hdr[1 + t]) + 0.5f * ordered_value(hdr[1 + kPbMaxD + t]);
 }
 
+// ---------------------------------------------------------------------------------------
+// Threshold seed (D <= kSeedMaxD).  The points are counted into a grid of G^D cells over their
+// bounding box.  A query finds the smallest block of cells around its own cell (own cell, then
+// 3^D, then 5^D cells) that holds at least k points: each of those points lies inside the block,
+// so the squared distance from the query to the block's farthest corner bounds the query's k-th
+// smallest distance from above, and its list can start from that threshold instead of +inf.
+// Pairs beyond the bound never reach the exact test, which takes most of the list warm-up away;
+// results do not change, because every pair at or below the true k-th distance still passes.
+// ---------------------------------------------------------------------------------------
+template <int D>
+struct SeedGrid {
+    float mn[D], inv_w[D], w[D], slack[D];
+    int G;
+};
+
+template <int D>
+__device__ __forceinline__ SeedGrid<D> seed_grid(const unsigned* __restrict__ hdr, int G) {
+    SeedGrid<D> g;
+    g.G = G;
+#pragma unroll
+    for (int t = 0; t < D; ++t) {
+        const float mn = ordered_value(hdr[1 + t]);
+        const float mx = ordered_value(hdr[1 + kPbMaxD + t]);
+        float rg = mx - mn;
+        if (!(rg > 1e-30f)) rg = 1.f;  // all points share this coordinate: one cell holds them
+        g.mn[t] = mn;
+        g.inv_w[t] = (float)G / rg;
+        g.w[t] = rg / (float)G;
+        // A point whose computed cell number is c lies in mn + [c w, (c + 1) w] up to the
+        // roundings of (x - mn) * inv_w, of w and of the two ends: under 16 ulps of the
+        // magnitudes involved; the slack is twice that.
+        g.slack[t] = 0x1p-19f * (fabsf(mn) + fabsf(mx) + rg);
+    }
+    return g;
+}
+
+// cell number along axis t, the same expression for points and queries (queries outside the
+// box land in the nearest cell)
+template <int D>
+__device__ __forceinline__ int seed_cell(const SeedGrid<D>& g, int t, float x) {
+    const float u = (x - g.mn[t]) * g.inv_w[t];
+    return (int)fminf(fmaxf(u, 0.f), (float)(g.G - 1));  // NaN -> 0
+}
+
+__global__ void knn_zero_ints_kernel(int* __restrict__ p, int count) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < count) p[i] = 0;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void knn_cell_count_kernel(const float* __restrict__ X, int64_t ldx,
+                                                             int n, const unsigned* __restrict__ hdr,
+                                                             int G, int* __restrict__ cells) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    const SeedGrid<D> g = seed_grid<D>(hdr, G);
+    int cell = 0;
+#pragma unroll
+    for (int t = D - 1; t >= 0; --t) cell = cell * G + seed_cell<D>(g, t, X[(int64_t)j * ldx + t]);
+    atomicAdd(cells + cell, 1);
+}
+
+// upper bound of the k-th smallest fp32 difference-form squared distance from q to the counted
+// points, +inf when even the 5^D block around q's cell holds fewer than k
+template <int D>
+__device__ __forceinline__ float seed_bound(const SeedGrid<D>& g, const int* __restrict__ cells,
+                                            const float (&q)[D], int k) {
+    static_assert(D <= 3, "block walk below is written for up to three axes");
+    int cq[3] = {0, 0, 0};
+#pragma unroll
+    for (int t = 0; t < D; ++t) cq[t] = seed_cell<D>(g, t, q[t]);
+    const int G = g.G;
+    for (int R = 0; R <= 2; ++R) {
+        int c0[3] = {0, 0, 0}, c1[3] = {0, 0, 0};
+#pragma unroll
+        for (int t = 0; t < D; ++t) {
+            c0[t] = max(cq[t] - R, 0);
+            c1[t] = min(cq[t] + R, G - 1);
+        }
+        int count = 0;
+        for (int z = c0[2]; z <= c1[2]; ++z)
+            for (int y = c0[1]; y <= c1[1]; ++y)
+                for (int x = c0[0]; x <= c1[0]; ++x) count += cells[(z * G + y) * G + x];
+        if (count >= k) {
+            float b = 0.f;
+#pragma unroll
+            for (int t = 0; t < D; ++t) {
+                const float lo = (g.mn[t] + (float)c0[t] * g.w[t]) - g.slack[t];
+                const float hi = (g.mn[t] + (float)(c1[t] + 1) * g.w[t]) + g.slack[t];
+                const float far = fmaxf(fabsf(q[t] - lo), fabsf(hi - q[t]));
+                b = fmaf(far, far, b);
+            }
+            // roundings of the bound itself and of the distance it is compared with
+            return b * (1.f + 0x1p-17f);
+        }
+    }
+    return kInf;
+}
+
 // K slots of the filter's contraction for dimension D (3 D + 3 of them, padded with zeros to
 // NM MFMAs of 16 slots): slot s < D pairs xh_s with -2 qh_s, D <= s < 2D pairs xh with -2 ql,
 // 2D <= s < 3D pairs xl with -2 qh, and the three pieces of the squared norm meet 1.
@@ -674,8 +773,9 @@ __global__ __launch_bounds__(256) void knn_pack_bf16_kernel(const float* __restr
 template <int D>
 __global__ __launch_bounds__(256, FilterSlots<D>::kMfmas == 1 ? 4 : 3) void knn_lowd_bf16_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
-    const uint4* __restrict__ Xp, const unsigned* __restrict__ hdr, int rows, int n, int k, int S,
-    int split_len, float* __restrict__ lk, int* __restrict__ li) {
+    const uint4* __restrict__ Xp, const unsigned* __restrict__ hdr, const int* __restrict__ cells,
+    int seed_cells, int rows, int n, int k, int S, int split_len, float* __restrict__ lk,
+    int* __restrict__ li) {
     constexpr int C = kPbCand;
     constexpr int NS = kPbSets;  // query sets of 32 per wave: one A-operand load feeds NS MFMAs
     constexpr int NM = FilterSlots<D>::kMfmas;  // MFMAs (of 16 K slots) per 32 x 32 keys
@@ -719,6 +819,7 @@ __global__ __launch_bounds__(256, FilterSlots<D>::kMfmas == 1 ? 4 : 3) void knn_
     bf16x8 bq[NS][NM];
     float qn[NS], cross[NS], tau[NS], tauf[NS];
     int taui[NS], cnt[NS];  // (tau, taui): key and index of the query's current k-th best
+    float tcap[NS];         // upper bound of the k-th smallest distance known before the scan
     // A pair with exact fp32 distance <= tau has a filter key below (tau - qn) + slack: the cross
     // terms the bf16 pieces leave out (<= 6.1 * 2^-18 ||x'|| ||q'|| < 2^-15 sqrt(xmax qn)), the
     // fp32 roundings of the accumulation, of qn, of the moved coordinates and of the distance
@@ -763,7 +864,14 @@ __global__ __launch_bounds__(256, FilterSlots<D>::kMfmas == 1 ? 4 : 3) void knn_
             }
             bq[st][i] = __builtin_bit_cast(bf16x8, uint4{w[0], w[1], w[2], w[3]});
         }
-        tau[st] = active ? kInf : -kInf;
+        tcap[st] = kInf;
+        if constexpr (D <= kSeedMaxD) {
+            if (seed_cells > 0 && active) {
+                const SeedGrid<D> g = seed_grid<D>(hdr, seed_cells);
+                tcap[st] = seed_bound<D>(g, cells, q[st], k);
+            }
+        }
+        tau[st] = active ? tcap[st] : -kInf;
         taui[st] = active ? kNoIdx : -1;
         tauf[st] = key_bound(st, tau[st]);
         cnt[st] = 0;
@@ -784,10 +892,12 @@ __global__ __launch_bounds__(256, FilterSlots<D>::kMfmas == 1 ? 4 : 3) void knn_
             }
             const size_t lb = ((size_t)(wave_row0 + st * 32 + L) * S + s) * k;
             const uint64_t mr = wave_merge_pair(lk + lb, li + lb, k, key, id, sc, lane, cc);
-            const float t_new = merged_key(mr);
+            // a list that is not full yet returns +inf: the seed bound stays the threshold
+            const bool capped = !(merged_key(mr) <= tcap[st]);
+            const float t_new = capped ? tcap[st] : merged_key(mr);
             if (i32 == L) {
                 tau[st] = t_new;
-                taui[st] = merged_idx(mr);
+                taui[st] = capped ? kNoIdx : merged_idx(mr);
                 tauf[st] = key_bound(st, t_new);
                 cnt[st] = 0;
             }
@@ -1012,15 +1122,31 @@ static hipError_t launch_lowd_mfma_d(const float* Q, int64_t ldq, const float* X
 template <int D>
 static hipError_t launch_lowd_bf16_d(const float* Q, int64_t ldq, const float* X, int64_t ldx,
                                      void* packed, int64_t rows, int64_t n, int k, int S,
-                                     bool pack, float* lk, int* li, hipStream_t stream) {
+                                     bool pack, int seed_cells, float* lk, int* li,
+                                     hipStream_t stream) {
+    constexpr int NM = FilterSlots<D>::kMfmas;
     unsigned* hdr = static_cast<unsigned*>(packed);
     uint4* Xp = reinterpret_cast<uint4*>(static_cast<unsigned char*>(packed) + kAlign);
+    // the cell counts of the threshold seed follow the packed points
+    int* cells = reinterpret_cast<int*>(static_cast<unsigned char*>(packed) + kAlign +
+                                        align_up((uint64_t)n * 32 * NM));
+    if (D > kSeedMaxD) seed_cells = 0;
     const dim3 pgrid((unsigned)((n + 255) / 256));
     if (pack) {
         knn_bbox_init_kernel<<<dim3(1), dim3(64), 0, stream>>>(hdr);
         const unsigned bgrid = pgrid.x < 1024u ? pgrid.x : 1024u;
         knn_bbox_kernel<D><<<dim3(bgrid), dim3(256), 0, stream>>>(X, ldx, (int)n, hdr);
         knn_pack_bf16_kernel<D><<<pgrid, dim3(256), 0, stream>>>(X, ldx, (int)n, Xp, hdr);
+        if constexpr (D <= kSeedMaxD) {
+            if (seed_cells > 0) {
+                int ncell = 1;
+                for (int t = 0; t < D; ++t) ncell *= seed_cells;
+                knn_zero_ints_kernel<<<dim3((unsigned)((ncell + 255) / 256)), dim3(256), 0, stream>>>(
+                    cells, ncell);
+                knn_cell_count_kernel<D><<<pgrid, dim3(256), 0, stream>>>(X, ldx, (int)n, hdr,
+                                                                          seed_cells, cells);
+            }
+        }
         hipError_t e0 = hipGetLastError();
         if (e0 != hipSuccess) return e0;
     }
@@ -1033,22 +1159,22 @@ static hipError_t launch_lowd_bf16_d(const float* Q, int64_t ldq, const float* X
     split_len = (split_len + 127) / 128 * 128;
     dim3 grid((unsigned)((rows + kPbTileQ - 1) / kPbTileQ), (unsigned)S);
     knn_lowd_bf16_kernel<D><<<grid, dim3(256), lds, stream>>>(
-        Q, ldq, X, ldx, Xp, hdr, (int)rows, (int)n, k, S, (int)split_len, lk, li);
+        Q, ldq, X, ldx, Xp, hdr, cells, seed_cells, (int)rows, (int)n, k, S, (int)split_len, lk, li);
     return hipGetLastError();
 }
 
 hipError_t launch_lowd_bf16(const float* Q, int64_t ldq, const float* X, int64_t ldx, void* packed,
-                            int64_t rows, int64_t n, int d, int k, int S, bool pack, float* lk,
-                            int* li, hipStream_t stream) {
+                            int64_t rows, int64_t n, int d, int k, int S, bool pack, int seed_cells,
+                            float* lk, int* li, hipStream_t stream) {
     switch (d) {
-        case 1: return launch_lowd_bf16_d<1>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
-        case 2: return launch_lowd_bf16_d<2>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
-        case 3: return launch_lowd_bf16_d<3>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
-        case 4: return launch_lowd_bf16_d<4>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
-        case 5: return launch_lowd_bf16_d<5>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
-        case 6: return launch_lowd_bf16_d<6>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
-        case 7: return launch_lowd_bf16_d<7>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
-        case 8: return launch_lowd_bf16_d<8>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, lk, li, stream);
+        case 1: return launch_lowd_bf16_d<1>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, seed_cells, lk, li, stream);
+        case 2: return launch_lowd_bf16_d<2>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, seed_cells, lk, li, stream);
+        case 3: return launch_lowd_bf16_d<3>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, seed_cells, lk, li, stream);
+        case 4: return launch_lowd_bf16_d<4>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, seed_cells, lk, li, stream);
+        case 5: return launch_lowd_bf16_d<5>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, seed_cells, lk, li, stream);
+        case 6: return launch_lowd_bf16_d<6>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, seed_cells, lk, li, stream);
+        case 7: return launch_lowd_bf16_d<7>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, seed_cells, lk, li, stream);
+        case 8: return launch_lowd_bf16_d<8>(Q, ldq, X, ldx, packed, rows, n, k, S, pack, seed_cells, lk, li, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -140,6 +140,24 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
             out->tile_q = kPbTileQ;
             out->tile_x = 32;
             out->norms_bytes = packed16;
+            // threshold seed: a grid with about 2 k points per cell, when the grid is worth
+            // having (two cells or more per axis) and its counts fit as well
+            if (d <= kSeedMaxD) {
+                const int64_t want = n / ((int64_t)kSeedPointsPerCellPerK * k);
+                int64_t G = 1;
+                auto cells_of = [&](int64_t g) {
+                    int64_t c = 1;
+                    for (int t = 0; t < d; ++t) c *= g;
+                    return c;
+                };
+                while (cells_of(G + 1) <= want && cells_of(G + 1) <= kSeedMaxCells) ++G;
+                const uint64_t seed = align_up((uint64_t)cells_of(G) * 4);
+                if (G >= 2 && mem_limit_bytes >= packed16 + seed + lists_bytes_for((uint64_t)min_rows16,
+                                                                                   1, (uint64_t)k)) {
+                    out->seed_cells = (int32_t)G;
+                    out->norms_bytes = packed16 + seed;
+                }
+            }
         }
     }
     const int64_t tile = out->tile_q;
