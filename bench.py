@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per search-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/*_pmc.txt), scaled by the copy-kernel calibration stated there.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "c2_pointcloud_d3": 227.34e9,   # knn_lowd_bf16_kernel: 224.72 GB fetched + 2.62 GB written
+    "c2_pointcloud_d3": 190.47e9,   # knn_lowd_bf16_kernel: 189.54 GB fetched + 0.93 GB written
     "c3_imagelike_d784": 351.5e9,   # knn_mfma_kernel: 351.4 GB fetched + 0.07 GB written
     "c4_clustered_d128": 3455.6e9,  # knn_mfma_qreg_kernel: 3443.4 GB fetched + 12.2 GB written
     "c5_memsweep_d256": 577.5e9,    # knn_mfma_qreg_kernel: 576.4 GB fetched + 1.05 GB written

@@ -28,10 +28,12 @@ constexpr int kPbSets = 2;
 constexpr int kPbTileQ = 4 * 32 * kPbSets;       // query rows per workgroup
 constexpr int kPbCand = 16;                      // candidate slots per query (LDS)
 // threshold seed of that path, d <= kSeedMaxD: the points are counted into a grid of at most
-// kSeedMaxCells cells (about kSeedPointsPerCellPerK * k points per cell)
+// kSeedMaxCells cells, about 1.5 k points per cell (n * 2 / (3 k) cells): measured best between
+// 1 k (own cell too often short of k points) and 2 k (looser bound) at n = 1e6, k = 16 and 64
 constexpr int kSeedMaxD = 3;
 constexpr int kSeedMaxCells = 32768;
-constexpr int kSeedPointsPerCellPerK = 2;
+constexpr int kSeedCellsPerPointNum = 2;
+constexpr int kSeedCellsPerPointDen = 3;
 
 // d > kLowdMaxD: fp32 MFMA tile, 4 waves, each wave owns 32 queries x 128 points.
 constexpr int kMfmaTileQ = 128;

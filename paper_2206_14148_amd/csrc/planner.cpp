@@ -8,7 +8,6 @@
 // device memory (norms + every partial list of a chunk) and keeps the sum under the limit.
 #include <cctype>
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 
 #include "../../include/knn.h"
@@ -140,10 +139,10 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
             out->tile_q = kPbTileQ;
             out->tile_x = 32;
             out->norms_bytes = packed16;
-            // threshold seed: a grid with about 2 k points per cell, when the grid is worth
+            // threshold seed: a grid with about 1.5 k points per cell, when the grid is worth
             // having (two cells or more per axis) and its counts fit as well
             if (d <= kSeedMaxD) {
-                const int64_t want = n / ((int64_t)kSeedPointsPerCellPerK * k);
+                const int64_t want = n * kSeedCellsPerPointNum / ((int64_t)kSeedCellsPerPointDen * k);
                 int64_t G = 1;
                 auto cells_of = [&](int64_t g) {
                     int64_t c = 1;

@@ -399,6 +399,87 @@ def test_exact_ties_keep_the_lower_index_on_every_low_d_path(K, oracle, seed, d,
     assert paths == {K.KNN_PATH_LOWD_BF16, K.KNN_PATH_LOWD_MFMA, K.KNN_PATH_LOWD}
 
 
+def _seed_cases():
+    # (name, d, k, builder(g) -> (Q, X)): data that strains the grid-count threshold seed of the
+    # bf16 filter path: empty and crowded cells, a flat axis, queries far outside the points'
+    # box, a large common offset, k above what the widest block of cells holds
+    def clustered(g, d):
+        centres = g.uniform(-1, 1, size=(12, d))
+        X = centres[g.integers(0, 12, size=40_000)] + 0.003 * g.standard_normal((40_000, d))
+        X[:50] = g.uniform(-30, 30, size=(50, d))  # a few far outliers stretch the box
+        Q = np.concatenate([X[g.integers(0, 40_000, size=900)] + 0.001 * g.standard_normal((900, d)),
+                            g.uniform(-60, 60, size=(300, d))])
+        return Q, X
+
+    def flat_axis(g, d):
+        X = g.uniform(0, 1, size=(30_000, d))
+        X[:, d - 1] = 0.25
+        Q = g.uniform(-0.5, 1.5, size=(1000, d))
+        return Q, X
+
+    def offset(g, d):
+        X = 4096.0 + g.uniform(0, 1, size=(30_000, d))
+        Q = 4096.0 + g.uniform(-0.2, 1.2, size=(1000, d))
+        return Q, X
+
+    def lattice(g, d):
+        # points exactly on cell borders of many grids, heavy duplication
+        X = g.integers(0, 17, size=(40_000, d)) / 16.0
+        Q = g.integers(-2, 19, size=(1200, d)) / 16.0
+        return Q, X
+
+    def two_points_far_apart(g, d):
+        X = np.concatenate([np.zeros((20_000, d)), np.ones((20_000, d)) * 1000.0])
+        X += 1e-3 * g.standard_normal(X.shape)
+        Q = g.uniform(-10, 1010, size=(800, d))
+        return Q, X
+
+    cases = []
+    for d in (1, 2, 3):
+        cases += [("clustered", d, 16, clustered), ("flat_axis", d, 9, flat_axis),
+                  ("offset", d, 16, offset), ("lattice", d, 5, lattice),
+                  ("two_clumps", d, 3, two_points_far_apart), ("clustered_k200", d, 200, clustered)]
+    return cases
+
+
+@pytest.mark.parametrize("name,d,k,build", _seed_cases(), ids=lambda v: str(v) if not callable(v) else "")
+def test_threshold_seed_keeps_results_exact_on_uneven_data(K, oracle, name, d, k, build):
+    g = np.random.Generator(np.random.PCG64(W.SEED_BASE + 13_000_000 + 31 * d + k))
+    Q, X = build(g, d)
+    Q, X = np.ascontiguousarray(Q, np.float32), np.ascontiguousarray(X, np.float32)
+    m, n = Q.shape[0], X.shape[0]
+    roomy = K.knn_plan(m, n, d, k, 256 * W.MB)
+    assert roomy.path == K.KNN_PATH_LOWD_BF16 and roomy.seed_cells >= 2
+    lo = roomy.min_limit_bytes
+    assert K.knn_plan(m, n, d, k, lo + 40_000).path == K.KNN_PATH_LOWD  # no filter, no seed
+    a_idx, a_dist = run_gpu(K, Q, X, k, lo + 40_000)
+    b_idx, b_dist = run_gpu(K, Q, X, k, 256 * W.MB)
+    assert np.array_equal(a_idx, b_idx) and np.array_equal(a_dist, b_dist)
+    # a limit with room for the packed points but not for the cell counts: same path, unseeded
+    o_idx, o_dist, o_next = oracle.knn(Q, X, k)
+    say("  ", name, d, "cells/axis", roomy.seed_cells, check(b_idx, b_dist, o_idx, o_dist, o_next, n))
+
+
+def test_threshold_seed_with_several_point_ranges_and_query_chunks(K, oracle):
+    # few queries: the point axis is cut into ranges, each with its own lists under the same
+    # seed bound; a tight limit: several query chunks reuse one grid
+    Q, X = W.random_case(4242, 300, 400_000, 3, kind="uniform")
+    k = 16
+    plan = K.knn_plan(300, 400_000, 3, k, 256 * W.MB)
+    assert plan.path == K.KNN_PATH_LOWD_BF16 and plan.seed_cells >= 2 and plan.n_splits > 1
+    stats, idx, dist = parity(K, oracle, Q, X, k, 256 * W.MB)
+    Q2, X2 = W.random_case(4243, 5000, 60_000, 2, kind="uniform")
+    base = K.knn_plan(5000, 60_000, 2, k, 1 << 40)
+    tight = None
+    for extra in range(200_000, 2_000_000, 50_000):
+        p = K.knn_plan(5000, 60_000, 2, k, base.norms_bytes + extra)
+        if p.path == K.KNN_PATH_LOWD_BF16 and p.seed_cells >= 2 and p.q_chunks > 1:
+            tight = base.norms_bytes + extra
+            break
+    assert tight is not None
+    parity(K, oracle, Q2, X2, k, tight)
+
+
 def test_seeded_random_shapes_and_limits(K, oracle):
     # a seeded sweep over shapes, k, metrics and limits (from the smallest feasible one up):
     # whatever plan comes out - path, chunks, ranges - the result passes the parity rule
