@@ -22,6 +22,7 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 # published MI355X peaks
+PEAK_BF16_MATRIX_TFLOPS = 2500.0  # dense bf16 MFMA, MI355X published
 PEAK_FP32_MATRIX_TFLOPS = 157.3
 PEAK_FP32_VECTOR_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
@@ -371,7 +372,7 @@ def main() -> int:
     ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
     idx = torch.empty((w.m, w.k), dtype=torch.int32, device=dev)
     dist = torch.empty((w.m, w.k), dtype=torch.float32, device=dev)
-    path_name = {0: "lowd", 1: "mfma", 2: "lowd_mfma", 3: "l1", 4: "lowd_bf16"}[plan.path]
+    path_name = {0: "lowd", 1: "mfma", 2: "lowd_mfma", 3: "l1", 4: "lowd_bf16", 5: "mfma_split"}[plan.path]
     log(f"[bench] plan: path={path_name} chunks={plan.q_chunks} "
         f"ranges={plan.n_splits} workspace={plan.workspace_bytes} B (limit {limit} B)")
 
@@ -418,6 +419,19 @@ def main() -> int:
                     "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_FP32_MATRIX_TFLOPS, "traffic": traffic,
                     "flops_per_pair": 2 * w.d}
+    elif plan.path == K.KNN_PATH_MFMA_SPLIT:
+        # The -2 Q X^T contraction runs as three bf16 products per coordinate pair (values cut
+        # into two bf16 pieces): 6 d bf16 flops per pair on the matrix cores, with d rounded
+        # up to the 16 coordinates of a pipeline step, against the dense bf16 peak.
+        d_pad = (w.d + 15) // 16 * 16
+        flops = 6.0 * d_pad * pairs_per_launch
+        achieved = flops / avg_launch_s / 1e12
+        roofline = {"bound": "mfma", "kernel": "knn_split_kernel", "achieved": achieved,
+                    "peak": PEAK_BF16_MATRIX_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_BF16_MATRIX_TFLOPS, "traffic": traffic,
+                    "flops_per_pair": 6 * d_pad,
+                    # the same launch priced as the 2 d flops per pair of the plain contraction
+                    "contraction_tflops": 2.0 * w.d * pairs_per_launch / avg_launch_s / 1e12}
     elif plan.path == K.KNN_PATH_LOWD_MFMA:
         # filter contraction over K = 4: [x0 x1 x2 |x|^2] . [-2q0 -2q1 -2q2 1]
         flops = 2.0 * 4 * pairs_per_launch

@@ -55,13 +55,17 @@ typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1, KNN_METRIC_L1 = 2 } k
 
 /* kernel families (knn_plan_t.path) */
 #define KNN_PATH_LOWD 0 /* d <= 8: difference-form distances on the vector ALU  */
-#define KNN_PATH_MFMA 1 /* d  > 8: fp32 matrix-core tile of -2 Q X^T plus norms */
+#define KNN_PATH_MFMA 1 /* d  > 8, cosine metric: fp32 matrix-core tile of -2 Q X^T plus norms */
 #define KNN_PATH_L1 3   /* L1 metric: absolute differences on the vector ALU, any d   */
 #define KNN_PATH_LOWD_MFMA 2 /* d <= 3 and room for 16 n bytes of packed points:
                                 matrix-core filter + the same exact test as path 0 */
 #define KNN_PATH_LOWD_BF16 4 /* d <= 8 and room for 32 n bytes (d <= 4) or 64 n bytes: the filter
                                 in bf16 pieces on points moved by their bounding box's midpoint,
                                 same exact test */
+#define KNN_PATH_MFMA_SPLIT 5 /* d > 8, squared-Euclidean: every fp32 value cut into two bf16
+                                 pieces, -2 Q X^T plus norms from three bf16 matrix-core
+                                 products per coordinate as a filter, exact fp32
+                                 difference-form test of the pairs that pass */
 
 /*
  * The plan: how the call is cut into pieces (section 4.3: split the largest
@@ -86,9 +90,13 @@ typedef struct {
                             into to give every list a finite starting threshold; 0: none */
     uint64_t norms_bytes;     /* workspace: per-point data. path 1: squared norms, plus the
                                  blocked copy of X when x_blocked; path 2: packed points
-                                 [x0 x1 x2 |x|^2]; path 4: a 256-byte header, 32 bytes
+                                 [x0 x1 x2 |x|^2]; path 5: squared norms and a 256-byte
+                                 header (their maximum); path 4: a 256-byte header, 32 bytes
                                  per point and 16 K slots, and seed_cells^d counts;
                                  paths 0, 3: nothing                                   */
+    uint64_t query_bytes;     /* workspace: per-query data of one chunk. path 5: the split
+                                 queries (64 bytes per row and 16 coordinates) and their
+                                 squared norms; else 0                                 */
     uint64_t lists_bytes;     /* workspace: partial k-lists of one chunk        */
     uint64_t workspace_bytes; /* total device workspace needed, <= mem_limit    */
     uint64_t min_limit_bytes; /* smallest limit any plan for this shape fits in */

@@ -23,6 +23,7 @@ KNN_PATH_LOWD = 0
 KNN_PATH_MFMA = 1
 KNN_PATH_LOWD_MFMA = 2
 KNN_PATH_LOWD_BF16 = 4
+KNN_PATH_MFMA_SPLIT = 5
 KNN_METRIC_L2SQ = 0
 KNN_METRIC_COSINE = 1
 KNN_METRIC_L1 = 2
@@ -96,7 +97,8 @@ class PlanStruct(ctypes.Structure):
         ("chunk_rows", ctypes.c_int64), ("q_chunks", ctypes.c_int64),
         ("streams", ctypes.c_int32), ("x_blocked", ctypes.c_int32),
         ("metric", ctypes.c_int32), ("seed_cells", ctypes.c_int32),
-        ("norms_bytes", ctypes.c_uint64), ("lists_bytes", ctypes.c_uint64),
+        ("norms_bytes", ctypes.c_uint64), ("query_bytes", ctypes.c_uint64),
+        ("lists_bytes", ctypes.c_uint64),
         ("workspace_bytes", ctypes.c_uint64), ("min_limit_bytes", ctypes.c_uint64),
     ]
 
@@ -147,6 +149,7 @@ class Plan:
     metric: int
     seed_cells: int
     norms_bytes: int
+    query_bytes: int
     lists_bytes: int
     workspace_bytes: int
     min_limit_bytes: int
@@ -230,7 +233,7 @@ def knn_status_string(status: int) -> str:
 def _plan_from_struct(ps: PlanStruct) -> Plan:
     return Plan(ps.m, ps.n, ps.d, ps.k, ps.path, ps.tile_q, ps.tile_x, ps.n_splits,
                 ps.chunk_rows, ps.q_chunks, ps.streams, ps.x_blocked, ps.metric, ps.seed_cells,
-                ps.norms_bytes, ps.lists_bytes,
+                ps.norms_bytes, ps.query_bytes, ps.lists_bytes,
                 ps.workspace_bytes, ps.min_limit_bytes)
 
 

@@ -150,8 +150,16 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     using namespace knn;
     float* xn = reinterpret_cast<float*>(ws);
     void* xblocked = plan.x_blocked ? ws + align_up((uint64_t)n * 4) : nullptr;
-    float* lk = reinterpret_cast<float*>(ws + plan.norms_bytes);
-    int* li = reinterpret_cast<int*>(ws + plan.norms_bytes + plan.lists_bytes / 2);
+    // path 5: [squared norms][header: their maximum] | [split queries][query norms][shared
+    // thresholds] | lists
+    unsigned char* hdr = ws + align_up((uint64_t)n * 4);
+    unsigned char* qs = ws + plan.norms_bytes;
+    float* qn = reinterpret_cast<float*>(
+        qs + align_up((uint64_t)plan.chunk_rows * 64 * (((uint64_t)d + kSpKC - 1) / kSpKC)));
+    unsigned char* tsh = reinterpret_cast<unsigned char*>(qn) + align_up((uint64_t)plan.chunk_rows * 4);
+    unsigned char* lists = ws + plan.norms_bytes + plan.query_bytes;
+    float* lk = reinterpret_cast<float*>(lists);
+    int* li = reinterpret_cast<int*>(lists + plan.lists_bytes / 2);
     const int S = plan.n_splits;
     const bool cosine = metric == KNN_METRIC_COSINE;
 
@@ -164,6 +172,15 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
         if (e != hipSuccess) {
             drop_bracket(t0);
             return hip_fail(e, "row norms / point blocking launch");
+        }
+        close_bracket(t0, stream, 0);
+    } else if (plan.path == KNN_PATH_MFMA_SPLIT) {
+        hipEvent_t t0 = mark(stream);
+        e = launch_row_norms(X, ldx, n, d, false, xn, stream);
+        if (e == hipSuccess) e = launch_max_norm(xn, n, hdr, stream);
+        if (e != hipSuccess) {
+            drop_bracket(t0);
+            return hip_fail(e, "row norms launch");
         }
         close_bracket(t0, stream, 0);
     } else if (plan.path == KNN_PATH_LOWD_MFMA || plan.path == KNN_PATH_LOWD_BF16) {
@@ -191,7 +208,13 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
         else if (plan.path == KNN_PATH_LOWD_BF16)
             e = launch_lowd_bf16(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, plan.seed_cells, lk,
                                  li, stream);
-        else
+        else if (plan.path == KNN_PATH_MFMA_SPLIT) {
+            e = launch_split_queries(Qc, ldq, rows, d, qs, tsh, stream);
+            if (e == hipSuccess) e = launch_row_norms(Qc, ldq, rows, d, false, qn, stream);
+            if (e == hipSuccess)
+                e = launch_split(Qc, ldq, X, ldx, qs, qn, tsh, xn, hdr, rows, n, d, k, S, lk, li,
+                                 stream);
+        } else
             e = launch_mfma(Qc, ldq, X, ldx, xn, xblocked, cosine, rows, n, d, k, S, lk, li,
                             stream);
         if (e != hipSuccess) {

@@ -43,9 +43,19 @@ constexpr int kMfmaRowStride = 20;   // floats per staged row (16 + 4 pad, keeps
 constexpr int kMfmaQregMaxChunks = 16;  // d <= 256: queries stay in registers
 constexpr int kMfmaCand = 32;        // candidate slots per query (LDS)
 
+// d > kPbMaxD, squared-Euclidean metric: bf16 matrix-core filter on split values + exact fp32 test,
+// 8 waves, each wave owns 32 queries x 128 points.
+constexpr int kSpWaves = 8;
+constexpr int kSpTileQ = 32 * kSpWaves;
+constexpr int kSpTileX = 128;
+constexpr int kSpKC = 16;            // coordinates per pipeline step (three MFMAs of 16 K slots)
+constexpr int kSpCand = 32;          // buffered point indices per query (LDS)
+constexpr int kSpRoom = 8;           // a buffer with fewer free slots than this is emptied after the tile
+
 // Workgroups the chip holds at once (LDS-limited): the planner sizes launches in rounds of these.
 constexpr int kLowdResidentWorkgroups = 4 * kNumCU;
 constexpr int kMfmaResidentWorkgroups = 2 * kNumCU;
+constexpr int kSpResidentWorkgroups = kNumCU;   // 8 waves of up to 256 registers: one per CU
 constexpr int kWarmupPointsPerK = 64;     // list warm-up of one point range, in point-equivalents per k
 // the same for the low-d filter kernels, per k and per unit of 1 + ln(range / k): measured
 // ~370 cycles per accepted pair against ~5 (bf16, 64 queries per wave) or ~7 (fp32 filter, 32

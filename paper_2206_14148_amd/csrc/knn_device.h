@@ -132,9 +132,10 @@ struct MergeScratch {
 // key's bits in the low word, the index in the high word (both stay in registers that way).
 // ncand: the candidates sit in lanes 0 .. ncand-1 (wave-uniform; 16 or fewer take a shorter
 // network).  All 64 lanes must call it together.
-__device__ __noinline__ uint64_t wave_merge_pair(float* __restrict__ gk, int* __restrict__ gi, int k,
-                                                 float ckey, int cidx, const MergeScratch& sc,
-                                                 int lane, int ncand) {
+__device__ __forceinline__ uint64_t wave_merge_pair_inline(float* __restrict__ gk,
+                                                           int* __restrict__ gi, int k, float ckey,
+                                                           int cidx, const MergeScratch& sc, int lane,
+                                                           int ncand) {
     // A list is read and written only by the wave that owns its query, so wave-level
     // ordering is enough; wave_sync() also orders this wave's earlier global stores to the
     // list before the loads below (same compute unit, same vector L1).
@@ -198,6 +199,14 @@ __device__ __noinline__ uint64_t wave_merge_pair(float* __restrict__ gk, int* __
     tidx = __shfl(tidx, src);
     wave_sync();
     return ((uint64_t)(unsigned)tidx << 32) | __float_as_uint(tau);
+}
+// Out of line: in most kernels the merge is rare and its registers should not count in the
+// search loop.  (A kernel whose loop already fills the register file calls the inline form: a
+// call would force everything live across it into the callee-saved half of the registers.)
+__device__ __noinline__ uint64_t wave_merge_pair(float* __restrict__ gk, int* __restrict__ gi, int k,
+                                                 float ckey, int cidx, const MergeScratch& sc,
+                                                 int lane, int ncand) {
+    return wave_merge_pair_inline(gk, gi, k, ckey, cidx, sc, lane, ncand);
 }
 __device__ __forceinline__ float merged_key(uint64_t r) { return __uint_as_float((unsigned)r); }
 __device__ __forceinline__ int merged_idx(uint64_t r) { return (int)(r >> 32); }

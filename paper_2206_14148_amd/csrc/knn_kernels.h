@@ -47,6 +47,19 @@ hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx,
                        const void* xblocked, bool cosine, int64_t rows, int64_t n, int d, int k,
                        int S, float* lk, int* li, hipStream_t stream);
 
+// d > kPbMaxD, squared-Euclidean metric: bf16 matrix-core filter on split values, exact fp32
+// difference-form test of what passes it (knn_split.hip).
+//   launch_max_norm      hdr word 0 = max of xn[0..n) (hdr: kAlign bytes)
+//   launch_split_queries qs = the B operands of `rows` queries: ceil(d / 16) * 64 bytes per row;
+//                        tsh = [rows] words set to +inf (the thresholds the ranges share)
+//   launch_split         the search; qn = squared norms of the chunk's queries (fp32, [rows])
+hipError_t launch_max_norm(const float* xn, int64_t n, void* hdr, hipStream_t stream);
+hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d, void* qs,
+                                void* tsh, hipStream_t stream);
+hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* qs,
+                        const float* qn, void* tsh, const float* xn, const void* hdr, int64_t rows,
+                        int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream);
+
 // Blocked copy of X: [ceil(n/128)][ceil(d/16)] contiguous blocks of 128 x 16 floats, zero-filled.
 hipError_t launch_block_points(const float* X, int64_t ldx, int64_t n, int d, void* xblocked,
                                hipStream_t stream);

@@ -1,0 +1,518 @@
+// gfx950 (CDNA4, MI355X) kNN search for d > 8, squared-Euclidean metric: the expansion
+// sum x^2 - 2 q.x of paper section 4.1 as a FILTER on the bf16 matrix cores, in front of an exact
+// fp32 test of the few pairs that pass it.
+//
+// An fp32 MFMA delivers 256 flops per cycle and compute unit, a bf16 MFMA 4096.  Every fp32 value
+// is cut into two bf16 pieces, v = vh + vl + (|rest| <= 2^-18 |v|), and the dot product is taken
+// as  sum_t xh_t qh_t + xh_t ql_t + xl_t qh_t : three bf16 MFMAs per 16 coordinates instead of
+// eight fp32 ones of twice the length each, products exact in fp32.  What is left out is at most
+// 3 * 2^-18 |x| |q| (doubled by the factor -2); the filter threshold allows for it and for every
+// fp32 rounding on the way, so no pair at or below a query's current k-th distance is lost.  The
+// pairs that pass are buffered per query and, when a buffer is full, evaluated exactly (fp32
+// difference form, fixed summation order) and merged into the query's list; the list keys and
+// hence the results do not depend on the filter.  The distance tile still never leaves the
+// registers (section 4.3).
+#include <hip/hip_runtime.h>
+
+#include <climits>
+#include <cmath>
+#include <cstdint>
+
+#include "knn_config.h"
+#include "knn_device.h"
+#include "knn_kernels.h"
+
+namespace knn {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// bf16 pieces (round to nearest even) of two floats: hi = bf16(v), lo = bf16(v - hi), each word
+// holding the first value in its low half.  scale multiplies both pieces (a power of two: exact).
+__device__ __forceinline__ void split_pair(float a, float b, float scale, unsigned& hi, unsigned& lo) {
+    const f32x2 p = {a, b};
+    const bf16x2 hb = __builtin_convertvector(p, bf16x2);
+    const f32x2 hv = __builtin_convertvector(hb, f32x2);
+    const bf16x2 lb = __builtin_convertvector(p - hv, bf16x2);
+    if (scale == 1.f) {
+        hi = __builtin_bit_cast(unsigned, hb);
+        lo = __builtin_bit_cast(unsigned, lb);
+    } else {
+        const f32x2 lv = __builtin_convertvector(lb, f32x2);
+        hi = __builtin_bit_cast(unsigned, __builtin_convertvector(hv * scale, bf16x2));
+        lo = __builtin_bit_cast(unsigned, __builtin_convertvector(lv * scale, bf16x2));
+    }
+}
+
+__device__ __forceinline__ void split8(const f32x4& x0, const f32x4& x1, float scale, uint4& hi,
+                                       uint4& lo) {
+    split_pair(x0[0], x0[1], scale, hi.x, lo.x);
+    split_pair(x0[2], x0[3], scale, hi.y, lo.y);
+    split_pair(x1[0], x1[1], scale, hi.z, lo.z);
+    split_pair(x1[2], x1[3], scale, hi.w, lo.w);
+}
+
+// header word 0 of the per-point area: max ||x||^2 (bits of a non-negative float)
+__global__ void knn_split_init_kernel(unsigned* __restrict__ hdr) {
+    if (threadIdx.x == 0) hdr[0] = 0u;
+}
+
+__global__ __launch_bounds__(256) void knn_max_norm_kernel(const float* __restrict__ xn, int64_t n,
+                                                           unsigned* __restrict__ hdr) {
+    float m = 0.f;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+        m = fmaxf(m, xn[i]);
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
+    if ((threadIdx.x & 63) == 0) atomicMax(hdr, __float_as_uint(m));
+}
+
+// B operands of the queries of one chunk: per row and 16-coordinate chunk 64 bytes,
+// [-2 qh: coordinates 0..7 | -2 qh: 8..15 | -2 ql: 0..7 | -2 ql: 8..15], zero past d.
+template <bool ALIGNED>
+__global__ __launch_bounds__(256) void knn_split_queries_kernel(const float* __restrict__ Q,
+                                                                int64_t ldq, int rows, int d,
+                                                                int nch, uint4* __restrict__ Qs) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)rows * nch) return;
+    const int r = (int)(idx / nch);
+    const int c = (int)(idx - (int64_t)r * nch);
+    uint4 hi[2], lo[2];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int col = c * 16 + half * 8;
+        const f32x4 v0 = mask_row4(load_row4<ALIGNED>(Q, ldq, r, rows, col, d), true, col, d, 1.f);
+        const f32x4 v1 =
+            mask_row4(load_row4<ALIGNED>(Q, ldq, r, rows, col + 4, d), true, col + 4, d, 1.f);
+        split8(v0, v1, -2.f, hi[half], lo[half]);
+    }
+    uint4* o = Qs + idx * 4;
+    o[0] = hi[0];
+    o[1] = hi[1];
+    o[2] = lo[0];
+    o[3] = lo[1];
+}
+
+// One lane's share of the exact key sum_t (q_t - x_t)^2 of a candidate: the groups of four
+// coordinates g = part, part + 2, ... in ascending order, one fma chain.  The loads of eight groups
+// are issued before the first is used, so that a row of a few KB costs a few memory round trips,
+// not one per group.
+template <bool ALIGNED>
+__device__ __forceinline__ float exact_partial(const float* __restrict__ qp, const float* __restrict__ xp,
+                                            int d, int part) {
+    constexpr int U = 8;
+    float sum = 0.f;
+    const int ng = (d + 3) >> 2;  // groups of four coordinates (the last may be ragged)
+    for (int g0 = part; g0 < ng; g0 += 2 * U) {
+        f32x4 xv[U], qv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int g = g0 + 2 * u;
+            const int gc = g < ng ? g : part;  // a valid group; its value is not used
+            if (ALIGNED) {
+                xv[u] = *reinterpret_cast<const f32x4*>(xp + 4 * gc);
+                qv[u] = *reinterpret_cast<const f32x4*>(qp + 4 * gc);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int t = 4 * gc + e < d ? 4 * gc + e : 0;
+                    xv[u][e] = xp[t];
+                    qv[u][e] = qp[t];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int g = g0 + 2 * u;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float df = qv[u][e] - xv[u][e];
+                const float next = fmaf(df, df, sum);
+                sum = (g < ng && 4 * g + e < d) ? next : sum;
+            }
+        }
+    }
+    return sum;
+}
+
+// The rare path of knn_split_kernel for one query, out of line and with everything passed by
+// value, so that the search loop keeps its state in registers and pays for this only where it
+// is called.  The cc <= 32 candidates are the point indices cbuf[0 .. cc-1], or, with cbuf null,
+// the points jbase .. jbase + cc - 1.  Two lanes per
+// candidate: lane 2c + p sums the groups of four coordinates g = p, p + 2, ... (exact_partial),
+// the two partial sums are added; that order is part of the key's definition.  The keys are
+// merged into the query's list gk/gi, the list's k-th key is published in *tshr (atomic
+// minimum; keys are sums of squares, so as unsigned words they order like the floats, +inf
+// above all).  Returns the list's new k-th key (low word) and the lowest k-th key any range of
+// the query has published so far (high word), both as float bits.
+template <bool ALIGNED>
+__device__ __noinline__ uint64_t split_flush_query(const float* __restrict__ qp,
+                                                   const float* __restrict__ X, int64_t ldx, int d,
+                                                   int jsafe, const int* __restrict__ cbuf, int jbase,
+                                                   int cc,
+                                                   float* __restrict__ gk, int* __restrict__ gi, int k,
+                                                   float* scratch, unsigned* __restrict__ tshr,
+                                                   int lane) {
+    MergeScratch sc;
+    sc.cand_key = scratch;
+    sc.cand_idx = reinterpret_cast<int*>(scratch + kWave);
+    sc.list_key = scratch + 2 * kWave;
+    sc.list_idx = reinterpret_cast<int*>(scratch + 2 * kWave + k);
+    wave_sync();
+    const int cand = lane >> 1, part = lane & 1;
+    const int j = cand < cc ? (cbuf ? cbuf[cand] : jbase + cand) : -1;
+    float sum = exact_partial<ALIGNED>(qp, X + (int64_t)(j < 0 ? jsafe : j) * ldx, d, part);
+    sum += lane_xor<1>(sum);
+    // candidate c sits in lanes 2c, 2c + 1; the merge wants it in lane c
+    const int src = (2 * lane) & 63;
+    float key = __shfl(sum, src);
+    int id = __shfl(j, src);
+    if (lane >= cc) {
+        key = kInf;
+        id = kNoIdx;
+    }
+    const uint64_t mr = wave_merge_pair_inline(gk, gi, k, key, id, sc, lane, cc);
+    const unsigned t_bits = (unsigned)mr;
+    unsigned seen = 0x7f800000u;
+    if (lane == 0) seen = atomicMin(tshr, t_bits);
+    seen = (unsigned)__builtin_amdgcn_readfirstlane((int)seen);
+    const unsigned low = seen < t_bits ? seen : t_bits;
+    return ((uint64_t)low << 32) | t_bits;
+}
+
+// ---------------------------------------------------------------------------------------
+// One workgroup = 256 queries (8 waves x 32) against a range of the points, in tiles of 128
+// points.  Per 16 coordinates the workgroup loads a 128 x 16 fp32 piece of X (one float4 per
+// thread), splits it into bf16 pieces on the way into LDS (laid out as the MFMA's A operand:
+// 32 bytes per row and piece, the lower half-wave reads coordinates 0..7, the upper 8..15), and
+// every wave runs 4 blocks x 3 MFMAs on it; the queries' B operands were split once per chunk
+// of queries and come straight from the workspace (L2) into registers.  LDS and registers are
+// double-buffered over (tile, chunk) steps, one workgroup barrier per step.  64 accumulator
+// registers per lane leave room for two workgroups per compute unit.
+//
+// Nothing of X is masked on the way: coordinates past d meet zeros in the B operands, and rows
+// past the range get +inf as their norm, so whatever valid (finite) data the clamped loads
+// return there cannot make a key pass.
+//
+// The point ranges of one query run in different workgroups at the same time.  Each publishes
+// the k-th key of its own list in tsh[row] (atomic minimum) and reads the others' at every
+// tile: a range's k-th best bounds the overall k-th best from above, so pairs beyond it need
+// not enter any list.  The lists of a range then hold the range's best entries only as far as
+// they can matter; the merged result is the same.
+// ---------------------------------------------------------------------------------------
+template <bool ALIGNED>
+__global__ __launch_bounds__(512, 2) void knn_split_kernel(
+    const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
+    const uint4* __restrict__ Qs, const float* __restrict__ qnorm, unsigned* __restrict__ tsh,
+    const float* __restrict__ xn, const unsigned* __restrict__ hdr, int rows, int n, int d, int nch,
+    int k, int S, int split_len, int BQ, int BS, float* __restrict__ lk, int* __restrict__ li) {
+    constexpr int TQ = kSpTileQ, TX = kSpTileX, C = kSpCand;
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint4* as = reinterpret_cast<uint4*>(smem);                  // [2 buffers][2 pieces][TX][2]
+    float* xns = reinterpret_cast<float*>(as + 2 * 2 * TX * 2);  // [2][TX] accumulator start values
+    int* ci = reinterpret_cast<int*>(xns + 2 * TX);              // [TQ][C] buffered point indices
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int i32 = lane & 31;
+    const int h = lane >> 5;
+
+    int s, wg_row0;
+    if (!xcd_block_map(rows, TQ, S, BQ, BS, s, wg_row0)) return;  // padding (before any barrier)
+    const int wave_row0 = wg_row0 + wave * 32;
+    int* wci = ci + wave * 32 * C;
+    init_lists32(lk, li, wave_row0, rows, S, s, k, lane);
+
+    const float xmax = __uint_as_float(hdr[0]);
+    // Filter keys are  xn_j - 2 (xh.qh + xh.ql + xl.qh)  accumulated in fp32; the exact test
+    // gives  dd = sum (q - x)^2  in fp32.  dd <= tau implies key < (tau - qn) + slack with
+    //   dropped products            6 * 2^-18 |x| |q|            (|x| |q| <= sqrt(xmax qn))
+    //   3 d fp32 accumulations       of terms that sum to at most 2.02 |x| |q| in magnitude
+    //   roundings of xn, qn, dd      each below (d / 64 + 8) ulps of the value
+    // The constants below are at least twice those sums.
+    const float e_dot = 6.2f * 0x1p-18f + (float)(12 * d + 32) * 0x1p-24f;
+    const float e_sum = (float)(d + 16) * 0x1p-23f;
+    // own = k-th key of this range's list (+inf until it is full, -inf for a lane without a
+    // query), cap = the lowest k-th key any range of the query has published, tauf = the filter
+    // threshold that follows from min(own, cap)
+    const int r_mine = wave_row0 + i32;
+    const bool active = r_mine < rows;
+    const int qrow = active ? r_mine : rows - 1;
+    const float qn = qnorm[qrow];
+    const float cross = e_dot * sqrtf(xmax * qn);
+    float own = active ? kInf : -kInf;
+    float cap = kInf;
+    float tauf = own;
+    int cnt = 0, ovf = 0;
+    const uint4* const qb = Qs + (size_t)qrow * nch * 4 + h;
+    auto key_bound = [&](float t) { return (t - qn) + (cross + e_sum * (xmax + qn + t)); };
+
+    const int j0 = s * split_len;
+    const int j1 = min(n, j0 + split_len);
+    const int ntiles = (j1 > j0) ? (j1 - j0 + TX - 1) / TX : 0;
+    const int total = ntiles * nch;
+
+    // ---- rare path, only entered while the accumulators are dead (between two tiles) ----
+    float* const my_scratch =
+        reinterpret_cast<float*>(ci + TQ * C) + (size_t)wave * (2 * kWave + 2 * k);
+    // exact keys of cc candidates of query L (its buffer, or with from_range the points
+    // jbase ..), merged into its list; the lanes of the query get the new thresholds
+    auto flush_one = [&](int L, bool from_range, int jbase, int cc) {
+        const int r = wave_row0 + L;
+        const size_t lb = ((size_t)r * S + s) * k;
+        const uint64_t fr = split_flush_query<ALIGNED>(
+            Q + (int64_t)r * ldq, X, ldx, d, j0, from_range ? nullptr : wci + L * C, jbase, cc,
+            lk + lb, li + lb, k, my_scratch, tsh + r, lane);
+        if (i32 == L) {
+            own = __uint_as_float((unsigned)fr);
+            cap = fminf(cap, __uint_as_float((unsigned)(fr >> 32)));
+            tauf = key_bound(fminf(own, cap));
+            if (!from_range) cnt = 0;
+        }
+    };
+    // After a tile: buffers with fewer than kSpRoom free slots are emptied; a query whose
+    // buffer could not take all of the tile's candidates (ovf; the part it took was dropped
+    // again) gets every point of the tile tested instead.
+    auto drain = [&](int tile_base, bool everything) {
+        uint64_t full =
+            __builtin_amdgcn_ballot_w64(cnt > 0 && (everything || ovf || cnt > C - kSpRoom)) &
+            0xffffffffull;
+        while (full) {
+            const int L = __builtin_ctzll(full);
+            full &= full - 1;
+            flush_one(L, false, 0, __builtin_amdgcn_readlane(cnt, L));
+        }
+        uint64_t redo = __builtin_amdgcn_ballot_w64(ovf != 0) & 0xffffffffull;
+        while (redo) {
+            const int L = __builtin_ctzll(redo);
+            redo &= redo - 1;
+            for (int b = 0; b < 4; ++b) {
+                const int base = tile_base + 32 * b;
+                const int cc = min(32, j1 - base);
+                if (cc > 0) flush_one(L, true, base, cc);
+            }
+        }
+        ovf = 0;
+    };
+
+    // End of a tile, accumulators still live, no calls: keys below the filter threshold are
+    // buffered (point index only; the two halves of the wave take consecutive slots).
+    // Register e of a lane of half h holds point row 8 (e / 4) + 4 h + e % 4 of its block.
+    auto epilogue = [&](const f32x16 (&a)[4], int tile_base) {
+        float m = kInf;
+#pragma unroll
+        for (int pb = 0; pb < 4; ++pb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) m = fminf(m, a[pb][e]);
+        if (__builtin_amdgcn_ballot_w64(m < tauf) == 0) return;
+        const int cnt0 = cnt;
+#pragma unroll
+        for (int pb = 0; pb < 4; ++pb) {
+            int mine = 0;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) mine += (a[pb][e] < tauf) ? 1 : 0;
+            if (__builtin_amdgcn_ballot_w64(mine > 0) == 0) continue;
+            const int oth = lane_xor<32>(mine);
+            if (cnt + mine + oth > C) ovf = 1;  // the same in both halves of the wave
+            if (!ovf) {
+                int slot = i32 * C + cnt + (h ? oth : 0);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    if (a[pb][e] < tauf) {
+                        wci[slot] = tile_base + pb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
+                        ++slot;
+                    }
+                }
+                cnt += mine + oth;
+            }
+        }
+        if (ovf) cnt = cnt0;
+    };
+
+    // staging of the points: thread -> (row = tid / 4, coordinates 4 (tid % 4) .. + 3 of the chunk)
+    const int srow = tid >> 2;
+    const int squad = tid & 3;
+    struct XS {
+        f32x4 x0;
+        float xnv;
+    };
+    struct BS_ {
+        uint4 hi, lo;
+    };
+    int f_tile = 0, f_c = 0;  // (tile, chunk) of the next fetch
+    const float* frow = X + (int64_t)min(j0 + srow, j1 - 1) * ldx;  // this thread's row of tile f_tile
+    auto fetchX = [&](XS& g) {
+        g.x0 = load_row4<ALIGNED>(frow, 0, 0, 1, f_c * 16 + squad * 4, d);
+        if (f_c == 0) g.xnv = xn[min(j0 + f_tile * TX + (tid & (TX - 1)), j1 - 1)];
+        if (++f_c == nch) {
+            f_c = 0;
+            if (f_tile + 1 < ntiles) ++f_tile;
+            frow = X + (int64_t)min(j0 + f_tile * TX + srow, j1 - 1) * ldx;
+        }
+    };
+    int s_tile = 0, s_c = 0;  // (tile, chunk) of the next stash
+    uint2* const as_w = reinterpret_cast<uint2*>(as) + srow * 4 + squad;
+    auto stash = [&](int buf, const XS& g) {
+        uint2 hi, lo;
+        split_pair(g.x0[0], g.x0[1], 1.f, hi.x, lo.x);
+        split_pair(g.x0[2], g.x0[3], 1.f, hi.y, lo.y);
+        as_w[(buf * 2 + 0) * TX * 4] = hi;
+        as_w[(buf * 2 + 1) * TX * 4] = lo;
+        if (s_c == 0 && tid < TX)  // +inf past the range: such a row never passes
+            xns[(s_tile & 1) * TX + tid] = (j0 + s_tile * TX + tid < j1) ? g.xnv : kInf;
+        if (++s_c == nch) {
+            s_c = 0;
+            ++s_tile;
+        }
+    };
+    auto fetchQ = [&](int c, BS_& g) {
+        g.hi = qb[c * 4];
+        g.lo = qb[c * 4 + 2];
+    };
+
+    f32x16 acc[4];
+    // accumulators of a tile start from the norms of its points
+    auto start_tile = [&](int t) {
+        const float* xt = xns + (t & 1) * TX;
+#pragma unroll
+        for (int pb = 0; pb < 4; ++pb) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(xt + pb * 32 + g * 8 + h * 4);
+                acc[pb][g * 4 + 0] = v[0];
+                acc[pb][g * 4 + 1] = v[1];
+                acc[pb][g * 4 + 2] = v[2];
+                acc[pb][g * 4 + 3] = v[3];
+            }
+        }
+    };
+    XS xe, xo;
+    BS_ be, bo;
+    xe.xnv = xo.xnv = 0.f;
+    if (total > 0) {
+        fetchX(xe);
+        stash(0, xe);
+        fetchX(xo);
+        fetchQ(0, be);
+    }
+    __syncthreads();
+    if (total > 0) start_tile(0);
+    int tile = 0, c = 0;
+    const uint4* const as_r = as + i32 * 2 + h;
+    auto body = [&](int step, int par, XS& mine, const XS& next, const BS_& bcur, BS_& bnext) {
+        fetchQ(c + 1 == nch ? 0 : c + 1, bnext);
+        fetchX(mine);
+        const uint4* ab = as_r + par * (2 * TX * 2);
+        const bf16x8 bh = __builtin_bit_cast(bf16x8, bcur.hi);
+        const bf16x8 bl = __builtin_bit_cast(bf16x8, bcur.lo);
+#pragma unroll
+        for (int pb = 0; pb < 4; ++pb) {
+            const bf16x8 xh = __builtin_bit_cast(bf16x8, ab[pb * 64]);
+            const bf16x8 xl = __builtin_bit_cast(bf16x8, ab[TX * 2 + pb * 64]);
+            acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, bh, acc[pb], 0, 0, 0);
+            acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, bl, acc[pb], 0, 0, 0);
+            acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, bh, acc[pb], 0, 0, 0);
+            if (pb == 1 && step + 1 < total) stash(par ^ 1, next);
+        }
+        if (c == nch - 1) {
+            // The last use of this tile's accumulators is the epilogue; they are set again
+            // right after the barrier of this branch, so nothing of them is live across the
+            // calls in drain().
+            const int tile_base = j0 + tile * TX;
+            // what the other ranges of the query have reached since the last look
+            cap = fminf(cap, __uint_as_float(tsh[qrow]));
+            tauf = key_bound(fminf(own, cap));
+            epilogue(acc, tile_base);
+            if (__builtin_amdgcn_ballot_w64(ovf != 0 || cnt > C - kSpRoom) != 0)
+                drain(tile_base, false);
+            c = 0;
+            ++tile;
+            __syncthreads();
+            if (step + 1 < total) start_tile(tile);
+        } else {
+            ++c;
+            __syncthreads();
+        }
+    };
+    for (int step = 0; step < total; step += 2) {
+        body(step, 0, xe, xo, be, bo);
+        if (step + 1 < total) body(step + 1, 1, xo, xe, bo, be);
+    }
+    drain(0, true);
+}
+
+__global__ void knn_fill_words_kernel(unsigned* __restrict__ p, int64_t count, unsigned value) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) p[i] = value;
+}
+
+}  // namespace
+
+hipError_t launch_max_norm(const float* xn, int64_t n, void* hdr, hipStream_t stream) {
+    unsigned* w = static_cast<unsigned*>(hdr);
+    knn_split_init_kernel<<<dim3(1), dim3(64), 0, stream>>>(w);
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    knn_max_norm_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(xn, n, w);
+    return hipGetLastError();
+}
+
+hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d, void* qs,
+                                void* tsh, hipStream_t stream) {
+    const int nch = (d + kSpKC - 1) / kSpKC;
+    knn_fill_words_kernel<<<dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream>>>(
+        static_cast<unsigned*>(tsh), rows, 0x7f800000u);  // +inf: nothing published yet
+    const int64_t items = rows * nch;
+    const bool aligned = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) && (ldq % 4 == 0) && (d % 4 == 0);
+    const dim3 grid((unsigned)((items + 255) / 256));
+    if (aligned)
+        knn_split_queries_kernel<true><<<grid, dim3(256), 0, stream>>>(Q, ldq, (int)rows, d, nch,
+                                                                       static_cast<uint4*>(qs));
+    else
+        knn_split_queries_kernel<false><<<grid, dim3(256), 0, stream>>>(Q, ldq, (int)rows, d, nch,
+                                                                        static_cast<uint4*>(qs));
+    return hipGetLastError();
+}
+
+hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* qs,
+                        const float* qn, void* tsh, const float* xn, const void* hdr, int64_t rows,
+                        int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream) {
+    const int nch = (d + kSpKC - 1) / kSpKC;
+    const size_t lds = (size_t)2 * 2 * kSpTileX * 2 * 16 + (size_t)2 * kSpTileX * 4 +
+                       (size_t)kSpTileQ * kSpCand * 4 + (size_t)kSpWaves * (2 * kWave + 2 * k) * 4;
+    int64_t split_len = (n + S - 1) / S;
+    split_len = (split_len + kSpTileX - 1) / kSpTileX * kSpTileX;
+    // One workgroup per compute unit is resident, so the (tile, range) pairs go to the 8 XCDs
+    // round-robin (block shape 1 x 1 of the mapping): consecutive query tiles of one range land
+    // on every XCD in turn, each XCD holds at most one pair more than another, and the
+    // workgroups that share an XCD's L2 mostly walk the same range of points.
+    const int T = (int)((rows + kSpTileQ - 1) / kSpTileQ);
+    const int BQ = 1, BS = 1;
+    const int blocks = T * S;
+    const dim3 grid((unsigned)((blocks + 7) / 8 * 8));
+    const bool aligned = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldq % 4 == 0) &&
+                         (ldx % 4 == 0) && (d % 4 == 0);
+    hipError_t e;
+    if (aligned) {
+        e = raise_lds_limit(knn_split_kernel<true>, lds);
+        if (e != hipSuccess) return e;
+        knn_split_kernel<true><<<grid, dim3(64 * kSpWaves), lds, stream>>>(
+            Q, ldq, X, ldx, static_cast<const uint4*>(qs), qn, static_cast<unsigned*>(tsh), xn,
+            static_cast<const unsigned*>(hdr),
+            (int)rows, (int)n, d, nch, k, S, (int)split_len, BQ, BS, lk, li);
+    } else {
+        e = raise_lds_limit(knn_split_kernel<false>, lds);
+        if (e != hipSuccess) return e;
+        knn_split_kernel<false><<<grid, dim3(64 * kSpWaves), lds, stream>>>(
+            Q, ldq, X, ldx, static_cast<const uint4*>(qs), qn, static_cast<unsigned*>(tsh), xn,
+            static_cast<const unsigned*>(hdr),
+            (int)rows, (int)n, d, nch, k, S, (int)split_len, BQ, BS, lk, li);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace knn

@@ -71,11 +71,26 @@ uint64_t lists_bytes_for(uint64_t rows, uint64_t S, uint64_t k) {
     return 2 * align_up(rows * S * k * 4);
 }
 
-// largest row count whose lists fit in `avail` bytes with S ranges
-int64_t rows_fitting(uint64_t avail, uint64_t S, uint64_t k) {
-    // 2 * align_up(x) <= avail  <=>  x <= floor(floor(avail / 2) / kAlign) * kAlign
-    uint64_t usable = avail / 2 / kAlign * kAlign;
-    return knn_chunk_rows(usable, S * k * 4);
+// per-query data of a chunk besides its lists.  Path 5: the queries' split B operands
+// (qrow = 64 bytes per 16 coordinates), their squared norms and the thresholds their point
+// ranges share (a word each); other paths: nothing.
+uint64_t query_bytes_for(uint64_t rows, uint64_t qrow) {
+    return qrow ? align_up(rows * qrow) + 2 * align_up(rows * 4) : 0;
+}
+
+// largest row count whose lists (S ranges) and per-query data fit in `avail` bytes
+int64_t rows_fitting(uint64_t avail, uint64_t S, uint64_t k, uint64_t qrow) {
+    if (!qrow) {
+        // 2 * align_up(x) <= avail  <=>  x <= floor(floor(avail / 2) / kAlign) * kAlign
+        uint64_t usable = avail / 2 / kAlign * kAlign;
+        return knn_chunk_rows(usable, S * k * 4);
+    }
+    auto need = [&](uint64_t rows) { return lists_bytes_for(rows, S, k) + query_bytes_for(rows, qrow); };
+    const uint64_t per_row = 2 * S * k * 4 + qrow + 8;
+    // the five roundings add less than 5 * kAlign: start below the answer, then step up to it
+    uint64_t rows = avail > 5 * kAlign ? (avail - 5 * kAlign) / per_row : 0;
+    while (need(rows + 1) <= avail) ++rows;
+    return (int64_t)rows;
 }
 
 }  // namespace
@@ -103,16 +118,23 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     // the cosine keys come from the matrix-core kernels only
     // (lowd also stands for the L1 kernel: same workgroup shape, no per-point workspace)
     const bool lowd = (d <= kLowdMaxD && metric == KNN_METRIC_L2SQ) || metric == KNN_METRIC_L1;
-    // smallest plan of all: the vector-ALU path (no per-point workspace) or the MFMA path
-    out->path = metric == KNN_METRIC_L1 ? KNN_PATH_L1 : (lowd ? KNN_PATH_LOWD : KNN_PATH_MFMA);
-    out->tile_q = lowd ? kLowdTileQ : kMfmaTileQ;
+    // d > 8, squared-Euclidean: the bf16 filter on split values + exact test; the fp32 MFMA
+    // path serves the cosine metric
+    const bool split = !lowd && metric == KNN_METRIC_L2SQ;
+    // smallest plan of all: the vector-ALU path (no per-point workspace) or a matrix-core path
+    out->path = metric == KNN_METRIC_L1 ? KNN_PATH_L1
+                : lowd                  ? KNN_PATH_LOWD
+                : split                 ? KNN_PATH_MFMA_SPLIT
+                                        : KNN_PATH_MFMA;
+    out->tile_q = lowd ? kLowdTileQ : (split ? kSpTileQ : kMfmaTileQ);
     out->tile_x = lowd ? kLowdUnroll : kMfmaTileX;
-    out->norms_bytes = lowd ? 0 : align_up((uint64_t)n * 4);
+    out->norms_bytes = lowd ? 0 : align_up((uint64_t)n * 4) + (split ? kAlign : 0);
+    const uint64_t qrow = split ? 64ull * (((uint64_t)d + kSpKC - 1) / kSpKC) : 0;
     {
         const int64_t t0 = out->tile_q;
         const int64_t min_rows = m < t0 ? (m > 0 ? m : 1) : t0;
-        out->min_limit_bytes =
-            out->norms_bytes + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k);
+        out->min_limit_bytes = out->norms_bytes + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k) +
+                               query_bytes_for((uint64_t)min_rows, qrow);
     }
     if (m == 0) return KNN_OK;
     if (mem_limit_bytes < out->min_limit_bytes) return KNN_ERR_MEM_LIMIT_TOO_SMALL;
@@ -169,11 +191,12 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     int64_t s_max = n / kMinSplitPoints;
     if (s_max < 1) s_max = 1;
     if (s_max > kMaxSplits) s_max = kMaxSplits;
-    const int64_t slots = lowd ? kLowdResidentWorkgroups : kMfmaResidentWorkgroups;
+    const int64_t slots = lowd ? kLowdResidentWorkgroups
+                               : (split ? kSpResidentWorkgroups : kMfmaResidentWorkgroups);
     int64_t best_s = 0, best_rows = 0;
     double best_cost = 0.0;
     for (int64_t S = 1; S <= s_max; S = (S < 8 ? S + 1 : S + 8)) {
-        int64_t rows = rows_fitting(avail, (uint64_t)S, (uint64_t)k);
+        int64_t rows = rows_fitting(avail, (uint64_t)S, (uint64_t)k, qrow);
         if (rows > kMaxChunkRows) rows = kMaxChunkRows;
         if (rows >= m) rows = m;
         else rows = rows / tile * tile;
@@ -205,7 +228,8 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     out->chunk_rows = best_rows;
     out->q_chunks = (m + best_rows - 1) / best_rows;
     out->lists_bytes = lists_bytes_for((uint64_t)best_rows, (uint64_t)best_s, (uint64_t)k);
-    out->workspace_bytes = out->norms_bytes + out->lists_bytes;
+    out->query_bytes = query_bytes_for((uint64_t)best_rows, qrow);
+    out->workspace_bytes = out->norms_bytes + out->query_bytes + out->lists_bytes;
     if (out->path == KNN_PATH_MFMA && d <= kMfmaKC * kMfmaQregMaxChunks) {
         // spare room under the limit buys a blocked copy of the points (contiguous 8 KB blocks
         // in the order the kernel streams them); it never costs a query chunk

@@ -78,9 +78,9 @@ CONFIGS = [
 def test_every_baseline_config_has_a_plan_under_its_limit(m, n, d, k, limit):
     p = K.knn_plan(m, n, d, k, limit)
     assert p.workspace_bytes <= limit
-    assert p.workspace_bytes == p.norms_bytes + p.lists_bytes
+    assert p.workspace_bytes == p.norms_bytes + p.query_bytes + p.lists_bytes
     # d <= 3 with room for the packed points takes the matrix-core filter path
-    want = K.KNN_PATH_LOWD_BF16 if d <= 8 else K.KNN_PATH_MFMA
+    want = K.KNN_PATH_LOWD_BF16 if d <= 8 else K.KNN_PATH_MFMA_SPLIT
     assert p.path == want
     assert p.q_chunks * p.chunk_rows >= m
     assert p.chunk_rows == m or p.chunk_rows % p.tile_q == 0
@@ -104,14 +104,14 @@ def test_min_limit_is_exact_boundary():
 def test_small_limits_cut_queries_into_chunks_and_never_exceed_the_limit():
     m, n, d, k = 50_000, 2_000_000, 256, 32
     prev_chunks = None
-    for limit in [8_100_000, 8_500_000, 9_000_000, 12_000_000, 20_000_000, 50_000_000, 128_000_000, 10 ** 9]:
+    for limit in [8_400_000, 8_700_000, 9_000_000, 12_000_000, 20_000_000, 50_000_000, 128_000_000, 10 ** 9]:
         p = K.knn_plan(m, n, d, k, limit)
         assert p.workspace_bytes <= limit
         assert p.chunk_rows >= p.tile_q or p.chunk_rows == m
         if prev_chunks is not None:
             assert p.q_chunks <= prev_chunks  # more memory never means more passes
         prev_chunks = p.q_chunks
-    assert K.knn_plan(m, n, d, k, 8_100_000).q_chunks > 1
+    assert K.knn_plan(m, n, d, k, 8_400_000).q_chunks > 1
 
 
 def test_low_d_falls_back_to_the_vector_path_when_packed_points_do_not_fit():
@@ -129,7 +129,8 @@ def test_low_d_falls_back_to_the_vector_path_when_packed_points_do_not_fit():
     assert K.knn_plan(m, n, 8, k, 10 ** 9).path == K.KNN_PATH_LOWD_BF16
     assert K.knn_plan(m, n, 8, k, 10 ** 9).norms_bytes == 256 + 64 * n
     assert K.knn_plan(m, n, 8, k, 60 * 10 ** 6).path == K.KNN_PATH_LOWD
-    assert K.knn_plan(m, n, 9, k, 10 ** 9).path == K.KNN_PATH_MFMA
+    assert K.knn_plan(m, n, 9, k, 10 ** 9).path == K.KNN_PATH_MFMA_SPLIT
+    assert K.knn_plan(m, n, 9, k, 10 ** 9, metric="cosine").path == K.KNN_PATH_MFMA
 
 
 def test_threshold_seed_grid_is_sized_from_n_and_k_and_paid_for_under_the_limit():
