@@ -154,7 +154,7 @@ __device__ __noinline__ uint64_t split_flush_query(const float* __restrict__ qp,
                                                    int jsafe, const int* __restrict__ cbuf, int jbase,
                                                    int cc,
                                                    float* __restrict__ gk, int* __restrict__ gi, int k,
-                                                   float* scratch, unsigned* __restrict__ tshr,
+                                                   float* scratch, unsigned* tshr,
                                                    int lane) {
     MergeScratch sc;
     sc.cand_key = scratch;
@@ -203,12 +203,23 @@ __device__ __noinline__ uint64_t split_flush_query(const float* __restrict__ qp,
 // not enter any list.  The lists of a range then hold the range's best entries only as far as
 // they can matter; the merged result is the same.
 // ---------------------------------------------------------------------------------------
-template <bool ALIGNED>
+//
+// NCH > 0 (d <= 16 NCH <= 128): the B operands of all NCH chunks stay in registers for the whole
+// kernel, so only the points are streamed; the chunk loop is unrolled (with a second tile when
+// NCH is odd, so that the alternation of the two buffers is static).  NCH == 0: any d, the B
+// operands of the next chunk are fetched from the workspace in every step; that doubles to
+// triples the traffic (bytes per pair and coordinate: 4 / 256 for the points, 4 / 128 for the
+// queries), which is what bounds the kernel there.
+template <int NCH, bool ALIGNED>
 __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
-    const uint4* __restrict__ Qs, const float* __restrict__ qnorm, unsigned* __restrict__ tsh,
-    const float* __restrict__ xn, const unsigned* __restrict__ hdr, int rows, int n, int d, int nch,
-    int k, int S, int split_len, int BQ, int BS, float* __restrict__ lk, int* __restrict__ li) {
+    const uint4* __restrict__ Qs, const float* __restrict__ qnorm, unsigned* tsh,
+    const float* __restrict__ xn, const unsigned* __restrict__ hdr, int rows, int n, int d,
+    int nch_real, int k, int S, int split_len, int BQ, int BS, float* __restrict__ lk,
+    int* __restrict__ li) {
+    // chunks per tile that the pipeline walks: all of NCH when the queries are resident (the
+    // ones past the real count meet zero B operands)
+    const int nch = NCH > 0 ? NCH : nch_real;
     constexpr int TQ = kSpTileQ, TX = kSpTileX, C = kSpCand;
     extern __shared__ __align__(16) unsigned char smem[];
     uint4* as = reinterpret_cast<uint4*>(smem);                  // [2 buffers][2 pieces][TX][2]
@@ -247,8 +258,9 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     float cap = kInf;
     float tauf = own;
     int cnt = 0, ovf = 0;
-    const uint4* const qb = Qs + (size_t)qrow * nch * 4 + h;
-    auto key_bound = [&](float t) { return (t - qn) + (cross + e_sum * (xmax + qn + t)); };
+    const uint4* const qb = Qs + (size_t)qrow * nch_real * 4 + h;
+    // (the smallest normal number keeps the bound strict when every value involved is zero)
+    auto key_bound = [&](float t) { return (t - qn) + (cross + e_sum * (xmax + qn + t) + 0x1p-126f); };
 
     const int j0 = s * split_len;
     const int j1 = min(n, j0 + split_len);
@@ -390,24 +402,24 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
         }
     };
     XS xe, xo;
-    BS_ be, bo;
     xe.xnv = xo.xnv = 0.f;
     if (total > 0) {
         fetchX(xe);
         stash(0, xe);
         fetchX(xo);
-        fetchQ(0, be);
     }
     __syncthreads();
     if (total > 0) start_tile(0);
-    int tile = 0, c = 0;
+    int tile = 0;
     const uint4* const as_r = as + i32 * 2 + h;
-    auto body = [&](int step, int par, XS& mine, const XS& next, const BS_& bcur, BS_& bnext) {
-        fetchQ(c + 1 == nch ? 0 : c + 1, bnext);
+    // one (tile, chunk) step: MFMAs on LDS buffer `par` with the given B operands, the next
+    // step's points go to the other buffer meanwhile; last = the tile's last chunk
+    auto step_fn = [&](int step, int par, bool last, const uint4& bhi, const uint4& blo, XS& mine,
+                       const XS& next) {
         fetchX(mine);
         const uint4* ab = as_r + par * (2 * TX * 2);
-        const bf16x8 bh = __builtin_bit_cast(bf16x8, bcur.hi);
-        const bf16x8 bl = __builtin_bit_cast(bf16x8, bcur.lo);
+        const bf16x8 bh = __builtin_bit_cast(bf16x8, bhi);
+        const bf16x8 bl = __builtin_bit_cast(bf16x8, blo);
 #pragma unroll
         for (int pb = 0; pb < 4; ++pb) {
             const bf16x8 xh = __builtin_bit_cast(bf16x8, ab[pb * 64]);
@@ -417,29 +429,65 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
             acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, bh, acc[pb], 0, 0, 0);
             if (pb == 1 && step + 1 < total) stash(par ^ 1, next);
         }
-        if (c == nch - 1) {
+        if (last) {
             // The last use of this tile's accumulators is the epilogue; they are set again
             // right after the barrier of this branch, so nothing of them is live across the
             // calls in drain().
             const int tile_base = j0 + tile * TX;
             // what the other ranges of the query have reached since the last look
-            cap = fminf(cap, __uint_as_float(tsh[qrow]));
+            cap = fminf(cap, __uint_as_float(__hip_atomic_load(tsh + qrow, __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT)));
             tauf = key_bound(fminf(own, cap));
             epilogue(acc, tile_base);
             if (__builtin_amdgcn_ballot_w64(ovf != 0 || cnt > C - kSpRoom) != 0)
                 drain(tile_base, false);
-            c = 0;
             ++tile;
             __syncthreads();
             if (step + 1 < total) start_tile(tile);
         } else {
-            ++c;
             __syncthreads();
         }
     };
-    for (int step = 0; step < total; step += 2) {
-        body(step, 0, xe, xo, be, bo);
-        if (step + 1 < total) body(step + 1, 1, xo, xe, bo, be);
+    if constexpr (NCH == 0) {
+        BS_ be, bo;
+        if (total > 0) fetchQ(0, be);
+        int c = 0;
+        auto body = [&](int step, int par, XS& mine, const XS& next, const BS_& bcur, BS_& bnext) {
+            fetchQ(c + 1 == nch ? 0 : c + 1, bnext);
+            const bool last = c == nch - 1;
+            c = last ? 0 : c + 1;
+            step_fn(step, par, last, bcur.hi, bcur.lo, mine, next);
+        };
+        for (int step = 0; step < total; step += 2) {
+            body(step, 0, xe, xo, be, bo);
+            if (step + 1 < total) body(step + 1, 1, xo, xe, bo, be);
+        }
+    } else {
+        constexpr int NR = NCH > 0 ? NCH : 1;
+        uint4 bqh[NR], bql[NR];
+#pragma unroll
+        for (int c = 0; c < NR; ++c) {
+            const uint4 zero = {0u, 0u, 0u, 0u};
+            bqh[c] = c < nch_real ? qb[(c < nch_real ? c : 0) * 4] : zero;
+            bql[c] = c < nch_real ? qb[(c < nch_real ? c : 0) * 4 + 2] : zero;
+        }
+        constexpr int TU = (NR % 2) ? 2 : 1;  // tiles per unrolled iteration
+        for (int tile0 = 0; tile0 < ntiles; tile0 += TU) {
+#pragma unroll
+            for (int tt = 0; tt < TU; ++tt) {
+                if (tile0 + tt >= ntiles) break;  // uniform
+#pragma unroll
+                for (int c = 0; c < NR; ++c) {
+                    const int step = (tile0 + tt) * NR + c;
+                    constexpr int dummy = 0;
+                    (void)dummy;
+                    if (((tt * NR + c) & 1) == 0)
+                        step_fn(step, 0, c == NR - 1, bqh[c], bql[c], xe, xo);
+                    else
+                        step_fn(step, 1, c == NR - 1, bqh[c], bql[c], xo, xe);
+                }
+            }
+        }
     }
     drain(0, true);
 }
@@ -496,22 +544,31 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
     const bool aligned = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldq % 4 == 0) &&
                          (ldx % 4 == 0) && (d % 4 == 0);
-    hipError_t e;
-    if (aligned) {
-        e = raise_lds_limit(knn_split_kernel<true>, lds);
-        if (e != hipSuccess) return e;
-        knn_split_kernel<true><<<grid, dim3(64 * kSpWaves), lds, stream>>>(
-            Q, ldq, X, ldx, static_cast<const uint4*>(qs), qn, static_cast<unsigned*>(tsh), xn,
-            static_cast<const unsigned*>(hdr),
-            (int)rows, (int)n, d, nch, k, S, (int)split_len, BQ, BS, lk, li);
-    } else {
-        e = raise_lds_limit(knn_split_kernel<false>, lds);
-        if (e != hipSuccess) return e;
-        knn_split_kernel<false><<<grid, dim3(64 * kSpWaves), lds, stream>>>(
-            Q, ldq, X, ldx, static_cast<const uint4*>(qs), qn, static_cast<unsigned*>(tsh), xn,
-            static_cast<const unsigned*>(hdr),
-            (int)rows, (int)n, d, nch, k, S, (int)split_len, BQ, BS, lk, li);
-    }
+#define KNN_SPLIT_LAUNCH_A(N, A)                                                                  \
+    do {                                                                                          \
+        hipError_t e2 = raise_lds_limit(knn_split_kernel<N, A>, lds);                             \
+        if (e2 != hipSuccess) return e2;                                                          \
+        knn_split_kernel<N, A><<<grid, dim3(64 * kSpWaves), lds, stream>>>(                       \
+            Q, ldq, X, ldx, static_cast<const uint4*>(qs), qn, static_cast<unsigned*>(tsh), xn,   \
+            static_cast<const unsigned*>(hdr), (int)rows, (int)n, d, nch, k, S, (int)split_len,   \
+            BQ, BS, lk, li);                                                                      \
+    } while (0)
+#define KNN_SPLIT_LAUNCH(N)                                                                       \
+    do {                                                                                          \
+        if (aligned) KNN_SPLIT_LAUNCH_A(N, true);                                                 \
+        else KNN_SPLIT_LAUNCH_A(N, false);                                                        \
+    } while (0)
+    // queries resident in registers up to d = 128 (the template value is the chunk count
+    // rounded up to one that is instantiated)
+    if (nch <= 1) KNN_SPLIT_LAUNCH(1);
+    else if (nch <= 2) KNN_SPLIT_LAUNCH(2);
+    else if (nch <= 3) KNN_SPLIT_LAUNCH(3);
+    else if (nch <= 4) KNN_SPLIT_LAUNCH(4);
+    else if (nch <= 6) KNN_SPLIT_LAUNCH(6);
+    else if (nch <= kSpResidentMaxChunks) KNN_SPLIT_LAUNCH(8);
+    else KNN_SPLIT_LAUNCH(0);
+#undef KNN_SPLIT_LAUNCH
+#undef KNN_SPLIT_LAUNCH_A
     return hipGetLastError();
 }
 

@@ -480,6 +480,62 @@ def test_threshold_seed_with_several_point_ranges_and_query_chunks(K, oracle):
     parity(K, oracle, Q2, X2, k, tight)
 
 
+def test_split_path_identical_points_break_ties_by_index_across_ranges(K, oracle):
+    # every distance of a query is the same number: the result is the k lowest indices, also
+    # when the ranges that hold the higher indices publish their thresholds first; all-zero data
+    # is the case in which every error allowance of the filter is zero as well
+    for value in (0.0, 0.75):
+        X = np.full((40_000, 20), value, np.float32)
+        Q = np.full((70, 20), value, np.float32)
+        Q[35:] += np.float32(0.5)
+        k = 9
+        plan = K.knn_plan(70, 40_000, 20, k, 64 * W.MB)
+        assert plan.path == K.KNN_PATH_MFMA_SPLIT and plan.n_splits > 1
+        idx, dist = run_gpu(K, Q, X, k, 64 * W.MB)
+        assert np.array_equal(idx, np.tile(np.arange(k, dtype=np.int32), (70, 1))), value
+        o_idx, o_dist, _ = oracle.knn(Q, X, k)
+        assert np.array_equal(idx, o_idx)
+        assert np.allclose(dist, o_dist, rtol=1e-6, atol=0)
+
+
+@pytest.mark.parametrize("d,ld", [(13, 13), (24, 28), (50, 50), (100, 101)])
+def test_split_path_points_in_decreasing_distance_order(K, oracle, d, ld):
+    # the worst order for a running top-k: every point beats the current k-th best, so every
+    # tile overflows the candidate buffers and takes the test-everything route
+    g = np.random.Generator(np.random.PCG64(W.SEED_BASE + 14_000_000 + d))
+    n, m, k = 6000, 300, 12
+    X = g.standard_normal((n, d)).astype(np.float32)
+    X = X[np.argsort(-np.einsum("ij,ij->i", X.astype(np.float64), X.astype(np.float64)))]
+    Q = (0.01 * g.standard_normal((m, d))).astype(np.float32)
+    Xp = np.zeros((n, ld), np.float32)
+    Xp[:, :d] = X
+    Qp = np.zeros((m, ld), np.float32)
+    Qp[:, :d] = Q
+    Xd, Qd = torch.from_numpy(Xp).cuda()[:, :d], torch.from_numpy(Qp).cuda()[:, :d]
+    assert K.knn_plan(m, n, d, k, 64 * W.MB).path == K.KNN_PATH_MFMA_SPLIT
+    idx, dist = K.knn_search(Qd, Xd, k, 64 * W.MB)
+    torch.cuda.synchronize()
+    o_idx, o_dist, o_next = oracle.knn(Q, X, k)
+    say("   ", d, ld, check(idx.cpu().numpy(), dist.cpu().numpy(), o_idx, o_dist, o_next, n))
+
+
+def test_split_path_far_from_the_origin_and_exact_integer_ties(K, oracle):
+    # an offset of 100 per coordinate makes the filter's allowance larger than the neighbour
+    # distances (it passes far more than it needs to); integer coordinates give dozens of exact
+    # ties at the k-th distance, decided by index
+    g = np.random.Generator(np.random.PCG64(W.SEED_BASE + 14_100_000))
+    X = (100.0 + g.uniform(0, 1, size=(20_000, 32))).astype(np.float32)
+    Q = (100.0 + g.uniform(0, 1, size=(260, 32))).astype(np.float32)
+    parity(K, oracle, Q, X, 10)
+    Xi = g.integers(0, 3, size=(30_000, 12)).astype(np.float32)
+    Qi = g.integers(0, 3, size=(400, 12)).astype(np.float32)
+    o_idx, o_dist, _ = oracle.knn(Qi, Xi, 25)
+    for limit in (64 * W.MB, 2 * W.MB):
+        idx, dist = run_gpu(K, Qi, Xi, 25, limit)
+        assert np.array_equal(idx, o_idx), limit
+        assert np.array_equal(dist.astype(np.float64), o_dist), limit
+
+
 def test_seeded_random_shapes_and_limits(K, oracle):
     # a seeded sweep over shapes, k, metrics and limits (from the smallest feasible one up):
     # whatever plan comes out - path, chunks, ranges - the result passes the parity rule
