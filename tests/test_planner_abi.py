@@ -158,6 +158,40 @@ def test_threshold_seed_grid_is_sized_from_n_and_k_and_paid_for_under_the_limit(
     assert full.seed_cells == 32 and full.workspace_bytes <= packed + tile_lists + 4 * 32 ** 3
 
 
+def test_split_path_accounts_for_the_per_query_data_and_uses_every_byte_it_can():
+    # path 5 (d > 8, squared-Euclidean): per query 64 bytes per 16 coordinates of split B
+    # operands, a squared norm and a shared-threshold word, each array 256-aligned; the chunk is
+    # the longest multiple of the query tile that fits with them
+    import random
+    rnd = random.Random(20240611)
+
+    def up(v):
+        return (v + 255) // 256 * 256
+
+    for _ in range(300):
+        d = rnd.choice([9, 16, 17, 100, 128, 129, 256, 784, 2000])
+        k = rnd.choice([1, 7, 32, 100, 1024])
+        n = rnd.randrange(k, 3_000_000)
+        m = rnd.choice([1, 255, 256, 257, 5000, 123_457])
+        lo = K.knn_plan(m, n, d, k, 1 << 44).min_limit_bytes
+        limit = lo + rnd.choice([0, 1, 255, 256, 4096, 10 ** 6, 10 ** 8, 10 ** 10])
+        p = K.knn_plan(m, n, d, k, limit)
+        assert p.path == K.KNN_PATH_MFMA_SPLIT and p.tile_q == 256
+        nch = (d + 15) // 16
+        assert p.norms_bytes == up(4 * n) + 256
+        assert p.query_bytes == up(p.chunk_rows * nch * 64) + 2 * up(p.chunk_rows * 4)
+        assert p.lists_bytes == 2 * up(p.chunk_rows * p.n_splits * k * 4)
+        assert p.workspace_bytes == p.norms_bytes + p.query_bytes + p.lists_bytes <= limit
+        assert p.chunk_rows == m or p.chunk_rows % 256 == 0
+        assert p.q_chunks == -(-m // p.chunk_rows)
+        if p.chunk_rows < m and p.chunk_rows < (1 << 22):  # a longer chunk would not have fitted
+            r = p.chunk_rows + 256
+            more = up(r * nch * 64) + 2 * up(r * 4) + 2 * up(r * p.n_splits * k * 4)
+            assert p.norms_bytes + more > limit
+        with pytest.raises(K.KnnError):
+            K.knn_plan(m, n, d, k, lo - 1)
+
+
 def test_plan_argument_errors():
     bad = [(-1, 10, 3, 1), (5, 0, 3, 1), (5, 10, 0, 1), (5, 10, 3, 0), (5, 10, 3, 11)]
     for m, n, d, k in bad:
