@@ -146,10 +146,9 @@ __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, con
 // the two partial sums are added; that order is part of the key's definition.  The keys are
 // merged into the query's list gk/gi, the list's k-th key is published in *tshr (atomic
 // minimum; keys are sums of squares, so as unsigned words they order like the floats, +inf
-// above all).  Returns the list's new k-th key (low word) and the lowest k-th key any range of
-// the query has published so far (high word), both as float bits.
+// above all).  Returns the list's new k-th key as float bits.
 template <bool ALIGNED>
-__device__ __noinline__ uint64_t split_flush_query(const float* __restrict__ qp,
+__device__ __noinline__ unsigned split_flush_query(const float* __restrict__ qp,
                                                    const float* __restrict__ X, int64_t ldx, int d,
                                                    int jsafe, const int* __restrict__ cbuf, int jbase,
                                                    int cc,
@@ -176,11 +175,8 @@ __device__ __noinline__ uint64_t split_flush_query(const float* __restrict__ qp,
     }
     const uint64_t mr = wave_merge_pair_inline(gk, gi, k, key, id, sc, lane, cc);
     const unsigned t_bits = (unsigned)mr;
-    unsigned seen = 0x7f800000u;
-    if (lane == 0) seen = atomicMin(tshr, t_bits);
-    seen = (unsigned)__builtin_amdgcn_readfirstlane((int)seen);
-    const unsigned low = seen < t_bits ? seen : t_bits;
-    return ((uint64_t)low << 32) | t_bits;
+    if (lane == 0) atomicMin(tshr, t_bits);  // no value returned: nothing waits for the round trip
+    return t_bits;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -275,12 +271,11 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     auto flush_one = [&](int L, bool from_range, int jbase, int cc) {
         const int r = wave_row0 + L;
         const size_t lb = ((size_t)r * S + s) * k;
-        const uint64_t fr = split_flush_query<ALIGNED>(
+        const unsigned fr = split_flush_query<ALIGNED>(
             Q + (int64_t)r * ldq, X, ldx, d, j0, from_range ? nullptr : wci + L * C, jbase, cc,
             lk + lb, li + lb, k, my_scratch, tsh + r, lane);
         if (i32 == L) {
-            own = __uint_as_float((unsigned)fr);
-            cap = fminf(cap, __uint_as_float((unsigned)(fr >> 32)));
+            own = __uint_as_float(fr);
             tauf = key_bound(fminf(own, cap));
             if (!from_range) cnt = 0;
         }
