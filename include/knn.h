@@ -140,7 +140,10 @@ uint64_t knn_workspace_bytes(int64_t m, int64_t n, int32_t d, int32_t k,
  *
  * Argument and plan errors are returned synchronously and leave the outputs
  * untouched.  The result does not depend on mem_limit_bytes: every limit that
- * admits a plan gives bit-identical idx and dist.
+ * admits a plan gives bit-identical idx and dist.  Nor does it depend on how
+ * the launch is scheduled: on path 5 the point ranges of a query tell each
+ * other their current k-th distance while they run, which changes how many
+ * pairs each of them looks at more closely, never which ones win.
  */
 knn_status knn_search(const float *Q, int64_t ldq, const float *X, int64_t ldx,
                       int64_t m, int64_t n, int32_t d, int32_t k,
