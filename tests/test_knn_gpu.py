@@ -536,6 +536,27 @@ def test_split_path_far_from_the_origin_and_exact_integer_ties(K, oracle):
         assert np.array_equal(dist.astype(np.float64), o_dist), limit
 
 
+def test_split_path_repeated_runs_with_many_ranges_give_the_same_bits(K, oracle):
+    # few queries, many point ranges that exchange thresholds while they run: which pairs a
+    # range looks at depends on timing, the result must not (near-duplicate points make ties
+    # and near-ties at the k-th place common)
+    g = np.random.Generator(np.random.PCG64(W.SEED_BASE + 14_200_000))
+    base = g.standard_normal((400, 40)).astype(np.float32)
+    X = np.repeat(base, 150, axis=0)
+    X += (1e-3 * g.integers(0, 3, size=X.shape)).astype(np.float32)
+    X = X[g.permutation(X.shape[0])]
+    Q = base[:90] + np.float32(1e-3)
+    k = 20
+    plan = K.knn_plan(90, X.shape[0], 40, k, 64 * W.MB)
+    assert plan.path == K.KNN_PATH_MFMA_SPLIT and plan.n_splits >= 8
+    first = run_gpu(K, Q, X, k, 64 * W.MB)
+    for _ in range(5):
+        again = run_gpu(K, Q, X, k, 64 * W.MB)
+        assert np.array_equal(first[0], again[0]) and np.array_equal(first[1], again[1])
+    o_idx, o_dist, o_next = oracle.knn(Q, X, k)
+    say("   ", check(first[0], first[1], o_idx, o_dist, o_next, X.shape[0]))
+
+
 def test_seeded_random_shapes_and_limits(K, oracle):
     # a seeded sweep over shapes, k, metrics and limits (from the smallest feasible one up):
     # whatever plan comes out - path, chunks, ranges - the result passes the parity rule
