@@ -372,7 +372,7 @@ def main() -> int:
     ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
     idx = torch.empty((w.m, w.k), dtype=torch.int32, device=dev)
     dist = torch.empty((w.m, w.k), dtype=torch.float32, device=dev)
-    path_name = {0: "lowd", 1: "mfma", 2: "lowd_mfma", 3: "l1", 4: "lowd_bf16", 5: "mfma_split"}[plan.path]
+    path_name = {0: "lowd", 2: "lowd_mfma", 3: "l1", 4: "lowd_bf16", 5: "mfma_split"}[plan.path]
     log(f"[bench] plan: path={path_name} chunks={plan.q_chunks} "
         f"ranges={plan.n_splits} workspace={plan.workspace_bytes} B (limit {limit} B)")
 
@@ -411,15 +411,7 @@ def main() -> int:
     pairs_per_launch = pairs * args.steps / max(launches, 1)
     traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
     hbm_equiv = (pairs_per_launch / avg_launch_s) * 8.0 / (PEAK_HBM_GBS * 1e9)
-    if plan.path == K.KNN_PATH_MFMA:
-        flops = 2.0 * w.d * pairs_per_launch  # the -2 Q X^T contraction
-        achieved = flops / avg_launch_s / 1e12
-        kernel = "knn_mfma_qreg_kernel" if w.d <= 256 else "knn_mfma_kernel"
-        roofline = {"bound": "mfma", "kernel": kernel, "achieved": achieved,
-                    "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / PEAK_FP32_MATRIX_TFLOPS, "traffic": traffic,
-                    "flops_per_pair": 2 * w.d}
-    elif plan.path == K.KNN_PATH_MFMA_SPLIT:
+    if plan.path == K.KNN_PATH_MFMA_SPLIT:
         # The -2 Q X^T contraction runs as three bf16 products per coordinate pair (values cut
         # into two bf16 pieces): 6 d bf16 flops per pair on the matrix cores, with d rounded
         # up to the 16 coordinates of a pipeline step, against the dense bf16 peak.
@@ -517,7 +509,7 @@ def main() -> int:
             dt = (time.perf_counter() - t0) / args.steps
             sweep.append({"mem_limit_bytes": lim, "workspace_bytes": p2.workspace_bytes,
                           "q_chunks": p2.q_chunks, "point_ranges": p2.n_splits,
-                          "x_blocked": bool(p2.x_blocked), "ms_per_step": dt * 1e3,
+                          "ms_per_step": dt * 1e3,
                           "pairs_per_s": pairs / dt,
                           "same_result": bool(torch.equal(i2, idx) and torch.equal(d2, dist))})
             log(f"[bench] sweep limit={lim}: {dt*1e3:.1f} ms, {pairs/dt:.3e} pairs/s, "
@@ -556,7 +548,6 @@ def main() -> int:
         "config": {"workload": w.name, "metric": w.metric, "m": w.m, "n": w.n, "d": w.d, "k": w.k,
                    "mem_limit_bytes": limit, "workspace_bytes": plan.workspace_bytes,
                    "q_chunks": plan.q_chunks, "point_ranges": plan.n_splits,
-                   "x_blocked": bool(plan.x_blocked),
                    "path": path_name},
         "kernel_ms_per_step": {"norms": norms_ms / args.steps, "search": search_ms / args.steps,
                                "merge_refine": refine_ms / args.steps},

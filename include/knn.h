@@ -55,17 +55,17 @@ typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1, KNN_METRIC_L1 = 2 } k
 
 /* kernel families (knn_plan_t.path) */
 #define KNN_PATH_LOWD 0 /* d <= 8: difference-form distances on the vector ALU  */
-#define KNN_PATH_MFMA 1 /* d  > 8, cosine metric: fp32 matrix-core tile of -2 Q X^T plus norms */
 #define KNN_PATH_L1 3   /* L1 metric: absolute differences on the vector ALU, any d   */
 #define KNN_PATH_LOWD_MFMA 2 /* d <= 3 and room for 16 n bytes of packed points:
                                 matrix-core filter + the same exact test as path 0 */
 #define KNN_PATH_LOWD_BF16 4 /* d <= 8 and room for 32 n bytes (d <= 4) or 64 n bytes: the filter
                                 in bf16 pieces on points moved by their bounding box's midpoint,
                                 same exact test */
-#define KNN_PATH_MFMA_SPLIT 5 /* d > 8, squared-Euclidean: every fp32 value cut into two bf16
-                                 pieces, -2 Q X^T plus norms from three bf16 matrix-core
-                                 products per coordinate as a filter, exact fp32
-                                 difference-form test of the pairs that pass */
+#define KNN_PATH_MFMA_SPLIT 5 /* d > 8, and the cosine metric at any d: every fp32 value cut
+                                 into two bf16 pieces, -2 Q X^T (plus norms) from three bf16
+                                 matrix-core products per coordinate as a filter, exact fp32
+                                 test of the pairs that pass.  (Number 1 was this path's
+                                 fp32 matrix-core predecessor.) */
 
 /*
  * The plan: how the call is cut into pieces (section 4.3: split the largest
@@ -84,14 +84,13 @@ typedef struct {
     int64_t chunk_rows;  /* query rows per chunk (multiple of tile_q, or m)     */
     int64_t q_chunks;    /* ceil(m / chunk_rows); 0 when m == 0                 */
     int32_t streams;     /* HIP streams used (1: the caller's)                  */
-    int32_t x_blocked;   /* 1: path 1 reads the points from a blocked copy in the workspace */
+    int32_t reserved;    /* 0 */
     int32_t metric;      /* knn_metric                                          */
     int32_t seed_cells;  /* path 4, d <= 3: cells per axis of the grid the points are counted
                             into to give every list a finite starting threshold; 0: none */
-    uint64_t norms_bytes;     /* workspace: per-point data. path 1: squared norms, plus the
-                                 blocked copy of X when x_blocked; path 2: packed points
-                                 [x0 x1 x2 |x|^2]; path 5: squared norms and a 256-byte
-                                 header (their maximum); path 4: a 256-byte header, 32 bytes
+    uint64_t norms_bytes;     /* workspace: per-point data. path 2: packed points
+                                 [x0 x1 x2 |x|^2]; path 5: squared norms (cosine: 1 / norm)
+                                 and a 256-byte header; path 4: a 256-byte header, 32 bytes
                                  per point and 16 K slots, and seed_cells^d counts;
                                  paths 0, 3: nothing                                   */
     uint64_t query_bytes;     /* workspace: per-query data of one chunk. path 5: the split

@@ -20,7 +20,6 @@ KNN_ERR_UNSUPPORTED = 4
 KNN_ERR_HIP = 5
 KNN_MAX_K = 1024
 KNN_PATH_LOWD = 0
-KNN_PATH_MFMA = 1
 KNN_PATH_LOWD_MFMA = 2
 KNN_PATH_LOWD_BF16 = 4
 KNN_PATH_MFMA_SPLIT = 5
@@ -95,7 +94,7 @@ class PlanStruct(ctypes.Structure):
         ("path", ctypes.c_int32), ("tile_q", ctypes.c_int32),
         ("tile_x", ctypes.c_int32), ("n_splits", ctypes.c_int32),
         ("chunk_rows", ctypes.c_int64), ("q_chunks", ctypes.c_int64),
-        ("streams", ctypes.c_int32), ("x_blocked", ctypes.c_int32),
+        ("streams", ctypes.c_int32), ("reserved", ctypes.c_int32),
         ("metric", ctypes.c_int32), ("seed_cells", ctypes.c_int32),
         ("norms_bytes", ctypes.c_uint64), ("query_bytes", ctypes.c_uint64),
         ("lists_bytes", ctypes.c_uint64),
@@ -145,7 +144,6 @@ class Plan:
     chunk_rows: int
     q_chunks: int
     streams: int
-    x_blocked: int
     metric: int
     seed_cells: int
     norms_bytes: int
@@ -232,7 +230,7 @@ def knn_status_string(status: int) -> str:
 
 def _plan_from_struct(ps: PlanStruct) -> Plan:
     return Plan(ps.m, ps.n, ps.d, ps.k, ps.path, ps.tile_q, ps.tile_x, ps.n_splits,
-                ps.chunk_rows, ps.q_chunks, ps.streams, ps.x_blocked, ps.metric, ps.seed_cells,
+                ps.chunk_rows, ps.q_chunks, ps.streams, ps.metric, ps.seed_cells,
                 ps.norms_bytes, ps.query_bytes, ps.lists_bytes,
                 ps.workspace_bytes, ps.min_limit_bytes)
 

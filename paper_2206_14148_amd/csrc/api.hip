@@ -149,7 +149,6 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
                       unsigned char* ws, int32_t* idx, float* dist, hipStream_t stream) {
     using namespace knn;
     float* xn = reinterpret_cast<float*>(ws);
-    void* xblocked = plan.x_blocked ? ws + align_up((uint64_t)n * 4) : nullptr;
     // path 5: [squared norms][header: their maximum] | [split queries][query norms][shared
     // thresholds] | lists
     unsigned char* hdr = ws + align_up((uint64_t)n * 4);
@@ -164,19 +163,9 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     const bool cosine = metric == KNN_METRIC_COSINE;
 
     hipError_t e;
-    if (plan.path == KNN_PATH_MFMA) {
+    if (plan.path == KNN_PATH_MFMA_SPLIT) {
         hipEvent_t t0 = mark(stream);
         e = launch_row_norms(X, ldx, n, d, cosine, xn, stream);
-        if (e == hipSuccess && plan.x_blocked)
-            e = launch_block_points(X, ldx, n, d, xblocked, stream);
-        if (e != hipSuccess) {
-            drop_bracket(t0);
-            return hip_fail(e, "row norms / point blocking launch");
-        }
-        close_bracket(t0, stream, 0);
-    } else if (plan.path == KNN_PATH_MFMA_SPLIT) {
-        hipEvent_t t0 = mark(stream);
-        e = launch_row_norms(X, ldx, n, d, false, xn, stream);
         if (e == hipSuccess) e = launch_max_norm(xn, n, hdr, stream);
         if (e != hipSuccess) {
             drop_bracket(t0);
@@ -212,11 +201,10 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
             e = launch_split_queries(Qc, ldq, rows, d, qs, tsh, stream);
             if (e == hipSuccess) e = launch_row_norms(Qc, ldq, rows, d, false, qn, stream);
             if (e == hipSuccess)
-                e = launch_split(Qc, ldq, X, ldx, qs, qn, tsh, xn, hdr, rows, n, d, k, S, lk, li,
-                                 stream);
+                e = launch_split(Qc, ldq, X, ldx, qs, qn, tsh, xn, hdr, cosine, rows, n, d, k, S,
+                                 lk, li, stream);
         } else
-            e = launch_mfma(Qc, ldq, X, ldx, xn, xblocked, cosine, rows, n, d, k, S, lk, li,
-                            stream);
+            e = hipErrorInvalidValue;  // no such path
         if (e != hipSuccess) {
             drop_bracket(t1);
             return hip_fail(e, "search launch");

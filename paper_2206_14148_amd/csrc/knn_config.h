@@ -35,15 +35,12 @@ constexpr int kSeedMaxCells = 32768;
 constexpr int kSeedCellsPerPointNum = 2;
 constexpr int kSeedCellsPerPointDen = 3;
 
-// d > kLowdMaxD: fp32 MFMA tile, 4 waves, each wave owns 32 queries x 128 points.
-constexpr int kMfmaTileQ = 128;
-constexpr int kMfmaTileX = 128;
+// fp32 MFMA tiles of the kernel matrix-vector product and the SGPR sums (kmv_kernels.hip,
+// sgpr_kernels.hip): LDS staging of 128-row tiles
 constexpr int kMfmaKC = 16;          // K columns staged in LDS per pipeline step
 constexpr int kMfmaRowStride = 20;   // floats per staged row (16 + 4 pad, keeps 16 B alignment)
-constexpr int kMfmaQregMaxChunks = 16;  // d <= 256: queries stay in registers
-constexpr int kMfmaCand = 32;        // candidate slots per query (LDS)
 
-// d > kPbMaxD, squared-Euclidean metric: bf16 matrix-core filter on split values + exact fp32 test,
+// d > kPbMaxD, and the cosine metric: bf16 matrix-core filter on split values + exact fp32 test,
 // 8 waves, each wave owns 32 queries x 128 points.
 constexpr int kSpWaves = 8;
 constexpr int kSpTileQ = 32 * kSpWaves;
@@ -55,7 +52,6 @@ constexpr int kSpRoom = 8;           // a buffer with fewer free slots than this
 
 // Workgroups the chip holds at once (LDS-limited): the planner sizes launches in rounds of these.
 constexpr int kLowdResidentWorkgroups = 4 * kNumCU;
-constexpr int kMfmaResidentWorkgroups = 2 * kNumCU;
 constexpr int kSpResidentWorkgroups = kNumCU;   // 8 waves of up to 256 registers: one per CU
 constexpr int kWarmupPointsPerK = 64;     // list warm-up of one point range, in point-equivalents per k
 // the same for the low-d filter kernels, per k and per unit of 1 + ln(range / k): measured

@@ -217,86 +217,6 @@ __device__ __forceinline__ float wave_merge(float* __restrict__ gk, int* __restr
     return merged_key(wave_merge_pair(gk, gi, k, ckey, cidx, sc, lane, ncand));
 }
 
-// Bookkeeping of the 32 queries one wave owns in the matrix-core kernels: lane % 32 names the
-// query, the two halves of the wave (lane / 32) hold different points of the same query.
-struct WaveLists {
-    float* lk;        // list keys of the chunk, [rows][S][k]
-    int* li;          // list indices
-    int k, S, s;      // list length, ranges, this workgroup's range
-    int row0;         // first query row (inside the chunk) of this wave
-    float* ck;        // candidate keys of this wave, [32][C]
-    int* ci;          // candidate indices
-    MergeScratch sc;
-    int lane;
-};
-
-// Merge the buffered candidates of the queries named by bits 0..31 of `mask` into their lists;
-// lanes of a merged query get the new threshold and an empty buffer.
-template <int C>
-__device__ __forceinline__ void flush_lists(const WaveLists& w, uint64_t mask, float& tau,
-                                            int& cnt) {
-    while (mask) {
-        const int L = __builtin_ctzll(mask);
-        mask &= mask - 1;
-        wave_sync();
-        const int c = __shfl(cnt, L);
-        float key = kInf;
-        int id = kNoIdx;
-        if (w.lane < c) {
-            key = w.ck[L * C + w.lane];
-            id = w.ci[L * C + w.lane];
-        }
-        const size_t lb = ((size_t)(w.row0 + L) * w.S + w.s) * w.k;
-        const float t_new = wave_merge(w.lk + lb, w.li + lb, w.k, key, id, w.sc, w.lane, c);
-        if ((w.lane & 31) == L) {
-            tau = t_new;
-            cnt = 0;
-        }
-    }
-}
-
-// End of a 128-point tile: acc[pb][e] is the key of query lane % 32 against point
-// tile_base + pb*32 + (e/4)*8 + (lane/32)*4 + e%4.  Keys below the query's threshold are
-// buffered (the two halves of the wave take consecutive slots), full buffers are merged first.
-template <int C>
-__device__ __forceinline__ void tile_epilogue(const f32x16 (&acc)[4], const WaveLists& w,
-                                              int tile_base, float& tau, int& cnt) {
-    float mn = kInf;
-#pragma unroll
-    for (int pb = 0; pb < 4; ++pb) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) mn = fminf(mn, acc[pb][e]);
-    }
-    if (__builtin_amdgcn_ballot_w64(mn < tau) == 0) return;
-    const int i32 = w.lane & 31;
-    const int h = w.lane >> 5;
-#pragma unroll
-    for (int pb = 0; pb < 4; ++pb) {
-        int own = 0;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) own += (acc[pb][e] < tau) ? 1 : 0;
-        int oth = __shfl_xor(own, 32);
-        const uint64_t need = __builtin_amdgcn_ballot_w64(cnt + own + oth > C) & 0xffffffffull;
-        if (need) {
-            flush_lists<C>(w, need, tau, cnt);
-            own = 0;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) own += (acc[pb][e] < tau) ? 1 : 0;
-            oth = __shfl_xor(own, 32);
-        }
-        int slot = i32 * C + cnt + (h ? oth : 0);
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            if (acc[pb][e] < tau) {
-                w.ck[slot] = acc[pb][e];
-                w.ci[slot] = tile_base + pb * 32 + (e >> 2) * 8 + h * 4 + (e & 3);
-                ++slot;
-            }
-        }
-        cnt += own + oth;
-    }
-}
-
 // Cosine metric: the accumulators hold -2 q.x; multiply each by 1/|x| of its point row (rs is
 // the tile's 128 row scales in LDS) to get the rank-equivalent key -2 q.x / |x|.
 __device__ __forceinline__ void scale_rows(f32x16 (&acc)[4], const float* rs, int h) {

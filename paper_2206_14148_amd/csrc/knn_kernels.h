@@ -40,29 +40,20 @@ hipError_t launch_lowd_bf16(const float* Q, int64_t ldq, const float* X, int64_t
                             int64_t rows, int64_t n, int d, int k, int S, bool pack, int seed_cells,
                             float* lk, int* li, hipStream_t stream);
 
-// d > kLowdMaxD: key = xn[j] - 2 q.x from fp32 MFMA tiles (rank-equivalent to the distance).
-// xblocked: nullptr, or (d <= 256 only) the blocked copy of X made by launch_block_points.
-// cosine: xn holds 1/|x| and the key is -2 q.x / |x| (rank-equivalent to the cosine distance).
-hipError_t launch_mfma(const float* Q, int64_t ldq, const float* X, int64_t ldx, const float* xn,
-                       const void* xblocked, bool cosine, int64_t rows, int64_t n, int d, int k,
-                       int S, float* lk, int* li, hipStream_t stream);
-
-// d > kPbMaxD, squared-Euclidean metric: bf16 matrix-core filter on split values, exact fp32
-// difference-form test of what passes it (knn_split.hip).
+// d > kPbMaxD, and the cosine metric at any d: bf16 matrix-core filter on split values, exact
+// fp32 test of what passes it (knn_split.hip).
 //   launch_max_norm      hdr word 0 = max of xn[0..n) (hdr: kAlign bytes)
 //   launch_split_queries qs = the B operands of `rows` queries: ceil(d / 16) * 64 bytes per row;
 //                        tsh = [rows] words set to +inf (the thresholds the ranges share)
-//   launch_split         the search; qn = squared norms of the chunk's queries (fp32, [rows])
+//   launch_split         the search; qn = squared norms of the chunk's queries (fp32, [rows]);
+//                        cosine: xn holds 1 / |x| and the keys are -2 q.x / |x|
 hipError_t launch_max_norm(const float* xn, int64_t n, void* hdr, hipStream_t stream);
 hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d, void* qs,
                                 void* tsh, hipStream_t stream);
 hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* qs,
-                        const float* qn, void* tsh, const float* xn, const void* hdr, int64_t rows,
-                        int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream);
-
-// Blocked copy of X: [ceil(n/128)][ceil(d/16)] contiguous blocks of 128 x 16 floats, zero-filled.
-hipError_t launch_block_points(const float* X, int64_t ldx, int64_t n, int d, void* xblocked,
-                               hipStream_t stream);
+                        const float* qn, void* tsh, const float* xn, const void* hdr, bool cosine,
+                        int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
+                        hipStream_t stream);
 
 // Merge the S lists of each row, re-evaluate the k winners in fp64 (metric: knn_metric value),
 // order by (distance, index) and write idx / dist rows.

@@ -55,6 +55,16 @@ __device__ __forceinline__ void split8(const f32x4& x0, const f32x4& x1, float s
     split_pair(x1[2], x1[3], scale, hi.w, lo.w);
 }
 
+// floats <-> unsigned words with the same order (for atomicMin on keys of either sign)
+__device__ __forceinline__ unsigned key_word(float f) {
+    const unsigned u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float word_key(unsigned w) {
+    return __uint_as_float((w & 0x80000000u) ? (w & 0x7fffffffu) : ~w);
+}
+constexpr unsigned kInfWord = 0xff800000u;  // key_word(+inf)
+
 // header word 0 of the per-point area: max ||x||^2 (bits of a non-negative float)
 __global__ void knn_split_init_kernel(unsigned* __restrict__ hdr) {
     if (threadIdx.x == 0) hdr[0] = 0u;
@@ -96,13 +106,14 @@ __global__ __launch_bounds__(256) void knn_split_queries_kernel(const float* __r
     o[3] = lo[1];
 }
 
-// One lane's share of the exact key sum_t (q_t - x_t)^2 of a candidate: the groups of four
+// One lane's share of the exact key of a candidate - sum_t (q_t - x_t)^2, or with DOT the
+// product sum_t q_t x_t of the cosine metric: the groups of four
 // coordinates g = part, part + 2, ... in ascending order, one fma chain.  The loads of eight groups
 // are issued before the first is used, so that a row of a few KB costs a few memory round trips,
 // not one per group.
-template <bool ALIGNED>
+template <bool ALIGNED, bool DOT>
 __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, const float* __restrict__ xp,
-                                            int d, int part) {
+                                               int d, int part) {
     constexpr int U = 8;
     float sum = 0.f;
     const int ng = (d + 3) >> 2;  // groups of four coordinates (the last may be ragged)
@@ -130,7 +141,7 @@ __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, con
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float df = qv[u][e] - xv[u][e];
-                const float next = fmaf(df, df, sum);
+                const float next = DOT ? fmaf(qv[u][e], xv[u][e], sum) : fmaf(df, df, sum);
                 sum = (g < ng && 4 * g + e < d) ? next : sum;
             }
         }
@@ -145,8 +156,9 @@ __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, con
 // candidate: lane 2c + p sums the groups of four coordinates g = p, p + 2, ... (exact_partial),
 // the two partial sums are added; that order is part of the key's definition.  The keys are
 // merged into the query's list gk/gi, the list's k-th key is published in *tshr (atomic
-// minimum; keys are sums of squares, so as unsigned words they order like the floats, +inf
-// above all).  Returns the list's new k-th key as float bits.
+// minimum on order-preserving words).  rn != null selects the cosine metric: the key of point j
+// is -2 (q . x_j) rn[j] with the dot product summed in the same order.  Returns the list's new
+// k-th key as float bits.
 template <bool ALIGNED>
 __device__ __noinline__ unsigned split_flush_query(const float* __restrict__ qp,
                                                    const float* __restrict__ X, int64_t ldx, int d,
@@ -154,7 +166,7 @@ __device__ __noinline__ unsigned split_flush_query(const float* __restrict__ qp,
                                                    int cc,
                                                    float* __restrict__ gk, int* __restrict__ gi, int k,
                                                    float* scratch, unsigned* tshr,
-                                                   int lane) {
+                                                   const float* __restrict__ rn, int lane) {
     MergeScratch sc;
     sc.cand_key = scratch;
     sc.cand_idx = reinterpret_cast<int*>(scratch + kWave);
@@ -163,8 +175,16 @@ __device__ __noinline__ unsigned split_flush_query(const float* __restrict__ qp,
     wave_sync();
     const int cand = lane >> 1, part = lane & 1;
     const int j = cand < cc ? (cbuf ? cbuf[cand] : jbase + cand) : -1;
-    float sum = exact_partial<ALIGNED>(qp, X + (int64_t)(j < 0 ? jsafe : j) * ldx, d, part);
-    sum += lane_xor<1>(sum);
+    const int jl = j < 0 ? jsafe : j;
+    float sum;
+    if (rn) {
+        sum = exact_partial<ALIGNED, true>(qp, X + (int64_t)jl * ldx, d, part);
+        sum += lane_xor<1>(sum);
+        sum = (-2.f * sum) * rn[jl];
+    } else {
+        sum = exact_partial<ALIGNED, false>(qp, X + (int64_t)jl * ldx, d, part);
+        sum += lane_xor<1>(sum);
+    }
     // candidate c sits in lanes 2c, 2c + 1; the merge wants it in lane c
     const int src = (2 * lane) & 63;
     float key = __shfl(sum, src);
@@ -175,7 +195,8 @@ __device__ __noinline__ unsigned split_flush_query(const float* __restrict__ qp,
     }
     const uint64_t mr = wave_merge_pair_inline(gk, gi, k, key, id, sc, lane, cc);
     const unsigned t_bits = (unsigned)mr;
-    if (lane == 0) atomicMin(tshr, t_bits);  // no value returned: nothing waits for the round trip
+    // no value returned: nothing waits for the round trip
+    if (lane == 0) atomicMin(tshr, key_word(__uint_as_float(t_bits)));
     return t_bits;
 }
 
@@ -210,8 +231,8 @@ template <int NCH, bool ALIGNED>
 __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
     const uint4* __restrict__ Qs, const float* __restrict__ qnorm, unsigned* tsh,
-    const float* __restrict__ xn, const unsigned* __restrict__ hdr, int rows, int n, int d,
-    int nch_real, int k, int S, int split_len, int BQ, int BS, float* __restrict__ lk,
+    const float* __restrict__ xn, const unsigned* __restrict__ hdr, int cosine, int rows, int n,
+    int d, int nch_real, int k, int S, int split_len, int BQ, int BS, float* __restrict__ lk,
     int* __restrict__ li) {
     // chunks per tile that the pipeline walks: all of NCH when the queries are resident (the
     // ones past the real count meet zero B operands)
@@ -220,7 +241,8 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     extern __shared__ __align__(16) unsigned char smem[];
     uint4* as = reinterpret_cast<uint4*>(smem);                  // [2 buffers][2 pieces][TX][2]
     float* xns = reinterpret_cast<float*>(as + 2 * 2 * TX * 2);  // [2][TX] accumulator start values
-    int* ci = reinterpret_cast<int*>(xns + 2 * TX);              // [TQ][C] buffered point indices
+    float* rns = xns + 2 * TX;                                   // [2][TX] row scales (cosine)
+    int* ci = reinterpret_cast<int*>(rns + 2 * TX);              // [TQ][C] buffered point indices
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -255,8 +277,16 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     float tauf = own;
     int cnt = 0, ovf = 0;
     const uint4* const qb = Qs + (size_t)qrow * nch_real * 4 + h;
-    // (the smallest normal number keeps the bound strict when every value involved is zero)
-    auto key_bound = [&](float t) { return (t - qn) + (cross + e_sum * (xmax + qn + t) + 0x1p-126f); };
+    // (the smallest normal number keeps the bound strict when every value involved is zero).
+    // Cosine metric (xn holds 1 / |x|): filter key = -2 (xh.qh + xh.ql + xl.qh) / |x|, exact key
+    // = -2 (q.x) / |x| from an fp32 dot product; |x| / |x| = 1 leaves e_dot |q| for the
+    // products, and the roundings of 1 / |x|, of the scaling and of the dot product are ulps of
+    // values below 2.02 |q|.
+    const float cross_cos = (e_dot + 4.f * e_sum) * sqrtf(qn);
+    auto key_bound = [&](float t) {
+        return cosine ? t + (cross_cos + 0x1p-126f)
+                      : (t - qn) + (cross + e_sum * (xmax + qn + t) + 0x1p-126f);
+    };
 
     const int j0 = s * split_len;
     const int j1 = min(n, j0 + split_len);
@@ -273,7 +303,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
         const size_t lb = ((size_t)r * S + s) * k;
         const unsigned fr = split_flush_query<ALIGNED>(
             Q + (int64_t)r * ldq, X, ldx, d, j0, from_range ? nullptr : wci + L * C, jbase, cc,
-            lk + lb, li + lb, k, my_scratch, tsh + r, lane);
+            lk + lb, li + lb, k, my_scratch, tsh + r, cosine ? xn : nullptr, lane);
         if (i32 == L) {
             own = __uint_as_float(fr);
             tauf = key_bound(fminf(own, cap));
@@ -368,8 +398,13 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
         split_pair(g.x0[2], g.x0[3], 1.f, hi.y, lo.y);
         as_w[(buf * 2 + 0) * TX * 4] = hi;
         as_w[(buf * 2 + 1) * TX * 4] = lo;
-        if (s_c == 0 && tid < TX)  // +inf past the range: such a row never passes
-            xns[(s_tile & 1) * TX + tid] = (j0 + s_tile * TX + tid < j1) ? g.xnv : kInf;
+        if (s_c == 0 && tid < TX) {  // +inf past the range: such a row never passes
+            const bool ok = j0 + s_tile * TX + tid < j1;
+            // xn is |x|^2, or for the cosine metric 1 / |x|: then the sums start from 0 and are
+            // scaled by it at the end of the tile
+            xns[(s_tile & 1) * TX + tid] = ok ? (cosine ? 0.f : g.xnv) : kInf;
+            rns[(s_tile & 1) * TX + tid] = (ok && cosine) ? g.xnv : 1.f;
+        }
         if (++s_c == nch) {
             s_c = 0;
             ++s_tile;
@@ -430,9 +465,10 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
             // calls in drain().
             const int tile_base = j0 + tile * TX;
             // what the other ranges of the query have reached since the last look
-            cap = fminf(cap, __uint_as_float(__hip_atomic_load(tsh + qrow, __ATOMIC_RELAXED,
-                                                               __HIP_MEMORY_SCOPE_AGENT)));
+            cap = fminf(cap, word_key(__hip_atomic_load(tsh + qrow, __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT)));
             tauf = key_bound(fminf(own, cap));
+            if (cosine) scale_rows(acc, rns + (tile & 1) * TX, h);
             epilogue(acc, tile_base);
             if (__builtin_amdgcn_ballot_w64(ovf != 0 || cnt > C - kSpRoom) != 0)
                 drain(tile_base, false);
@@ -507,7 +543,7 @@ hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d
                                 void* tsh, hipStream_t stream) {
     const int nch = (d + kSpKC - 1) / kSpKC;
     knn_fill_words_kernel<<<dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream>>>(
-        static_cast<unsigned*>(tsh), rows, 0x7f800000u);  // +inf: nothing published yet
+        static_cast<unsigned*>(tsh), rows, kInfWord);  // +inf: nothing published yet
     const int64_t items = rows * nch;
     const bool aligned = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) && (ldq % 4 == 0) && (d % 4 == 0);
     const dim3 grid((unsigned)((items + 255) / 256));
@@ -521,10 +557,11 @@ hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d
 }
 
 hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* qs,
-                        const float* qn, void* tsh, const float* xn, const void* hdr, int64_t rows,
-                        int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream) {
+                        const float* qn, void* tsh, const float* xn, const void* hdr, bool cosine,
+                        int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
+                        hipStream_t stream) {
     const int nch = (d + kSpKC - 1) / kSpKC;
-    const size_t lds = (size_t)2 * 2 * kSpTileX * 2 * 16 + (size_t)2 * kSpTileX * 4 +
+    const size_t lds = (size_t)2 * 2 * kSpTileX * 2 * 16 + (size_t)4 * kSpTileX * 4 +
                        (size_t)kSpTileQ * kSpCand * 4 + (size_t)kSpWaves * (2 * kWave + 2 * k) * 4;
     int64_t split_len = (n + S - 1) / S;
     split_len = (split_len + kSpTileX - 1) / kSpTileX * kSpTileX;
@@ -545,8 +582,8 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
         if (e2 != hipSuccess) return e2;                                                          \
         knn_split_kernel<N, A><<<grid, dim3(64 * kSpWaves), lds, stream>>>(                       \
             Q, ldq, X, ldx, static_cast<const uint4*>(qs), qn, static_cast<unsigned*>(tsh), xn,   \
-            static_cast<const unsigned*>(hdr), (int)rows, (int)n, d, nch, k, S, (int)split_len,   \
-            BQ, BS, lk, li);                                                                      \
+            static_cast<const unsigned*>(hdr), cosine ? 1 : 0, (int)rows, (int)n, d, nch, k, S,   \
+            (int)split_len, BQ, BS, lk, li);                                                      \
     } while (0)
 #define KNN_SPLIT_LAUNCH(N)                                                                       \
     do {                                                                                          \

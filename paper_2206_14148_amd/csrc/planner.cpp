@@ -118,16 +118,12 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     // the cosine keys come from the matrix-core kernels only
     // (lowd also stands for the L1 kernel: same workgroup shape, no per-point workspace)
     const bool lowd = (d <= kLowdMaxD && metric == KNN_METRIC_L2SQ) || metric == KNN_METRIC_L1;
-    // d > 8, squared-Euclidean: the bf16 filter on split values + exact test; the fp32 MFMA
-    // path serves the cosine metric
-    const bool split = !lowd && metric == KNN_METRIC_L2SQ;
+    // d > 8, or the cosine metric at any d: the bf16 filter on split values + exact test
+    const bool split = !lowd;
     // smallest plan of all: the vector-ALU path (no per-point workspace) or a matrix-core path
-    out->path = metric == KNN_METRIC_L1 ? KNN_PATH_L1
-                : lowd                  ? KNN_PATH_LOWD
-                : split                 ? KNN_PATH_MFMA_SPLIT
-                                        : KNN_PATH_MFMA;
-    out->tile_q = lowd ? kLowdTileQ : (split ? kSpTileQ : kMfmaTileQ);
-    out->tile_x = lowd ? kLowdUnroll : kMfmaTileX;
+    out->path = metric == KNN_METRIC_L1 ? KNN_PATH_L1 : (lowd ? KNN_PATH_LOWD : KNN_PATH_MFMA_SPLIT);
+    out->tile_q = lowd ? kLowdTileQ : kSpTileQ;
+    out->tile_x = lowd ? kLowdUnroll : kSpTileX;
     out->norms_bytes = lowd ? 0 : align_up((uint64_t)n * 4) + (split ? kAlign : 0);
     const uint64_t qrow = split ? 64ull * (((uint64_t)d + kSpKC - 1) / kSpKC) : 0;
     {
@@ -191,8 +187,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     int64_t s_max = n / kMinSplitPoints;
     if (s_max < 1) s_max = 1;
     if (s_max > kMaxSplits) s_max = kMaxSplits;
-    const int64_t slots = lowd ? kLowdResidentWorkgroups
-                               : (split ? kSpResidentWorkgroups : kMfmaResidentWorkgroups);
+    const int64_t slots = lowd ? kLowdResidentWorkgroups : kSpResidentWorkgroups;
     int64_t best_s = 0, best_rows = 0;
     double best_cost = 0.0;
     for (int64_t S = 1; S <= s_max; S = (S < 8 ? S + 1 : S + 8)) {
@@ -230,18 +225,6 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     out->lists_bytes = lists_bytes_for((uint64_t)best_rows, (uint64_t)best_s, (uint64_t)k);
     out->query_bytes = query_bytes_for((uint64_t)best_rows, qrow);
     out->workspace_bytes = out->norms_bytes + out->query_bytes + out->lists_bytes;
-    if (out->path == KNN_PATH_MFMA && d <= kMfmaKC * kMfmaQregMaxChunks) {
-        // spare room under the limit buys a blocked copy of the points (contiguous 8 KB blocks
-        // in the order the kernel streams them); it never costs a query chunk
-        const uint64_t tiles = ((uint64_t)n + kMfmaTileX - 1) / kMfmaTileX;
-        const uint64_t chunks = ((uint64_t)d + kMfmaKC - 1) / kMfmaKC;
-        const uint64_t blocked = align_up(tiles * chunks * kMfmaTileX * kMfmaKC * 4);
-        if (out->workspace_bytes + blocked <= mem_limit_bytes) {
-            out->x_blocked = 1;
-            out->norms_bytes += blocked;
-            out->workspace_bytes += blocked;
-        }
-    }
     return KNN_OK;
 }
 

@@ -315,8 +315,8 @@ def test_cosine_result_does_not_depend_on_limit_or_point_layout(K):
     lo = K.knn_plan(m, n, d, k, 1 << 40, "cosine").min_limit_bytes
     limits = [lo, lo + 300_000, 64 * W.MB]
     plans = [K.knn_plan(m, n, d, k, lim, "cosine") for lim in limits]
-    say("   plans", [(p.q_chunks, p.n_splits, p.x_blocked) for p in plans])
-    assert plans[0].x_blocked == 0 and plans[-1].x_blocked == 1 and plans[0].q_chunks > 1
+    say("   plans", [(p.q_chunks, p.n_splits) for p in plans])
+    assert plans[0].q_chunks > 1 and plans[-1].q_chunks == 1 and plans[-1].n_splits > 1
     ref = run_gpu(K, Q, X, k, limits[0], metric="cosine")
     for lim in limits[1:]:
         idx, dist = run_gpu(K, Q, X, k, lim, metric="cosine")

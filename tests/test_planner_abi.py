@@ -130,7 +130,8 @@ def test_low_d_falls_back_to_the_vector_path_when_packed_points_do_not_fit():
     assert K.knn_plan(m, n, 8, k, 10 ** 9).norms_bytes == 256 + 64 * n
     assert K.knn_plan(m, n, 8, k, 60 * 10 ** 6).path == K.KNN_PATH_LOWD
     assert K.knn_plan(m, n, 9, k, 10 ** 9).path == K.KNN_PATH_MFMA_SPLIT
-    assert K.knn_plan(m, n, 9, k, 10 ** 9, metric="cosine").path == K.KNN_PATH_MFMA
+    assert K.knn_plan(m, n, 9, k, 10 ** 9, metric="cosine").path == K.KNN_PATH_MFMA_SPLIT
+    assert K.knn_plan(m, n, 3, k, 10 ** 9, metric="cosine").path == K.KNN_PATH_MFMA_SPLIT
 
 
 def test_threshold_seed_grid_is_sized_from_n_and_k_and_paid_for_under_the_limit():
