@@ -63,6 +63,7 @@ constexpr int kMaxSplits = 64;
 constexpr int64_t kMaxPoints = ((int64_t)1 << 31) - 65536;
 constexpr int64_t kMaxChunkRows = 1 << 22;  // keeps per-launch row counts and grids in int range
 constexpr int kMinSplitPoints = 2048;    // a point range shorter than this is not worth a split
+constexpr int kSpMinSplitPoints = 512;   // the same on the split path
 
 constexpr uint64_t kAlign = 256;
 constexpr inline uint64_t align_up(uint64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }

@@ -184,7 +184,9 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     // n / S points, but also more list warm-up and merge work.  Estimated run time of a
     // plan: chunks x rounds of resident workgroups x points per workgroup (+ a warm-up
     // allowance); a larger S must beat a smaller one by 10 %.
-    int64_t s_max = n / kMinSplitPoints;
+    // (on the split path the ranges of a query share their thresholds, so short ranges cost
+    // little list warm-up: they may be shorter)
+    int64_t s_max = n / (split ? kSpMinSplitPoints : kMinSplitPoints);
     if (s_max < 1) s_max = 1;
     if (s_max > kMaxSplits) s_max = kMaxSplits;
     const int64_t slots = lowd ? kLowdResidentWorkgroups : kSpResidentWorkgroups;
