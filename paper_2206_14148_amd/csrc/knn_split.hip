@@ -376,7 +376,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
         f32x4 x0;
         float xnv;
     };
-    struct BS_ {
+    struct QB {
         uint4 hi, lo;
     };
     int f_tile = 0, f_c = 0;  // (tile, chunk) of the next fetch
@@ -410,7 +410,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
             ++s_tile;
         }
     };
-    auto fetchQ = [&](int c, BS_& g) {
+    auto fetchQ = [&](int c, QB& g) {
         g.hi = qb[c * 4];
         g.lo = qb[c * 4 + 2];
     };
@@ -480,10 +480,10 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
         }
     };
     if constexpr (NCH == 0) {
-        BS_ be, bo;
+        QB be, bo;
         if (total > 0) fetchQ(0, be);
         int c = 0;
-        auto body = [&](int step, int par, XS& mine, const XS& next, const BS_& bcur, BS_& bnext) {
+        auto body = [&](int step, int par, XS& mine, const XS& next, const QB& bcur, QB& bnext) {
             fetchQ(c + 1 == nch ? 0 : c + 1, bnext);
             const bool last = c == nch - 1;
             c = last ? 0 : c + 1;
@@ -510,8 +510,6 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
 #pragma unroll
                 for (int c = 0; c < NR; ++c) {
                     const int step = (tile0 + tt) * NR + c;
-                    constexpr int dummy = 0;
-                    (void)dummy;
                     if (((tt * NR + c) & 1) == 0)
                         step_fn(step, 0, c == NR - 1, bqh[c], bql[c], xe, xo);
                     else
