@@ -4,9 +4,11 @@
  *
  * Operation (paper section 5.2, "K-Nearest Neighbours"): for each of m query
  * points select the k closest of n data points.  Distances are squared
- * Euclidean, evaluated through the expansion of section 4.1
- * (sum x^2 + y^2 - 2xy, whose largest operand is m x n instead of m x n x d);
- * the m x n matrix itself is never stored: it is produced tile by tile and
+ * Euclidean.  The expansion of section 4.1 (sum x^2 + y^2 - 2xy, whose largest
+ * operand is m x n instead of m x n x d) runs on the matrix cores and decides
+ * which pairs can still matter to a query; those pairs are then evaluated in
+ * the difference form in fp32, and the k winners once more in fp64.
+ * The m x n matrix itself is never stored: it is produced tile by tile and
  * reduced on the fly to each query's k smallest, in the spirit of the
  * generator / reducer loop of section 4.3 (figure 2, algorithm 1).  All
  * library-owned device memory is one workspace whose size never exceeds the
@@ -48,7 +50,7 @@ typedef enum {
  * Distance (section 5.2 and the appendix table report squared-Euclidean, L1 and cosine rows).
  *   KNN_METRIC_L2SQ    sum_t (q_t - x_t)^2
  *   KNN_METRIC_COSINE  max(0, 1 - <q, x> / (|q| |x|)); 1 if either vector is zero.
- *                      Always runs on the matrix-core path (path 1), whatever d.
+ *                      Always runs on the matrix-core path (path 5), whatever d.
  *   KNN_METRIC_L1      sum_t |q_t - x_t|.  Vector-ALU path 3, whatever d.
  */
 typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1, KNN_METRIC_L1 = 2 } knn_metric;
