@@ -7,6 +7,7 @@
 #include <climits>
 #include <cmath>
 #include <cstdint>
+#include <type_traits>
 
 #include "knn_config.h"
 #include "knn_device.h"
@@ -216,12 +217,14 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_l1_kernel(
         float acc[P];
 #pragma unroll
         for (int p = 0; p < P; ++p) acc[p] = 0.f;
-        for (int t0 = 0; t0 < d; t0 += TC) {
-            const bool full = t0 + TC <= d;  // uniform
-            float qv[TC];
-            if (full && qvec) {  // uniform: whole chunk inside the row and 16-byte aligned
+        // N dimensions t0 .. t0 + N - 1 for the P points of the group; masked: some of them
+        // lie past d (only the last, shorter piece of a row)
+        auto piece = [&](auto n_tag, int t0, bool masked) {
+            constexpr int N = decltype(n_tag)::value;
+            float qv[N];
+            if (!masked && qvec) {  // uniform: inside the row and 16-byte aligned
 #pragma unroll
-                for (int t4 = 0; t4 < TC / 4; ++t4) {
+                for (int t4 = 0; t4 < N / 4; ++t4) {
                     const f32x4 v = *reinterpret_cast<const f32x4*>(qrow + t0 + 4 * t4);
                     qv[4 * t4 + 0] = v[0];
                     qv[4 * t4 + 1] = v[1];
@@ -230,7 +233,7 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_l1_kernel(
                 }
             } else {
 #pragma unroll
-                for (int t = 0; t < TC; ++t) {
+                for (int t = 0; t < N; ++t) {
                     const int tt = t0 + t;
                     const float v = qrow[tt < d ? tt : d - 1];
                     qv[t] = tt < d ? v : 0.f;
@@ -241,12 +244,12 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_l1_kernel(
                 const int jp = (j + p < j1) ? j + p : j1 - 1;  // uniform; repeats of the last point are masked below
                 const float* xp = X + (int64_t)jp * ldx;
                 float a = acc[p];
-                if (full) {
+                if (!masked) {
 #pragma unroll
-                    for (int t = 0; t < TC; ++t) a += fabsf(qv[t] - xp[t0 + t]);
+                    for (int t = 0; t < N; ++t) a += fabsf(qv[t] - xp[t0 + t]);
                 } else {
 #pragma unroll
-                    for (int t = 0; t < TC; ++t) {
+                    for (int t = 0; t < N; ++t) {
                         const int tt = t0 + t;
                         const float xv = xp[tt < d ? tt : d - 1];
                         a += fabsf(qv[t] - (tt < d ? xv : 0.f));
@@ -254,7 +257,12 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_l1_kernel(
                 }
                 acc[p] = a;
             }
-        }
+        };
+        // whole chunks of TC dimensions, then pieces of 4, then what is left (ascending t throughout)
+        int t0 = 0;
+        for (; t0 + TC <= d; t0 += TC) piece(std::integral_constant<int, TC>{}, t0, false);
+        for (; t0 + 4 <= d; t0 += 4) piece(std::integral_constant<int, 4>{}, t0, false);
+        if (t0 < d) piece(std::integral_constant<int, 4>{}, t0, true);
         float mn = kInf;
 #pragma unroll
         for (int p = 0; p < P; ++p) {
