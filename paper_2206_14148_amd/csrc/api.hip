@@ -144,9 +144,13 @@ namespace {
 
 // The search of one resident point set under a given plan: norms / packing, then per query
 // chunk the search kernel over all point ranges and the merge + exact re-evaluation.
+// keep_thresholds (path 5, one query chunk): the thresholds that an earlier call with the same
+// plan left in the workspace - k-th keys of the same queries against OTHER points, lists of
+// the same length k - bound this call's lists from the start.
 knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const float* X,
                       int64_t ldx, int64_t m, int64_t n, int32_t d, int32_t k, knn_metric metric,
-                      unsigned char* ws, int32_t* idx, float* dist, hipStream_t stream) {
+                      unsigned char* ws, int32_t* idx, float* dist, hipStream_t stream,
+                      bool keep_thresholds = false) {
     using namespace knn;
     float* xn = reinterpret_cast<float*>(ws);
     // path 5: [squared norms][header: their maximum] | [split queries][query norms][shared
@@ -198,7 +202,7 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
             e = launch_lowd_bf16(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, plan.seed_cells, lk,
                                  li, stream);
         else if (plan.path == KNN_PATH_MFMA_SPLIT) {
-            e = launch_split_queries(Qc, ldq, rows, d, qs, tsh, stream);
+            e = launch_split_queries(Qc, ldq, rows, d, qs, tsh, !keep_thresholds, stream);
             if (e == hipSuccess) e = launch_row_norms(Qc, ldq, rows, d, false, qn, stream);
             if (e == hipSuccess)
                 e = launch_split(Qc, ldq, X, ldx, qs, qn, tsh, xn, hdr, cosine, rows, n, d, k, S,
@@ -345,8 +349,13 @@ extern "C" knn_status knn_search_host_x(const float* Q, int64_t ldq, const float
             st = knn_plan_metric(m, nb, d, kb, metric, hp.inner_limit_bytes, &plan);
             if (st != KNN_OK) return st;
         }
+        // From the second full block on, a block's lists start under the thresholds the
+        // blocks before it reached (every earlier block is a full one with lists of length k,
+        // so its k-th key bounds the overall k-th key) instead of warming up again.
+        const bool keep = b > 0 && nb == hp.block_rows && plan.path == KNN_PATH_MFMA_SPLIT &&
+                          plan.q_chunks == 1;
         st = run_search(plan, Q, ldq, stage[buf], d, m, nb, d, kb, metric, inner_ws, bidx, bdist,
-                        stream);
+                        stream, keep);
         if (st != KNN_OK) return st;
         e = launch_fold_block(bidx, bdist, kb, j0, b == 0 ? 1 : 0, m, k, idx, dist, stream);
         if (e == hipSuccess) e = hipEventRecord(g_host.consumed[buf], stream);

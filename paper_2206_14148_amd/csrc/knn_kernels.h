@@ -44,12 +44,14 @@ hipError_t launch_lowd_bf16(const float* Q, int64_t ldq, const float* X, int64_t
 // fp32 test of what passes it (knn_split.hip).
 //   launch_max_norm      hdr word 0 = max of xn[0..n) (hdr: kAlign bytes)
 //   launch_split_queries qs = the B operands of `rows` queries: ceil(d / 16) * 64 bytes per row;
-//                        tsh = [rows] words set to +inf (the thresholds the ranges share)
+//                        tsh = [rows] words, the thresholds the ranges share: set to +inf, or
+//                        (reset_thresholds false) kept from an earlier search of other points
+//                        for the same queries and the same k
 //   launch_split         the search; qn = squared norms of the chunk's queries (fp32, [rows]);
 //                        cosine: xn holds 1 / |x| and the keys are -2 q.x / |x|
 hipError_t launch_max_norm(const float* xn, int64_t n, void* hdr, hipStream_t stream);
 hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d, void* qs,
-                                void* tsh, hipStream_t stream);
+                                void* tsh, bool reset_thresholds, hipStream_t stream);
 hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* qs,
                         const float* qn, void* tsh, const float* xn, const void* hdr, bool cosine,
                         int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,

@@ -110,8 +110,11 @@ __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
     for (int w = lane; w < k; w += kWave) {
         const double dw = wd[w];
         const int jw = wi[w];
+        // (identical entries can only be the (+inf, no index) fillers of lists that ended up
+        // shorter than k; their slot number keeps the ranks distinct)
         int rank = 0;
-        for (int v = 0; v < k; ++v) rank += before64(wd[v], wi[v], dw, jw) ? 1 : 0;
+        for (int v = 0; v < k; ++v)
+            rank += (before64(wd[v], wi[v], dw, jw) || (wd[v] == dw && wi[v] == jw && v < w)) ? 1 : 0;
         idx_out[(size_t)r * k + rank] = jw;
         dist_out[(size_t)r * k + rank] = (float)dw;
     }

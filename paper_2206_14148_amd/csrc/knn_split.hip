@@ -538,10 +538,11 @@ hipError_t launch_max_norm(const float* xn, int64_t n, void* hdr, hipStream_t st
 }
 
 hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d, void* qs,
-                                void* tsh, hipStream_t stream) {
+                                void* tsh, bool reset_thresholds, hipStream_t stream) {
     const int nch = (d + kSpKC - 1) / kSpKC;
-    knn_fill_words_kernel<<<dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream>>>(
-        static_cast<unsigned*>(tsh), rows, kInfWord);  // +inf: nothing published yet
+    if (reset_thresholds)
+        knn_fill_words_kernel<<<dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream>>>(
+            static_cast<unsigned*>(tsh), rows, kInfWord);  // +inf: nothing published yet
     const int64_t items = rows * nch;
     const bool aligned = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) && (ldq % 4 == 0) && (d % 4 == 0);
     const dim3 grid((unsigned)((items + 255) / 256));

@@ -159,3 +159,28 @@ def test_image_like_workload_under_its_limit(K, oracle):
     rows = W.sample_rows(w, 200)
     o_idx, o_dist, o_next = oracle.knn(Q, X, w.k, rows=rows)
     say("   parity", check(idx.cpu().numpy()[rows], dist.cpu().numpy()[rows], o_idx, o_dist, o_next, w.n))
+
+
+@pytest.mark.parametrize("order", ["nearest_first", "nearest_last"])
+@pytest.mark.parametrize("metric", ["l2", "cosine"])
+def test_thresholds_carried_from_block_to_block(K, oracle, order, metric):
+    # d > 8: from the second block on, the lists start under the thresholds the earlier blocks
+    # reached.  With the nearest points first, the later blocks find nothing below them and
+    # hand back empty lists (fillers only); with the nearest points last, every block improves
+    # on the one before.  Either way the result is that of the resident search.
+    g = np.random.Generator(np.random.PCG64(W.SEED_BASE + 15_000_000))
+    n, m, d, k = 24_000, 260, 24, 12
+    X = g.standard_normal((n, d)).astype(np.float32)
+    Q = (0.05 * g.standard_normal((m, d))).astype(np.float32) + np.float32(0.3)
+    centre = Q.mean(axis=0, dtype=np.float64)
+    Xc = X.astype(np.float64)
+    if metric == "cosine":
+        score = -(Xc @ centre) / np.linalg.norm(Xc, axis=1)
+    else:
+        score = ((Xc - centre) ** 2).sum(axis=1)
+    perm = np.argsort(score if order == "nearest_first" else -score)
+    X = np.ascontiguousarray(X[perm])
+    limit = K.knn_plan_host_x(m, n, d, k, 10 ** 9, metric).min_limit_bytes + 600_000
+    plan = K.knn_plan_host_x(m, n, d, k, limit, metric)
+    assert plan.n_blocks >= 4 and plan.inner.q_chunks == 1 and plan.inner.path == K.KNN_PATH_MFMA_SPLIT
+    run_both(K, oracle, Q, X, k, limit, metric)
