@@ -444,7 +444,10 @@ def main() -> int:
         peak = 256 * 4 * 16 * 2.4e9 / 1e12
         achieved = lane_ops * pairs_per_launch / avg_launch_s / 1e12
         roofline = {"bound": "alu", "kernel": "knn_lowd_bf16_kernel", "achieved": achieved,
-                    "peak": peak, "unit": "Tlane-op/s", "frac": achieved / peak, "traffic": traffic,
+                    # one lane-operation = one issue slot of one lane = one non-fused, non-packed
+                    # fp32 operation, so the figures read as TFLOP/s of such operations
+                    "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
+                    "unit_note": "issue slots of the shared VALU/MFMA port, 1 lane-op = 1 flop",
                     "lane_ops_per_pair": lane_ops,
                     # the filter contraction alone: 2 x 16 bf16 flops per pair against 2.5 PFLOP/s
                     "mfma_bf16_frac": 32.0 * pairs_per_launch / avg_launch_s / 2.5e15,
