@@ -31,7 +31,8 @@ extern "C" {
 
 /* kernel families (kmv_plan_t.path) */
 #define KMV_PATH_LOWD 0 /* d <= 8: difference-form squared distance on the vector ALU   */
-#define KMV_PATH_MFMA 1 /* d  > 8: section 4.1 expansion, fp32 matrix-core tile of X Z^T */
+#define KMV_PATH_MFMA 1 /* d  > 8: section 4.1 expansion, matrix-core tile of X Z^T (bf16
+                           instructions on three-piece splits: fp32-accurate products) */
 #define KMV_PATH_VALU 2 /* fp64 entry points, d > 8: difference form, row re-read in chunks */
 
 /*

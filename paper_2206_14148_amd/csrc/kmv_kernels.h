@@ -10,6 +10,8 @@ namespace kmv {
 constexpr int kLowdMaxD = 8;      // difference form on the vector ALU up to here
 constexpr int kLowdTileRows = 256;
 constexpr int kMfmaTileRows = 128;
+constexpr int kMfmaKC = 16;      // coordinates per pipeline step
+constexpr int kMfmaResidentChunks = 4;  // d <= 64: the bf16 pieces of a row of X stay in registers
 constexpr int kGroup = 64;        // points per fp32 partial sum
 constexpr int kMaxSplits = 64;
 
@@ -22,7 +24,8 @@ hipError_t launch_lowd(const float* X, int64_t ldx, const float* Z, int64_t ldz,
                        int64_t n, int64_t m, int d, float c2, double variance, int S, double* out,
                        hipStream_t stream);
 
-// d > kLowdMaxD: squared distance through the expansion, X Z^T on fp32 MFMA.
+// d > kLowdMaxD: squared distance through the expansion, X Z^T on bf16 MFMA over three-piece
+// splits of the fp32 values (products as accurate as fp32's).
 hipError_t launch_mfma(const float* X, int64_t ldx, const float* Z, int64_t ldz, const float* v,
                        const float* zn, int64_t n, int64_t m, int d, float c2, double variance, int S,
                        double* out, hipStream_t stream);

@@ -11,6 +11,8 @@
 
 #include <cmath>
 #include <cstdint>
+#include <type_traits>
+#include <utility>
 
 #include "kmv_kernels.h"
 #include "knn_config.h"
@@ -110,24 +112,61 @@ __global__ __launch_bounds__(kLowdTileRows) void kmv_lowd_kernel(
 
 // ---------------------------------------------------------------------------------------
 // d > 8: a workgroup of 4 waves owns 128 rows of X and walks its point range in tiles of 128
-// points.  Points are the M side and rows of X the N side of v_mfma_f32_32x32x2_f32, so the
-// 16 accumulator values a lane holds per 32x32 block belong to ONE row x_i (column = lane %
-// 32) and 16 different points.  The accumulators start at -c2 |z_j|^2 and receive
-// (2 c2 x_i) . z_j; adding -c2 |x_i|^2 gives the exponent -c2 |x_i - z_j|^2 of the expansion
-// in section 4.1.  Both operands stream through LDS in chunks of 16 columns, double buffered,
-// with the global loads of step s+2 in flight during step s.
+// points, on the bf16 matrix cores.  Points are the M side and rows of X the N side of
+// v_mfma_f32_32x32x16_bf16, so the 16 accumulator values a lane holds per 32x32 block belong
+// to ONE row x_i (column = lane % 32) and 16 different points.  The accumulators start at
+// -c2 |z_j|^2 and receive (2 c2 x_i) . z_j; adding -c2 |x_i|^2 gives the exponent
+// -c2 |x_i - z_j|^2 of the expansion in section 4.1.
+//
+// Every fp32 value is cut into three bf16 pieces, hi + mid + lo = the value exactly (3 x 8
+// significant bits); of the nine piece products of a pair of values the six of weight >= 2^-16
+// are kept, each exact in the fp32 accumulator, so a product is off by about 2^-23 of its
+// size, the rounding an fp32 multiply would have made.  Six bf16 MFMAs per 16 coordinates
+// take 192 cycles against 512 for the sixteen v_mfma_f32_32x32x2_f32 of an fp32 contraction.
+// The points are cut while they are staged into LDS (double buffered, the global loads of
+// step s+2 in flight during step s).  NCH > 0 (d <= 16 NCH): the pieces of this lane's row are
+// made once and stay in registers.  NCH = 0: the rows of X stream through LDS like the points.
+// Inputs must be finite with squares that fit fp32.
 // ---------------------------------------------------------------------------------------
-template <bool ALIGNED>
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void split3_pair(float a, float b, unsigned& hi, unsigned& mid,
+                                            unsigned& lo) {
+    const f32x2 p = {a, b};
+    const bf16x2 hb = __builtin_convertvector(p, bf16x2);
+    const f32x2 r1 = p - __builtin_convertvector(hb, f32x2);
+    const bf16x2 mb = __builtin_convertvector(r1, bf16x2);
+    const f32x2 r2 = r1 - __builtin_convertvector(mb, f32x2);
+    const bf16x2 lb = __builtin_convertvector(r2, bf16x2);
+    hi = __builtin_bit_cast(unsigned, hb);
+    mid = __builtin_bit_cast(unsigned, mb);
+    lo = __builtin_bit_cast(unsigned, lb);
+}
+
+__device__ __forceinline__ void split3_row8(const f32x4& x0, const f32x4& x1, uint4& hi, uint4& mid,
+                                            uint4& lo) {
+    split3_pair(x0[0], x0[1], hi.x, mid.x, lo.x);
+    split3_pair(x0[2], x0[3], hi.y, mid.y, lo.y);
+    split3_pair(x1[0], x1[1], hi.z, mid.z, lo.z);
+    split3_pair(x1[2], x1[3], hi.w, mid.w, lo.w);
+}
+
+template <int NCH, bool ALIGNED>
 __global__ __launch_bounds__(256, 2) void kmv_mfma_kernel(
     const float* __restrict__ X, int64_t ldx, const float* __restrict__ Z, int64_t ldz,
     const float* __restrict__ v, const float* __restrict__ zn, int n, int m, int d, int split_len,
     float c2, double variance, double* __restrict__ out) {
-    constexpr int TR = kMfmaTileRows, TZ = 128, KC = knn::kMfmaKC, RS = knn::kMfmaRowStride;
+    constexpr int TR = kMfmaTileRows, TZ = 128, KC = kMfmaKC;
+    constexpr bool RES = NCH > 0;
+    constexpr int PIECE = TZ * 2;  // uint4 words of one piece of a staged tile (TR == TZ)
+    static_assert(TR == TZ, "one staging layout for both operands");
     extern __shared__ __align__(16) unsigned char smem[];
-    float* zs = reinterpret_cast<float*>(smem);  // [2][TZ][RS]
-    float* xs = zs + 2 * TZ * RS;                // [2][TR][RS]
-    float* zns = xs + 2 * TR * RS;               // [2][TZ] accumulator start values
-    float* vs = zns + 2 * TZ;                    // [2][TZ] pieces of v
+    uint4* zs = reinterpret_cast<uint4*>(smem);      // [2][3 pieces][TZ][2 halves of 8 bf16]
+    float* zns = reinterpret_cast<float*>(zs + 2 * 3 * PIECE);  // [2][TZ] accumulator start values
+    float* vs = zns + 2 * TZ;                        // [2][TZ] pieces of v
+    uint4* xs = reinterpret_cast<uint4*>(vs + 2 * TZ);  // NCH = 0 only: [2][3 pieces][TR][2]
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -138,25 +177,44 @@ __global__ __launch_bounds__(256, 2) void kmv_mfma_kernel(
     const int my_row = wave * 32 + i32;
     const int r = wg_row0 + my_row;
     const bool active = r < n;
+    const float bscale = 2.f * c2;
+    const int nch = RES ? NCH : (d + KC - 1) / KC;
 
-    // -c2 |x_i|^2 of this lane's row, summed in ascending t
+    // this lane's row: -c2 |x_i|^2, summed in ascending t, and (NCH > 0) the pieces of
+    // 2 c2 x_i for the coordinates 8h .. 8h+7 of every chunk
     float nxn = 0.f;
-    if (active) {
-        const float* p = X + (int64_t)r * ldx;
-        float acc = 0.f;
-        for (int t = 0; t < d; ++t) acc = fmaf(p[t], p[t], acc);
-        nxn = -c2 * acc;
+    bf16x8 bx[RES ? NCH : 1][3];
+    {
+        const int64_t rr = active ? r : n - 1;
+        if (active) {
+            const float* p = X + rr * ldx;
+            float acc = 0.f;
+            for (int t = 0; t < d; ++t) acc = fmaf(p[t], p[t], acc);
+            nxn = -c2 * acc;
+        }
+        if constexpr (RES) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int col = c * KC + h * 8;
+                uint4 ph, pm, pl;
+                split3_row8(
+                    mask_row4(load_row4<ALIGNED>(X, ldx, rr, n, col, d), active, col, d, bscale),
+                    mask_row4(load_row4<ALIGNED>(X, ldx, rr, n, col + 4, d), active, col + 4, d, bscale),
+                    ph, pm, pl);
+                bx[c][0] = __builtin_bit_cast(bf16x8, ph);
+                bx[c][1] = __builtin_bit_cast(bf16x8, pm);
+                bx[c][2] = __builtin_bit_cast(bf16x8, pl);
+            }
+        }
     }
 
     const int j0 = s * split_len;  // split_len is a multiple of TZ
     const int j1 = min(m, j0 + split_len);
     const int ntiles = (j1 > j0) ? (j1 - j0 + TZ - 1) / TZ : 0;
-    const int nch = (d + KC - 1) / KC;
     const int total = ntiles * nch;
-    const float bscale = 2.f * c2;
 
-    const int srow = tid >> 2;
-    const int scol = (tid & 3) * 4;
+    const int srow = tid >> 1;        // staging: this thread cuts 8 coordinates of one row
+    const int scol = (tid & 1) * 8;
 
     struct Staged {
         f32x4 z0, z1, x0, x1;
@@ -170,9 +228,11 @@ __global__ __launch_bounds__(256, 2) void kmv_mfma_kernel(
         const int col = c * KC + scol;
         const int64_t jr = (int64_t)j0 + (int64_t)tile * TZ + srow;
         g.z0 = load_row4<ALIGNED>(Z, ldz, jr, j1, col, d);
-        g.z1 = load_row4<ALIGNED>(Z, ldz, jr + 64, j1, col, d);
-        g.x0 = load_row4<ALIGNED>(X, ldx, (int64_t)wg_row0 + srow, n, col, d);
-        g.x1 = load_row4<ALIGNED>(X, ldx, (int64_t)wg_row0 + srow + 64, n, col, d);
+        g.z1 = load_row4<ALIGNED>(Z, ldz, jr, j1, col + 4, d);
+        if constexpr (!RES) {
+            g.x0 = load_row4<ALIGNED>(X, ldx, (int64_t)wg_row0 + srow, n, col, d);
+            g.x1 = load_row4<ALIGNED>(X, ldx, (int64_t)wg_row0 + srow, n, col + 4, d);
+        }
         const int64_t jj = (int64_t)j0 + (int64_t)tile * TZ + (tid & (TZ - 1));
         const int64_t jc = jj < j1 ? jj : j1 - 1;
         g.znv = zn[jc];
@@ -184,15 +244,22 @@ __global__ __launch_bounds__(256, 2) void kmv_mfma_kernel(
         const int buf = step & 1;
         const int col = c * KC + scol;
         const int64_t jr = (int64_t)j0 + (int64_t)tile * TZ + srow;
-        float* zb = zs + buf * TZ * RS;
-        float* xb = xs + buf * TR * RS;
-        *reinterpret_cast<f32x4*>(zb + srow * RS + scol) = mask_row4(g.z0, jr < j1, col, d, 1.f);
-        *reinterpret_cast<f32x4*>(zb + (srow + 64) * RS + scol) =
-            mask_row4(g.z1, jr + 64 < j1, col, d, 1.f);
-        *reinterpret_cast<f32x4*>(xb + srow * RS + scol) =
-            mask_row4(g.x0, wg_row0 + srow < n, col, d, bscale);
-        *reinterpret_cast<f32x4*>(xb + (srow + 64) * RS + scol) =
-            mask_row4(g.x1, wg_row0 + srow + 64 < n, col, d, bscale);
+        uint4 ph, pm, pl;
+        split3_row8(mask_row4(g.z0, jr < j1, col, d, 1.f), mask_row4(g.z1, jr < j1, col + 4, d, 1.f),
+                    ph, pm, pl);
+        uint4* zb = zs + buf * 3 * PIECE + tid;  // row srow, half tid & 1
+        zb[0] = ph;
+        zb[PIECE] = pm;
+        zb[2 * PIECE] = pl;
+        if constexpr (!RES) {
+            const bool ok = wg_row0 + srow < n;
+            split3_row8(mask_row4(g.x0, ok, col, d, bscale), mask_row4(g.x1, ok, col + 4, d, bscale),
+                        ph, pm, pl);
+            uint4* xb = xs + buf * 3 * PIECE + tid;
+            xb[0] = ph;
+            xb[PIECE] = pm;
+            xb[2 * PIECE] = pl;
+        }
         if (c == 0 && tid < TZ) {
             const int64_t jj = (int64_t)j0 + (int64_t)tile * TZ + tid;
             // points past the range: exponent -inf and weight 0, so they add exactly 0
@@ -212,14 +279,18 @@ __global__ __launch_bounds__(256, 2) void kmv_mfma_kernel(
     if (total > 1) fetch(1, set_odd);
     __syncthreads();
 
-    auto run_step = [&](int step, Staged& mine, const Staged& next) {
-        const int tile = step / nch;
-        const int c = step - tile * nch;
-        const int buf = step & 1;
+    // cc: the chunk, tbc: tile & 1 -- integral constants when NCH > 0 (so bx[c] is a register),
+    // plain ints otherwise; parc: step & 1, always a constant (which staging set is whose)
+    auto run_step = [&](int step, auto cc, auto parc, auto tbc) {
+        constexpr int buf = decltype(parc)::value;
+        const int c = cc;
+        const int tbuf = tbc;
+        Staged& mine = buf ? set_odd : set_even;
+        const Staged& next = buf ? set_even : set_odd;
         fetch(step + 2 < total ? step + 2 : total - 1, mine);  // past the end: a harmless re-load
 
         if (c == 0) {
-            const float* zt = zns + (tile & 1) * TZ;
+            const float* zt = zns + tbuf * TZ;
 #pragma unroll
             for (int pb = 0; pb < 4; ++pb) {
 #pragma unroll
@@ -233,26 +304,34 @@ __global__ __launch_bounds__(256, 2) void kmv_mfma_kernel(
             }
         }
         {
-            const float* zb = zs + buf * TZ * RS;
-            const float* xb = xs + buf * TR * RS;
-            f32x4 b[KC / 8], a[KC / 8][4];
+            bf16x8 b[3];
+            if constexpr (RES) {
+                constexpr int C = decltype(cc)::value;
+                b[0] = bx[C][0];
+                b[1] = bx[C][1];
+                b[2] = bx[C][2];
+            } else {
+                const uint4* xb = xs + buf * 3 * PIECE + my_row * 2 + h;
 #pragma unroll
-            for (int g = 0; g < KC / 8; ++g) {
-                const int col = g * 8 + h * 4;
-                b[g] = *reinterpret_cast<const f32x4*>(xb + my_row * RS + col);
-#pragma unroll
-                for (int pb = 0; pb < 4; ++pb)
-                    a[g][pb] = *reinterpret_cast<const f32x4*>(zb + (pb * 32 + i32) * RS + col);
+                for (int p = 0; p < 3; ++p) b[p] = __builtin_bit_cast(bf16x8, xb[p * PIECE]);
             }
+            const uint4* zb = zs + buf * 3 * PIECE + i32 * 2 + h;
+            bf16x8 a[4][3];
 #pragma unroll
-            for (int g = 0; g < KC / 8; ++g) {
+            for (int pb = 0; pb < 4; ++pb)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
+                for (int p = 0; p < 3; ++p)
+                    a[pb][p] = __builtin_bit_cast(bf16x8, zb[p * PIECE + pb * 64]);
 #pragma unroll
-                    for (int pb = 0; pb < 4; ++pb)
-                        acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g][pb][e], b[g][e], acc[pb], 0, 0, 0);
-                }
-                if (g == 0 && step + 1 < total) stash(step + 1, next);
+            for (int pb = 0; pb < 4; ++pb) {
+                // smallest products first: lo.hi, hi.lo, mid.mid, then mid.hi, hi.mid, hi.hi
+                acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[pb][2], b[0], acc[pb], 0, 0, 0);
+                acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[pb][0], b[2], acc[pb], 0, 0, 0);
+                acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[pb][1], b[1], acc[pb], 0, 0, 0);
+                acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[pb][1], b[0], acc[pb], 0, 0, 0);
+                acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[pb][0], b[1], acc[pb], 0, 0, 0);
+                acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[pb][0], b[0], acc[pb], 0, 0, 0);
+                if (pb == 1 && step + 1 < total) stash(step + 1, next);
             }
         }
 
@@ -260,7 +339,7 @@ __global__ __launch_bounds__(256, 2) void kmv_mfma_kernel(
             // This lane's 64 points of the tile, in ascending j: block pb, register group g,
             // element e is point pb*32 + g*8 + h*4 + e.  The two halves of the wave hold
             // interleaved runs of 4 points; they are added at the very end.
-            const float* vt = vs + (tile & 1) * TZ;
+            const float* vt = vs + tbuf * TZ;
             float part = 0.f;
 #pragma unroll
             for (int pb = 0; pb < 4; ++pb) {
@@ -278,9 +357,43 @@ __global__ __launch_bounds__(256, 2) void kmv_mfma_kernel(
         }
         __syncthreads();
     };
-    for (int step = 0; step < total; step += 2) {
-        run_step(step, set_even, set_odd);
-        if (step + 1 < total) run_step(step + 1, set_odd, set_even);
+    using std::integral_constant;
+    if constexpr (RES) {
+        // two tiles per trip, so that the parity of a step is a constant whatever NCH is
+        auto run_tile = [&](int tile, auto ttc) {
+            constexpr int tt = decltype(ttc)::value;
+            run_step(tile * NCH, integral_constant<int, 0>{}, integral_constant<int, (tt * NCH) & 1>{}, ttc);
+            if constexpr (NCH > 1)
+                run_step(tile * NCH + 1, integral_constant<int, 1>{},
+                         integral_constant<int, (tt * NCH + 1) & 1>{}, ttc);
+            if constexpr (NCH > 2)
+                run_step(tile * NCH + 2, integral_constant<int, 2>{},
+                         integral_constant<int, (tt * NCH + 2) & 1>{}, ttc);
+            if constexpr (NCH > 3)
+                run_step(tile * NCH + 3, integral_constant<int, 3>{},
+                         integral_constant<int, (tt * NCH + 3) & 1>{}, ttc);
+            static_assert(NCH <= 4, "one run_step per chunk is written out up to four");
+        };
+        for (int tile0 = 0; tile0 < ntiles; tile0 += 2) {
+            run_tile(tile0, integral_constant<int, 0>{});
+            if (tile0 + 1 < ntiles) run_tile(tile0 + 1, integral_constant<int, 1>{});
+        }
+    } else {
+        int tile = 0, c = 0;
+        auto advance = [&]() {
+            if (++c == nch) {
+                c = 0;
+                ++tile;
+            }
+        };
+        for (int step = 0; step < total; step += 2) {
+            run_step(step, c, integral_constant<int, 0>{}, tile & 1);
+            advance();
+            if (step + 1 < total) {
+                run_step(step + 1, c, integral_constant<int, 1>{}, tile & 1);
+                advance();
+            }
+        }
     }
     const double other = __shfl_xor(sum, 32);
     if (active && h == 0) out[(int64_t)s * n + r] = variance * (sum + other);
@@ -493,20 +606,37 @@ hipError_t launch_mfma(const float* X, int64_t ldx, const float* Z, int64_t ldz,
                        const float* zn, int64_t n, int64_t m, int d, float c2, double variance, int S,
                        double* out, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    const size_t lds = (size_t)(4 * 128 * knn::kMfmaRowStride + 4 * 128) * 4;
     const dim3 grid((unsigned)((n + kMfmaTileRows - 1) / kMfmaTileRows), (unsigned)S);
     const int split_len = (int)split_length(m, S, 128);
     const bool aligned = (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(Z) % 16 == 0) && (ldx % 4 == 0) &&
                          (ldz % 4 == 0) && (d % 4 == 0);
-    if (aligned) {
-        kmv_mfma_kernel<true><<<grid, dim3(256), lds, stream>>>(
-            X, ldx, Z, ldz, v, zn, (int)n, (int)m, d, split_len, c2, variance, out);
-    } else {
-        kmv_mfma_kernel<false><<<grid, dim3(256), lds, stream>>>(
-            X, ldx, Z, ldz, v, zn, (int)n, (int)m, d, split_len, c2, variance, out);
+    const int nch = (d + kMfmaKC - 1) / kMfmaKC;
+    const int variant = nch <= kMfmaResidentChunks ? nch : 0;
+    // staged pieces of a tile of points (and of rows, when they stream), start values, v
+    const size_t tile_bytes = (size_t)2 * 3 * 128 * 2 * 16;
+    const size_t lds = tile_bytes * (variant == 0 ? 2 : 1) + 4 * 128 * 4;
+    hipError_t err = hipSuccess;
+    auto go = [&](auto kernel) {
+        err = knn::raise_lds_limit(kernel, lds);
+        if (err != hipSuccess) return;
+        kernel<<<grid, dim3(256), lds, stream>>>(X, ldx, Z, ldz, v, zn, (int)n, (int)m, d, split_len,
+                                                 c2, variance, out);
+        err = hipGetLastError();
+    };
+    switch (variant * 2 + (aligned ? 1 : 0)) {
+        case 0: go(kmv_mfma_kernel<0, false>); break;
+        case 1: go(kmv_mfma_kernel<0, true>); break;
+        case 2: go(kmv_mfma_kernel<1, false>); break;
+        case 3: go(kmv_mfma_kernel<1, true>); break;
+        case 4: go(kmv_mfma_kernel<2, false>); break;
+        case 5: go(kmv_mfma_kernel<2, true>); break;
+        case 6: go(kmv_mfma_kernel<3, false>); break;
+        case 7: go(kmv_mfma_kernel<3, true>); break;
+        case 8: go(kmv_mfma_kernel<4, false>); break;
+        default: go(kmv_mfma_kernel<4, true>); break;
     }
-    return hipGetLastError();
+    return err;
 }
 
 }  // namespace kmv

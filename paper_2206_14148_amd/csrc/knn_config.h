@@ -35,8 +35,7 @@ constexpr int kSeedMaxCells = 32768;
 constexpr int kSeedCellsPerPointNum = 2;
 constexpr int kSeedCellsPerPointDen = 3;
 
-// fp32 MFMA tiles of the kernel matrix-vector product and the SGPR sums (kmv_kernels.hip,
-// sgpr_kernels.hip): LDS staging of 128-row tiles
+// fp32 MFMA tiles of the SGPR sums (sgpr_kernels.hip): LDS staging of 128-row tiles
 constexpr int kMfmaKC = 16;          // K columns staged in LDS per pipeline step
 constexpr int kMfmaRowStride = 20;   // floats per staged row (16 + 4 pad, keeps 16 B alignment)
 

@@ -102,6 +102,10 @@ SMALL = [
     (15, 500, 900, 12, 1.0, 100.0, 1.0),  # long lengthscale: K close to all ones
     (16, 400, 800, 2, 1.0, 1.0, 30.0),    # large coordinates
     (17, 400, 800, 24, 1.0, 40.0, 10.0),  # large coordinates on the expansion path
+    (18, 200, 900, 48, 1.0, 7.0, 1.0),    # three K chunks of rows kept in registers, aligned
+    (19, 200, 900, 64, 1.0, 8.0, 1.0),    # four: the last dimension with resident rows
+    (20, 130, 500, 65, 1.0, 8.0, 1.0),    # first dimension whose rows stream through LDS
+    (21, 150, 700, 100, 1.0, 10.0, 1.0),  # streamed rows, odd number of chunks, aligned
 ]
 
 
