@@ -154,7 +154,7 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     using namespace knn;
     float* xn = reinterpret_cast<float*>(ws);
     // path 5: [squared norms][header: their maximum] | [split queries][query norms][shared
-    // thresholds] | lists
+    // thresholds] | lists; L1 path: [transposed queries] | lists
     unsigned char* hdr = ws + align_up((uint64_t)n * 4);
     unsigned char* qs = ws + plan.norms_bytes;
     float* qn = reinterpret_cast<float*>(
@@ -195,7 +195,7 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
         if (plan.path == KNN_PATH_LOWD)
             e = launch_lowd(Qc, ldq, X, ldx, rows, n, d, k, S, lk, li, stream);
         else if (plan.path == KNN_PATH_L1)
-            e = launch_l1(Qc, ldq, X, ldx, rows, n, d, k, S, lk, li, stream);
+            e = launch_l1(Qc, ldq, X, ldx, qs, rows, n, d, k, S, lk, li, stream);
         else if (plan.path == KNN_PATH_LOWD_MFMA)
             e = launch_lowd_mfma(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, lk, li, stream);
         else if (plan.path == KNN_PATH_LOWD_BF16)

@@ -19,9 +19,11 @@ hipError_t launch_row_norms(const float* X, int64_t ldx, int64_t n, int d, bool 
 hipError_t launch_lowd(const float* Q, int64_t ldq, const float* X, int64_t ldx, int64_t rows,
                        int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream);
 
-// L1 metric, any d: key = fp32 sum of absolute differences.
-hipError_t launch_l1(const float* Q, int64_t ldq, const float* X, int64_t ldx, int64_t rows,
-                     int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream);
+// L1 metric, any d: key = fp32 sum of absolute differences.  qt = room for the transposed
+// queries, ceil(rows / 64) * 64 * ceil(d / 4) * 16 bytes (written here, read by the search).
+hipError_t launch_l1(const float* Q, int64_t ldq, const float* X, int64_t ldx, void* qt,
+                     int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
+                     hipStream_t stream);
 
 // d <= kPmMaxD with room for the packed points: the same keys as launch_lowd, found through an
 // MFMA filter.  `packed` = kAlign bytes (max ||x||^2 word) + 16 n bytes ([x0 x1 x2 ||x||^2] per

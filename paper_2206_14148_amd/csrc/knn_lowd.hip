@@ -148,10 +148,33 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_lowd_kernel(
 // in registers and one running sum per point of the group, so a query value is loaded once
 // per 8 points and a point value costs no vector work.  Two VALU ops per pair and dimension
 // (subtract, add-absolute).  Sums run in ascending t, whatever the chunking.
+// The queries are read from a transposed copy, blocks of 64 rows x 4 coordinates with a
+// lane's four values side by side (zeros past the rows and past d): a wave's load of a chunk
+// is then four fully coalesced 1 KB reads.  Read from their own rows, every lane touched a
+// different cache line and the vector L1's tag rate, not the ALU, set the pace.
 // ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void knn_l1_transpose_kernel(const float* __restrict__ Q,
+                                                               int64_t ldq, int rows, int d,
+                                                               f32x4* __restrict__ Qt) {
+    const int d4 = (d + 3) / 4;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (block of 64 rows, t / 4, lane)
+    const int64_t total = (int64_t)((rows + kWave - 1) / kWave) * d4 * kWave;
+    if (i >= total) return;
+    const int lane = (int)(i % kWave);
+    const int t4 = (int)(i / kWave % d4);
+    const int64_t r = i / ((int64_t)kWave * d4) * kWave + lane;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (r < rows) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (4 * t4 + e < d) v[e] = Q[r * ldq + 4 * t4 + e];
+    }
+    Qt[i] = v;
+}
+
 __global__ __launch_bounds__(kLowdTileQ) void knn_l1_kernel(
-    const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx, int rows,
-    int n, int d, int k, int S, int split_len, float* __restrict__ lk, int* __restrict__ li) {
+    const f32x4* __restrict__ Qt, const float* __restrict__ X, int64_t ldx, int rows, int n, int d,
+    int k, int S, int split_len, float* __restrict__ lk, int* __restrict__ li) {
     constexpr int P = 8;    // points per group
     constexpr int TC = 16;  // dimensions per register chunk
     constexpr int H = 4;    // points pushed between two overflow checks
@@ -185,8 +208,8 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_l1_kernel(
             }
         }
     }
-    const float* qrow = Q + (int64_t)(active ? r : 0) * ldq;
-    const bool qvec = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) && (ldq % 4 == 0);
+    // this lane's query: coordinates 4 t4 .. 4 t4 + 3 are qt[t4 * 64]
+    const f32x4* qt = Qt + (size_t)(wave_row0 / kWave) * ((d + 3) / 4) * kWave + lane;
     float tau = active ? kInf : -kInf;
     int cnt = 0;
 
@@ -213,31 +236,94 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_l1_kernel(
 
     const int j0 = s * split_len;
     const int j1 = min(n, j0 + split_len);
+    // The query's next TC values are asked for one piece ahead (at the end of a row: those of
+    // the row's start, for the next group of points).
+    struct QV {
+        f32x4 v[TC / 4];
+    };
+    const int d4 = (d + 3) / 4;
+    auto load_q = [&](QV& q, int t) {
+        const int g0 = (t < d ? t : 0) / 4;
+#pragma unroll
+        for (int t4 = 0; t4 < TC / 4; ++t4) q.v[t4] = qt[(size_t)min(g0 + t4, d4 - 1) * kWave];
+    };
+    QV qa, qb;
+    load_q(qa, 0);
+    float ahead = 0.f;
     for (int j = j0; j < j1; j += P) {
         float acc[P];
 #pragma unroll
         for (int p = 0; p < P; ++p) acc[p] = 0.f;
         // N dimensions t0 .. t0 + N - 1 for the P points of the group; masked: some of them
         // lie past d (only the last, shorter piece of a row)
-        auto piece = [&](auto n_tag, int t0, bool masked) {
+        // cur: the query's values from t0 on; nxt receives those of the piece after this one
+        auto piece = [&](auto n_tag, int t0, bool masked, const QV& cur, QV& nxt) {
             constexpr int N = decltype(n_tag)::value;
+            load_q(nxt, t0 + N);
+            // What the piece after this one will read of its points is asked for now through
+            // the vector memory path (one word at each end of a point's span, lane l for
+            // point l % 8; the value is not used, it only has to be waited for, one piece
+            // later): that brings the lines into the L2, so the scalar loads that touch them
+            // then wait for the L2 and not for HBM.
+            if (N == TC) {
+                asm volatile("" ::"v"(ahead));
+                const bool wrap = t0 + N >= d;
+                const int tn = wrap ? 0 : t0 + N;
+                const int jn = (wrap ? j + P : j) + (lane & (P - 1));
+                const int tw = (lane & P) ? tn : min(tn + N - 1, d - 1);
+                ahead = X[(int64_t)min(jn, j1 - 1) * ldx + tw];
+            }
             float qv[N];
-            if (!masked && qvec) {  // uniform: inside the row and 16-byte aligned
 #pragma unroll
-                for (int t4 = 0; t4 < N / 4; ++t4) {
-                    const f32x4 v = *reinterpret_cast<const f32x4*>(qrow + t0 + 4 * t4);
-                    qv[4 * t4 + 0] = v[0];
-                    qv[4 * t4 + 1] = v[1];
-                    qv[4 * t4 + 2] = v[2];
-                    qv[4 * t4 + 3] = v[3];
-                }
-            } else {
+            for (int t = 0; t < N; ++t) qv[t] = cur.v[t / 4][t % 4];
+            // Scalar loads return in any order, so every wait is for all of them, and the 64
+            // bytes a piece reads of a point are one or two cache lines that nobody has touched
+            // before: left alone, the P loads of a piece miss one after the other, each in
+            // front of its point's arithmetic.  Asking for the last word of every point's span
+            // first (and the first word at the start of a row; later pieces share that line
+            // with the piece before) brings the lines in side by side, one wait for all.
+            if (N == TC) {
+                static_assert(P == 8, "one operand per load below");
+                const int tl = min(t0 + N - 1, d - 1);
+                float w[P];
+                if (t0 == 0) {
 #pragma unroll
-                for (int t = 0; t < N; ++t) {
-                    const int tt = t0 + t;
-                    const float v = qrow[tt < d ? tt : d - 1];
-                    qv[t] = tt < d ? v : 0.f;
+                    for (int p = 0; p < P; ++p) w[p] = X[(int64_t)((j + p < j1) ? j + p : j1 - 1) * ldx];
+                    asm volatile("" ::"s"(w[0]), "s"(w[1]), "s"(w[2]), "s"(w[3]), "s"(w[4]), "s"(w[5]),
+                                 "s"(w[6]), "s"(w[7]));
                 }
+#pragma unroll
+                for (int p = 0; p < P; ++p) w[p] = X[(int64_t)((j + p < j1) ? j + p : j1 - 1) * ldx + tl];
+                asm volatile("" ::"s"(w[0]), "s"(w[1]), "s"(w[2]), "s"(w[3]), "s"(w[4]), "s"(w[5]),
+                             "s"(w[6]), "s"(w[7])
+                             : "memory");
+            }
+            if (N == TC) {
+                // A wait for scalar data is a wait for all of it, so the next point's values
+                // can be on their way only while this point's are being used: ask for them
+                // right behind the first use (which is where the wait sits), not later.
+                float xv[2][N];
+                auto load_x = [&](float(&dst)[N], int p) {
+                    const float* xp = X + (int64_t)((j + p < j1) ? j + p : j1 - 1) * ldx + t0;
+#pragma unroll
+                    for (int t = 0; t < N; ++t) dst[t] = xp[t];
+                };
+                load_x(xv[0], 0);
+#pragma unroll
+                for (int p = 0; p < P; ++p) {
+                    float a = acc[p] + fabsf(qv[0] - xv[p & 1][0]);
+                    if (p + 1 < P) {
+                        // (the sum threads through both statements, so the arithmetic before
+                        // and after them stays where it is written)
+                        asm volatile("" : "+v"(a)::"memory");
+                        load_x(xv[(p + 1) & 1], p + 1);
+                        asm volatile("" : "+v"(a)::"memory");
+                    }
+#pragma unroll
+                    for (int t = 1; t < N; ++t) a += fabsf(qv[t] - xv[p & 1][t]);
+                    acc[p] = a;
+                }
+                return;
             }
 #pragma unroll
             for (int p = 0; p < P; ++p) {
@@ -259,10 +345,27 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_l1_kernel(
             }
         };
         // whole chunks of TC dimensions, then pieces of 4, then what is left (ascending t throughout)
+        // (chunks in pairs, so that the two sets of query registers swap roles without copies)
+        constexpr std::integral_constant<int, TC> whole{};
+        constexpr std::integral_constant<int, 4> four{};
         int t0 = 0;
-        for (; t0 + TC <= d; t0 += TC) piece(std::integral_constant<int, TC>{}, t0, false);
-        for (; t0 + 4 <= d; t0 += 4) piece(std::integral_constant<int, 4>{}, t0, false);
-        if (t0 < d) piece(std::integral_constant<int, 4>{}, t0, true);
+        for (; t0 + 2 * TC <= d; t0 += 2 * TC) {
+            piece(whole, t0, false, qa, qb);
+            piece(whole, t0 + TC, false, qb, qa);
+        }
+        if (t0 + TC <= d) {
+            piece(whole, t0, false, qa, qb);
+            qa = qb;
+            t0 += TC;
+        }
+        for (; t0 + 4 <= d; t0 += 4) {
+            piece(four, t0, false, qa, qb);
+            qa = qb;
+        }
+        if (t0 < d) {
+            piece(four, t0, true, qa, qb);
+            qa = qb;
+        }
         float mn = kInf;
 #pragma unroll
         for (int p = 0; p < P; ++p) {
@@ -1072,8 +1175,16 @@ static hipError_t launch_lowd_d(const float* Q, int64_t ldq, const float* X, int
     return hipGetLastError();
 }
 
-hipError_t launch_l1(const float* Q, int64_t ldq, const float* X, int64_t ldx, int64_t rows,
-                     int64_t n, int d, int k, int S, float* lk, int* li, hipStream_t stream) {
+hipError_t launch_l1(const float* Q, int64_t ldq, const float* X, int64_t ldx, void* qt,
+                     int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
+                     hipStream_t stream) {
+    {
+        const int64_t total = (rows + kWave - 1) / kWave * ((d + 3) / 4) * kWave;
+        knn_l1_transpose_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(
+            Q, ldq, (int)rows, d, static_cast<f32x4*>(qt));
+        hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return e0;
+    }
     const size_t per_wave = (size_t)(2 * kWave * (kLowdCand + 1) + 2 * k + 2 * kWave) * 4;
     const size_t lds = per_wave * kLowdWaves;
     hipError_t e = raise_lds_limit(knn_l1_kernel, lds);
@@ -1081,7 +1192,8 @@ hipError_t launch_l1(const float* Q, int64_t ldq, const float* X, int64_t ldx, i
     int64_t split_len = (n + S - 1) / S;
     split_len = (split_len + 7) / 8 * 8;
     dim3 grid((unsigned)((rows + kLowdTileQ - 1) / kLowdTileQ), (unsigned)S);
-    knn_l1_kernel<<<grid, dim3(kLowdTileQ), lds, stream>>>(Q, ldq, X, ldx, (int)rows, (int)n, d, k, S,
+    knn_l1_kernel<<<grid, dim3(kLowdTileQ), lds, stream>>>(static_cast<const f32x4*>(qt), X, ldx,
+                                                           (int)rows, (int)n, d, k, S,
                                                            (int)split_len, lk, li);
     return hipGetLastError();
 }

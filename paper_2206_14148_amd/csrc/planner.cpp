@@ -71,24 +71,31 @@ uint64_t lists_bytes_for(uint64_t rows, uint64_t S, uint64_t k) {
     return 2 * align_up(rows * S * k * 4);
 }
 
-// per-query data of a chunk besides its lists.  Path 5: the queries' split B operands
+// per-query data of a chunk besides its lists.  kind 1 (path 5): the queries' split B operands
 // (qrow = 64 bytes per 16 coordinates), their squared norms and the thresholds their point
-// ranges share (a word each); other paths: nothing.
-uint64_t query_bytes_for(uint64_t rows, uint64_t qrow) {
-    return qrow ? align_up(rows * qrow) + 2 * align_up(rows * 4) : 0;
+// ranges share (a word each); kind 2 (L1 path): the queries transposed in blocks of 64 rows
+// (qrow = 16 bytes per 4 coordinates); kind 0: nothing.
+uint64_t query_bytes_for(uint64_t rows, uint64_t qrow, int kind) {
+    if (kind == 1) return align_up(rows * qrow) + 2 * align_up(rows * 4);
+    if (kind == 2) return align_up((rows + 63) / 64 * 64 * qrow);
+    return 0;
 }
 
 // largest row count whose lists (S ranges) and per-query data fit in `avail` bytes
-int64_t rows_fitting(uint64_t avail, uint64_t S, uint64_t k, uint64_t qrow) {
-    if (!qrow) {
+int64_t rows_fitting(uint64_t avail, uint64_t S, uint64_t k, uint64_t qrow, int kind) {
+    if (kind == 0) {
         // 2 * align_up(x) <= avail  <=>  x <= floor(floor(avail / 2) / kAlign) * kAlign
         uint64_t usable = avail / 2 / kAlign * kAlign;
         return knn_chunk_rows(usable, S * k * 4);
     }
-    auto need = [&](uint64_t rows) { return lists_bytes_for(rows, S, k) + query_bytes_for(rows, qrow); };
-    const uint64_t per_row = 2 * S * k * 4 + qrow + 8;
-    // the five roundings add less than 5 * kAlign: start below the answer, then step up to it
-    uint64_t rows = avail > 5 * kAlign ? (avail - 5 * kAlign) / per_row : 0;
+    auto need = [&](uint64_t rows) {
+        return lists_bytes_for(rows, S, k) + query_bytes_for(rows, qrow, kind);
+    };
+    const uint64_t per_row = 2 * S * k * 4 + qrow + (kind == 1 ? 8 : 0);  // exact, roundings aside
+    // the roundings (five to kAlign, one to 64 rows) add less than this: start below the
+    // answer, then step up to it
+    const uint64_t slack = 5 * kAlign + 64 * qrow;
+    uint64_t rows = avail > slack ? (avail - slack) / per_row : 0;
     while (need(rows + 1) <= avail) ++rows;
     return (int64_t)rows;
 }
@@ -116,7 +123,8 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     out->k = k;
     out->streams = 1;
     // the cosine keys come from the matrix-core kernels only
-    // (lowd also stands for the L1 kernel: same workgroup shape, no per-point workspace)
+    // (lowd also stands for the L1 kernel: same workgroup shape, no per-point workspace; its
+    // queries are kept transposed per chunk)
     const bool lowd = (d <= kLowdMaxD && metric == KNN_METRIC_L2SQ) || metric == KNN_METRIC_L1;
     // d > 8, or the cosine metric at any d: the bf16 filter on split values + exact test
     const bool split = !lowd;
@@ -125,12 +133,15 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     out->tile_q = lowd ? kLowdTileQ : kSpTileQ;
     out->tile_x = lowd ? kLowdUnroll : kSpTileX;
     out->norms_bytes = lowd ? 0 : align_up((uint64_t)n * 4) + (split ? kAlign : 0);
-    const uint64_t qrow = split ? 64ull * (((uint64_t)d + kSpKC - 1) / kSpKC) : 0;
+    const bool l1 = metric == KNN_METRIC_L1;
+    const int qkind = split ? 1 : (l1 ? 2 : 0);
+    const uint64_t qrow = split ? 64ull * (((uint64_t)d + kSpKC - 1) / kSpKC)
+                                : (l1 ? 16ull * (((uint64_t)d + 3) / 4) : 0);
     {
         const int64_t t0 = out->tile_q;
         const int64_t min_rows = m < t0 ? (m > 0 ? m : 1) : t0;
         out->min_limit_bytes = out->norms_bytes + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k) +
-                               query_bytes_for((uint64_t)min_rows, qrow);
+                               query_bytes_for((uint64_t)min_rows, qrow, qkind);
     }
     if (m == 0) return KNN_OK;
     if (mem_limit_bytes < out->min_limit_bytes) return KNN_ERR_MEM_LIMIT_TOO_SMALL;
@@ -193,7 +204,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     int64_t best_s = 0, best_rows = 0;
     double best_cost = 0.0;
     for (int64_t S = 1; S <= s_max; S = (S < 8 ? S + 1 : S + 8)) {
-        int64_t rows = rows_fitting(avail, (uint64_t)S, (uint64_t)k, qrow);
+        int64_t rows = rows_fitting(avail, (uint64_t)S, (uint64_t)k, qrow, qkind);
         if (rows > kMaxChunkRows) rows = kMaxChunkRows;
         if (rows >= m) rows = m;
         else rows = rows / tile * tile;
@@ -225,7 +236,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     out->chunk_rows = best_rows;
     out->q_chunks = (m + best_rows - 1) / best_rows;
     out->lists_bytes = lists_bytes_for((uint64_t)best_rows, (uint64_t)best_s, (uint64_t)k);
-    out->query_bytes = query_bytes_for((uint64_t)best_rows, qrow);
+    out->query_bytes = query_bytes_for((uint64_t)best_rows, qrow, qkind);
     out->workspace_bytes = out->norms_bytes + out->query_bytes + out->lists_bytes;
     return KNN_OK;
 }

@@ -193,6 +193,40 @@ def test_split_path_accounts_for_the_per_query_data_and_uses_every_byte_it_can()
             K.knn_plan(m, n, d, k, lo - 1)
 
 
+def test_l1_path_accounts_for_the_transposed_queries():
+    # L1 metric, any d: besides the lists a chunk holds its queries transposed in blocks of 64
+    # rows, 16 bytes per row and 4 coordinates; nothing per point
+    import random
+    rnd = random.Random(20240612)
+
+    def up(v):
+        return (v + 255) // 256 * 256
+
+    def qbytes(rows, d):
+        return up(-(-rows // 64) * 64 * -(-d // 4) * 16)
+
+    for _ in range(300):
+        d = rnd.choice([1, 3, 4, 5, 16, 17, 100, 128, 784, 2001])
+        k = rnd.choice([1, 7, 32, 100, 1024])
+        n = rnd.randrange(k, 3_000_000)
+        m = rnd.choice([1, 63, 64, 65, 255, 256, 257, 5000, 123_457])
+        lo = K.knn_plan(m, n, d, k, 1 << 44, metric="l1").min_limit_bytes
+        limit = lo + rnd.choice([0, 1, 255, 256, 4096, 10 ** 6, 10 ** 8, 10 ** 10])
+        p = K.knn_plan(m, n, d, k, limit, metric="l1")
+        assert p.path == K.KNN_PATH_L1 and p.tile_q == 256
+        assert p.norms_bytes == 0
+        assert p.query_bytes == qbytes(p.chunk_rows, d)
+        assert p.lists_bytes == 2 * up(p.chunk_rows * p.n_splits * k * 4)
+        assert p.workspace_bytes == p.query_bytes + p.lists_bytes <= limit
+        assert p.chunk_rows == m or p.chunk_rows % 256 == 0
+        assert p.q_chunks == -(-m // p.chunk_rows)
+        if p.chunk_rows < m and p.chunk_rows < (1 << 22):  # a longer chunk would not have fitted
+            r = p.chunk_rows + 256
+            assert qbytes(r, d) + 2 * up(r * p.n_splits * k * 4) > limit
+        with pytest.raises(K.KnnError):
+            K.knn_plan(m, n, d, k, lo - 1, metric="l1")
+
+
 def test_plan_argument_errors():
     bad = [(-1, 10, 3, 1), (5, 0, 3, 1), (5, 10, 0, 1), (5, 10, 3, 0), (5, 10, 3, 11)]
     for m, n, d, k in bad:
