@@ -35,7 +35,7 @@ MEASURED_TRAFFIC_BYTES = {
     "c4_clustered_d128": 1513.1e9,  # knn_split_kernel (resident queries): fetched + written
     "c5_memsweep_d256": 1155.5e9,   # knn_split_kernel (streamed queries): fetched + written
     "c6_cosine_d100": 13.52e9,      # knn_split_kernel (resident queries): fetched + written
-    "c7_l1_d100": 8.75e9,           # knn_l1_kernel: 8.33 GB fetched + 0.42 GB written
+    "c7_l1_d100": 28.34e9,          # knn_l1_kernel: 27.92 GB fetched + 0.42 GB written
     "kmv1_d1": 1.84e9,              # kmv_lowd_kernel: 1.83 GB fetched + 0.01 GB written
     "kmv2_d32": 1.49e9,             # kmv_mfma_kernel: 1.49 GB fetched + 0.002 GB written
     "kmv3_d1_f64": 4.02e9,          # kmv_lowd_f64_kernel: 4.01 GB fetched + 0.01 GB written

@@ -96,8 +96,10 @@ typedef struct {
                                  per point and 16 K slots, and seed_cells^d counts;
                                  paths 0, 3: nothing                                   */
     uint64_t query_bytes;     /* workspace: per-query data of one chunk. path 5: the split
-                                 queries (64 bytes per row and 16 coordinates) and their
-                                 squared norms; else 0                                 */
+                                 queries (64 bytes per row and 16 coordinates), their
+                                 squared norms and shared thresholds; path 3: the queries
+                                 transposed in blocks of 64 rows (16 bytes per row and 4
+                                 coordinates); else 0                                  */
     uint64_t lists_bytes;     /* workspace: partial k-lists of one chunk        */
     uint64_t workspace_bytes; /* total device workspace needed, <= mem_limit    */
     uint64_t min_limit_bytes; /* smallest limit any plan for this shape fits in */

@@ -150,8 +150,8 @@ __global__ __launch_bounds__(kLowdTileQ) void knn_lowd_kernel(
 // (subtract, add-absolute).  Sums run in ascending t, whatever the chunking.
 // The queries are read from a transposed copy, blocks of 64 rows x 4 coordinates with a
 // lane's four values side by side (zeros past the rows and past d): a wave's load of a chunk
-// is then four fully coalesced 1 KB reads.  Read from their own rows, every lane touched a
-// different cache line and the vector L1's tag rate, not the ALU, set the pace.
+// is then four fully coalesced 1 KB reads (read from their own rows, every lane touched a
+// different cache line: 64 tag look-ups per load instruction, the vector L1 busy all the time).
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void knn_l1_transpose_kernel(const float* __restrict__ Q,
                                                                int64_t ldq, int rows, int d,
