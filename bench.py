@@ -37,7 +37,7 @@ MEASURED_TRAFFIC_BYTES = {
     "c6_cosine_d100": 13.52e9,      # knn_split_kernel (resident queries): fetched + written
     "c7_l1_d100": 28.34e9,          # knn_l1_kernel: 27.92 GB fetched + 0.42 GB written
     "kmv1_d1": 1.84e9,              # kmv_lowd_kernel: 1.83 GB fetched + 0.01 GB written
-    "kmv2_d32": 1.49e9,             # kmv_mfma_kernel: 1.49 GB fetched + 0.002 GB written
+    "kmv2_d32": 1.47e9,             # kmv_mfma_kernel: 1.46 GB fetched + 0.007 GB written
     "kmv3_d1_f64": 4.02e9,          # kmv_lowd_f64_kernel: 4.01 GB fetched + 0.01 GB written
     "sgpr1_road_d3_m10000": 8.97e9,      # sgpr_syrk_kernel, per launch: 8.57 GB fetched + 0.41 GB written
     "sgpr2_electric_d11_m4000": 1.10e9,  # sgpr_syrk_kernel, per launch: 1.04 GB fetched + 0.07 GB written

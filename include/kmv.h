@@ -38,10 +38,12 @@ extern "C" {
 /*
  * The plan.  One workgroup owns tile_rows rows of X (one row of K per lane)
  * and walks a range of the m points; the point axis is cut into n_splits
- * ranges only as far as is needed to fill the GPU when n is small, each range
- * giving a partial sum per row in the workspace (fp64, [n_splits][n]) that a
- * last kernel adds in ascending range order.  With n_splits == 1 the sums go
- * straight to y.  Path 1 also keeps c * ||z_j||^2 (fp32, m values) in the
+ * ranges as far as that fills the GPU (small n) or evens out its last round
+ * of workgroups (path 1) and the limit has room, each range giving a partial
+ * sum per row in the workspace (fp64, [n_splits][n]) that a last kernel adds
+ * in ascending range order.  With n_splits == 1 the sums go straight to y.
+ * n_splits depends on the limit, so y can differ between limits by the fp64
+ * rounding of the range sums.  Path 1 also keeps c * ||z_j||^2 (fp32, m values) in the
  * workspace, c = log2(e) / (2 lengthscale^2).
  */
 typedef struct {

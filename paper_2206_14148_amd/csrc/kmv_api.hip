@@ -50,15 +50,43 @@ int plan_impl(int64_t n, int64_t m, int32_t d, int64_t mem_limit_bytes, bool f64
     out->norms_bytes = valu ? 0 : align_up(4 * m);
     out->min_limit_bytes = out->norms_bytes;
     if (mem_limit_bytes < out->min_limit_bytes) return KNN_ERR_MEM_LIMIT_TOO_SMALL;
-    // Ranges: double until the launch has enough workgroups for every CU to hold its share
-    // (the low-d kernel runs 4 workgroups per CU, the matrix-core kernel 2), as long as a
-    // range keeps at least 2048 points and the partial sums fit under the limit.
     const int64_t tiles = (n + out->tile_rows - 1) / out->tile_rows;
-    const int64_t want = (lowd ? 4 : 2) * (int64_t)knn::kNumCU;
     int S = 1;
-    while (tiles > 0 && tiles * S < want && 2 * S <= kmv::kMaxSplits && m / (2 * S) >= 2048 &&
-           out->norms_bytes + align_up(8 * n * (2 * S)) <= mem_limit_bytes)
-        S *= 2;
+    if (lowd) {
+        // Ranges: double until the launch has enough workgroups for every CU to hold its share
+        // (the low-d kernel runs 4 workgroups per CU), as long as a range keeps at least 2048
+        // points and the partial sums fit under the limit.
+        const int64_t want = 4 * (int64_t)knn::kNumCU;
+        while (tiles > 0 && tiles * S < want && 2 * S <= kmv::kMaxSplits && m / (2 * S) >= 2048 &&
+               out->norms_bytes + align_up(8 * n * (2 * S)) <= mem_limit_bytes)
+            S *= 2;
+    } else if (tiles > 0) {
+        // The matrix-core kernel holds few workgroups per CU (2 or 3, by its registers), all of
+        // the same length, so a launch runs in rounds and the last one may be nearly empty:
+        // 1563 workgroups on 768 places take three rounds for two rounds' worth of work.
+        // Ranges make the rounds shorter.  Cost of S ranges = rounds x (points per range + a
+        // fixed start-up worth about 512 points); the smallest S within 4 % of the best is
+        // taken, among those whose ranges keep 2048 points and whose partial sums fit.
+        const int nch = (d + kmv::kMfmaKC - 1) / kmv::kMfmaKC;
+        const int64_t places = (int64_t)knn::kNumCU * (nch <= 2 ? 3 : 2);
+        auto cost = [&](int64_t s) {
+            const int64_t rounds = (tiles * s + places - 1) / places;
+            return (double)rounds * (double)((m + s - 1) / s + 512);
+        };
+        auto allowed = [&](int64_t s) {
+            return s == 1 || (s <= kmv::kMaxSplits && m / s >= 2048 &&
+                              out->norms_bytes + align_up(8 * n * s) <= mem_limit_bytes);
+        };
+        static const int kCandidates[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
+        double best = cost(1);
+        for (int s : kCandidates)
+            if (allowed(s) && cost(s) < best) best = cost(s);
+        for (int s : kCandidates)
+            if (allowed(s) && cost(s) <= 1.04 * best) {
+                S = s;
+                break;
+            }
+    }
     out->n_splits = S;
     out->partials_bytes = S > 1 ? align_up(8 * n * S) : 0;
     out->workspace_bytes = out->norms_bytes + out->partials_bytes;

@@ -32,7 +32,7 @@ def test_ranges_grow_only_while_they_fit(d):
         p = K.kmv_plan(n, m, d, limit)
         assert p.workspace_bytes <= limit
         assert p.workspace_bytes == p.norms_bytes + p.partials_bytes
-        assert p.n_splits in (1, 2, 4, 8, 16, 32, 64)
+        assert p.n_splits in (1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64)
         assert (p.partials_bytes == 0) == (p.n_splits == 1)
         if p.n_splits > 1:
             assert p.partials_bytes >= 8 * n * p.n_splits
