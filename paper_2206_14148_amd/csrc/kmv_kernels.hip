@@ -160,13 +160,20 @@ __global__ __launch_bounds__(256, 2) void kmv_mfma_kernel(
     float c2, double variance, double* __restrict__ out) {
     constexpr int TR = kMfmaTileRows, TZ = 128, KC = kMfmaKC;
     constexpr bool RES = NCH > 0;
-    constexpr int PIECE = TZ * 2;  // uint4 words of one piece of a staged tile (TR == TZ)
+    // One piece of a staged tile: per block of 32 rows the 16-byte words of the rows' first
+    // halves (coordinates 0..7 of the chunk), 8 words of padding, then the second halves.  A
+    // wave's read of an MFMA operand (lane = row, upper lanes the second half) then covers
+    // consecutive words, and the two words a pair of staging threads writes for one row lie
+    // 640 bytes apart, in different halves of the banks: no bank conflicts either way.
+    constexpr int BLK = 32 + 8 + 32;       // words per block of 32 rows
+    constexpr int HALF = 32 + 8;           // offset of the second halves inside a block
+    constexpr int PIECE = (TZ / 32) * BLK;  // words of one piece of a staged tile (TR == TZ)
     static_assert(TR == TZ, "one staging layout for both operands");
     extern __shared__ __align__(16) unsigned char smem[];
-    uint4* zs = reinterpret_cast<uint4*>(smem);      // [2][3 pieces][TZ][2 halves of 8 bf16]
+    uint4* zs = reinterpret_cast<uint4*>(smem);      // [2][3 pieces][PIECE]
     float* zns = reinterpret_cast<float*>(zs + 2 * 3 * PIECE);  // [2][TZ] accumulator start values
     float* vs = zns + 2 * TZ;                        // [2][TZ] pieces of v
-    uint4* xs = reinterpret_cast<uint4*>(vs + 2 * TZ);  // NCH = 0 only: [2][3 pieces][TR][2]
+    uint4* xs = reinterpret_cast<uint4*>(vs + 2 * TZ);  // NCH = 0 only: [2][3 pieces][PIECE]
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -247,7 +254,8 @@ __global__ __launch_bounds__(256, 2) void kmv_mfma_kernel(
         uint4 ph, pm, pl;
         split3_row8(mask_row4(g.z0, jr < j1, col, d, 1.f), mask_row4(g.z1, jr < j1, col + 4, d, 1.f),
                     ph, pm, pl);
-        uint4* zb = zs + buf * 3 * PIECE + tid;  // row srow, half tid & 1
+        const int slot = (srow >> 5) * BLK + (tid & 1) * HALF + (srow & 31);
+        uint4* zb = zs + buf * 3 * PIECE + slot;
         zb[0] = ph;
         zb[PIECE] = pm;
         zb[2 * PIECE] = pl;
@@ -255,7 +263,7 @@ __global__ __launch_bounds__(256, 2) void kmv_mfma_kernel(
             const bool ok = wg_row0 + srow < n;
             split3_row8(mask_row4(g.x0, ok, col, d, bscale), mask_row4(g.x1, ok, col + 4, d, bscale),
                         ph, pm, pl);
-            uint4* xb = xs + buf * 3 * PIECE + tid;
+            uint4* xb = xs + buf * 3 * PIECE + slot;
             xb[0] = ph;
             xb[PIECE] = pm;
             xb[2 * PIECE] = pl;
@@ -311,17 +319,17 @@ __global__ __launch_bounds__(256, 2) void kmv_mfma_kernel(
                 b[1] = bx[C][1];
                 b[2] = bx[C][2];
             } else {
-                const uint4* xb = xs + buf * 3 * PIECE + my_row * 2 + h;
+                const uint4* xb = xs + buf * 3 * PIECE + wave * BLK + h * HALF + i32;
 #pragma unroll
                 for (int p = 0; p < 3; ++p) b[p] = __builtin_bit_cast(bf16x8, xb[p * PIECE]);
             }
-            const uint4* zb = zs + buf * 3 * PIECE + i32 * 2 + h;
+            const uint4* zb = zs + buf * 3 * PIECE + h * HALF + i32;
             bf16x8 a[4][3];
 #pragma unroll
             for (int pb = 0; pb < 4; ++pb)
 #pragma unroll
                 for (int p = 0; p < 3; ++p)
-                    a[pb][p] = __builtin_bit_cast(bf16x8, zb[p * PIECE + pb * 64]);
+                    a[pb][p] = __builtin_bit_cast(bf16x8, zb[p * PIECE + pb * BLK]);
 #pragma unroll
             for (int pb = 0; pb < 4; ++pb) {
                 // smallest products first: lo.hi, hi.lo, mid.mid, then mid.hi, hi.mid, hi.hi
@@ -614,7 +622,7 @@ hipError_t launch_mfma(const float* X, int64_t ldx, const float* Z, int64_t ldz,
     const int nch = (d + kMfmaKC - 1) / kMfmaKC;
     const int variant = nch <= kMfmaResidentChunks ? nch : 0;
     // staged pieces of a tile of points (and of rows, when they stream), start values, v
-    const size_t tile_bytes = (size_t)2 * 3 * 128 * 2 * 16;
+    const size_t tile_bytes = (size_t)2 * 3 * (128 / 32) * (32 + 8 + 32) * 16;
     const size_t lds = tile_bytes * (variant == 0 ? 2 : 1) + 4 * 128 * 4;
     hipError_t err = hipSuccess;
     auto go = [&](auto kernel) {
