@@ -617,10 +617,14 @@ __global__ __launch_bounds__(256, 4) void knn_lowd_mfma_kernel(
 // of the kernel above costs two fp32 MFMAs (128 cycles) per 32 x 32 keys; one
 // v_mfma_f32_32x32x16_bf16 (32 cycles) gives keys that are nearly as sharp if every fp32 value
 // is cut into bf16 pieces and the cross products that matter are spread over the 16 K slots:
-//     x = xh + xl + (|rest| <= 2^-18 |x|),  q = qh + ql + (same),  ||x||^2 = nh + nm + nl exactly
-//     key = sum_t  xh_t (-2 qh_t) + xh_t (-2 ql_t) + xl_t (-2 qh_t)  +  (nh + nm + nl) * 1
-// (12 slots, products of two bf16 values are exact in fp32).  What is left out is at most
-// 6.1 * 2^-18 ||x|| ||q||, which the filter bound allows for.  Points and queries are first
+//     x = xh + xl + xr,  |xl| <= 2^-8 |x|,  |xr| <= 2^-17 |x|  (round to nearest, 8 significant
+//     bits a piece),  q likewise,  ||x||^2 = nh + nm + nl exactly
+//     key = sum_t  xh_t (-2 qh_t) + xh_t (-2 ql_t) + xl_t (-2 qh_t) + xl_t (-2 ql_t)
+//           +  (nh + nm + nl) * 1
+// (15 of 16 slots at d = 3, products of two bf16 values are exact in fp32).  What is left out,
+// -2 (xr q + x qr - xr qr), is at most 2^-15 (1 + 2^-16) ||x|| ||q||, which the filter bound
+// allows for; d = 4 and d = 8 have no slots for xl ql, there the bound is twice that plus
+// 2^-15.  Points and queries are first
 // moved by the midpoint of the points' bounding box, so that bound scales with the spread of
 // the data, not with its offset from the origin.  The filter only decides which pairs go to
 // the exact test; that test reads the point's original fp32 coordinates from X and is the
@@ -804,13 +808,16 @@ __device__ __forceinline__ float seed_bound(const SeedGrid<D>& g, const int* __r
     return kInf;
 }
 
-// K slots of the filter's contraction for dimension D (3 D + 3 of them, padded with zeros to
-// NM MFMAs of 16 slots): slot s < D pairs xh_s with -2 qh_s, D <= s < 2D pairs xh with -2 ql,
-// 2D <= s < 3D pairs xl with -2 qh, and the three pieces of the squared norm meet 1.
+// K slots of the filter's contraction for dimension D, padded with zeros to NM MFMAs of 16
+// slots: slot s < D pairs xh_s with -2 qh_s, D <= s < 2D pairs xh with -2 ql, 2D <= s < 3D pairs
+// xl with -2 qh; where 4 D + 3 slots fit into the same number of MFMAs (all D but 4 and 8) the
+// slots 3D <= s < 4D pair xl with -2 ql as well; the three pieces of the squared norm meet 1.
 template <int D>
 struct FilterSlots {
-    static constexpr int kUsed = 3 * D + 3;
-    static constexpr int kMfmas = (kUsed + 15) / 16;  // 1 for D <= 4, 2 for D <= 8
+    static constexpr int kMfmas = (3 * D + 3 + 15) / 16;  // 1 for D <= 4, 2 for D <= 8
+    static constexpr bool kLowLow = 4 * D + 3 <= 16 * kMfmas;
+    static constexpr int kProducts = (kLowLow ? 4 : 3) * D;  // slots before the norm pieces
+    static constexpr int kUsed = kProducts + 3;
 };
 
 // A-operand piece of slot s: xh / xl are the bf16 pieces of the moved coordinates, np the three
@@ -818,18 +825,21 @@ struct FilterSlots {
 template <int D>
 __device__ __forceinline__ unsigned slot_a(int s, const unsigned (&xh)[D], const unsigned (&xl)[D],
                                            const unsigned (&np)[3]) {
+    constexpr int P = FilterSlots<D>::kProducts;
     if (s < 2 * D) return xh[s < D ? s : s - D];
-    if (s < 3 * D) return xl[s - 2 * D];
-    if (s < 3 * D + 3) return np[s - 3 * D];
+    if (s < P) return xl[s < 3 * D ? s - 2 * D : s - 3 * D];
+    if (s < P + 3) return np[s - P];
     return 0u;
 }
 // B-operand piece of slot s: qh / ql hold the bf16 bits of -2 qh_t and -2 ql_t
 template <int D>
 __device__ __forceinline__ unsigned slot_b(int s, const unsigned (&qh)[D], const unsigned (&ql)[D]) {
+    constexpr int P = FilterSlots<D>::kProducts;
     if (s < D) return qh[s];
     if (s < 2 * D) return ql[s - D];
     if (s < 3 * D) return qh[s - 2 * D];
-    if (s < 3 * D + 3) return 0x3f80u;  // 1.0
+    if (s < P) return ql[s - 3 * D];
+    if (s < P + 3) return 0x3f80u;  // 1.0
     return 0u;
 }
 
@@ -932,12 +942,16 @@ __global__ __launch_bounds__(256, FilterSlots<D>::kMfmas == 1 ? 4 : 3) void knn_
     int taui[NS], cnt[NS];  // (tau, taui): key and index of the query's current k-th best
     float tcap[NS];         // upper bound of the k-th smallest distance known before the scan
     // A pair with exact fp32 distance <= tau has a filter key below (tau - qn) + slack: the cross
-    // terms the bf16 pieces leave out (<= 6.1 * 2^-18 ||x'|| ||q'|| < 2^-15 sqrt(xmax qn)), the
-    // fp32 roundings of the accumulation, of qn, of the moved coordinates and of the distance
-    // itself (each a few 2^-24 of ||x'||^2 + ||q'||^2 + tau; 2^-19 of that sum is several times
-    // their total).
+    // terms the bf16 pieces leave out (<= kCross ||x'|| ||q'|| <= kCross sqrt(xmax qn)), the
+    // fp32 roundings of the accumulation (16 NM additions of terms whose magnitudes sum to at
+    // most 2.01 (xmax + qn): 2^-19 NM of that sum if the matrix core rounds after every one), of
+    // qn, of the moved coordinates and of the distance itself (a few 2^-24 each): kSum of
+    // ||x'||^2 + ||q'||^2 + tau covers twice their total.
+    // (with the xl ql products: 2 (2^-17 + 2^-17 + 2^-34); without: 2 2^-16 (1 + 2^-7) more)
+    constexpr float kCross = FilterSlots<D>::kLowLow ? 0x1p-15f * 1.001f : 0x1p-14f * 1.006f;
+    constexpr float kSum = NM == 1 ? 0x1p-18f : 0x1p-17f;
     auto key_bound = [&](int st, float t) {
-        return (t - qn[st]) + (cross[st] + 0x1p-19f * (xmax + qn[st] + t));
+        return (t - qn[st]) + (cross[st] + kSum * (xmax + qn[st] + t));
     };
 #pragma unroll
     for (int st = 0; st < NS; ++st) {
@@ -952,7 +966,7 @@ __global__ __launch_bounds__(256, FilterSlots<D>::kMfmas == 1 ? 4 : 3) void knn_
         qn[st] = qc[0] * qc[0];
 #pragma unroll
         for (int t = 1; t < D; ++t) qn[st] = fmaf(qc[t], qc[t], qn[st]);
-        cross[st] = 0x1p-15f * sqrtf(xmax * qn[st]);
+        cross[st] = kCross * sqrtf(xmax * qn[st]);
         // B operands: the pieces -2 qh, -2 ql and 1 in the slot order of FilterSlots; a lane of
         // half h holds slots 8h .. 8h + 7 of each MFMA
         unsigned qh[D], ql[D];
@@ -1124,7 +1138,7 @@ __global__ __launch_bounds__(256, FilterSlots<D>::kMfmas == 1 ? 4 : 3) void knn_
         }
     }
     if (jb < j1) {  // ragged tail: rows past the range read a valid row and get ||x||^2 = +inf
-        constexpr int kNormSlot = 3 * D;  // slot of the leading piece of the squared norm
+        constexpr int kNormSlot = FilterSlots<D>::kProducts;  // leading piece of the squared norm
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
             const int row = jb + u * 32 + i32;

@@ -3,10 +3,10 @@
 // fp32 test of the few pairs that pass it.
 //
 // An fp32 MFMA delivers 256 flops per cycle and compute unit, a bf16 MFMA 4096.  Every fp32 value
-// is cut into two bf16 pieces, v = vh + vl + (|rest| <= 2^-18 |v|), and the dot product is taken
-// as  sum_t xh_t qh_t + xh_t ql_t + xl_t qh_t : three bf16 MFMAs per 16 coordinates instead of
-// eight fp32 ones of twice the length each, products exact in fp32.  What is left out is at most
-// 3 * 2^-18 |x| |q| (doubled by the factor -2); the filter threshold allows for it and for every
+// is cut into two bf16 pieces, v = vh + vl + vr with |vl| <= 2^-8 |v|, |vr| <= 2^-17 |v|, and the
+// dot product is taken as  sum_t xh_t qh_t + xh_t ql_t + xl_t qh_t : three bf16 MFMAs per 16
+// coordinates instead of eight fp32 ones of twice the length each, products exact in fp32.  What
+// is left out is at most 2^-15 |x| |q| (doubled by the factor -2); the filter threshold allows for it and for every
 // fp32 rounding on the way, so no pair at or below a query's current k-th distance is lost.  The
 // pairs that pass are buffered per query and, when a buffer is full, evaluated exactly (fp32
 // difference form, fixed summation order) and merged into the query's list; the list keys and
@@ -258,11 +258,14 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     const float xmax = __uint_as_float(hdr[0]);
     // Filter keys are  xn_j - 2 (xh.qh + xh.ql + xl.qh)  accumulated in fp32; the exact test
     // gives  dd = sum (q - x)^2  in fp32.  dd <= tau implies key < (tau - qn) + slack with
-    //   dropped products            6 * 2^-18 |x| |q|            (|x| |q| <= sqrt(xmax qn))
+    //   dropped products            2 (xl ql + xr q + x qr): with |xl| <= 2^-8 (1 + 2^-8) |x| and
+    //                               |xr| <= 2^-17 |x| per coordinate (round to nearest, 8
+    //                               significant bits a piece) at most 1.004 * 2^-14 |x| |q|,
+    //                               and |x| |q| <= sqrt(xmax qn)
     //   3 d fp32 accumulations       of terms that sum to at most 2.02 |x| |q| in magnitude
     //   roundings of xn, qn, dd      each below (d / 64 + 8) ulps of the value
-    // The constants below are at least twice those sums.
-    const float e_dot = 6.2f * 0x1p-18f + (float)(12 * d + 32) * 0x1p-24f;
+    // The constants below cover the first in full and are at least twice the others.
+    const float e_dot = 1.01f * 0x1p-14f + (float)(12 * d + 32) * 0x1p-24f;
     const float e_sum = (float)(d + 16) * 0x1p-23f;
     // own = k-th key of this range's list (+inf until it is full, -inf for a lane without a
     // query), cap = the lowest k-th key any range of the query has published, tauf = the filter
