@@ -415,18 +415,16 @@ def main() -> int:
     traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
     hbm_equiv = (pairs_per_launch / avg_launch_s) * 8.0 / (PEAK_HBM_GBS * 1e9)
     if plan.path == K.KNN_PATH_MFMA_SPLIT:
-        # The -2 Q X^T contraction runs as three bf16 products per coordinate pair (values cut
-        # into two bf16 pieces): 6 d bf16 flops per pair on the matrix cores, with d rounded
-        # up to the 16 coordinates of a pipeline step, against the dense bf16 peak.
+        # The -2 Q X^T contraction of the filter runs on bf16 roundings of the values: 2 d bf16
+        # flops per pair on the matrix cores, with d rounded up to the 16 coordinates of an MFMA,
+        # against the dense bf16 peak.
         d_pad = (w.d + 15) // 16 * 16
-        flops = 6.0 * d_pad * pairs_per_launch
+        flops = 2.0 * d_pad * pairs_per_launch
         achieved = flops / avg_launch_s / 1e12
         roofline = {"bound": "mfma", "kernel": "knn_split_kernel", "achieved": achieved,
                     "peak": PEAK_BF16_MATRIX_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_BF16_MATRIX_TFLOPS, "traffic": traffic,
-                    "flops_per_pair": 6 * d_pad,
-                    # the same launch priced as the 2 d flops per pair of the plain contraction
-                    "contraction_tflops": 2.0 * w.d * pairs_per_launch / avg_launch_s / 1e12}
+                    "flops_per_pair": 2 * d_pad}
     elif plan.path == K.KNN_PATH_LOWD_MFMA:
         # filter contraction over K = 4: [x0 x1 x2 |x|^2] . [-2q0 -2q1 -2q2 1]
         flops = 2.0 * 4 * pairs_per_launch

@@ -158,7 +158,7 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     unsigned char* hdr = ws + align_up((uint64_t)n * 4);
     unsigned char* qs = ws + plan.norms_bytes;
     float* qn = reinterpret_cast<float*>(
-        qs + align_up((uint64_t)plan.chunk_rows * 64 * (((uint64_t)d + kSpKC - 1) / kSpKC)));
+        qs + align_up((uint64_t)plan.chunk_rows * 32 * (((uint64_t)d + kSpKC - 1) / kSpKC)));
     unsigned char* tsh = reinterpret_cast<unsigned char*>(qn) + align_up((uint64_t)plan.chunk_rows * 4);
     unsigned char* lists = ws + plan.norms_bytes + plan.query_bytes;
     float* lk = reinterpret_cast<float*>(lists);

@@ -46,7 +46,7 @@ constexpr int kSpTileQ = 32 * kSpWaves;
 constexpr int kSpTileX = 128;
 constexpr int kSpKC = 16;            // coordinates per pipeline step (three MFMAs of 16 K slots)
 constexpr int kSpCand = 32;          // buffered point indices per query (LDS)
-constexpr int kSpResidentMaxChunks = 8;  // d <= 128: the queries' B operands stay in registers
+constexpr int kSpResidentMaxChunks = 16;  // d <= 256: the queries' B operands stay in registers
 constexpr int kSpRoom = 8;           // a buffer with fewer free slots than this is emptied after the tile
 
 // Workgroups the chip holds at once (LDS-limited): the planner sizes launches in rounds of these.

@@ -55,6 +55,12 @@ __device__ __forceinline__ void split8(const f32x4& x0, const f32x4& x1, float s
     split_pair(x1[2], x1[3], scale, hi.w, lo.w);
 }
 
+// bf16 (round to nearest even) of two floats in one word, the first in the low half
+__device__ __forceinline__ unsigned round_pair(float a, float b) {
+    const f32x2 p = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(p, bf16x2));
+}
+
 // floats <-> unsigned words with the same order (for atomicMin on keys of either sign)
 __device__ __forceinline__ unsigned key_word(float f) {
     const unsigned u = __float_as_uint(f);
@@ -80,8 +86,8 @@ __global__ __launch_bounds__(256) void knn_max_norm_kernel(const float* __restri
     if ((threadIdx.x & 63) == 0) atomicMax(hdr, __float_as_uint(m));
 }
 
-// B operands of the queries of one chunk: per row and 16-coordinate chunk 64 bytes,
-// [-2 qh: coordinates 0..7 | -2 qh: 8..15 | -2 ql: 0..7 | -2 ql: 8..15], zero past d.
+// B operands of the queries of one chunk: per row and 16-coordinate chunk 32 bytes,
+// [bf16(-2 q): coordinates 0..7 | 8..15], zero past d.
 template <bool ALIGNED>
 __global__ __launch_bounds__(256) void knn_split_queries_kernel(const float* __restrict__ Q,
                                                                 int64_t ldq, int rows, int d,
@@ -99,11 +105,9 @@ __global__ __launch_bounds__(256) void knn_split_queries_kernel(const float* __r
             mask_row4(load_row4<ALIGNED>(Q, ldq, r, rows, col + 4, d), true, col + 4, d, 1.f);
         split8(v0, v1, -2.f, hi[half], lo[half]);
     }
-    uint4* o = Qs + idx * 4;
+    uint4* o = Qs + idx * 2;
     o[0] = hi[0];
     o[1] = hi[1];
-    o[2] = lo[0];
-    o[3] = lo[1];
 }
 
 // One lane's share of the exact key of a candidate - sum_t (q_t - x_t)^2, or with DOT the
@@ -239,8 +243,8 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     const int nch = NCH > 0 ? NCH : nch_real;
     constexpr int TQ = kSpTileQ, TX = kSpTileX, C = kSpCand;
     extern __shared__ __align__(16) unsigned char smem[];
-    uint4* as = reinterpret_cast<uint4*>(smem);                  // [2 buffers][2 pieces][TX][2]
-    float* xns = reinterpret_cast<float*>(as + 2 * 2 * TX * 2);  // [2][TX] accumulator start values
+    uint4* as = reinterpret_cast<uint4*>(smem);              // [2 buffers][TX][2 halves of 8 bf16]
+    float* xns = reinterpret_cast<float*>(as + 2 * TX * 2);  // [2][TX] accumulator start values
     float* rns = xns + 2 * TX;                                   // [2][TX] row scales (cosine)
     int* ci = reinterpret_cast<int*>(rns + 2 * TX);              // [TQ][C] buffered point indices
     const int tid = threadIdx.x;
@@ -265,7 +269,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     //   3 d fp32 accumulations       of terms that sum to at most 2.02 |x| |q| in magnitude
     //   roundings of xn, qn, dd      each below (d / 64 + 8) ulps of the value
     // The constants below cover the first in full and are at least twice the others.
-    const float e_dot = 1.01f * 0x1p-14f + (float)(12 * d + 32) * 0x1p-24f;
+    const float e_dot = 1.01f * 0x1p-6f + (float)(4 * d + 32) * 0x1p-24f;
     const float e_sum = (float)(d + 16) * 0x1p-23f;
     // own = k-th key of this range's list (+inf until it is full, -inf for a lane without a
     // query), cap = the lowest k-th key any range of the query has published, tauf = the filter
@@ -279,7 +283,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     float cap = kInf;
     float tauf = own;
     int cnt = 0, ovf = 0;
-    const uint4* const qb = Qs + (size_t)qrow * nch_real * 4 + h;
+    const uint4* const qb = Qs + (size_t)qrow * nch_real * 2 + h;
     // (the smallest normal number keeps the bound strict when every value involved is zero).
     // Cosine metric (xn holds 1 / |x|): filter key = -2 (xh.qh + xh.ql + xl.qh) / |x|, exact key
     // = -2 (q.x) / |x| from an fp32 dot product; |x| / |x| = 1 leaves e_dot |q| for the
@@ -380,7 +384,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
         float xnv;
     };
     struct QB {
-        uint4 hi, lo;
+        uint4 hi;
     };
     int f_tile = 0, f_c = 0;  // (tile, chunk) of the next fetch
     const float* frow = X + (int64_t)min(j0 + srow, j1 - 1) * ldx;  // this thread's row of tile f_tile
@@ -396,11 +400,10 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     int s_tile = 0, s_c = 0;  // (tile, chunk) of the next stash
     uint2* const as_w = reinterpret_cast<uint2*>(as) + srow * 4 + squad;
     auto stash = [&](int buf, const XS& g) {
-        uint2 hi, lo;
-        split_pair(g.x0[0], g.x0[1], 1.f, hi.x, lo.x);
-        split_pair(g.x0[2], g.x0[3], 1.f, hi.y, lo.y);
-        as_w[(buf * 2 + 0) * TX * 4] = hi;
-        as_w[(buf * 2 + 1) * TX * 4] = lo;
+        uint2 hi;
+        hi.x = round_pair(g.x0[0], g.x0[1]);
+        hi.y = round_pair(g.x0[2], g.x0[3]);
+        as_w[buf * TX * 4] = hi;
         if (s_c == 0 && tid < TX) {  // +inf past the range: such a row never passes
             const bool ok = j0 + s_tile * TX + tid < j1;
             // xn is |x|^2, or for the cosine metric 1 / |x|: then the sums start from 0 and are
@@ -414,8 +417,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
         }
     };
     auto fetchQ = [&](int c, QB& g) {
-        g.hi = qb[c * 4];
-        g.lo = qb[c * 4 + 2];
+        g.hi = qb[c * 2];
     };
 
     f32x16 acc[4];
@@ -447,19 +449,14 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     const uint4* const as_r = as + i32 * 2 + h;
     // one (tile, chunk) step: MFMAs on LDS buffer `par` with the given B operands, the next
     // step's points go to the other buffer meanwhile; last = the tile's last chunk
-    auto step_fn = [&](int step, int par, bool last, const uint4& bhi, const uint4& blo, XS& mine,
-                       const XS& next) {
+    auto step_fn = [&](int step, int par, bool last, const uint4& bhi, XS& mine, const XS& next) {
         fetchX(mine);
-        const uint4* ab = as_r + par * (2 * TX * 2);
+        const uint4* ab = as_r + par * (TX * 2);
         const bf16x8 bh = __builtin_bit_cast(bf16x8, bhi);
-        const bf16x8 bl = __builtin_bit_cast(bf16x8, blo);
 #pragma unroll
         for (int pb = 0; pb < 4; ++pb) {
             const bf16x8 xh = __builtin_bit_cast(bf16x8, ab[pb * 64]);
-            const bf16x8 xl = __builtin_bit_cast(bf16x8, ab[TX * 2 + pb * 64]);
             acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, bh, acc[pb], 0, 0, 0);
-            acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, bl, acc[pb], 0, 0, 0);
-            acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, bh, acc[pb], 0, 0, 0);
             if (pb == 1 && step + 1 < total) stash(par ^ 1, next);
         }
         if (last) {
@@ -490,7 +487,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
             fetchQ(c + 1 == nch ? 0 : c + 1, bnext);
             const bool last = c == nch - 1;
             c = last ? 0 : c + 1;
-            step_fn(step, par, last, bcur.hi, bcur.lo, mine, next);
+            step_fn(step, par, last, bcur.hi, mine, next);
         };
         for (int step = 0; step < total; step += 2) {
             body(step, 0, xe, xo, be, bo);
@@ -498,12 +495,11 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
         }
     } else {
         constexpr int NR = NCH > 0 ? NCH : 1;
-        uint4 bqh[NR], bql[NR];
+        uint4 bqh[NR];
 #pragma unroll
         for (int c = 0; c < NR; ++c) {
             const uint4 zero = {0u, 0u, 0u, 0u};
-            bqh[c] = c < nch_real ? qb[(c < nch_real ? c : 0) * 4] : zero;
-            bql[c] = c < nch_real ? qb[(c < nch_real ? c : 0) * 4 + 2] : zero;
+            bqh[c] = c < nch_real ? qb[(c < nch_real ? c : 0) * 2] : zero;
         }
         constexpr int TU = (NR % 2) ? 2 : 1;  // tiles per unrolled iteration
         for (int tile0 = 0; tile0 < ntiles; tile0 += TU) {
@@ -514,9 +510,9 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
                 for (int c = 0; c < NR; ++c) {
                     const int step = (tile0 + tt) * NR + c;
                     if (((tt * NR + c) & 1) == 0)
-                        step_fn(step, 0, c == NR - 1, bqh[c], bql[c], xe, xo);
+                        step_fn(step, 0, c == NR - 1, bqh[c], xe, xo);
                     else
-                        step_fn(step, 1, c == NR - 1, bqh[c], bql[c], xo, xe);
+                        step_fn(step, 1, c == NR - 1, bqh[c], xo, xe);
                 }
             }
         }
@@ -563,7 +559,7 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
                         int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
                         hipStream_t stream) {
     const int nch = (d + kSpKC - 1) / kSpKC;
-    const size_t lds = (size_t)2 * 2 * kSpTileX * 2 * 16 + (size_t)4 * kSpTileX * 4 +
+    const size_t lds = (size_t)2 * kSpTileX * 2 * 16 + (size_t)4 * kSpTileX * 4 +
                        (size_t)kSpTileQ * kSpCand * 4 + (size_t)kSpWaves * (2 * kWave + 2 * k) * 4;
     int64_t split_len = (n + S - 1) / S;
     split_len = (split_len + kSpTileX - 1) / kSpTileX * kSpTileX;
@@ -599,7 +595,9 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
     else if (nch <= 3) KNN_SPLIT_LAUNCH(3);
     else if (nch <= 4) KNN_SPLIT_LAUNCH(4);
     else if (nch <= 6) KNN_SPLIT_LAUNCH(6);
-    else if (nch <= kSpResidentMaxChunks) KNN_SPLIT_LAUNCH(8);
+    else if (nch <= 8) KNN_SPLIT_LAUNCH(8);
+    else if (nch <= 12) KNN_SPLIT_LAUNCH(12);
+    else if (nch <= kSpResidentMaxChunks) KNN_SPLIT_LAUNCH(16);
     else KNN_SPLIT_LAUNCH(0);
 #undef KNN_SPLIT_LAUNCH
 #undef KNN_SPLIT_LAUNCH_A

@@ -135,7 +135,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     out->norms_bytes = lowd ? 0 : align_up((uint64_t)n * 4) + (split ? kAlign : 0);
     const bool l1 = metric == KNN_METRIC_L1;
     const int qkind = split ? 1 : (l1 ? 2 : 0);
-    const uint64_t qrow = split ? 64ull * (((uint64_t)d + kSpKC - 1) / kSpKC)
+    const uint64_t qrow = split ? 32ull * (((uint64_t)d + kSpKC - 1) / kSpKC)
                                 : (l1 ? 16ull * (((uint64_t)d + 3) / 4) : 0);
     {
         const int64_t t0 = out->tile_q;

@@ -103,15 +103,18 @@ def test_min_limit_is_exact_boundary():
 
 def test_small_limits_cut_queries_into_chunks_and_never_exceed_the_limit():
     m, n, d, k = 50_000, 2_000_000, 256, 32
-    prev_chunks = None
+    prev_lists = None
     for limit in [8_400_000, 8_700_000, 9_000_000, 12_000_000, 20_000_000, 50_000_000, 128_000_000, 10 ** 9]:
         p = K.knn_plan(m, n, d, k, limit)
         assert p.workspace_bytes <= limit
         assert p.chunk_rows >= p.tile_q or p.chunk_rows == m
-        if prev_chunks is not None:
-            assert p.q_chunks <= prev_chunks  # more memory never means more passes
-        prev_chunks = p.q_chunks
+        # more memory never means fewer (query, range) lists in flight; the chunk count itself
+        # may go up when the plan trades rows for ranges (more workgroups per launch)
+        if prev_lists is not None:
+            assert p.chunk_rows * p.n_splits >= prev_lists
+        prev_lists = p.chunk_rows * p.n_splits
     assert K.knn_plan(m, n, d, k, 8_400_000).q_chunks > 1
+    assert K.knn_plan(m, n, d, k, 10 ** 9).q_chunks == 1
 
 
 def test_low_d_falls_back_to_the_vector_path_when_packed_points_do_not_fit():
@@ -160,7 +163,7 @@ def test_threshold_seed_grid_is_sized_from_n_and_k_and_paid_for_under_the_limit(
 
 
 def test_split_path_accounts_for_the_per_query_data_and_uses_every_byte_it_can():
-    # path 5 (d > 8, squared-Euclidean): per query 64 bytes per 16 coordinates of split B
+    # path 5 (d > 8, squared-Euclidean): per query 32 bytes per 16 coordinates of bf16 B
     # operands, a squared norm and a shared-threshold word, each array 256-aligned; the chunk is
     # the longest multiple of the query tile that fits with them
     import random
@@ -180,14 +183,14 @@ def test_split_path_accounts_for_the_per_query_data_and_uses_every_byte_it_can()
         assert p.path == K.KNN_PATH_MFMA_SPLIT and p.tile_q == 256
         nch = (d + 15) // 16
         assert p.norms_bytes == up(4 * n) + 256
-        assert p.query_bytes == up(p.chunk_rows * nch * 64) + 2 * up(p.chunk_rows * 4)
+        assert p.query_bytes == up(p.chunk_rows * nch * 32) + 2 * up(p.chunk_rows * 4)
         assert p.lists_bytes == 2 * up(p.chunk_rows * p.n_splits * k * 4)
         assert p.workspace_bytes == p.norms_bytes + p.query_bytes + p.lists_bytes <= limit
         assert p.chunk_rows == m or p.chunk_rows % 256 == 0
         assert p.q_chunks == -(-m // p.chunk_rows)
         if p.chunk_rows < m and p.chunk_rows < (1 << 22):  # a longer chunk would not have fitted
             r = p.chunk_rows + 256
-            more = up(r * nch * 64) + 2 * up(r * 4) + 2 * up(r * p.n_splits * k * 4)
+            more = up(r * nch * 32) + 2 * up(r * 4) + 2 * up(r * p.n_splits * k * 4)
             assert p.norms_bytes + more > limit
         with pytest.raises(K.KnnError):
             K.knn_plan(m, n, d, k, lo - 1)
