@@ -231,20 +231,20 @@ __device__ __noinline__ unsigned split_flush_query(const float* __restrict__ qp,
 // operands of the next chunk are fetched from the workspace in every step; that doubles to
 // triples the traffic (bytes per pair and coordinate: 4 / 256 for the points, 4 / 128 for the
 // queries), which is what bounds the kernel there.
-template <int NCH, bool ALIGNED>
+template <int W, int NST, bool ALIGNED>
 __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
     const uint4* __restrict__ Qs, const float* __restrict__ qnorm, unsigned* tsh,
     const float* __restrict__ xn, const unsigned* __restrict__ hdr, int cosine, int rows, int n,
     int d, int nch_real, int k, int S, int split_len, int BQ, int BS, float* __restrict__ lk,
     int* __restrict__ li) {
-    // chunks per tile that the pipeline walks: all of NCH when the queries are resident (the
-    // ones past the real count meet zero B operands)
-    const int nch = NCH > 0 ? NCH : nch_real;
+    // steps per tile that the pipeline walks, W chunks of 16 coordinates each (the chunks past
+    // the real count meet zero B operands)
+    const int nst = NST > 0 ? NST : (nch_real + W - 1) / W;
     constexpr int TQ = kSpTileQ, TX = kSpTileX, C = kSpCand;
     extern __shared__ __align__(16) unsigned char smem[];
-    uint4* as = reinterpret_cast<uint4*>(smem);              // [2 buffers][TX][2 halves of 8 bf16]
-    float* xns = reinterpret_cast<float*>(as + 2 * TX * 2);  // [2][TX] accumulator start values
+    uint4* as = reinterpret_cast<uint4*>(smem);  // [2 buffers][W chunks][TX][2 halves of 8 bf16]
+    float* xns = reinterpret_cast<float*>(as + 2 * W * TX * 2);  // [2][TX] accumulator start values
     float* rns = xns + 2 * TX;                                   // [2][TX] row scales (cosine)
     int* ci = reinterpret_cast<int*>(rns + 2 * TX);              // [TQ][C] buffered point indices
     const int tid = threadIdx.x;
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     //   3 d fp32 accumulations       of terms that sum to at most 2.02 |x| |q| in magnitude
     //   roundings of xn, qn, dd      each below (d / 64 + 8) ulps of the value
     // The constants below cover the first in full and are at least twice the others.
-    const float e_dot = 1.01f * 0x1p-6f + (float)(4 * d + 32) * 0x1p-24f;
+    const float e_dot = 1.01f * 0x1p-6f + (float)(4 * (nst * W * 16) + 32) * 0x1p-24f;
     const float e_sum = (float)(d + 16) * 0x1p-23f;
     // own = k-th key of this range's list (+inf until it is full, -inf for a lane without a
     // query), cap = the lowest k-th key any range of the query has published, tauf = the filter
@@ -298,7 +298,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     const int j0 = s * split_len;
     const int j1 = min(n, j0 + split_len);
     const int ntiles = (j1 > j0) ? (j1 - j0 + TX - 1) / TX : 0;
-    const int total = ntiles * nch;
+    const int total = ntiles * nst;
 
     // ---- rare path, only entered while the accumulators are dead (between two tiles) ----
     float* const my_scratch =
@@ -380,30 +380,35 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     const int srow = tid >> 2;
     const int squad = tid & 3;
     struct XS {
-        f32x4 x0;
+        f32x4 x[W];
         float xnv;
     };
     struct QB {
-        uint4 hi;
+        uint4 b[W];
     };
-    int f_tile = 0, f_c = 0;  // (tile, chunk) of the next fetch
+    int f_tile = 0, f_c = 0;  // (tile, step) of the next fetch
     const float* frow = X + (int64_t)min(j0 + srow, j1 - 1) * ldx;  // this thread's row of tile f_tile
     auto fetchX = [&](XS& g) {
-        g.x0 = load_row4<ALIGNED>(frow, 0, 0, 1, f_c * 16 + squad * 4, d);
+#pragma unroll
+        for (int kk = 0; kk < W; ++kk)
+            g.x[kk] = load_row4<ALIGNED>(frow, 0, 0, 1, (f_c * W + kk) * 16 + squad * 4, d);
         if (f_c == 0) g.xnv = xn[min(j0 + f_tile * TX + (tid & (TX - 1)), j1 - 1)];
-        if (++f_c == nch) {
+        if (++f_c == nst) {
             f_c = 0;
             if (f_tile + 1 < ntiles) ++f_tile;
             frow = X + (int64_t)min(j0 + f_tile * TX + srow, j1 - 1) * ldx;
         }
     };
-    int s_tile = 0, s_c = 0;  // (tile, chunk) of the next stash
+    int s_tile = 0, s_c = 0;  // (tile, step) of the next stash
     uint2* const as_w = reinterpret_cast<uint2*>(as) + srow * 4 + squad;
     auto stash = [&](int buf, const XS& g) {
-        uint2 hi;
-        hi.x = round_pair(g.x0[0], g.x0[1]);
-        hi.y = round_pair(g.x0[2], g.x0[3]);
-        as_w[buf * TX * 4] = hi;
+#pragma unroll
+        for (int kk = 0; kk < W; ++kk) {
+            uint2 hi;
+            hi.x = round_pair(g.x[kk][0], g.x[kk][1]);
+            hi.y = round_pair(g.x[kk][2], g.x[kk][3]);
+            as_w[(buf * W + kk) * TX * 4] = hi;
+        }
         if (s_c == 0 && tid < TX) {  // +inf past the range: such a row never passes
             const bool ok = j0 + s_tile * TX + tid < j1;
             // xn is |x|^2, or for the cosine metric 1 / |x|: then the sums start from 0 and are
@@ -411,13 +416,19 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
             xns[(s_tile & 1) * TX + tid] = ok ? (cosine ? 0.f : g.xnv) : kInf;
             rns[(s_tile & 1) * TX + tid] = (ok && cosine) ? g.xnv : 1.f;
         }
-        if (++s_c == nch) {
+        if (++s_c == nst) {
             s_c = 0;
             ++s_tile;
         }
     };
-    auto fetchQ = [&](int c, QB& g) {
-        g.hi = qb[c * 2];
+    auto fetchQ = [&](int c, QB& g) {  // the B operands of step c; zero past the real chunks
+#pragma unroll
+        for (int kk = 0; kk < W; ++kk) {
+            const int ch = c * W + kk;
+            const uint4 v = qb[(ch < nch_real ? ch : nch_real - 1) * 2];
+            const uint4 zero = {0u, 0u, 0u, 0u};
+            g.b[kk] = ch < nch_real ? v : zero;
+        }
     };
 
     f32x16 acc[4];
@@ -447,17 +458,20 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     if (total > 0) start_tile(0);
     int tile = 0;
     const uint4* const as_r = as + i32 * 2 + h;
-    // one (tile, chunk) step: MFMAs on LDS buffer `par` with the given B operands, the next
-    // step's points go to the other buffer meanwhile; last = the tile's last chunk
-    auto step_fn = [&](int step, int par, bool last, const uint4& bhi, XS& mine, const XS& next) {
+    // one (tile, step) step: MFMAs on LDS buffer `par` with the given B operands, the next
+    // step's points go to the other buffer meanwhile; last = the tile's last step
+    auto step_fn = [&](int step, int par, bool last, const QB& b, XS& mine, const XS& next) {
         fetchX(mine);
-        const uint4* ab = as_r + par * (TX * 2);
-        const bf16x8 bh = __builtin_bit_cast(bf16x8, bhi);
+        const uint4* ab = as_r + par * (W * TX * 2);
 #pragma unroll
-        for (int pb = 0; pb < 4; ++pb) {
-            const bf16x8 xh = __builtin_bit_cast(bf16x8, ab[pb * 64]);
-            acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, bh, acc[pb], 0, 0, 0);
-            if (pb == 1 && step + 1 < total) stash(par ^ 1, next);
+        for (int kk = 0; kk < W; ++kk) {
+            const bf16x8 bh = __builtin_bit_cast(bf16x8, b.b[kk]);
+#pragma unroll
+            for (int pb = 0; pb < 4; ++pb) {
+                const bf16x8 xh = __builtin_bit_cast(bf16x8, ab[kk * TX * 2 + pb * 64]);
+                acc[pb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, bh, acc[pb], 0, 0, 0);
+            }
+            if (kk == (W - 1) / 2 && step + 1 < total) stash(par ^ 1, next);
         }
         if (last) {
             // The last use of this tile's accumulators is the epilogue; they are set again
@@ -479,28 +493,25 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
             __syncthreads();
         }
     };
-    if constexpr (NCH == 0) {
+    if constexpr (NST == 0) {
         QB be, bo;
         if (total > 0) fetchQ(0, be);
         int c = 0;
         auto body = [&](int step, int par, XS& mine, const XS& next, const QB& bcur, QB& bnext) {
-            fetchQ(c + 1 == nch ? 0 : c + 1, bnext);
-            const bool last = c == nch - 1;
+            fetchQ(c + 1 == nst ? 0 : c + 1, bnext);
+            const bool last = c == nst - 1;
             c = last ? 0 : c + 1;
-            step_fn(step, par, last, bcur.hi, mine, next);
+            step_fn(step, par, last, bcur, mine, next);
         };
         for (int step = 0; step < total; step += 2) {
             body(step, 0, xe, xo, be, bo);
             if (step + 1 < total) body(step + 1, 1, xo, xe, bo, be);
         }
     } else {
-        constexpr int NR = NCH > 0 ? NCH : 1;
-        uint4 bqh[NR];
+        constexpr int NR = NST > 0 ? NST : 1;
+        QB bq[NR];
 #pragma unroll
-        for (int c = 0; c < NR; ++c) {
-            const uint4 zero = {0u, 0u, 0u, 0u};
-            bqh[c] = c < nch_real ? qb[(c < nch_real ? c : 0) * 2] : zero;
-        }
+        for (int c = 0; c < NR; ++c) fetchQ(c, bq[c]);
         constexpr int TU = (NR % 2) ? 2 : 1;  // tiles per unrolled iteration
         for (int tile0 = 0; tile0 < ntiles; tile0 += TU) {
 #pragma unroll
@@ -510,9 +521,9 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
                 for (int c = 0; c < NR; ++c) {
                     const int step = (tile0 + tt) * NR + c;
                     if (((tt * NR + c) & 1) == 0)
-                        step_fn(step, 0, c == NR - 1, bqh[c], xe, xo);
+                        step_fn(step, 0, c == NR - 1, bq[c], xe, xo);
                     else
-                        step_fn(step, 1, c == NR - 1, bqh[c], xo, xe);
+                        step_fn(step, 1, c == NR - 1, bq[c], xo, xe);
                 }
             }
         }
@@ -559,8 +570,8 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
                         int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
                         hipStream_t stream) {
     const int nch = (d + kSpKC - 1) / kSpKC;
-    const size_t lds = (size_t)2 * kSpTileX * 2 * 16 + (size_t)4 * kSpTileX * 4 +
-                       (size_t)kSpTileQ * kSpCand * 4 + (size_t)kSpWaves * (2 * kWave + 2 * k) * 4;
+    const size_t lds_fixed = (size_t)4 * kSpTileX * 4 + (size_t)kSpTileQ * kSpCand * 4 +
+                             (size_t)kSpWaves * (2 * kWave + 2 * k) * 4;
     int64_t split_len = (n + S - 1) / S;
     split_len = (split_len + kSpTileX - 1) / kSpTileX * kSpTileX;
     // One workgroup per compute unit is resident, so the (tile, range) pairs go to the 8 XCDs
@@ -574,33 +585,45 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
     const bool aligned = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldq % 4 == 0) &&
                          (ldx % 4 == 0) && (d % 4 == 0);
-#define KNN_SPLIT_LAUNCH_A(N, A)                                                                  \
+#define KNN_SPLIT_LAUNCH(W, N, A)                                                                 \
     do {                                                                                          \
-        hipError_t e2 = raise_lds_limit(knn_split_kernel<N, A>, lds);                             \
+        const size_t lds = lds_fixed + (size_t)2 * (W) * kSpTileX * 2 * 16;                       \
+        hipError_t e2 = raise_lds_limit(knn_split_kernel<W, N, A>, lds);                          \
         if (e2 != hipSuccess) return e2;                                                          \
-        knn_split_kernel<N, A><<<grid, dim3(64 * kSpWaves), lds, stream>>>(                       \
+        knn_split_kernel<W, N, A><<<grid, dim3(64 * kSpWaves), lds, stream>>>(                    \
             Q, ldq, X, ldx, static_cast<const uint4*>(qs), qn, static_cast<unsigned*>(tsh), xn,   \
             static_cast<const unsigned*>(hdr), cosine ? 1 : 0, (int)rows, (int)n, d, nch, k, S,   \
             (int)split_len, BQ, BS, lk, li);                                                      \
     } while (0)
-#define KNN_SPLIT_LAUNCH(N)                                                                       \
-    do {                                                                                          \
-        if (aligned) KNN_SPLIT_LAUNCH_A(N, true);                                                 \
-        else KNN_SPLIT_LAUNCH_A(N, false);                                                        \
-    } while (0)
-    // queries resident in registers up to d = 128 (the template value is the chunk count
-    // rounded up to one that is instantiated)
-    if (nch <= 1) KNN_SPLIT_LAUNCH(1);
-    else if (nch <= 2) KNN_SPLIT_LAUNCH(2);
-    else if (nch <= 3) KNN_SPLIT_LAUNCH(3);
-    else if (nch <= 4) KNN_SPLIT_LAUNCH(4);
-    else if (nch <= 6) KNN_SPLIT_LAUNCH(6);
-    else if (nch <= 8) KNN_SPLIT_LAUNCH(8);
-    else if (nch <= 12) KNN_SPLIT_LAUNCH(12);
-    else if (nch <= kSpResidentMaxChunks) KNN_SPLIT_LAUNCH(16);
-    else KNN_SPLIT_LAUNCH(0);
+    // W chunks of 16 coordinates per pipeline step, N steps per tile with the queries resident
+    // in registers (up to d = 256; W * N is the chunk count rounded up to a shape that is
+    // instantiated), N = 0: any d, queries streamed.  Wide steps keep more bytes of the point
+    // stream in flight, which is what the kernel waits for; the shapes are the fastest measured
+    // among those that fit the register budget (the element-wise loads of unaligned rows need
+    // more registers, so those take narrower steps).
+    if (aligned) {
+        if (nch <= 1) KNN_SPLIT_LAUNCH(1, 1, true);
+        else if (nch <= 2) KNN_SPLIT_LAUNCH(2, 1, true);
+        else if (nch <= 3) KNN_SPLIT_LAUNCH(3, 1, true);
+        else if (nch <= 4) KNN_SPLIT_LAUNCH(4, 1, true);
+        else if (nch <= 6) KNN_SPLIT_LAUNCH(3, 2, true);
+        else if (nch <= 8) KNN_SPLIT_LAUNCH(4, 2, true);
+        else if (nch <= 10) KNN_SPLIT_LAUNCH(2, 5, true);
+        else if (nch <= 12) KNN_SPLIT_LAUNCH(2, 6, true);
+        else if (nch <= kSpResidentMaxChunks) KNN_SPLIT_LAUNCH(2, 8, true);
+        else KNN_SPLIT_LAUNCH(4, 0, true);
+    } else {
+        if (nch <= 1) KNN_SPLIT_LAUNCH(1, 1, false);
+        else if (nch <= 2) KNN_SPLIT_LAUNCH(2, 1, false);
+        else if (nch <= 4) KNN_SPLIT_LAUNCH(2, 2, false);
+        else if (nch <= 6) KNN_SPLIT_LAUNCH(2, 3, false);
+        else if (nch <= 8) KNN_SPLIT_LAUNCH(2, 4, false);
+        else if (nch <= 10) KNN_SPLIT_LAUNCH(2, 5, false);
+        else if (nch <= 12) KNN_SPLIT_LAUNCH(2, 6, false);
+        else if (nch <= kSpResidentMaxChunks) KNN_SPLIT_LAUNCH(2, 8, false);
+        else KNN_SPLIT_LAUNCH(2, 0, false);
+    }
 #undef KNN_SPLIT_LAUNCH
-#undef KNN_SPLIT_LAUNCH_A
     return hipGetLastError();
 }
 
