@@ -63,11 +63,11 @@ typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1, KNN_METRIC_L1 = 2 } k
 #define KNN_PATH_LOWD_BF16 4 /* d <= 8 and room for 32 n bytes (d <= 4) or 64 n bytes: the filter
                                 in bf16 pieces on points moved by their bounding box's midpoint,
                                 same exact test */
-#define KNN_PATH_MFMA_SPLIT 5 /* d > 8, and the cosine metric at any d: every fp32 value cut
-                                 into two bf16 pieces, -2 Q X^T (plus norms) from three bf16
-                                 matrix-core products per coordinate as a filter, exact fp32
-                                 test of the pairs that pass.  (Number 1 was this path's
-                                 fp32 matrix-core predecessor.) */
+#define KNN_PATH_MFMA_SPLIT 5 /* d > 8, and the cosine metric at any d: -2 Q X^T (plus norms)
+                                 from the values rounded to bf16, one matrix-core product per
+                                 coordinate, as a filter whose threshold allows for the
+                                 rounding; exact fp32 test of the pairs that pass.  (Number 1
+                                 was this path's fp32 matrix-core predecessor.) */
 
 /*
  * The plan: how the call is cut into pieces (section 4.3: split the largest
@@ -95,8 +95,8 @@ typedef struct {
                                  and a 256-byte header; path 4: a 256-byte header, 32 bytes
                                  per point and 16 K slots, and seed_cells^d counts;
                                  paths 0, 3: nothing                                   */
-    uint64_t query_bytes;     /* workspace: per-query data of one chunk. path 5: the split
-                                 queries (64 bytes per row and 16 coordinates), their
+    uint64_t query_bytes;     /* workspace: per-query data of one chunk. path 5: the queries
+                                 rounded to bf16 (32 bytes per row and 16 coordinates), their
                                  squared norms and shared thresholds; path 3: the queries
                                  transposed in blocks of 64 rows (16 bytes per row and 4
                                  coordinates); else 0                                  */

@@ -39,12 +39,12 @@ constexpr int kSeedCellsPerPointDen = 3;
 constexpr int kMfmaKC = 16;          // K columns staged in LDS per pipeline step
 constexpr int kMfmaRowStride = 20;   // floats per staged row (16 + 4 pad, keeps 16 B alignment)
 
-// d > kPbMaxD, and the cosine metric: bf16 matrix-core filter on split values + exact fp32 test,
+// d > kPbMaxD, and the cosine metric: bf16 matrix-core filter on rounded values + exact fp32 test,
 // 8 waves, each wave owns 32 queries x 128 points.
 constexpr int kSpWaves = 8;
 constexpr int kSpTileQ = 32 * kSpWaves;
 constexpr int kSpTileX = 128;
-constexpr int kSpKC = 16;            // coordinates per pipeline step (three MFMAs of 16 K slots)
+constexpr int kSpKC = 16;            // coordinates per chunk (one MFMA's K slots); a step takes 1..4
 constexpr int kSpCand = 32;          // buffered point indices per query (LDS)
 constexpr int kSpResidentMaxChunks = 16;  // d <= 256: the queries' B operands stay in registers
 constexpr int kSpRoom = 8;           // a buffer with fewer free slots than this is emptied after the tile

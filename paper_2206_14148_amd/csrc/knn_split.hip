@@ -2,16 +2,16 @@
 // sum x^2 - 2 q.x of paper section 4.1 as a FILTER on the bf16 matrix cores, in front of an exact
 // fp32 test of the few pairs that pass it.
 //
-// An fp32 MFMA delivers 256 flops per cycle and compute unit, a bf16 MFMA 4096.  Every fp32 value
-// is cut into two bf16 pieces, v = vh + vl + vr with |vl| <= 2^-8 |v|, |vr| <= 2^-17 |v|, and the
-// dot product is taken as  sum_t xh_t qh_t + xh_t ql_t + xl_t qh_t : three bf16 MFMAs per 16
-// coordinates instead of eight fp32 ones of twice the length each, products exact in fp32.  What
-// is left out is at most 2^-15 |x| |q| (doubled by the factor -2); the filter threshold allows for it and for every
-// fp32 rounding on the way, so no pair at or below a query's current k-th distance is lost.  The
-// pairs that pass are buffered per query and, when a buffer is full, evaluated exactly (fp32
-// difference form, fixed summation order) and merged into the query's list; the list keys and
-// hence the results do not depend on the filter.  The distance tile still never leaves the
-// registers (section 4.3).
+// An fp32 MFMA delivers 256 flops per cycle and compute unit, a bf16 MFMA 4096.  The filter takes
+// the dot product of the values rounded to bf16 (8 significant bits, relative error <= 2^-8 a
+// value): one bf16 MFMA per 16 coordinates.  Its keys are off by at most 1.002 * 2^-6 |x| |q|;
+// the filter threshold allows for that and for every fp32 rounding on the way, so no pair at or
+// below a query's current k-th distance is lost.  (Two bf16 pieces a value - three MFMAs - give
+// an allowance 256 times smaller and were the first design; the pairs the coarser filter lets
+// through in addition cost far less than the two MFMAs saved.)  The pairs that pass are buffered
+// per query and, when a buffer is full, evaluated exactly (fp32 difference form, fixed summation
+// order) and merged into the query's list; the list keys and hence the results do not depend on
+// the filter.  The distance tile still never leaves the registers (section 4.3).
 #include <hip/hip_runtime.h>
 
 #include <climits>
@@ -29,31 +29,6 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-
-// bf16 pieces (round to nearest even) of two floats: hi = bf16(v), lo = bf16(v - hi), each word
-// holding the first value in its low half.  scale multiplies both pieces (a power of two: exact).
-__device__ __forceinline__ void split_pair(float a, float b, float scale, unsigned& hi, unsigned& lo) {
-    const f32x2 p = {a, b};
-    const bf16x2 hb = __builtin_convertvector(p, bf16x2);
-    const f32x2 hv = __builtin_convertvector(hb, f32x2);
-    const bf16x2 lb = __builtin_convertvector(p - hv, bf16x2);
-    if (scale == 1.f) {
-        hi = __builtin_bit_cast(unsigned, hb);
-        lo = __builtin_bit_cast(unsigned, lb);
-    } else {
-        const f32x2 lv = __builtin_convertvector(lb, f32x2);
-        hi = __builtin_bit_cast(unsigned, __builtin_convertvector(hv * scale, bf16x2));
-        lo = __builtin_bit_cast(unsigned, __builtin_convertvector(lv * scale, bf16x2));
-    }
-}
-
-__device__ __forceinline__ void split8(const f32x4& x0, const f32x4& x1, float scale, uint4& hi,
-                                       uint4& lo) {
-    split_pair(x0[0], x0[1], scale, hi.x, lo.x);
-    split_pair(x0[2], x0[3], scale, hi.y, lo.y);
-    split_pair(x1[0], x1[1], scale, hi.z, lo.z);
-    split_pair(x1[2], x1[3], scale, hi.w, lo.w);
-}
 
 // bf16 (round to nearest even) of two floats in one word, the first in the low half
 __device__ __forceinline__ unsigned round_pair(float a, float b) {
@@ -96,14 +71,16 @@ __global__ __launch_bounds__(256) void knn_split_queries_kernel(const float* __r
     if (idx >= (int64_t)rows * nch) return;
     const int r = (int)(idx / nch);
     const int c = (int)(idx - (int64_t)r * nch);
-    uint4 hi[2], lo[2];
+    uint4 hi[2];
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
         const int col = c * 16 + half * 8;
-        const f32x4 v0 = mask_row4(load_row4<ALIGNED>(Q, ldq, r, rows, col, d), true, col, d, 1.f);
+        const f32x4 v0 = mask_row4(load_row4<ALIGNED>(Q, ldq, r, rows, col, d), true, col, d, -2.f);
         const f32x4 v1 =
-            mask_row4(load_row4<ALIGNED>(Q, ldq, r, rows, col + 4, d), true, col + 4, d, 1.f);
-        split8(v0, v1, -2.f, hi[half], lo[half]);
+            mask_row4(load_row4<ALIGNED>(Q, ldq, r, rows, col + 4, d), true, col + 4, d, -2.f);
+        // (scaling by a power of two and rounding commute)
+        hi[half] = uint4{round_pair(v0[0], v0[1]), round_pair(v0[2], v0[3]), round_pair(v1[0], v1[1]),
+                         round_pair(v1[2], v1[3])};
     }
     uint4* o = Qs + idx * 2;
     o[0] = hi[0];
@@ -206,13 +183,14 @@ __device__ __noinline__ unsigned split_flush_query(const float* __restrict__ qp,
 
 // ---------------------------------------------------------------------------------------
 // One workgroup = 256 queries (8 waves x 32) against a range of the points, in tiles of 128
-// points.  Per 16 coordinates the workgroup loads a 128 x 16 fp32 piece of X (one float4 per
-// thread), splits it into bf16 pieces on the way into LDS (laid out as the MFMA's A operand:
-// 32 bytes per row and piece, the lower half-wave reads coordinates 0..7, the upper 8..15), and
-// every wave runs 4 blocks x 3 MFMAs on it; the queries' B operands were split once per chunk
-// of queries and come straight from the workspace (L2) into registers.  LDS and registers are
-// double-buffered over (tile, chunk) steps, one workgroup barrier per step.  64 accumulator
-// registers per lane leave room for two workgroups per compute unit.
+// points.  A pipeline step covers W chunks of 16 coordinates: the workgroup loads a 128 x 16 W
+// fp32 piece of X (W float4 per thread), rounds it to bf16 on the way into LDS (laid out as the
+// MFMA's A operand: 32 bytes per row and chunk, the lower half-wave reads coordinates 0..7, the
+// upper 8..15), and every wave runs W x 4 MFMAs on it; the queries' B operands were rounded once
+// per chunk of queries and sit in registers (or come from the workspace, see below).  LDS and
+// registers are double-buffered over (tile, step), one workgroup barrier per step, the loads of
+// step s + 2 in flight during step s: wide steps are what keeps enough of the point stream in
+// flight.
 //
 // Nothing of X is masked on the way: coordinates past d meet zeros in the B operands, and rows
 // past the range get +inf as their norm, so whatever valid (finite) data the clamped loads
@@ -225,12 +203,10 @@ __device__ __noinline__ unsigned split_flush_query(const float* __restrict__ qp,
 // they can matter; the merged result is the same.
 // ---------------------------------------------------------------------------------------
 //
-// NCH > 0 (d <= 16 NCH <= 128): the B operands of all NCH chunks stay in registers for the whole
-// kernel, so only the points are streamed; the chunk loop is unrolled (with a second tile when
-// NCH is odd, so that the alternation of the two buffers is static).  NCH == 0: any d, the B
-// operands of the next chunk are fetched from the workspace in every step; that doubles to
-// triples the traffic (bytes per pair and coordinate: 4 / 256 for the points, 4 / 128 for the
-// queries), which is what bounds the kernel there.
+// NST > 0 (d <= 16 W NST <= 256): the B operands of all W NST chunks stay in registers for the
+// whole kernel, so only the points are streamed; the step loop is unrolled (with a second tile
+// when NST is odd, so that the alternation of the two buffers is static).  NST == 0: any d, the
+// B operands of the next step are fetched from the workspace in every step.
 template <int W, int NST, bool ALIGNED>
 __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
@@ -260,13 +236,13 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     init_lists32(lk, li, wave_row0, rows, S, s, k, lane);
 
     const float xmax = __uint_as_float(hdr[0]);
-    // Filter keys are  xn_j - 2 (xh.qh + xh.ql + xl.qh)  accumulated in fp32; the exact test
-    // gives  dd = sum (q - x)^2  in fp32.  dd <= tau implies key < (tau - qn) + slack with
-    //   dropped products            2 (xl ql + xr q + x qr): with |xl| <= 2^-8 (1 + 2^-8) |x| and
-    //                               |xr| <= 2^-17 |x| per coordinate (round to nearest, 8
-    //                               significant bits a piece) at most 1.004 * 2^-14 |x| |q|,
-    //                               and |x| |q| <= sqrt(xmax qn)
-    //   3 d fp32 accumulations       of terms that sum to at most 2.02 |x| |q| in magnitude
+    // Filter keys are  xn_j - 2 bf16(x).bf16(q)  accumulated in fp32; the exact test gives
+    // dd = sum (q - x)^2  in fp32.  dd <= tau implies key < (tau - qn) + slack with
+    //   rounded operands            2 (x q - bf16(x) bf16(q)): each value moves by at most 2^-8
+    //                               of itself (round to nearest, 8 significant bits), so at
+    //                               most 1.002 * 2^-6 |x| |q|, and |x| |q| <= sqrt(xmax qn)
+    //   fp32 accumulations           one per coordinate (padded), of terms that sum to at most
+    //                               2.02 |x| |q| in magnitude
     //   roundings of xn, qn, dd      each below (d / 64 + 8) ulps of the value
     // The constants below cover the first in full and are at least twice the others.
     const float e_dot = 1.01f * 0x1p-6f + (float)(4 * (nst * W * 16) + 32) * 0x1p-24f;
@@ -285,7 +261,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     int cnt = 0, ovf = 0;
     const uint4* const qb = Qs + (size_t)qrow * nch_real * 2 + h;
     // (the smallest normal number keeps the bound strict when every value involved is zero).
-    // Cosine metric (xn holds 1 / |x|): filter key = -2 (xh.qh + xh.ql + xl.qh) / |x|, exact key
+    // Cosine metric (xn holds 1 / |x|): filter key = -2 bf16(x).bf16(q) / |x|, exact key
     // = -2 (q.x) / |x| from an fp32 dot product; |x| / |x| = 1 leaves e_dot |q| for the
     // products, and the roundings of 1 / |x|, of the scaling and of the dot product are ulps of
     // values below 2.02 |q|.
