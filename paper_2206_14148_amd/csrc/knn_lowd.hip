@@ -759,53 +759,153 @@ __global__ void knn_zero_ints_kernel(int* __restrict__ p, int count) {
 }
 
 template <int D>
+__device__ __forceinline__ int seed_cell_of(const SeedGrid<D>& g, const float* __restrict__ x) {
+    int cell = 0;
+#pragma unroll
+    for (int t = D - 1; t >= 0; --t) cell = cell * g.G + seed_cell<D>(g, t, x[t]);
+    return cell;
+}
+
+template <int D>
 __global__ __launch_bounds__(256) void knn_cell_count_kernel(const float* __restrict__ X, int64_t ldx,
                                                              int n, const unsigned* __restrict__ hdr,
-                                                             int G, int* __restrict__ cells) {
+                                                             int G, int* __restrict__ counts) {
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= n) return;
     const SeedGrid<D> g = seed_grid<D>(hdr, G);
-    int cell = 0;
-#pragma unroll
-    for (int t = D - 1; t >= 0; --t) cell = cell * G + seed_cell<D>(g, t, X[(int64_t)j * ldx + t]);
-    atomicAdd(cells + cell, 1);
+    atomicAdd(counts + seed_cell_of<D>(g, X + (int64_t)j * ldx), 1);
 }
 
-// upper bound of the k-th smallest fp32 difference-form squared distance from q to the counted
-// points, +inf when even the 5^D block around q's cell holds fewer than k
+// starts[c] = number of points in the cells before c (starts[ncell] = n); the counts are set
+// back to zero, to serve as the cells' fill cursors.  One workgroup: ncell <= kSeedMaxCells.
+__global__ __launch_bounds__(256) void knn_cell_scan_kernel(int* __restrict__ counts, int ncell,
+                                                            int* __restrict__ starts) {
+    __shared__ int part[256];
+    const int t = threadIdx.x;
+    const int per = (ncell + 255) / 256;
+    const int c0 = min(t * per, ncell), c1 = min(c0 + per, ncell);
+    int sum = 0;
+    for (int c = c0; c < c1; ++c) sum += counts[c];
+    part[t] = sum;
+    __syncthreads();
+    if (t == 0) {
+        int run = 0;
+        for (int i = 0; i < 256; ++i) {
+            const int v = part[i];
+            part[i] = run;
+            run += v;
+        }
+        starts[ncell] = run;
+    }
+    __syncthreads();
+    int run = part[t];
+    for (int c = c0; c < c1; ++c) {
+        starts[c] = run;
+        run += counts[c];
+        counts[c] = 0;
+    }
+}
+
+// the points in cell order: (x0, x1, x2, index bits) at sorted[starts[cell] ...]; the order
+// inside a cell is whatever the atomics give (only sets of points are read from it)
 template <int D>
-__device__ __forceinline__ float seed_bound(const SeedGrid<D>& g, const int* __restrict__ cells,
-                                            const float (&q)[D], int k) {
+__global__ __launch_bounds__(256) void knn_cell_fill_kernel(const float* __restrict__ X, int64_t ldx,
+                                                            int n, const unsigned* __restrict__ hdr,
+                                                            int G, const int* __restrict__ starts,
+                                                            int* __restrict__ cursor,
+                                                            f32x4* __restrict__ sorted) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    const SeedGrid<D> g = seed_grid<D>(hdr, G);
+    const float* x = X + (int64_t)j * ldx;
+    const int cell = seed_cell_of<D>(g, x);
+    const int pos = starts[cell] + atomicAdd(cursor + cell, 1);
+    f32x4 v = {0.f, 0.f, 0.f, __int_as_float(j)};
+#pragma unroll
+    for (int t = 0; t < D; ++t) v[t] = x[t];
+    sorted[pos] = v;
+}
+
+// The smallest block of cells around q's cell (own cell, 3^D, 5^D cells) that holds at least k
+// points; false when even 5^D cells hold fewer.
+template <int D>
+__device__ __forceinline__ bool seed_block(const SeedGrid<D>& g, const int* __restrict__ starts,
+                                           const float (&q)[D], int k, int (&c0)[3], int (&c1)[3]) {
     static_assert(D <= 3, "block walk below is written for up to three axes");
     int cq[3] = {0, 0, 0};
 #pragma unroll
     for (int t = 0; t < D; ++t) cq[t] = seed_cell<D>(g, t, q[t]);
     const int G = g.G;
     for (int R = 0; R <= 2; ++R) {
-        int c0[3] = {0, 0, 0}, c1[3] = {0, 0, 0};
 #pragma unroll
-        for (int t = 0; t < D; ++t) {
-            c0[t] = max(cq[t] - R, 0);
-            c1[t] = min(cq[t] + R, G - 1);
+        for (int t = 0; t < 3; ++t) {
+            c0[t] = t < D ? max(cq[t] - R, 0) : 0;
+            c1[t] = t < D ? min(cq[t] + R, G - 1) : 0;
         }
         int count = 0;
         for (int z = c0[2]; z <= c1[2]; ++z)
-            for (int y = c0[1]; y <= c1[1]; ++y)
-                for (int x = c0[0]; x <= c1[0]; ++x) count += cells[(z * G + y) * G + x];
-        if (count >= k) {
-            float b = 0.f;
-#pragma unroll
-            for (int t = 0; t < D; ++t) {
-                const float lo = (g.mn[t] + (float)c0[t] * g.w[t]) - g.slack[t];
-                const float hi = (g.mn[t] + (float)(c1[t] + 1) * g.w[t]) + g.slack[t];
-                const float far = fmaxf(fabsf(q[t] - lo), fabsf(hi - q[t]));
-                b = fmaf(far, far, b);
+            for (int y = c0[1]; y <= c1[1]; ++y) {
+                const int row = (z * G + y) * G;  // cells of one row are neighbours in memory
+                count += starts[row + c1[0] + 1] - starts[row + c0[0]];
             }
-            // roundings of the bound itself and of the distance it is compared with
-            return b * (1.f + 0x1p-17f);
-        }
+        if (count >= k) return true;
     }
-    return kInf;
+    return false;
+}
+
+// upper bound of the k-th smallest fp32 difference-form squared distance from q to the counted
+// points: all points of the block lie inside it, so the distance to its farthest corner
+template <int D>
+__device__ __forceinline__ float seed_bound(const SeedGrid<D>& g, const float (&q)[D],
+                                            const int (&c0)[3], const int (&c1)[3]) {
+    float b = 0.f;
+#pragma unroll
+    for (int t = 0; t < D; ++t) {
+        const float lo = (g.mn[t] + (float)c0[t] * g.w[t]) - g.slack[t];
+        const float hi = (g.mn[t] + (float)(c1[t] + 1) * g.w[t]) + g.slack[t];
+        const float far = fmaxf(fabsf(q[t] - lo), fabsf(hi - q[t]));
+        b = fmaf(far, far, b);
+    }
+    // roundings of the bound itself and of the distance it is compared with
+    return b * (1.f + 0x1p-17f);
+}
+
+// The k-th smallest key among the points of the block itself, k <= K: the keys are those of the
+// exact test (same arithmetic), so at least k pairs are at or below the value returned and it
+// can start the list's threshold.  K running minima in registers, 2 K operations per point.
+template <int D, int K>
+__device__ __forceinline__ float seed_exact(const SeedGrid<D>& g, const int* __restrict__ starts,
+                                            const f32x4* __restrict__ sorted, const float (&q)[D],
+                                            int k, const int (&c0)[3], const int (&c1)[3]) {
+    float best[K];
+#pragma unroll
+    for (int i = 0; i < K; ++i) best[i] = kInf;
+    const int G = g.G;
+    for (int z = c0[2]; z <= c1[2]; ++z)
+        for (int y = c0[1]; y <= c1[1]; ++y) {
+            const int row = (z * G + y) * G;
+            const int p1 = starts[row + c1[0] + 1];
+            for (int p = starts[row + c0[0]]; p < p1; ++p) {
+                const f32x4 x = sorted[p];
+                float df = q[0] - x[0];
+                float v = df * df;
+#pragma unroll
+                for (int t = 1; t < D; ++t) {
+                    df = q[t] - x[t];
+                    v = fmaf(df, df, v);
+                }
+#pragma unroll
+                for (int i = 0; i < K; ++i) {  // v sinks to its place, the largest falls out
+                    const float lo = fminf(best[i], v);
+                    v = fmaxf(best[i], v);
+                    best[i] = lo;
+                }
+            }
+        }
+    float r = kInf;
+#pragma unroll
+    for (int i = 0; i < K; ++i) r = (i == k - 1) ? best[i] : r;
+    return r;
 }
 
 // K slots of the filter's contraction for dimension D, padded with zeros to NM MFMAs of 16
@@ -894,8 +994,9 @@ __global__ __launch_bounds__(256) void knn_pack_bf16_kernel(const float* __restr
 template <int D>
 __global__ __launch_bounds__(256, FilterSlots<D>::kMfmas == 1 ? 4 : 3) void knn_lowd_bf16_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
-    const uint4* __restrict__ Xp, const unsigned* __restrict__ hdr, const int* __restrict__ cells,
-    int seed_cells, int rows, int n, int k, int S, int split_len, float* __restrict__ lk,
+    const uint4* __restrict__ Xp, const unsigned* __restrict__ hdr, const int* __restrict__ starts,
+    const f32x4* __restrict__ sorted, int seed_cells, int rows, int n, int k, int S, int split_len,
+    float* __restrict__ lk,
     int* __restrict__ li) {
     constexpr int C = kPbCand;
     constexpr int NS = kPbSets;  // query sets of 32 per wave: one A-operand load feeds NS MFMAs
@@ -990,17 +1091,40 @@ __global__ __launch_bounds__(256, FilterSlots<D>::kMfmas == 1 ? 4 : 3) void knn_
             bq[st][i] = __builtin_bit_cast(bf16x8, uint4{w[0], w[1], w[2], w[3]});
         }
         tcap[st] = kInf;
-        if constexpr (D <= kSeedMaxD) {
-            if (seed_cells > 0 && active) {
-                const SeedGrid<D> g = seed_grid<D>(hdr, seed_cells);
-                tcap[st] = seed_bound<D>(g, cells, q[st], k);
-            }
-        }
-        tau[st] = active ? tcap[st] : -kInf;
+        tau[st] = active ? kInf : -kInf;
         taui[st] = active ? kNoIdx : -1;
-        tauf[st] = key_bound(st, tau[st]);
         cnt[st] = 0;
     }
+    // Threshold seed: the lanes of half h work for the queries of set h, then the halves swap
+    // what they found.  Up to k = 32 the k-th smallest exact key inside the block of cells, above
+    // that the distance to the block's farthest corner.
+    if constexpr (D <= kSeedMaxD) {
+        static_assert(NS == 2, "one query set per half of the wave");
+        if (seed_cells > 0) {
+            float mine = kInf;
+            const int r = wave_row0 + h * 32 + i32;
+            if (r < rows) {
+                float qm[D];
+#pragma unroll
+                for (int t = 0; t < D; ++t) qm[t] = h ? q[1][t] : q[0][t];
+                const SeedGrid<D> g = seed_grid<D>(hdr, seed_cells);
+                int c0[3], c1[3];
+                if (seed_block<D>(g, starts, qm, k, c0, c1)) {
+                    if (k <= 16) mine = seed_exact<D, 16>(g, starts, sorted, qm, k, c0, c1);
+                    else if (k <= 32) mine = seed_exact<D, 32>(g, starts, sorted, qm, k, c0, c1);
+                    else mine = seed_bound<D>(g, qm, c0, c1);
+                }
+            }
+            const float other = lane_xor<32>(mine);
+            tcap[0] = h ? other : mine;
+            tcap[1] = h ? mine : other;
+#pragma unroll
+            for (int st = 0; st < NS; ++st)
+                if (wave_row0 + st * 32 + i32 < rows) tau[st] = tcap[st];
+        }
+    }
+#pragma unroll
+    for (int st = 0; st < NS; ++st) tauf[st] = key_bound(st, tau[st]);
 
     // bits 0..31 of mask: queries of set st to merge
     auto flush = [&](int st, uint64_t mask) {
@@ -1261,10 +1385,17 @@ static hipError_t launch_lowd_bf16_d(const float* Q, int64_t ldq, const float* X
     constexpr int NM = FilterSlots<D>::kMfmas;
     unsigned* hdr = static_cast<unsigned*>(packed);
     uint4* Xp = reinterpret_cast<uint4*>(static_cast<unsigned char*>(packed) + kAlign);
-    // the cell counts of the threshold seed follow the packed points
-    int* cells = reinterpret_cast<int*>(static_cast<unsigned char*>(packed) + kAlign +
-                                        align_up((uint64_t)n * 32 * NM));
+    // the threshold seed's data follow the packed points: cell starts (ncell + 1 words), fill
+    // cursors (ncell words), the points in cell order (16 bytes each)
     if (D > kSeedMaxD) seed_cells = 0;
+    int ncell = 1;
+    for (int t = 0; t < D && seed_cells > 0; ++t) ncell *= seed_cells;
+    unsigned char* seed_base =
+        static_cast<unsigned char*>(packed) + kAlign + align_up((uint64_t)n * 32 * NM);
+    int* starts = reinterpret_cast<int*>(seed_base);
+    int* cursor = reinterpret_cast<int*>(seed_base + align_up((uint64_t)(ncell + 1) * 4));
+    f32x4* sorted = reinterpret_cast<f32x4*>(reinterpret_cast<unsigned char*>(cursor) +
+                                             align_up((uint64_t)ncell * 4));
     const dim3 pgrid((unsigned)((n + 255) / 256));
     if (pack) {
         knn_bbox_init_kernel<<<dim3(1), dim3(64), 0, stream>>>(hdr);
@@ -1273,12 +1404,13 @@ static hipError_t launch_lowd_bf16_d(const float* Q, int64_t ldq, const float* X
         knn_pack_bf16_kernel<D><<<pgrid, dim3(256), 0, stream>>>(X, ldx, (int)n, Xp, hdr);
         if constexpr (D <= kSeedMaxD) {
             if (seed_cells > 0) {
-                int ncell = 1;
-                for (int t = 0; t < D; ++t) ncell *= seed_cells;
                 knn_zero_ints_kernel<<<dim3((unsigned)((ncell + 255) / 256)), dim3(256), 0, stream>>>(
-                    cells, ncell);
+                    cursor, ncell);
                 knn_cell_count_kernel<D><<<pgrid, dim3(256), 0, stream>>>(X, ldx, (int)n, hdr,
-                                                                          seed_cells, cells);
+                                                                          seed_cells, cursor);
+                knn_cell_scan_kernel<<<dim3(1), dim3(256), 0, stream>>>(cursor, ncell, starts);
+                knn_cell_fill_kernel<D><<<pgrid, dim3(256), 0, stream>>>(
+                    X, ldx, (int)n, hdr, seed_cells, starts, cursor, sorted);
             }
         }
         hipError_t e0 = hipGetLastError();
@@ -1293,7 +1425,8 @@ static hipError_t launch_lowd_bf16_d(const float* Q, int64_t ldq, const float* X
     split_len = (split_len + 127) / 128 * 128;
     dim3 grid((unsigned)((rows + kPbTileQ - 1) / kPbTileQ), (unsigned)S);
     knn_lowd_bf16_kernel<D><<<grid, dim3(256), lds, stream>>>(
-        Q, ldq, X, ldx, Xp, hdr, cells, seed_cells, (int)rows, (int)n, k, S, (int)split_len, lk, li);
+        Q, ldq, X, ldx, Xp, hdr, starts, sorted, seed_cells, (int)rows, (int)n, k, S, (int)split_len,
+        lk, li);
     return hipGetLastError();
 }
 

@@ -179,7 +179,9 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
                     return c;
                 };
                 while (cells_of(G + 1) <= want && cells_of(G + 1) <= kSeedMaxCells) ++G;
-                const uint64_t seed = align_up((uint64_t)cells_of(G) * 4);
+                // cell starts, fill cursors and the points in cell order (16 bytes each)
+                const uint64_t seed = align_up(((uint64_t)cells_of(G) + 1) * 4) +
+                                      align_up((uint64_t)cells_of(G) * 4) + align_up((uint64_t)n * 16);
                 if (G >= 2 && mem_limit_bytes >= packed16 + seed + lists_bytes_for((uint64_t)min_rows16,
                                                                                    1, (uint64_t)k)) {
                     out->seed_cells = (int32_t)G;

@@ -400,8 +400,9 @@ def test_exact_ties_keep_the_lower_index_on_every_low_d_path(K, oracle, seed, d,
 
 
 def _seed_cases():
-    # (name, d, k, builder(g) -> (Q, X)): data that strains the grid-count threshold seed of the
-    # bf16 filter path: empty and crowded cells, a flat axis, queries far outside the points'
+    # (name, d, k, builder(g) -> (Q, X)): data that strains the threshold seed of the bf16 filter
+    # path (the k-th smallest distance inside a block of grid cells; above k = 32 the distance to
+    # the block's farthest corner): empty and crowded cells, a flat axis, queries far outside the points'
     # box, a large common offset, k above what the widest block of cells holds
     def clustered(g, d):
         centres = g.uniform(-1, 1, size=(12, d))
@@ -438,7 +439,10 @@ def _seed_cases():
     for d in (1, 2, 3):
         cases += [("clustered", d, 16, clustered), ("flat_axis", d, 9, flat_axis),
                   ("offset", d, 16, offset), ("lattice", d, 5, lattice),
-                  ("two_clumps", d, 3, two_points_far_apart), ("clustered_k200", d, 200, clustered)]
+                  ("two_clumps", d, 3, two_points_far_apart), ("clustered_k200", d, 200, clustered),
+                  # 17 .. 32: the longer of the two register lists of the exact seed
+                  ("clustered_k25", d, 25, clustered), ("lattice_k32", d, 32, lattice),
+                  ("offset_k17", d, 17, offset)]
     return cases
 
 

@@ -139,27 +139,34 @@ def test_low_d_falls_back_to_the_vector_path_when_packed_points_do_not_fit():
 
 def test_threshold_seed_grid_is_sized_from_n_and_k_and_paid_for_under_the_limit():
     # path 4, d <= 3: G cells per axis, the largest G with G^d <= min(2 n / (3 k), 32768); the
-    # counts (4 G^d bytes, 256-aligned) follow the packed points inside norms_bytes
+    # cell starts (G^d + 1 words), the fill cursors (G^d words) and the points in cell order
+    # (16 bytes each), 256-aligned each, follow the packed points inside norms_bytes
+    def up(v):
+        return (v + 255) // 256 * 256
+
+    def seed_bytes(n, cells):
+        return up(4 * (cells + 1)) + up(4 * cells) + up(16 * n)
+
     for n, d, k, G in [(1_000_000, 3, 16, 32), (1_000_000, 2, 16, 181), (750_000, 1, 16, 31250),
                        (10_000_000, 1, 1, 32768), (10_000_000, 3, 1, 32), (10_000_000, 2, 1, 181),
                        (9000, 3, 12, 7), (40_000, 3, 200, 5), (500, 3, 16, 2)]:
         p = K.knn_plan(1000, n, d, k, 10 ** 10)
         assert p.path == K.KNN_PATH_LOWD_BF16 and p.seed_cells == G, (n, d, k, p.seed_cells)
         assert G ** d <= min(2 * n // (3 * k), 32768) < (G + 1) ** d or G ** d <= 32768 < (G + 1) ** d
-        counts = (4 * G ** d + 255) // 256 * 256
-        assert p.norms_bytes == 256 + (32 * n + 255) // 256 * 256 + counts
+        assert p.norms_bytes == 256 + up(32 * n) + seed_bytes(n, G ** d)
         assert p.workspace_bytes <= 10 ** 10
     # fewer than two cells per axis, or d > 3: no grid
     assert K.knn_plan(1000, 100, 3, 16, 10 ** 9).seed_cells == 0
     assert K.knn_plan(1000, 1_000_000, 4, 16, 10 ** 9).seed_cells == 0
-    # room for the packed points and one tile of lists but not for the counts: same path, no grid
+    # room for the packed points and one tile of lists but not for the grid: same path, no grid
     n, d, k = 1_000_000, 3, 16
     packed = 256 + 32 * n
     tile_lists = 2 * ((256 * k * 4 + 255) // 256 * 256)
     bare = K.knn_plan(1000, n, d, k, packed + tile_lists)
     assert bare.path == K.KNN_PATH_LOWD_BF16 and bare.seed_cells == 0 and bare.norms_bytes == packed
-    full = K.knn_plan(1000, n, d, k, packed + tile_lists + 4 * 32 ** 3)
-    assert full.seed_cells == 32 and full.workspace_bytes <= packed + tile_lists + 4 * 32 ** 3
+    assert K.knn_plan(1000, n, d, k, packed + tile_lists + seed_bytes(n, 32 ** 3) - 1).seed_cells == 0
+    full = K.knn_plan(1000, n, d, k, packed + tile_lists + seed_bytes(n, 32 ** 3))
+    assert full.seed_cells == 32 and full.workspace_bytes <= packed + tile_lists + seed_bytes(n, 32 ** 3)
 
 
 def test_split_path_accounts_for_the_per_query_data_and_uses_every_byte_it_can():
