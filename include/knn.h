@@ -88,12 +88,15 @@ typedef struct {
     int32_t streams;     /* HIP streams used (1: the caller's)                  */
     int32_t reserved;    /* 0 */
     int32_t metric;      /* knn_metric                                          */
-    int32_t seed_cells;  /* path 4, d <= 3: cells per axis of the grid the points are counted
-                            into to give every list a finite starting threshold; 0: none */
+    int32_t seed_cells;  /* path 4, d <= 3: cells per axis of the grid the points are sorted
+                            into to give every list a finite starting threshold (up to k = 32
+                            the k-th smallest distance among a query's neighbouring cells,
+                            above that the distance to their farthest corner); 0: none */
     uint64_t norms_bytes;     /* workspace: per-point data. path 2: packed points
                                  [x0 x1 x2 |x|^2]; path 5: squared norms (cosine: 1 / norm)
                                  and a 256-byte header; path 4: a 256-byte header, 32 bytes
-                                 per point and 16 K slots, and seed_cells^d counts;
+                                 per point and 16 K slots, and with seed_cells the grid's cell
+                                 starts and cursors and the points in cell order (16 bytes each);
                                  paths 0, 3: nothing                                   */
     uint64_t query_bytes;     /* workspace: per-query data of one chunk. path 5: the queries
                                  rounded to bf16 (32 bytes per row and 16 coordinates), their
