@@ -322,19 +322,24 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     // buffered (point index only; the two halves of the wave take consecutive slots).
     // Register e of a lane of half h holds point row 8 (e / 4) + 4 h + e % 4 of its block.
     auto epilogue = [&](const f32x16 (&a)[4], int tile_base) {
-        float m = kInf;
+        // the smallest key of each block of 32 points first: a block without a key under some
+        // lane's threshold costs its 16 minima and one vote
+        float mb[4];
 #pragma unroll
-        for (int pb = 0; pb < 4; ++pb)
+        for (int pb = 0; pb < 4; ++pb) {
+            mb[pb] = a[pb][0];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) m = fminf(m, a[pb][e]);
-        if (__builtin_amdgcn_ballot_w64(m < tauf) == 0) return;
+            for (int e = 1; e < 16; ++e) mb[pb] = fminf(mb[pb], a[pb][e]);
+        }
+        if (__builtin_amdgcn_ballot_w64(fminf(fminf(mb[0], mb[1]), fminf(mb[2], mb[3])) < tauf) == 0)
+            return;
         const int cnt0 = cnt;
 #pragma unroll
         for (int pb = 0; pb < 4; ++pb) {
+            if (__builtin_amdgcn_ballot_w64(mb[pb] < tauf) == 0) continue;
             int mine = 0;
 #pragma unroll
             for (int e = 0; e < 16; ++e) mine += (a[pb][e] < tauf) ? 1 : 0;
-            if (__builtin_amdgcn_ballot_w64(mine > 0) == 0) continue;
             const int oth = lane_xor<32>(mine);
             if (cnt + mine + oth > C) ovf = 1;  // the same in both halves of the wave
             if (!ovf) {
