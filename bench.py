@@ -340,7 +340,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 "
-              "(sharding over GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+              "(more GPUs would each take a share of the query rows; that is not built)", file=sys.stderr)
         return 2
 
     if args.workload.startswith("kmv"):
