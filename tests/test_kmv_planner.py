@@ -24,6 +24,22 @@ def test_matrix_core_path_keeps_scaled_norms():
     assert K.kmv_plan(200_000, 200_000, 32, p.norms_bytes).n_splits == 1
 
 
+def test_matrix_core_path_cuts_ranges_to_even_out_its_rounds():
+    # 1563 workgroups of equal length on 3 x 256 places would run three rounds for two rounds'
+    # worth of work; ranges shorten the rounds when their partial sums fit under the limit
+    n = m = 200_000
+    p = K.kmv_plan(n, m, 32, W.GB)
+    assert p.n_splits in (2, 3, 4, 6, 8) and m // p.n_splits >= 2048
+    assert p.partials_bytes == (8 * n * p.n_splits + 255) // 256 * 256
+    assert p.workspace_bytes == p.norms_bytes + p.partials_bytes <= W.GB
+    # no room for partial sums: one range, the sums go straight to y
+    q = K.kmv_plan(n, m, 32, p.norms_bytes + 8 * n)
+    assert (q.n_splits, q.partials_bytes) == (1, 0)
+    # a launch that fills whole rounds anyway stays at one range
+    r = K.kmv_plan(2 * 768 * 128, m, 32, W.GB)
+    assert r.n_splits == 1
+
+
 @pytest.mark.parametrize("d", [2, 16])
 def test_ranges_grow_only_while_they_fit(d):
     n, m = 300, 10 ** 6
