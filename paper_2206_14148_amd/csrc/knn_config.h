@@ -47,6 +47,7 @@ constexpr int kSpTileX = 128;
 constexpr int kSpKC = 16;            // coordinates per chunk (one MFMA's K slots); a step takes 1..4
 constexpr int kSpCand = 32;          // buffered point indices per query (LDS)
 constexpr int kSpResidentMaxChunks = 16;  // d <= 256: the queries' B operands stay in registers
+constexpr int kSpShareMin = 20;      // when the workgroup stops to empty buffers: all with at least this many entries
 constexpr int kSpRoom = 4;           // a buffer with fewer free slots than this is emptied after the tile
 
 // Workgroups the chip holds at once (LDS-limited): the planner sizes launches in rounds of these.

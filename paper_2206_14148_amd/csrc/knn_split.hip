@@ -318,6 +318,45 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
         ovf = 0;
     };
 
+    // While one wave evaluates candidates the other seven stand at the next barrier, and what it
+    // waits for is memory.  So when any wave has a buffer to empty, the whole workgroup empties
+    // every buffer that is at least kSpShareMin full, the queries dealt out over the eight waves:
+    // the waits overlap, and the next such stop is further away.  (Overflowed queries stay with
+    // their own wave, drain() above.)
+    int* const co_cnt = reinterpret_cast<int*>(reinterpret_cast<float*>(ci + TQ * C) +
+                                               (size_t)kSpWaves * (2 * kWave + 2 * k));  // [TQ]
+    unsigned* const co_res = reinterpret_cast<unsigned*>(co_cnt + TQ);                   // [TQ]
+    int* const co_queue = reinterpret_cast<int*>(co_res + TQ);                          // [TQ]
+    int* const co_n = co_queue + TQ;                                                    // [1]
+    if (tid == 0) *co_n = 0;  // (a barrier follows before the first use)
+    auto shared_drain = [&](int tile_base) {
+        const bool mine = !ovf && cnt >= kSpShareMin;
+        if (h == 0) {
+            const int q = wave * 32 + i32;
+            co_cnt[q] = cnt;
+            if (mine) co_queue[atomicAdd(co_n, 1)] = q;
+        }
+        __syncthreads();
+        const int nq = *co_n;
+        for (int e = wave; e < nq; e += kSpWaves) {
+            const int q = co_queue[e];
+            const int r = wg_row0 + q;
+            const size_t lb = ((size_t)r * S + s) * k;
+            const unsigned fr = split_flush_query<ALIGNED>(
+                Q + (int64_t)r * ldq, X, ldx, d, j0, ci + q * C, 0, co_cnt[q], lk + lb, li + lb, k,
+                my_scratch, tsh + r, cosine ? xn : nullptr, lane);
+            if (lane == 0) co_res[q] = fr;
+        }
+        __syncthreads();
+        if (mine) {
+            own = __uint_as_float(co_res[wave * 32 + i32]);
+            tauf = key_bound(fminf(own, cap));
+            cnt = 0;
+        }
+        if (tid == 0) *co_n = 0;  // the next use is behind the barrier that ends the tile
+        if (__builtin_amdgcn_ballot_w64(ovf != 0) != 0) drain(tile_base, false);
+    };
+
     // End of a tile, accumulators still live, no calls: keys below the filter threshold are
     // buffered (point index only; the two halves of the wave take consecutive slots).
     // Register e of a lane of half h holds point row 8 (e / 4) + 4 h + e % 4 of its block.
@@ -465,8 +504,8 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
             tauf = key_bound(fminf(own, cap));
             if (cosine) scale_rows(acc, rns + (tile & 1) * TX, h);
             epilogue(acc, tile_base);
-            if (__builtin_amdgcn_ballot_w64(ovf != 0 || cnt > C - kSpRoom) != 0)
-                drain(tile_base, false);
+            const bool need = __builtin_amdgcn_ballot_w64(ovf != 0 || cnt > C - kSpRoom) != 0;
+            if (__syncthreads_or(need ? 1 : 0)) shared_drain(tile_base);
             ++tile;
             __syncthreads();
             if (step + 1 < total) start_tile(tile);
@@ -552,7 +591,8 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
                         hipStream_t stream) {
     const int nch = (d + kSpKC - 1) / kSpKC;
     const size_t lds_fixed = (size_t)4 * kSpTileX * 4 + (size_t)kSpTileQ * kSpCand * 4 +
-                             (size_t)kSpWaves * (2 * kWave + 2 * k) * 4;
+                             (size_t)kSpWaves * (2 * kWave + 2 * k) * 4 +
+                             (size_t)(3 * kSpTileQ + 4) * 4;  // the shared drain's arrays
     int64_t split_len = (n + S - 1) / S;
     split_len = (split_len + kSpTileX - 1) / kSpTileX * kSpTileX;
     // One workgroup per compute unit is resident, so the (tile, range) pairs go to the 8 XCDs
@@ -591,7 +631,7 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
         else if (nch <= 8) KNN_SPLIT_LAUNCH(4, 2, true);
         else if (nch <= 10) KNN_SPLIT_LAUNCH(2, 5, true);
         else if (nch <= 12) KNN_SPLIT_LAUNCH(2, 6, true);
-        else if (nch <= kSpResidentMaxChunks) KNN_SPLIT_LAUNCH(2, 8, true);
+        else if (nch <= kSpResidentMaxChunks) KNN_SPLIT_LAUNCH(1, 16, true);
         else KNN_SPLIT_LAUNCH(4, 0, true);
     } else {
         if (nch <= 1) KNN_SPLIT_LAUNCH(1, 1, false);
