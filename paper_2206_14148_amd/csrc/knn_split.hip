@@ -89,13 +89,14 @@ __global__ __launch_bounds__(256) void knn_split_queries_kernel(const float* __r
 
 // One lane's share of the exact key of a candidate - sum_t (q_t - x_t)^2, or with DOT the
 // product sum_t q_t x_t of the cosine metric: the groups of four
-// coordinates g = part, part + 2, ... in ascending order, one fma chain.  The loads of eight groups
-// are issued before the first is used, so that a row of a few KB costs a few memory round trips,
-// not one per group.
+// coordinates g = part, part + 2, ... in ascending order, one fma chain.  The loads of two groups
+// are issued before the first is used.  More in flight would shorten the wait for a long row,
+// but every register this out-of-line path uses is one the search loop has to give up around
+// its calls: measured, eight groups in flight were slower than two (c5 99.6 against 88.9 ms).
 template <bool ALIGNED, bool DOT>
 __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, const float* __restrict__ xp,
                                                int d, int part) {
-    constexpr int U = 8;
+    constexpr int U = 2;
     float sum = 0.f;
     const int ng = (d + 3) >> 2;  // groups of four coordinates (the last may be ragged)
     for (int g0 = part; g0 < ng; g0 += 2 * U) {
