@@ -630,9 +630,9 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
         else if (nch <= 4) KNN_SPLIT_LAUNCH(4, 1, true);
         else if (nch <= 6) KNN_SPLIT_LAUNCH(3, 2, true);
         else if (nch <= 8) KNN_SPLIT_LAUNCH(4, 2, true);
-        else if (nch <= 10) KNN_SPLIT_LAUNCH(2, 5, true);
-        else if (nch <= 12) KNN_SPLIT_LAUNCH(2, 6, true);
-        else if (nch <= kSpResidentMaxChunks) KNN_SPLIT_LAUNCH(1, 16, true);
+        else if (nch <= 9) KNN_SPLIT_LAUNCH(3, 3, true);
+        else if (nch <= 12) KNN_SPLIT_LAUNCH(4, 3, true);
+        else if (nch <= kSpResidentMaxChunks) KNN_SPLIT_LAUNCH(4, 4, true);
         else KNN_SPLIT_LAUNCH(4, 0, true);
     } else {
         if (nch <= 1) KNN_SPLIT_LAUNCH(1, 1, false);
