@@ -329,7 +329,11 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     unsigned* const co_res = reinterpret_cast<unsigned*>(co_cnt + TQ);                   // [TQ]
     int* const co_queue = reinterpret_cast<int*>(co_res + TQ);                          // [TQ]
     int* const co_n = co_queue + TQ;                                                    // [1]
-    if (tid == 0) *co_n = 0;  // (a barrier follows before the first use)
+    // "some wave of the workgroup has a buffer to empty", one word per tile in turn: set before
+    // the barrier that ends tile t, read by everybody behind it, cleared behind the barrier of
+    // tile t + 1 - three words, so that clearing one never meets a wave that is a tile ahead
+    int* const co_stop = co_n + 1;                                                      // [3]
+    if (tid < 4) co_n[tid] = 0;  // (a barrier follows before the first use)
     auto shared_drain = [&](int tile_base) {
         const bool mine = !ovf && cnt >= kSpShareMin;
         if (h == 0) {
@@ -477,7 +481,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     }
     __syncthreads();
     if (total > 0) start_tile(0);
-    int tile = 0;
+    int tile = 0, tile3 = 0;  // tile3 = tile % 3
     const uint4* const as_r = as + i32 * 2 + h;
     // one (tile, step) step: MFMAs on LDS buffer `par` with the given B operands, the next
     // step's points go to the other buffer meanwhile; last = the tile's last step
@@ -505,10 +509,14 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
             tauf = key_bound(fminf(own, cap));
             if (cosine) scale_rows(acc, rns + (tile & 1) * TX, h);
             epilogue(acc, tile_base);
+            // The barrier that ends the step carries the vote on stopping as well.
             const bool need = __builtin_amdgcn_ballot_w64(ovf != 0 || cnt > C - kSpRoom) != 0;
-            if (__syncthreads_or(need ? 1 : 0)) shared_drain(tile_base);
-            ++tile;
+            if (need && lane == 0) co_stop[tile3] = 1;
             __syncthreads();
+            if (tid == 0) co_stop[tile3 == 0 ? 2 : tile3 - 1] = 0;  // the previous tile's word
+            if (co_stop[tile3] != 0) shared_drain(tile_base);
+            ++tile;
+            tile3 = tile3 == 2 ? 0 : tile3 + 1;
             if (step + 1 < total) start_tile(tile);
         } else {
             __syncthreads();
