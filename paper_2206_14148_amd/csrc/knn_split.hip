@@ -486,6 +486,12 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     // one (tile, step) step: MFMAs on LDS buffer `par` with the given B operands, the next
     // step's points go to the other buffer meanwhile; last = the tile's last step
     auto step_fn = [&](int step, int par, bool last, const QB& b, XS& mine, const XS& next) {
+        // What the other ranges of the query have reached since the last look: asked for
+        // before the step's MFMAs and ahead of the point loads (loads return in order, so the
+        // wait for this word at the end of the tile does not wait for those), used behind them.
+        unsigned others = 0;
+        if (last)
+            others = __hip_atomic_load(tsh + qrow, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         fetchX(mine);
         const uint4* ab = as_r + par * (W * TX * 2);
 #pragma unroll
@@ -503,9 +509,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
             // right after the barrier of this branch, so nothing of them is live across the
             // calls in drain().
             const int tile_base = j0 + tile * TX;
-            // what the other ranges of the query have reached since the last look
-            cap = fminf(cap, word_key(__hip_atomic_load(tsh + qrow, __ATOMIC_RELAXED,
-                                                        __HIP_MEMORY_SCOPE_AGENT)));
+            cap = fminf(cap, word_key(others));
             tauf = key_bound(fminf(own, cap));
             if (cosine) scale_rows(acc, rns + (tile & 1) * TX, h);
             epilogue(acc, tile_base);
