@@ -31,10 +31,10 @@ PEAK_HBM_GBS = 8000.0
 # (profiles/*_pmc.txt), scaled by the copy-kernel calibration stated there.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
     "c2_pointcloud_d3": 209.7e9,    # knn_lowd_bf16_kernel: fetched + written
-    "c3_imagelike_d784": 165.1e9,   # knn_split_kernel (streamed queries): fetched + written
-    "c4_clustered_d128": 1617.0e9,  # knn_split_kernel (resident queries): fetched + written
-    "c5_memsweep_d256": 332.4e9,    # knn_split_kernel (resident queries): fetched + written
-    "c6_cosine_d100": 15.36e9,      # knn_split_kernel (resident queries): fetched + written
+    "c3_imagelike_d784": 164.0e9,   # knn_split_kernel (streamed queries): fetched + written
+    "c4_clustered_d128": 1821.5e9,  # knn_split_kernel (resident queries): fetched + written
+    "c5_memsweep_d256": 346.2e9,    # knn_split_kernel (resident queries): fetched + written
+    "c6_cosine_d100": 16.03e9,      # knn_split_kernel (resident queries): fetched + written
     "c7_l1_d100": 28.34e9,          # knn_l1_kernel: 27.92 GB fetched + 0.42 GB written
     "kmv1_d1": 1.84e9,              # kmv_lowd_kernel: 1.83 GB fetched + 0.01 GB written
     "kmv2_d32": 1.47e9,             # kmv_mfma_kernel: 1.46 GB fetched + 0.007 GB written
