@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per search-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/*_pmc.txt), scaled by the copy-kernel calibration stated there.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "c2_pointcloud_d3": 209.7e9,    # knn_lowd_bf16_kernel: fetched + written
+    "c2_pointcloud_d3": 214.8e9,    # knn_lowd_bf16_kernel: fetched + written
     "c3_imagelike_d784": 164.0e9,   # knn_split_kernel (streamed queries): fetched + written
     "c4_clustered_d128": 1821.5e9,  # knn_split_kernel (resident queries): fetched + written
     "c5_memsweep_d256": 346.2e9,    # knn_split_kernel (resident queries): fetched + written
