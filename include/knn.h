@@ -41,7 +41,9 @@ typedef enum {
     KNN_ERR_MEM_LIMIT_TOO_SMALL = 2, /* limit below knn_plan_t.min_limit_bytes      */
     KNN_ERR_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes < plan.workspace_bytes      */
     KNN_ERR_UNSUPPORTED = 4,         /* n > 2^31 - 65536 (int32 indices) or k > KNN_MAX_K */
-    KNN_ERR_HIP = 5                  /* a HIP call or kernel launch failed          */
+    KNN_ERR_HIP = 5,                 /* a HIP call or kernel launch failed          */
+    KNN_ERR_STATIC_SCRATCH_TOO_SMALL = 6 /* knn_search_static: no plan of this shape fits
+                                        KNN_STATIC_SCRATCH_BYTES                     */
 } knn_status;
 
 #define KNN_MAX_K 1024
@@ -258,6 +260,28 @@ knn_status knn_plan_host_x(int64_t m, int64_t n, int32_t d, int32_t k, knn_metri
 knn_status knn_search_host_x(const float *Q, int64_t ldq, const float *X /* HOST */, int64_t ldx,
                              int64_t m, int64_t n, int32_t d, int32_t k, knn_metric metric,
                              uint64_t mem_limit_bytes, void *workspace, uint64_t workspace_bytes,
+                             int32_t *idx, float *dist, void *hip_stream);
+
+/*
+ * knn_search_static - knn_search for callers that cannot allocate device memory and have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same kernels, same result (bit for bit) as knn_search; the workspace is a
+ * buffer of KNN_STATIC_SCRATCH_BYTES that is part of the library's device image (one copy per
+ * GPU the library runs on, held until the process ends), and the plan is the one knn_plan gives
+ * for mem_limit_bytes = KNN_STATIC_SCRATCH_BYTES.  The call allocates nothing (no hipMalloc,
+ * hipFree or allocating library routine); the first call on a device looks up that device's
+ * address of the buffer.
+ *   Q, X, idx, dist, hip_stream   as in knn_search (DEVICE pointers of the current device)
+ * Errors: those of knn_search, and KNN_ERR_STATIC_SCRATCH_TOO_SMALL (outputs untouched) when
+ * the smallest plan of the shape needs more than KNN_STATIC_SCRATCH_BYTES - for d > 8 that is
+ * 4 n bytes of norms plus one query tile of lists, so n up to about 8e6.
+ * Every call on a GPU uses that GPU's one buffer: calls that overlap in time on one GPU (other
+ * streams, other host threads) race and must be serialised by the caller.  The buffer keeps
+ * the last call's contents; every kernel initialises what it reads.
+ */
+#define KNN_STATIC_SCRATCH_BYTES 33554432ull /* 32 MiB */
+knn_status knn_search_static(const float *Q, int64_t ldq, const float *X, int64_t ldx,
+                             int64_t m, int64_t n, int32_t d, int32_t k,
                              int32_t *idx, float *dist, void *hip_stream);
 
 /* Last HIP error text seen by this thread ("" if none). */

@@ -18,6 +18,8 @@ KNN_ERR_MEM_LIMIT_TOO_SMALL = 2
 KNN_ERR_WORKSPACE_TOO_SMALL = 3
 KNN_ERR_UNSUPPORTED = 4
 KNN_ERR_HIP = 5
+KNN_ERR_STATIC_SCRATCH_TOO_SMALL = 6
+KNN_STATIC_SCRATCH_BYTES = 33554432
 KNN_MAX_K = 1024
 KNN_PATH_LOWD = 0
 KNN_PATH_LOWD_MFMA = 2
@@ -35,6 +37,7 @@ EXPORTED_SYMBOLS = (
     "knn_profile_read", "knn_plan_metric", "knn_search_metric",
     "kmv_plan", "kmv_apply", "kmv_plan_f64", "kmv_apply_f64",
     "knn_plan_host_x", "knn_search_host_x", "sgpr_plan", "sgpr_accumulate",
+    "knn_search_static",
 )
 KMV_PATH_LOWD = 0
 KMV_PATH_MFMA = 1
@@ -187,6 +190,8 @@ def load():
     lib.knn_workspace_bytes.restype = u64
     lib.knn_search.argtypes = [vp, i64, vp, i64, i64, i64, i32, i32, u64, vp, u64, vp, vp, vp]
     lib.knn_search.restype = ctypes.c_int
+    lib.knn_search_static.argtypes = [vp, i64, vp, i64, i64, i64, i32, i32, vp, vp, vp]
+    lib.knn_search_static.restype = ctypes.c_int
     lib.knn_last_stats.argtypes = [ctypes.POINTER(PlanStruct), ctypes.POINTER(u64)]
     lib.knn_last_stats.restype = ctypes.c_int
     lib.knn_status_string.argtypes = [ctypes.c_int]
@@ -320,13 +325,58 @@ def knn_search(Q, X, k: int, mem_limit_bytes: int, workspace=None, out=None, met
         idx = torch.empty((m, k), dtype=torch.int32, device=Q.device)
         dist = torch.empty((m, k), dtype=torch.float32, device=Q.device)
     else:
-        idx, dist = out
+        idx, dist = _check_out(out, m, k, Q.device)
     stream = torch.cuda.current_stream(Q.device).cuda_stream
     ldq = Q.stride(0) if m > 1 else max(d, Q.stride(0))
     ldx = X.stride(0) if n > 1 else max(d, X.stride(0))
     st = knn_search_raw(Q.data_ptr(), ldq, X.data_ptr(), ldx, m, n, d, k, mem_limit_bytes,
                         workspace.data_ptr(), workspace.numel(), idx.data_ptr(),
                         dist.data_ptr(), stream, METRICS[metric])
+    if st != KNN_OK:
+        detail = knn_status_string(st)
+        if st == KNN_ERR_HIP:
+            detail += " (" + load().knn_last_hip_error().decode() + ")"
+        raise KnnError(st, detail)
+    return idx, dist
+
+
+def _check_out(out, m: int, k: int, device):
+    """The kernels write m*k int32 / fp32 values through raw pointers: the tensors must be that."""
+    import torch
+
+    idx, dist = out
+    for t, dt in ((idx, torch.int32), (dist, torch.float32)):
+        if not t.is_cuda or t.device != device or t.dtype != dt or tuple(t.shape) != (m, k) or \
+                not t.is_contiguous():
+            raise KnnError(KNN_ERR_INVALID_ARG,
+                           "out must be (int32[m,k], float32[m,k]), contiguous, on the device of Q")
+    return idx, dist
+
+
+def knn_search_static(Q, X, k: int, out=None):
+    """knn_search through the library's static scratch buffer: the call allocates nothing on the
+    library side (the outputs are the caller's: pass `out` to allocate nothing here either).
+    Squared-Euclidean metric; the shape must fit KNN_STATIC_SCRATCH_BYTES."""
+    import torch
+
+    if not (Q.is_cuda and X.is_cuda):
+        raise KnnError(KNN_ERR_INVALID_ARG, "Q and X must be device tensors (no CPU path exists)")
+    if Q.dtype != torch.float32 or X.dtype != torch.float32 or Q.dim() != 2 or X.dim() != 2:
+        raise KnnError(KNN_ERR_INVALID_ARG, "Q and X must be 2-D float32")
+    if Q.shape[1] != X.shape[1] or Q.stride(1) != 1 or X.stride(1) != 1:
+        raise KnnError(KNN_ERR_INVALID_ARG, "Q and X must share d and have unit column stride")
+    m, d = Q.shape
+    n = X.shape[0]
+    if out is None:
+        idx = torch.empty((m, k), dtype=torch.int32, device=Q.device)
+        dist = torch.empty((m, k), dtype=torch.float32, device=Q.device)
+    else:
+        idx, dist = _check_out(out, m, k, Q.device)
+    stream = torch.cuda.current_stream(Q.device).cuda_stream
+    ldq = Q.stride(0) if m > 1 else max(d, Q.stride(0))
+    ldx = X.stride(0) if n > 1 else max(d, X.stride(0))
+    st = int(load().knn_search_static(Q.data_ptr(), ldq, X.data_ptr(), ldx, m, n, d, k,
+                                      idx.data_ptr(), dist.data_ptr(), stream))
     if st != KNN_OK:
         detail = knn_status_string(st)
         if st == KNN_ERR_HIP:
@@ -439,7 +489,7 @@ def knn_search_host_x(Q, X_host, k: int, mem_limit_bytes: int, workspace=None, o
         idx = torch.empty((m, k), dtype=torch.int32, device=Q.device)
         dist = torch.empty((m, k), dtype=torch.float32, device=Q.device)
     else:
-        idx, dist = out
+        idx, dist = _check_out(out, m, k, Q.device)
     stream = torch.cuda.current_stream(Q.device).cuda_stream
     ldq = Q.stride(0) if m > 1 else max(d, Q.stride(0))
     st = int(load().knn_search_host_x(Q.data_ptr(), ldq, x_ptr, ldx, m, n, d, k, METRICS[metric],

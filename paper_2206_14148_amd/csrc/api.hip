@@ -10,6 +10,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "../../include/knn.h"
@@ -257,6 +258,62 @@ extern "C" knn_status knn_search_metric(const float* Q, int64_t ldq, const float
     if (st != KNN_OK) return st;
     g_last_plan = plan;
     g_last_peak = plan.workspace_bytes;
+    g_have_last = true;
+    return KNN_OK;
+}
+
+// Workspace of knn_search_static: part of the device image, so no call ever allocates it.  In
+// host code this name is only a handle for hipGetSymbolAddress; the address kernels can use is
+// looked up once per device and kept in g_static_ptr.
+static __device__ __align__(256) unsigned char scratch[KNN_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+unsigned char* g_static_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (each GPU holds its own copy).
+knn_status static_scratch(unsigned char** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return KNN_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        g_static_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    *out = g_static_ptr[dev];
+    return KNN_OK;
+}
+
+}  // namespace
+
+extern "C" knn_status knn_search_static(const float* Q, int64_t ldq, const float* X, int64_t ldx,
+                                        int64_t m, int64_t n, int32_t d, int32_t k, int32_t* idx,
+                                        float* dist, void* hip_stream) {
+    if (m < 0 || n < 1 || d < 1 || k < 1 || (int64_t)k > n) return KNN_ERR_INVALID_ARG;
+    if (ldq < d || ldx < d) return KNN_ERR_INVALID_ARG;
+    if (!X) return KNN_ERR_INVALID_ARG;
+    if (m > 0 && (!Q || !idx || !dist)) return KNN_ERR_INVALID_ARG;
+    knn_plan_t plan;
+    knn_status st = knn_plan_metric(m, n, d, k, KNN_METRIC_L2SQ, KNN_STATIC_SCRATCH_BYTES, &plan);
+    if (st == KNN_ERR_MEM_LIMIT_TOO_SMALL) return KNN_ERR_STATIC_SCRATCH_TOO_SMALL;
+    if (st != KNN_OK) return st;
+    if (m > 0) {
+        if (plan.workspace_bytes > KNN_STATIC_SCRATCH_BYTES) return KNN_ERR_STATIC_SCRATCH_TOO_SMALL;
+        unsigned char* ws = nullptr;
+        st = static_scratch(&ws);
+        if (st != KNN_OK) return st;
+        st = run_search(plan, Q, ldq, X, ldx, m, n, d, k, KNN_METRIC_L2SQ, ws, idx, dist,
+                        static_cast<hipStream_t>(hip_stream));
+        if (st != KNN_OK) return st;
+    }
+    g_last_plan = plan;
+    g_last_peak = m > 0 ? plan.workspace_bytes : 0;
     g_have_last = true;
     return KNN_OK;
 }

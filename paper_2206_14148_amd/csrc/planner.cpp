@@ -60,6 +60,8 @@ extern "C" const char* knn_status_string(knn_status s) {
         case KNN_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than the plan requires";
         case KNN_ERR_UNSUPPORTED: return "unsupported size (n >= 2^31 or k > KNN_MAX_K)";
         case KNN_ERR_HIP: return "HIP runtime error";
+        case KNN_ERR_STATIC_SCRATCH_TOO_SMALL:
+            return "no plan of this shape fits the static scratch buffer (KNN_STATIC_SCRATCH_BYTES)";
     }
     return "unknown status";
 }
