@@ -375,7 +375,7 @@ def main() -> int:
     ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
     idx = torch.empty((w.m, w.k), dtype=torch.int32, device=dev)
     dist = torch.empty((w.m, w.k), dtype=torch.float32, device=dev)
-    path_name = {0: "lowd", 2: "lowd_mfma", 3: "l1", 4: "lowd_bf16", 5: "mfma_split"}[plan.path]
+    path_name = {0: "lowd", 2: "lowd_mfma", 3: "l1", 4: "lowd_bf16", 5: "mfma_split", 6: "mfma_packed"}[plan.path]
     log(f"[bench] plan: path={path_name} chunks={plan.q_chunks} "
         f"ranges={plan.n_splits} workspace={plan.workspace_bytes} B (limit {limit} B)")
 
@@ -414,14 +414,14 @@ def main() -> int:
     pairs_per_launch = pairs * args.steps / max(launches, 1)
     traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
     hbm_equiv = (pairs_per_launch / avg_launch_s) * 8.0 / (PEAK_HBM_GBS * 1e9)
-    if plan.path == K.KNN_PATH_MFMA_SPLIT:
+    if plan.path in (K.KNN_PATH_MFMA_SPLIT, K.KNN_PATH_MFMA_PACKED):
         # The -2 Q X^T contraction of the filter runs on bf16 roundings of the values: 2 d bf16
         # flops per pair on the matrix cores, with d rounded up to the 16 coordinates of an MFMA,
         # against the dense bf16 peak.
         d_pad = (w.d + 15) // 16 * 16
         flops = 2.0 * d_pad * pairs_per_launch
         achieved = flops / avg_launch_s / 1e12
-        roofline = {"bound": "mfma", "kernel": "knn_split_kernel", "achieved": achieved,
+        roofline = {"bound": "mfma", "kernel": "knn_split_kernel" if plan.path == K.KNN_PATH_MFMA_SPLIT else "knn_packed_kernel", "achieved": achieved,
                     "peak": PEAK_BF16_MATRIX_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_BF16_MATRIX_TFLOPS, "traffic": traffic,
                     "flops_per_pair": 2 * d_pad}

@@ -71,6 +71,13 @@ typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1, KNN_METRIC_L1 = 2 } k
                                  rounding; exact fp32 test of the pairs that pass.  (Number 1
                                  was this path's fp32 matrix-core predecessor.) */
 
+#define KNN_PATH_MFMA_PACKED 6 /* 16 < d <= 256, squared-Euclidean, n >= 65536 and room for the
+                                  points rounded to bf16 (32 bytes per point and 16 coordinates):
+                                  the filter of path 5 with the queries resident in LDS and the
+                                  points read from that copy in matrix-core operand order; the
+                                  first points of X go through path 5's kernel to warm the lists.
+                                  Same exact test, same keys, same results as path 5. */
+
 /*
  * The plan: how the call is cut into pieces (section 4.3: split the largest
  * splittable axis so that each piece stays under the limit; the loop body
@@ -96,7 +103,8 @@ typedef struct {
                             above that the distance to their farthest corner); 0: none */
     uint64_t norms_bytes;     /* workspace: per-point data. path 2: packed points
                                  [x0 x1 x2 |x|^2]; path 5: squared norms (cosine: 1 / norm)
-                                 and a 256-byte header; path 4: a 256-byte header, 32 bytes
+                                 and a 256-byte header; path 6: the same (norms padded to a
+                                 multiple of 64 points) and the points rounded to bf16; path 4: a 256-byte header, 32 bytes
                                  per point and 16 K slots, and with seed_cells the grid's cell
                                  starts and cursors and the points in cell order (16 bytes each);
                                  paths 0, 3: nothing                                   */

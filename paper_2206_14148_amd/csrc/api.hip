@@ -156,11 +156,18 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     float* xn = reinterpret_cast<float*>(ws);
     // path 5: [squared norms][header: their maximum] | [split queries][query norms][shared
     // thresholds] | lists; L1 path: [transposed queries] | lists
-    unsigned char* hdr = ws + align_up((uint64_t)n * 4);
+    const bool packed_plan = plan.path == KNN_PATH_MFMA_PACKED;
+    const uint64_t n64 = ((uint64_t)n + kPkStep - 1) / kPkStep * kPkStep;
+    unsigned char* hdr = ws + align_up((packed_plan ? n64 : (uint64_t)n) * 4);
+    unsigned char* xp = hdr + kAlign;  // path 6: the points rounded to bf16
+    // path 6 needs 16-byte aligned rows; other calls run its plan on path 5's kernel
+    const bool packed = packed_plan && packed_rows_aligned(Q, ldq, X, ldx, d);
+    const int64_t warm = pk_warm_points(k);
     unsigned char* qs = ws + plan.norms_bytes;
     float* qn = reinterpret_cast<float*>(
         qs + align_up((uint64_t)plan.chunk_rows * 32 * (((uint64_t)d + kSpKC - 1) / kSpKC)));
     unsigned char* tsh = reinterpret_cast<unsigned char*>(qn) + align_up((uint64_t)plan.chunk_rows * 4);
+    unsigned char* tsr = tsh + align_up((uint64_t)plan.chunk_rows * 4);  // path 6: [rows][S] words
     unsigned char* lists = ws + plan.norms_bytes + plan.query_bytes;
     float* lk = reinterpret_cast<float*>(lists);
     int* li = reinterpret_cast<int*>(lists + plan.lists_bytes / 2);
@@ -168,10 +175,14 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     const bool cosine = metric == KNN_METRIC_COSINE;
 
     hipError_t e;
-    if (plan.path == KNN_PATH_MFMA_SPLIT) {
+    if (plan.path == KNN_PATH_MFMA_SPLIT || packed_plan) {
         hipEvent_t t0 = mark(stream);
         e = launch_row_norms(X, ldx, n, d, cosine, xn, stream);
         if (e == hipSuccess) e = launch_max_norm(xn, n, hdr, stream);
+        if (e == hipSuccess && packed) e = launch_pad_norms(xn, n, stream);
+        if (e == hipSuccess && packed) e = launch_residual_max(X, ldx, n, d, hdr, stream);
+        if (e == hipSuccess && packed)
+            e = launch_pack_operands(X, ldx, n, d, warm, (int64_t)n64 - warm, xp, stream);
         if (e != hipSuccess) {
             drop_bracket(t0);
             return hip_fail(e, "row norms launch");
@@ -202,12 +213,24 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
         else if (plan.path == KNN_PATH_LOWD_BF16)
             e = launch_lowd_bf16(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, plan.seed_cells, lk,
                                  li, stream);
-        else if (plan.path == KNN_PATH_MFMA_SPLIT) {
+        else if (plan.path == KNN_PATH_MFMA_SPLIT || packed_plan) {
             e = launch_split_queries(Qc, ldq, rows, d, qs, tsh, !keep_thresholds, stream);
             if (e == hipSuccess) e = launch_row_norms(Qc, ldq, rows, d, false, qn, stream);
-            if (e == hipSuccess)
-                e = launch_split(Qc, ldq, X, ldx, qs, qn, tsh, xn, hdr, cosine, rows, n, d, k, S,
-                                 lk, li, stream);
+            // path 6: the first points warm the lists on path 5's kernel, the rest follow out of
+            // the packed copy and continue the same S lists
+            if (e == hipSuccess && !packed)
+                e = launch_split(Qc, ldq, X, ldx, qs, qn, tsh, xn, hdr, cosine, rows, n, d, k, S, lk,
+                                 li, stream);
+            // path 6: the first points warm the list of range 0 on path 5's kernel (one range: the
+            // fewest pairs to evaluate), the rest follow out of the packed copy in S ranges
+            if (e == hipSuccess && packed)
+                e = launch_split(Qc, ldq, X, ldx, qs, qn, tsh, xn, hdr, false, rows, warm, d, k, 1, lk,
+                                 li, stream, S);
+            if (e == hipSuccess && packed)
+                e = launch_fill_words(tsr, rows * S, 0xff800000u, stream);
+            if (e == hipSuccess && packed)
+                e = launch_packed(Qc, ldq, X, ldx, xp, warm, qs, qn, tsh, tsr, xn, hdr, rows, n, d, k, S,
+                                  plan.tile_q / 32, warm, n, 1, lk, li, stream);
         } else
             e = hipErrorInvalidValue;  // no such path
         if (e != hipSuccess) {

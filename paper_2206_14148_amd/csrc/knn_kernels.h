@@ -50,14 +50,45 @@ hipError_t launch_lowd_bf16(const float* Q, int64_t ldq, const float* X, int64_t
 //                        (reset_thresholds false) kept from an earlier search of other points
 //                        for the same queries and the same k
 //   launch_split         the search; qn = squared norms of the chunk's queries (fp32, [rows]);
-//                        cosine: xn holds 1 / |x| and the keys are -2 q.x / |x|
+//                        cosine: xn holds 1 / |x| and the keys are -2 q.x / |x|;
+//                        list_S > S: the lists of a row are list_S * k entries apart (the S
+//                        ranges fill the first S of them, the others are not touched)
 hipError_t launch_max_norm(const float* xn, int64_t n, void* hdr, hipStream_t stream);
 hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d, void* qs,
                                 void* tsh, bool reset_thresholds, hipStream_t stream);
 hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* qs,
                         const float* qn, void* tsh, const float* xn, const void* hdr, bool cosine,
                         int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
-                        hipStream_t stream);
+                        hipStream_t stream, int list_S = 0);
+
+// 16 < d <= 256 with the points rounded to bf16 in the workspace (knn_packed.hip).
+//   launch_pack_operands  xp = `points` points from j_first on (j_first and points multiples of
+//                         64; rows past n are zero), ceil(d / 16) padded to an instantiated
+//                         chunk count x 32 bytes per point
+//   launch_pad_norms      xn[n .. next multiple of 64) = +inf
+//   launch_packed         the search of points [j_first, j_end) (j_first a multiple of 64) out of
+//                         the copy xp whose first point is slab_first, for queries whose B
+//                         operands, norms and shared thresholds are those of launch_split;
+//                         sets = query sets of 32 per workgroup (<= pk_max_sets); the lists of
+//                         ranges < init_from continue (launch_split filled them from other
+//                         points), the others start empty; tsr = [rows][S] words, set to
+//                         0xff800000 (+inf) beforehand: the key at position ceil(k / S) - 1 of
+//                         every range's list, through which the ranges bound each other.
+//                         Rows must be 16-byte aligned (packed_rows_aligned).
+hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, int64_t j_first,
+                                int64_t points, void* xp, hipStream_t stream);
+hipError_t launch_pad_norms(float* xn, int64_t n, hipStream_t stream);
+// hdr word 1 = max_j |x_j - bf16(x_j)|^2 (after launch_max_norm, which zeroes the header)
+hipError_t launch_residual_max(const float* X, int64_t ldx, int64_t n, int d, void* hdr,
+                               hipStream_t stream);
+bool packed_rows_aligned(const float* Q, int64_t ldq, const float* X, int64_t ldx, int d);
+hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* xp,
+                         int64_t slab_first, const void* qs, const float* qn, void* tsh, void* tsr,
+                         const float* xn, const void* hdr, int64_t rows, int64_t n, int d, int k, int S,
+                         int sets, int64_t j_first, int64_t j_end, int init_from, float* lk, int* li,
+                         hipStream_t stream);
+// p[0 .. count) = value (32-bit words)
+hipError_t launch_fill_words(void* p, int64_t count, unsigned value, hipStream_t stream);
 
 // Merge the S lists of each row, re-evaluate the k winners in fp64 (metric: knn_metric value),
 // order by (distance, index) and write idx / dist rows.

@@ -1,0 +1,606 @@
+// gfx950 (CDNA4, MI355X) kNN search for 16 < d <= 256 and many points: the bf16 matrix-core
+// filter of knn_split.hip with the roles of the operands swapped.
+//
+// The expansion sum x^2 - 2 q.x of paper section 4.1 runs on the values rounded to bf16 and only
+// filters; what passes is evaluated exactly (knn_exact.h) and merged into the query's list, so
+// the distance tile never leaves the registers (section 4.3) and the results do not depend on
+// the filter.  What differs from knn_split_kernel is where the operands live:
+//   - the points are rounded to bf16 ONCE, by knn_pack_operands_kernel, into a copy in the
+//     workspace that is laid out in the order of the MFMA's A operand, so that a wave fetches an
+//     operand with one coalesced 1 KB load straight into registers: no conversion, no LDS
+//     staging, no workgroup barrier in the search loop;
+//   - a workgroup keeps the B operands of up to 16 sets of 32 queries in LDS for its whole
+//     life; each of its 8 waves walks its own steps of 64 points, and for every step runs
+//     through all query sets: one 1 KB LDS read feeds two MFMAs, and the accumulators start
+//     from the points' squared norms through the MFMA's C operand, held in registers per step.
+// The eight waves therefore see different points for the same queries.  Pairs that pass the
+// filter go to per-query buffers in LDS that all waves append to (slots reserved with a
+// compare-and-swap, all of a wave's pairs for a query and step or none); when a buffer runs
+// full the workgroup stops at the next step boundary, the queries with enough buffered pairs are
+// dealt out over the waves, evaluated exactly and merged into their lists, and a (wave, query,
+// step) that found no room is made good by testing all 64 points of that step.
+//
+// The lists are warm when this kernel starts: the first pk_warm_points(k) points of X went
+// through knn_split_kernel, whose k-th keys bound every query's threshold from the first step on
+// (a list that starts from +inf would accept everything and spend its time in the stops).
+#include <hip/hip_runtime.h>
+
+#include <climits>
+#include <cmath>
+#include <cstdint>
+
+#include "knn_config.h"
+#include "knn_device.h"
+#include "knn_exact.h"
+#include "knn_kernels.h"
+
+namespace knn {
+
+namespace {
+
+// The points of a slab rounded to bf16 in A-operand order: step (64 points) -> row block (32) ->
+// chunk of 16 coordinates -> lane: lane (i32, h) holds coordinates 16 c + 8 h .. + 7 of point
+// 32 pb + i32, zero past d and past n.  One thread per (point, chunk, half): the reads of a
+// wave cover whole rows, the 16-byte writes come in runs of four lanes.
+template <bool ALIGNED>
+__global__ __launch_bounds__(256) void knn_pack_operands_kernel(const float* __restrict__ X,
+                                                                int64_t ldx, int n, int d, int nch,
+                                                                int j_first, int64_t pieces,
+                                                                uint4* __restrict__ Xp) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= pieces) return;
+    const int per_row = nch * 2;
+    const int rel = (int)(idx / per_row);
+    const int piece = (int)(idx - (int64_t)rel * per_row);
+    const int c = piece >> 1, h = piece & 1;
+    const int j = j_first + rel;
+    const bool ok = j < n;
+    const int col = c * 16 + h * 8;
+    const f32x4 v0 = mask_row4(load_row4<ALIGNED>(X, ldx, j, n, col, d), ok, col, d, 1.f);
+    const f32x4 v1 = mask_row4(load_row4<ALIGNED>(X, ldx, j, n, col + 4, d), ok, col + 4, d, 1.f);
+    const uint4 w = {round_pair(v0[0], v0[1]), round_pair(v0[2], v0[3]), round_pair(v1[0], v1[1]),
+                     round_pair(v1[2], v1[3])};
+    const int st = rel >> 6, pb = (rel >> 5) & 1, i32 = rel & 31;
+    Xp[((size_t)(st * 2 + pb) * nch + c) * 64 + h * 32 + i32] = w;
+}
+
+// float - its bf16 rounding (exact in fp32)
+__device__ __forceinline__ float bf16_residual(float v) {
+    return v - __uint_as_float(round_pair(v, 0.f) << 16);
+}
+
+// hdr word 1 = max over the points of |x - bf16(x)|^2, the rounding residual the filter has to
+// allow for: one wave per row (bits of a non-negative float, so an integer maximum orders them).
+__global__ __launch_bounds__(256) void knn_residual_max_kernel(const float* __restrict__ X, int64_t ldx,
+                                                               int64_t n, int d, unsigned* __restrict__ hdr) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    float worst = 0.f;
+    for (int64_t j = wave; j < n; j += nwaves) {
+        const float* row = X + j * ldx;
+        float acc = 0.f;
+        for (int t = lane; t < d; t += kWave) {
+            const float r = bf16_residual(row[t]);
+            acc = fmaf(r, r, acc);
+        }
+#pragma unroll
+        for (int s = 32; s > 0; s >>= 1) acc += __shfl_xor(acc, s);
+        worst = fmaxf(worst, acc);
+    }
+    if (lane == 0) atomicMax(hdr + 1, __float_as_uint(worst));
+}
+
+// norms past n (up to the end of the last step) are +inf: such a row never passes the filter
+__global__ void knn_pad_norms_kernel(float* __restrict__ xn, int n, int n_pad) {
+    const int i = n + blockIdx.x * 64 + threadIdx.x;
+    if (i < n_pad) xn[i] = kInf;
+}
+
+struct PkArgs {
+    const float* Q;
+    int64_t ldq;
+    const float* X;
+    int64_t ldx;
+    const uint4* Xp;       // packed points of the slab
+    const float* xn;       // squared norms of all points, +inf up to the end of the last step
+    const uint4* Qs;       // B operands of the chunk's queries (knn_split_queries_kernel)
+    const float* qnorm;    // their squared norms
+    unsigned* tsh;         // [rows] lowest k-th key any range of the query has reached
+                           // (order-preserving words)
+    unsigned* tsr;         // [rows][S] key at position ceil(k / S) - 1 of each range's list
+    const unsigned* hdr;   // word 0: max of xn
+    float* lk;
+    int* li;
+    int rows, n, d, nch_real, k, S, sets, tiles;
+    int step_slab0;   // step index of the slab's first step (a step = 64 consecutive points)
+    int step_first;   // first step this launch covers
+    int step_end;     // one past the last
+    int range_steps;  // steps per point range
+    int init_from;    // the lists of ranges >= this start empty, the others continue
+    int j_valid;      // a valid point index for lanes that hold no candidate
+#ifdef KNN_PK_STATS
+    unsigned long long* stats;
+#endif
+};
+#ifdef KNN_PK_STATS
+#define PK_STAT(i, v) do { if (a.stats && lane == 0) atomicAdd(ctl + 32 + (i), (int)(v)); } while (0)
+#define PK_CLOCK() wall_clock64()
+#else
+#define PK_STAT(i, v) do { } while (0)
+#define PK_CLOCK() 0ull
+#endif
+
+enum { kCtlStop = 16, kCtlCount = 17, kCtlDone = 18, kCtlNext = 19 };
+
+template <int NCH, bool ALIGNED>
+__global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkArgs a) {
+    constexpr int C = kPkCand;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i32 = lane & 31;
+    const int h = lane >> 5;
+    const int sets = a.sets, Qw = sets * 32, k = a.k, S = a.S;
+    // consecutive workgroups take consecutive query tiles of one range: the workgroups that are
+    // resident together (on every XCD) walk the same points at about the same time
+    const int s = blockIdx.x / a.tiles;
+    const int wg_row0 = (blockIdx.x - s * a.tiles) * Qw;
+
+    uint4* const Bq = reinterpret_cast<uint4*>(smem);                // [sets][NCH][64]
+    int* const cand = reinterpret_cast<int*>(Bq + (size_t)sets * NCH * 64);  // [Qw][C]
+    float* const qn_l = reinterpret_cast<float*>(cand + Qw * C);     // [Qw] squared norms
+    float* const own_l = qn_l + Qw;      // [Qw] k-th key of the query's list in this range
+    float* const tauf_l = own_l + Qw;    // [Qw] filter thresholds
+    int* const alloc_l = reinterpret_cast<int*>(tauf_l + Qw);  // [Qw] buffered pairs
+    int* const ovf_l = alloc_l + Qw;     // [Qw] bit 2 w + p: wave w found no room in its step of parity p
+    int* const queue_l = ovf_l + Qw;     // [Qw] queries a stop has to serve
+    float* const cross_l = reinterpret_cast<float*>(queue_l + Qw);  // [Qw] allowance for the rounded operands
+    float* const scratch = cross_l + Qw;  // [waves][2 * 64 + 2 k]
+    float* const xn_stage = scratch + (size_t)kPkWaves * (2 * kWave + 2 * k);  // [waves][64]
+    int* const ctl = reinterpret_cast<int*>(xn_stage + kPkWaves * 64);
+    // ctl[2 w + p]: the step wave w walks in its iterations of parity p; then the three words above
+
+    for (int i = tid; i < sets * NCH * 64; i += 64 * kPkWaves) {
+        const int qs = i / (NCH * 64);
+        const int rem = i - qs * (NCH * 64);
+        const int c = rem >> 6, ln = rem & 63;
+        const int row = min(wg_row0 + qs * 32 + (ln & 31), a.rows - 1);
+        uint4 v = {0u, 0u, 0u, 0u};
+        if (c < a.nch_real) v = a.Qs[((size_t)row * a.nch_real + c) * 2 + (ln >> 5)];
+        Bq[i] = v;
+    }
+    // The filter bound.  The filter key is  xn_j + sum_t bf16(x_jt) bf16(-2 q_it)  accumulated in
+    // fp32, the exact test gives dd = sum (q - x)^2 in fp32; dd <= tau implies
+    // key < (tau - qn) + slack with
+    //   rounded operands    sum x~ q~' - sum x q' = sum x~ (q~' - q') + sum (x~ - x) q'  (q' = -2 q),
+    //                       at most |x~| |q~' - q'| + |x~ - x| |q'| by Cauchy-Schwarz: the queries'
+    //                       residual norms rq are taken here, the largest residual norm of a
+    //                       point comes with the header, |x~| <= sqrt(xmax) + that; 1 % on top
+    //                       for the fp32 arithmetic of these norms.  (The worst case, 2^-8 of
+    //                       every value, is about 2.5 times this on ordinary data.)
+    //   fp32 accumulations   one per coordinate (padded), of terms that sum to at most
+    //                       2.02 |x| |q| in magnitude
+    //   roundings of xn, qn, dd   each below (d / 64 + 8) ulps of the value
+    // The constants below cover the first in full and are at least twice the others.
+    const float xmax = __uint_as_float(a.hdr[0]);
+    const float rxm = sqrtf(__uint_as_float(a.hdr[1]));
+    const float e_acc = (float)(4 * (NCH * 16) + 32) * 0x1p-24f;
+    const float e_sum = (float)(a.d + 16) * 0x1p-23f;
+    auto key_bound = [&](float t, float qn, float cross) {
+        return (t - qn) + (cross + e_sum * (xmax + qn + t) + 0x1p-126f);
+    };
+    // Thresholds.  A query's S ranges run in different workgroups; any upper bound of the k-th
+    // smallest key over ALL points may cut every range's candidates:
+    //   own     the k-th key of this range's list;
+    //   tsh[r]  the lowest k-th key any range has published;
+    //   tsr     every range publishes the key at position p = ceil(k / S) - 1 of its list: the
+    //           ranges hold different points, so at least S (p + 1) >= k keys are at or below the
+    //           largest of the S published values.  A range that has seen a fraction of the
+    //           points finds its (k / S)-th best where the whole stream's k-th best lies, so
+    //           this bound is as tight as one list over all points would give.
+    const int pos_s = (k + S - 1) / S - 1;
+    auto shared_cap = [&](int r) {
+        float c = 0.f;
+        bool all_finite = true;
+        for (int t = 0; t < S; ++t) {
+            const float v = word_key(
+                __hip_atomic_load(a.tsr + (size_t)r * S + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            all_finite = all_finite && v < kInf;
+            c = t == 0 ? v : fmaxf(c, v);
+        }
+        const float lowest =
+            word_key(__hip_atomic_load(a.tsh + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        return all_finite ? fminf(c, lowest) : lowest;
+    };
+    const bool init_mine = s >= a.init_from;
+    if (tid < Qw) {
+        const int r = wg_row0 + tid;
+        const bool active = r < a.rows;
+        const int rc = active ? r : a.rows - 1;
+        const float qn = a.qnorm[rc];
+        qn_l[tid] = qn;
+        // |bf16(-2 q) - (-2 q)|^2 of this query
+        float rq2 = 0.f;
+        {
+            const float* qrow = a.Q + (int64_t)rc * a.ldq;
+            for (int t = 0; t < a.d; t += 4) {  // rows are 16-byte aligned, d % 4 == 0
+                const f32x4 v = *reinterpret_cast<const f32x4*>(qrow + t);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float r = bf16_residual(-2.f * v[e]);
+                    rq2 = fmaf(r, r, rq2);
+                }
+            }
+        }
+        const float cross = 1.01f * ((sqrtf(xmax) + rxm) * sqrtf(rq2) + rxm * 2.f * sqrtf(qn)) +
+                            e_acc * sqrtf(xmax * qn);
+        cross_l[tid] = cross;
+        float own = -kInf;  // a row past the chunk: nothing passes
+        if (active) {
+            const size_t lb = ((size_t)r * S + s) * k;
+            own = init_mine ? kInf : a.lk[lb + (k - 1)];
+            if (!init_mine)
+                __hip_atomic_store(a.tsr + (size_t)r * S + s, key_word(a.lk[lb + pos_s]), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
+        own_l[tid] = own;
+        tauf_l[tid] = active ? key_bound(fminf(own, shared_cap(rc)), qn, cross) : -kInf;
+        alloc_l[tid] = 0;
+        ovf_l[tid] = 0;
+    }
+    if (tid < 64) ctl[tid] = tid == kCtlNext ? a.step_first + s * a.range_steps : 0;
+    if (init_mine) {
+        for (int e = tid; e < Qw * k; e += 64 * kPkWaves) {
+            const int q = e / k;
+            const int r = wg_row0 + q;
+            if (r < a.rows) {
+                const size_t at = ((size_t)r * S + s) * k + (e - q * k);
+                a.lk[at] = kInf;
+                a.li[at] = kNoIdx;
+            }
+        }
+    }
+    __syncthreads();
+
+    // The range's steps are handed out one at a time (a counter in LDS): the waves of a SIMD do
+    // not run at the same pace (the older wave of a pair is served first), and with fixed shares
+    // the faster ones would stand idle at the end of the range.
+    const int step_lo = a.step_first + s * a.range_steps;
+    const int step_hi = min(step_lo + a.range_steps, a.step_end);
+    auto take_step = [&]() {
+        int v = 0;
+        if (lane == 0) v = atomicAdd(ctl + kCtlNext, 1);
+        return __builtin_amdgcn_readfirstlane(v);
+    };
+    uint4 A[2][NCH];
+    f32x16 XN[2];
+    auto loadA = [&](int st) {
+        const uint4* p = a.Xp + (size_t)(st - a.step_slab0) * (2 * NCH * 64) + lane;
+#pragma unroll
+        for (int pb = 0; pb < 2; ++pb)
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) A[pb][c] = p[(pb * NCH + c) * 64];
+    };
+    // the step's 64 norms, one per lane, into the accumulator layout: register e of a lane of
+    // half h belongs to point row 8 (e / 4) + 4 h + e % 4 of its block
+    float* const xs = xn_stage + wave * 64;
+    // (the wave's LDS accesses execute in program order, so the reads below see the write
+    // without a fence - and a fence would also wait for the A operands that are in flight)
+    auto spread_xn = [&](float v) {
+        __builtin_amdgcn_wave_barrier();
+        xs[lane] = v;
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int pb = 0; pb < 2; ++pb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 t = *reinterpret_cast<const f32x4*>(xs + pb * 32 + g * 8 + h * 4);
+                XN[pb][g * 4 + 0] = t[0];
+                XN[pb][g * 4 + 1] = t[1];
+                XN[pb][g * 4 + 2] = t[2];
+                XN[pb][g * 4 + 3] = t[3];
+            }
+    };
+
+    // Pairs of query q (this lane's, in set qs) under its threshold: nearly always one key of the
+    // whole wave, so every accumulator register gets a vote, and a lane whose key passes takes a
+    // slot of the query's buffer (a counter in LDS that all waves add to).  A pair that finds
+    // the buffer full marks (wave, step parity) for the query: the stop then tests all 64 points
+    // of that step for it and drops what the buffer already holds of them.
+    auto append = [&](int q, float tq, const f32x16& a0, const f32x16& a1, int st, int parity) {
+        bool call = false;
+        const int jb = st * kPkStep + h * 4;
+        auto one = [&](float key, int j) {
+            if (__builtin_amdgcn_ballot_w64(key < tq) == 0) return;
+            if (key < tq) {
+                const int slot = atomicAdd(&alloc_l[q], 1);
+                if (slot < C) cand[q * C + slot] = j;
+                else atomicOr(&ovf_l[q], 1 << (wave * 2 + parity));
+                call = call || slot >= C - kPkRoom;
+            }
+        };
+#pragma unroll
+        for (int e = 0; e < 16; ++e) one(a0[e], jb + (e >> 2) * 8 + (e & 3));
+#pragma unroll
+        for (int e = 0; e < 16; ++e) one(a1[e], jb + 32 + (e >> 2) * 8 + (e & 3));
+        if (__builtin_amdgcn_ballot_w64(call) != 0 && lane == 0)
+            __hip_atomic_store(ctl + kCtlStop, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+
+    // One query set against the wave's 64 points.  roll: this is the step's last use of the A
+    // operands, and the next step's are requested into the registers as they fall free.
+    auto body = [&](int qs, bool roll, const uint4* xnext, int st, int parity) {
+        const int q = qs * 32 + i32;
+        const float tq = tauf_l[q];
+        const uint4* bq = Bq + (size_t)qs * (NCH * 64) + lane;
+        f32x16 acc0, acc1;
+        // the B operands are read kPkAhead chunks ahead of their use
+        constexpr int AH = NCH < 4 ? NCH : 4;
+        uint4 bw[AH];
+#pragma unroll
+        for (int c = 0; c < AH; ++c) bw[c] = bq[c * 64];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const bf16x8 b = __builtin_bit_cast(bf16x8, bw[c % AH]);
+            if (c + AH < NCH) bw[c % AH] = bq[(c + AH) * 64];
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[0][c]), b,
+                                                           c == 0 ? XN[0] : acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[1][c]), b,
+                                                           c == 0 ? XN[1] : acc1, 0, 0, 0);
+            if (roll) {
+                A[0][c] = xnext[c * 64];
+                A[1][c] = xnext[(NCH + c) * 64];
+            }
+        }
+        float m0 = acc0[0], m1 = acc1[0];
+#pragma unroll
+        for (int e = 1; e < 16; e += 2) {
+            m0 = fminf(fminf(m0, acc0[e]), acc0[e + 1 < 16 ? e + 1 : e]);
+            m1 = fminf(fminf(m1, acc1[e]), acc1[e + 1 < 16 ? e + 1 : e]);
+        }
+        if (__builtin_amdgcn_ballot_w64(fminf(m0, m1) < tq) != 0) {
+            PK_STAT(7, 1);
+            append(q, tq, acc0, acc1, st, parity);
+        }
+    };
+
+    // A stop: every wave of the workgroup is here, nobody appends.  The queries with enough
+    // buffered pairs (everything: all that have any) and those with a step to make good are
+    // dealt out over the waves; then every query's filter threshold is brought up to date.
+    float* const my_scratch = scratch + (size_t)wave * (2 * kWave + 2 * k);
+    auto stop_work = [&](bool everything) {
+        if (tid == 0) ctl[kCtlStop] = 0;
+        const int share = everything ? 1 : kPkShareMin;
+        if (tid < Qw && (alloc_l[tid] >= share || ovf_l[tid] != 0))
+            queue_l[atomicAdd(ctl + kCtlCount, 1)] = tid;
+        __syncthreads();
+        const int nq = ctl[kCtlCount];
+        if (wave == 0) { PK_STAT(0, 1); PK_STAT(1, nq); }
+        const unsigned long long tf0 = PK_CLOCK();
+        for (int e = wave; e < nq; e += kPkWaves) {
+            const int q = __builtin_amdgcn_readfirstlane(queue_l[e]);
+            const int r = wg_row0 + q;
+            const size_t lb = ((size_t)r * S + s) * k;
+            const int cc = min(C, __builtin_amdgcn_readfirstlane(alloc_l[q]));
+            unsigned rem = (unsigned)__builtin_amdgcn_readfirstlane(ovf_l[q]);
+            unsigned t_bits = __float_as_uint(own_l[q]);
+            // work items: the buffer, then the two row blocks of every step to make good
+            // what the buffer holds of a step that is made good in full is dropped (-1: no pair)
+            if (rem != 0 && lane < cc) {
+                const int j = cand[q * C + lane];
+                bool drop = false;
+                for (unsigned bits = rem; bits != 0; bits &= bits - 1)
+                    drop = drop || (j >> 6) == ctl[__builtin_ctz(bits)];
+                if (drop) cand[q * C + lane] = -1;
+            }
+            int item = 0, half = 0;
+            for (;;) {
+                const int* cbuf = cand + q * C;
+                int jb = 0, n_c = cc;
+                if (item != 0) {
+                    if (rem == 0) break;
+                    const int bit = __builtin_ctz(rem);
+                    const int stv = __builtin_amdgcn_readfirstlane(ctl[bit]);
+                    cbuf = nullptr;
+                    jb = stv * kPkStep + half * 32;
+                    n_c = min(32, a.n - jb);
+                    if (half == 1) rem &= rem - 1;
+                    half ^= 1;
+                }
+                ++item;
+                if (n_c > 0) { PK_STAT(item == 1 ? 2 : 3, n_c); }
+                if (n_c > 0)
+                    t_bits = flush_query_exact<ALIGNED, 8>(a.Q + (int64_t)r * a.ldq, a.X, a.ldx, a.d,
+                                                           a.j_valid, cbuf, jb, n_c, a.lk + lb, a.li + lb,
+                                                           k, my_scratch, a.tsh + r, nullptr, lane);
+            }
+            if (lane == 0) {
+                own_l[q] = __uint_as_float(t_bits);
+                alloc_l[q] = 0;
+                ovf_l[q] = 0;
+                // (the merge ends with a wave_sync: the list's new entries are visible here)
+                __hip_atomic_store(a.tsr + (size_t)r * S + s, key_word(a.lk[lb + pos_s]), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        PK_STAT(8, PK_CLOCK() - tf0);
+        __syncthreads();
+        if (tid == 0) ctl[kCtlCount] = 0;
+        if (tid < Qw && wg_row0 + tid < a.rows)
+            tauf_l[tid] = key_bound(fminf(own_l[tid], shared_cap(wg_row0 + tid)), qn_l[tid], cross_l[tid]);
+        __syncthreads();
+    };
+
+    // Every path out of a stop loads the A operands and norms again, so that nothing of them is
+    // live across it (a wave that has no step left loads a valid one for nothing).
+    const int step_any = a.step_first;
+    int step = take_step();
+    bool have = step < step_hi;
+    loadA(have ? step : step_any);
+    spread_xn(a.xn[(size_t)(have ? step : step_any) * kPkStep + lane]);
+    const unsigned long long tk0 = PK_CLOCK();
+    int parity = 0;
+    bool announced = false;
+    float xn_next = 0.f;
+    for (;;) {
+        if (have) {
+            if (lane == 0) ctl[wave * 2 + parity] = step;
+            const int taken = take_step();
+            const bool has_next = taken < step_hi;
+            const int nstep = has_next ? taken : step;
+            xn_next = a.xn[(size_t)nstep * kPkStep + lane];
+            const uint4* xnext = a.Xp + (size_t)(nstep - a.step_slab0) * (2 * NCH * 64) + lane;
+            for (int qs = 0; qs + 1 < sets; ++qs) body(qs, false, xnext, step, parity);
+            const int stop = __builtin_amdgcn_readfirstlane(
+                __hip_atomic_load(ctl + kCtlStop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+            if (stop == 0) {
+                body(sets - 1, true, xnext, step, parity);
+                step = nstep;
+                have = has_next;
+                parity ^= 1;
+                spread_xn(xn_next);
+                continue;
+            }
+            body(sets - 1, false, xnext, step, parity);
+            step = nstep;
+            have = has_next;
+            parity ^= 1;
+        } else if (!announced) {
+            if (lane == 0) atomicAdd(ctl + kCtlDone, 1);
+            announced = true;
+        }
+        const unsigned long long ts0 = PK_CLOCK();
+        __syncthreads();
+        const unsigned long long ts1 = PK_CLOCK();
+        const bool all_done = ctl[kCtlDone] == kPkWaves;
+        stop_work(all_done);
+        if (wave == 0) { PK_STAT(6, ts1 - ts0); PK_STAT(4, PK_CLOCK() - ts0); if (announced) { PK_STAT(10, ts1 - ts0); PK_STAT(11, 1); } }
+        if (wave == 5) { PK_STAT(12, ts1 - ts0); if (announced) { PK_STAT(13, ts1 - ts0); } }
+        if (all_done) break;
+        loadA(have ? step : step_any);
+        spread_xn(have ? xn_next : 0.f);
+    }
+    if (wave == 0) { PK_STAT(5, PK_CLOCK() - tk0); PK_STAT(9, 1); }
+#ifdef KNN_PK_STATS
+    __syncthreads();
+    if (a.stats && tid < 16) atomicAdd(a.stats + tid, (unsigned long long)ctl[32 + tid]);
+#endif
+}
+
+}  // namespace
+
+#ifdef KNN_PK_STATS
+static unsigned long long* g_pk_stats = nullptr;
+extern "C" void knn_debug_set_stats(void* p) { g_pk_stats = static_cast<unsigned long long*>(p); }
+#endif
+
+hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, int64_t j_first,
+                                int64_t points, void* xp, hipStream_t stream) {
+    const int nch = pk_padded_chunks((d + kSpKC - 1) / kSpKC);
+    const int64_t pieces = points * nch * 2;
+    const dim3 grid((unsigned)((pieces + 255) / 256));
+    const bool aligned = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 4 == 0) && (d % 4 == 0);
+    if (aligned)
+        knn_pack_operands_kernel<true><<<grid, dim3(256), 0, stream>>>(X, ldx, (int)n, d, nch, (int)j_first,
+                                                                       pieces, static_cast<uint4*>(xp));
+    else
+        knn_pack_operands_kernel<false><<<grid, dim3(256), 0, stream>>>(X, ldx, (int)n, d, nch, (int)j_first,
+                                                                        pieces, static_cast<uint4*>(xp));
+    return hipGetLastError();
+}
+
+hipError_t launch_residual_max(const float* X, int64_t ldx, int64_t n, int d, void* hdr,
+                               hipStream_t stream) {
+    int64_t blocks = (n + 3) / 4;
+    if (blocks > 16384) blocks = 16384;
+    knn_residual_max_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
+        X, ldx, n, d, static_cast<unsigned*>(hdr));
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_norms(float* xn, int64_t n, hipStream_t stream) {
+    const int64_t n_pad = (n + kPkStep - 1) / kPkStep * kPkStep;
+    if (n_pad > n) knn_pad_norms_kernel<<<dim3(1), dim3(64), 0, stream>>>(xn, (int)n, (int)n_pad);
+    return hipGetLastError();
+}
+
+bool packed_rows_aligned(const float* Q, int64_t ldq, const float* X, int64_t ldx, int d) {
+    return (reinterpret_cast<uintptr_t>(Q) % 16 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
+           (ldq % 4 == 0) && (ldx % 4 == 0) && (d % 4 == 0);
+}
+
+hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* xp,
+                         int64_t slab_first, const void* qs, const float* qn, void* tsh, void* tsr,
+                         const float* xn, const void* hdr, int64_t rows, int64_t n, int d, int k, int S,
+                         int sets, int64_t j_first, int64_t j_end, int init_from, float* lk, int* li,
+                         hipStream_t stream) {
+    const int nch_real = (d + kSpKC - 1) / kSpKC;
+    const int nch = pk_padded_chunks(nch_real);
+    if (nch > kPkMaxChunks || sets < 1 || sets > pk_max_sets(nch, k) || !packed_rows_aligned(Q, ldq, X, ldx, d) ||
+        j_first % kPkStep != 0 || slab_first % kPkStep != 0 || j_first < slab_first || j_end <= j_first ||
+        j_end > n)
+        return hipErrorInvalidValue;
+    PkArgs a;
+    a.Q = Q;
+    a.ldq = ldq;
+    a.X = X;
+    a.ldx = ldx;
+    a.Xp = static_cast<const uint4*>(xp);
+    a.xn = xn;
+    a.Qs = static_cast<const uint4*>(qs);
+    a.qnorm = qn;
+    a.tsh = static_cast<unsigned*>(tsh);
+    a.tsr = static_cast<unsigned*>(tsr);
+    a.hdr = static_cast<const unsigned*>(hdr);
+    a.lk = lk;
+    a.li = li;
+    a.rows = (int)rows;
+    a.n = (int)n;
+    a.d = d;
+    a.nch_real = nch_real;
+    a.k = k;
+    a.S = S;
+    a.sets = sets;
+    a.tiles = (int)((rows + sets * 32 - 1) / (sets * 32));
+    a.step_slab0 = (int)(slab_first / kPkStep);
+    a.step_first = (int)(j_first / kPkStep);
+    a.step_end = (int)((j_end + kPkStep - 1) / kPkStep);
+    // ranges of whole rounds of the eight waves
+    const int steps = a.step_end - a.step_first;
+    int per = (steps + S - 1) / S;
+    per = (per + kPkWaves - 1) / kPkWaves * kPkWaves;
+    a.range_steps = per;
+    a.init_from = init_from;
+    a.j_valid = (int)j_first;
+#ifdef KNN_PK_STATS
+    a.stats = g_pk_stats;
+#endif
+    const size_t lds = (size_t)pk_lds_bytes(nch, k, sets);
+    const dim3 grid((unsigned)(a.tiles * S));
+#define KNN_PACKED_LAUNCH(N)                                                                   \
+    do {                                                                                       \
+        hipError_t e2 = raise_lds_limit(knn_packed_kernel<N, true>, lds);                      \
+        if (e2 != hipSuccess) return e2;                                                       \
+        knn_packed_kernel<N, true><<<grid, dim3(64 * kPkWaves), lds, stream>>>(a);             \
+    } while (0)
+    switch (nch) {
+        case 2: KNN_PACKED_LAUNCH(2); break;
+        case 3: KNN_PACKED_LAUNCH(3); break;
+        case 4: KNN_PACKED_LAUNCH(4); break;
+        case 5: KNN_PACKED_LAUNCH(5); break;
+        case 6: KNN_PACKED_LAUNCH(6); break;
+        case 7: KNN_PACKED_LAUNCH(7); break;
+        case 8: KNN_PACKED_LAUNCH(8); break;
+        case 10: KNN_PACKED_LAUNCH(10); break;
+        case 12: KNN_PACKED_LAUNCH(12); break;
+        case 14: KNN_PACKED_LAUNCH(14); break;
+        case 16: KNN_PACKED_LAUNCH(16); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef KNN_PACKED_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace knn

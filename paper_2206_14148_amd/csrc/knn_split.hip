@@ -20,35 +20,16 @@
 
 #include "knn_config.h"
 #include "knn_device.h"
+#include "knn_exact.h"
 #include "knn_kernels.h"
 
 namespace knn {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-
-// bf16 (round to nearest even) of two floats in one word, the first in the low half
-__device__ __forceinline__ unsigned round_pair(float a, float b) {
-    const f32x2 p = {a, b};
-    return __builtin_bit_cast(unsigned, __builtin_convertvector(p, bf16x2));
-}
-
-// floats <-> unsigned words with the same order (for atomicMin on keys of either sign)
-__device__ __forceinline__ unsigned key_word(float f) {
-    const unsigned u = __float_as_uint(f);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float word_key(unsigned w) {
-    return __uint_as_float((w & 0x80000000u) ? (w & 0x7fffffffu) : ~w);
-}
-constexpr unsigned kInfWord = 0xff800000u;  // key_word(+inf)
-
 // header word 0 of the per-point area: max ||x||^2 (bits of a non-negative float)
 __global__ void knn_split_init_kernel(unsigned* __restrict__ hdr) {
-    if (threadIdx.x == 0) hdr[0] = 0u;
+    if (threadIdx.x < 2) hdr[threadIdx.x] = 0u;  // (word 1: the largest bf16 rounding residual, path 6)
 }
 
 __global__ __launch_bounds__(256) void knn_max_norm_kernel(const float* __restrict__ xn, int64_t n,
@@ -87,60 +68,10 @@ __global__ __launch_bounds__(256) void knn_split_queries_kernel(const float* __r
     o[1] = hi[1];
 }
 
-// One lane's share of the exact key of a candidate - sum_t (q_t - x_t)^2, or with DOT the
-// product sum_t q_t x_t of the cosine metric: the groups of four
-// coordinates g = part, part + 2, ... in ascending order, one fma chain.  The loads of two groups
-// are issued before the first is used.  More in flight would shorten the wait for a long row,
-// but every register this out-of-line path uses is one the search loop has to give up around
-// its calls: measured, eight groups in flight were slower than two (c5 99.6 against 88.9 ms).
-template <bool ALIGNED, bool DOT>
-__device__ __forceinline__ float exact_partial(const float* __restrict__ qp, const float* __restrict__ xp,
-                                               int d, int part) {
-    constexpr int U = 2;
-    float sum = 0.f;
-    const int ng = (d + 3) >> 2;  // groups of four coordinates (the last may be ragged)
-    for (int g0 = part; g0 < ng; g0 += 2 * U) {
-        f32x4 xv[U], qv[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int g = g0 + 2 * u;
-            const int gc = g < ng ? g : part;  // a valid group; its value is not used
-            if (ALIGNED) {
-                xv[u] = *reinterpret_cast<const f32x4*>(xp + 4 * gc);
-                qv[u] = *reinterpret_cast<const f32x4*>(qp + 4 * gc);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int t = 4 * gc + e < d ? 4 * gc + e : 0;
-                    xv[u][e] = xp[t];
-                    qv[u][e] = qp[t];
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int g = g0 + 2 * u;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float df = qv[u][e] - xv[u][e];
-                const float next = DOT ? fmaf(qv[u][e], xv[u][e], sum) : fmaf(df, df, sum);
-                sum = (g < ng && 4 * g + e < d) ? next : sum;
-            }
-        }
-    }
-    return sum;
-}
-
-// The rare path of knn_split_kernel for one query, out of line and with everything passed by
-// value, so that the search loop keeps its state in registers and pays for this only where it
-// is called.  The cc <= 32 candidates are the point indices cbuf[0 .. cc-1], or, with cbuf null,
-// the points jbase .. jbase + cc - 1.  Two lanes per
-// candidate: lane 2c + p sums the groups of four coordinates g = p, p + 2, ... (exact_partial),
-// the two partial sums are added; that order is part of the key's definition.  The keys are
-// merged into the query's list gk/gi, the list's k-th key is published in *tshr (atomic
-// minimum on order-preserving words).  rn != null selects the cosine metric: the key of point j
-// is -2 (q . x_j) rn[j] with the dot product summed in the same order.  Returns the list's new
-// k-th key as float bits.
+// Out of line and with everything passed by value, so that the search loop of knn_split_kernel
+// keeps its state in registers and pays for the rare path only where it is called.  Two groups
+// of a row in flight: every register this path uses is one the search loop has to give up
+// around its calls (measured, eight groups in flight were slower: c5 99.6 against 88.9 ms).
 template <bool ALIGNED>
 __device__ __noinline__ unsigned split_flush_query(const float* __restrict__ qp,
                                                    const float* __restrict__ X, int64_t ldx, int d,
@@ -149,37 +80,8 @@ __device__ __noinline__ unsigned split_flush_query(const float* __restrict__ qp,
                                                    float* __restrict__ gk, int* __restrict__ gi, int k,
                                                    float* scratch, unsigned* tshr,
                                                    const float* __restrict__ rn, int lane) {
-    MergeScratch sc;
-    sc.cand_key = scratch;
-    sc.cand_idx = reinterpret_cast<int*>(scratch + kWave);
-    sc.list_key = scratch + 2 * kWave;
-    sc.list_idx = reinterpret_cast<int*>(scratch + 2 * kWave + k);
-    wave_sync();
-    const int cand = lane >> 1, part = lane & 1;
-    const int j = cand < cc ? (cbuf ? cbuf[cand] : jbase + cand) : -1;
-    const int jl = j < 0 ? jsafe : j;
-    float sum;
-    if (rn) {
-        sum = exact_partial<ALIGNED, true>(qp, X + (int64_t)jl * ldx, d, part);
-        sum += lane_xor<1>(sum);
-        sum = (-2.f * sum) * rn[jl];
-    } else {
-        sum = exact_partial<ALIGNED, false>(qp, X + (int64_t)jl * ldx, d, part);
-        sum += lane_xor<1>(sum);
-    }
-    // candidate c sits in lanes 2c, 2c + 1; the merge wants it in lane c
-    const int src = (2 * lane) & 63;
-    float key = __shfl(sum, src);
-    int id = __shfl(j, src);
-    if (lane >= cc) {
-        key = kInf;
-        id = kNoIdx;
-    }
-    const uint64_t mr = wave_merge_pair_inline(gk, gi, k, key, id, sc, lane, cc);
-    const unsigned t_bits = (unsigned)mr;
-    // no value returned: nothing waits for the round trip
-    if (lane == 0) atomicMin(tshr, key_word(__uint_as_float(t_bits)));
-    return t_bits;
+    return flush_query_exact<ALIGNED, 2>(qp, X, ldx, d, jsafe, cbuf, jbase, cc, gk, gi, k, scratch,
+                                         tshr, rn, lane);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -213,7 +115,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
     const uint4* __restrict__ Qs, const float* __restrict__ qnorm, unsigned* tsh,
     const float* __restrict__ xn, const unsigned* __restrict__ hdr, int cosine, int rows, int n,
-    int d, int nch_real, int k, int S, int split_len, int BQ, int BS, float* __restrict__ lk,
+    int d, int nch_real, int k, int S, int LS, int split_len, int BQ, int BS, float* __restrict__ lk,
     int* __restrict__ li) {
     // steps per tile that the pipeline walks, W chunks of 16 coordinates each (the chunks past
     // the real count meet zero B operands)
@@ -234,7 +136,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     if (!xcd_block_map(rows, TQ, S, BQ, BS, s, wg_row0)) return;  // padding (before any barrier)
     const int wave_row0 = wg_row0 + wave * 32;
     int* wci = ci + wave * 32 * C;
-    init_lists32(lk, li, wave_row0, rows, S, s, k, lane);
+    init_lists32(lk, li, wave_row0, rows, LS, s, k, lane);
 
     const float xmax = __uint_as_float(hdr[0]);
     // Filter keys are  xn_j - 2 bf16(x).bf16(q)  accumulated in fp32; the exact test gives
@@ -284,7 +186,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     // jbase ..), merged into its list; the lanes of the query get the new thresholds
     auto flush_one = [&](int L, bool from_range, int jbase, int cc) {
         const int r = wave_row0 + L;
-        const size_t lb = ((size_t)r * S + s) * k;
+        const size_t lb = ((size_t)r * LS + s) * k;
         const unsigned fr = split_flush_query<ALIGNED>(
             Q + (int64_t)r * ldq, X, ldx, d, j0, from_range ? nullptr : wci + L * C, jbase, cc,
             lk + lb, li + lb, k, my_scratch, tsh + r, cosine ? xn : nullptr, lane);
@@ -346,7 +248,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
         for (int e = wave; e < nq; e += kSpWaves) {
             const int q = co_queue[e];
             const int r = wg_row0 + q;
-            const size_t lb = ((size_t)r * S + s) * k;
+            const size_t lb = ((size_t)r * LS + s) * k;
             const unsigned fr = split_flush_query<ALIGNED>(
                 Q + (int64_t)r * ldq, X, ldx, d, j0, ci + q * C, 0, co_cnt[q], lk + lb, li + lb, k,
                 my_scratch, tsh + r, cosine ? xn : nullptr, lane);
@@ -580,6 +482,13 @@ hipError_t launch_max_norm(const float* xn, int64_t n, void* hdr, hipStream_t st
     return hipGetLastError();
 }
 
+hipError_t launch_fill_words(void* p, int64_t count, unsigned value, hipStream_t stream) {
+    if (count > 0)
+        knn_fill_words_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream>>>(
+            static_cast<unsigned*>(p), count, value);
+    return hipGetLastError();
+}
+
 hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d, void* qs,
                                 void* tsh, bool reset_thresholds, hipStream_t stream) {
     const int nch = (d + kSpKC - 1) / kSpKC;
@@ -601,7 +510,7 @@ hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d
 hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* qs,
                         const float* qn, void* tsh, const float* xn, const void* hdr, bool cosine,
                         int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
-                        hipStream_t stream) {
+                        hipStream_t stream, int list_S) {
     const int nch = (d + kSpKC - 1) / kSpKC;
     const size_t lds_fixed = (size_t)4 * kSpTileX * 4 + (size_t)kSpTileQ * kSpCand * 4 +
                              (size_t)kSpWaves * (2 * kWave + 2 * k) * 4 +
@@ -627,6 +536,7 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
         knn_split_kernel<W, N, A><<<grid, dim3(64 * kSpWaves), lds, stream>>>(                    \
             Q, ldq, X, ldx, static_cast<const uint4*>(qs), qn, static_cast<unsigned*>(tsh), xn,   \
             static_cast<const unsigned*>(hdr), cosine ? 1 : 0, (int)rows, (int)n, d, nch, k, S,   \
+            list_S > 0 ? list_S : S,                                                            \
             (int)split_len, BQ, BS, lk, li);                                                      \
     } while (0)
     // W chunks of 16 coordinates per pipeline step, N steps per tile with the queries resident

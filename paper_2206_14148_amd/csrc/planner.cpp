@@ -77,8 +77,10 @@ uint64_t lists_bytes_for(uint64_t rows, uint64_t S, uint64_t k) {
 // (qrow = 64 bytes per 16 coordinates), their squared norms and the thresholds their point
 // ranges share (a word each); kind 2 (L1 path): the queries transposed in blocks of 64 rows
 // (qrow = 16 bytes per 4 coordinates); kind 0: nothing.
-uint64_t query_bytes_for(uint64_t rows, uint64_t qrow, int kind) {
+uint64_t query_bytes_for(uint64_t rows, uint64_t qrow, int kind, uint64_t S = 1) {
     if (kind == 1) return align_up(rows * qrow) + 2 * align_up(rows * 4);
+    // kind 3 (path 6): as kind 1, and a word per query and point range
+    if (kind == 3) return align_up(rows * qrow) + 2 * align_up(rows * 4) + align_up(rows * S * 4);
     if (kind == 2) return align_up((rows + 63) / 64 * 64 * qrow);
     return 0;
 }
@@ -91,12 +93,13 @@ int64_t rows_fitting(uint64_t avail, uint64_t S, uint64_t k, uint64_t qrow, int 
         return knn_chunk_rows(usable, S * k * 4);
     }
     auto need = [&](uint64_t rows) {
-        return lists_bytes_for(rows, S, k) + query_bytes_for(rows, qrow, kind);
+        return lists_bytes_for(rows, S, k) + query_bytes_for(rows, qrow, kind, S);
     };
-    const uint64_t per_row = 2 * S * k * 4 + qrow + (kind == 1 ? 8 : 0);  // exact, roundings aside
-    // the roundings (five to kAlign, one to 64 rows) add less than this: start below the
+    const uint64_t per_row =
+        2 * S * k * 4 + qrow + (kind == 1 ? 8 : 0) + (kind == 3 ? 8 + S * 4 : 0);  // exact, roundings aside
+    // the roundings (six to kAlign, one to 64 rows) add less than this: start below the
     // answer, then step up to it
-    const uint64_t slack = 5 * kAlign + 64 * qrow;
+    const uint64_t slack = 6 * kAlign + 64 * qrow;
     uint64_t rows = avail > slack ? (avail - slack) / per_row : 0;
     while (need(rows + 1) <= avail) ++rows;
     return (int64_t)rows;
@@ -189,6 +192,67 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
                     out->seed_cells = (int32_t)G;
                     out->norms_bytes = packed16 + seed;
                 }
+            }
+        }
+    }
+    // 16 < d <= 256 and many points: with room for the points rounded to bf16 in operand order
+    // the search runs with the queries resident in LDS (knn_packed.hip).  Its workspace is that
+    // of path 5 plus the packed copy, so a call whose rows turn out not to be 16-byte aligned
+    // still runs under this plan, on path 5's kernel.
+    if (split && metric == KNN_METRIC_L2SQ && d > kSpKC && d <= kPkMaxChunks * kSpKC &&
+        n >= kPkMinPoints && n >= 4 * pk_warm_points(k)) {
+        const int nch_p = pk_padded_chunks((d + kSpKC - 1) / kSpKC);
+        const int sets_max = pk_max_sets(nch_p, k);
+        const uint64_t n64 = ((uint64_t)n + kPkStep - 1) / kPkStep * kPkStep;
+        const uint64_t per_point = align_up(n64 * 4) + kAlign + align_up(n64 * (uint64_t)nch_p * 32);
+        const int64_t min_rows = m < 64 ? m : 64;
+        if (sets_max >= 2 &&
+            mem_limit_bytes >= per_point + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k) +
+                                   query_bytes_for((uint64_t)min_rows, qrow, 3, 1)) {
+            // Query sets per workgroup and point ranges: a launch runs in rounds of one workgroup
+            // per compute unit, a workgroup's time goes with sets x (range + a start-up allowance).
+            const uint64_t avail6 = mem_limit_bytes - per_point;
+            double best = 0.0;
+            int best_sets = 0;
+            int64_t best_S = 0, best_r = 0;
+            for (int sets = sets_max; sets >= 2 && sets >= sets_max - 6; --sets) {
+                const int64_t tile6 = 32 * sets;
+                for (int64_t S = 1; S <= 32; ++S) {
+                    if ((n - pk_warm_points(k)) / S < 8 * kPkStep * 16) break;  // ranges of >= 16 rounds of the waves
+                    int64_t rows = rows_fitting(avail6, (uint64_t)S, (uint64_t)k, qrow, 3);
+                    if (rows > kMaxChunkRows) rows = kMaxChunkRows;
+                    if (rows >= m) rows = m;
+                    else rows = rows / tile6 * tile6;
+                    if (rows < 1) continue;
+                    const int64_t chunks = (m + rows - 1) / rows;
+                    const int64_t wgs = (rows + tile6 - 1) / tile6 * S;
+                    const int64_t rounds = (wgs + kNumCU - 1) / kNumCU;
+                    const double range = (double)((n + S - 1) / S);
+                    // larger tiles re-read the points less often: a mild preference
+                    // and fewer ranges mean fewer lists to fill and to merge
+                    const double cost = (double)chunks * (double)rounds * (double)sets *
+                                        (range + 4096.0 + 64.0 * (double)k) * (1.0 + 0.5 / (double)sets) *
+                                        (1.0 + 0.005 * (double)S);
+                    if (best_sets == 0 || cost < best) {
+                        best = cost;
+                        best_sets = sets;
+                        best_S = S;
+                        best_r = rows;
+                    }
+                }
+            }
+            if (best_sets != 0) {
+                out->path = KNN_PATH_MFMA_PACKED;
+                out->tile_q = 32 * best_sets;
+                out->tile_x = kPkStep;
+                out->norms_bytes = per_point;
+                out->n_splits = (int32_t)best_S;
+                out->chunk_rows = best_r;
+                out->q_chunks = (m + best_r - 1) / best_r;
+                out->lists_bytes = lists_bytes_for((uint64_t)best_r, (uint64_t)best_S, (uint64_t)k);
+                out->query_bytes = query_bytes_for((uint64_t)best_r, qrow, 3, (uint64_t)best_S);
+                out->workspace_bytes = out->norms_bytes + out->query_bytes + out->lists_bytes;
+                return KNN_OK;
             }
         }
     }

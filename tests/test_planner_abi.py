@@ -62,25 +62,26 @@ def test_chunk_rows_floor():
     assert K.knn_chunk_rows(5, 0) == 0
 
 
+# (m, n, d, k, limit, path): d <= 8 with room for the packed points takes the low-d matrix-core
+# filter; 16 < d <= 256 with room for the points rounded to bf16 (32 bytes per point and 16
+# coordinates: 2.56 GB at d = 128, n = 1e7; 1.02 GB at d = 256, n = 2e6) the packed path
 CONFIGS = [
-    (1_000, 10_000, 16, 10, 64 * 10 ** 6),
-    (1_000_000, 1_000_000, 3, 16, 10 ** 9),
-    (10_000, 1_000_000, 784, 10, 2 * 10 ** 9),
-    (100_000, 10_000_000, 128, 100, 8 * 10 ** 9),
-    (50_000, 2_000_000, 256, 32, 128 * 10 ** 6),
-    (50_000, 2_000_000, 256, 32, 10 ** 9),
-    (50_000, 2_000_000, 256, 32, 8 * 10 ** 9),
-    (50_000, 2_000_000, 256, 32, 64 * 10 ** 9),
+    (1_000, 10_000, 16, 10, 64 * 10 ** 6, K.KNN_PATH_MFMA_SPLIT),
+    (1_000_000, 1_000_000, 3, 16, 10 ** 9, K.KNN_PATH_LOWD_BF16),
+    (10_000, 1_000_000, 784, 10, 2 * 10 ** 9, K.KNN_PATH_MFMA_SPLIT),
+    (100_000, 10_000_000, 128, 100, 8 * 10 ** 9, K.KNN_PATH_MFMA_PACKED),
+    (50_000, 2_000_000, 256, 32, 128 * 10 ** 6, K.KNN_PATH_MFMA_SPLIT),
+    (50_000, 2_000_000, 256, 32, 10 ** 9, K.KNN_PATH_MFMA_SPLIT),
+    (50_000, 2_000_000, 256, 32, 8 * 10 ** 9, K.KNN_PATH_MFMA_PACKED),
+    (50_000, 2_000_000, 256, 32, 64 * 10 ** 9, K.KNN_PATH_MFMA_PACKED),
 ]
 
 
-@pytest.mark.parametrize("m,n,d,k,limit", CONFIGS)
-def test_every_baseline_config_has_a_plan_under_its_limit(m, n, d, k, limit):
+@pytest.mark.parametrize("m,n,d,k,limit,want", CONFIGS)
+def test_every_baseline_config_has_a_plan_under_its_limit(m, n, d, k, limit, want):
     p = K.knn_plan(m, n, d, k, limit)
     assert p.workspace_bytes <= limit
     assert p.workspace_bytes == p.norms_bytes + p.query_bytes + p.lists_bytes
-    # d <= 3 with room for the packed points takes the matrix-core filter path
-    want = K.KNN_PATH_LOWD_BF16 if d <= 8 else K.KNN_PATH_MFMA_SPLIT
     assert p.path == want
     assert p.q_chunks * p.chunk_rows >= m
     assert p.chunk_rows == m or p.chunk_rows % p.tile_q == 0
@@ -169,38 +170,60 @@ def test_threshold_seed_grid_is_sized_from_n_and_k_and_paid_for_under_the_limit(
     assert full.seed_cells == 32 and full.workspace_bytes <= packed + tile_lists + seed_bytes(n, 32 ** 3)
 
 
-def test_split_path_accounts_for_the_per_query_data_and_uses_every_byte_it_can():
-    # path 5 (d > 8, squared-Euclidean): per query 32 bytes per 16 coordinates of bf16 B
+def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can():
+    # paths 5 and 6 (d > 8, squared-Euclidean): per query 32 bytes per 16 coordinates of bf16 B
     # operands, a squared norm and a shared-threshold word, each array 256-aligned; the chunk is
-    # the longest multiple of the query tile that fits with them
+    # the longest multiple of the query tile that fits with them.  Path 6 (16 < d <= 256, at least
+    # 65536 points and four times its warm-up length) adds the points rounded to bf16, 32 bytes
+    # per point and 16 coordinates (the chunk count padded to an even one above 8), and pads the
+    # norms to a multiple of 64 points; its query tile is 32 x the query sets of a workgroup.
     import random
     rnd = random.Random(20240611)
 
     def up(v):
         return (v + 255) // 256 * 256
 
-    for _ in range(300):
-        d = rnd.choice([9, 16, 17, 100, 128, 129, 256, 784, 2000])
+    seen = set()
+    for _ in range(400):
+        d = rnd.choice([9, 16, 17, 100, 128, 129, 144, 256, 784, 2000])
         k = rnd.choice([1, 7, 32, 100, 1024])
         n = rnd.randrange(k, 3_000_000)
         m = rnd.choice([1, 255, 256, 257, 5000, 123_457])
         lo = K.knn_plan(m, n, d, k, 1 << 44).min_limit_bytes
         limit = lo + rnd.choice([0, 1, 255, 256, 4096, 10 ** 6, 10 ** 8, 10 ** 10])
         p = K.knn_plan(m, n, d, k, limit)
-        assert p.path == K.KNN_PATH_MFMA_SPLIT and p.tile_q == 256
         nch = (d + 15) // 16
-        assert p.norms_bytes == up(4 * n) + 256
-        assert p.query_bytes == up(p.chunk_rows * nch * 32) + 2 * up(p.chunk_rows * 4)
+        seen.add(p.path)
+        if p.path == K.KNN_PATH_MFMA_PACKED:
+            warm = (max(4096, 128 * k) + 127) // 128 * 128
+            assert 16 < d <= 256 and n >= 65536 and n >= 4 * warm
+            nch_p = nch if nch <= 8 else (nch + 1) // 2 * 2
+            n64 = (n + 63) // 64 * 64
+            assert p.norms_bytes == up(4 * n64) + 256 + up(n64 * nch_p * 32)
+            assert p.tile_q % 32 == 0 and 64 <= p.tile_q <= 512 and p.tile_x == 64
+            # the workgroup's LDS: B operands, candidate buffers and state, merge scratch, control
+            sets = p.tile_q // 32
+            assert sets * nch_p * 1024 + sets * 32 * (32 * 4 + 28) + 8 * (128 + 2 * k) * 4 + 8 * 256 + 256 \
+                <= 160 * 1024
+        else:
+            assert p.path == K.KNN_PATH_MFMA_SPLIT and p.tile_q == 256
+            assert p.norms_bytes == up(4 * n) + 256
+        tile = p.tile_q
+        # path 6 also keeps one word per query and point range (the ranges bound each other)
+        per_range = up(p.chunk_rows * p.n_splits * 4) if p.path == K.KNN_PATH_MFMA_PACKED else 0
+        assert p.query_bytes == up(p.chunk_rows * nch * 32) + 2 * up(p.chunk_rows * 4) + per_range
         assert p.lists_bytes == 2 * up(p.chunk_rows * p.n_splits * k * 4)
         assert p.workspace_bytes == p.norms_bytes + p.query_bytes + p.lists_bytes <= limit
-        assert p.chunk_rows == m or p.chunk_rows % 256 == 0
+        assert p.chunk_rows == m or p.chunk_rows % tile == 0
         assert p.q_chunks == -(-m // p.chunk_rows)
         if p.chunk_rows < m and p.chunk_rows < (1 << 22):  # a longer chunk would not have fitted
-            r = p.chunk_rows + 256
-            more = up(r * nch * 32) + 2 * up(r * 4) + 2 * up(r * p.n_splits * k * 4)
+            r = p.chunk_rows + tile
+            more = up(r * nch * 32) + 2 * up(r * 4) + 2 * up(r * p.n_splits * k * 4) + \
+                (up(r * p.n_splits * 4) if p.path == K.KNN_PATH_MFMA_PACKED else 0)
             assert p.norms_bytes + more > limit
         with pytest.raises(K.KnnError):
             K.knn_plan(m, n, d, k, lo - 1)
+    assert seen == {K.KNN_PATH_MFMA_SPLIT, K.KNN_PATH_MFMA_PACKED}
 
 
 def test_l1_path_accounts_for_the_transposed_queries():
