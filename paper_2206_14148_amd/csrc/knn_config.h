@@ -54,24 +54,31 @@ constexpr int kSpRoom = 4;           // a buffer with fewer free slots than this
 // rounded to bf16 in matrix-core operand order: the same filter with the roles swapped.  A
 // workgroup keeps the B operands of up to 16 sets of 32 queries in LDS for its whole life; each of
 // its 8 waves streams its own steps of 64 points from the packed copy straight into registers.
-constexpr int kPkWaves = 8;
 constexpr int kPkStep = 64;              // points per wave step (two MFMA row blocks)
-constexpr int kPkMaxChunks = 16;         // d <= 256
+constexpr int kPkMaxD = 256;
 constexpr int kPkMaxSets = 16;           // 512 queries: one thread per query in the stops
 constexpr int kPkCand = 32;              // buffered point indices per query (LDS)
 constexpr int kPkShareMin = 12;          // a stop empties every buffer with at least this many entries
 constexpr int kPkRoom = 8;               // a buffer with fewer free slots than this calls a stop
 constexpr int kPkLdsBytes = 160 * 1024;  // LDS of a gfx950 compute unit
-constexpr int kPkWarmPerK = 128;         // the first max(4096, this * k) points go through knn_split_kernel
+constexpr int kPkWarmPerK = 64;          // the first max(4096, this * k) points go through knn_split_kernel
 constexpr int kPkWarmMin = 4096;
 constexpr int64_t kPkMinPoints = 65536;  // fewer points: not worth packing
-// the chunk counts the kernel is instantiated for; others are padded up with zero operands
-constexpr inline int pk_padded_chunks(int nch) { return nch <= 8 ? nch : (nch + 1) / 2 * 2; }
+// the chunk counts the kernel is instantiated for (2 .. 8 and the even ones up to 16); others are
+// padded up with zero operands
+constexpr inline int pk_padded_chunks(int d) {
+    const int nch = (d + kSpKC - 1) / kSpKC;
+    return nch <= 8 ? nch : (nch + 1) / 2 * 2;
+}
+// Waves per workgroup.  Up to 8 chunks (d <= 128) a wave's state fits 256 registers and two waves
+// share a SIMD; above that the A operands alone take up to 128, so a workgroup has four waves of
+// up to 512 registers, one per SIMD.
+constexpr inline int pk_waves(int nch_padded) { return nch_padded <= 8 ? 8 : 4; }
 // LDS bytes of a workgroup with `sets` query sets: B operands, candidate buffers, seven words of
 // state per query, the merge scratch of each wave, a few control words
 constexpr inline int64_t pk_lds_bytes(int nch_padded, int k, int sets) {
     return (int64_t)sets * nch_padded * 1024 + (int64_t)sets * 32 * (kPkCand * 4 + 28) +
-           (int64_t)kPkWaves * (2 * kWave + 2 * k) * 4 + (int64_t)kPkWaves * 256 + 256;
+           (int64_t)pk_waves(nch_padded) * (2 * kWave + 2 * k) * 4 + (int64_t)pk_waves(nch_padded) * 256 + 256;
 }
 // most query sets a workgroup can hold (0: the shape does not fit)
 constexpr inline int pk_max_sets(int nch_padded, int k) {

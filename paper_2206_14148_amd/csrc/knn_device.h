@@ -132,10 +132,28 @@ struct MergeScratch {
 // key's bits in the low word, the index in the high word (both stay in registers that way).
 // ncand: the candidates sit in lanes 0 .. ncand-1 (wave-uniform; 16 or fewer take a shorter
 // network).  All 64 lanes must call it together.
-__device__ __forceinline__ uint64_t wave_merge_pair_inline(float* __restrict__ gk,
-                                                           int* __restrict__ gi, int k, float ckey,
-                                                           int cidx, const MergeScratch& sc, int lane,
-                                                           int ncand) {
+// The first 128 entries of a list as a wave holds them when it has asked for them ahead of a
+// merge: entry `lane` and entry 64 + `lane` (values past k are not used).
+struct ListHead {
+    float k0, k1;
+    int i0, i1;
+};
+__device__ __forceinline__ ListHead load_list_head(const float* __restrict__ gk,
+                                                   const int* __restrict__ gi, int k, int lane) {
+    ListHead h;
+    const int p0 = lane < k ? lane : 0, p1 = lane + kWave < k ? lane + kWave : 0;
+    h.k0 = gk[p0];
+    h.i0 = gi[p0];
+    h.k1 = gk[p1];
+    h.i1 = gi[p1];
+    return h;
+}
+
+template <bool HAVE_HEAD>
+__device__ __forceinline__ uint64_t wave_merge_pair_impl(float* __restrict__ gk,
+                                                         int* __restrict__ gi, int k, float ckey,
+                                                         int cidx, const MergeScratch& sc, int lane,
+                                                         int ncand, const ListHead& head) {
     // A list is read and written only by the wave that owns its query, so wave-level
     // ordering is enough; wave_sync() also orders this wave's earlier global stores to the
     // list before the loads below (same compute unit, same vector L1).
@@ -145,7 +163,17 @@ __device__ __forceinline__ uint64_t wave_merge_pair_inline(float* __restrict__ g
     else wave_sort64(ckey, cidx, lane);
     sc.cand_key[lane] = ckey;
     sc.cand_idx[lane] = cidx;
-    for (int p = lane; p < k; p += kWave) {
+    if (HAVE_HEAD) {
+        if (lane < k) {
+            sc.list_key[lane] = head.k0;
+            sc.list_idx[lane] = head.i0;
+        }
+        if (lane + kWave < k) {
+            sc.list_key[lane + kWave] = head.k1;
+            sc.list_idx[lane + kWave] = head.i1;
+        }
+    }
+    for (int p = lane + (HAVE_HEAD ? 2 * kWave : 0); p < k; p += kWave) {
         sc.list_key[p] = gk[p];
         sc.list_idx[p] = gi[p];
     }
@@ -199,6 +227,13 @@ __device__ __forceinline__ uint64_t wave_merge_pair_inline(float* __restrict__ g
     tidx = __shfl(tidx, src);
     wave_sync();
     return ((uint64_t)(unsigned)tidx << 32) | __float_as_uint(tau);
+}
+__device__ __forceinline__ uint64_t wave_merge_pair_inline(float* __restrict__ gk,
+                                                           int* __restrict__ gi, int k, float ckey,
+                                                           int cidx, const MergeScratch& sc, int lane,
+                                                           int ncand) {
+    const ListHead none = {0.f, 0.f, 0, 0};
+    return wave_merge_pair_impl<false>(gk, gi, k, ckey, cidx, sc, lane, ncand, none);
 }
 // Out of line: in most kernels the merge is rare and its registers should not count in the
 // search loop.  (A kernel whose loop already fills the register file calls the inline form: a

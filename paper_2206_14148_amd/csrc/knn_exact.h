@@ -84,7 +84,7 @@ __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, con
 // minimum on order-preserving words).  rn != null selects the cosine metric: the key of point j
 // is -2 (q . x_j) rn[j] with the dot product summed in the same order.  Returns the list's new
 // k-th key as float bits.
-template <bool ALIGNED, int U>
+template <bool ALIGNED, int U, bool HEAD_AHEAD = false>
 __device__ __forceinline__ unsigned flush_query_exact(const float* __restrict__ qp,
                                                    const float* __restrict__ X, int64_t ldx, int d,
                                                    int jsafe, const int* __restrict__ cbuf, int jbase,
@@ -98,6 +98,11 @@ __device__ __forceinline__ unsigned flush_query_exact(const float* __restrict__ 
     sc.list_key = scratch + 2 * kWave;
     sc.list_idx = reinterpret_cast<int*>(scratch + 2 * kWave + k);
     wave_sync();
+    // HEAD_AHEAD: the list is asked for first and used last, so that its round trip runs beside
+    // the rows' (four more registers all through the evaluation: not for callers that are short
+    // of them)
+    ListHead head = {0.f, 0.f, 0, 0};
+    if (HEAD_AHEAD) head = load_list_head(gk, gi, k, lane);
     const int cand = lane >> 1, part = lane & 1;
     const int j = cand < cc ? (cbuf ? cbuf[cand] : jbase + cand) : -1;
     const int jl = j < 0 ? jsafe : j;
@@ -118,7 +123,7 @@ __device__ __forceinline__ unsigned flush_query_exact(const float* __restrict__ 
         key = kInf;
         id = kNoIdx;
     }
-    const uint64_t mr = wave_merge_pair_inline(gk, gi, k, key, id, sc, lane, cc);
+    const uint64_t mr = wave_merge_pair_impl<HEAD_AHEAD>(gk, gi, k, key, id, sc, lane, cc, head);
     const unsigned t_bits = (unsigned)mr;
     // no value returned: nothing waits for the round trip
     if (lane == 0) atomicMin(tshr, key_word(__uint_as_float(t_bits)));

@@ -63,8 +63,7 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
 
 // 16 < d <= 256 with the points rounded to bf16 in the workspace (knn_packed.hip).
 //   launch_pack_operands  xp = `points` points from j_first on (j_first and points multiples of
-//                         64; rows past n are zero), ceil(d / 16) padded to an instantiated
-//                         chunk count x 32 bytes per point
+//                         64; rows past n are zero), pk_padded_chunks(d) x 32 bytes per point
 //   launch_pad_norms      xn[n .. next multiple of 64) = +inf
 //   launch_packed         the search of points [j_first, j_end) (j_first a multiple of 64) out of
 //                         the copy xp whose first point is slab_first, for queries whose B

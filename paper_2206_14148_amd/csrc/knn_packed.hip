@@ -97,6 +97,8 @@ __global__ void knn_pad_norms_kernel(float* __restrict__ xn, int n, int n_pad) {
     if (i < n_pad) xn[i] = kInf;
 }
 
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
 struct PkArgs {
     const float* Q;
     int64_t ldq;
@@ -134,8 +136,10 @@ struct PkArgs {
 enum { kCtlStop = 16, kCtlCount = 17, kCtlDone = 18, kCtlNext = 19 };
 
 template <int NCH, bool ALIGNED>
-__global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkArgs a) {
+__global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) void knn_packed_kernel(const PkArgs a) {
     constexpr int C = kPkCand;
+    constexpr int kPkWaves = pk_waves(NCH);  // 8 waves of <= 256 registers, or 4 of <= 512
+    constexpr int NT = 64 * kPkWaves;
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -143,10 +147,12 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
     const int i32 = lane & 31;
     const int h = lane >> 5;
     const int sets = a.sets, Qw = sets * 32, k = a.k, S = a.S;
-    // consecutive workgroups take consecutive query tiles of one range: the workgroups that are
-    // resident together (on every XCD) walk the same points at about the same time
-    const int s = blockIdx.x / a.tiles;
-    const int wg_row0 = (blockIdx.x - s * a.tiles) * Qw;
+    // Consecutive workgroups take the S ranges of one query tile, so the 256 that are resident
+    // together are few tiles times all ranges and start their ranges at about the same time;
+    // workgroup ids go round-robin to the 8 XCDs, so with S a multiple or a divisor of 8 the
+    // workgroups of one XCD walk the same one or few streams and find them in its L2.
+    const int s = blockIdx.x % S;
+    const int wg_row0 = (blockIdx.x / S) * Qw;
 
     uint4* const Bq = reinterpret_cast<uint4*>(smem);                // [sets][NCH][64]
     int* const cand = reinterpret_cast<int*>(Bq + (size_t)sets * NCH * 64);  // [Qw][C]
@@ -162,7 +168,7 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
     int* const ctl = reinterpret_cast<int*>(xn_stage + kPkWaves * 64);
     // ctl[2 w + p]: the step wave w walks in its iterations of parity p; then the three words above
 
-    for (int i = tid; i < sets * NCH * 64; i += 64 * kPkWaves) {
+    for (int i = tid; i < sets * NCH * 64; i += NT) {
         const int qs = i / (NCH * 64);
         const int rem = i - qs * (NCH * 64);
         const int c = rem >> 6, ln = rem & 63;
@@ -215,12 +221,12 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
         return all_finite ? fminf(c, lowest) : lowest;
     };
     const bool init_mine = s >= a.init_from;
-    if (tid < Qw) {
-        const int r = wg_row0 + tid;
+    for (int qq = tid; qq < Qw; qq += NT) {
+        const int r = wg_row0 + qq;
         const bool active = r < a.rows;
         const int rc = active ? r : a.rows - 1;
         const float qn = a.qnorm[rc];
-        qn_l[tid] = qn;
+        qn_l[qq] = qn;
         // |bf16(-2 q) - (-2 q)|^2 of this query
         float rq2 = 0.f;
         {
@@ -236,7 +242,7 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
         }
         const float cross = 1.01f * ((sqrtf(xmax) + rxm) * sqrtf(rq2) + rxm * 2.f * sqrtf(qn)) +
                             e_acc * sqrtf(xmax * qn);
-        cross_l[tid] = cross;
+        cross_l[qq] = cross;
         float own = -kInf;  // a row past the chunk: nothing passes
         if (active) {
             const size_t lb = ((size_t)r * S + s) * k;
@@ -245,14 +251,14 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
                 __hip_atomic_store(a.tsr + (size_t)r * S + s, key_word(a.lk[lb + pos_s]), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
         }
-        own_l[tid] = own;
-        tauf_l[tid] = active ? key_bound(fminf(own, shared_cap(rc)), qn, cross) : -kInf;
-        alloc_l[tid] = 0;
-        ovf_l[tid] = 0;
+        own_l[qq] = own;
+        tauf_l[qq] = active ? key_bound(fminf(own, shared_cap(rc)), qn, cross) : -kInf;
+        alloc_l[qq] = 0;
+        ovf_l[qq] = 0;
     }
     if (tid < 64) ctl[tid] = tid == kCtlNext ? a.step_first + s * a.range_steps : 0;
     if (init_mine) {
-        for (int e = tid; e < Qw * k; e += 64 * kPkWaves) {
+        for (int e = tid; e < Qw * k; e += NT) {
             const int q = e / k;
             const int r = wg_row0 + q;
             if (r < a.rows) {
@@ -274,10 +280,10 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
         if (lane == 0) v = atomicAdd(ctl + kCtlNext, 1);
         return __builtin_amdgcn_readfirstlane(v);
     };
-    uint4 A[2][NCH];
+    u32x4 A[2][NCH];
     f32x16 XN[2];
     auto loadA = [&](int st) {
-        const uint4* p = a.Xp + (size_t)(st - a.step_slab0) * (2 * NCH * 64) + lane;
+        const u32x4* p = reinterpret_cast<const u32x4*>(a.Xp) + (size_t)(st - a.step_slab0) * (2 * NCH * 64) + lane;
 #pragma unroll
         for (int pb = 0; pb < 2; ++pb)
 #pragma unroll
@@ -312,9 +318,14 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
     auto append = [&](int q, float tq, const f32x16& a0, const f32x16& a1, int st, int parity) {
         bool call = false;
         const int jb = st * kPkStep + h * 4;
-        auto one = [&](float key, int j) {
+        auto one = [&](float key, int off) {
             if (__builtin_amdgcn_ballot_w64(key < tq) == 0) return;
             if (key < tq) {
+                // (the index is formed here, behind a barrier to code motion: the 32 sums would
+                // otherwise be kept in registers all through the search loop)
+                int j = jb;
+                asm volatile("" : "+v"(j));
+                j += off;
                 const int slot = atomicAdd(&alloc_l[q], 1);
                 if (slot < C) cand[q * C + slot] = j;
                 else atomicOr(&ovf_l[q], 1 << (wave * 2 + parity));
@@ -322,21 +333,21 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
             }
         };
 #pragma unroll
-        for (int e = 0; e < 16; ++e) one(a0[e], jb + (e >> 2) * 8 + (e & 3));
+        for (int e = 0; e < 16; ++e) one(a0[e], (e >> 2) * 8 + (e & 3));
 #pragma unroll
-        for (int e = 0; e < 16; ++e) one(a1[e], jb + 32 + (e >> 2) * 8 + (e & 3));
+        for (int e = 0; e < 16; ++e) one(a1[e], 32 + (e >> 2) * 8 + (e & 3));
         if (__builtin_amdgcn_ballot_w64(call) != 0 && lane == 0)
             __hip_atomic_store(ctl + kCtlStop, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     };
 
     // One query set against the wave's 64 points.  roll: this is the step's last use of the A
     // operands, and the next step's are requested into the registers as they fall free.
-    auto body = [&](int qs, bool roll, const uint4* xnext, int st, int parity) {
+    auto body = [&](int qs, bool roll, const u32x4* xbase, int st, int parity) {
         const int q = qs * 32 + i32;
         const float tq = tauf_l[q];
         const uint4* bq = Bq + (size_t)qs * (NCH * 64) + lane;
         f32x16 acc0, acc1;
-        // the B operands are read kPkAhead chunks ahead of their use
+        // the B operands are read AH chunks ahead of their use
         constexpr int AH = NCH < 4 ? NCH : 4;
         uint4 bw[AH];
 #pragma unroll
@@ -350,8 +361,15 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
             acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[1][c]), b,
                                                            c == 0 ? XN[1] : acc1, 0, 0, 0);
             if (roll) {
-                A[0][c] = xnext[c * 64];
-                A[1][c] = xnext[(NCH + c) * 64];
+                // (kept in this place: moved up by the scheduler, the next step's operands would
+                // be in flight all through the set.  The compiler still gives them registers of
+                // their own beside the current ones - it does not load into a register that an
+                // MFMA has only just read - which is why more than 8 chunks run with four waves
+                // of up to 512 registers.)
+                __builtin_amdgcn_sched_barrier(0);
+                A[0][c] = xbase[c * 64 + lane];
+                A[1][c] = xbase[(NCH + c) * 64 + lane];
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         float m0 = acc0[0], m1 = acc1[0];
@@ -369,12 +387,18 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
     // A stop: every wave of the workgroup is here, nobody appends.  The queries with enough
     // buffered pairs (everything: all that have any) and those with a step to make good are
     // dealt out over the waves; then every query's filter threshold is brought up to date.
-    float* const my_scratch = scratch + (size_t)wave * (2 * kWave + 2 * k);
     auto stop_work = [&](bool everything) {
+        // The lane index is taken afresh here, in a form the compiler cannot move: everything a
+        // stop derives from it (addresses, the sort network's lane tests) would otherwise be
+        // computed once before the search loop and occupy some seventy registers all through it.
+        int lane;
+        asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane));
+        const int tid = wave * 64 + lane;
+        float* const my_scratch = scratch + (size_t)wave * (2 * kWave + 2 * k);
         if (tid == 0) ctl[kCtlStop] = 0;
         const int share = everything ? 1 : kPkShareMin;
-        if (tid < Qw && (alloc_l[tid] >= share || ovf_l[tid] != 0))
-            queue_l[atomicAdd(ctl + kCtlCount, 1)] = tid;
+        for (int qq = tid; qq < Qw; qq += NT)
+            if (alloc_l[qq] >= share || ovf_l[qq] != 0) queue_l[atomicAdd(ctl + kCtlCount, 1)] = qq;
         __syncthreads();
         const int nq = ctl[kCtlCount];
         if (wave == 0) { PK_STAT(0, 1); PK_STAT(1, nq); }
@@ -412,7 +436,7 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
                 ++item;
                 if (n_c > 0) { PK_STAT(item == 1 ? 2 : 3, n_c); }
                 if (n_c > 0)
-                    t_bits = flush_query_exact<ALIGNED, 8>(a.Q + (int64_t)r * a.ldq, a.X, a.ldx, a.d,
+                    t_bits = flush_query_exact<ALIGNED, 8, true>(a.Q + (int64_t)r * a.ldq, a.X, a.ldx, a.d,
                                                            a.j_valid, cbuf, jb, n_c, a.lk + lb, a.li + lb,
                                                            k, my_scratch, a.tsh + r, nullptr, lane);
             }
@@ -428,8 +452,9 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
         PK_STAT(8, PK_CLOCK() - tf0);
         __syncthreads();
         if (tid == 0) ctl[kCtlCount] = 0;
-        if (tid < Qw && wg_row0 + tid < a.rows)
-            tauf_l[tid] = key_bound(fminf(own_l[tid], shared_cap(wg_row0 + tid)), qn_l[tid], cross_l[tid]);
+        for (int qq = tid; qq < Qw; qq += NT)
+            if (wg_row0 + qq < a.rows)
+                tauf_l[qq] = key_bound(fminf(own_l[qq], shared_cap(wg_row0 + qq)), qn_l[qq], cross_l[qq]);
         __syncthreads();
     };
 
@@ -451,22 +476,20 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
             const bool has_next = taken < step_hi;
             const int nstep = has_next ? taken : step;
             xn_next = a.xn[(size_t)nstep * kPkStep + lane];
-            const uint4* xnext = a.Xp + (size_t)(nstep - a.step_slab0) * (2 * NCH * 64) + lane;
+            const u32x4* xnext =
+                reinterpret_cast<const u32x4*>(a.Xp) + (size_t)(nstep - a.step_slab0) * (2 * NCH * 64);
             for (int qs = 0; qs + 1 < sets; ++qs) body(qs, false, xnext, step, parity);
             const int stop = __builtin_amdgcn_readfirstlane(
                 __hip_atomic_load(ctl + kCtlStop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-            if (stop == 0) {
-                body(sets - 1, true, xnext, step, parity);
-                step = nstep;
-                have = has_next;
-                parity ^= 1;
-                spread_xn(xn_next);
-                continue;
-            }
-            body(sets - 1, false, xnext, step, parity);
+            // (the last set always requests the next step's operands as it goes; a stop reloads them)
+            body(sets - 1, true, xnext, step, parity);
             step = nstep;
             have = has_next;
             parity ^= 1;
+            if (stop == 0) {
+                spread_xn(xn_next);
+                continue;
+            }
         } else if (!announced) {
             if (lane == 0) atomicAdd(ctl + kCtlDone, 1);
             announced = true;
@@ -498,7 +521,7 @@ extern "C" void knn_debug_set_stats(void* p) { g_pk_stats = static_cast<unsigned
 
 hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, int64_t j_first,
                                 int64_t points, void* xp, hipStream_t stream) {
-    const int nch = pk_padded_chunks((d + kSpKC - 1) / kSpKC);
+    const int nch = pk_padded_chunks(d);
     const int64_t pieces = points * nch * 2;
     const dim3 grid((unsigned)((pieces + 255) / 256));
     const bool aligned = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 4 == 0) && (d % 4 == 0);
@@ -537,8 +560,8 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
                          int sets, int64_t j_first, int64_t j_end, int init_from, float* lk, int* li,
                          hipStream_t stream) {
     const int nch_real = (d + kSpKC - 1) / kSpKC;
-    const int nch = pk_padded_chunks(nch_real);
-    if (nch > kPkMaxChunks || sets < 1 || sets > pk_max_sets(nch, k) || !packed_rows_aligned(Q, ldq, X, ldx, d) ||
+    const int nch = pk_padded_chunks(d);
+    if (d > kPkMaxD || sets < 1 || sets > pk_max_sets(nch, k) || !packed_rows_aligned(Q, ldq, X, ldx, d) ||
         j_first % kPkStep != 0 || slab_first % kPkStep != 0 || j_first < slab_first || j_end <= j_first ||
         j_end > n)
         return hipErrorInvalidValue;
@@ -570,7 +593,7 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
     // ranges of whole rounds of the eight waves
     const int steps = a.step_end - a.step_first;
     int per = (steps + S - 1) / S;
-    per = (per + kPkWaves - 1) / kPkWaves * kPkWaves;
+    per = (per + 7) / 8 * 8;
     a.range_steps = per;
     a.init_from = init_from;
     a.j_valid = (int)j_first;
@@ -583,7 +606,7 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
     do {                                                                                       \
         hipError_t e2 = raise_lds_limit(knn_packed_kernel<N, true>, lds);                      \
         if (e2 != hipSuccess) return e2;                                                       \
-        knn_packed_kernel<N, true><<<grid, dim3(64 * kPkWaves), lds, stream>>>(a);             \
+        knn_packed_kernel<N, true><<<grid, dim3(64 * pk_waves(N)), lds, stream>>>(a);          \
     } while (0)
     switch (nch) {
         case 2: KNN_PACKED_LAUNCH(2); break;

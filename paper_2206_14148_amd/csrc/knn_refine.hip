@@ -29,6 +29,36 @@ __device__ __forceinline__ double exact_sqdist(const float* __restrict__ q,
     return acc;
 }
 
+// The same sum in the same order (ascending t, one addition per coordinate, no contraction) for
+// rows that are 16-byte aligned with d a multiple of 4: the coordinates arrive four at a time.
+// A lane walks its own row, so every load instruction of the wave touches 64 different cache
+// lines; with 16 bytes per lane and instruction there are four times fewer of them.
+__device__ __forceinline__ double exact_sqdist_aligned(const float* __restrict__ q,
+                                                       const float* __restrict__ x, int d) {
+#pragma clang fp contract(off)
+    double acc = 0.0;
+    for (int t = 0; t < d; t += 8) {
+        const f32x4 x0 = *reinterpret_cast<const f32x4*>(x + t);
+        const f32x4 q0 = *reinterpret_cast<const f32x4*>(q + t);
+        const bool more = t + 4 < d;
+        const f32x4 x1 = *reinterpret_cast<const f32x4*>(x + (more ? t + 4 : t));
+        const f32x4 q1 = *reinterpret_cast<const f32x4*>(q + (more ? t + 4 : t));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const double diff = (double)q0[e] - (double)x0[e];
+            acc = acc + diff * diff;
+        }
+        if (more) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const double diff = (double)q1[e] - (double)x1[e];
+                acc = acc + diff * diff;
+            }
+        }
+    }
+    return acc;
+}
+
 // Cosine distance in fp64: 1 - <q,x> / (|q| |x|), clamped at 0; 1 if either vector is zero.
 __device__ __forceinline__ double exact_cosdist(const float* __restrict__ q,
                                                 const float* __restrict__ x, int d) {
@@ -56,7 +86,7 @@ __device__ __forceinline__ double exact_l1dist(const float* __restrict__ q,
 // metric: 0 squared Euclidean, 1 cosine, 2 L1 (the values of knn_metric)
 __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx, int rows,
-    int n, int d, int k, int S, int metric, const float* __restrict__ lk,
+    int n, int d, int k, int S, int metric, int aligned, const float* __restrict__ lk,
     const int* __restrict__ li, int32_t* __restrict__ idx_out, float* __restrict__ dist_out) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
@@ -102,7 +132,9 @@ __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
             const float* qp = Q + (int64_t)r * ldq;
             const float* xp = X + (int64_t)j * ldx;
             dist = metric == 1 ? exact_cosdist(qp, xp, d)
-                               : (metric == 2 ? exact_l1dist(qp, xp, d) : exact_sqdist(qp, xp, d));
+                               : (metric == 2 ? exact_l1dist(qp, xp, d)
+                                              : (aligned ? exact_sqdist_aligned(qp, xp, d)
+                                                         : exact_sqdist(qp, xp, d)));
         }
         wd[w] = dist;
     }
@@ -202,8 +234,10 @@ hipError_t launch_merge_refine(const float* Q, int64_t ldq, const float* X, int6
     hipError_t e = raise_lds_limit(knn_merge_refine_kernel, lds);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((rows + 3) / 4));
+    const int aligned = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
+                        (ldq % 4 == 0) && (ldx % 4 == 0) && (d % 4 == 0);
     knn_merge_refine_kernel<<<grid, dim3(256), lds, stream>>>(
-        Q, ldq, X, ldx, (int)rows, (int)n, d, k, S, metric, lk, li, idx, dist);
+        Q, ldq, X, ldx, (int)rows, (int)n, d, k, S, metric, aligned, lk, li, idx, dist);
     return hipGetLastError();
 }
 

@@ -9,6 +9,7 @@
 #include <cctype>
 #include <cmath>
 #include <cstring>
+#include <cstdlib>
 
 #include "../../include/knn.h"
 #include "knn_config.h"
@@ -199,9 +200,9 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     // the search runs with the queries resident in LDS (knn_packed.hip).  Its workspace is that
     // of path 5 plus the packed copy, so a call whose rows turn out not to be 16-byte aligned
     // still runs under this plan, on path 5's kernel.
-    if (split && metric == KNN_METRIC_L2SQ && d > kSpKC && d <= kPkMaxChunks * kSpKC &&
+    if (split && metric == KNN_METRIC_L2SQ && d > kSpKC && d <= kPkMaxD &&
         n >= kPkMinPoints && n >= 4 * pk_warm_points(k)) {
-        const int nch_p = pk_padded_chunks((d + kSpKC - 1) / kSpKC);
+        const int nch_p = pk_padded_chunks(d);
         const int sets_max = pk_max_sets(nch_p, k);
         const uint64_t n64 = ((uint64_t)n + kPkStep - 1) / kPkStep * kPkStep;
         const uint64_t per_point = align_up(n64 * 4) + kAlign + align_up(n64 * (uint64_t)nch_p * 32);
@@ -215,9 +216,13 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
             double best = 0.0;
             int best_sets = 0;
             int64_t best_S = 0, best_r = 0;
+            const char* fs_ = getenv("KNN_FORCE_S");      // DEV-ONLY
+            const char* fq_ = getenv("KNN_FORCE_SETS");   // DEV-ONLY
             for (int sets = sets_max; sets >= 2 && sets >= sets_max - 6; --sets) {
+                if (fq_ && sets != atoi(fq_)) continue;   // DEV-ONLY
                 const int64_t tile6 = 32 * sets;
                 for (int64_t S = 1; S <= 32; ++S) {
+                    if (fs_ && S != atoi(fs_)) continue;  // DEV-ONLY
                     if ((n - pk_warm_points(k)) / S < 8 * kPkStep * 16) break;  // ranges of >= 16 rounds of the waves
                     int64_t rows = rows_fitting(avail6, (uint64_t)S, (uint64_t)k, qrow, 3);
                     if (rows > kMaxChunkRows) rows = kMaxChunkRows;

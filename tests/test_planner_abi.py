@@ -195,15 +195,16 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
         nch = (d + 15) // 16
         seen.add(p.path)
         if p.path == K.KNN_PATH_MFMA_PACKED:
-            warm = (max(4096, 128 * k) + 127) // 128 * 128
+            warm = (max(4096, 64 * k) + 127) // 128 * 128
             assert 16 < d <= 256 and n >= 65536 and n >= 4 * warm
             nch_p = nch if nch <= 8 else (nch + 1) // 2 * 2
+            waves = 8 if nch_p <= 8 else 4  # above 8 chunks: four waves of up to 512 registers
             n64 = (n + 63) // 64 * 64
             assert p.norms_bytes == up(4 * n64) + 256 + up(n64 * nch_p * 32)
             assert p.tile_q % 32 == 0 and 64 <= p.tile_q <= 512 and p.tile_x == 64
             # the workgroup's LDS: B operands, candidate buffers and state, merge scratch, control
             sets = p.tile_q // 32
-            assert sets * nch_p * 1024 + sets * 32 * (32 * 4 + 28) + 8 * (128 + 2 * k) * 4 + 8 * 256 + 256 \
+            assert sets * nch_p * 1024 + sets * 32 * (32 * 4 + 28) + waves * (128 + 2 * k) * 4 + waves * 256 + 256 \
                 <= 160 * 1024
         else:
             assert p.path == K.KNN_PATH_MFMA_SPLIT and p.tile_q == 256
