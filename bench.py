@@ -3,11 +3,15 @@
 
 A "step" is one knn_search call (norms, tiled distances + running top-k, merge, exact
 re-evaluation) over one synthetic workload whose inputs are already resident in HBM.
-Default workload: the point-cloud kNN graph (m = n = 1e6, d = 3, k = 16, 1 GB limit).
+Default (--workload all): the five kNN configurations, one after the other.  The top-level
+record is the largest one, c4 (m = 1e5 queries, n = 1e7 points, d = 128, k = 100, 8 GB limit);
+c1, c2, c3 and c5 (with its sweep over four memory limits) follow as sub-records under
+"configs", each with its own time, kernel times, roofline, oracle timing and parity.
 
 Prints ONE JSON line: pairs/s for the whole job, the roofline of the dominant kernel
-(measured live with HIP events on the launch stream) and the CPU oracle timed on the host
-cores on a bounded sample of the same workload (reported baseline, also a parity check).
+(measured live with HIP events on the launch stream), the matrix-core peak measured on the
+same GPU, and the CPU oracle timed on the host cores on a bounded sample of the same workload
+(reported baseline, also a parity check).
 """
 from __future__ import annotations
 
@@ -27,21 +31,28 @@ PEAK_FP32_MATRIX_TFLOPS = 157.3
 PEAK_FP32_VECTOR_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per search-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/*_pmc.txt), scaled by the copy-kernel calibration stated there.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {
-    "c2_pointcloud_d3": 214.8e9,    # knn_lowd_bf16_kernel: fetched + written
-    "c3_imagelike_d784": 164.0e9,   # knn_split_kernel (streamed queries): fetched + written
-    "c4_clustered_d128": 1821.5e9,  # knn_split_kernel (resident queries): fetched + written
-    "c5_memsweep_d256": 346.2e9,    # knn_split_kernel (resident queries): fetched + written
-    "c6_cosine_d100": 16.03e9,      # knn_split_kernel (resident queries): fetched + written
-    "c7_l1_d100": 28.34e9,          # knn_l1_kernel: 27.92 GB fetched + 0.42 GB written
-    "kmv1_d1": 1.84e9,              # kmv_lowd_kernel: 1.83 GB fetched + 0.01 GB written
-    "kmv2_d32": 1.47e9,             # kmv_mfma_kernel: 1.46 GB fetched + 0.007 GB written
-    "kmv3_d1_f64": 4.02e9,          # kmv_lowd_f64_kernel: 4.01 GB fetched + 0.01 GB written
-    "sgpr1_road_d3_m10000": 8.97e9,      # sgpr_syrk_kernel, per launch: 8.57 GB fetched + 0.41 GB written
-    "sgpr2_electric_d11_m4000": 1.10e9,  # sgpr_syrk_kernel, per launch: 1.04 GB fetched + 0.07 GB written
+# HBM-side bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# scaled by the copy-kernel calibration stated in the profile.  They describe the default shape of
+# a workload on the kernel named; a run with other sizes, another limit or another kernel reports
+# null.  {workload: (kernel, bytes, profile)}
+PROFILED_TRAFFIC = {
+    "c2_pointcloud_d3": ("knn_lowd_bf16_kernel", 214.8e9, "profiles/knn_lowd_bf16_kernel_c2.md"),
+    "c3_imagelike_d784": ("knn_split_kernel", 164.0e9, "profiles/knn_split_kernel_c3.md"),
+    "c6_cosine_d100": ("knn_split_kernel", 16.03e9, "profiles/knn_split_kernel_c6.md"),
+    "c7_l1_d100": ("knn_l1_kernel", 28.34e9, "profiles/knn_l1_kernel_c7.md"),
+    "kmv1_d1": ("kmv_lowd_kernel", 1.84e9, "profiles/kmv_lowd_kernel_kmv1.md"),
+    "kmv2_d32": ("kmv_mfma_kernel", 1.47e9, "profiles/kmv_mfma_kernel_kmv2.md"),
+    "kmv3_d1_f64": ("kmv_lowd_f64_kernel", 4.02e9, "profiles/kmv_lowd_f64_kernel_kmv3.md"),
+    "sgpr1_road_d3_m10000": ("sgpr_syrk_kernel", 8.97e9, "profiles/sgpr_syrk_kernel_sgpr1.md"),
 }
+
+
+def profiled_traffic(name: str, kernel: str, default_shape: bool):
+    """(bytes, source) of the committed counter profile, only where it describes this run."""
+    rec = PROFILED_TRAFFIC.get(name)
+    if rec is None or not default_shape or rec[0] != kernel:
+        return None, None
+    return rec[1], rec[2]
 
 
 def log(*a):
@@ -130,13 +141,19 @@ def bench_kmv(args) -> int:
     else:
         # the contraction runs as six bf16 MFMAs per 16 coordinates (three-piece splits of the
         # fp32 values): 12 bf16 flops per pair and padded coordinate, priced at the bf16 peak
+        # headline: the method's own contraction, 2 d flops per pair, against the bf16 peak; the
+        # twelve bf16 flops per pair and padded coordinate that the three-piece emulation really
+        # issues are reported beside it as `issued_*`
         d_pad = (w.d + 15) // 16 * 16
-        fpp = 12 * d_pad
+        fpp = 2 * w.d
         roofline = {"bound": "mfma", "kernel": "kmv_mfma_kernel", "achieved": rate * fpp / 1e12,
                     "peak": PEAK_BF16_MATRIX_TFLOPS, "unit": "TFLOP/s",
                     "frac": rate * fpp / 1e12 / PEAK_BF16_MATRIX_TFLOPS, "traffic": None,
-                    "flops_per_pair": fpp, "contraction_tflops": rate * 2 * w.d / 1e12}
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(w.name)
+                    "flops_per_pair": fpp, "issued_flops_per_pair": 12 * d_pad,
+                    "issued_tflops": rate * 12 * d_pad / 1e12,
+                    "issued_frac": rate * 12 * d_pad / 1e12 / PEAK_BF16_MATRIX_TFLOPS}
+    roofline["traffic"], roofline["traffic_source"] = profiled_traffic(
+        w.name, roofline["kernel"], not (args.n or args.m or args.mem_limit))
     roofline["avg_launch_ms"] = call_ms
 
     cpu_baseline = None
@@ -269,8 +286,9 @@ def bench_sgpr(args) -> int:
     roofline = {"bound": "mfma", "kernel": "sgpr_syrk_kernel", "achieved": achieved,
                 "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_FP32_MATRIX_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
-                "flops_per_pair": w.m + 1, "avg_launch_ms": avg_launch_s * 1e3}
+                "traffic": None, "flops_per_pair": w.m + 1, "avg_launch_ms": avg_launch_s * 1e3}
+    roofline["traffic"], roofline["traffic_source"] = profiled_traffic(
+        w.name, "sgpr_syrk_kernel", not (args.n or args.m or args.mem_limit))
 
     cpu_baseline = None
     parity = None
@@ -318,51 +336,22 @@ def bench_sgpr(args) -> int:
     return 0
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c2", help="c1..c7 (default c2, the metric's workload; c6 cosine, c7 L1), or kmv1 / kmv2 / kmv3: "
-                         "the kernel matrix-vector product, or sgpr1 / sgpr2: the SGPR accumulations")
-    ap.add_argument("--mem-limit", default=None, help="e.g. 128MB, 1GB (decimal); default: the workload's")
-    ap.add_argument("--m", type=int, default=None, help="override the query count (testing)")
-    ap.add_argument("--n", type=int, default=None, help="override the point count (testing)")
-    ap.add_argument("--k", type=int, default=None, help="override the neighbour count (testing)")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle time budget; 0 skips it")
-    ap.add_argument("--host-x", action="store_true",
-                    help="also time knn_search_host_x: the same search with X in pinned host memory, "
-                         "streamed through staging buffers inside the limit (PCIe-inclusive; reported "
-                         "beside the resident figure, never as `value`)")
-    ap.add_argument("--calibrate-copy-mb", type=int, default=0,
-                    help="also run one plain elementwise copy of this many MB (read + write) before "
-                         "the timed region, as the known-size reference for rocprofv3 --pmc byte counters")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build is single-GPU; run with --gpus 1 "
-              "(more GPUs would each take a share of the query rows; that is not built)", file=sys.stderr)
-        return 2
+PATH_NAMES = {0: "lowd", 2: "lowd_mfma", 3: "l1", 4: "lowd_bf16", 5: "mfma_split", 6: "mfma_packed"}
+# arithmetic the path computes in: what the matrix cores filter in, what the list keys are, what the
+# returned distances are evaluated in
+PATH_DTYPES = {0: "f32 keys / f64 refine", 3: "f32 keys / f64 refine",
+               2: "f32 filter / f32 keys / f64 refine", 4: "bf16 filter / f32 keys / f64 refine",
+               5: "bf16 filter / f32 keys / f64 refine", 6: "bf16 filter / f32 keys / f64 refine"}
 
-    if args.workload.startswith("kmv"):
-        return bench_kmv(args)
-    if args.workload.startswith("sgpr"):
-        return bench_sgpr(args)
 
+def knn_record(w, limit, steps, warmup, cpu_seconds, peaks, default_shape, host_x=False,
+               calibrate_copy_mb=0, sweep=True):
+    """Times one kNN workload; returns the record (the top-level fields of a bench line)."""
     import numpy as np
     import torch
 
     import paper_2206_14148_amd as K
     import workloads as W
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
-        return 2
-    K.load()
-    cfg = int(args.workload.lstrip("c"))
-    w = W.scaled(cfg, m=args.m, n=args.n) if (args.m or args.n) else W.WORKLOADS[cfg]
-    if args.k:
-        w = W.scaled(cfg, m=w.m, n=w.n, k=args.k)
-    limit = K.knn_parse_size(args.mem_limit) if args.mem_limit else w.mem_limit
 
     t0 = time.time()
     Q, X = W.make(w)
@@ -375,80 +364,83 @@ def main() -> int:
     ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device=dev)
     idx = torch.empty((w.m, w.k), dtype=torch.int32, device=dev)
     dist = torch.empty((w.m, w.k), dtype=torch.float32, device=dev)
-    path_name = {0: "lowd", 2: "lowd_mfma", 3: "l1", 4: "lowd_bf16", 5: "mfma_split", 6: "mfma_packed"}[plan.path]
-    log(f"[bench] plan: path={path_name} chunks={plan.q_chunks} "
-        f"ranges={plan.n_splits} workspace={plan.workspace_bytes} B (limit {limit} B)")
+    path_name = PATH_NAMES[plan.path]
+    log(f"[bench] plan: path={path_name} chunks={plan.q_chunks} ranges={plan.n_splits} "
+        f"tile={plan.tile_q} workspace={plan.workspace_bytes} B (limit {limit} B)")
 
     def step():
         K.knn_search(Qd, Xd, w.k, limit, workspace=ws, out=(idx, dist), metric=w.metric)
 
-    if args.calibrate_copy_mb > 0:
-        src = torch.ones(args.calibrate_copy_mb * 250_000, dtype=torch.float32, device=dev)
+    if calibrate_copy_mb > 0:
+        src = torch.ones(calibrate_copy_mb * 250_000, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
         torch.mul(src, 1.0, out=dst)  # one elementwise kernel: reads and writes calibrate_copy_mb MB
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     K.knn_profile_enable(True)
     K.knn_profile_read()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    norms_ms, search_ms, refine_ms, launches = K.knn_profile_read()
+    prep_ms, search_ms, refine_ms, launches = K.knn_profile_read()
     K.knn_profile_enable(False)
-    ms_per_step = elapsed * 1e3 / args.steps
+    ms_per_step = elapsed * 1e3 / steps
     pairs = float(w.m) * float(w.n)
-    value = pairs * args.steps / elapsed
-    log(f"[bench] {ms_per_step:.2f} ms/step, {value:.3e} pairs/s; kernels per step: "
-        f"norms {norms_ms/args.steps:.3f} ms, search {search_ms/args.steps:.3f} ms "
-        f"({launches // max(args.steps,1)} launch), merge+refine {refine_ms/args.steps:.3f} ms")
+    value = pairs * steps / elapsed
+    log(f"[bench] {w.name}: {ms_per_step:.2f} ms/step, {value:.3e} pairs/s; kernels per step: "
+        f"preparation {prep_ms/steps:.3f} ms, search {search_ms/steps:.3f} ms "
+        f"({launches // max(steps,1)} launch), merge+refine {refine_ms/steps:.3f} ms")
 
-    # roofline of the dominant kernel (the search kernel), per launch
+    # roofline of the dominant kernel, per launch
     avg_launch_s = (search_ms / max(launches, 1)) * 1e-3
-    pairs_per_launch = pairs * args.steps / max(launches, 1)
-    traffic = MEASURED_TRAFFIC_BYTES.get(w.name)
+    launches_per_step = max(launches, 1) / steps
+    # pairs one launch of the dominant kernel covers (path 6: the warm-up points are another kernel's)
+    n_main = w.n - plan.warm_points if plan.path == K.KNN_PATH_MFMA_PACKED else w.n
+    pairs_per_launch = float(w.m) * float(n_main) / launches_per_step
     hbm_equiv = (pairs_per_launch / avg_launch_s) * 8.0 / (PEAK_HBM_GBS * 1e9)
     if plan.path in (K.KNN_PATH_MFMA_SPLIT, K.KNN_PATH_MFMA_PACKED):
         # The -2 Q X^T contraction of the filter runs on bf16 roundings of the values: 2 d bf16
         # flops per pair on the matrix cores, with d rounded up to the 16 coordinates of an MFMA,
         # against the dense bf16 peak.
+        kernel = "knn_split_kernel" if plan.path == K.KNN_PATH_MFMA_SPLIT else "knn_packed_kernel"
         d_pad = (w.d + 15) // 16 * 16
-        flops = 2.0 * d_pad * pairs_per_launch
-        achieved = flops / avg_launch_s / 1e12
-        roofline = {"bound": "mfma", "kernel": "knn_split_kernel" if plan.path == K.KNN_PATH_MFMA_SPLIT else "knn_packed_kernel", "achieved": achieved,
+        achieved = 2.0 * d_pad * pairs_per_launch / avg_launch_s / 1e12
+        roofline = {"bound": "mfma", "kernel": kernel, "achieved": achieved,
                     "peak": PEAK_BF16_MATRIX_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / PEAK_BF16_MATRIX_TFLOPS, "traffic": traffic,
-                    "flops_per_pair": 2 * d_pad}
+                    "frac": achieved / PEAK_BF16_MATRIX_TFLOPS, "flops_per_pair": 2 * d_pad}
+        if peaks.get("bf16"):
+            roofline["measured_peak"] = peaks["bf16"]
+            roofline["frac_of_measured_peak"] = achieved / peaks["bf16"]
     elif plan.path == K.KNN_PATH_LOWD_MFMA:
         # filter contraction over K = 4: [x0 x1 x2 |x|^2] . [-2q0 -2q1 -2q2 1]
-        flops = 2.0 * 4 * pairs_per_launch
-        achieved = flops / avg_launch_s / 1e12
+        achieved = 8.0 * pairs_per_launch / avg_launch_s / 1e12
         roofline = {"bound": "mfma", "kernel": "knn_lowd_mfma_kernel", "achieved": achieved,
                     "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / PEAK_FP32_MATRIX_TFLOPS, "traffic": traffic,
-                    "flops_per_pair": 8,
+                    "frac": achieved / PEAK_FP32_MATRIX_TFLOPS, "flops_per_pair": 8,
                     # what a design that stores the distance tile would move: 4 B out + 4 B in
                     "hbm_equiv_frac": hbm_equiv}
+        if peaks.get("f32"):
+            roofline["measured_peak"] = peaks["f32"]
+            roofline["frac_of_measured_peak"] = achieved / peaks["f32"]
     elif plan.path == K.KNN_PATH_LOWD_BF16:
-        # Bound: instruction issue of the vector ALU and the matrix core, which share a port on
-        # this chip (their busy cycles add).  Per 32 x 32 keys a wave issues one
+        # Bound: instruction issue of one wave.  Per 32 x 32 keys a wave issues one
         # v_mfma_f32_32x32x16_bf16 (8 passes = the slot of 8 vector instructions) and 9 vector
         # instructions (8 three-input minima, 1 compare): 17 slots x 64 lanes / 1024 pairs =
-        # 1.0625 lane-operations per pair against 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz.
+        # 1.0625 lane-operations per pair against 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz.  The
+        # unit is issue slots of one lane, not flops.
         lane_ops = 17.0 * 64.0 / 1024.0
         peak = 256 * 4 * 16 * 2.4e9 / 1e12
         achieved = lane_ops * pairs_per_launch / avg_launch_s / 1e12
         roofline = {"bound": "alu", "kernel": "knn_lowd_bf16_kernel", "achieved": achieved,
-                    # one lane-operation = one issue slot of one lane = one non-fused, non-packed
-                    # fp32 operation, so the figures read as TFLOP/s of such operations
-                    "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
-                    "unit_note": "issue slots of the shared VALU/MFMA port, 1 lane-op = 1 flop",
+                    "peak": peak, "unit": "Tlane-op/s", "frac": achieved / peak,
+                    "unit_note": "issue slots of the vector ALU / matrix core port per lane and second",
                     "lane_ops_per_pair": lane_ops,
                     # the filter contraction alone: 2 x 16 bf16 flops per pair against 2.5 PFLOP/s
                     "mfma_bf16_frac": 32.0 * pairs_per_launch / avg_launch_s / 2.5e15,
@@ -456,25 +448,25 @@ def main() -> int:
                     "hbm_equiv_frac": hbm_equiv}
     elif plan.path == K.KNN_PATH_L1:
         # d subtractions and d-1 additions per pair (the absolute value is an operand modifier)
-        flops = (2.0 * w.d - 1.0) * pairs_per_launch
-        achieved = flops / avg_launch_s / 1e12
+        achieved = (2.0 * w.d - 1.0) * pairs_per_launch / avg_launch_s / 1e12
         roofline = {"bound": "alu", "kernel": "knn_l1_kernel", "achieved": achieved,
                     "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / PEAK_FP32_VECTOR_TFLOPS, "traffic": traffic,
-                    "flops_per_pair": 2 * w.d - 1}
+                    "frac": achieved / PEAK_FP32_VECTOR_TFLOPS, "flops_per_pair": 2 * w.d - 1}
     else:
         # difference form: d subtractions, d multiplications, d-1 additions per pair
-        flops = (3.0 * w.d - 1.0) * pairs_per_launch
-        achieved = flops / avg_launch_s / 1e12
+        achieved = (3.0 * w.d - 1.0) * pairs_per_launch / avg_launch_s / 1e12
         roofline = {"bound": "alu", "kernel": "knn_lowd_kernel", "achieved": achieved,
                     "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / PEAK_FP32_VECTOR_TFLOPS, "traffic": traffic,
+                    "frac": achieved / PEAK_FP32_VECTOR_TFLOPS,
                     "flops_per_pair": 3 * w.d - 1, "hbm_equiv_frac": hbm_equiv}
+    roofline["traffic"], roofline["traffic_source"] = profiled_traffic(w.name, roofline["kernel"],
+                                                                       default_shape)
     roofline["avg_launch_ms"] = avg_launch_s * 1e3
+    roofline["algorithmic_bytes"] = 4.0 * (w.m + w.n) * w.d + 8.0 * w.m * w.k
 
     cpu_baseline = None
     parity = None
-    if args.cpu_seconds > 0:
+    if cpu_seconds > 0:
         import oracle
         from parity import check
 
@@ -483,7 +475,7 @@ def main() -> int:
         t0 = time.perf_counter()
         oracle.knn(Q, X, w.k, rows=probe_rows, metric=w.metric)
         probe_rate = len(probe_rows) / max(time.perf_counter() - t0, 1e-6)
-        nrows = int(max(len(probe_rows), min(w.m, probe_rate * args.cpu_seconds)))
+        nrows = int(max(len(probe_rows), min(w.m, probe_rate * cpu_seconds)))
         rows = W.sample_rows(w, nrows)
         t0 = time.perf_counter()
         o_idx, o_dist, o_next = oracle.knn(Q, X, w.k, rows=rows, metric=w.metric)
@@ -495,11 +487,15 @@ def main() -> int:
         parity = check(idx[rows_t].cpu().numpy(), dist[rows_t].cpu().numpy(), o_idx, o_dist, o_next, w.n)
         log(f"[bench] oracle: {cpu_baseline['value']:.3e} pairs/s on {threads} threads; parity {parity}")
 
-    # the memory-limit sweep of the sweep workload (config 5): same inputs, each of its limits
-    sweep = None
-    if w.sweep and not args.mem_limit:
-        sweep = []
-        for lim in w.sweep:
+    # the memory-limit sweep of the sweep workload (config 5): same inputs, each of its limits, and
+    # one limit small enough to cut the queries into several chunks
+    sweep_out = None
+    if w.sweep and sweep:
+        sweep_out = []
+        # (room for the per-point data and about a third of the lists of the smallest sweep limit)
+        p_lo = K.knn_plan(w.m, w.n, w.d, w.k, min(w.sweep), w.metric)
+        small = p_lo.norms_bytes + (p_lo.query_bytes + p_lo.lists_bytes) // 3
+        for lim in (small,) + tuple(w.sweep):
             p2 = K.knn_plan(w.m, w.n, w.d, w.k, lim, w.metric)
             ws2 = torch.empty(max(p2.workspace_bytes, 256), dtype=torch.uint8, device=dev)
             i2 = torch.empty_like(idx)
@@ -507,21 +503,22 @@ def main() -> int:
             K.knn_search(Qd, Xd, w.k, lim, workspace=ws2, out=(i2, d2))  # warm-up
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for _ in range(args.steps):
+            for _ in range(steps):
                 K.knn_search(Qd, Xd, w.k, lim, workspace=ws2, out=(i2, d2))
             torch.cuda.synchronize()
-            dt = (time.perf_counter() - t0) / args.steps
-            sweep.append({"mem_limit_bytes": lim, "workspace_bytes": p2.workspace_bytes,
-                          "q_chunks": p2.q_chunks, "point_ranges": p2.n_splits,
-                          "ms_per_step": dt * 1e3,
-                          "pairs_per_s": pairs / dt,
-                          "same_result": bool(torch.equal(i2, idx) and torch.equal(d2, dist))})
-            log(f"[bench] sweep limit={lim}: {dt*1e3:.1f} ms, {pairs/dt:.3e} pairs/s, "
-                f"workspace {p2.workspace_bytes} B, same result: {sweep[-1]['same_result']}")
+            dt = (time.perf_counter() - t0) / steps
+            sweep_out.append({"mem_limit_bytes": lim, "workspace_bytes": p2.workspace_bytes,
+                              "path": PATH_NAMES[p2.path], "q_chunks": p2.q_chunks,
+                              "point_ranges": p2.n_splits, "ms_per_step": dt * 1e3,
+                              "pairs_per_s": pairs / dt,
+                              "same_result": bool(torch.equal(i2, idx) and torch.equal(d2, dist))})
+            log(f"[bench] sweep limit={lim}: {dt*1e3:.1f} ms, {pairs/dt:.3e} pairs/s, path "
+                f"{PATH_NAMES[p2.path]}, {p2.q_chunks} chunks, workspace {p2.workspace_bytes} B, "
+                f"same result: {sweep_out[-1]['same_result']}")
             del ws2, i2, d2
 
     host_streamed = None
-    if args.host_x:
+    if host_x:
         hp = K.knn_plan_host_x(w.m, w.n, w.d, w.k, limit, w.metric)
         Xp = torch.from_numpy(X).pin_memory()
         ws3 = torch.empty(max(hp.workspace_bytes, 256), dtype=torch.uint8, device=dev)
@@ -530,10 +527,10 @@ def main() -> int:
         K.knn_search_host_x(Qd, Xp, w.k, limit, workspace=ws3, out=(i3, d3), metric=w.metric)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(steps):
             K.knn_search_host_x(Qd, Xp, w.k, limit, workspace=ws3, out=(i3, d3), metric=w.metric)
         torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / args.steps
+        dt = (time.perf_counter() - t0) / steps
         host_streamed = {"ms_per_step": dt * 1e3, "pairs_per_s": pairs / dt,
                          "h2d_GB_per_s": X.nbytes / dt / 1e9, "x_bytes": X.nbytes,
                          "n_blocks": hp.n_blocks, "block_rows": hp.block_rows,
@@ -544,23 +541,104 @@ def main() -> int:
             f"{X.nbytes/dt/1e9:.1f} GB/s over the host link, {hp.n_blocks} blocks of {hp.block_rows}")
         del ws3, i3, d3, Xp
 
-    out = {
+    rec = {
         "metric": "query-point pairs per second, exact brute-force kNN (m*n/s)",
-        "value": value, "unit": "pairs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": value, "unit": "pairs/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": PATH_DTYPES[plan.path], "data": "synthetic",
         "config": {"workload": w.name, "metric": w.metric, "m": w.m, "n": w.n, "d": w.d, "k": w.k,
                    "mem_limit_bytes": limit, "workspace_bytes": plan.workspace_bytes,
                    "q_chunks": plan.q_chunks, "point_ranges": plan.n_splits,
+                   "queries_per_workgroup": plan.tile_q, "warm_points": plan.warm_points,
                    "path": path_name},
-        "kernel_ms_per_step": {"norms": norms_ms / args.steps, "search": search_ms / args.steps,
-                               "merge_refine": refine_ms / args.steps},
+        "kernel_ms_per_step": {"preparation": prep_ms / steps, "search": search_ms / steps,
+                               "merge_refine": refine_ms / steps},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity,
     }
-    if sweep is not None:
-        out["mem_limit_sweep"] = sweep
+    if sweep_out is not None:
+        rec["mem_limit_sweep"] = sweep_out
     if host_streamed is not None:
-        out["host_streamed_x"] = host_streamed
+        rec["host_streamed_x"] = host_streamed
+    del Xd, Qd, ws, idx, dist
+    torch.cuda.empty_cache()
+    return rec
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="all",
+                    help="all (default: c4 as the top-level record, c1, c2, c3, c5 as sub-records), or one of "
+                         "c1..c7 (c6 cosine, c7 L1), kmv1 / kmv2 / kmv3 (the kernel matrix-vector product), "
+                         "sgpr1 / sgpr2 (the SGPR accumulations)")
+    ap.add_argument("--mem-limit", default=None, help="e.g. 128MB, 1GB (decimal); default: the workload's")
+    ap.add_argument("--m", type=int, default=None, help="override the query count (testing)")
+    ap.add_argument("--n", type=int, default=None, help="override the point count (testing)")
+    ap.add_argument("--k", type=int, default=None, help="override the neighbour count (testing)")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0,
+                    help="oracle time budget of the top-level record (sub-records get a third); 0 skips it")
+    ap.add_argument("--host-x", action="store_true",
+                    help="also time knn_search_host_x: the same search with X in pinned host memory, "
+                         "streamed through staging buffers inside the limit (PCIe-inclusive; reported "
+                         "beside the resident figure, never as `value`)")
+    ap.add_argument("--calibrate-copy-mb", type=int, default=0,
+                    help="also run one plain elementwise copy of this many MB (read + write) before "
+                         "the timed region, as the known-size reference for rocprofv3 --pmc byte counters")
+    ap.add_argument("--no-peak", action="store_true", help="skip the MFMA-only peak measurement")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 "
+              "(more GPUs would each take a share of the query rows; that is not built)", file=sys.stderr)
+        return 2
+
+    if args.workload.startswith("kmv"):
+        return bench_kmv(args)
+    if args.workload.startswith("sgpr"):
+        return bench_sgpr(args)
+
+    import torch
+
+    import paper_2206_14148_amd as K
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    K.load()
+    peaks = {}
+    if not args.no_peak:
+        peaks = {"bf16": K.knn_measure_mfma_peak("bf16"), "f32": K.knn_measure_mfma_peak("f32")}
+        log(f"[bench] MFMA-only loops on this GPU: bf16 {peaks['bf16']:.0f} TFLOP/s "
+            f"(published 2500), f32 {peaks['f32']:.1f} TFLOP/s (published 157.3)")
+
+    def one(cfg: int, steps: int, cpu_seconds: float, overrides: bool):
+        w = W.WORKLOADS[cfg]
+        default_shape = True
+        if overrides and (args.m or args.n):
+            w = W.scaled(cfg, m=args.m, n=args.n)
+            default_shape = False
+        if overrides and args.k:
+            w = W.scaled(cfg, m=w.m, n=w.n, k=args.k)
+            default_shape = False
+        limit = w.mem_limit
+        if overrides and args.mem_limit:
+            limit = K.knn_parse_size(args.mem_limit)
+            default_shape = False
+        return knn_record(w, limit, steps, args.warmup, cpu_seconds, peaks, default_shape,
+                          host_x=args.host_x and overrides, calibrate_copy_mb=args.calibrate_copy_mb if overrides else 0,
+                          sweep=not (overrides and args.mem_limit))
+
+    if args.workload == "all":
+        out = one(4, args.steps, args.cpu_seconds, False)
+        out["configs"] = {}
+        for cfg in (1, 2, 3, 5):
+            out["configs"][f"c{cfg}"] = one(cfg, max(args.steps, 5), args.cpu_seconds / 3.0, False)
+    else:
+        out = one(int(args.workload.lstrip("c")), args.steps, args.cpu_seconds, True)
+    if peaks:
+        out["measured_mfma_peak_tflops"] = peaks
     print(json.dumps(out), flush=True)
     return 0
 

@@ -95,7 +95,8 @@ typedef struct {
     int64_t chunk_rows;  /* query rows per chunk (multiple of tile_q, or m)     */
     int64_t q_chunks;    /* ceil(m / chunk_rows); 0 when m == 0                 */
     int32_t streams;     /* HIP streams used (1: the caller's)                  */
-    int32_t reserved;    /* 0 */
+    int32_t warm_points; /* path 6: the first warm_points points go through path 5's kernel (they
+                            warm the lists), the packed kernel takes the rest; else 0 */
     int32_t metric;      /* knn_metric                                          */
     int32_t seed_cells;  /* path 4, d <= 3: cells per axis of the grid the points are sorted
                             into to give every list a finite starting threshold (up to k = 32
@@ -215,6 +216,20 @@ int64_t knn_chunk_rows(uint64_t limit_bytes, uint64_t row_bytes);
 knn_status knn_profile_enable(int32_t on);
 knn_status knn_profile_read(float *norms_ms /* HOST */, float *search_ms /* HOST */,
                             float *refine_ms /* HOST */, int64_t *search_launches /* HOST */);
+
+/*
+ * knn_measure_mfma_peak - what the matrix cores of this GPU sustain: a kernel of nothing but
+ * MFMAs (one workgroup of 8 waves per compute unit, about 15 ms, run three times, the last two
+ * timed with HIP events on hip_stream; the call waits for them).  Section 5 reports measured
+ * times; a roofline fraction needs a peak to stand against, and under matrix-core load the chip
+ * does not hold the clock its published peak assumes.
+ *   dtype        0: v_mfma_f32_32x32x16_bf16 (published 2.5 PFLOP/s), 1: v_mfma_f32_32x32x2_f32
+ *                (published 157.3 TFLOP/s)
+ *   scratch      DEVICE, at least 512 KiB, contents undefined afterwards (never written in fact)
+ *   tflops_out   HOST
+ */
+knn_status knn_measure_mfma_peak(int32_t dtype, void *scratch /* DEVICE */, uint64_t scratch_bytes,
+                                 void *hip_stream, float *tflops_out /* HOST */);
 
 /*
  * Data points in HOST memory, streamed through the workspace.

@@ -11,6 +11,6 @@ from .binding import (  # noqa: F401
     knn_profile_read,
     KMV_PATH_LOWD, KMV_PATH_MFMA, KMV_PATH_VALU, KmvPlan, kmv_apply, kmv_apply_raw, kmv_plan,
     HostPlan, knn_plan_host_x, knn_search_host_x, SgprPlan, sgpr_accumulate, sgpr_plan,
-    KNN_ERR_STATIC_SCRATCH_TOO_SMALL, KNN_STATIC_SCRATCH_BYTES, knn_search_static,
+    KNN_ERR_STATIC_SCRATCH_TOO_SMALL, KNN_STATIC_SCRATCH_BYTES, knn_search_static, knn_measure_mfma_peak,
     knn_search, knn_search_raw, knn_status_string, knn_workspace_bytes, library_path, load,
 )

@@ -38,7 +38,7 @@ EXPORTED_SYMBOLS = (
     "knn_profile_read", "knn_plan_metric", "knn_search_metric",
     "kmv_plan", "kmv_apply", "kmv_plan_f64", "kmv_apply_f64",
     "knn_plan_host_x", "knn_search_host_x", "sgpr_plan", "sgpr_accumulate",
-    "knn_search_static",
+    "knn_search_static", "knn_measure_mfma_peak",
 )
 KMV_PATH_LOWD = 0
 KMV_PATH_MFMA = 1
@@ -98,7 +98,7 @@ class PlanStruct(ctypes.Structure):
         ("path", ctypes.c_int32), ("tile_q", ctypes.c_int32),
         ("tile_x", ctypes.c_int32), ("n_splits", ctypes.c_int32),
         ("chunk_rows", ctypes.c_int64), ("q_chunks", ctypes.c_int64),
-        ("streams", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("streams", ctypes.c_int32), ("warm_points", ctypes.c_int32),
         ("metric", ctypes.c_int32), ("seed_cells", ctypes.c_int32),
         ("norms_bytes", ctypes.c_uint64), ("query_bytes", ctypes.c_uint64),
         ("lists_bytes", ctypes.c_uint64),
@@ -148,6 +148,7 @@ class Plan:
     chunk_rows: int
     q_chunks: int
     streams: int
+    warm_points: int
     metric: int
     seed_cells: int
     norms_bytes: int
@@ -193,6 +194,8 @@ def load():
     lib.knn_search.restype = ctypes.c_int
     lib.knn_search_static.argtypes = [vp, i64, vp, i64, i64, i64, i32, i32, vp, vp, vp]
     lib.knn_search_static.restype = ctypes.c_int
+    lib.knn_measure_mfma_peak.argtypes = [i32, vp, u64, vp, ctypes.POINTER(ctypes.c_float)]
+    lib.knn_measure_mfma_peak.restype = ctypes.c_int
     lib.knn_last_stats.argtypes = [ctypes.POINTER(PlanStruct), ctypes.POINTER(u64)]
     lib.knn_last_stats.restype = ctypes.c_int
     lib.knn_status_string.argtypes = [ctypes.c_int]
@@ -236,7 +239,7 @@ def knn_status_string(status: int) -> str:
 
 def _plan_from_struct(ps: PlanStruct) -> Plan:
     return Plan(ps.m, ps.n, ps.d, ps.k, ps.path, ps.tile_q, ps.tile_x, ps.n_splits,
-                ps.chunk_rows, ps.q_chunks, ps.streams, ps.metric, ps.seed_cells,
+                ps.chunk_rows, ps.q_chunks, ps.streams, ps.warm_points, ps.metric, ps.seed_cells,
                 ps.norms_bytes, ps.query_bytes, ps.lists_bytes,
                 ps.workspace_bytes, ps.min_limit_bytes)
 
@@ -339,6 +342,19 @@ def knn_search(Q, X, k: int, mem_limit_bytes: int, workspace=None, out=None, met
             detail += " (" + load().knn_last_hip_error().decode() + ")"
         raise KnnError(st, detail)
     return idx, dist
+
+
+def knn_measure_mfma_peak(dtype: str = "bf16") -> float:
+    """TFLOP/s of a kernel of nothing but MFMAs on the current device ("bf16" or "f32")."""
+    import torch
+
+    scratch = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    out = ctypes.c_float(0)
+    st = int(load().knn_measure_mfma_peak({"bf16": 0, "f32": 1}[dtype], scratch.data_ptr(), scratch.numel(),
+                                          torch.cuda.current_stream().cuda_stream, ctypes.byref(out)))
+    if st != KNN_OK:
+        raise KnnError(st, knn_status_string(st))
+    return float(out.value)
 
 
 def _check_out(out, m: int, k: int, device):

@@ -162,7 +162,7 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     unsigned char* xp = hdr + kAlign;  // path 6: the points rounded to bf16
     // path 6 needs 16-byte aligned rows; other calls run its plan on path 5's kernel
     const bool packed = packed_plan && packed_rows_aligned(Q, ldq, X, ldx, d);
-    const int64_t warm = pk_warm_points(k);
+    const int64_t warm = plan.warm_points;
     unsigned char* qs = ws + plan.norms_bytes;
     float* qn = reinterpret_cast<float*>(
         qs + align_up((uint64_t)plan.chunk_rows * 32 * (((uint64_t)d + kSpKC - 1) / kSpKC)));
@@ -216,21 +216,23 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
         else if (plan.path == KNN_PATH_MFMA_SPLIT || packed_plan) {
             e = launch_split_queries(Qc, ldq, rows, d, qs, tsh, !keep_thresholds, stream);
             if (e == hipSuccess) e = launch_row_norms(Qc, ldq, rows, d, false, qn, stream);
-            // path 6: the first points warm the lists on path 5's kernel, the rest follow out of
-            // the packed copy and continue the same S lists
             if (e == hipSuccess && !packed)
                 e = launch_split(Qc, ldq, X, ldx, qs, qn, tsh, xn, hdr, cosine, rows, n, d, k, S, lk,
                                  li, stream);
             // path 6: the first points warm the list of range 0 on path 5's kernel (one range: the
-            // fewest pairs to evaluate), the rest follow out of the packed copy in S ranges
+            // fewest pairs to evaluate), the rest follow out of the packed copy in S ranges.  The
+            // warm-up counts as preparation in the event brackets, the packed kernel as the search.
             if (e == hipSuccess && packed)
                 e = launch_split(Qc, ldq, X, ldx, qs, qn, tsh, xn, hdr, false, rows, warm, d, k, 1, lk,
                                  li, stream, S);
             if (e == hipSuccess && packed)
                 e = launch_fill_words(tsr, rows * S, 0xff800000u, stream);
-            if (e == hipSuccess && packed)
+            if (e == hipSuccess && packed) {
+                close_bracket(t1, stream, 0);
+                t1 = mark(stream);
                 e = launch_packed(Qc, ldq, X, ldx, xp, warm, qs, qn, tsh, tsr, xn, hdr, rows, n, d, k, S,
                                   plan.tile_q / 32, warm, n, 1, lk, li, stream);
+            }
         } else
             e = hipErrorInvalidValue;  // no such path
         if (e != hipSuccess) {

@@ -248,6 +248,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
             }
             if (best_sets != 0) {
                 out->path = KNN_PATH_MFMA_PACKED;
+                out->warm_points = (int32_t)pk_warm_points(k);
                 out->tile_q = 32 * best_sets;
                 out->tile_x = kPkStep;
                 out->norms_bytes = per_point;
