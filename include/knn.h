@@ -225,7 +225,7 @@ knn_status knn_profile_read(float *norms_ms /* HOST */, float *search_ms /* HOST
  * does not hold the clock its published peak assumes.
  *   dtype        0: v_mfma_f32_32x32x16_bf16 (published 2.5 PFLOP/s), 1: v_mfma_f32_32x32x2_f32
  *                (published 157.3 TFLOP/s)
- *   scratch      DEVICE, at least 512 KiB, contents undefined afterwards (never written in fact)
+ *   scratch      DEVICE, at least 512 KiB, contents undefined afterwards
  *   tflops_out   HOST
  */
 knn_status knn_measure_mfma_peak(int32_t dtype, void *scratch /* DEVICE */, uint64_t scratch_bytes,

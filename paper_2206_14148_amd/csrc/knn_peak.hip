@@ -20,8 +20,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int kPeakUnroll = 16;  // MFMAs per accumulator and loop iteration
 
 // 8 waves per workgroup, one workgroup per compute unit: two waves per SIMD, four independent
-// accumulators each, operands that never change.  out gets one word per thread, and only if
-// the sums are not what an all-zero product leaves (never: it keeps the loop alive).
+// accumulators each, operands that never change.  out gets one word per thread (the sums: they
+// keep the loop alive).
 template <bool BF16>
 __global__ __launch_bounds__(512, 2) void knn_mfma_peak_kernel(int iters, float seed, float* __restrict__ out) {
     f32x16 acc[4];
@@ -29,20 +29,35 @@ __global__ __launch_bounds__(512, 2) void knn_mfma_peak_kernel(int iters, float 
     for (int u = 0; u < 4; ++u)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[u][e] = 0.f;
-    const float av = seed * (float)(threadIdx.x & 7);
-    bf16x8 a8, b8;
+    // Eight different A and B operands of pseudo-random bits, taken in turn: operands that never
+    // change (or all zeros) toggle hardly a wire, draw far less power than real data and flatter
+    // the result.  Magnitudes stay below 2^-4 and signs are mixed, so the sums stay far from
+    // overflow.
+    bf16x8 a8[8], b8[8];
+    unsigned h = (threadIdx.x * 2654435761u) ^ (blockIdx.x * 40503u) ^ (unsigned)__float_as_uint(seed);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        a8[e] = (__bf16)av;
-        b8[e] = (__bf16)seed;
+    for (int r = 0; r < 8; ++r) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            h = h * 1664525u + 1013904223u;
+            // sign and 7 mantissa bits random, exponent 2^-8 .. 2^-5
+            const unsigned short ua = (unsigned short)(((h >> 16) & 0x807f) | ((119 + ((h >> 8) & 3)) << 7));
+            h = h * 1664525u + 1013904223u;
+            const unsigned short ub = (unsigned short)(((h >> 16) & 0x807f) | ((119 + ((h >> 8) & 3)) << 7));
+            a8[r][e] = __builtin_bit_cast(__bf16, ua);
+            b8[r][e] = __builtin_bit_cast(__bf16, ub);
+        }
     }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int r = 0; r < kPeakUnroll; ++r) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                if (BF16) acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a8, b8, acc[u], 0, 0, 0);
-                else acc[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, seed, acc[u], 0, 0, 0);
+                if (BF16)
+                    acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a8[(r + u) & 7], b8[(r + 3 * u) & 7], acc[u], 0, 0, 0);
+                else
+                    acc[u] = __builtin_amdgcn_mfma_f32_32x32x2f32((float)a8[(r + u) & 7][u], (float)b8[r & 7][u],
+                                                               acc[u], 0, 0, 0);
             }
         }
     }
@@ -51,7 +66,7 @@ __global__ __launch_bounds__(512, 2) void knn_mfma_peak_kernel(int iters, float 
     for (int u = 0; u < 4; ++u)
 #pragma unroll
         for (int e = 0; e < 16; ++e) s += acc[u][e];
-    if (s != 0.f) out[blockIdx.x * 512 + threadIdx.x] = s;
+    out[blockIdx.x * 512 + threadIdx.x] = s;
 }
 
 }  // namespace
@@ -72,8 +87,8 @@ extern "C" knn_status knn_measure_mfma_peak(int32_t dtype, void* scratch, uint64
     for (int rep = 0; rep < 3 && e == hipSuccess; ++rep) {
         if (rep == 1) e = hipEventRecord(e0, stream);
         if (e != hipSuccess) break;
-        if (dtype == 0) knn_mfma_peak_kernel<true><<<dim3(blocks), dim3(512), 0, stream>>>(iters, 0.f, out);
-        else knn_mfma_peak_kernel<false><<<dim3(blocks), dim3(512), 0, stream>>>(iters, 0.f, out);
+        if (dtype == 0) knn_mfma_peak_kernel<true><<<dim3(blocks), dim3(512), 0, stream>>>(iters, 0.0078125f, out);
+        else knn_mfma_peak_kernel<false><<<dim3(blocks), dim3(512), 0, stream>>>(iters, 0.0078125f, out);
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipEventRecord(e1, stream);
