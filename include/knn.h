@@ -117,6 +117,14 @@ typedef struct {
     uint64_t lists_bytes;     /* workspace: partial k-lists of one chunk        */
     uint64_t workspace_bytes; /* total device workspace needed, <= mem_limit    */
     uint64_t min_limit_bytes; /* smallest limit any plan for this shape fits in */
+    uint64_t private_bytes;   /* device memory the plan's kernels use beside the workspace: their
+                                 private (register spill) segment, which the HIP runtime provides.
+                                 Bytes per lane x 64 lanes x the waves that can be resident on
+                                 the 256 compute units.  0 on every path except path 4 (at
+                                 most 64 bytes per lane, 16 waves per compute unit); the
+                                 planner takes that path only where workspace_bytes +
+                                 private_bytes stays within the limit.  Not part of
+                                 workspace_bytes: the caller does not allocate it. */
 } knn_plan_t;
 
 /*

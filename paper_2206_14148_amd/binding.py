@@ -103,6 +103,7 @@ class PlanStruct(ctypes.Structure):
         ("norms_bytes", ctypes.c_uint64), ("query_bytes", ctypes.c_uint64),
         ("lists_bytes", ctypes.c_uint64),
         ("workspace_bytes", ctypes.c_uint64), ("min_limit_bytes", ctypes.c_uint64),
+        ("private_bytes", ctypes.c_uint64),
     ]
 
 
@@ -156,6 +157,7 @@ class Plan:
     lists_bytes: int
     workspace_bytes: int
     min_limit_bytes: int
+    private_bytes: int = 0
 
 
 class KnnError(RuntimeError):
@@ -241,7 +243,7 @@ def _plan_from_struct(ps: PlanStruct) -> Plan:
     return Plan(ps.m, ps.n, ps.d, ps.k, ps.path, ps.tile_q, ps.tile_x, ps.n_splits,
                 ps.chunk_rows, ps.q_chunks, ps.streams, ps.warm_points, ps.metric, ps.seed_cells,
                 ps.norms_bytes, ps.query_bytes, ps.lists_bytes,
-                ps.workspace_bytes, ps.min_limit_bytes)
+                ps.workspace_bytes, ps.min_limit_bytes, ps.private_bytes)
 
 
 def knn_plan(m: int, n: int, d: int, k: int, mem_limit_bytes: int, metric: str = "l2") -> Plan:

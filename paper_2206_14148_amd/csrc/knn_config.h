@@ -107,6 +107,13 @@ constexpr int64_t kMaxChunkRows = 1 << 22;  // keeps per-launch row counts and g
 constexpr int kMinSplitPoints = 2048;    // a point range shorter than this is not worth a split
 constexpr int kSpMinSplitPoints = 512;   // the same on the split path
 
+// Private memory of knn_lowd_bf16_kernel (its out-of-line list merge takes the scratch pointers
+// as a struct in the caller's stack frame, and up to d = 4 a few registers spill under the cap
+// of 128): at most this many bytes per lane, and the bound the plan reports for it (64 lanes, up
+// to 16 resident waves on each compute unit)
+constexpr int kPbPrivateBytesPerLane = 64;
+constexpr uint64_t kPbPrivateBytes = (uint64_t)kPbPrivateBytesPerLane * kWave * 16 * kNumCU;
+
 constexpr uint64_t kAlign = 256;
 constexpr inline uint64_t align_up(uint64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 

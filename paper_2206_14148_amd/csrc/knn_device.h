@@ -238,10 +238,32 @@ __device__ __forceinline__ uint64_t wave_merge_pair_inline(float* __restrict__ g
 // Out of line: in most kernels the merge is rare and its registers should not count in the
 // search loop.  (A kernel whose loop already fills the register file calls the inline form: a
 // call would force everything live across it into the callee-saved half of the registers.)
-__device__ __noinline__ uint64_t wave_merge_pair(float* __restrict__ gk, int* __restrict__ gi, int k,
-                                                 float ckey, int cidx, const MergeScratch& sc,
-                                                 int lane, int ncand) {
+// (The scratch pointers travel by value: a struct passed by reference to a real call has to
+// live in the caller's private memory, 48 bytes per lane that the HIP runtime would provide
+// for every resident wave behind the workspace accounting.)
+__device__ __noinline__ uint64_t wave_merge_pair_call(float* __restrict__ gk, int* __restrict__ gi, int k,
+                                                      float ckey, int cidx, float* list_key, int* list_idx,
+                                                      float* cand_key, int* cand_idx, int lane, int ncand) {
+    MergeScratch sc;
+    sc.list_key = list_key;
+    sc.list_idx = list_idx;
+    sc.cand_key = cand_key;
+    sc.cand_idx = cand_idx;
     return wave_merge_pair_inline(gk, gi, k, ckey, cidx, sc, lane, ncand);
+}
+// The same call with the scratch struct passed by reference: for knn_lowd_bf16_kernel, whose
+// register allocation around the call is better that way (measured: 43 against 57 ms on the
+// d = 3 workload) and whose private memory the plan accounts for anyway.
+__device__ __noinline__ uint64_t wave_merge_pair_ref(float* __restrict__ gk, int* __restrict__ gi, int k,
+                                                     float ckey, int cidx, const MergeScratch& sc,
+                                                     int lane, int ncand) {
+    return wave_merge_pair_inline(gk, gi, k, ckey, cidx, sc, lane, ncand);
+}
+__device__ __forceinline__ uint64_t wave_merge_pair(float* __restrict__ gk, int* __restrict__ gi, int k,
+                                                    float ckey, int cidx, const MergeScratch& sc,
+                                                    int lane, int ncand) {
+    return wave_merge_pair_call(gk, gi, k, ckey, cidx, sc.list_key, sc.list_idx, sc.cand_key, sc.cand_idx,
+                                lane, ncand);
 }
 __device__ __forceinline__ float merged_key(uint64_t r) { return __uint_as_float((unsigned)r); }
 __device__ __forceinline__ int merged_idx(uint64_t r) { return (int)(r >> 32); }

@@ -1140,7 +1140,7 @@ __global__ __launch_bounds__(256, FilterSlots<D>::kMfmas == 1 ? 4 : 3) void knn_
                 id = ci[(st * 32 + L) * C + lane];
             }
             const size_t lb = ((size_t)(wave_row0 + st * 32 + L) * S + s) * k;
-            const uint64_t mr = wave_merge_pair(lk + lb, li + lb, k, key, id, sc, lane, cc);
+            const uint64_t mr = wave_merge_pair_ref(lk + lb, li + lb, k, key, id, sc, lane, cc);
             // a list that is not full yet returns +inf: the seed bound stays the threshold
             const bool capped = !(merged_key(mr) <= tcap[st]);
             const float t_new = capped ? tcap[st] : merged_key(mr);

@@ -545,11 +545,11 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
     // stream in flight, which is what the kernel waits for; the shapes are the fastest measured
     // among those that fit the register budget (the element-wise loads of unaligned rows need
     // more registers, so those take narrower steps).
+    // (No shape with one step per tile: its loop is unrolled over two tiles and then spills two
+    // registers to private memory, which the runtime would have to provide beside the workspace.)
     if (aligned) {
-        if (nch <= 1) KNN_SPLIT_LAUNCH(1, 1, true);
-        else if (nch <= 2) KNN_SPLIT_LAUNCH(2, 1, true);
-        else if (nch <= 3) KNN_SPLIT_LAUNCH(3, 1, true);
-        else if (nch <= 4) KNN_SPLIT_LAUNCH(4, 1, true);
+        if (nch <= 2) KNN_SPLIT_LAUNCH(1, 2, true);
+        else if (nch <= 4) KNN_SPLIT_LAUNCH(2, 2, true);
         else if (nch <= 6) KNN_SPLIT_LAUNCH(3, 2, true);
         else if (nch <= 8) KNN_SPLIT_LAUNCH(4, 2, true);
         else if (nch <= 9) KNN_SPLIT_LAUNCH(3, 3, true);
@@ -557,8 +557,7 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
         else if (nch <= kSpResidentMaxChunks) KNN_SPLIT_LAUNCH(4, 4, true);
         else KNN_SPLIT_LAUNCH(4, 0, true);
     } else {
-        if (nch <= 1) KNN_SPLIT_LAUNCH(1, 1, false);
-        else if (nch <= 2) KNN_SPLIT_LAUNCH(2, 1, false);
+        if (nch <= 2) KNN_SPLIT_LAUNCH(1, 2, false);
         else if (nch <= 4) KNN_SPLIT_LAUNCH(2, 2, false);
         else if (nch <= 6) KNN_SPLIT_LAUNCH(2, 3, false);
         else if (nch <= 8) KNN_SPLIT_LAUNCH(2, 4, false);

@@ -169,8 +169,12 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
         const uint64_t per_point = 32ull * ((3 * (uint64_t)d + 3 + 15) / 16);
         const uint64_t packed16 = kAlign + align_up((uint64_t)n * per_point);
         const int64_t min_rows16 = m < kPbTileQ ? m : kPbTileQ;
-        if (mem_limit_bytes >= packed16 + lists_bytes_for((uint64_t)min_rows16, 1, (uint64_t)k)) {
+        // (section 4.4: everything that is live counts - this kernel uses a little private
+        // memory, which the runtime provides beside the workspace)
+        const uint64_t priv = kPbPrivateBytes;
+        if (mem_limit_bytes >= packed16 + priv + lists_bytes_for((uint64_t)min_rows16, 1, (uint64_t)k)) {
             out->path = KNN_PATH_LOWD_BF16;
+            out->private_bytes = priv;
             out->tile_q = kPbTileQ;
             out->tile_x = 32;
             out->norms_bytes = packed16;
@@ -188,8 +192,8 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
                 // cell starts, fill cursors and the points in cell order (16 bytes each)
                 const uint64_t seed = align_up(((uint64_t)cells_of(G) + 1) * 4) +
                                       align_up((uint64_t)cells_of(G) * 4) + align_up((uint64_t)n * 16);
-                if (G >= 2 && mem_limit_bytes >= packed16 + seed + lists_bytes_for((uint64_t)min_rows16,
-                                                                                   1, (uint64_t)k)) {
+                if (G >= 2 && mem_limit_bytes >= packed16 + priv + seed +
+                                                     lists_bytes_for((uint64_t)min_rows16, 1, (uint64_t)k)) {
                     out->seed_cells = (int32_t)G;
                     out->norms_bytes = packed16 + seed;
                 }
@@ -263,7 +267,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
         }
     }
     const int64_t tile = out->tile_q;
-    const uint64_t avail = mem_limit_bytes - out->norms_bytes;
+    const uint64_t avail = mem_limit_bytes - out->norms_bytes - out->private_bytes;
 
     // Number of point ranges S.  More ranges mean more workgroups (tiles x S), each walking
     // n / S points, but also more list warm-up and merge work.  Estimated run time of a

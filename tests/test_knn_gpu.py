@@ -476,9 +476,10 @@ def test_threshold_seed_with_several_point_ranges_and_query_chunks(K, oracle):
     base = K.knn_plan(5000, 60_000, 2, k, 1 << 40)
     tight = None
     for extra in range(200_000, 2_000_000, 50_000):
-        p = K.knn_plan(5000, 60_000, 2, k, base.norms_bytes + extra)
+        # (the kernel's private segment counts against the limit beside the workspace)
+        p = K.knn_plan(5000, 60_000, 2, k, base.norms_bytes + base.private_bytes + extra)
         if p.path == K.KNN_PATH_LOWD_BF16 and p.seed_cells >= 2 and p.q_chunks > 1:
-            tight = base.norms_bytes + extra
+            tight = base.norms_bytes + base.private_bytes + extra
             break
     assert tight is not None
     parity(K, oracle, Q2, X2, k, tight)

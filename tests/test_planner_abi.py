@@ -160,14 +160,20 @@ def test_threshold_seed_grid_is_sized_from_n_and_k_and_paid_for_under_the_limit(
     assert K.knn_plan(1000, 100, 3, 16, 10 ** 9).seed_cells == 0
     assert K.knn_plan(1000, 1_000_000, 4, 16, 10 ** 9).seed_cells == 0
     # room for the packed points and one tile of lists but not for the grid: same path, no grid
+    # (the kernel's private segment, at most 64 bytes per lane x 64 lanes x 16 waves x 256 compute
+    # units, counts against the limit as well)
     n, d, k = 1_000_000, 3, 16
+    priv = 64 * 64 * 16 * 256
     packed = 256 + 32 * n
     tile_lists = 2 * ((256 * k * 4 + 255) // 256 * 256)
-    bare = K.knn_plan(1000, n, d, k, packed + tile_lists)
+    assert K.knn_plan(1000, n, d, k, packed + priv + tile_lists - 1).path != K.KNN_PATH_LOWD_BF16
+    bare = K.knn_plan(1000, n, d, k, packed + priv + tile_lists)
     assert bare.path == K.KNN_PATH_LOWD_BF16 and bare.seed_cells == 0 and bare.norms_bytes == packed
-    assert K.knn_plan(1000, n, d, k, packed + tile_lists + seed_bytes(n, 32 ** 3) - 1).seed_cells == 0
-    full = K.knn_plan(1000, n, d, k, packed + tile_lists + seed_bytes(n, 32 ** 3))
-    assert full.seed_cells == 32 and full.workspace_bytes <= packed + tile_lists + seed_bytes(n, 32 ** 3)
+    assert bare.private_bytes == priv and bare.workspace_bytes + priv <= packed + priv + tile_lists
+    assert K.knn_plan(1000, n, d, k, packed + priv + tile_lists + seed_bytes(n, 32 ** 3) - 1).seed_cells == 0
+    full = K.knn_plan(1000, n, d, k, packed + priv + tile_lists + seed_bytes(n, 32 ** 3))
+    assert full.seed_cells == 32
+    assert full.workspace_bytes + full.private_bytes <= packed + priv + tile_lists + seed_bytes(n, 32 ** 3)
 
 
 def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can():
