@@ -9,7 +9,6 @@
 #include <cctype>
 #include <cmath>
 #include <cstring>
-#include <cstdlib>
 
 #include "../../include/knn.h"
 #include "knn_config.h"
@@ -75,7 +74,7 @@ uint64_t lists_bytes_for(uint64_t rows, uint64_t S, uint64_t k) {
 }
 
 // per-query data of a chunk besides its lists.  kind 1 (path 5): the queries' split B operands
-// (qrow = 64 bytes per 16 coordinates), their squared norms and the thresholds their point
+// (qrow = 32 bytes per 16 coordinates), their squared norms and the thresholds their point
 // ranges share (a word each); kind 2 (L1 path): the queries transposed in blocks of 64 rows
 // (qrow = 16 bytes per 4 coordinates); kind 0: nothing.
 uint64_t query_bytes_for(uint64_t rows, uint64_t qrow, int kind, uint64_t S = 1) {
@@ -220,13 +219,9 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
             double best = 0.0;
             int best_sets = 0;
             int64_t best_S = 0, best_r = 0;
-            const char* fs_ = getenv("KNN_FORCE_S");      // DEV-ONLY
-            const char* fq_ = getenv("KNN_FORCE_SETS");   // DEV-ONLY
             for (int sets = sets_max; sets >= 2 && sets >= sets_max - 6; --sets) {
-                if (fq_ && sets != atoi(fq_)) continue;   // DEV-ONLY
                 const int64_t tile6 = 32 * sets;
                 for (int64_t S = 1; S <= 32; ++S) {
-                    if (fs_ && S != atoi(fs_)) continue;  // DEV-ONLY
                     if ((n - pk_warm_points(k)) / S < 8 * kPkStep * 16) break;  // ranges of >= 16 rounds of the waves
                     int64_t rows = rows_fitting(avail6, (uint64_t)S, (uint64_t)k, qrow, 3);
                     if (rows > kMaxChunkRows) rows = kMaxChunkRows;

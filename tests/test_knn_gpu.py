@@ -309,6 +309,28 @@ def test_cosine_parity_small(K, oracle, seed, m, n, d, k):
     assert idx[2].tolist() == list(range(k)) and np.all(dist[2] == 1.0)
 
 
+def test_cosine_near_parallel_neighbours(K, oracle):
+    # Every query has a cloud of points in almost its own direction: the neighbours' cosine
+    # distances are around 5e-3 and a few 1e-5 apart, with lengths that vary by a factor of
+    # eight.  The selection keys are fp32 values -2 (q.x) / |x| (absolute error about 1e-7 |q|);
+    # the parity rule asks for the oracle's index set wherever the k-th gap exceeds 1e-4 relative,
+    # here about 5e-7 absolute - a few times the key error.  The returned distances are fp64
+    # re-evaluations and must agree everywhere.
+    say("\ncosine near-parallel case")
+    rng = np.random.default_rng(77001)
+    m, d, per, k = 60, 48, 400, 12
+    Q = rng.standard_normal((m, d)).astype(np.float32)
+    near = Q[np.repeat(np.arange(m), per)].astype(np.float64)
+    near += 0.1 * np.linalg.norm(Q, axis=1).mean() / np.sqrt(d) * rng.standard_normal(near.shape)
+    near *= rng.uniform(0.5, 4.0, size=(near.shape[0], 1))
+    far = rng.standard_normal((20000, d))
+    X = np.concatenate([far, near]).astype(np.float32)
+    X = np.ascontiguousarray(X[rng.permutation(X.shape[0])])
+    stats, idx, dist = parity(K, oracle, Q, X, k, metric="cosine")
+    assert float(dist.max()) < 0.05  # all neighbours come from the near clouds
+    assert stats["set_rule_rows"] >= 0.9 * stats["rows"]
+
+
 def test_cosine_result_does_not_depend_on_limit_or_point_layout(K):
     m, n, d, k = 300, 9000, 64, 15
     Q, X = W.random_case(1200, m, n, d)
