@@ -94,7 +94,9 @@ typedef struct {
     int32_t n_splits;    /* ranges the point axis is cut into                   */
     int64_t chunk_rows;  /* query rows per chunk (multiple of tile_q, or m)     */
     int64_t q_chunks;    /* ceil(m / chunk_rows); 0 when m == 0                 */
-    int32_t streams;     /* HIP streams used (1: the caller's)                  */
+    int32_t streams;     /* HIP streams used.  1: the caller's.  2 (more than one query chunk and
+                            room for two sets of lists): merge and exact re-evaluation of a
+                            chunk run on an internal stream while the next chunk is searched */
     int32_t warm_points; /* path 6: the first warm_points points go through path 5's kernel (they
                             warm the lists), the packed kernel takes the rest; else 0 */
     int32_t metric;      /* knn_metric                                          */
@@ -114,7 +116,7 @@ typedef struct {
                                  squared norms and shared thresholds; path 3: the queries
                                  transposed in blocks of 64 rows (16 bytes per row and 4
                                  coordinates); else 0                                  */
-    uint64_t lists_bytes;     /* workspace: partial k-lists of one chunk        */
+    uint64_t lists_bytes;     /* workspace: partial k-lists of one chunk (streams == 2: of two) */
     uint64_t workspace_bytes; /* total device workspace needed, <= mem_limit    */
     uint64_t min_limit_bytes; /* smallest limit any plan for this shape fits in */
     uint64_t private_bytes;   /* device memory the plan's kernels use beside the workspace: their
@@ -159,9 +161,11 @@ uint64_t knn_workspace_bytes(int64_t m, int64_t n, int32_t d, int32_t k,
  *   idx  [m, k]        DEVICE out, int32, contiguous; point indices
  *   dist [m, k]        DEVICE out, fp32, contiguous; squared distances >= 0,
  *                      the fp64 difference-form value rounded to fp32
- *   hip_stream         hipStream_t (NULL = default stream).  All work is
- *                      enqueued there; outputs are valid once the caller has
- *                      synchronised it.
+ *   hip_stream         hipStream_t (NULL = default stream).  The work is enqueued
+ *                      there (with plan.streams == 2 partly on one internal stream
+ *                      of default priority, forked from and joined back into
+ *                      hip_stream with events); outputs are valid once the caller
+ *                      has synchronised hip_stream.
  *
  * Argument and plan errors are returned synchronously and leave the outputs
  * untouched.  The result does not depend on mem_limit_bytes: every limit that
@@ -299,7 +303,8 @@ knn_status knn_search_host_x(const float *Q, int64_t ldq, const float *X /* HOST
  * forbid hipMalloc.  Same kernels, same result (bit for bit) as knn_search; the workspace is a
  * buffer of KNN_STATIC_SCRATCH_BYTES that is part of the library's device image (one copy per
  * GPU the library runs on, held until the process ends), and the plan is the one knn_plan gives
- * for mem_limit_bytes = KNN_STATIC_SCRATCH_BYTES.  The call allocates nothing (no hipMalloc,
+ * for mem_limit_bytes = KNN_STATIC_SCRATCH_BYTES (all of it on hip_stream: no internal stream
+ * is created).  The call allocates nothing (no hipMalloc,
  * hipFree or allocating library routine); the first call on a device looks up that device's
  * address of the buffer.
  *   Q, X, idx, dist, hip_stream   as in knn_search (DEVICE pointers of the current device)

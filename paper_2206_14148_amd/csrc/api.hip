@@ -143,6 +143,35 @@ extern "C" knn_status knn_search(const float* Q, int64_t ldq, const float* X, in
 
 namespace {
 
+// Second stream of a search in several query chunks (one per host thread and device, created on
+// first use, default priority): merge and exact re-evaluation of chunk c run there while the
+// caller's stream searches chunk c + 1.
+struct ChunkStreamState {
+    int device = -1;
+    hipStream_t side = nullptr;
+    hipEvent_t searched[2] = {nullptr, nullptr};  // lists of buffer b are complete
+    hipEvent_t merged[2] = {nullptr, nullptr};    // lists of buffer b are free again
+};
+thread_local ChunkStreamState g_chunk;
+
+hipError_t chunk_state_init() {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (g_chunk.side && g_chunk.device == dev) return hipSuccess;
+    ChunkStreamState fresh;
+    fresh.device = dev;
+    e = hipStreamCreateWithFlags(&fresh.side, hipStreamNonBlocking);
+    if (e != hipSuccess) return e;
+    hipEvent_t* all[4] = {&fresh.searched[0], &fresh.searched[1], &fresh.merged[0], &fresh.merged[1]};
+    for (hipEvent_t* ev : all) {
+        e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
+        if (e != hipSuccess) return e;
+    }
+    g_chunk = fresh;  // a set made for another device is left alone: it belongs to that device
+    return hipSuccess;
+}
+
 // The search of one resident point set under a given plan: norms / packing, then per query
 // chunk the search kernel over all point ranges and the merge + exact re-evaluation.
 // keep_thresholds (path 5, one query chunk): the thresholds that an earlier call with the same
@@ -151,7 +180,7 @@ namespace {
 knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const float* X,
                       int64_t ldx, int64_t m, int64_t n, int32_t d, int32_t k, knn_metric metric,
                       unsigned char* ws, int32_t* idx, float* dist, hipStream_t stream,
-                      bool keep_thresholds = false) {
+                      bool keep_thresholds = false, bool one_stream = false) {
     using namespace knn;
     float* xn = reinterpret_cast<float*>(ws);
     // path 5: [squared norms][header: their maximum] | [split queries][query norms][shared
@@ -169,8 +198,14 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     unsigned char* tsh = reinterpret_cast<unsigned char*>(qn) + align_up((uint64_t)plan.chunk_rows * 4);
     unsigned char* tsr = tsh + align_up((uint64_t)plan.chunk_rows * 4);  // path 6: [rows][S] words
     unsigned char* lists = ws + plan.norms_bytes + plan.query_bytes;
-    float* lk = reinterpret_cast<float*>(lists);
-    int* li = reinterpret_cast<int*>(lists + plan.lists_bytes / 2);
+    // plan.streams == 2: two sets of lists, used by the chunks in turn
+    const int nbuf = plan.streams == 2 ? 2 : 1;
+    const uint64_t set_bytes = plan.lists_bytes / nbuf;
+    const bool overlap = nbuf == 2 && !one_stream;
+    if (overlap) {
+        hipError_t e0 = chunk_state_init();
+        if (e0 != hipSuccess) return hip_fail(e0, "second stream / events");
+    }
     const int S = plan.n_splits;
     const bool cosine = metric == KNN_METRIC_COSINE;
 
@@ -191,8 +226,8 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     } else if (plan.path == KNN_PATH_LOWD_MFMA || plan.path == KNN_PATH_LOWD_BF16) {
         hipEvent_t t0 = mark(stream);
         e = plan.path == KNN_PATH_LOWD_BF16
-                ? launch_lowd_bf16(Q, ldq, X, ldx, ws, 0, n, d, k, S, true, plan.seed_cells, lk, li, stream)
-                : launch_lowd_mfma(Q, ldq, X, ldx, ws, 0, n, d, k, S, true, lk, li, stream);
+                ? launch_lowd_bf16(Q, ldq, X, ldx, ws, 0, n, d, k, S, true, plan.seed_cells, nullptr, nullptr, stream)
+                : launch_lowd_mfma(Q, ldq, X, ldx, ws, 0, n, d, k, S, true, nullptr, nullptr, stream);
         if (e != hipSuccess) {
             drop_bracket(t0);
             return hip_fail(e, "point packing launch");
@@ -200,6 +235,13 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
         close_bracket(t0, stream, 0);
     }
     for (int64_t c = 0; c < plan.q_chunks; ++c) {
+        const int buf = (int)(c % nbuf);
+        float* lk = reinterpret_cast<float*>(lists + buf * set_bytes);
+        int* li = reinterpret_cast<int*>(lists + buf * set_bytes + set_bytes / 2);
+        if (overlap && c >= 2) {  // the merge that read this set of lists two chunks ago
+            e = hipStreamWaitEvent(stream, g_chunk.merged[buf], 0);
+            if (e != hipSuccess) return hip_fail(e, "waiting for a set of lists");
+        }
         const int64_t row0 = c * plan.chunk_rows;
         const int64_t rows = (m - row0 < plan.chunk_rows) ? (m - row0) : plan.chunk_rows;
         const float* Qc = Q + row0 * ldq;
@@ -240,14 +282,32 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
             return hip_fail(e, "search launch");
         }
         close_bracket(t1, stream, 1);
-        hipEvent_t t2 = mark(stream);
+        hipStream_t ms = stream;
+        if (overlap) {
+            ms = g_chunk.side;
+            e = hipEventRecord(g_chunk.searched[buf], stream);
+            if (e == hipSuccess) e = hipStreamWaitEvent(ms, g_chunk.searched[buf], 0);
+            if (e != hipSuccess) return hip_fail(e, "ordering the second stream");
+        }
+        hipEvent_t t2 = mark(ms);
         e = launch_merge_refine(Qc, ldq, X, ldx, rows, n, d, k, S, (int)metric, lk, li,
-                                idx + row0 * k, dist + row0 * k, stream);
+                                idx + row0 * k, dist + row0 * k, ms);
         if (e != hipSuccess) {
             drop_bracket(t2);
             return hip_fail(e, "merge/refine launch");
         }
-        close_bracket(t2, stream, 2);
+        close_bracket(t2, ms, 2);
+        if (overlap) {
+            e = hipEventRecord(g_chunk.merged[buf], ms);
+            if (e != hipSuccess) return hip_fail(e, "ordering the second stream");
+        }
+    }
+    if (overlap) {  // the caller's stream ends behind the last merges
+        const int64_t last = plan.q_chunks - 1;
+        for (int64_t c = last > 0 ? last - 1 : 0; c <= last; ++c) {
+            e = hipStreamWaitEvent(stream, g_chunk.merged[c % 2], 0);
+            if (e != hipSuccess) return hip_fail(e, "joining the second stream");
+        }
     }
     return KNN_OK;
 }
@@ -333,8 +393,9 @@ extern "C" knn_status knn_search_static(const float* Q, int64_t ldq, const float
         unsigned char* ws = nullptr;
         st = static_scratch(&ws);
         if (st != KNN_OK) return st;
+        // (no second stream here: creating one may allocate)
         st = run_search(plan, Q, ldq, X, ldx, m, n, d, k, KNN_METRIC_L2SQ, ws, idx, dist,
-                        static_cast<hipStream_t>(hip_stream));
+                        static_cast<hipStream_t>(hip_stream), false, true);
         if (st != KNN_OK) return st;
     }
     g_last_plan = plan;

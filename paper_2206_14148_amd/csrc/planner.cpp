@@ -105,6 +105,30 @@ int64_t rows_fitting(uint64_t avail, uint64_t S, uint64_t k, uint64_t qrow, int 
     return (int64_t)rows;
 }
 
+// More than one query chunk: the merge and exact re-evaluation of a chunk can run on a second
+// stream while the next chunk is searched, if each of the two has lists of its own.  Both sets
+// are live at once, so both count (section 4.4): the chunk is shortened until two sets of lists
+// fit beside everything else; where not even one query tile fits twice, the chunks stay serial.
+void plan_two_streams(knn_plan_t* out, int64_t m, uint64_t mem_limit_bytes, uint64_t qrow, int qkind) {
+    if (out->q_chunks <= 1) return;
+    const uint64_t S = (uint64_t)out->n_splits, k = (uint64_t)out->k;
+    const uint64_t fixed = out->norms_bytes + out->private_bytes;
+    const int64_t tile = out->tile_q;
+    auto need = [&](int64_t rows) {
+        return fixed + query_bytes_for((uint64_t)rows, qrow, qkind, S) + 2 * lists_bytes_for((uint64_t)rows, S, k);
+    };
+    int64_t rows = out->chunk_rows / 2 / tile * tile;
+    while (rows >= tile && need(rows) > mem_limit_bytes) rows -= tile;
+    if (rows < tile) return;
+    while (rows + tile < m && rows + tile <= kMaxChunkRows && need(rows + tile) <= mem_limit_bytes) rows += tile;
+    out->streams = 2;
+    out->chunk_rows = rows;
+    out->q_chunks = (m + rows - 1) / rows;
+    out->query_bytes = query_bytes_for((uint64_t)rows, qrow, qkind, S);
+    out->lists_bytes = 2 * lists_bytes_for((uint64_t)rows, S, k);
+    out->workspace_bytes = out->norms_bytes + out->query_bytes + out->lists_bytes;
+}
+
 }  // namespace
 
 extern "C" knn_status knn_plan(int64_t m, int64_t n, int32_t d, int32_t k,
@@ -257,6 +281,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
                 out->lists_bytes = lists_bytes_for((uint64_t)best_r, (uint64_t)best_S, (uint64_t)k);
                 out->query_bytes = query_bytes_for((uint64_t)best_r, qrow, 3, (uint64_t)best_S);
                 out->workspace_bytes = out->norms_bytes + out->query_bytes + out->lists_bytes;
+                plan_two_streams(out, m, mem_limit_bytes, qrow, 3);
                 return KNN_OK;
             }
         }
@@ -311,6 +336,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     out->lists_bytes = lists_bytes_for((uint64_t)best_rows, (uint64_t)best_s, (uint64_t)k);
     out->query_bytes = query_bytes_for((uint64_t)best_rows, qrow, qkind);
     out->workspace_bytes = out->norms_bytes + out->query_bytes + out->lists_bytes;
+    plan_two_streams(out, m, mem_limit_bytes, qrow, qkind);
     return KNN_OK;
 }
 

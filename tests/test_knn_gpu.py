@@ -609,3 +609,30 @@ def test_seeded_random_shapes_and_limits(K, oracle):
         o_idx, o_dist, o_next = oracle.knn(Q, X, k, metric=metric)
         check(idx, dist, o_idx, o_dist, o_next, n)
     assert len({p for p, _, _ in seen}) >= 4  # several kernel families were exercised
+
+
+def test_several_chunks_overlap_on_a_second_stream_and_give_the_same_bits(K):
+    # a limit that cuts the queries into chunks: plan.streams == 2, merge and re-evaluation of a
+    # chunk run on the library's internal stream while the next chunk is searched; the call is made
+    # on a stream of the caller's, three times in a row into the same workspace
+    for (m, n, d, k) in [(3000, 30_000, 24, 16), (4000, 50_000, 3, 8), (900, 70_000, 64, 10)]:
+        Q, X = W.random_case(9100 + d, m, n, d)
+        Xd = torch.from_numpy(X).cuda()
+        Qd = torch.from_numpy(Q).cuda()
+        ref_i, ref_d = K.knn_search(Qd, Xd, k, 4 * 10 ** 9)
+        one = K.knn_last_stats()[0]
+        lo = K.knn_plan(m, n, d, k, 1 << 40)
+        tight = p = None
+        for extra in range(0, 4_000_000, 10_000):
+            tight = lo.min_limit_bytes + lo.private_bytes + extra
+            p = K.knn_plan(m, n, d, k, tight)
+            if p.q_chunks > 2 and p.streams == 2:
+                break
+        assert one.q_chunks == 1 and p.q_chunks > 2 and p.streams == 2, (one, p)
+        ws = torch.empty(p.workspace_bytes, dtype=torch.uint8, device="cuda")
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                i2, d2 = K.knn_search(Qd, Xd, k, tight, workspace=ws)
+        side.synchronize()
+        assert torch.equal(ref_i, i2) and torch.equal(ref_d.view(torch.int32), d2.view(torch.int32))

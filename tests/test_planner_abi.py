@@ -111,11 +111,21 @@ def test_small_limits_cut_queries_into_chunks_and_never_exceed_the_limit():
         assert p.chunk_rows >= p.tile_q or p.chunk_rows == m
         # more memory never means fewer (query, range) lists in flight; the chunk count itself
         # may go up when the plan trades rows for ranges (more workgroups per launch)
+        # (with several chunks two sets of lists are live, one being merged while the other is
+        # filled: plan.streams == 2)
         if prev_lists is not None:
-            assert p.chunk_rows * p.n_splits >= prev_lists
-        prev_lists = p.chunk_rows * p.n_splits
-    assert K.knn_plan(m, n, d, k, 8_400_000).q_chunks > 1
-    assert K.knn_plan(m, n, d, k, 10 ** 9).q_chunks == 1
+            assert p.chunk_rows * p.n_splits * p.streams >= prev_lists
+        prev_lists = p.chunk_rows * p.n_splits * p.streams
+        assert p.streams == (2 if p.q_chunks > 1 and p.lists_bytes >= 4 * p.tile_q * p.n_splits * k * 4 else 1)
+    tight = K.knn_plan(m, n, d, k, 8_400_000)
+    assert tight.q_chunks > 1
+    one = K.knn_plan(m, n, d, k, 10 ** 9)
+    assert one.q_chunks == 1 and one.streams == 1
+    # two streams: both sets of lists are counted
+    two = K.knn_plan(m, n, d, k, 20_000_000)
+    assert two.q_chunks > 1 and two.streams == 2
+    assert two.lists_bytes == 2 * 2 * ((two.chunk_rows * two.n_splits * k * 4 + 255) // 256 * 256)
+    assert two.workspace_bytes == two.norms_bytes + two.query_bytes + two.lists_bytes <= 20_000_000
 
 
 def test_low_d_falls_back_to_the_vector_path_when_packed_points_do_not_fit():
@@ -219,13 +229,14 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
         # path 6 also keeps one word per query and point range (the ranges bound each other)
         per_range = up(p.chunk_rows * p.n_splits * 4) if p.path == K.KNN_PATH_MFMA_PACKED else 0
         assert p.query_bytes == up(p.chunk_rows * nch * 32) + 2 * up(p.chunk_rows * 4) + per_range
-        assert p.lists_bytes == 2 * up(p.chunk_rows * p.n_splits * k * 4)
+        assert p.lists_bytes == p.streams * 2 * up(p.chunk_rows * p.n_splits * k * 4)
+        assert p.streams == 1 or p.q_chunks > 1
         assert p.workspace_bytes == p.norms_bytes + p.query_bytes + p.lists_bytes <= limit
         assert p.chunk_rows == m or p.chunk_rows % tile == 0
         assert p.q_chunks == -(-m // p.chunk_rows)
         if p.chunk_rows < m and p.chunk_rows < (1 << 22):  # a longer chunk would not have fitted
             r = p.chunk_rows + tile
-            more = up(r * nch * 32) + 2 * up(r * 4) + 2 * up(r * p.n_splits * k * 4) + \
+            more = up(r * nch * 32) + 2 * up(r * 4) + p.streams * 2 * up(r * p.n_splits * k * 4) + \
                 (up(r * p.n_splits * 4) if p.path == K.KNN_PATH_MFMA_PACKED else 0)
             assert p.norms_bytes + more > limit
         with pytest.raises(K.KnnError):
@@ -256,13 +267,13 @@ def test_l1_path_accounts_for_the_transposed_queries():
         assert p.path == K.KNN_PATH_L1 and p.tile_q == 256
         assert p.norms_bytes == 0
         assert p.query_bytes == qbytes(p.chunk_rows, d)
-        assert p.lists_bytes == 2 * up(p.chunk_rows * p.n_splits * k * 4)
+        assert p.lists_bytes == p.streams * 2 * up(p.chunk_rows * p.n_splits * k * 4)
         assert p.workspace_bytes == p.query_bytes + p.lists_bytes <= limit
         assert p.chunk_rows == m or p.chunk_rows % 256 == 0
         assert p.q_chunks == -(-m // p.chunk_rows)
         if p.chunk_rows < m and p.chunk_rows < (1 << 22):  # a longer chunk would not have fitted
             r = p.chunk_rows + 256
-            assert qbytes(r, d) + 2 * up(r * p.n_splits * k * 4) > limit
+            assert qbytes(r, d) + p.streams * 2 * up(r * p.n_splits * k * 4) > limit
         with pytest.raises(K.KnnError):
             K.knn_plan(m, n, d, k, lo - 1, metric="l1")
 
