@@ -255,7 +255,8 @@ knn_status knn_measure_mfma_peak(int32_t dtype, void *scratch /* DEVICE */, uint
  * are folded into the running result held in idx / dist.
  *
  * The plan: workspace = staging (two buffers of block_rows x d fp32, one if n_blocks == 1)
- *           + block_out (one block's idx and dist, m x k each) + the workspace of `inner`,
+ *           + block_out (one block's indices, list keys and fp64 distances and the running
+ *           result's fp64 distances, m x k each) + the workspace of `inner`,
  *           the knn_plan_metric of one full block under inner_limit_bytes.
  */
 typedef struct {
@@ -283,10 +284,11 @@ knn_status knn_plan_host_x(int64_t m, int64_t n, int32_t d, int32_t k, knn_metri
  *                   valid and unchanged until the caller has synchronised hip_stream.
  *   Q, idx, dist, workspace   DEVICE, as in knn_search; workspace_bytes >=
  *                   knn_plan_host_x(...).workspace_bytes
- * Result: the same neighbours and distances as knn_search_metric on a device copy of X.  The
- * running result is merged on the fp32 distances, so among neighbours of one query whose
- * distances round to the same fp32 value the order (and, at the k-th place, the choice) follows
- * the block order, lower block first, rather than the fp64 values.
+ * Result: bit for bit what knn_search_metric gives on a device copy of X.  The blocks' winners
+ * are folded in the order of their list keys (key, index) - the order in which a resident
+ * search merges its point ranges - with their fp64 distances carried along, and the final
+ * order by (fp64 distance, index) is written when the last block is in; until then dist holds
+ * list keys.
  * The call enqueues work on hip_stream and on one internal stream (created on first use, default
  * priority) ordered against it with events; it returns without waiting for the GPU when X is
  * pinned.  It allocates no device memory.  Calls of one host thread that share a workspace

@@ -180,7 +180,7 @@ hipError_t chunk_state_init() {
 knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const float* X,
                       int64_t ldx, int64_t m, int64_t n, int32_t d, int32_t k, knn_metric metric,
                       unsigned char* ws, int32_t* idx, float* dist, hipStream_t stream,
-                      bool keep_thresholds = false, bool one_stream = false) {
+                      bool keep_thresholds = false, bool one_stream = false, double* block_d64 = nullptr) {
     using namespace knn;
     float* xn = reinterpret_cast<float*>(ws);
     // path 5: [squared norms][header: their maximum] | [split queries][query norms][shared
@@ -291,7 +291,7 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
         }
         hipEvent_t t2 = mark(ms);
         e = launch_merge_refine(Qc, ldq, X, ldx, rows, n, d, k, S, (int)metric, lk, li,
-                                idx + row0 * k, dist + row0 * k, ms);
+                                idx + row0 * k, dist + row0 * k, ms, block_d64 ? block_d64 + row0 * k : nullptr);
         if (e != hipSuccess) {
             drop_bracket(t2);
             return hip_fail(e, "merge/refine launch");
@@ -458,12 +458,16 @@ extern "C" knn_status knn_search_host_x(const float* Q, int64_t ldq, const float
     hipError_t e = host_state_init();
     if (e != hipSuccess) return hip_fail(e, "copy stream / events");
 
-    // workspace: [staging 0 | staging 1] [block idx | block dist] [workspace of the block's plan]
+    // workspace: [staging 0 | staging 1] [block idx | block keys | block fp64 | running fp64]
+    // [workspace of the block's plan]
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     const uint64_t stage_bytes = hp.staging_bytes / (hp.n_blocks > 1 ? 2 : 1);
     float* stage[2] = {reinterpret_cast<float*>(ws), reinterpret_cast<float*>(ws + stage_bytes)};
+    const uint64_t a4 = align_up((uint64_t)m * (uint64_t)k * 4), a8 = align_up((uint64_t)m * (uint64_t)k * 8);
     int32_t* bidx = reinterpret_cast<int32_t*>(ws + hp.staging_bytes);
-    float* bdist = reinterpret_cast<float*>(ws + hp.staging_bytes + hp.block_out_bytes / 2);
+    float* bdist = reinterpret_cast<float*>(ws + hp.staging_bytes + a4);
+    double* bd64 = reinterpret_cast<double*>(ws + hp.staging_bytes + 2 * a4);
+    double* rd64 = reinterpret_cast<double*>(ws + hp.staging_bytes + 2 * a4 + a8);
     unsigned char* inner_ws = ws + hp.staging_bytes + hp.block_out_bytes;
 
     // the staging buffers may still be in use by earlier work on the caller's stream
@@ -498,12 +502,15 @@ extern "C" knn_status knn_search_host_x(const float* Q, int64_t ldq, const float
         const bool keep = b > 0 && nb == hp.block_rows && plan.path == KNN_PATH_MFMA_SPLIT &&
                           plan.q_chunks == 1;
         st = run_search(plan, Q, ldq, stage[buf], d, m, nb, d, kb, metric, inner_ws, bidx, bdist,
-                        stream, keep);
+                        stream, keep, false, bd64);
         if (st != KNN_OK) return st;
-        e = launch_fold_block(bidx, bdist, kb, j0, b == 0 ? 1 : 0, m, k, idx, dist, stream);
+        // (until the final order below, dist holds the running result's list keys)
+        e = launch_fold_keyed(bidx, bdist, bd64, kb, j0, b == 0 ? 1 : 0, m, k, idx, dist, rd64, stream);
         if (e == hipSuccess) e = hipEventRecord(g_host.consumed[buf], stream);
         if (e != hipSuccess) return hip_fail(e, "folding a block into the result");
     }
+    e = launch_order_final(m, k, idx, dist, rd64, stream);
+    if (e != hipSuccess) return hip_fail(e, "final order of the folded result");
     g_last_plan = hp.inner;
     g_last_peak = hp.workspace_bytes;
     g_have_last = true;

@@ -90,18 +90,23 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
 hipError_t launch_fill_words(void* p, int64_t count, unsigned value, hipStream_t stream);
 
 // Merge the S lists of each row, re-evaluate the k winners in fp64 (metric: knn_metric value),
-// order by (distance, index) and write idx / dist rows.
+// order by (distance, index) and write idx / dist rows.  d64 != null (one block of a search over
+// blocks of points): the winners are left in the order of their list keys, dist gets the KEYS and
+// d64 the fp64 distances, for launch_fold_keyed.
 hipError_t launch_merge_refine(const float* Q, int64_t ldq, const float* X, int64_t ldx,
                                int64_t rows, int64_t n, int d, int k, int S, int metric,
                                const float* lk, const int* li, int32_t* idx, float* dist,
-                               hipStream_t stream);
+                               hipStream_t stream, double* d64 = nullptr);
 
-// Running result of a search over blocks of points: idx/dist [rows][k] (ascending by fp32
-// distance) absorb one block's [rows][kb] results, whose indices get `offset` added.  On equal
-// distances the running entries (earlier blocks, lower indices) stay in front.  first != 0:
-// the running result is empty (the block becomes the result, padded with +inf / INT_MAX).
-hipError_t launch_fold_block(const int32_t* bidx, const float* bdist, int kb, int64_t offset,
-                             int first, int64_t rows, int k, int32_t* idx, float* dist,
-                             hipStream_t stream);
+// Running result of a search over blocks of points: idx / key / d64 [rows][k], ascending by
+// (list key, index) - the order in which a resident search merges its point ranges - absorb one
+// block's [rows][kb] results in the same order, whose indices get `offset` added.  first != 0: the
+// running result is empty.  launch_order_final then orders every row by (fp64 distance, index)
+// and writes the distances rounded to fp32 over the keys.
+hipError_t launch_fold_keyed(const int32_t* bidx, const float* bkey, const double* bd64, int kb,
+                             int64_t offset, int first, int64_t rows, int k, int32_t* idx, float* key,
+                             double* d64, hipStream_t stream);
+hipError_t launch_order_final(int64_t rows, int k, int32_t* idx, float* dist, const double* d64,
+                              hipStream_t stream);
 
 }  // namespace knn

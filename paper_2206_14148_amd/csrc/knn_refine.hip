@@ -87,7 +87,8 @@ __device__ __forceinline__ double exact_l1dist(const float* __restrict__ q,
 __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx, int rows,
     int n, int d, int k, int S, int metric, int aligned, const float* __restrict__ lk,
-    const int* __restrict__ li, int32_t* __restrict__ idx_out, float* __restrict__ dist_out) {
+    const int* __restrict__ li, int32_t* __restrict__ idx_out, float* __restrict__ dist_out,
+    double* __restrict__ d64_out) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -95,10 +96,15 @@ __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
     if (r >= rows) return;  // no workgroup barrier below
     double* wd = reinterpret_cast<double*>(smem) + (size_t)wave * k;
     int* wi = reinterpret_cast<int*>(reinterpret_cast<double*>(smem) + (size_t)4 * k) + (size_t)wave * k;
+    float* wk = reinterpret_cast<float*>(reinterpret_cast<int*>(reinterpret_cast<double*>(smem) + (size_t)4 * k) +
+                                         (size_t)4 * k) + (size_t)wave * k;  // the winners' list keys
 
     const size_t rb = (size_t)r * S * k;
     if (S == 1) {
-        for (int p = lane; p < k; p += kWave) wi[p] = li[rb + p];
+        for (int p = lane; p < k; p += kWave) {
+            wi[p] = li[rb + p];
+            wk[p] = lk[rb + p];
+        }
     } else {
         // rank of an entry = its position in its own list + entries of the other lists
         // that come before it; indices are distinct, so ranks are too
@@ -121,7 +127,10 @@ __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
                 }
                 rank += lo;
             }
-            if (rank < k) wi[rank] = id;
+            if (rank < k) {
+                wi[rank] = id;
+                wk[rank] = key;
+            }
         }
     }
     wave_sync();
@@ -139,6 +148,17 @@ __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
         wd[w] = dist;
     }
     wave_sync();
+    if (d64_out) {
+        // One block of a search over blocks of points (knn_search_host_x): the winners stay in
+        // the order of their list keys, with the key in dist_out and the fp64 distance beside
+        // it, for knn_fold_keyed_kernel; the final order comes when all blocks are in.
+        for (int w = lane; w < k; w += kWave) {
+            idx_out[(size_t)r * k + w] = wi[w];
+            dist_out[(size_t)r * k + w] = wk[w];
+            d64_out[(size_t)r * k + w] = wd[w];
+        }
+        return;
+    }
     for (int w = lane; w < k; w += kWave) {
         const double dw = wd[w];
         const int jw = wi[w];
@@ -152,92 +172,140 @@ __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
     }
 }
 
-// One wave per query row: both lists are staged in LDS, every element finds its place in the
-// merged order by a binary search over the other list's distances, the first k are written.
-__global__ __launch_bounds__(256) void knn_fold_block_kernel(
-    const int32_t* __restrict__ bidx, const float* __restrict__ bdist, int kb, int offset,
-    int first, int rows, int k, int32_t* __restrict__ idx, float* __restrict__ dist) {
+// Running result of a search over blocks of points, kept in the order of the list keys - the
+// total order (key, index) in which a resident search merges its point ranges - so that the k
+// entries that survive all blocks are the very ones a resident search selects.  One wave per
+// query row: running entries (index in idx, key in key, fp64 distance in d64; none yet with
+// first != 0) and the block's kb entries (indices + offset) are staged in LDS, every entry finds
+// its place by a binary search over the other list, the first k are written back.
+__global__ __launch_bounds__(256) void knn_fold_keyed_kernel(
+    const int32_t* __restrict__ bidx, const float* __restrict__ bkey, const double* __restrict__ bd64,
+    int kb, int offset, int first, int rows, int k, int32_t* __restrict__ idx, float* __restrict__ key,
+    double* __restrict__ d64) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    float* ad = reinterpret_cast<float*>(smem) + (size_t)wave * 4 * k;  // running distances [k]
-    int* ai = reinterpret_cast<int*>(ad + k);                           // running indices   [k]
-    float* bd = reinterpret_cast<float*>(ai + k);                       // block distances   [k]
-    int* bi = reinterpret_cast<int*>(bd + k);                           // block indices     [k]
+    double* ad = reinterpret_cast<double*>(smem) + (size_t)wave * 2 * k;  // running fp64 [k]
+    double* bd = ad + k;                                                  // block fp64   [k]
+    float* ak = reinterpret_cast<float*>(reinterpret_cast<double*>(smem) + (size_t)4 * 2 * k) + (size_t)wave * 4 * k;
+    int* ai = reinterpret_cast<int*>(ak + k);
+    float* bk = reinterpret_cast<float*>(ai + k);
+    int* bi = reinterpret_cast<int*>(bk + k);
     const int r = blockIdx.x * 4 + wave;
     if (r >= rows) return;  // whole wave; no workgroup barrier below
     const int na = first ? 0 : k;
+    const size_t rb = (size_t)r * k;
     for (int p = lane; p < na; p += kWave) {
-        ad[p] = dist[(size_t)r * k + p];
-        ai[p] = idx[(size_t)r * k + p];
+        ak[p] = key[rb + p];
+        ai[p] = idx[rb + p];
+        ad[p] = d64[rb + p];
     }
     for (int p = lane; p < kb; p += kWave) {
-        bd[p] = bdist[(size_t)r * kb + p];
-        bi[p] = bidx[(size_t)r * kb + p] + offset;
+        bk[p] = bkey[(size_t)r * kb + p];
+        const int j = bidx[(size_t)r * kb + p];
+        bi[p] = j == kNoIdx ? kNoIdx : j + offset;
+        bd[p] = bd64[(size_t)r * kb + p];
     }
     wave_sync();
-    // running element p goes behind the block elements that are strictly closer
-    for (int p = lane; p < na; p += kWave) {
-        const float key = ad[p];
+    for (int p = lane; p < na; p += kWave) {  // behind the block entries that come before it
         int lo = 0, hi = kb;
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
-            if (bd[mid] < key) lo = mid + 1;
+            if (before(bk[mid], bi[mid], ak[p], ai[p])) lo = mid + 1;
             else hi = mid;
         }
         const int pos = p + lo;
         if (pos < k) {
-            dist[(size_t)r * k + pos] = key;
-            idx[(size_t)r * k + pos] = ai[p];
+            key[rb + pos] = ak[p];
+            idx[rb + pos] = ai[p];
+            d64[rb + pos] = ad[p];
         }
     }
-    // block element p goes behind the running elements that are closer or equally close
-    for (int p = lane; p < kb; p += kWave) {
-        const float key = bd[p];
+    for (int p = lane; p < kb; p += kWave) {  // behind the running entries that come before it
         int lo = 0, hi = na;
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
-            if (ad[mid] <= key) lo = mid + 1;
+            if (before(ak[mid], ai[mid], bk[p], bi[p])) lo = mid + 1;
             else hi = mid;
         }
         const int pos = p + lo;
         if (pos < k) {
-            dist[(size_t)r * k + pos] = key;
-            idx[(size_t)r * k + pos] = bi[p];
+            key[rb + pos] = bk[p];
+            idx[rb + pos] = bi[p];
+            d64[rb + pos] = bd[p];
         }
     }
-    // nothing yet for the places beyond the points seen so far
-    for (int p = na + kb + lane; p < k; p += kWave) {
-        dist[(size_t)r * k + p] = kInf;
-        idx[(size_t)r * k + p] = kNoIdx;
+    for (int p = na + kb + lane; p < k; p += kWave) {  // nothing yet beyond the points seen so far
+        key[rb + p] = kInf;
+        idx[rb + p] = kNoIdx;
+        d64[rb + p] = __builtin_huge_val();
+    }
+}
+
+// The final order of such a running result: by (fp64 distance, index), as knn_merge_refine_kernel
+// orders the winners of a resident search; dist gets the fp64 distance rounded to fp32.
+__global__ __launch_bounds__(256) void knn_order_final_kernel(int rows, int k, int32_t* __restrict__ idx,
+                                                              float* __restrict__ dist,
+                                                              const double* __restrict__ d64) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    double* wd = reinterpret_cast<double*>(smem) + (size_t)wave * k;
+    int* wi = reinterpret_cast<int*>(reinterpret_cast<double*>(smem) + (size_t)4 * k) + (size_t)wave * k;
+    const int r = blockIdx.x * 4 + wave;
+    if (r >= rows) return;
+    const size_t rb = (size_t)r * k;
+    for (int p = lane; p < k; p += kWave) {
+        wd[p] = d64[rb + p];
+        wi[p] = idx[rb + p];
+    }
+    wave_sync();
+    for (int w = lane; w < k; w += kWave) {
+        const double dw = wd[w];
+        const int jw = wi[w];
+        int rank = 0;
+        for (int v = 0; v < k; ++v)
+            rank += (before64(wd[v], wi[v], dw, jw) || (wd[v] == dw && wi[v] == jw && v < w)) ? 1 : 0;
+        idx[rb + rank] = jw;
+        dist[rb + rank] = (float)dw;
     }
 }
 
 }  // namespace
 
-hipError_t launch_fold_block(const int32_t* bidx, const float* bdist, int kb, int64_t offset,
-                             int first, int64_t rows, int k, int32_t* idx, float* dist,
-                             hipStream_t stream) {
-    const size_t lds = (size_t)4 * 4 * k * 4;
-    hipError_t e = raise_lds_limit(knn_fold_block_kernel, lds);
+hipError_t launch_fold_keyed(const int32_t* bidx, const float* bkey, const double* bd64, int kb,
+                             int64_t offset, int first, int64_t rows, int k, int32_t* idx, float* key,
+                             double* d64, hipStream_t stream) {
+    const size_t lds = (size_t)4 * k * (2 * sizeof(double) + 4 * sizeof(float));
+    hipError_t e = raise_lds_limit(knn_fold_keyed_kernel, lds);
     if (e != hipSuccess) return e;
-    knn_fold_block_kernel<<<dim3((unsigned)((rows + 3) / 4)), dim3(256), lds, stream>>>(
-        bidx, bdist, kb, (int)offset, first, (int)rows, k, idx, dist);
+    knn_fold_keyed_kernel<<<dim3((unsigned)((rows + 3) / 4)), dim3(256), lds, stream>>>(
+        bidx, bkey, bd64, kb, (int)offset, first, (int)rows, k, idx, key, d64);
+    return hipGetLastError();
+}
+
+hipError_t launch_order_final(int64_t rows, int k, int32_t* idx, float* dist, const double* d64,
+                              hipStream_t stream) {
+    const size_t lds = (size_t)4 * k * (sizeof(double) + sizeof(int));
+    hipError_t e = raise_lds_limit(knn_order_final_kernel, lds);
+    if (e != hipSuccess) return e;
+    knn_order_final_kernel<<<dim3((unsigned)((rows + 3) / 4)), dim3(256), lds, stream>>>((int)rows, k, idx,
+                                                                                       dist, d64);
     return hipGetLastError();
 }
 
 hipError_t launch_merge_refine(const float* Q, int64_t ldq, const float* X, int64_t ldx,
                                int64_t rows, int64_t n, int d, int k, int S, int metric,
                                const float* lk, const int* li, int32_t* idx, float* dist,
-                               hipStream_t stream) {
-    const size_t lds = (size_t)4 * k * (sizeof(double) + sizeof(int));
+                               hipStream_t stream, double* d64) {
+    const size_t lds = (size_t)4 * k * (sizeof(double) + sizeof(int) + sizeof(float));
     hipError_t e = raise_lds_limit(knn_merge_refine_kernel, lds);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((rows + 3) / 4));
     const int aligned = (reinterpret_cast<uintptr_t>(Q) % 16 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0) &&
                         (ldq % 4 == 0) && (ldx % 4 == 0) && (d % 4 == 0);
     knn_merge_refine_kernel<<<grid, dim3(256), lds, stream>>>(
-        Q, ldq, X, ldx, (int)rows, (int)n, d, k, S, metric, aligned, lk, li, idx, dist);
+        Q, ldq, X, ldx, (int)rows, (int)n, d, k, S, metric, aligned, lk, li, idx, dist, d64);
     return hipGetLastError();
 }
 

@@ -358,7 +358,9 @@ extern "C" knn_status knn_plan_host_x(int64_t m, int64_t n, int32_t d, int32_t k
     out->metric = (int32_t)metric;
     if (m == 0) return KNN_OK;
     const uint64_t row = (uint64_t)d * 4;
-    const uint64_t outb = 2 * align_up((uint64_t)m * (uint64_t)k * 4);
+    // a block's winners (index, list key, fp64 distance) and the running result's fp64 distances
+    // (its indices and keys live in the caller's idx and dist until the final order is written)
+    const uint64_t outb = 2 * align_up((uint64_t)m * (uint64_t)k * 4) + 2 * align_up((uint64_t)m * (uint64_t)k * 8);
     const int64_t b_floor = n < 1024 ? n : ((int64_t)k > 1024 ? (int64_t)k : 1024);  // shortest block
     {
         knn_plan_t smallest;

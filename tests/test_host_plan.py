@@ -16,7 +16,8 @@ def test_roomy_limit_stages_everything_as_one_block():
     p = K.knn_plan_host_x(1000, 10_000, 16, 10, 64 * W.MB)
     assert (p.n_blocks, p.block_rows) == (1, 10_000)
     assert p.staging_bytes == up(10_000 * 16 * 4)
-    assert p.block_out_bytes == 2 * up(1000 * 10 * 4)
+    # a block's winners (index, list key, fp64 distance) and the running result's fp64 distances
+    assert p.block_out_bytes == 2 * up(1000 * 10 * 4) + 2 * up(1000 * 10 * 8)
     assert p.workspace_bytes == p.staging_bytes + p.block_out_bytes + p.inner.workspace_bytes
     assert p.workspace_bytes <= 64 * W.MB
     assert (p.inner.m, p.inner.n, p.inner.k) == (1000, 10_000, 10)

@@ -44,15 +44,13 @@ def run_both(K, oracle, Q, X, k, limit, metric="l2", pinned=True, min_blocks=2):
     o_idx, o_dist, o_next = oracle.knn(Q, X, k, metric=metric)
     stats = check(idx, dist, o_idx, o_dist, o_next, X.shape[0])
     say("   parity", stats)
-    # the resident search on a device copy gives the same bits on every row whose oracle
-    # distances (the (k+1)-th included) are pairwise clearly apart
+    # the resident search on a device copy gives the same bits on every row: the blocks are folded
+    # in the order of the list keys, the order in which a resident search merges its point ranges,
+    # and the final order comes from the fp64 distances
     r_idx, r_dist = K.knn_search(Qd, torch.from_numpy(X).cuda(), k, 64 * W.MB, metric=metric)
     torch.cuda.synchronize()
     r_idx, r_dist = r_idx.cpu().numpy(), r_dist.cpu().numpy()
-    ext = np.concatenate([o_dist, o_next[:, None]], axis=1)
-    clear = (np.diff(ext, axis=1) > 1e-4 * np.maximum(ext[:, :-1], 1e-30)).all(axis=1)
-    assert clear.mean() > 0.2
-    assert np.array_equal(idx[clear], r_idx[clear]) and np.array_equal(dist[clear], r_dist[clear])
+    assert np.array_equal(idx, r_idx) and np.array_equal(dist.view(np.int32), r_dist.view(np.int32))
     return idx, dist
 
 
