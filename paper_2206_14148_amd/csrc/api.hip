@@ -212,10 +212,13 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     hipError_t e;
     if (plan.path == KNN_PATH_MFMA_SPLIT || packed_plan) {
         hipEvent_t t0 = mark(stream);
-        e = launch_row_norms(X, ldx, n, d, cosine, xn, stream);
+        // (the header's second word: the points' largest bf16 rounding residual, which the
+        // filters' allowance is built from; not used by the cosine metric)
+        e = launch_header_init(hdr, stream);
+        if (e == hipSuccess)
+            e = launch_row_norms(X, ldx, n, d, cosine, xn, stream, cosine ? nullptr : hdr + 4);
         if (e == hipSuccess) e = launch_max_norm(xn, n, hdr, stream);
         if (e == hipSuccess && packed) e = launch_pad_norms(xn, n, stream);
-        if (e == hipSuccess && packed) e = launch_residual_max(X, ldx, n, d, hdr, stream);
         if (e == hipSuccess && packed)
             e = launch_pack_operands(X, ldx, n, d, warm, (int64_t)n64 - warm, xp, stream);
         if (e != hipSuccess) {

@@ -23,6 +23,11 @@ __device__ __forceinline__ unsigned round_pair(float a, float b) {
     return __builtin_bit_cast(unsigned, __builtin_convertvector(p, bf16x2));
 }
 
+// float - its bf16 rounding (exact in fp32)
+__device__ __forceinline__ float bf16_residual(float v) {
+    return v - __uint_as_float(round_pair(v, 0.f) << 16);
+}
+
 // floats <-> unsigned words with the same order (for atomicMin on keys of either sign)
 __device__ __forceinline__ unsigned key_word(float f) {
     const unsigned u = __float_as_uint(f);

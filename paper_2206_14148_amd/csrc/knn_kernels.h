@@ -12,8 +12,10 @@ namespace knn {
 
 // xn[j] = sum_t X[j][t]^2 in fp32 (the sum x^2 term of paper section 4.1); inverse = true writes
 // 1 / sqrt(that) instead (0 for a zero row), the row scale of the cosine metric.
+// resid != null (a word zeroed beforehand, launch_header_init): it also gets the bits of
+// max_j |x_j - bf16(x_j)|^2.
 hipError_t launch_row_norms(const float* X, int64_t ldx, int64_t n, int d, bool inverse, float* xn,
-                            hipStream_t stream);
+                            hipStream_t stream, void* resid = nullptr);
 
 // d <= kLowdMaxD: key = fp32 difference-form squared distance.
 hipError_t launch_lowd(const float* Q, int64_t ldq, const float* X, int64_t ldx, int64_t rows,
@@ -44,7 +46,8 @@ hipError_t launch_lowd_bf16(const float* Q, int64_t ldq, const float* X, int64_t
 
 // d > kPbMaxD, and the cosine metric at any d: bf16 matrix-core filter on split values, exact
 // fp32 test of what passes it (knn_split.hip).
-//   launch_max_norm      hdr word 0 = max of xn[0..n) (hdr: kAlign bytes)
+//   launch_header_init   hdr words 0 and 1 = 0 (hdr: kAlign bytes)
+//   launch_max_norm      hdr word 0 = max of xn[0..n), after launch_header_init
 //   launch_split_queries qs = the B operands of `rows` queries: ceil(d / 16) * 64 bytes per row;
 //                        tsh = [rows] words, the thresholds the ranges share: set to +inf, or
 //                        (reset_thresholds false) kept from an earlier search of other points
@@ -53,6 +56,7 @@ hipError_t launch_lowd_bf16(const float* Q, int64_t ldq, const float* X, int64_t
 //                        cosine: xn holds 1 / |x| and the keys are -2 q.x / |x|;
 //                        list_S > S: the lists of a row are list_S * k entries apart (the S
 //                        ranges fill the first S of them, the others are not touched)
+hipError_t launch_header_init(void* hdr, hipStream_t stream);
 hipError_t launch_max_norm(const float* xn, int64_t n, void* hdr, hipStream_t stream);
 hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d, void* qs,
                                 void* tsh, bool reset_thresholds, hipStream_t stream);
@@ -77,9 +81,6 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
 hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, int64_t j_first,
                                 int64_t points, void* xp, hipStream_t stream);
 hipError_t launch_pad_norms(float* xn, int64_t n, hipStream_t stream);
-// hdr word 1 = max_j |x_j - bf16(x_j)|^2 (after launch_max_norm, which zeroes the header)
-hipError_t launch_residual_max(const float* X, int64_t ldx, int64_t n, int d, void* hdr,
-                               hipStream_t stream);
 bool packed_rows_aligned(const float* Q, int64_t ldq, const float* X, int64_t ldx, int d);
 hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* xp,
                          int64_t slab_first, const void* qs, const float* qn, void* tsh, void* tsr,

@@ -64,33 +64,6 @@ __global__ __launch_bounds__(256) void knn_pack_operands_kernel(const float* __r
     Xp[((size_t)(st * 2 + pb) * nch + c) * 64 + h * 32 + i32] = w;
 }
 
-// float - its bf16 rounding (exact in fp32)
-__device__ __forceinline__ float bf16_residual(float v) {
-    return v - __uint_as_float(round_pair(v, 0.f) << 16);
-}
-
-// hdr word 1 = max over the points of |x - bf16(x)|^2, the rounding residual the filter has to
-// allow for: one wave per row (bits of a non-negative float, so an integer maximum orders them).
-__global__ __launch_bounds__(256) void knn_residual_max_kernel(const float* __restrict__ X, int64_t ldx,
-                                                               int64_t n, int d, unsigned* __restrict__ hdr) {
-    const int lane = threadIdx.x & 63;
-    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t nwaves = (int64_t)gridDim.x * 4;
-    float worst = 0.f;
-    for (int64_t j = wave; j < n; j += nwaves) {
-        const float* row = X + j * ldx;
-        float acc = 0.f;
-        for (int t = lane; t < d; t += kWave) {
-            const float r = bf16_residual(row[t]);
-            acc = fmaf(r, r, acc);
-        }
-#pragma unroll
-        for (int s = 32; s > 0; s >>= 1) acc += __shfl_xor(acc, s);
-        worst = fmaxf(worst, acc);
-    }
-    if (lane == 0) atomicMax(hdr + 1, __float_as_uint(worst));
-}
-
 // norms past n (up to the end of the last step) are +inf: such a row never passes the filter
 __global__ void knn_pad_norms_kernel(float* __restrict__ xn, int n, int n_pad) {
     const int i = n + blockIdx.x * 64 + threadIdx.x;
@@ -533,15 +506,6 @@ hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, i
     else
         knn_pack_operands_kernel<false><<<grid, dim3(256), 0, stream>>>(X, ldx, (int)n, d, nch, (int)j_first,
                                                                         pieces, static_cast<uint4*>(xp));
-    return hipGetLastError();
-}
-
-hipError_t launch_residual_max(const float* X, int64_t ldx, int64_t n, int d, void* hdr,
-                               hipStream_t stream) {
-    int64_t blocks = (n + 3) / 4;
-    if (blocks > 16384) blocks = 16384;
-    knn_residual_max_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(
-        X, ldx, n, d, static_cast<unsigned*>(hdr));
     return hipGetLastError();
 }
 

@@ -139,16 +139,21 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     init_lists32(lk, li, wave_row0, rows, LS, s, k, lane);
 
     const float xmax = __uint_as_float(hdr[0]);
-    // Filter keys are  xn_j - 2 bf16(x).bf16(q)  accumulated in fp32; the exact test gives
+    // Filter keys are  xn_j + bf16(x).bf16(-2 q)  accumulated in fp32; the exact test gives
     // dd = sum (q - x)^2  in fp32.  dd <= tau implies key < (tau - qn) + slack with
-    //   rounded operands            2 (x q - bf16(x) bf16(q)): each value moves by at most 2^-8
-    //                               of itself (round to nearest, 8 significant bits), so at
-    //                               most 1.002 * 2^-6 |x| |q|, and |x| |q| <= sqrt(xmax qn)
-    //   fp32 accumulations           one per coordinate (padded), of terms that sum to at most
-    //                               2.02 |x| |q| in magnitude
-    //   roundings of xn, qn, dd      each below (d / 64 + 8) ulps of the value
+    //   rounded operands    sum x~ q~' - sum x q' = sum x~ (q~' - q') + sum (x~ - x) q'  (q' = -2 q),
+    //                       at most |x~| |q~' - q'| + |x~ - x| |q'| by Cauchy-Schwarz: the query's
+    //                       residual norm is taken below, the largest residual norm of a point
+    //                       comes with the header (word 1), |x~| <= sqrt(xmax) + that; 1 % on
+    //                       top for the fp32 arithmetic of these norms.  (The worst case, 2^-8 of
+    //                       every value, gives 2^-6 |x| |q|: about 2.5 times this on dense data,
+    //                       more where many coordinates are zero or exact in bf16.)
+    //   fp32 accumulations   one per coordinate (padded), of terms that sum to at most
+    //                       2.02 |x| |q| in magnitude
+    //   roundings of xn, qn, dd   each below (d / 64 + 8) ulps of the value
     // The constants below cover the first in full and are at least twice the others.
-    const float e_dot = 1.01f * 0x1p-6f + (float)(4 * (nst * W * 16) + 32) * 0x1p-24f;
+    const float e_acc = (float)(4 * (nst * W * 16) + 32) * 0x1p-24f;
+    const float e_dot = 1.01f * 0x1p-6f + e_acc;  // (the worst-case form: cosine metric)
     const float e_sum = (float)(d + 16) * 0x1p-23f;
     // own = k-th key of this range's list (+inf until it is full, -inf for a lane without a
     // query), cap = the lowest k-th key any range of the query has published, tauf = the filter
@@ -157,7 +162,30 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     const bool active = r_mine < rows;
     const int qrow = active ? r_mine : rows - 1;
     const float qn = qnorm[qrow];
-    const float cross = e_dot * sqrtf(xmax * qn);
+    float cross = 0.f;
+    if (!cosine) {
+        // |bf16(-2 q) - (-2 q)|^2 of the lane's query: the two halves of the wave share the sum
+        const float* qrp = Q + (int64_t)qrow * ldq;
+        float rq2 = 0.f;
+        if (ALIGNED) {
+            for (int g = h; 4 * g < d; g += 2) {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(qrp + 4 * g);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float r = bf16_residual(-2.f * v[e]);
+                    rq2 = fmaf(r, r, rq2);
+                }
+            }
+        } else {
+            for (int t = h; t < d; t += 2) {
+                const float r = bf16_residual(-2.f * qrp[t]);
+                rq2 = fmaf(r, r, rq2);
+            }
+        }
+        rq2 += lane_xor<32>(rq2);
+        const float rxm = sqrtf(__uint_as_float(hdr[1]));
+        cross = 1.01f * ((sqrtf(xmax) + rxm) * sqrtf(rq2) + rxm * 2.f * sqrtf(qn)) + e_acc * sqrtf(xmax * qn);
+    }
     float own = active ? kInf : -kInf;
     float cap = kInf;
     float tauf = own;
@@ -473,9 +501,13 @@ __global__ void knn_fill_words_kernel(unsigned* __restrict__ p, int64_t count, u
 
 }  // namespace
 
+hipError_t launch_header_init(void* hdr, hipStream_t stream) {
+    knn_split_init_kernel<<<dim3(1), dim3(64), 0, stream>>>(static_cast<unsigned*>(hdr));
+    return hipGetLastError();
+}
+
 hipError_t launch_max_norm(const float* xn, int64_t n, void* hdr, hipStream_t stream) {
     unsigned* w = static_cast<unsigned*>(hdr);
-    knn_split_init_kernel<<<dim3(1), dim3(64), 0, stream>>>(w);
     int64_t blocks = (n + 255) / 256;
     if (blocks > 1024) blocks = 1024;
     knn_max_norm_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(xn, n, w);
