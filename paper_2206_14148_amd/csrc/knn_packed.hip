@@ -94,17 +94,7 @@ struct PkArgs {
     int range_steps;  // steps per point range
     int init_from;    // the lists of ranges >= this start empty, the others continue
     int j_valid;      // a valid point index for lanes that hold no candidate
-#ifdef KNN_PK_STATS
-    unsigned long long* stats;
-#endif
 };
-#ifdef KNN_PK_STATS
-#define PK_STAT(i, v) do { if (a.stats && lane == 0) atomicAdd(ctl + 32 + (i), (int)(v)); } while (0)
-#define PK_CLOCK() wall_clock64()
-#else
-#define PK_STAT(i, v) do { } while (0)
-#define PK_CLOCK() 0ull
-#endif
 
 enum { kCtlStop = 16, kCtlCount = 17, kCtlDone = 18, kCtlNext = 19 };
 
@@ -290,7 +280,8 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
     // slot of the query's buffer (a counter in LDS that all waves add to).  A pair that finds
     // the buffer full marks (wave, step parity) for the query: the stop then tests all 64 points
     // of that step for it and drops what the buffer already holds of them.
-    auto append = [&](int q, float tq, const f32x16& a0, const f32x16& a1, int st, int parity) {
+    auto append = [&](int q, float tq, const f32x16& a0, const f32x16& a1, const float (&g)[8], int st,
+                      int parity) {
         bool call = false;
         const int jb = st * kPkStep + h * 4;
         auto one = [&](float key, int off) {
@@ -308,9 +299,17 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
             }
         };
 #pragma unroll
-        for (int e = 0; e < 16; ++e) one(a0[e], (e >> 2) * 8 + (e & 3));
+        for (int u = 0; u < 4; ++u) {
+            if (__builtin_amdgcn_ballot_w64(g[u] < tq) == 0) continue;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) one(a1[e], 32 + (e >> 2) * 8 + (e & 3));
+            for (int e = 4 * u; e < 4 * u + 4; ++e) one(a0[e], (e >> 2) * 8 + (e & 3));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (__builtin_amdgcn_ballot_w64(g[4 + u] < tq) == 0) continue;
+#pragma unroll
+            for (int e = 4 * u; e < 4 * u + 4; ++e) one(a1[e], 32 + (e >> 2) * 8 + (e & 3));
+        }
         if (__builtin_amdgcn_ballot_w64(call) != 0 && lane == 0)
             __hip_atomic_store(ctl + kCtlStop, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     };
@@ -347,15 +346,18 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        float m0 = acc0[0], m1 = acc1[0];
+        // minima of the eight groups of four registers, then of all 32: the rare path below only
+        // looks into groups that hold a key under some lane's threshold
+        float g[8];
 #pragma unroll
-        for (int e = 1; e < 16; e += 2) {
-            m0 = fminf(fminf(m0, acc0[e]), acc0[e + 1 < 16 ? e + 1 : e]);
-            m1 = fminf(fminf(m1, acc1[e]), acc1[e + 1 < 16 ? e + 1 : e]);
+        for (int u = 0; u < 4; ++u) {
+            g[u] = fminf(fminf(fminf(acc0[4 * u], acc0[4 * u + 1]), acc0[4 * u + 2]), acc0[4 * u + 3]);
+            g[4 + u] = fminf(fminf(fminf(acc1[4 * u], acc1[4 * u + 1]), acc1[4 * u + 2]), acc1[4 * u + 3]);
         }
-        if (__builtin_amdgcn_ballot_w64(fminf(m0, m1) < tq) != 0) {
-            PK_STAT(7, 1);
-            append(q, tq, acc0, acc1, st, parity);
+        const float m = fminf(fminf(fminf(fminf(g[0], g[1]), g[2]), fminf(fminf(g[3], g[4]), g[5])),
+                              fminf(g[6], g[7]));
+        if (__builtin_amdgcn_ballot_w64(m < tq) != 0) {
+            append(q, tq, acc0, acc1, g, st, parity);
         }
     };
 
@@ -376,8 +378,6 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
             if (alloc_l[qq] >= share || ovf_l[qq] != 0) queue_l[atomicAdd(ctl + kCtlCount, 1)] = qq;
         __syncthreads();
         const int nq = ctl[kCtlCount];
-        if (wave == 0) { PK_STAT(0, 1); PK_STAT(1, nq); }
-        const unsigned long long tf0 = PK_CLOCK();
         for (int e = wave; e < nq; e += kPkWaves) {
             const int q = __builtin_amdgcn_readfirstlane(queue_l[e]);
             const int r = wg_row0 + q;
@@ -409,7 +409,6 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
                     half ^= 1;
                 }
                 ++item;
-                if (n_c > 0) { PK_STAT(item == 1 ? 2 : 3, n_c); }
                 if (n_c > 0)
                     t_bits = flush_query_exact<ALIGNED, 8, true>(a.Q + (int64_t)r * a.ldq, a.X, a.ldx, a.d,
                                                            a.j_valid, cbuf, jb, n_c, a.lk + lb, a.li + lb,
@@ -424,7 +423,6 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
                                    __HIP_MEMORY_SCOPE_AGENT);
             }
         }
-        PK_STAT(8, PK_CLOCK() - tf0);
         __syncthreads();
         if (tid == 0) ctl[kCtlCount] = 0;
         for (int qq = tid; qq < Qw; qq += NT)
@@ -440,7 +438,6 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
     bool have = step < step_hi;
     loadA(have ? step : step_any);
     spread_xn(a.xn[(size_t)(have ? step : step_any) * kPkStep + lane]);
-    const unsigned long long tk0 = PK_CLOCK();
     int parity = 0;
     bool announced = false;
     float xn_next = 0.f;
@@ -469,30 +466,16 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
             if (lane == 0) atomicAdd(ctl + kCtlDone, 1);
             announced = true;
         }
-        const unsigned long long ts0 = PK_CLOCK();
         __syncthreads();
-        const unsigned long long ts1 = PK_CLOCK();
         const bool all_done = ctl[kCtlDone] == kPkWaves;
         stop_work(all_done);
-        if (wave == 0) { PK_STAT(6, ts1 - ts0); PK_STAT(4, PK_CLOCK() - ts0); if (announced) { PK_STAT(10, ts1 - ts0); PK_STAT(11, 1); } }
-        if (wave == 5) { PK_STAT(12, ts1 - ts0); if (announced) { PK_STAT(13, ts1 - ts0); } }
         if (all_done) break;
         loadA(have ? step : step_any);
         spread_xn(have ? xn_next : 0.f);
     }
-    if (wave == 0) { PK_STAT(5, PK_CLOCK() - tk0); PK_STAT(9, 1); }
-#ifdef KNN_PK_STATS
-    __syncthreads();
-    if (a.stats && tid < 16) atomicAdd(a.stats + tid, (unsigned long long)ctl[32 + tid]);
-#endif
 }
 
 }  // namespace
-
-#ifdef KNN_PK_STATS
-static unsigned long long* g_pk_stats = nullptr;
-extern "C" void knn_debug_set_stats(void* p) { g_pk_stats = static_cast<unsigned long long*>(p); }
-#endif
 
 hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, int64_t j_first,
                                 int64_t points, void* xp, hipStream_t stream) {
@@ -563,9 +546,6 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
     a.range_steps = per;
     a.init_from = init_from;
     a.j_valid = (int)j_first;
-#ifdef KNN_PK_STATS
-    a.stats = g_pk_stats;
-#endif
     const size_t lds = (size_t)pk_lds_bytes(nch, k, sets);
     const dim3 grid((unsigned)(a.tiles * S));
 #define KNN_PACKED_LAUNCH(N)                                                                   \
