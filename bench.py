@@ -404,9 +404,7 @@ def knn_record(w, limit, steps, warmup, cpu_seconds, peaks, default_shape, host_
     # roofline of the dominant kernel, per launch
     avg_launch_s = (search_ms / max(launches, 1)) * 1e-3
     launches_per_step = max(launches, 1) / steps
-    # pairs one launch of the dominant kernel covers (path 6: the warm-up points are another kernel's)
-    n_main = w.n - plan.warm_points if plan.path == K.KNN_PATH_MFMA_PACKED else w.n
-    pairs_per_launch = float(w.m) * float(n_main) / launches_per_step
+    pairs_per_launch = float(w.m) * float(w.n) / launches_per_step
     hbm_equiv = (pairs_per_launch / avg_launch_s) * 8.0 / (PEAK_HBM_GBS * 1e9)
     if plan.path in (K.KNN_PATH_MFMA_SPLIT, K.KNN_PATH_MFMA_PACKED):
         # The -2 Q X^T contraction of the filter runs on bf16 roundings of the values: 2 d bf16
@@ -552,7 +550,7 @@ def knn_record(w, limit, steps, warmup, cpu_seconds, peaks, default_shape, host_
         "config": {"workload": w.name, "metric": w.metric, "m": w.m, "n": w.n, "d": w.d, "k": w.k,
                    "mem_limit_bytes": limit, "workspace_bytes": plan.workspace_bytes,
                    "q_chunks": plan.q_chunks, "point_ranges": plan.n_splits,
-                   "queries_per_workgroup": plan.tile_q, "warm_points": plan.warm_points,
+                   "queries_per_workgroup": plan.tile_q, "seed_points": plan.seed_points,
                    "path": path_name},
         "kernel_ms_per_step": {"preparation": prep_ms / steps, "search": search_ms / steps,
                                "merge_refine": refine_ms / steps},

@@ -75,7 +75,7 @@ typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1, KNN_METRIC_L1 = 2 } k
                                   points rounded to bf16 (32 bytes per point and 16 coordinates):
                                   the filter of path 5 with the queries resident in LDS and the
                                   points read from that copy in matrix-core operand order; the
-                                  first points of X go through path 5's kernel to warm the lists.
+                                  lists start under thresholds found from a sample's filter keys.
                                   Same exact test, same keys, same results as path 5. */
 
 /*
@@ -97,8 +97,8 @@ typedef struct {
     int32_t streams;     /* HIP streams used.  1: the caller's.  2 (more than one query chunk and
                             room for two sets of lists): merge and exact re-evaluation of a
                             chunk run on an internal stream while the next chunk is searched */
-    int32_t warm_points; /* path 6: the first warm_points points go through path 5's kernel (they
-                            warm the lists), the packed kernel takes the rest; else 0 */
+    int32_t seed_points; /* path 6: every query's first threshold comes from the filter keys of
+                            this many points spread over X (no exact evaluation); else 0 */
     int32_t metric;      /* knn_metric                                          */
     int32_t seed_cells;  /* path 4, d <= 3: cells per axis of the grid the points are sorted
                             into to give every list a finite starting threshold (up to k = 32

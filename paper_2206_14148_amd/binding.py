@@ -98,7 +98,7 @@ class PlanStruct(ctypes.Structure):
         ("path", ctypes.c_int32), ("tile_q", ctypes.c_int32),
         ("tile_x", ctypes.c_int32), ("n_splits", ctypes.c_int32),
         ("chunk_rows", ctypes.c_int64), ("q_chunks", ctypes.c_int64),
-        ("streams", ctypes.c_int32), ("warm_points", ctypes.c_int32),
+        ("streams", ctypes.c_int32), ("seed_points", ctypes.c_int32),
         ("metric", ctypes.c_int32), ("seed_cells", ctypes.c_int32),
         ("norms_bytes", ctypes.c_uint64), ("query_bytes", ctypes.c_uint64),
         ("lists_bytes", ctypes.c_uint64),
@@ -149,7 +149,7 @@ class Plan:
     chunk_rows: int
     q_chunks: int
     streams: int
-    warm_points: int
+    seed_points: int
     metric: int
     seed_cells: int
     norms_bytes: int
@@ -241,7 +241,7 @@ def knn_status_string(status: int) -> str:
 
 def _plan_from_struct(ps: PlanStruct) -> Plan:
     return Plan(ps.m, ps.n, ps.d, ps.k, ps.path, ps.tile_q, ps.tile_x, ps.n_splits,
-                ps.chunk_rows, ps.q_chunks, ps.streams, ps.warm_points, ps.metric, ps.seed_cells,
+                ps.chunk_rows, ps.q_chunks, ps.streams, ps.seed_points, ps.metric, ps.seed_cells,
                 ps.norms_bytes, ps.query_bytes, ps.lists_bytes,
                 ps.workspace_bytes, ps.min_limit_bytes, ps.private_bytes)
 

@@ -191,7 +191,6 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     unsigned char* xp = hdr + kAlign;  // path 6: the points rounded to bf16
     // path 6 needs 16-byte aligned rows; other calls run its plan on path 5's kernel
     const bool packed = packed_plan && packed_rows_aligned(Q, ldq, X, ldx, d);
-    const int64_t warm = plan.warm_points;
     unsigned char* qs = ws + plan.norms_bytes;
     float* qn = reinterpret_cast<float*>(
         qs + align_up((uint64_t)plan.chunk_rows * 32 * (((uint64_t)d + kSpKC - 1) / kSpKC)));
@@ -220,7 +219,7 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
         if (e == hipSuccess) e = launch_max_norm(xn, n, hdr, stream);
         if (e == hipSuccess && packed) e = launch_pad_norms(xn, n, stream);
         if (e == hipSuccess && packed)
-            e = launch_pack_operands(X, ldx, n, d, warm, (int64_t)n64 - warm, xp, stream);
+            e = launch_pack_operands(X, ldx, n, d, 0, (int64_t)n64, xp, stream);
         if (e != hipSuccess) {
             drop_bracket(t0);
             return hip_fail(e, "row norms launch");
@@ -264,19 +263,18 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
             if (e == hipSuccess && !packed)
                 e = launch_split(Qc, ldq, X, ldx, qs, qn, tsh, xn, hdr, cosine, rows, n, d, k, S, lk,
                                  li, stream);
-            // path 6: the first points warm the list of range 0 on path 5's kernel (one range: the
-            // fewest pairs to evaluate), the rest follow out of the packed copy in S ranges.  The
-            // warm-up counts as preparation in the event brackets, the packed kernel as the search.
+            // path 6: the thresholds start from the filter keys of a sample (preparation in the
+            // event brackets), then the packed kernel searches all points in S ranges
             if (e == hipSuccess && packed)
-                e = launch_split(Qc, ldq, X, ldx, qs, qn, tsh, xn, hdr, false, rows, warm, d, k, 1, lk,
-                                 li, stream, S);
+                e = launch_seed_thresholds(Qc, ldq, xp, xn, qs, qn, tsh, hdr, rows, n, d, k, plan.seed_points,
+                                           stream);
             if (e == hipSuccess && packed)
                 e = launch_fill_words(tsr, rows * S, 0xff800000u, stream);
             if (e == hipSuccess && packed) {
                 close_bracket(t1, stream, 0);
                 t1 = mark(stream);
-                e = launch_packed(Qc, ldq, X, ldx, xp, warm, qs, qn, tsh, tsr, xn, hdr, rows, n, d, k, S,
-                                  plan.tile_q / 32, warm, n, 1, lk, li, stream);
+                e = launch_packed(Qc, ldq, X, ldx, xp, 0, qs, qn, tsh, tsr, xn, hdr, rows, n, d, k, S,
+                                  plan.tile_q / 32, 0, n, 0, lk, li, stream);
             }
         } else
             e = hipErrorInvalidValue;  // no such path

@@ -61,8 +61,7 @@ constexpr int kPkCand = 32;              // buffered point indices per query (LD
 constexpr int kPkShareMin = 12;          // a stop empties every buffer with at least this many entries
 constexpr int kPkRoom = 8;               // a buffer with fewer free slots than this calls a stop
 constexpr int kPkLdsBytes = 160 * 1024;  // LDS of a gfx950 compute unit
-constexpr int kPkWarmPerK = 64;          // the first max(4096, this * k) points go through knn_split_kernel
-constexpr int kPkWarmMin = 4096;
+constexpr int kPkSeedMin = 8192;         // sample of max(this, 8 k) points for the first thresholds
 constexpr int64_t kPkMinPoints = 65536;  // fewer points: not worth packing
 // the chunk counts the kernel is instantiated for (2 .. 8 and the even ones up to 16); others are
 // padded up with zero operands
@@ -86,10 +85,10 @@ constexpr inline int pk_max_sets(int nch_padded, int k) {
     while (sets < kPkMaxSets && pk_lds_bytes(nch_padded, k, sets + 1) <= kPkLdsBytes) ++sets;
     return sets;
 }
-// points that go through the warm-up search before the packed kernel takes over
-constexpr inline int64_t pk_warm_points(int k) {
-    const int64_t w = (int64_t)kPkWarmPerK * k;
-    return ((w > kPkWarmMin ? w : kPkWarmMin) + 127) / 128 * 128;
+// points whose filter keys give every query its first threshold on path 6 (knn_seed_kernel)
+constexpr inline int64_t pk_seed_points(int k) {
+    const int64_t w = 8 * (int64_t)k;
+    return ((w > kPkSeedMin ? w : kPkSeedMin) + kPkStep - 1) / kPkStep * kPkStep;
 }
 
 // Workgroups the chip holds at once (LDS-limited): the planner sizes launches in rounds of these.

@@ -53,9 +53,7 @@ hipError_t launch_lowd_bf16(const float* Q, int64_t ldq, const float* X, int64_t
 //                        (reset_thresholds false) kept from an earlier search of other points
 //                        for the same queries and the same k
 //   launch_split         the search; qn = squared norms of the chunk's queries (fp32, [rows]);
-//                        cosine: xn holds 1 / |x| and the keys are -2 q.x / |x|;
-//                        list_S > S: the lists of a row are list_S * k entries apart (the S
-//                        ranges fill the first S of them, the others are not touched)
+//                        cosine: xn holds 1 / |x| and the keys are -2 q.x / |x|
 hipError_t launch_header_init(void* hdr, hipStream_t stream);
 hipError_t launch_max_norm(const float* xn, int64_t n, void* hdr, hipStream_t stream);
 hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d, void* qs,
@@ -63,7 +61,7 @@ hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d
 hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* qs,
                         const float* qn, void* tsh, const float* xn, const void* hdr, bool cosine,
                         int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
-                        hipStream_t stream, int list_S = 0);
+                        hipStream_t stream);
 
 // 16 < d <= 256 with the points rounded to bf16 in the workspace (knn_packed.hip).
 //   launch_pack_operands  xp = `points` points from j_first on (j_first and points multiples of
@@ -73,14 +71,21 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
 //                         the copy xp whose first point is slab_first, for queries whose B
 //                         operands, norms and shared thresholds are those of launch_split;
 //                         sets = query sets of 32 per workgroup (<= pk_max_sets); the lists of
-//                         ranges < init_from continue (launch_split filled them from other
-//                         points), the others start empty; tsr = [rows][S] words, set to
+//                         ranges < init_from continue (an earlier launch filled them from
+//                         other points), the others start empty; tsr = [rows][S] words, set to
 //                         0xff800000 (+inf) beforehand: the key at position ceil(k / S) - 1 of
 //                         every range's list, through which the ranges bound each other.
 //                         Rows must be 16-byte aligned (packed_rows_aligned).
 hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, int64_t j_first,
                                 int64_t points, void* xp, hipStream_t stream);
 hipError_t launch_pad_norms(float* xn, int64_t n, hipStream_t stream);
+//   launch_seed_thresholds  tsh[r] = min(tsh[r], an upper bound of query r's k-th smallest distance
+//                         found from the filter keys of seed_points points spread over the packed
+//                         copy xp (of all n points)); after launch_split_queries, the queries'
+//                         norms and the header
+hipError_t launch_seed_thresholds(const float* Q, int64_t ldq, const void* xp, const float* xn, const void* qs,
+                                  const float* qn, void* tsh, const void* hdr, int64_t rows, int64_t n, int d,
+                                  int k, int64_t seed_points, hipStream_t stream);
 bool packed_rows_aligned(const float* Q, int64_t ldq, const float* X, int64_t ldx, int d);
 hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* xp,
                          int64_t slab_first, const void* qs, const float* qn, void* tsh, void* tsr,

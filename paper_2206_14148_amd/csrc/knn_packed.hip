@@ -20,9 +20,9 @@
 // dealt out over the waves, evaluated exactly and merged into their lists, and a (wave, query,
 // step) that found no room is made good by testing all 64 points of that step.
 //
-// The lists are warm when this kernel starts: the first pk_warm_points(k) points of X went
-// through knn_split_kernel, whose k-th keys bound every query's threshold from the first step on
-// (a list that starts from +inf would accept everything and spend its time in the stops).
+// The thresholds are finite when this kernel starts: knn_seed_kernel has bounded every query's
+// k-th distance from the filter keys of a sample of the points (a list that starts from +inf
+// would accept everything and spend its time in the stops).
 #include <hip/hip_runtime.h>
 
 #include <climits>
@@ -71,6 +71,159 @@ __global__ void knn_pad_norms_kernel(float* __restrict__ xn, int n, int n_pad) {
 }
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// A first threshold for every query from FILTER keys alone.  The filter key f of a pair and its
+// exact key dd differ by at most the filter's allowance (in either direction), so if t is such
+// that at least k points of a sample have f <= t, at least k points have dd <= t + qn + allowance:
+// an upper bound of the query's k-th smallest distance, as valid a starting threshold as +inf and
+// far tighter - without evaluating a single pair exactly.  (Lists that start from +inf accept
+// every pair until they hold k entries; with eight waves feeding one buffer that phase would be
+// spent in stops.)  The sample is `sample_steps` steps of 64 points spread evenly over the packed
+// copy.  One wave per 64 queries, B operands in registers; a first pass finds the lane's lowest
+// and highest filter key, then kSeedIters passes quarter the interval [lo, hi] keeping
+// count(f <= hi) >= k.  The bound goes into tsh (atomic minimum on the order-preserving word).
+constexpr int kSeedIters = 6;
+constexpr int kSeedSets = 2;  // sets of 32 queries per wave: one fetch of a step's operands serves both
+template <int NCH>
+__global__ __launch_bounds__(256) void knn_seed_kernel(const uint4* __restrict__ Xp, const float* __restrict__ xn,
+                                                       const uint4* __restrict__ Qs,
+                                                       const float* __restrict__ qnorm,
+                                                       const unsigned* __restrict__ hdr,
+                                                       const float* __restrict__ Q, int64_t ldq,
+                                                       unsigned* __restrict__ tsh, int rows, int d,
+                                                       int nch_real, int k, int nsteps, int sample_steps) {
+    const int lane = threadIdx.x & 63;
+    const int i32 = lane & 31, h = lane >> 5;
+    const int row0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * (32 * kSeedSets);
+    if (row0 >= rows) return;  // whole wave; no workgroup barrier below
+    uint4 bq[kSeedSets][NCH];
+#pragma unroll
+    for (int t = 0; t < kSeedSets; ++t) {
+        const int rc = min(row0 + 32 * t + i32, rows - 1);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const uint4 zero = {0u, 0u, 0u, 0u};
+            bq[t][c] = c < nch_real ? Qs[((size_t)rc * nch_real + c) * 2 + h] : zero;
+        }
+    }
+    // keys of one step: acc[t][pb] = query set t against row block pb (as in the search loop of
+    // knn_packed_kernel)
+    auto keys = [&](int step, f32x16 (&acc)[kSeedSets][2]) {
+        const u32x4* p = reinterpret_cast<const u32x4*>(Xp) + (size_t)step * (2 * NCH * 64) + lane;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 t0 = *reinterpret_cast<const f32x4*>(xn + (size_t)step * kPkStep + g * 8 + h * 4);
+            const f32x4 t1 = *reinterpret_cast<const f32x4*>(xn + (size_t)step * kPkStep + 32 + g * 8 + h * 4);
+#pragma unroll
+            for (int t = 0; t < kSeedSets; ++t)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc[t][0][g * 4 + e] = t0[e];
+                    acc[t][1][g * 4 + e] = t1[e];
+                }
+        }
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const bf16x8 x0 = __builtin_bit_cast(bf16x8, p[c * 64]);
+            const bf16x8 x1 = __builtin_bit_cast(bf16x8, p[(NCH + c) * 64]);
+#pragma unroll
+            for (int t = 0; t < kSeedSets; ++t) {
+                const bf16x8 b = __builtin_bit_cast(bf16x8, bq[t][c]);
+                acc[t][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0, b, acc[t][0], 0, 0, 0);
+                acc[t][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1, b, acc[t][1], 0, 0, 0);
+            }
+        }
+    };
+    auto step_of = [&](int i) { return (int)((int64_t)i * nsteps / sample_steps); };
+    float lo[kSeedSets], hi[kSeedSets];
+#pragma unroll
+    for (int t = 0; t < kSeedSets; ++t) {
+        lo[t] = kInf;
+        hi[t] = -kInf;
+    }
+    for (int i = 0; i < sample_steps; ++i) {
+        f32x16 acc[kSeedSets][2];
+        keys(step_of(i), acc);
+#pragma unroll
+        for (int t = 0; t < kSeedSets; ++t)
+#pragma unroll
+            for (int pb = 0; pb < 2; ++pb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float v = acc[t][pb][e];
+                    lo[t] = fminf(lo[t], v);
+                    hi[t] = fmaxf(hi[t], v < kInf ? v : -kInf);  // (rows past n carry +inf: no points)
+                }
+    }
+#pragma unroll
+    for (int t = 0; t < kSeedSets; ++t) {
+        lo[t] = fminf(lo[t], lane_xor<32>(lo[t]));
+        hi[t] = fmaxf(hi[t], lane_xor<32>(hi[t]));
+    }
+    // (three thresholds a pass, the quartiles of the interval: two bits of the answer for one
+    // walk over the sample, which is what a pass costs - the operands come out of the L2 again)
+    for (int it = 0; it < kSeedIters; ++it) {
+        float q1[kSeedSets], q2[kSeedSets], q3[kSeedSets];
+        int c1[kSeedSets], c2[kSeedSets], c3[kSeedSets];
+#pragma unroll
+        for (int t = 0; t < kSeedSets; ++t) {
+            q1[t] = lo[t] + 0.25f * (hi[t] - lo[t]);
+            q2[t] = lo[t] + 0.5f * (hi[t] - lo[t]);
+            q3[t] = lo[t] + 0.75f * (hi[t] - lo[t]);
+            c1[t] = c2[t] = c3[t] = 0;
+        }
+        for (int i = 0; i < sample_steps; ++i) {
+            f32x16 acc[kSeedSets][2];
+            keys(step_of(i), acc);
+#pragma unroll
+            for (int t = 0; t < kSeedSets; ++t)
+#pragma unroll
+                for (int pb = 0; pb < 2; ++pb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const float v = acc[t][pb][e];
+                        c1[t] += (v <= q1[t]) ? 1 : 0;
+                        c2[t] += (v <= q2[t]) ? 1 : 0;
+                        c3[t] += (v <= q3[t]) ? 1 : 0;
+                    }
+        }
+#pragma unroll
+        for (int t = 0; t < kSeedSets; ++t) {
+            c1[t] += lane_xor<32>(c1[t]);
+            c2[t] += lane_xor<32>(c2[t]);
+            c3[t] += lane_xor<32>(c3[t]);
+            // the lowest quarter whose upper end still has k keys at or below it
+            if (c1[t] >= k) hi[t] = q1[t];
+            else if (c2[t] >= k) { lo[t] = q1[t]; hi[t] = q2[t]; }
+            else if (c3[t] >= k) { lo[t] = q2[t]; hi[t] = q3[t]; }
+            else lo[t] = q3[t];
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < kSeedSets; ++t) {
+        const int r = row0 + 32 * t + i32;
+        if (r < rows && h == 0) {
+            // the allowance of knn_packed_kernel's filter (see there), with the bound itself in
+            // place of tau in the rounding term and that term doubled
+            const float xmax = __uint_as_float(hdr[0]);
+            const float rxm = sqrtf(__uint_as_float(hdr[1]));
+            const float qn = qnorm[r];
+            float rq2 = 0.f;
+            const float* qrow = Q + (int64_t)r * ldq;
+            for (int u = 0; u < d; ++u) {
+                const float res = bf16_residual(-2.f * qrow[u]);
+                rq2 = fmaf(res, res, rq2);
+            }
+            const float e_acc = (float)(4 * (NCH * 16) + 32) * 0x1p-24f;
+            const float e_sum = (float)(d + 16) * 0x1p-23f;
+            const float cross = 1.01f * ((sqrtf(xmax) + rxm) * sqrtf(rq2) + rxm * 2.f * sqrtf(qn)) +
+                                e_acc * sqrtf(xmax * qn);
+            const float base = hi[t] + qn;
+            const float bound = base + (cross + 2.f * e_sum * (xmax + qn + fabsf(base) + cross) + 0x1p-126f);
+            atomicMin(tsh + r, key_word(bound));
+        }
+    }
+}
 
 struct PkArgs {
     const float* Q;
@@ -489,6 +642,39 @@ hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, i
     else
         knn_pack_operands_kernel<false><<<grid, dim3(256), 0, stream>>>(X, ldx, (int)n, d, nch, (int)j_first,
                                                                         pieces, static_cast<uint4*>(xp));
+    return hipGetLastError();
+}
+
+hipError_t launch_seed_thresholds(const float* Q, int64_t ldq, const void* xp, const float* xn, const void* qs,
+                                  const float* qn, void* tsh, const void* hdr, int64_t rows, int64_t n, int d,
+                                  int k, int64_t seed_points, hipStream_t stream) {
+    const int nch_real = (d + kSpKC - 1) / kSpKC;
+    const int nch = pk_padded_chunks(d);
+    const int nsteps = (int)((n + kPkStep - 1) / kPkStep);
+    int sample_steps = (int)(seed_points / kPkStep);
+    if (sample_steps > nsteps) sample_steps = nsteps;
+    if (sample_steps < 1 || (int64_t)sample_steps * kPkStep < k) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((rows + 4 * 32 * kSeedSets - 1) / (4 * 32 * kSeedSets)));
+#define KNN_SEED_LAUNCH(N)                                                                          \
+    knn_seed_kernel<N><<<grid, dim3(256), 0, stream>>>(                                             \
+        static_cast<const uint4*>(xp), xn, static_cast<const uint4*>(qs), qn,                       \
+        static_cast<const unsigned*>(hdr), Q, ldq, static_cast<unsigned*>(tsh), (int)rows, d, nch_real, k, \
+        nsteps, sample_steps)
+    switch (nch) {
+        case 2: KNN_SEED_LAUNCH(2); break;
+        case 3: KNN_SEED_LAUNCH(3); break;
+        case 4: KNN_SEED_LAUNCH(4); break;
+        case 5: KNN_SEED_LAUNCH(5); break;
+        case 6: KNN_SEED_LAUNCH(6); break;
+        case 7: KNN_SEED_LAUNCH(7); break;
+        case 8: KNN_SEED_LAUNCH(8); break;
+        case 10: KNN_SEED_LAUNCH(10); break;
+        case 12: KNN_SEED_LAUNCH(12); break;
+        case 14: KNN_SEED_LAUNCH(14); break;
+        case 16: KNN_SEED_LAUNCH(16); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef KNN_SEED_LAUNCH
     return hipGetLastError();
 }
 

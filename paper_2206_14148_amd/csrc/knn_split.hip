@@ -115,7 +115,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     const float* __restrict__ Q, int64_t ldq, const float* __restrict__ X, int64_t ldx,
     const uint4* __restrict__ Qs, const float* __restrict__ qnorm, unsigned* tsh,
     const float* __restrict__ xn, const unsigned* __restrict__ hdr, int cosine, int rows, int n,
-    int d, int nch_real, int k, int S, int LS, int split_len, int BQ, int BS, float* __restrict__ lk,
+    int d, int nch_real, int k, int S, int split_len, int BQ, int BS, float* __restrict__ lk,
     int* __restrict__ li) {
     // steps per tile that the pipeline walks, W chunks of 16 coordinates each (the chunks past
     // the real count meet zero B operands)
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     if (!xcd_block_map(rows, TQ, S, BQ, BS, s, wg_row0)) return;  // padding (before any barrier)
     const int wave_row0 = wg_row0 + wave * 32;
     int* wci = ci + wave * 32 * C;
-    init_lists32(lk, li, wave_row0, rows, LS, s, k, lane);
+    init_lists32(lk, li, wave_row0, rows, S, s, k, lane);
 
     const float xmax = __uint_as_float(hdr[0]);
     // Filter keys are  xn_j + bf16(x).bf16(-2 q)  accumulated in fp32; the exact test gives
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
     // jbase ..), merged into its list; the lanes of the query get the new thresholds
     auto flush_one = [&](int L, bool from_range, int jbase, int cc) {
         const int r = wave_row0 + L;
-        const size_t lb = ((size_t)r * LS + s) * k;
+        const size_t lb = ((size_t)r * S + s) * k;
         const unsigned fr = split_flush_query<ALIGNED>(
             Q + (int64_t)r * ldq, X, ldx, d, j0, from_range ? nullptr : wci + L * C, jbase, cc,
             lk + lb, li + lb, k, my_scratch, tsh + r, cosine ? xn : nullptr, lane);
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
         for (int e = wave; e < nq; e += kSpWaves) {
             const int q = co_queue[e];
             const int r = wg_row0 + q;
-            const size_t lb = ((size_t)r * LS + s) * k;
+            const size_t lb = ((size_t)r * S + s) * k;
             const unsigned fr = split_flush_query<ALIGNED>(
                 Q + (int64_t)r * ldq, X, ldx, d, j0, ci + q * C, 0, co_cnt[q], lk + lb, li + lb, k,
                 my_scratch, tsh + r, cosine ? xn : nullptr, lane);
@@ -542,7 +542,7 @@ hipError_t launch_split_queries(const float* Q, int64_t ldq, int64_t rows, int d
 hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* qs,
                         const float* qn, void* tsh, const float* xn, const void* hdr, bool cosine,
                         int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
-                        hipStream_t stream, int list_S) {
+                        hipStream_t stream) {
     const int nch = (d + kSpKC - 1) / kSpKC;
     const size_t lds_fixed = (size_t)4 * kSpTileX * 4 + (size_t)kSpTileQ * kSpCand * 4 +
                              (size_t)kSpWaves * (2 * kWave + 2 * k) * 4 +
@@ -568,7 +568,6 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
         knn_split_kernel<W, N, A><<<grid, dim3(64 * kSpWaves), lds, stream>>>(                    \
             Q, ldq, X, ldx, static_cast<const uint4*>(qs), qn, static_cast<unsigned*>(tsh), xn,   \
             static_cast<const unsigned*>(hdr), cosine ? 1 : 0, (int)rows, (int)n, d, nch, k, S,   \
-            list_S > 0 ? list_S : S,                                                            \
             (int)split_len, BQ, BS, lk, li);                                                      \
     } while (0)
     // W chunks of 16 coordinates per pipeline step, N steps per tile with the queries resident

@@ -228,7 +228,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     // of path 5 plus the packed copy, so a call whose rows turn out not to be 16-byte aligned
     // still runs under this plan, on path 5's kernel.
     if (split && metric == KNN_METRIC_L2SQ && d > kSpKC && d <= kPkMaxD &&
-        n >= kPkMinPoints && n >= 4 * pk_warm_points(k)) {
+        n >= kPkMinPoints && n >= 4 * pk_seed_points(k)) {
         const int nch_p = pk_padded_chunks(d);
         const int sets_max = pk_max_sets(nch_p, k);
         const uint64_t n64 = ((uint64_t)n + kPkStep - 1) / kPkStep * kPkStep;
@@ -246,7 +246,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
             for (int sets = sets_max; sets >= 2 && sets >= sets_max - 6; --sets) {
                 const int64_t tile6 = 32 * sets;
                 for (int64_t S = 1; S <= 32; ++S) {
-                    if ((n - pk_warm_points(k)) / S < 8 * kPkStep * 16) break;  // ranges of >= 16 rounds of the waves
+                    if (n / S < 8 * kPkStep * 16) break;  // ranges of >= 16 rounds of the waves
                     int64_t rows = rows_fitting(avail6, (uint64_t)S, (uint64_t)k, qrow, 3);
                     if (rows > kMaxChunkRows) rows = kMaxChunkRows;
                     if (rows >= m) rows = m;
@@ -271,7 +271,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
             }
             if (best_sets != 0) {
                 out->path = KNN_PATH_MFMA_PACKED;
-                out->warm_points = (int32_t)pk_warm_points(k);
+                out->seed_points = (int32_t)pk_seed_points(k);
                 out->tile_q = 32 * best_sets;
                 out->tile_x = kPkStep;
                 out->norms_bytes = per_point;

@@ -190,7 +190,7 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
     # paths 5 and 6 (d > 8, squared-Euclidean): per query 32 bytes per 16 coordinates of bf16 B
     # operands, a squared norm and a shared-threshold word, each array 256-aligned; the chunk is
     # the longest multiple of the query tile that fits with them.  Path 6 (16 < d <= 256, at least
-    # 65536 points and four times its warm-up length) adds the points rounded to bf16, 32 bytes
+    # 65536 points and four times the sample its first thresholds come from) adds the points rounded to bf16, 32 bytes
     # per point and 16 coordinates (the chunk count padded to an even one above 8), and pads the
     # norms to a multiple of 64 points; its query tile is 32 x the query sets of a workgroup.
     import random
@@ -211,8 +211,8 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
         nch = (d + 15) // 16
         seen.add(p.path)
         if p.path == K.KNN_PATH_MFMA_PACKED:
-            warm = (max(4096, 64 * k) + 127) // 128 * 128
-            assert 16 < d <= 256 and n >= 65536 and n >= 4 * warm
+            seed = (max(8192, 8 * k) + 63) // 64 * 64
+            assert 16 < d <= 256 and n >= 65536 and n >= 4 * seed and p.seed_points == seed
             nch_p = nch if nch <= 8 else (nch + 1) // 2 * 2
             waves = 8 if nch_p <= 8 else 4  # above 8 chunks: four waves of up to 512 registers
             n64 = (n + 63) // 64 * 64
