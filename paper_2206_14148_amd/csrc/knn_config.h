@@ -58,8 +58,9 @@ constexpr int kPkStep = 64;              // points per wave step (two MFMA row b
 constexpr int kPkMaxD = 256;
 constexpr int kPkMaxSets = 16;           // 512 queries: one thread per query in the stops
 constexpr int kPkCand = 32;              // buffered point indices per query (LDS)
-constexpr int kPkShareMin = 12;          // a stop empties every buffer with at least this many entries
-constexpr int kPkRoom = 8;               // a buffer with fewer free slots than this calls a stop
+constexpr int kPkShareMin = 20;          // a stop empties every buffer with at least this many entries
+constexpr int kPkRoom = 4;               // a buffer with fewer free slots than this calls a stop
+// (swept at d = 128, k = 100: 12 / 8 250.6 ms, 16 / 8 247.9, 16 / 4 248.0, 20 / 4 245.1, 24 / 4 246.3, 8 / 8 257.5)
 constexpr int kPkLdsBytes = 160 * 1024;  // LDS of a gfx950 compute unit
 constexpr int kPkSeedMin = 8192;         // sample of max(this, 8 k) points for the first thresholds
 constexpr int64_t kPkMinPoints = 65536;  // fewer points: not worth packing
