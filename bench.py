@@ -36,17 +36,17 @@ PEAK_HBM_GBS = 8000.0
 # a workload on the kernel named; a run with other sizes, another limit or another kernel reports
 # null.  {workload: (kernel, bytes, profile)}
 PROFILED_TRAFFIC = {
-    "c1_random_d16": ("knn_split_kernel", 11.4e6, "profiles/knn_split_kernel_c1.md"),
-    "c2_pointcloud_d3": ("knn_lowd_bf16_kernel", 212.9e9, "profiles/knn_lowd_bf16_kernel_c2.md"),
-    "c3_imagelike_d784": ("knn_split_kernel", 167.0e9, "profiles/knn_split_kernel_c3.md"),
-    "c4_clustered_d128": ("knn_packed_kernel", 542.2e9, "profiles/knn_packed_kernel_c4.md"),
-    "c5_memsweep_d256": ("knn_split_kernel", 349.1e9, "profiles/knn_split_kernel_c5.md"),
-    "c6_cosine_d100": ("knn_split_kernel", 15.75e9, "profiles/knn_split_kernel_c6.md"),
-    "c7_l1_d100": ("knn_l1_kernel", 27.46e9, "profiles/knn_l1_kernel_c7.md"),
+    "c1_random_d16": ("knn_split_kernel", 12.3e6, "profiles/knn_split_kernel_c1.md"),
+    "c2_pointcloud_d3": ("knn_lowd_bf16_kernel", 211.4e9, "profiles/knn_lowd_bf16_kernel_c2.md"),
+    "c3_imagelike_d784": ("knn_split_kernel", 158.2e9, "profiles/knn_split_kernel_c3.md"),
+    "c4_clustered_d128": ("knn_packed_kernel", 492.7e9, "profiles/knn_packed_kernel_c4.md"),
+    "c5_memsweep_d256": ("knn_split_kernel", 342.0e9, "profiles/knn_split_kernel_c5.md"),
+    "c6_cosine_d100": ("knn_split_kernel", 15.69e9, "profiles/knn_split_kernel_c6.md"),
+    "c7_l1_d100": ("knn_l1_kernel", 25.8e9, "profiles/knn_l1_kernel_c7.md"),
     "kmv1_d1": ("kmv_lowd_kernel", 1.84e9, "profiles/kmv_lowd_kernel_kmv1.md"),
     "kmv2_d32": ("kmv_mfma_kernel", 1.47e9, "profiles/kmv_mfma_kernel_kmv2.md"),
     "kmv3_d1_f64": ("kmv_lowd_f64_kernel", 4.02e9, "profiles/kmv_lowd_f64_kernel_kmv3.md"),
-    "sgpr1_road_d3_m10000": ("sgpr_syrk_kernel", 8.96e9, "profiles/sgpr_syrk_kernel_sgpr1.md"),
+    "sgpr1_road_d3_m10000": ("sgpr_syrk_kernel", 8.99e9, "profiles/sgpr_syrk_kernel_sgpr1.md"),
 }
 
 
