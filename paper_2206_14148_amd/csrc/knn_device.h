@@ -153,7 +153,9 @@ template <bool HAVE_HEAD>
 __device__ __forceinline__ uint64_t wave_merge_pair_impl(float* __restrict__ gk,
                                                          int* __restrict__ gi, int k, float ckey,
                                                          int cidx, const MergeScratch& sc, int lane,
-                                                         int ncand, const ListHead& head) {
+                                                         int ncand, const ListHead& head, int pos2 = -1,
+                                                         float* key2 = nullptr) {
+    // (pos2 >= 0: *key2 also gets the key that the merged list holds at position pos2 < k)
     // A list is read and written only by the wave that owns its query, so wave-level
     // ordering is enough; wave_sync() also orders this wave's earlier global stores to the
     // list before the loads below (same compute unit, same vector L1).
@@ -181,6 +183,8 @@ __device__ __forceinline__ uint64_t wave_merge_pair_impl(float* __restrict__ gk,
     float tau = kInf;
     int tidx = kNoIdx;
     bool last = false;  // this lane wrote position k-1 (exactly one lane does)
+    float t2 = kInf;
+    bool hit2 = false;  // this lane wrote position pos2 (exactly one lane does)
     // list entries move right by the number of candidates that come before them
     for (int p = lane; p < k; p += kWave) {
         const float ek = sc.list_key[p];
@@ -201,6 +205,10 @@ __device__ __forceinline__ uint64_t wave_merge_pair_impl(float* __restrict__ gk,
                 tidx = ei;
                 last = true;
             }
+            if (pos == pos2) {
+                t2 = ek;
+                hit2 = true;
+            }
         }
     }
     // candidate c lands after the c candidates before it and the list entries <= it
@@ -220,11 +228,16 @@ __device__ __forceinline__ uint64_t wave_merge_pair_impl(float* __restrict__ gk,
                 tidx = cidx;
                 last = true;
             }
+            if (pos == pos2) {
+                t2 = ckey;
+                hit2 = true;
+            }
         }
     }
     const int src = __builtin_ctzll(__builtin_amdgcn_ballot_w64(last) | (1ull << 63));
     tau = __shfl(tau, src);
     tidx = __shfl(tidx, src);
+    if (key2) *key2 = __shfl(t2, __builtin_ctzll(__builtin_amdgcn_ballot_w64(hit2) | (1ull << 63)));
     wave_sync();
     return ((uint64_t)(unsigned)tidx << 32) | __float_as_uint(tau);
 }

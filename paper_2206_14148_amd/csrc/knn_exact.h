@@ -88,7 +88,7 @@ __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, con
 // merged into the query's list gk/gi, the list's k-th key is published in *tshr (atomic
 // minimum on order-preserving words).  rn != null selects the cosine metric: the key of point j
 // is -2 (q . x_j) rn[j] with the dot product summed in the same order.  Returns the list's new
-// k-th key as float bits.
+// k-th key as float bits; with pos2 >= 0, *key2 gets the key at position pos2 of the merged list.
 template <bool ALIGNED, int U, bool HEAD_AHEAD = false>
 __device__ __forceinline__ unsigned flush_query_exact(const float* __restrict__ qp,
                                                    const float* __restrict__ X, int64_t ldx, int d,
@@ -96,7 +96,8 @@ __device__ __forceinline__ unsigned flush_query_exact(const float* __restrict__ 
                                                    int cc,
                                                    float* __restrict__ gk, int* __restrict__ gi, int k,
                                                    float* scratch, unsigned* tshr,
-                                                   const float* __restrict__ rn, int lane) {
+                                                   const float* __restrict__ rn, int lane, int pos2 = -1,
+                                                   float* key2 = nullptr) {
     MergeScratch sc;
     sc.cand_key = scratch;
     sc.cand_idx = reinterpret_cast<int*>(scratch + kWave);
@@ -128,7 +129,7 @@ __device__ __forceinline__ unsigned flush_query_exact(const float* __restrict__ 
         key = kInf;
         id = kNoIdx;
     }
-    const uint64_t mr = wave_merge_pair_impl<HEAD_AHEAD>(gk, gi, k, key, id, sc, lane, cc, head);
+    const uint64_t mr = wave_merge_pair_impl<HEAD_AHEAD>(gk, gi, k, key, id, sc, lane, cc, head, pos2, key2);
     const unsigned t_bits = (unsigned)mr;
     // no value returned: nothing waits for the round trip
     if (lane == 0) atomicMin(tshr, key_word(__uint_as_float(t_bits)));

@@ -538,6 +538,8 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
             const int cc = min(C, __builtin_amdgcn_readfirstlane(alloc_l[q]));
             unsigned rem = (unsigned)__builtin_amdgcn_readfirstlane(ovf_l[q]);
             unsigned t_bits = __float_as_uint(own_l[q]);
+            float key_s = kInf;  // the list's key at position pos_s after the last merge
+            bool merged = false;
             // work items: the buffer, then the two row blocks of every step to make good
             // what the buffer holds of a step that is made good in full is dropped (-1: no pair)
             if (rem != 0 && lane < cc) {
@@ -562,18 +564,21 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
                     half ^= 1;
                 }
                 ++item;
-                if (n_c > 0)
+                if (n_c > 0) {
                     t_bits = flush_query_exact<ALIGNED, 8, true>(a.Q + (int64_t)r * a.ldq, a.X, a.ldx, a.d,
                                                            a.j_valid, cbuf, jb, n_c, a.lk + lb, a.li + lb,
-                                                           k, my_scratch, a.tsh + r, nullptr, lane);
+                                                           k, my_scratch, a.tsh + r, nullptr, lane, pos_s,
+                                                           &key_s);
+                    merged = true;
+                }
             }
             if (lane == 0) {
                 own_l[q] = __uint_as_float(t_bits);
                 alloc_l[q] = 0;
                 ovf_l[q] = 0;
-                // (the merge ends with a wave_sync: the list's new entries are visible here)
-                __hip_atomic_store(a.tsr + (size_t)r * S + s, key_word(a.lk[lb + pos_s]), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+                if (merged)
+                    __hip_atomic_store(a.tsr + (size_t)r * S + s, key_word(key_s), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         __syncthreads();
