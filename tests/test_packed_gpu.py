@@ -1,4 +1,4 @@
-"""GPU parity tests of the packed path (16 < d <= 256, at least 65536 points, room for the points
+"""GPU parity tests of the packed path (16 < d <= 256, at least 2048 queries and 65536 points, room for the points
 rounded to bf16): through the C ABI against the CPU oracle on sampled rows, and bit for bit
 against the split path, which the same call takes under a limit too small for the packed copy.
 """
@@ -61,18 +61,18 @@ def against_oracle(oracle, Q, X, k, idx, dist, rows):
 
 # (seed, m, n, d, k, kind): every instantiated chunk count, ragged query tiles, ragged last step
 CASES = [
-    (1, 1000, 70001, 128, 10, "normal"),     # 8 chunks, n not a multiple of 64
-    (2, 333, 131072, 32, 16, "normal"),      # 2 chunks
-    (3, 700, 90000, 48, 5, "uniform"),       # 3 chunks
-    (4, 513, 80000, 64, 100, "normal"),      # 4 chunks, k = 100
-    (5, 200, 66000, 80, 7, "normal"),        # 5 chunks
-    (6, 1500, 100000, 96, 10, "clustered"),  # 6 chunks
-    (7, 900, 120000, 100, 10, "clustered"),  # 7 chunks, the shape of the embedding rows
-    (8, 400, 70000, 144, 12, "normal"),      # 9 chunks -> 10
-    (9, 400, 70000, 192, 12, "normal"),      # 12 chunks
-    (10, 300, 70000, 200, 9, "normal"),      # 13 chunks -> 14
-    (11, 600, 75000, 256, 32, "normal"),     # 16 chunks
-    (12, 64, 65536, 20, 3, "normal"),        # two query sets only, d % 16 != 0
+    (1, 2500, 70001, 128, 10, "normal"),     # 8 chunks, n not a multiple of 64
+    (2, 2333, 131072, 32, 16, "normal"),     # 2 chunks
+    (3, 2700, 90000, 48, 5, "uniform"),      # 3 chunks
+    (4, 2513, 80000, 64, 100, "normal"),     # 4 chunks, k = 100
+    (5, 2200, 66000, 80, 7, "normal"),       # 5 chunks
+    (6, 3500, 100000, 96, 10, "clustered"),  # 6 chunks
+    (7, 2900, 120000, 100, 10, "clustered"), # 7 chunks, the shape of the embedding rows
+    (8, 2400, 70000, 144, 12, "normal"),     # 9 chunks -> 10
+    (9, 2400, 70000, 192, 12, "normal"),     # 12 chunks
+    (10, 2300, 70000, 200, 9, "normal"),     # 13 chunks -> 14
+    (11, 2600, 75000, 256, 32, "normal"),    # 16 chunks
+    (12, 2048, 65536, 20, 3, "normal"),      # the smallest shape the path takes, d % 16 != 0
 ]
 
 
@@ -107,7 +107,7 @@ def test_packed_worst_order_stream_overflows_the_buffers(K, oracle):
     # brings pairs under every threshold, so the buffers overflow and steps are made good
     say("packed worst-order case")
     rng = np.random.default_rng(77)
-    n, d, m, k = 70000, 32, 300, 8
+    n, d, m, k = 70000, 32, 2300, 8
     X = rng.standard_normal((n, d), dtype=np.float32)
     order = np.argsort(-np.linalg.norm(X, axis=1))
     X = np.ascontiguousarray(X[order])
@@ -115,7 +115,7 @@ def test_packed_worst_order_stream_overflows_the_buffers(K, oracle):
     Xd = torch.from_numpy(X).cuda()
     Qd = torch.from_numpy(Q).cuda()
     idx, dist = both_paths(K, Qd, Xd, k)
-    against_oracle(oracle, Q, X, k, idx, dist, np.arange(0, m, 13))
+    against_oracle(oracle, Q, X, k, idx, dist, np.arange(0, m, 97))
 
 
 def test_packed_ties_go_to_the_lower_index(K):
@@ -123,7 +123,7 @@ def test_packed_ties_go_to_the_lower_index(K):
     # groups of equal distances, which must come out in index order
     say("packed duplicated-points case")
     rng = np.random.default_rng(5)
-    base, d, m, k = 20000, 64, 200, 12
+    base, d, m, k = 20000, 64, 2200, 12
     B = rng.standard_normal((base, d), dtype=np.float32)
     X = np.concatenate([B, B, B, B])
     Q = rng.standard_normal((m, d), dtype=np.float32)
@@ -163,8 +163,8 @@ def test_packed_unaligned_rows_fall_back_to_the_split_kernel(K, oracle):
     # d % 4 != 0: the plan is the packed one, the call runs the split kernel inside its workspace
     say("packed plan, unaligned rows")
     rng = np.random.default_rng(11)
-    n, d, m, k = 70000, 30, 150, 6
+    n, d, m, k = 70000, 30, 2150, 6
     X = rng.standard_normal((n, d), dtype=np.float32)
     Q = rng.standard_normal((m, d), dtype=np.float32)
     idx, dist = both_paths(K, torch.from_numpy(Q).cuda(), torch.from_numpy(X).cuda(), k)
-    against_oracle(oracle, Q, X, k, idx, dist, np.arange(0, m, 7))
+    against_oracle(oracle, Q, X, k, idx, dist, np.arange(0, m, 89))
