@@ -107,7 +107,7 @@ typedef struct {
     uint64_t norms_bytes;     /* workspace: per-point data. path 2: packed points
                                  [x0 x1 x2 |x|^2]; path 5: squared norms (cosine: 1 / norm)
                                  and a 256-byte header; path 6: the same (norms padded to a
-                                 multiple of 64 points) and the points rounded to bf16; path 4: a 256-byte header, 32 bytes
+                                 multiple of 64 points) and slab_points points rounded to bf16; path 4: a 256-byte header, 32 bytes
                                  per point and 16 K slots, and with seed_cells the grid's cell
                                  starts and cursors and the points in cell order (16 bytes each);
                                  paths 0, 3: nothing                                   */
@@ -127,6 +127,10 @@ typedef struct {
                                  planner takes that path only where workspace_bytes +
                                  private_bytes stays within the limit.  Not part of
                                  workspace_bytes: the caller does not allocate it. */
+    int64_t slab_points;      /* path 6: points the bf16 copy holds at a time (n rounded up to 64
+                                 when all of them fit under the limit, else a multiple of 8192:
+                                 the points are then packed and searched slab after slab, the
+                                 lists carrying over); else 0 */
 } knn_plan_t;
 
 /*

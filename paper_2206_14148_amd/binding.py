@@ -103,7 +103,7 @@ class PlanStruct(ctypes.Structure):
         ("norms_bytes", ctypes.c_uint64), ("query_bytes", ctypes.c_uint64),
         ("lists_bytes", ctypes.c_uint64),
         ("workspace_bytes", ctypes.c_uint64), ("min_limit_bytes", ctypes.c_uint64),
-        ("private_bytes", ctypes.c_uint64),
+        ("private_bytes", ctypes.c_uint64), ("slab_points", ctypes.c_int64),
     ]
 
 
@@ -158,6 +158,7 @@ class Plan:
     workspace_bytes: int
     min_limit_bytes: int
     private_bytes: int = 0
+    slab_points: int = 0
 
 
 class KnnError(RuntimeError):
@@ -243,7 +244,7 @@ def _plan_from_struct(ps: PlanStruct) -> Plan:
     return Plan(ps.m, ps.n, ps.d, ps.k, ps.path, ps.tile_q, ps.tile_x, ps.n_splits,
                 ps.chunk_rows, ps.q_chunks, ps.streams, ps.seed_points, ps.metric, ps.seed_cells,
                 ps.norms_bytes, ps.query_bytes, ps.lists_bytes,
-                ps.workspace_bytes, ps.min_limit_bytes, ps.private_bytes)
+                ps.workspace_bytes, ps.min_limit_bytes, ps.private_bytes, ps.slab_points)
 
 
 def knn_plan(m: int, n: int, d: int, k: int, mem_limit_bytes: int, metric: str = "l2") -> Plan:

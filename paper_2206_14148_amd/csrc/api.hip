@@ -218,7 +218,8 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
             e = launch_row_norms(X, ldx, n, d, cosine, xn, stream, cosine ? nullptr : hdr + 4);
         if (e == hipSuccess) e = launch_max_norm(xn, n, hdr, stream);
         if (e == hipSuccess && packed) e = launch_pad_norms(xn, n, stream);
-        if (e == hipSuccess && packed)
+        // (one slab: the copy is made here, once for all query chunks)
+        if (e == hipSuccess && packed && plan.slab_points >= (int64_t)n64)
             e = launch_pack_operands(X, ldx, n, d, 0, (int64_t)n64, xp, stream);
         if (e != hipSuccess) {
             drop_bracket(t0);
@@ -263,18 +264,34 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
             if (e == hipSuccess && !packed)
                 e = launch_split(Qc, ldq, X, ldx, qs, qn, tsh, xn, hdr, cosine, rows, n, d, k, S, lk,
                                  li, stream);
-            // path 6: the thresholds start from the filter keys of a sample (preparation in the
-            // event brackets), then the packed kernel searches all points in S ranges
-            if (e == hipSuccess && packed)
-                e = launch_seed_thresholds(Qc, ldq, xp, xn, qs, qn, tsh, hdr, rows, n, d, k, plan.seed_points,
-                                           stream);
-            if (e == hipSuccess && packed)
-                e = launch_fill_words(tsr, rows * S, 0xff800000u, stream);
+            // path 6: the thresholds start from the filter keys of a sample of the first slab
+            // (preparation in the event brackets), then the packed kernel searches the points slab
+            // after slab, S ranges each; the lists of slab b + 1 continue those of slab b
             if (e == hipSuccess && packed) {
-                close_bracket(t1, stream, 0);
-                t1 = mark(stream);
-                e = launch_packed(Qc, ldq, X, ldx, xp, 0, qs, qn, tsh, tsr, xn, hdr, rows, n, d, k, S,
-                                  plan.tile_q / 32, 0, n, 0, lk, li, stream);
+                const int64_t slab = plan.slab_points;
+                const bool one = slab >= (int64_t)n64;
+                for (int64_t j0 = 0; j0 < (int64_t)n64 && e == hipSuccess; j0 += slab) {
+                    const int64_t pts = (int64_t)n64 - j0 < slab ? (int64_t)n64 - j0 : slab;
+                    const int64_t j1 = j0 + pts < n ? j0 + pts : n;
+                    if (!one) {
+                        if (j0 > 0) {
+                            close_bracket(t1, stream, 1);
+                            t1 = mark(stream);
+                        }
+                        e = launch_pack_operands(X, ldx, n, d, j0, pts, xp, stream);
+                    }
+                    if (j0 == 0) {
+                        if (e == hipSuccess)
+                            e = launch_seed_thresholds(Qc, ldq, xp, xn, qs, qn, tsh, hdr, rows, j1, d, k,
+                                                       plan.seed_points, stream);
+                        if (e == hipSuccess) e = launch_fill_words(tsr, rows * S, 0xff800000u, stream);
+                    }
+                    if (e != hipSuccess) break;
+                    close_bracket(t1, stream, 0);
+                    t1 = mark(stream);
+                    e = launch_packed(Qc, ldq, X, ldx, xp, j0, qs, qn, tsh, tsr, xn, hdr, rows, n, d, k, S,
+                                      plan.tile_q / 32, j0, j1, j0 == 0 ? 0 : S, lk, li, stream);
+                }
             }
         } else
             e = hipErrorInvalidValue;  // no such path

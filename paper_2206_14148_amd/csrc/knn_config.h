@@ -64,6 +64,7 @@ constexpr int kPkRoom = 4;               // a buffer with fewer free slots than 
 constexpr int kPkLdsBytes = 160 * 1024;  // LDS of a gfx950 compute unit
 constexpr int kPkSeedMin = 8192;         // sample of max(this, 8 k) points for the first thresholds
 constexpr int64_t kPkMinPoints = 65536;  // fewer points: not worth packing
+constexpr int64_t kPkSlabGrain = 8192;   // slabs of the packed copy are multiples of this many points
 constexpr int64_t kPkMinQueries = 2048;  // fewer queries: packing all points costs more than it saves
                                          // (measured: 1000 queries, n = 1e6, d = 64: 3.0 ms against 2.1 on path 5;
                                          // 2000 queries, n = 2e5, d = 128, k = 100: 4.5 against 10.0)

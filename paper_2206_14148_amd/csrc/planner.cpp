@@ -232,58 +232,72 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
         const int nch_p = pk_padded_chunks(d);
         const int sets_max = pk_max_sets(nch_p, k);
         const uint64_t n64 = ((uint64_t)n + kPkStep - 1) / kPkStep * kPkStep;
-        const uint64_t per_point = align_up(n64 * 4) + kAlign + align_up(n64 * (uint64_t)nch_p * 32);
+        // norms of all points and the header stay for the whole call; the bf16 copy holds one SLAB
+        // of the points at a time - all of them if the limit has room, else the largest slab that
+        // leaves the lists a place: the point axis is cut by the limit as well (section 4.3), each
+        // slab is packed into the same buffer and searched, and the lists carry over.
+        const uint64_t fixed = align_up(n64 * 4) + kAlign;
         const int64_t min_rows = m < 64 ? m : 64;
-        if (sets_max >= 2 &&
-            mem_limit_bytes >= per_point + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k) +
-                                   query_bytes_for((uint64_t)min_rows, qrow, 3, 1)) {
-            // Query sets per workgroup and point ranges: a launch runs in rounds of one workgroup
-            // per compute unit, a workgroup's time goes with sets x (range + a start-up allowance).
-            const uint64_t avail6 = mem_limit_bytes - per_point;
-            double best = 0.0;
-            int best_sets = 0;
-            int64_t best_S = 0, best_r = 0;
-            for (int sets = sets_max; sets >= 2 && sets >= sets_max - 6; --sets) {
-                const int64_t tile6 = 32 * sets;
-                for (int64_t S = 1; S <= 32; ++S) {
-                    if (n / S < 8 * kPkStep * 16) break;  // ranges of >= 16 rounds of the waves
-                    int64_t rows = rows_fitting(avail6, (uint64_t)S, (uint64_t)k, qrow, 3);
-                    if (rows > kMaxChunkRows) rows = kMaxChunkRows;
-                    if (rows >= m) rows = m;
-                    else rows = rows / tile6 * tile6;
-                    if (rows < 1) continue;
-                    const int64_t chunks = (m + rows - 1) / rows;
-                    const int64_t wgs = (rows + tile6 - 1) / tile6 * S;
-                    const int64_t rounds = (wgs + kNumCU - 1) / kNumCU;
-                    const double range = (double)((n + S - 1) / S);
-                    // larger tiles re-read the points less often: a mild preference
-                    // and fewer ranges mean fewer lists to fill and to merge
-                    const double cost = (double)chunks * (double)rounds * (double)sets *
-                                        (range + 4096.0 + 64.0 * (double)k) * (1.0 + 0.5 / (double)sets) *
-                                        (1.0 + 0.005 * (double)S);
-                    if (best_sets == 0 || cost < best) {
-                        best = cost;
-                        best_sets = sets;
-                        best_S = S;
-                        best_r = rows;
+        double best = 0.0;
+        int best_sets = 0;
+        int64_t best_S = 0, best_r = 0, best_slab = 0;
+        for (int64_t slab = (int64_t)n64; sets_max >= 2 && (slab == (int64_t)n64 || slab >= 2 * kPkMinPoints);
+             slab = (slab / 2 + kPkSlabGrain - 1) / kPkSlabGrain * kPkSlabGrain) {
+            const uint64_t copy = align_up((uint64_t)slab * (uint64_t)nch_p * 32);
+            if (mem_limit_bytes >= fixed + copy + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k) +
+                                       query_bytes_for((uint64_t)min_rows, qrow, 3, 1)) {
+                // Query sets per workgroup and point ranges: a launch runs in rounds of one
+                // workgroup per compute unit, a workgroup's time goes with sets x (range + a
+                // start-up allowance), and there is one launch per slab and query chunk.
+                const uint64_t avail6 = mem_limit_bytes - fixed - copy;
+                const int64_t nslabs = ((int64_t)n64 + slab - 1) / slab;
+                for (int sets = sets_max; sets >= 2 && sets >= sets_max - 6; --sets) {
+                    const int64_t tile6 = 32 * sets;
+                    for (int64_t S = 1; S <= 32; ++S) {
+                        if (slab / S < 8 * kPkStep * 16) break;  // ranges of >= 16 rounds of the waves
+                        int64_t rows = rows_fitting(avail6, (uint64_t)S, (uint64_t)k, qrow, 3);
+                        if (rows > kMaxChunkRows) rows = kMaxChunkRows;
+                        if (rows >= m) rows = m;
+                        else rows = rows / tile6 * tile6;
+                        if (rows < 1) continue;
+                        const int64_t chunks = (m + rows - 1) / rows;
+                        // (a slab is packed again for every query chunk, and small tiles make
+                        // poor use of it: slabs only where all queries fit one chunk of large tiles)
+                        if (nslabs > 1 && (chunks > 1 || sets < sets_max - 3)) continue;
+                        const int64_t wgs = (rows + tile6 - 1) / tile6 * S;
+                        const int64_t rounds = (wgs + kNumCU - 1) / kNumCU;
+                        const double range = (double)((slab + S - 1) / S);
+                        // larger tiles re-read the points less often: a mild preference
+                        // and fewer ranges mean fewer lists to fill and to merge
+                        const double cost = (double)chunks * (double)nslabs * (double)rounds * (double)sets *
+                                            (range + 4096.0 + 64.0 * (double)k) * (1.0 + 0.5 / (double)sets) *
+                                            (1.0 + 0.005 * (double)S);
+                        if (best_sets == 0 || cost < best) {
+                            best = cost;
+                            best_sets = sets;
+                            best_S = S;
+                            best_r = rows;
+                            best_slab = slab;
+                        }
                     }
                 }
             }
-            if (best_sets != 0) {
-                out->path = KNN_PATH_MFMA_PACKED;
-                out->seed_points = (int32_t)pk_seed_points(k);
-                out->tile_q = 32 * best_sets;
-                out->tile_x = kPkStep;
-                out->norms_bytes = per_point;
-                out->n_splits = (int32_t)best_S;
-                out->chunk_rows = best_r;
-                out->q_chunks = (m + best_r - 1) / best_r;
-                out->lists_bytes = lists_bytes_for((uint64_t)best_r, (uint64_t)best_S, (uint64_t)k);
-                out->query_bytes = query_bytes_for((uint64_t)best_r, qrow, 3, (uint64_t)best_S);
-                out->workspace_bytes = out->norms_bytes + out->query_bytes + out->lists_bytes;
-                plan_two_streams(out, m, mem_limit_bytes, qrow, 3);
-                return KNN_OK;
-            }
+        }
+        if (best_sets != 0) {
+            out->path = KNN_PATH_MFMA_PACKED;
+            out->seed_points = (int32_t)pk_seed_points(k);
+            out->slab_points = best_slab;
+            out->tile_q = 32 * best_sets;
+            out->tile_x = kPkStep;
+            out->norms_bytes = fixed + align_up((uint64_t)best_slab * (uint64_t)nch_p * 32);
+            out->n_splits = (int32_t)best_S;
+            out->chunk_rows = best_r;
+            out->q_chunks = (m + best_r - 1) / best_r;
+            out->lists_bytes = lists_bytes_for((uint64_t)best_r, (uint64_t)best_S, (uint64_t)k);
+            out->query_bytes = query_bytes_for((uint64_t)best_r, qrow, 3, (uint64_t)best_S);
+            out->workspace_bytes = out->norms_bytes + out->query_bytes + out->lists_bytes;
+            plan_two_streams(out, m, mem_limit_bytes, qrow, 3);
+            return KNN_OK;
         }
     }
     const int64_t tile = out->tile_q;

@@ -168,3 +168,33 @@ def test_packed_unaligned_rows_fall_back_to_the_split_kernel(K, oracle):
     Q = rng.standard_normal((m, d), dtype=np.float32)
     idx, dist = both_paths(K, torch.from_numpy(Q).cuda(), torch.from_numpy(X).cuda(), k)
     against_oracle(oracle, Q, X, k, idx, dist, np.arange(0, m, 89))
+
+
+def test_packed_slabs_under_a_limit_without_room_for_the_whole_copy(K, oracle):
+    # the bf16 copy of all points does not fit: the points are packed and searched slab after slab
+    # into the same buffer, the lists carrying over; same bits as with the whole copy and as the
+    # split path
+    say("packed slabs case")
+    rng = np.random.default_rng(31)
+    n, d, m, k = 600_001, 40, 2500, 20
+    X = rng.standard_normal((n, d), dtype=np.float32)
+    Q = rng.standard_normal((m, d), dtype=np.float32)
+    Xd, Qd = torch.from_numpy(X).cuda(), torch.from_numpy(Q).cuda()
+    full = K.knn_plan(m, n, d, k, 4 * 10 ** 9)
+    assert full.path == K.KNN_PATH_MFMA_PACKED and full.slab_points >= n
+    ref_i, ref_d = K.knn_search(Qd, Xd, k, 4 * 10 ** 9)
+    seen = set()
+    for frac in (0.6, 0.3):
+        lim = int(full.norms_bytes * frac) + full.query_bytes + full.lists_bytes + 4 * 10 ** 6
+        p = K.knn_plan(m, n, d, k, lim)
+        assert p.path == K.KNN_PATH_MFMA_PACKED and 131072 <= p.slab_points < n and p.q_chunks == 1, p
+        assert p.workspace_bytes <= lim
+        seen.add(-(-n // p.slab_points))
+        guard = 4096
+        ws = torch.full((p.workspace_bytes + guard,), 0x3C, dtype=torch.uint8, device="cuda")
+        i2, d2 = K.knn_search(Qd, Xd, k, lim, workspace=ws[:p.workspace_bytes])
+        torch.cuda.synchronize()
+        assert bool((ws[p.workspace_bytes:] == 0x3C).all())
+        assert torch.equal(ref_i, i2) and torch.equal(ref_d.view(torch.int32), d2.view(torch.int32)), p
+    assert len(seen) >= 2, seen  # different slab counts, one of them with a short last slab
+    against_oracle(oracle, Q, X, k, ref_i.cpu().numpy(), ref_d.cpu().numpy(), np.arange(0, m, 101))

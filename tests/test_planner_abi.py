@@ -64,14 +64,15 @@ def test_chunk_rows_floor():
 
 # (m, n, d, k, limit, path): d <= 8 with room for the packed points takes the low-d matrix-core
 # filter; 16 < d <= 256 with room for the points rounded to bf16 (32 bytes per point and 16
-# coordinates: 2.56 GB at d = 128, n = 1e7; 1.02 GB at d = 256, n = 2e6) the packed path
+# coordinates: 2.56 GB at d = 128, n = 1e7; 1.02 GB at d = 256, n = 2e6) or of a slab of them (at
+# least 65536 points) the packed path
 CONFIGS = [
     (1_000, 10_000, 16, 10, 64 * 10 ** 6, K.KNN_PATH_MFMA_SPLIT),
     (1_000_000, 1_000_000, 3, 16, 10 ** 9, K.KNN_PATH_LOWD_BF16),
     (10_000, 1_000_000, 784, 10, 2 * 10 ** 9, K.KNN_PATH_MFMA_SPLIT),
     (100_000, 10_000_000, 128, 100, 8 * 10 ** 9, K.KNN_PATH_MFMA_PACKED),
-    (50_000, 2_000_000, 256, 32, 128 * 10 ** 6, K.KNN_PATH_MFMA_SPLIT),
-    (50_000, 2_000_000, 256, 32, 10 ** 9, K.KNN_PATH_MFMA_SPLIT),
+    (50_000, 2_000_000, 256, 32, 128 * 10 ** 6, K.KNN_PATH_MFMA_PACKED),  # slabs of the copy
+    (50_000, 2_000_000, 256, 32, 10 ** 9, K.KNN_PATH_MFMA_PACKED),        # two slabs
     (50_000, 2_000_000, 256, 32, 8 * 10 ** 9, K.KNN_PATH_MFMA_PACKED),
     (50_000, 2_000_000, 256, 32, 64 * 10 ** 9, K.KNN_PATH_MFMA_PACKED),
 ]
@@ -104,7 +105,7 @@ def test_min_limit_is_exact_boundary():
 
 def test_small_limits_cut_queries_into_chunks_and_never_exceed_the_limit():
     m, n, d, k = 50_000, 2_000_000, 256, 32
-    prev_lists = None
+    prev_lists = prev_path = None
     for limit in [8_400_000, 8_700_000, 9_000_000, 12_000_000, 20_000_000, 50_000_000, 128_000_000, 10 ** 9]:
         p = K.knn_plan(m, n, d, k, limit)
         assert p.workspace_bytes <= limit
@@ -113,9 +114,12 @@ def test_small_limits_cut_queries_into_chunks_and_never_exceed_the_limit():
         # may go up when the plan trades rows for ranges (more workgroups per launch)
         # (with several chunks two sets of lists are live, one being merged while the other is
         # filled: plan.streams == 2)
-        if prev_lists is not None:
+        # (compared between plans of one kernel family: with room for a slab of the bf16 copy the
+        # plan changes to the packed path, which takes all queries in one chunk of few ranges)
+        if prev_lists is not None and p.path == prev_path:
             assert p.chunk_rows * p.n_splits * p.streams >= prev_lists
         prev_lists = p.chunk_rows * p.n_splits * p.streams
+        prev_path = p.path
         assert p.streams == (2 if p.q_chunks > 1 and p.lists_bytes >= 4 * p.tile_q * p.n_splits * k * 4 else 1)
     tight = K.knn_plan(m, n, d, k, 8_400_000)
     assert tight.q_chunks > 1
@@ -216,7 +220,9 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
             nch_p = nch if nch <= 8 else (nch + 1) // 2 * 2
             waves = 8 if nch_p <= 8 else 4  # above 8 chunks: four waves of up to 512 registers
             n64 = (n + 63) // 64 * 64
-            assert p.norms_bytes == up(4 * n64) + 256 + up(n64 * nch_p * 32)
+            # the copy holds all points, or a slab of them (a multiple of 8192 points, at least 65536)
+            assert p.slab_points == n64 or (p.slab_points % 8192 == 0 and 131072 <= p.slab_points < n64 and p.q_chunks == 1)
+            assert p.norms_bytes == up(4 * n64) + 256 + up(p.slab_points * nch_p * 32)
             assert p.tile_q % 32 == 0 and 64 <= p.tile_q <= 512 and p.tile_x == 64
             # the workgroup's LDS: B operands, candidate buffers and state, merge scratch, control
             sets = p.tile_q // 32
