@@ -82,7 +82,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 // copy.  One wave per 64 queries, B operands in registers; a first pass finds the lane's lowest
 // and highest filter key, then kSeedIters passes quarter the interval [lo, hi] keeping
 // count(f <= hi) >= k.  The bound goes into tsh (atomic minimum on the order-preserving word).
-constexpr int kSeedIters = 6;
+constexpr int kSeedIters = 4;
 constexpr int kSeedSets = 2;  // sets of 32 queries per wave: one fetch of a step's operands serves both
 template <int NCH>
 __global__ __launch_bounds__(256) void knn_seed_kernel(const uint4* __restrict__ Xp, const float* __restrict__ xn,
