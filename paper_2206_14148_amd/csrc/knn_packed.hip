@@ -514,6 +514,56 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
         }
     };
 
+    // The same for the four-wave shape, where a wave has its SIMD to itself and nothing runs
+    // under its MFMAs unless the wave's own instruction stream offers it: the minima and the
+    // vote of the PREVIOUS set (accumulators p0 / p1, query pq, threshold ptq) are interleaved
+    // with this set's MFMAs, two accumulator sets taking turns.  Returns this set's threshold.
+    auto body_pipe = [&](int qs, f32x16& c0, f32x16& c1, const f32x16& p0, const f32x16& p1, int pq,
+                         float ptq, int st, int parity) {
+        const int q = qs * 32 + i32;
+        const float tq = tauf_l[q];
+        const uint4* bq = Bq + (size_t)qs * (NCH * 64) + lane;
+        constexpr int AH = NCH < 4 ? NCH : 4;
+        uint4 bw[AH];
+#pragma unroll
+        for (int c = 0; c < AH; ++c) bw[c] = bq[c * 64];
+        float g[8];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const bf16x8 b = __builtin_bit_cast(bf16x8, bw[c % AH]);
+            if (c + AH < NCH) bw[c % AH] = bq[(c + AH) * 64];
+            c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[0][c]), b,
+                                                         c == 0 ? XN[0] : c0, 0, 0, 0);
+            c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[1][c]), b,
+                                                         c == 0 ? XN[1] : c1, 0, 0, 0);
+            // The previous set's group minima, written in among the first chunks.  (Where they end
+            // up is the compiler's choice - mostly under the last MFMAs - and better left to it:
+            // asked through scheduling group barriers for two MFMAs and five vector instructions
+            // a chunk, it also gave up reading the B operands ahead: 60.3 against 57.7 ms at
+            // d = 256.)
+            if (c < 4) {
+                g[c] = fminf(fminf(fminf(p0[4 * c], p0[4 * c + 1]), p0[4 * c + 2]), p0[4 * c + 3]);
+                g[4 + c] = fminf(fminf(fminf(p1[4 * c], p1[4 * c + 1]), p1[4 * c + 2]), p1[4 * c + 3]);
+            }
+        }
+        const float m = fminf(fminf(fminf(fminf(g[0], g[1]), g[2]), fminf(fminf(g[3], g[4]), g[5])),
+                              fminf(g[6], g[7]));
+        if (__builtin_amdgcn_ballot_w64(m < ptq) != 0) append(pq, ptq, p0, p1, g, st, parity);
+        return tq;
+    };
+    // the last set of a step has nobody behind it: its minima and vote on their own
+    auto tail_pipe = [&](int qs, float tq, const f32x16& p0, const f32x16& p1, int st, int parity) {
+        float g[8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            g[u] = fminf(fminf(fminf(p0[4 * u], p0[4 * u + 1]), p0[4 * u + 2]), p0[4 * u + 3]);
+            g[4 + u] = fminf(fminf(fminf(p1[4 * u], p1[4 * u + 1]), p1[4 * u + 2]), p1[4 * u + 3]);
+        }
+        const float m = fminf(fminf(fminf(fminf(g[0], g[1]), g[2]), fminf(fminf(g[3], g[4]), g[5])),
+                              fminf(g[6], g[7]));
+        if (__builtin_amdgcn_ballot_w64(m < tq) != 0) append(qs * 32 + i32, tq, p0, p1, g, st, parity);
+    };
+
     // A stop: every wave of the workgroup is here, nobody appends.  The queries with enough
     // buffered pairs (everything: all that have any) and those with a step to make good are
     // dealt out over the waves; then every query's filter threshold is brought up to date.
@@ -608,11 +658,44 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
             xn_next = a.xn[(size_t)nstep * kPkStep + lane];
             const u32x4* xnext =
                 reinterpret_cast<const u32x4*>(a.Xp) + (size_t)(nstep - a.step_slab0) * (2 * NCH * 64);
-            for (int qs = 0; qs + 1 < sets; ++qs) body(qs, false, xnext, step, parity);
-            const int stop = __builtin_amdgcn_readfirstlane(
-                __hip_atomic_load(ctl + kCtlStop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-            // (the last set always requests the next step's operands as it goes; a stop reloads them)
-            body(sets - 1, true, xnext, step, parity);
+            int stop;
+            if constexpr (kPkWaves == 4) {
+                // the next step's operands are requested when the step begins (there are registers
+                // for a second set of them); the sets run through the two-stage pipeline above
+                u32x4 A2[2][NCH];
+#pragma unroll
+                for (int pb = 0; pb < 2; ++pb)
+#pragma unroll
+                    for (int c = 0; c < NCH; ++c) A2[pb][c] = xnext[(pb * NCH + c) * 64 + lane];
+                f32x16 a0, a1, b0, b1;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) b0[e] = b1[e] = kInf;  // "the set before the first": nothing passes
+                float tqa = body_pipe(0, a0, a1, b0, b1, i32, -kInf, step, parity), tqb = -kInf;
+                int qs = 1;
+                for (; qs + 1 < sets; qs += 2) {
+                    tqb = body_pipe(qs, b0, b1, a0, a1, (qs - 1) * 32 + i32, tqa, step, parity);
+                    tqa = body_pipe(qs + 1, a0, a1, b0, b1, qs * 32 + i32, tqb, step, parity);
+                }
+                if (qs < sets) {
+                    tqb = body_pipe(qs, b0, b1, a0, a1, (qs - 1) * 32 + i32, tqa, step, parity);
+                    tail_pipe(qs, tqb, b0, b1, step, parity);
+                } else {
+                    tail_pipe(qs - 1, tqa, a0, a1, step, parity);
+                }
+                stop = __builtin_amdgcn_readfirstlane(
+                    __hip_atomic_load(ctl + kCtlStop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+#pragma unroll
+                for (int pb = 0; pb < 2; ++pb)
+#pragma unroll
+                    for (int c = 0; c < NCH; ++c) A[pb][c] = A2[pb][c];
+            } else {
+                for (int qs = 0; qs + 1 < sets; ++qs) body(qs, false, xnext, step, parity);
+                stop = __builtin_amdgcn_readfirstlane(
+                    __hip_atomic_load(ctl + kCtlStop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                // (the last set always requests the next step's operands as it goes; a stop reloads
+                // them)
+                body(sets - 1, true, xnext, step, parity);
+            }
             step = nstep;
             have = has_next;
             parity ^= 1;
