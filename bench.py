@@ -493,9 +493,12 @@ def knn_record(w, limit, steps, warmup, cpu_seconds, peaks, default_shape, host_
     sweep_out = None
     if w.sweep and sweep:
         sweep_out = []
-        # (room for the per-point data and about a third of the lists of the smallest sweep limit)
-        p_lo = K.knn_plan(w.m, w.n, w.d, w.k, min(w.sweep), w.metric)
-        small = p_lo.norms_bytes + (p_lo.query_bytes + p_lo.lists_bytes) // 3
+        # (the smallest limit, in steps of a quarter above the minimum, that takes 2 to 8 chunks)
+        small = K.knn_plan(w.m, w.n, w.d, w.k, 1 << 44, w.metric).min_limit_bytes
+        for _ in range(40):
+            if 2 <= K.knn_plan(w.m, w.n, w.d, w.k, small, w.metric).q_chunks <= 8:
+                break
+            small = small * 5 // 4
         for lim in (small,) + tuple(w.sweep):
             p2 = K.knn_plan(w.m, w.n, w.d, w.k, lim, w.metric)
             ws2 = torch.empty(max(p2.workspace_bytes, 256), dtype=torch.uint8, device=dev)
