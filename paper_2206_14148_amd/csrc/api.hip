@@ -281,7 +281,9 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
                         e = launch_pack_operands(X, ldx, n, d, j0, pts, xp, stream);
                     }
                     if (j0 == 0) {
-                        if (e == hipSuccess)
+                        // (thresholds kept from an earlier block of a host-streamed search are
+                        // tighter than a sample of this block would make them)
+                        if (e == hipSuccess && !keep_thresholds)
                             e = launch_seed_thresholds(Qc, ldq, xp, xn, qs, qn, tsh, hdr, rows, j1, d, k,
                                                        plan.seed_points, stream);
                         if (e == hipSuccess) e = launch_fill_words(tsr, rows * S, 0xff800000u, stream);
@@ -517,7 +519,8 @@ extern "C" knn_status knn_search_host_x(const float* Q, int64_t ldq, const float
         // From the second full block on, a block's lists start under the thresholds the
         // blocks before it reached (every earlier block is a full one with lists of length k,
         // so its k-th key bounds the overall k-th key) instead of warming up again.
-        const bool keep = b > 0 && nb == hp.block_rows && plan.path == KNN_PATH_MFMA_SPLIT &&
+        const bool keep = b > 0 && nb == hp.block_rows &&
+                          (plan.path == KNN_PATH_MFMA_SPLIT || plan.path == KNN_PATH_MFMA_PACKED) &&
                           plan.q_chunks == 1;
         st = run_search(plan, Q, ldq, stage[buf], d, m, nb, d, kb, metric, inner_ws, bidx, bdist,
                         stream, keep, false, bd64);
