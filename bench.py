@@ -339,12 +339,13 @@ def bench_sgpr(args) -> int:
     return 0
 
 
-PATH_NAMES = {0: "lowd", 2: "lowd_mfma", 3: "l1", 4: "lowd_bf16", 5: "mfma_split", 6: "mfma_packed"}
+PATH_NAMES = {0: "lowd", 2: "lowd_mfma", 3: "l1", 4: "lowd_bf16", 5: "mfma_split", 6: "mfma_packed", 7: "mfma_wide"}
 # arithmetic the path computes in: what the matrix cores filter in, what the list keys are, what the
 # returned distances are evaluated in
 PATH_DTYPES = {0: "f32 keys / f64 refine", 3: "f32 keys / f64 refine",
                2: "f32 filter / f32 keys / f64 refine", 4: "bf16 filter / f32 keys / f64 refine",
-               5: "bf16 filter / f32 keys / f64 refine", 6: "bf16 filter / f32 keys / f64 refine"}
+               5: "bf16 filter / f32 keys / f64 refine", 6: "bf16 filter / f32 keys / f64 refine",
+               7: "bf16 filter / f32 keys / f64 refine"}
 
 
 def knn_record(w, limit, steps, warmup, cpu_seconds, peaks, default_shape, host_x=False,
@@ -406,11 +407,12 @@ def knn_record(w, limit, steps, warmup, cpu_seconds, peaks, default_shape, host_
     launches_per_step = max(launches, 1) / steps
     pairs_per_launch = float(w.m) * float(w.n) / launches_per_step
     hbm_equiv = (pairs_per_launch / avg_launch_s) * 8.0 / (PEAK_HBM_GBS * 1e9)
-    if plan.path in (K.KNN_PATH_MFMA_SPLIT, K.KNN_PATH_MFMA_PACKED):
+    if plan.path in (K.KNN_PATH_MFMA_SPLIT, K.KNN_PATH_MFMA_PACKED, K.KNN_PATH_MFMA_WIDE):
         # The -2 Q X^T contraction of the filter runs on bf16 roundings of the values: 2 d bf16
         # flops per pair on the matrix cores, with d rounded up to the 16 coordinates of an MFMA,
         # against the dense bf16 peak.
-        kernel = "knn_split_kernel" if plan.path == K.KNN_PATH_MFMA_SPLIT else "knn_packed_kernel"
+        kernel = {K.KNN_PATH_MFMA_SPLIT: "knn_split_kernel", K.KNN_PATH_MFMA_PACKED: "knn_packed_kernel",
+                  K.KNN_PATH_MFMA_WIDE: "knn_wide_kernel"}[plan.path]
         d_pad = (w.d + 15) // 16 * 16
         achieved = 2.0 * d_pad * pairs_per_launch / avg_launch_s / 1e12
         roofline = {"bound": "mfma", "kernel": kernel, "achieved": achieved,

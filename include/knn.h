@@ -77,6 +77,12 @@ typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1, KNN_METRIC_L1 = 2 } k
                                   points read from that copy in matrix-core operand order; the
                                   lists start under thresholds found from a sample's filter keys.
                                   Same exact test, same keys, same results as path 5. */
+#define KNN_PATH_MFMA_WIDE 7 /* d > 256, squared-Euclidean, k <= 512, m >= 2048, n >= 65536 and room for
+                                the points rounded to bf16: the filter of path 5 on tiles of 512
+                                queries x 128 points, both operands read from bf16 copies in
+                                matrix-core operand order; a list without a bound takes its first
+                                threshold from the filter keys of its first tile.  Same exact test,
+                                same keys, same results as path 5. */
 
 /*
  * The plan: how the call is cut into pieces (section 4.3: split the largest
@@ -106,14 +112,15 @@ typedef struct {
                             above that the distance to their farthest corner); 0: none */
     uint64_t norms_bytes;     /* workspace: per-point data. path 2: packed points
                                  [x0 x1 x2 |x|^2]; path 5: squared norms (cosine: 1 / norm)
-                                 and a 256-byte header; path 6: the same (norms padded to a
+                                 and a 256-byte header; paths 6, 7: the same (norms padded to a
                                  multiple of 64 points) and slab_points points rounded to bf16; path 4: a 256-byte header, 32 bytes
                                  per point and 16 K slots, and with seed_cells the grid's cell
                                  starts and cursors and the points in cell order (16 bytes each);
                                  paths 0, 3: nothing                                   */
     uint64_t query_bytes;     /* workspace: per-query data of one chunk. path 5: the queries
                                  rounded to bf16 (32 bytes per row and 16 coordinates), their
-                                 squared norms and shared thresholds; path 3: the queries
+                                 squared norms and shared thresholds (paths 6, 7: and a word per
+                                 query and point range; path 7: rows rounded up to 64); path 3: the queries
                                  transposed in blocks of 64 rows (16 bytes per row and 4
                                  coordinates); else 0                                  */
     uint64_t lists_bytes;     /* workspace: partial k-lists of one chunk (streams == 2: of two) */
@@ -127,7 +134,7 @@ typedef struct {
                                  planner takes that path only where workspace_bytes +
                                  private_bytes stays within the limit.  Not part of
                                  workspace_bytes: the caller does not allocate it. */
-    int64_t slab_points;      /* path 6: points the bf16 copy holds at a time (n rounded up to 64
+    int64_t slab_points;      /* paths 6, 7: points the bf16 copy holds at a time (n rounded up to 64
                                  when all of them fit under the limit, else a multiple of 8192:
                                  the points are then packed and searched slab after slab, the
                                  lists carrying over); else 0 */

@@ -6,7 +6,7 @@ binding.py.
 """
 from .binding import (  # noqa: F401
     KNN_ERR_HIP, KNN_ERR_INVALID_ARG, KNN_ERR_MEM_LIMIT_TOO_SMALL, KNN_ERR_UNSUPPORTED,
-    KNN_ERR_WORKSPACE_TOO_SMALL, KNN_MAX_K, KNN_METRIC_COSINE, KNN_METRIC_L1, KNN_METRIC_L2SQ, KNN_OK, KNN_PATH_L1, KNN_PATH_LOWD, KNN_PATH_LOWD_MFMA, KNN_PATH_LOWD_BF16, KNN_PATH_MFMA_SPLIT, KNN_PATH_MFMA_PACKED,
+    KNN_ERR_WORKSPACE_TOO_SMALL, KNN_MAX_K, KNN_METRIC_COSINE, KNN_METRIC_L1, KNN_METRIC_L2SQ, KNN_OK, KNN_PATH_L1, KNN_PATH_LOWD, KNN_PATH_LOWD_MFMA, KNN_PATH_LOWD_BF16, KNN_PATH_MFMA_SPLIT, KNN_PATH_MFMA_PACKED, KNN_PATH_MFMA_WIDE,
     EXPORTED_SYMBOLS, KnnError, Plan, knn_chunk_rows, knn_last_stats, knn_parse_size, knn_plan, knn_profile_enable,
     knn_profile_read,
     KMV_PATH_LOWD, KMV_PATH_MFMA, KMV_PATH_VALU, KmvPlan, kmv_apply, kmv_apply_raw, kmv_plan,

@@ -26,6 +26,7 @@ KNN_PATH_LOWD_MFMA = 2
 KNN_PATH_LOWD_BF16 = 4
 KNN_PATH_MFMA_SPLIT = 5
 KNN_PATH_MFMA_PACKED = 6
+KNN_PATH_MFMA_WIDE = 7
 KNN_METRIC_L2SQ = 0
 KNN_METRIC_COSINE = 1
 KNN_METRIC_L1 = 2

@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libknn_mi355x.so")
-SOURCES = ["planner.cpp", "api.hip", "knn_lowd.hip", "knn_norms.hip", "knn_split.hip", "knn_packed.hip", "knn_refine.hip", "knn_peak.hip",
+SOURCES = ["planner.cpp", "api.hip", "knn_lowd.hip", "knn_norms.hip", "knn_split.hip", "knn_packed.hip", "knn_wide.hip", "knn_refine.hip", "knn_peak.hip",
            "kmv_api.hip", "kmv_kernels.hip", "sgpr_api.hip", "sgpr_kernels.hip"]
 HEADERS = ["knn_config.h", "knn_device.h", "knn_exact.h", "knn_kernels.h", "kmv_kernels.h", "sgpr_kernels.h",
            os.path.join("..", "..", "include", "sgpr.h"),

@@ -185,15 +185,19 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     float* xn = reinterpret_cast<float*>(ws);
     // path 5: [squared norms][header: their maximum] | [split queries][query norms][shared
     // thresholds] | lists; L1 path: [transposed queries] | lists
-    const bool packed_plan = plan.path == KNN_PATH_MFMA_PACKED;
+    const bool wide_plan = plan.path == KNN_PATH_MFMA_WIDE;
+    const bool packed_plan = plan.path == KNN_PATH_MFMA_PACKED || wide_plan;
     const uint64_t n64 = ((uint64_t)n + kPkStep - 1) / kPkStep * kPkStep;
     unsigned char* hdr = ws + align_up((packed_plan ? n64 : (uint64_t)n) * 4);
-    unsigned char* xp = hdr + kAlign;  // path 6: the points rounded to bf16
-    // path 6 needs 16-byte aligned rows; other calls run its plan on path 5's kernel
+    unsigned char* xp = hdr + kAlign;  // paths 6, 7: the points rounded to bf16
+    // paths 6, 7 need 16-byte aligned rows; other calls run their plans on path 5's kernel
     const bool packed = packed_plan && packed_rows_aligned(Q, ldq, X, ldx, d);
     unsigned char* qs = ws + plan.norms_bytes;
-    float* qn = reinterpret_cast<float*>(
-        qs + align_up((uint64_t)plan.chunk_rows * 32 * (((uint64_t)d + kSpKC - 1) / kSpKC)));
+    // (path 7: the B operands in operand order, rows rounded up to 64, chunks to an even count)
+    const uint64_t qs_bytes =
+        wide_plan ? ((uint64_t)plan.chunk_rows + 63) / 64 * 64 * 32 * (uint64_t)pk_padded_chunks(d)
+                  : (uint64_t)plan.chunk_rows * 32 * (((uint64_t)d + kSpKC - 1) / kSpKC);
+    float* qn = reinterpret_cast<float*>(qs + align_up(qs_bytes));
     unsigned char* tsh = reinterpret_cast<unsigned char*>(qn) + align_up((uint64_t)plan.chunk_rows * 4);
     unsigned char* tsr = tsh + align_up((uint64_t)plan.chunk_rows * 4);  // path 6: [rows][S] words
     unsigned char* lists = ws + plan.norms_bytes + plan.query_bytes;
@@ -259,7 +263,14 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
             e = launch_lowd_bf16(Qc, ldq, X, ldx, ws, rows, n, d, k, S, false, plan.seed_cells, lk,
                                  li, stream);
         else if (plan.path == KNN_PATH_MFMA_SPLIT || packed_plan) {
-            e = launch_split_queries(Qc, ldq, rows, d, qs, tsh, !keep_thresholds, stream);
+            if (wide_plan && packed) {
+                // the queries' B operands bf16(-2 q) in operand order; thresholds start from +inf
+                e = launch_pack_operands(Qc, ldq, rows, d, 0, (rows + kPkStep - 1) / kPkStep * kPkStep, qs,
+                                         stream, -2.f);
+                if (e == hipSuccess && !keep_thresholds) e = launch_fill_words(tsh, rows, 0xff800000u, stream);  // (the word of +inf)
+            } else {
+                e = launch_split_queries(Qc, ldq, rows, d, qs, tsh, !keep_thresholds, stream);
+            }
             if (e == hipSuccess) e = launch_row_norms(Qc, ldq, rows, d, false, qn, stream);
             if (e == hipSuccess && !packed)
                 e = launch_split(Qc, ldq, X, ldx, qs, qn, tsh, xn, hdr, cosine, rows, n, d, k, S, lk,
@@ -282,8 +293,9 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
                     }
                     if (j0 == 0) {
                         // (thresholds kept from an earlier block of a host-streamed search are
-                        // tighter than a sample of this block would make them)
-                        if (e == hipSuccess && !keep_thresholds)
+                        // tighter than a sample of this block would make them; path 7 takes its
+                        // first thresholds inside the search kernel)
+                        if (e == hipSuccess && !keep_thresholds && !wide_plan)
                             e = launch_seed_thresholds(Qc, ldq, xp, xn, qs, qn, tsh, hdr, rows, j1, d, k,
                                                        plan.seed_points, stream);
                         if (e == hipSuccess) e = launch_fill_words(tsr, rows * S, 0xff800000u, stream);
@@ -291,8 +303,12 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
                     if (e != hipSuccess) break;
                     close_bracket(t1, stream, 0);
                     t1 = mark(stream);
-                    e = launch_packed(Qc, ldq, X, ldx, xp, j0, qs, qn, tsh, tsr, xn, hdr, rows, n, d, k, S,
-                                      plan.tile_q / 32, j0, j1, j0 == 0 ? 0 : S, lk, li, stream);
+                    if (wide_plan)
+                        e = launch_wide(Qc, ldq, X, ldx, xp, j0, pts, qs, qn, tsh, tsr, xn, hdr, rows, n, d, k,
+                                        S, j0, j1, j0 == 0 ? 0 : S, lk, li, stream);
+                    else
+                        e = launch_packed(Qc, ldq, X, ldx, xp, j0, qs, qn, tsh, tsr, xn, hdr, rows, n, d, k, S,
+                                          plan.tile_q / 32, j0, j1, j0 == 0 ? 0 : S, lk, li, stream);
                 }
             }
         } else
@@ -520,7 +536,8 @@ extern "C" knn_status knn_search_host_x(const float* Q, int64_t ldq, const float
         // blocks before it reached (every earlier block is a full one with lists of length k,
         // so its k-th key bounds the overall k-th key) instead of warming up again.
         const bool keep = b > 0 && nb == hp.block_rows &&
-                          (plan.path == KNN_PATH_MFMA_SPLIT || plan.path == KNN_PATH_MFMA_PACKED) &&
+                          (plan.path == KNN_PATH_MFMA_SPLIT || plan.path == KNN_PATH_MFMA_PACKED ||
+                           plan.path == KNN_PATH_MFMA_WIDE) &&
                           plan.q_chunks == 1;
         st = run_search(plan, Q, ldq, stage[buf], d, m, nb, d, kb, metric, inner_ws, bidx, bdist,
                         stream, keep, false, bd64);

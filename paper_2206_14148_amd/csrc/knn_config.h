@@ -96,6 +96,30 @@ constexpr inline int64_t pk_seed_points(int k) {
     return ((w > kPkSeedMin ? w : kPkSeedMin) + kPkStep - 1) / kPkStep * kPkStep;
 }
 
+// d > 256, squared-Euclidean metric, many points and queries, room for the points rounded to bf16:
+// tiles of 512 queries x 128 points with both operands streamed from packed bf16 copies
+// (knn_wide.hip).  A workgroup has 8 waves of two query sets each; a pipeline stage covers two
+// chunks of 16 coordinates.
+constexpr int kWdWaves = 8;
+constexpr int kWdSets = 2;                            // query sets of 32 per wave
+constexpr int kWdTileQ = 32 * kWdSets * kWdWaves;     // 512
+constexpr int kWdTileX = 128;
+constexpr int kWdW = 2;                               // chunks per pipeline stage
+constexpr int kWdCand = 32;                           // buffered point indices per query (LDS)
+constexpr int kWdShareMin = 20;                       // a stop empties every buffer with at least this many entries
+constexpr int kWdRoom = 4;                            // a buffer with fewer free slots than this calls a stop
+constexpr int64_t kWdMinPoints = 65536;               // fewer points or queries: the split path
+constexpr int64_t kWdMinQueries = 2048;
+constexpr int kWdMaxSplits = 32;
+constexpr int kWdMaxK = 512;                          // larger k: the split path (LDS)
+// LDS bytes of a workgroup: two stage buffers of the points' operands, two tiles of norms, the
+// candidate buffers, six words of state per query, a few control words, the merge scratch of each wave
+constexpr inline int64_t wd_lds_bytes(int k) {
+    return (int64_t)2 * kWdW * 4 * 1024 + 2 * kWdTileX * 4 + (int64_t)kWdTileQ * kWdCand * 4 +
+           6 * kWdTileQ * 4 + 64 + (int64_t)kWdWaves * (2 * kWave + 2 * k) * 4;
+}
+static_assert(wd_lds_bytes(kWdMaxK) <= kPkLdsBytes, "the largest k must fit the LDS");
+
 // Workgroups the chip holds at once (LDS-limited): the planner sizes launches in rounds of these.
 constexpr int kLowdResidentWorkgroups = 4 * kNumCU;
 constexpr int kSpResidentWorkgroups = kNumCU;   // 8 waves of up to 256 registers: one per CU

@@ -65,7 +65,8 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
 
 // 16 < d <= 256 with the points rounded to bf16 in the workspace (knn_packed.hip).
 //   launch_pack_operands  xp = `points` points from j_first on (j_first and points multiples of
-//                         64; rows past n are zero), pk_padded_chunks(d) x 32 bytes per point
+//                         64; rows past n are zero), pk_padded_chunks(d) x 32 bytes per point;
+//                         scale = -2 packs queries as B operands (n = their number)
 //   launch_pad_norms      xn[n .. next multiple of 64) = +inf
 //   launch_packed         the search of points [j_first, j_end) (j_first a multiple of 64) out of
 //                         the copy xp whose first point is slab_first, for queries whose B
@@ -77,7 +78,7 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
 //                         every range's list, through which the ranges bound each other.
 //                         Rows must be 16-byte aligned (packed_rows_aligned).
 hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, int64_t j_first,
-                                int64_t points, void* xp, hipStream_t stream);
+                                int64_t points, void* xp, hipStream_t stream, float scale = 1.f);
 hipError_t launch_pad_norms(float* xn, int64_t n, hipStream_t stream);
 //   launch_seed_thresholds  tsh[r] = min(tsh[r], an upper bound of query r's k-th smallest distance
 //                         found from the filter keys of seed_points points spread over the packed
@@ -92,6 +93,17 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
                          const float* xn, const void* hdr, int64_t rows, int64_t n, int d, int k, int S,
                          int sets, int64_t j_first, int64_t j_end, int init_from, float* lk, int* li,
                          hipStream_t stream);
+// d > 256 with both operands rounded to bf16 in the workspace (knn_wide.hip).
+//   launch_wide   the search of points [j_first, j_end) (j_first a multiple of 64) out of the copy
+//                 xp (launch_pack_operands) that holds slab_points points from slab_first on, for
+//                 queries whose B operands qp were packed by launch_pack_operands with scale -2
+//                 (rows rounded up to 64), qn / tsh / tsr / xn / hdr / init_from as for
+//                 launch_packed.  S <= 64.  Rows must be 16-byte aligned (packed_rows_aligned).
+hipError_t launch_wide(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* xp,
+                       int64_t slab_first, int64_t slab_points, const void* qp, const float* qn, void* tsh,
+                       void* tsr, const float* xn, const void* hdr, int64_t rows, int64_t n, int d, int k,
+                       int S, int64_t j_first, int64_t j_end, int init_from, float* lk, int* li,
+                       hipStream_t stream);
 // p[0 .. count) = value (32-bit words)
 hipError_t launch_fill_words(void* p, int64_t count, unsigned value, hipStream_t stream);
 

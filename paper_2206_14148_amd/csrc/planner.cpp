@@ -81,6 +81,8 @@ uint64_t query_bytes_for(uint64_t rows, uint64_t qrow, int kind, uint64_t S = 1)
     if (kind == 1) return align_up(rows * qrow) + 2 * align_up(rows * 4);
     // kind 3 (path 6): as kind 1, and a word per query and point range
     if (kind == 3) return align_up(rows * qrow) + 2 * align_up(rows * 4) + align_up(rows * S * 4);
+    // kind 4 (path 7): as kind 3 with the B operands of rows rounded up to 64
+    if (kind == 4) return align_up((rows + 63) / 64 * 64 * qrow) + 2 * align_up(rows * 4) + align_up(rows * S * 4);
     if (kind == 2) return align_up((rows + 63) / 64 * 64 * qrow);
     return 0;
 }
@@ -96,7 +98,7 @@ int64_t rows_fitting(uint64_t avail, uint64_t S, uint64_t k, uint64_t qrow, int 
         return lists_bytes_for(rows, S, k) + query_bytes_for(rows, qrow, kind, S);
     };
     const uint64_t per_row =
-        2 * S * k * 4 + qrow + (kind == 1 ? 8 : 0) + (kind == 3 ? 8 + S * 4 : 0);  // exact, roundings aside
+        2 * S * k * 4 + qrow + (kind == 1 ? 8 : 0) + (kind == 3 || kind == 4 ? 8 + S * 4 : 0);  // exact, roundings aside
     // the roundings (six to kAlign, one to 64 rows) add less than this: start below the
     // answer, then step up to it
     const uint64_t slack = 6 * kAlign + 64 * qrow;
@@ -297,6 +299,70 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
             out->query_bytes = query_bytes_for((uint64_t)best_r, qrow, 3, (uint64_t)best_S);
             out->workspace_bytes = out->norms_bytes + out->query_bytes + out->lists_bytes;
             plan_two_streams(out, m, mem_limit_bytes, qrow, 3);
+            return KNN_OK;
+        }
+    }
+    // d > 256 with many points and queries: tiles of 512 queries x 128 points on bf16 copies of
+    // both operands (knn_wide.hip).  The workspace is path 5's plus the packed points (all of them,
+    // or one slab at a time as on path 6) with the queries' B operands in operand order, so a
+    // call whose rows turn out not to be 16-byte aligned still runs under this plan on path 5's
+    // kernel.
+    if (split && metric == KNN_METRIC_L2SQ && d > kPkMaxD && k <= kWdMaxK && n >= kWdMinPoints &&
+        m >= kWdMinQueries) {
+        const int nch_p = pk_padded_chunks(d);
+        const uint64_t qrow7 = 32ull * (uint64_t)nch_p;
+        const uint64_t n64 = ((uint64_t)n + kPkStep - 1) / kPkStep * kPkStep;
+        const uint64_t fixed = align_up(n64 * 4) + kAlign;
+        const int64_t min_rows = 64;
+        double best = 0.0;
+        int64_t best_S = 0, best_r = 0, best_slab = 0;
+        for (int64_t slab = (int64_t)n64; slab == (int64_t)n64 || slab >= 2 * kWdMinPoints;
+             slab = (slab / 2 + kPkSlabGrain - 1) / kPkSlabGrain * kPkSlabGrain) {
+            const uint64_t copy = align_up((uint64_t)slab * (uint64_t)nch_p * 32);
+            if (mem_limit_bytes < fixed + copy + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k) +
+                                      query_bytes_for((uint64_t)min_rows, qrow7, 4, 1))
+                continue;
+            const uint64_t avail7 = mem_limit_bytes - fixed - copy;
+            const int64_t nslabs = ((int64_t)n64 + slab - 1) / slab;
+            for (int64_t S = 1; S <= kWdMaxSplits; ++S) {
+                if (S > 1 && slab / S < 16 * kWdTileX) break;  // ranges of at least 16 tiles
+                int64_t rows = rows_fitting(avail7, (uint64_t)S, (uint64_t)k, qrow7, 4);
+                if (rows > kMaxChunkRows) rows = kMaxChunkRows;
+                if (rows >= m) rows = m;
+                else rows = rows / kWdTileQ * kWdTileQ;
+                if (rows < 1) continue;
+                const int64_t chunks = (m + rows - 1) / rows;
+                // (a slab is packed again for every query chunk)
+                if (nslabs > 1 && chunks > 1) continue;
+                const int64_t wgs = (rows + kWdTileQ - 1) / kWdTileQ * S;
+                const int64_t rounds = (wgs + kNumCU - 1) / kNumCU;
+                const double range = (double)((slab + S - 1) / S);
+                // one workgroup per compute unit at a time; a range costs its tiles plus the start
+                // of its lists (a first tile, and about 64 k points' worth of exact evaluations)
+                const double cost = (double)chunks * (double)nslabs * (double)rounds *
+                                    (range + 2048.0 + 64.0 * (double)k) * (1.0 + 0.005 * (double)S);
+                if (best_S == 0 || cost < best) {
+                    best = cost;
+                    best_S = S;
+                    best_r = rows;
+                    best_slab = slab;
+                }
+            }
+            if (best_S != 0) break;  // the largest slab that fits
+        }
+        if (best_S != 0) {
+            out->path = KNN_PATH_MFMA_WIDE;
+            out->slab_points = best_slab;
+            out->tile_q = kWdTileQ;
+            out->tile_x = kWdTileX;
+            out->norms_bytes = fixed + align_up((uint64_t)best_slab * (uint64_t)nch_p * 32);
+            out->n_splits = (int32_t)best_S;
+            out->chunk_rows = best_r;
+            out->q_chunks = (m + best_r - 1) / best_r;
+            out->lists_bytes = lists_bytes_for((uint64_t)best_r, (uint64_t)best_S, (uint64_t)k);
+            out->query_bytes = query_bytes_for((uint64_t)best_r, qrow7, 4, (uint64_t)best_S);
+            out->workspace_bytes = out->norms_bytes + out->query_bytes + out->lists_bytes;
+            plan_two_streams(out, m, mem_limit_bytes, qrow7, 4);
             return KNN_OK;
         }
     }

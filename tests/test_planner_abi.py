@@ -69,7 +69,7 @@ def test_chunk_rows_floor():
 CONFIGS = [
     (1_000, 10_000, 16, 10, 64 * 10 ** 6, K.KNN_PATH_MFMA_SPLIT),
     (1_000_000, 1_000_000, 3, 16, 10 ** 9, K.KNN_PATH_LOWD_BF16),
-    (10_000, 1_000_000, 784, 10, 2 * 10 ** 9, K.KNN_PATH_MFMA_SPLIT),
+    (10_000, 1_000_000, 784, 10, 2 * 10 ** 9, K.KNN_PATH_MFMA_WIDE),
     (100_000, 10_000_000, 128, 100, 8 * 10 ** 9, K.KNN_PATH_MFMA_PACKED),
     (50_000, 2_000_000, 256, 32, 128 * 10 ** 6, K.KNN_PATH_MFMA_PACKED),  # slabs of the copy
     (50_000, 2_000_000, 256, 32, 10 ** 9, K.KNN_PATH_MFMA_PACKED),        # two slabs
@@ -228,13 +228,31 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
             sets = p.tile_q // 32
             assert sets * nch_p * 1024 + sets * 32 * (32 * 4 + 28) + waves * (128 + 2 * k) * 4 + waves * 256 + 256 \
                 <= 160 * 1024
+        elif p.path == K.KNN_PATH_MFMA_WIDE:
+            # d > 256, k <= 512: the copy as on path 6, tiles of 512 queries x 128 points, at most 32
+            # ranges; the queries' B operands in operand order (rows rounded up to 64, chunk count
+            # to an even one)
+            assert d > 256 and k <= 512 and m >= 2048 and n >= 65536 and p.seed_points == 0
+            nch_p = (nch + 1) // 2 * 2
+            n64 = (n + 63) // 64 * 64
+            assert p.slab_points == n64 or (p.slab_points % 8192 == 0 and 131072 <= p.slab_points < n64 and p.q_chunks == 1)
+            assert p.norms_bytes == up(4 * n64) + 256 + up(p.slab_points * nch_p * 32)
+            assert p.tile_q == 512 and p.tile_x == 128 and 1 <= p.n_splits <= 32
+            # the workgroup's LDS: stage buffers, norms, candidate buffers, state, control, merge scratch
+            assert 16384 + 1024 + 512 * 32 * 4 + 6 * 512 * 4 + 64 + 8 * (128 + 2 * k) * 4 <= 160 * 1024
         else:
             assert p.path == K.KNN_PATH_MFMA_SPLIT and p.tile_q == 256
             assert p.norms_bytes == up(4 * n) + 256
         tile = p.tile_q
-        # path 6 also keeps one word per query and point range (the ranges bound each other)
-        per_range = up(p.chunk_rows * p.n_splits * 4) if p.path == K.KNN_PATH_MFMA_PACKED else 0
-        assert p.query_bytes == up(p.chunk_rows * nch * 32) + 2 * up(p.chunk_rows * 4) + per_range
+        wide = p.path == K.KNN_PATH_MFMA_WIDE
+
+        def operand_bytes(rows):
+            return up((rows + 63) // 64 * 64 * ((nch + 1) // 2 * 2) * 32) if wide else up(rows * nch * 32)
+
+        # paths 6 and 7 also keep one word per query and point range (the ranges bound each other)
+        ranged = p.path in (K.KNN_PATH_MFMA_PACKED, K.KNN_PATH_MFMA_WIDE)
+        per_range = up(p.chunk_rows * p.n_splits * 4) if ranged else 0
+        assert p.query_bytes == operand_bytes(p.chunk_rows) + 2 * up(p.chunk_rows * 4) + per_range
         assert p.lists_bytes == p.streams * 2 * up(p.chunk_rows * p.n_splits * k * 4)
         assert p.streams == 1 or p.q_chunks > 1
         assert p.workspace_bytes == p.norms_bytes + p.query_bytes + p.lists_bytes <= limit
@@ -242,12 +260,12 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
         assert p.q_chunks == -(-m // p.chunk_rows)
         if p.chunk_rows < m and p.chunk_rows < (1 << 22):  # a longer chunk would not have fitted
             r = p.chunk_rows + tile
-            more = up(r * nch * 32) + 2 * up(r * 4) + p.streams * 2 * up(r * p.n_splits * k * 4) + \
-                (up(r * p.n_splits * 4) if p.path == K.KNN_PATH_MFMA_PACKED else 0)
+            more = operand_bytes(r) + 2 * up(r * 4) + p.streams * 2 * up(r * p.n_splits * k * 4) + \
+                (up(r * p.n_splits * 4) if ranged else 0)
             assert p.norms_bytes + more > limit
         with pytest.raises(K.KnnError):
             K.knn_plan(m, n, d, k, lo - 1)
-    assert seen == {K.KNN_PATH_MFMA_SPLIT, K.KNN_PATH_MFMA_PACKED}
+    assert seen == {K.KNN_PATH_MFMA_SPLIT, K.KNN_PATH_MFMA_PACKED, K.KNN_PATH_MFMA_WIDE}
 
 
 def test_l1_path_accounts_for_the_transposed_queries():
