@@ -113,10 +113,10 @@ constexpr int64_t kWdMinQueries = 2048;
 constexpr int kWdMaxSplits = 32;
 constexpr int kWdMaxK = 512;                          // larger k: the split path (LDS)
 // LDS bytes of a workgroup: two stage buffers of the points' operands, two tiles of norms, the
-// candidate buffers, six words of state per query, a few control words, the merge scratch of each wave
+// candidate buffers, seven words of state per query, a few control words, the merge scratch of each wave
 constexpr inline int64_t wd_lds_bytes(int k) {
     return (int64_t)2 * kWdW * 4 * 1024 + 2 * kWdTileX * 4 + (int64_t)kWdTileQ * kWdCand * 4 +
-           6 * kWdTileQ * 4 + 64 + (int64_t)kWdWaves * (2 * kWave + 2 * k) * 4;
+           7 * kWdTileQ * 4 + 64 + (int64_t)kWdWaves * (2 * kWave + 2 * k) * 4;
 }
 static_assert(wd_lds_bytes(kWdMaxK) <= kPkLdsBytes, "the largest k must fit the LDS");
 

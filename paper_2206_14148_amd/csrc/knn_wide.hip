@@ -72,7 +72,8 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
     float* const cross_l = qn_l + TQ;   // [TQ] allowance for the rounded operands
     float* const own_l = cross_l + TQ;  // [TQ] k-th key of the query's list in this range
     float* const cap_l = own_l + TQ;    // [TQ] lowest bound of the query's k-th key seen in tsh
-    int* const co_cnt = reinterpret_cast<int*>(cap_l + TQ);  // [TQ] what a stop has to do for the query
+    float* const fbest_l = cap_l + TQ;  // [TQ] smallest filter key the query has met in this range
+    int* const co_cnt = reinterpret_cast<int*>(fbest_l + TQ);  // [TQ] what a stop has to do for the query
     int* const co_queue = co_cnt + TQ;                       // [TQ]
     int* const co_n = co_queue + TQ;                         // [1]
     int* const co_stop = co_n + 1;                           // [3]
@@ -147,9 +148,7 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
             if (active && !init_mine) {
                 const size_t lb = ((size_t)r * S + s) * k;
                 own = a.lk[lb + (k - 1)];
-                if (h == 0)
-                    __hip_atomic_store(a.tsr + (size_t)r * S + s, key_word(a.lk[lb + pos_s]), __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
+                if (h == 0) atomicMin(a.tsr + (size_t)r * S + s, key_word(a.lk[lb + pos_s]));
             }
             const float cap =
                 word_key(__hip_atomic_load(a.tsh + rc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
@@ -158,19 +157,84 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
                 cross_l[q] = cross;
                 own_l[q] = own;
                 cap_l[q] = cap;
+                fbest_l[q] = kInf;
             }
             tauf[t] = key_bound(fminf(own, cap), qn, cross);
             cnt[t] = 0;
         }
     }
 
+    // Row indices for the rare paths are passed through this: addresses formed from them are then
+    // computed where they are used instead of once before the search loop, where each would
+    // occupy two registers all through it.
+    auto here = [](int v) {
+        asm volatile("" : "+v"(v));
+        return v;
+    };
+    // An upper bound of a pair's exact key from its filter key fk: the allowance of the filter with
+    // the bound itself in place of tau in the rounding term and that term doubled (the filter key
+    // may be off in either direction).
+    auto exact_bound = [&](float fk, float qn, float cross) {
+        const float base = fk + qn;
+        return base + (cross + 2.f * e_sum * (xmax + qn + fabsf(base) + cross) + 0x1p-126f);
+    };
+    // What the S ranges of query r know together.  Range s' publishes in tsr an upper bound b_s' of
+    // the key at position pos_s of its list - pos_s + 1 of its points lie at or below it - and the
+    // ranges hold different points, so with need = ceil(k / (pos_s + 1)) <= S the need-th smallest
+    // of the S values has at least k points at or below it: an upper bound of the k-th smallest
+    // key over all points, as tight as one list over everything the ranges have seen would give
+    // (a range finds its (k / S)-th best where the whole stream's k-th best lies).  The whole
+    // wave calls this; `mine` is this range's own value; +inf: not enough ranges have published.
+    const int need_s = (k + pos_s) / (pos_s + 1);
+    auto union_bound = [&](int r, float mine, int ln) {
+        float v = kInf;
+        if (ln < S) {
+            v = word_key(__hip_atomic_load(a.tsr + (size_t)r * S + ln, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            if (ln == s) v = fminf(v, mine);
+        }
+        int rank = 0;
+        for (int t2 = 0; t2 < S; ++t2) {
+            const float o = __shfl(v, t2);
+            rank += (o < v || (o == v && t2 < ln)) ? 1 : 0;
+        }
+        const uint64_t hit = __builtin_amdgcn_ballot_w64(ln < S && rank == need_s - 1);
+        return __shfl(v, __builtin_ctzll(hit | (1ull << 63)));  // (lane 63 holds +inf unless S = 64)
+    };
+
+    // The same per lane, for the periodic look at the other ranges between stops: the need-th
+    // smallest of S values is the (S - need + 1)-th largest, found by keeping the four largest
+    // (shapes that would need more keep to the stops' refresh).
+    const int m_top = S - need_s + 1;
+    auto union_bound_lane = [&](int r) {
+        float t1 = -kInf, t2 = -kInf, t3 = -kInf, t4 = -kInf;
+        const unsigned* p = a.tsr + (size_t)r * S;
+        for (int s2 = 0; s2 < S; s2 += 4) {
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float w =
+                    word_key(__hip_atomic_load(p + min(s2 + i, S - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                v[i] = s2 + i < S ? w : -kInf;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float c = v[i], n;
+                n = fmaxf(t1, c); c = fminf(t1, c); t1 = n;
+                n = fmaxf(t2, c); c = fminf(t2, c); t2 = n;
+                n = fmaxf(t3, c); c = fminf(t3, c); t3 = n;
+                t4 = fmaxf(t4, c);
+            }
+        }
+        return m_top == 1 ? t1 : m_top == 2 ? t2 : m_top == 3 ? t3 : t4;
+    };
+
     // ---- the stop: between two tiles, accumulators dead, every wave of the workgroup here ----
     // Queries with at least `share` buffered pairs (everything: any) and those whose buffer
     // overflowed in the tile that just ended are dealt out over the eight waves: exact keys of
     // the buffered pairs, for an overflowed query then of all points of the tile (what the
     // buffer took of that tile was dropped again), merged into the list; the range's new key at
-    // position pos_s goes to tsr, and the bound that follows from all ranges' keys there - at
-    // least k points lie at or below the largest of them - to tsh.
+    // position pos_s goes to tsr, and the bound that follows from all ranges' values there
+    // (union_bound) to tsh.
     auto stop_work = [&](int tile_base, bool everything) __attribute__((always_inline)) {
         // The lane index is taken afresh here, in a form the compiler cannot move: what a stop
         // derives from it would otherwise be computed before the search loop and occupy
@@ -214,16 +278,9 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
             if (merged) {
                 if (ln == 0) {
                     own_l[q] = __uint_as_float(t_bits);
-                    __hip_atomic_store(a.tsr + (size_t)r * S + s, key_word(key_s), __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
+                    atomicMin(a.tsr + (size_t)r * S + s, key_word(key_s));
                 }
-                float m = -kInf;
-                if (ln < S)
-                    m = ln == s ? key_s
-                                : word_key(__hip_atomic_load(a.tsr + (size_t)r * S + ln, __ATOMIC_RELAXED,
-                                                             __HIP_MEMORY_SCOPE_AGENT));
-#pragma unroll
-                for (int sft = 32; sft > 0; sft >>= 1) m = fmaxf(m, __shfl_xor(m, sft));
+                const float m = union_bound(r, key_s, ln);
                 if (ln == 0 && m < kInf) atomicMin(a.tsh + r, key_word(m));
             }
         }
@@ -247,6 +304,8 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
     // exact keys <= f + qn + allowance - an upper bound of the k-th smallest, as good a threshold
     // as one from a full list.  f is narrowed by quartering [lowest, highest finite key] five
     // times while keeping count(<= upper end) >= k; the two halves of the wave hold 64 keys each.
+    // The same search for pos_s + 1 keys gives the value this range publishes in tsr until its
+    // list has entries.
     auto seed_from_tile = [&](int t, const f32x16 (&acc)[4]) {
         // (counts are kept as floats: their additions are not reassociated, so the compiler
         // forms one short chain per count instead of a tree over 64 compare results at a time)
@@ -265,37 +324,47 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
         hi = fmaxf(hi, lane_xor<32>(hi));
         nv += lane_xor<32>(nv);
         const float kf = (float)k;
+        const float lo0 = lo, hi0 = hi;
+        float f[2];  // f[0]: at least k keys are <= it; f[1]: at least pos_s + 1 keys are
 #pragma nounroll
-        for (int it = 0; it < 5; ++it) {
-            const float q1 = lo + 0.25f * (hi - lo), q2 = lo + 0.5f * (hi - lo), q3 = lo + 0.75f * (hi - lo);
-            float c1 = 0.f, c2 = 0.f, c3 = 0.f;
+        for (int which = 0; which < 2; ++which) {
+            const float want = which == 0 ? kf : (float)(pos_s + 1);
+            lo = lo0;
+            hi = hi0;
+#pragma nounroll
+            for (int it = 0; it < 5; ++it) {
+                const float q1 = lo + 0.25f * (hi - lo), q2 = lo + 0.5f * (hi - lo), q3 = lo + 0.75f * (hi - lo);
+                float c1 = 0.f, c2 = 0.f, c3 = 0.f;
 #pragma unroll
-            for (int pb = 0; pb < 4; ++pb)
+                for (int pb = 0; pb < 4; ++pb)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float v = acc[pb][e];
-                    c1 += (v <= q1) ? 1.f : 0.f;
-                    c2 += (v <= q2) ? 1.f : 0.f;
-                    c3 += (v <= q3) ? 1.f : 0.f;
-                }
-            c1 += lane_xor<32>(c1);
-            c2 += lane_xor<32>(c2);
-            c3 += lane_xor<32>(c3);
-            if (c1 >= kf) hi = q1;
-            else if (c2 >= kf) { lo = q1; hi = q2; }
-            else if (c3 >= kf) { lo = q2; hi = q3; }
-            else lo = q3;
+                    for (int e = 0; e < 16; ++e) {
+                        const float v = acc[pb][e];
+                        c1 += (v <= q1) ? 1.f : 0.f;
+                        c2 += (v <= q2) ? 1.f : 0.f;
+                        c3 += (v <= q3) ? 1.f : 0.f;
+                    }
+                c1 += lane_xor<32>(c1);
+                c2 += lane_xor<32>(c2);
+                c3 += lane_xor<32>(c3);
+                if (c1 >= want) hi = q1;
+                else if (c2 >= want) { lo = q1; hi = q2; }
+                else if (c3 >= want) { lo = q2; hi = q3; }
+                else lo = q3;
+            }
+            f[which] = hi;
         }
-        // the allowance of the filter with the bound itself in place of tau in the rounding
-        // term and that term doubled (the filter key may be off in either direction)
+        if (pos_s == 0) f[1] = lo0;  // (the tile's smallest key itself)
         const int q = wave_q0 + 32 * t + i32;
         const float qn = qn_l[q], cross = cross_l[q];
-        const float base = hi + qn;
-        const float bound = base + (cross + 2.f * e_sum * (xmax + qn + fabsf(base) + cross) + 0x1p-126f);
+        const float bound = exact_bound(f[0], qn, cross);
         if (tauf[t] == kInf && nv >= kf && bound < kInf) {
             if (h == 0) {
+                const int r = here(wg_row0 + q);  // (tauf == +inf: the lane holds a query)
                 cap_l[q] = bound;
-                atomicMin(a.tsh + min(wg_row0 + q, a.rows - 1), key_word(bound));
+                atomicMin(a.tsh + r, key_word(bound));
+                // and what the other ranges may count on: pos_s + 1 points of this range at or below
+                atomicMin(a.tsr + (size_t)r * S + s, key_word(exact_bound(f[1], qn, cross)));
             }
             tauf[t] = key_bound(bound, qn, cross);
         }
@@ -314,6 +383,18 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
         }
         if (__builtin_amdgcn_ballot_w64(fminf(fminf(mb[0], mb[1]), fminf(mb[2], mb[3])) < tauf[t]) == 0) return;
         if (__builtin_amdgcn_ballot_w64(tauf[t] == kInf) != 0) seed_from_tile(t, acc);
+        if (pos_s == 0) {
+            // Ranges that publish the bound of their BEST key (k <= S): a smaller filter key than any
+            // before bounds it anew, without waiting for the pair's exact evaluation.
+            float tm = fminf(fminf(mb[0], mb[1]), fminf(mb[2], mb[3]));
+            tm = fminf(tm, lane_xor<32>(tm));
+            const int q = wave_q0 + 32 * t + i32;
+            if (h == 0 && tm < fbest_l[q]) {
+                fbest_l[q] = tm;
+                atomicMin(a.tsr + (size_t)here(min(wg_row0 + q, a.rows - 1)) * S + s,
+                          key_word(exact_bound(tm, qn_l[q], cross_l[q])));
+            }
+        }
         int* const wci = ci + (wave_q0 + 32 * t) * C;
         // (formed here, behind a barrier to code motion: the compiler would otherwise keep the
         // sums of h * 4 and the 64 row offsets in registers all through the search loop)
@@ -454,7 +535,7 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
         // ahead of the tile's last stage, used behind it.
 #pragma unroll
         for (int t = 0; t < NT; ++t)
-            others[t] = __hip_atomic_load(a.tsh + min(wave_row0 + 32 * t + i32, a.rows - 1), __ATOMIC_RELAXED,
+            others[t] = __hip_atomic_load(a.tsh + here(min(wave_row0 + 32 * t + i32, a.rows - 1)), __ATOMIC_RELAXED,
                                           __HIP_MEMORY_SCOPE_AGENT);
     };
     int par0 = 0;  // LDS buffer of the tile's first stage
@@ -484,6 +565,35 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
         }
 #pragma unroll
         for (int t = 0; t < NT; ++t) epilogue(t, acc[t], tile_base);
+        if ((tile & 7) == 7 && m_top <= 4) {
+            // Every eighth tile (accumulators dead): what all ranges of the lane's queries have
+            // published by now.  The lower half of the wave looks for the first query set, the
+            // upper for the second.
+            static_assert(NT == 2, "one query set per half wave");
+            const float mine = union_bound_lane(here(min(wave_row0 + 32 * h + i32, a.rows - 1)));
+            const float oth = lane_xor<32>(mine);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int q = wave_q0 + 32 * t + i32;
+                const float cap = fminf(cap_l[q], (h == t) ? mine : oth);
+                if (h == 0) cap_l[q] = cap;
+                tauf[t] = key_bound(fminf(own_l[q], cap), qn_l[q], cross_l[q]);
+            }
+        }
+        if (tile == 1) {
+            // Every range of these queries has been through its first tile by now (they start
+            // together) and has left a first value in tsr: what follows from all of them bounds
+            // every range long before the first lists are full.  One query at a time, the wave's
+            // lanes reading the S words.
+            for (int qq = 0; qq < 32 * NT; ++qq) {
+                const int r = wave_row0 + qq;
+                if (r >= a.rows) break;
+                const float mine = word_key(
+                    __hip_atomic_load(a.tsr + (size_t)r * S + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                const float m = union_bound(r, mine, lane);
+                if (lane == 0 && m < kInf) atomicMin(a.tsh + r, key_word(m));
+            }
+        }
         // The barrier that ends the tile carries the vote on stopping as well: one word per tile
         // in turn, set before the barrier, read behind it, cleared behind the next one.  The
         // range's last tile ends with a stop that empties every buffer.

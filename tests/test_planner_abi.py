@@ -239,7 +239,7 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
             assert p.norms_bytes == up(4 * n64) + 256 + up(p.slab_points * nch_p * 32)
             assert p.tile_q == 512 and p.tile_x == 128 and 1 <= p.n_splits <= 32
             # the workgroup's LDS: stage buffers, norms, candidate buffers, state, control, merge scratch
-            assert 16384 + 1024 + 512 * 32 * 4 + 6 * 512 * 4 + 64 + 8 * (128 + 2 * k) * 4 <= 160 * 1024
+            assert 16384 + 1024 + 512 * 32 * 4 + 7 * 512 * 4 + 64 + 8 * (128 + 2 * k) * 4 <= 160 * 1024
         else:
             assert p.path == K.KNN_PATH_MFMA_SPLIT and p.tile_q == 256
             assert p.norms_bytes == up(4 * n) + 256
