@@ -218,13 +218,15 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
         // (the header's second word: the points' largest bf16 rounding residual, which the
         // filters' allowance is built from; not used by the cosine metric)
         e = launch_header_init(hdr, stream);
-        if (e == hipSuccess)
+        // (one slab: the copy is made here, once for all query chunks, and the pass that makes it
+        // takes the norms and the largest rounding residual along)
+        const bool copy_now = packed && plan.slab_points >= (int64_t)n64;
+        if (e == hipSuccess && copy_now)
+            e = launch_pack_operands(X, ldx, n, d, 0, (int64_t)n64, xp, stream, 1.f, xn, hdr);
+        if (e == hipSuccess && !copy_now)
             e = launch_row_norms(X, ldx, n, d, cosine, xn, stream, cosine ? nullptr : hdr + 4);
         if (e == hipSuccess) e = launch_max_norm(xn, n, hdr, stream);
         if (e == hipSuccess && packed) e = launch_pad_norms(xn, n, stream);
-        // (one slab: the copy is made here, once for all query chunks)
-        if (e == hipSuccess && packed && plan.slab_points >= (int64_t)n64)
-            e = launch_pack_operands(X, ldx, n, d, 0, (int64_t)n64, xp, stream);
         if (e != hipSuccess) {
             drop_bracket(t0);
             return hip_fail(e, "row norms launch");

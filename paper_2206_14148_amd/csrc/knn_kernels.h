@@ -66,7 +66,10 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
 // 16 < d <= 256 with the points rounded to bf16 in the workspace (knn_packed.hip).
 //   launch_pack_operands  xp = `points` points from j_first on (j_first and points multiples of
 //                         64; rows past n are zero), pk_padded_chunks(d) x 32 bytes per point;
-//                         scale = -2 packs queries as B operands (n = their number)
+//                         scale = -2 packs queries as B operands (n = their number); xn != null
+//                         (16-byte aligned rows only): the same pass also writes the rows'
+//                         squared norms to xn[j_first ..] and raises hdr word 1 to the largest
+//                         squared norm of a rounding residual, as launch_row_norms would
 //   launch_pad_norms      xn[n .. next multiple of 64) = +inf
 //   launch_packed         the search of points [j_first, j_end) (j_first a multiple of 64) out of
 //                         the copy xp whose first point is slab_first, for queries whose B
@@ -78,7 +81,8 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
 //                         every range's list, through which the ranges bound each other.
 //                         Rows must be 16-byte aligned (packed_rows_aligned).
 hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, int64_t j_first,
-                                int64_t points, void* xp, hipStream_t stream, float scale = 1.f);
+                                int64_t points, void* xp, hipStream_t stream, float scale = 1.f,
+                                float* xn = nullptr, void* hdr = nullptr);
 hipError_t launch_pad_norms(float* xn, int64_t n, hipStream_t stream);
 //   launch_seed_thresholds  tsh[r] = min(tsh[r], an upper bound of query r's k-th smallest distance
 //                         found from the filter keys of seed_points points spread over the packed

@@ -65,6 +65,91 @@ __global__ __launch_bounds__(256) void knn_pack_operands_kernel(const float* __r
     Xp[((size_t)(st * 2 + pb) * nch + c) * 64 + h * 32 + i32] = w;
 }
 
+// The same copy for rows that are 16-byte aligned, a row block of 32 points per workgroup, through
+// LDS: each of the four waves reads eight rows (32 bytes a lane, whole rows at a stretch) and
+// writes their rounded pieces into the block's operands in LDS; the block's operands - nch KB in a
+// row in the copy - then go out as whole 1 KB stores.  Rows longer than kPbSeg chunks take several
+// passes.  NORMS: the squared norms of the rows (one fma chain per lane over its pieces, lanes added
+// up by a butterfly: a fixed order) go to xn, and the largest squared norm of a rounding residual
+// x - bf16(x) to hdr[1] - the pass over X that knn_row_norms_kernel would otherwise repeat.
+constexpr int kPbSeg = 32;               // chunks per pass
+constexpr int kPbOperandStride = 64 + 2; // uint4 per operand in LDS (a half of 32 rows + one: no bank conflicts)
+template <bool NORMS>
+__global__ __launch_bounds__(256) void knn_pack_block_kernel(const float* __restrict__ X, int64_t ldx, int n,
+                                                             int d, int nch, int j_first, int nblocks,
+                                                             float scale, uint4* __restrict__ Xp,
+                                                             float* __restrict__ xn, unsigned* __restrict__ hdr) {
+    __shared__ uint4 ops[kPbSeg * kPbOperandStride];
+    __shared__ float wmax[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float worst = 0.f;
+    for (int blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
+        float acc[8], res[8];
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr) acc[rr] = res[rr] = 0.f;
+        for (int c0 = 0; c0 < nch; c0 += kPbSeg) {
+            const int cs = min(kPbSeg, nch - c0);
+            for (int m = lane; m < 2 * cs; m += 64) {  // piece m of the pass: chunk c0 + m / 2, half m % 2
+                const int col = c0 * 16 + m * 8;
+                f32x4 v0[8], v1[8];
+#pragma unroll
+                for (int rr = 0; rr < 8; ++rr) {
+                    const int j = j_first + blk * 32 + wave * 8 + rr;
+                    v0[rr] = load_row4<true>(X, ldx, j, n, col, d);
+                    v1[rr] = load_row4<true>(X, ldx, j, n, col + 4, d);
+                }
+#pragma unroll
+                for (int rr = 0; rr < 8; ++rr) {
+                    const bool ok = j_first + blk * 32 + wave * 8 + rr < n;
+                    const f32x4 a0 = mask_row4(v0[rr], ok, col, d, scale);
+                    const f32x4 a1 = mask_row4(v1[rr], ok, col + 4, d, scale);
+                    if (NORMS) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            acc[rr] = fmaf(a0[e], a0[e], acc[rr]);
+                            const float r = bf16_residual(a0[e]);
+                            res[rr] = fmaf(r, r, res[rr]);
+                        }
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            acc[rr] = fmaf(a1[e], a1[e], acc[rr]);
+                            const float r = bf16_residual(a1[e]);
+                            res[rr] = fmaf(r, r, res[rr]);
+                        }
+                    }
+                    const uint4 w = {round_pair(a0[0], a0[1]), round_pair(a0[2], a0[3]), round_pair(a1[0], a1[1]),
+                                     round_pair(a1[2], a1[3])};
+                    ops[(m >> 1) * kPbOperandStride + (m & 1) * 33 + wave * 8 + rr] = w;
+                }
+            }
+            __syncthreads();
+            for (int c = wave; c < cs; c += 4)
+                Xp[((size_t)blk * nch + c0 + c) * 64 + lane] = ops[c * kPbOperandStride + (lane >> 5) * 33 + (lane & 31)];
+            __syncthreads();
+        }
+        if (NORMS) {
+#pragma unroll
+            for (int rr = 0; rr < 8; ++rr) {
+                float a = acc[rr], r = res[rr];
+#pragma unroll
+                for (int sft = 32; sft > 0; sft >>= 1) {
+                    a += __shfl_xor(a, sft);
+                    r += __shfl_xor(r, sft);
+                }
+                const int j = j_first + blk * 32 + wave * 8 + rr;
+                if (lane == 0 && j < n) xn[j] = a;
+                worst = fmaxf(worst, r);
+            }
+        }
+    }
+    if (NORMS) {  // one atomic per workgroup (they all go to the same word)
+        if (lane == 0) wmax[wave] = worst;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            atomicMax(hdr + 1, __float_as_uint(fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]))));
+    }
+}
+
 // norms past n (up to the end of the last step) are +inf: such a row never passes the filter
 __global__ void knn_pad_norms_kernel(float* __restrict__ xn, int n, int n_pad) {
     const int i = n + blockIdx.x * 64 + threadIdx.x;
@@ -720,17 +805,28 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
 }  // namespace
 
 hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, int64_t j_first,
-                                int64_t points, void* xp, hipStream_t stream, float scale) {
+                                int64_t points, void* xp, hipStream_t stream, float scale, float* xn,
+                                void* hdr) {
     const int nch = pk_padded_chunks(d);
+    const bool aligned = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 4 == 0) && (d % 4 == 0);
+    if (xn && (!aligned || !hdr)) return hipErrorInvalidValue;
+    if (aligned) {
+        const int nblocks = (int)(points / 32);
+        const dim3 grid((unsigned)(nblocks < 16384 ? nblocks : 16384));
+        if (xn)
+            knn_pack_block_kernel<true><<<grid, dim3(256), 0, stream>>>(X, ldx, (int)n, d, nch, (int)j_first, nblocks,
+                                                                         scale, static_cast<uint4*>(xp), xn,
+                                                                         static_cast<unsigned*>(hdr));
+        else
+            knn_pack_block_kernel<false><<<grid, dim3(256), 0, stream>>>(X, ldx, (int)n, d, nch, (int)j_first,
+                                                                          nblocks, scale, static_cast<uint4*>(xp),
+                                                                          nullptr, nullptr);
+        return hipGetLastError();
+    }
     const int64_t pieces = points * nch * 2;
     const dim3 grid((unsigned)((pieces + 255) / 256));
-    const bool aligned = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 4 == 0) && (d % 4 == 0);
-    if (aligned)
-        knn_pack_operands_kernel<true><<<grid, dim3(256), 0, stream>>>(X, ldx, (int)n, d, nch, (int)j_first,
-                                                                       pieces, scale, static_cast<uint4*>(xp));
-    else
-        knn_pack_operands_kernel<false><<<grid, dim3(256), 0, stream>>>(X, ldx, (int)n, d, nch, (int)j_first,
-                                                                        pieces, scale, static_cast<uint4*>(xp));
+    knn_pack_operands_kernel<false><<<grid, dim3(256), 0, stream>>>(X, ldx, (int)n, d, nch, (int)j_first,
+                                                                    pieces, scale, static_cast<uint4*>(xp));
     return hipGetLastError();
 }
 
