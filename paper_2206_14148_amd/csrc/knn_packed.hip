@@ -169,9 +169,9 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 // and highest filter key, then kSeedIters passes quarter the interval [lo, hi] keeping
 // count(f <= hi) >= k.  The bound goes into tsh (atomic minimum on the order-preserving word).
 constexpr int kSeedIters = 4;
-constexpr int kSeedSets = 2;  // sets of 32 queries per wave: one fetch of a step's operands serves both
+constexpr int kSeedSets = 1;  // sets of 32 queries per wave
 template <int NCH>
-__global__ __launch_bounds__(256) void knn_seed_kernel(const uint4* __restrict__ Xp, const float* __restrict__ xn,
+__global__ __launch_bounds__(256, 2) void knn_seed_kernel(const uint4* __restrict__ Xp, const float* __restrict__ xn,
                                                        const uint4* __restrict__ Qs,
                                                        const float* __restrict__ qnorm,
                                                        const unsigned* __restrict__ hdr,
@@ -208,10 +208,17 @@ __global__ __launch_bounds__(256) void knn_seed_kernel(const uint4* __restrict__
                     acc[t][1][g * 4 + e] = t1[e];
                 }
         }
+        // (all of the step's operands are requested before the first is used: one wait a step)
+        u32x4 A[2][NCH];
+#pragma unroll
+        for (int pb = 0; pb < 2; ++pb)
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) A[pb][c] = p[(pb * NCH + c) * 64];
+        __builtin_amdgcn_sched_barrier(0);  // (or the scheduler moves each load down to its use)
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            const bf16x8 x0 = __builtin_bit_cast(bf16x8, p[c * 64]);
-            const bf16x8 x1 = __builtin_bit_cast(bf16x8, p[(NCH + c) * 64]);
+            const bf16x8 x0 = __builtin_bit_cast(bf16x8, A[0][c]);
+            const bf16x8 x1 = __builtin_bit_cast(bf16x8, A[1][c]);
 #pragma unroll
             for (int t = 0; t < kSeedSets; ++t) {
                 const bf16x8 b = __builtin_bit_cast(bf16x8, bq[t][c]);
