@@ -84,9 +84,17 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
     const int i32 = lane & 31;
     const int h = lane >> 5;
     const int k = a.k, S = a.S;
-    // consecutive workgroups: consecutive query tiles of one range
-    const int s = blockIdx.x / a.tiles;
-    const int wg_row0 = (blockIdx.x - s * a.tiles) * TQ;
+    // Workgroups go to the eight XCDs in turn.  The (query tile, range) pairs, tile by tile, are
+    // dealt out in eight runs, one per XCD, so that the workgroups sharing an L2 work on as few
+    // query tiles as possible: the tiles' B operands (re-read for every 128 points) then stay there.
+    int s, wg_row0;
+    {
+        const int total_wgs = a.tiles * S, xcd = blockIdx.x & 7;
+        const int pair = xcd * (total_wgs >> 3) + min(xcd, total_wgs & 7) + (blockIdx.x >> 3);
+        const int qt = pair / S;
+        s = pair - qt * S;
+        wg_row0 = qt * TQ;
+    }
     const int wave_q0 = wave * (32 * NT);  // the wave's first query within the workgroup
     const int wave_row0 = wg_row0 + wave_q0;
 
@@ -565,10 +573,11 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
         }
 #pragma unroll
         for (int t = 0; t < NT; ++t) epilogue(t, acc[t], tile_base);
-        if ((tile & 7) == 7 && m_top <= 4) {
-            // Every eighth tile (accumulators dead): what all ranges of the lane's queries have
-            // published by now.  The lower half of the wave looks for the first query set, the
-            // upper for the second.
+        if (((tile & 7) == 7 || tile == 1) && m_top <= 4) {
+            // After the second tile (every range has left its first value in tsr by then: they
+            // start together) and every eighth tile from there on, accumulators dead: what all
+            // ranges of the lane's queries have published by now.  The lower half of the wave
+            // looks for the first query set, the upper for the second.
             static_assert(NT == 2, "one query set per half wave");
             const float mine = union_bound_lane(here(min(wave_row0 + 32 * h + i32, a.rows - 1)));
             const float oth = lane_xor<32>(mine);
@@ -580,11 +589,9 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
                 tauf[t] = key_bound(fminf(own_l[q], cap), qn_l[q], cross_l[q]);
             }
         }
-        if (tile == 1) {
-            // Every range of these queries has been through its first tile by now (they start
-            // together) and has left a first value in tsr: what follows from all of them bounds
-            // every range long before the first lists are full.  One query at a time, the wave's
-            // lanes reading the S words.
+        if (tile == 1 && m_top > 4) {
+            // (shapes the per-lane form does not cover: the same look after the second tile,
+            // one query at a time, the wave's lanes reading the S words)
             for (int qq = 0; qq < 32 * NT; ++qq) {
                 const int r = wave_row0 + qq;
                 if (r >= a.rows) break;
