@@ -188,8 +188,11 @@ __global__ __launch_bounds__(256, 2) void knn_seed_kernel(const uint4* __restric
         const int rc = min(row0 + 32 * t + i32, rows - 1);
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
+            // (loaded from a valid chunk, then selected: a conditional load would be made a load
+            // through a selected pointer, with the zeros in private memory)
             const uint4 zero = {0u, 0u, 0u, 0u};
-            bq[t][c] = c < nch_real ? Qs[((size_t)rc * nch_real + c) * 2 + h] : zero;
+            const uint4 v = Qs[((size_t)rc * nch_real + min(c, nch_real - 1)) * 2 + h];
+            bq[t][c] = c < nch_real ? v : zero;
         }
     }
     // keys of one step: acc[t][pb] = query set t against row block pb (as in the search loop of
