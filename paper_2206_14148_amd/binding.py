@@ -183,6 +183,14 @@ def load():
         return _lib
     if not os.path.exists(_build.LIB_PATH):
         _build.build()
+    # The tensors this binding passes are torch's, so the HIP runtime inside torch has to be the
+    # one this library binds to: loaded first, its libamdhip64 satisfies the library's dependency.
+    # (The other way round the process holds two runtimes, and the one the library got sees no
+    # device.)  Planning needs neither.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(_build.LIB_PATH)
     i64, i32, u64, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_void_p
     lib.knn_plan.argtypes = [i64, i64, i32, i32, u64, ctypes.POINTER(PlanStruct)]

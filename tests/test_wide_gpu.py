@@ -85,6 +85,8 @@ CASES = [
     (4, 2049, 65613, 300, 1, "uniform"),     # k = 1, one query in the last tile's last wave
     (5, 2560, 70000, 272, 512, "normal"),    # k = 512
     (6, 3000, 90000, 400, 33, "clustered"),  # 25 chunks -> 26
+    (7, 2048, 65536, 260, 128, "normal"),    # the smallest shape the path takes; k = the points of a tile
+    (8, 2100, 66001, 264, 129, "uniform"),   # k above a tile's points: no bound from the first tile
 ]
 
 
