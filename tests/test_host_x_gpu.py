@@ -65,6 +65,7 @@ CASES = [
     (6, 64, 8_000, 2, 4, "grid", 60_000, "l2"),               # many exact ties across blocks
     (7, 100, 5_000, 300, 3, "normal", 4 * W.MB, "l2"),        # streamed-query kernel per block
     (8, 2100, 400_000, 32, 10, "normal", 60 * W.MB, "l2"),    # packed path per block, thresholds carried on
+    (9, 2100, 300_000, 272, 10, "normal", 300 * W.MB, "l2"),  # wide path per block (5 blocks), the same
 ]
 
 
