@@ -77,7 +77,7 @@ typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1, KNN_METRIC_L1 = 2 } k
                                   points read from that copy in matrix-core operand order; the
                                   lists start under thresholds found from a sample's filter keys.
                                   Same exact test, same keys, same results as path 5. */
-#define KNN_PATH_MFMA_WIDE 7 /* d > 256, squared-Euclidean, k <= 512, m >= 2048, n >= 65536 and room for
+#define KNN_PATH_MFMA_WIDE 7 /* d > 256, squared-Euclidean, k <= 512, m >= 16, n >= 65536 and room for
                                 the points rounded to bf16: the filter of path 5 on tiles of 512
                                 queries x 128 points, both operands read from bf16 copies in
                                 matrix-core operand order; a list without a bound takes its first

@@ -96,7 +96,7 @@ constexpr inline int64_t pk_seed_points(int k) {
     return ((w > kPkSeedMin ? w : kPkSeedMin) + kPkStep - 1) / kPkStep * kPkStep;
 }
 
-// d > 256, squared-Euclidean metric, many points and queries, room for the points rounded to bf16:
+// d > 256, squared-Euclidean metric, many points, room for the points rounded to bf16:
 // tiles of 512 queries x 128 points with both operands streamed from packed bf16 copies
 // (knn_wide.hip).  A workgroup has 8 waves of two query sets each; a pipeline stage covers two
 // chunks of 16 coordinates.
@@ -109,8 +109,9 @@ constexpr int kWdCand = 32;                           // buffered point indices 
 constexpr int kWdShareMin = 20;                       // a stop empties every buffer with at least this many entries
 constexpr int kWdRoom = 4;                            // a buffer with fewer free slots than this calls a stop
 constexpr int64_t kWdMinPoints = 65536;               // fewer points or queries: the split path
-constexpr int64_t kWdMinQueries = 2048;
-constexpr int kWdMaxSplits = 32;
+constexpr int64_t kWdMinQueries = 16;                 // (n = 1e6, d = 784: one query 3.6 ms against the split path's
+                                                      // 3.4, 16 queries 3.9 against 5.7, 256 queries 5.6 against 10.6)
+constexpr int kWdMaxSplits = 64;                      // (a wave's lanes read the ranges' words of a query)
 constexpr int kWdMaxK = 512;                          // larger k: the split path (LDS)
 // LDS bytes of a workgroup: two stage buffers of the points' operands, two tiles of norms, the
 // candidate buffers, seven words of state per query, a few control words, the merge scratch of each wave

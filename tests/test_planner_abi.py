@@ -229,15 +229,15 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
             assert sets * nch_p * 1024 + sets * 32 * (32 * 4 + 28) + waves * (128 + 2 * k) * 4 + waves * 256 + 256 \
                 <= 160 * 1024
         elif p.path == K.KNN_PATH_MFMA_WIDE:
-            # d > 256, k <= 512: the copy as on path 6, tiles of 512 queries x 128 points, at most 32
+            # d > 256, k <= 512: the copy as on path 6, tiles of 512 queries x 128 points, at most 64
             # ranges; the queries' B operands in operand order (rows rounded up to 64, chunk count
             # to an even one)
-            assert d > 256 and k <= 512 and m >= 2048 and n >= 65536 and p.seed_points == 0
+            assert d > 256 and k <= 512 and m >= 16 and n >= 65536 and p.seed_points == 0
             nch_p = (nch + 1) // 2 * 2
             n64 = (n + 63) // 64 * 64
             assert p.slab_points == n64 or (p.slab_points % 8192 == 0 and 131072 <= p.slab_points < n64 and p.q_chunks == 1)
             assert p.norms_bytes == up(4 * n64) + 256 + up(p.slab_points * nch_p * 32)
-            assert p.tile_q == 512 and p.tile_x == 128 and 1 <= p.n_splits <= 32
+            assert p.tile_q == 512 and p.tile_x == 128 and 1 <= p.n_splits <= 64
             # the workgroup's LDS: stage buffers, norms, candidate buffers, state, control, merge scratch
             assert 16384 + 1024 + 512 * 32 * 4 + 7 * 512 * 4 + 64 + 8 * (128 + 2 * k) * 4 <= 160 * 1024
         else:

@@ -1,4 +1,4 @@
-"""GPU parity tests of the wide path (d > 256, at least 2048 queries and 65536 points, k <= 512, room for
+"""GPU parity tests of the wide path (d > 256, at least 16 queries and 65536 points, k <= 512, room for
 the points rounded to bf16): through the C ABI against the CPU oracle on sampled rows, and bit for
 bit against the split path, which the same call takes under a limit too small for the packed copy.
 """
@@ -87,6 +87,8 @@ CASES = [
     (6, 3000, 90000, 400, 33, "clustered"),  # 25 chunks -> 26
     (7, 2048, 65536, 260, 128, "normal"),    # the smallest shape the path takes; k = the points of a tile
     (8, 2100, 66001, 264, 129, "uniform"),   # k above a tile's points: no bound from the first tile
+    (9, 16, 70000, 784, 10, "image"),        # the fewest queries the path takes: one wave holds them all
+    (10, 700, 131072, 300, 20, "normal"),    # two query tiles, 64 ranges
 ]
 
 
@@ -103,7 +105,9 @@ def test_wide_plan_bounds(K):
     # what the path does not take goes to the split path
     big = 8 * 10 ** 9
     assert K.knn_plan(4000, 100000, 300, 513, big).path == K.KNN_PATH_MFMA_SPLIT   # k > 512
-    assert K.knn_plan(2047, 100000, 300, 10, big).path == K.KNN_PATH_MFMA_SPLIT    # few queries
+    assert K.knn_plan(15, 100000, 300, 10, big).path == K.KNN_PATH_MFMA_SPLIT      # few queries
+    assert K.knn_plan(16, 100000, 300, 10, big).n_splits == 48                     # one query tile: ranges of at least 16 point tiles
+    assert K.knn_plan(16, 1000000, 300, 10, big).n_splits == 64                    # at most 64
     assert K.knn_plan(4000, 65535, 300, 10, big).path == K.KNN_PATH_MFMA_SPLIT     # few points
     assert K.knn_plan(4000, 100000, 256, 10, big).path == K.KNN_PATH_MFMA_PACKED   # d <= 256
     assert K.knn_plan(4000, 100000, 300, 10, big, "cosine").path == K.KNN_PATH_MFMA_SPLIT
