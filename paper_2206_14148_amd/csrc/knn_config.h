@@ -65,9 +65,10 @@ constexpr int kPkLdsBytes = 160 * 1024;  // LDS of a gfx950 compute unit
 constexpr int kPkSeedMin = 8192;         // sample of max(this, 8 k) points for the first thresholds
 constexpr int64_t kPkMinPoints = 65536;  // fewer points: not worth packing
 constexpr int64_t kPkSlabGrain = 8192;   // slabs of the packed copy are multiples of this many points
-constexpr int64_t kPkMinQueries = 2048;  // fewer queries: packing all points costs more than it saves
-                                         // (measured: 1000 queries, n = 1e6, d = 64: 3.0 ms against 2.1 on path 5;
-                                         // 2000 queries, n = 2e5, d = 128, k = 100: 4.5 against 10.0)
+constexpr int64_t kPkMinQueries = 64;    // fewer queries: packing all points costs more than it saves
+                                         // (n = 1e6, ms on path 6 against path 5: 64 queries d = 64, k = 10: 1.45 / 1.69;
+                                         // d = 128, k = 100: 3.3 / 9.3; d = 256, k = 32: 3.0 / 5.6; 1000 queries: 1.9 / 2.1,
+                                         // 4.1 / 15.0, 3.2 / 7.7)
 // the chunk counts the kernel is instantiated for (2 .. 8 and the even ones up to 16); others are
 // padded up with zero operands
 constexpr inline int pk_padded_chunks(int d) {

@@ -1,4 +1,4 @@
-"""GPU parity tests of the packed path (16 < d <= 256, at least 2048 queries and 65536 points, room for the points
+"""GPU parity tests of the packed path (16 < d <= 256, at least 64 queries and 65536 points, room for the points
 rounded to bf16): through the C ABI against the CPU oracle on sampled rows, and bit for bit
 against the split path, which the same call takes under a limit too small for the packed copy.
 """
@@ -72,7 +72,9 @@ CASES = [
     (9, 2400, 70000, 192, 12, "normal"),     # 12 chunks
     (10, 2300, 70000, 200, 9, "normal"),     # 13 chunks -> 14
     (11, 2600, 75000, 256, 32, "normal"),    # 16 chunks
-    (12, 2048, 65536, 20, 3, "normal"),      # the smallest shape the path takes, d % 16 != 0
+    (12, 2048, 65536, 20, 3, "normal"),      # the fewest points the path takes, d % 16 != 0
+    (13, 64, 70000, 128, 10, "normal"),      # the fewest queries the path takes
+    (14, 333, 80000, 256, 40, "clustered"),  # a few hundred queries, four-wave shape
 ]
 
 

@@ -216,7 +216,7 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
         seen.add(p.path)
         if p.path == K.KNN_PATH_MFMA_PACKED:
             seed = (max(8192, 8 * k) + 63) // 64 * 64
-            assert 16 < d <= 256 and m >= 2048 and n >= 65536 and n >= 4 * seed and p.seed_points == seed
+            assert 16 < d <= 256 and m >= 64 and n >= 65536 and n >= 4 * seed and p.seed_points == seed
             nch_p = nch if nch <= 8 else (nch + 1) // 2 * 2
             waves = 8 if nch_p <= 8 else 4  # above 8 chunks: four waves of up to 512 registers
             n64 = (n + 63) // 64 * 64
