@@ -292,6 +292,64 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
         if (__builtin_amdgcn_ballot_w64(ovf != 0) != 0) drain(tile_base, false);
     };
 
+    // A query that knows no bound yet (empty list, nothing published by another range) would
+    // accept all 128 points of its first tile, overflow its buffer and have the whole tile
+    // evaluated exactly.  Instead it takes a bound from the filter keys in the accumulators: if at
+    // least k of the tile's keys are <= f, at least k points have exact keys <= f + allowance - an
+    // upper bound of the k-th smallest, as good a threshold as one from a full list.  f is
+    // narrowed by quartering [lowest, highest finite key] five times while keeping
+    // count(<= upper end) >= k; the two halves of the wave hold 64 keys each.  (Counts are kept as
+    // floats: their additions are not reassociated, so the compiler forms one short chain per
+    // count instead of a tree over 64 compare results at a time.)
+    auto seed_from_tile = [&](const f32x16 (&a)[4]) {
+        float lo = kInf, hi = -kInf, nv = 0.f;
+#pragma unroll
+        for (int pb = 0; pb < 4; ++pb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float v = a[pb][e];
+                const bool fin = v < kInf;  // (rows past the range carry +inf)
+                lo = fminf(lo, v);
+                hi = fmaxf(hi, fin ? v : -kInf);
+                nv += fin ? 1.f : 0.f;
+            }
+        lo = fminf(lo, lane_xor<32>(lo));
+        hi = fmaxf(hi, lane_xor<32>(hi));
+        nv += lane_xor<32>(nv);
+        const float kf = (float)k;
+#pragma nounroll
+        for (int it = 0; it < 5; ++it) {
+            const float q1 = lo + 0.25f * (hi - lo), q2 = lo + 0.5f * (hi - lo), q3 = lo + 0.75f * (hi - lo);
+            float c1 = 0.f, c2 = 0.f, c3 = 0.f;
+#pragma unroll
+            for (int pb = 0; pb < 4; ++pb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float v = a[pb][e];
+                    c1 += (v <= q1) ? 1.f : 0.f;
+                    c2 += (v <= q2) ? 1.f : 0.f;
+                    c3 += (v <= q3) ? 1.f : 0.f;
+                }
+            c1 += lane_xor<32>(c1);
+            c2 += lane_xor<32>(c2);
+            c3 += lane_xor<32>(c3);
+            if (c1 >= kf) hi = q1;
+            else if (c2 >= kf) { lo = q1; hi = q2; }
+            else if (c3 >= kf) { lo = q2; hi = q3; }
+            else lo = q3;
+        }
+        // the filter's allowance with the bound itself in place of tau in the rounding term, doubled
+        // where it depends on the key (the filter key may be off in either direction)
+        const float base = hi + qn;
+        const float bound = cosine ? hi + 2.f * (cross_cos + 0x1p-126f)
+                                   : base + (cross + 2.f * e_sum * (xmax + qn + fabsf(base) + cross) + 0x1p-126f);
+        if (tauf == kInf && nv >= kf && bound < kInf) {
+            cap = bound;
+            if (h == 0) atomicMin(tsh + qrow, key_word(bound));
+            tauf = key_bound(bound);
+        }
+    };
+
     // End of a tile, accumulators still live, no calls: keys below the filter threshold are
     // buffered (point index only; the two halves of the wave take consecutive slots).
     // Register e of a lane of half h holds point row 8 (e / 4) + 4 h + e % 4 of its block.
@@ -307,6 +365,12 @@ __global__ __launch_bounds__(512, 2) void knn_split_kernel(
         }
         if (__builtin_amdgcn_ballot_w64(fminf(fminf(mb[0], mb[1]), fminf(mb[2], mb[3])) < tauf) == 0)
             return;
+        // (not in the one shape whose registers it would overflow: 12 resident chunks of aligned
+        // rows; there a first tile is evaluated in full as before)
+        constexpr bool kSeedFits = !(W == 4 && NST == 3 && ALIGNED);
+        if constexpr (kSeedFits) {
+            if (__builtin_amdgcn_ballot_w64(tauf == kInf) != 0) seed_from_tile(a);
+        }
         const int cnt0 = cnt;
 #pragma unroll
         for (int pb = 0; pb < 4; ++pb) {
