@@ -134,6 +134,63 @@ __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
         }
     }
     wave_sync();
+    if (metric == 0 && aligned) {
+        // Squared-Euclidean distances of rows that are 16-byte aligned: eight lanes per winner, so
+        // that a load instruction reads whole 128-byte lines of eight rows (with a lane per winner
+        // every instruction touched 64 rows - here every wave of the chip gathers rows at the same
+        // time, the case in which that costs half the throughput).  Lane t of a winner adds up the
+        // groups of four coordinates t, t + 8, ... in ascending order, one fp64 addition per
+        // coordinate and no contraction; the eight partial sums meet in a butterfly (lane distances
+        // 1, 2, 4).  Four passes of eight winners have their loads in flight together.
+#pragma clang fp contract(off)
+        const int part = lane & 7, wl = lane >> 3;
+        const int ng = d >> 2;
+        const float* qp = Q + (int64_t)r * ldq;
+        for (int w0 = 0; w0 < k; w0 += 32) {
+            double acc[4];
+            const float* xp[4];
+            bool ok[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int w = w0 + 8 * p + wl;
+                const int j = w < k ? wi[w] : -1;
+                ok[p] = (unsigned)j < (unsigned)n;
+                xp[p] = X + (int64_t)(ok[p] ? j : 0) * ldx;
+                acc[p] = 0.0;
+            }
+            for (int g0 = part; g0 < ng; g0 += 16) {
+                f32x4 qv[2], xv[4][2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int g = g0 + 8 * u;
+                    const int gc = g < ng ? g : part;  // a valid group; its value is not used
+                    qv[u] = *reinterpret_cast<const f32x4*>(qp + 4 * gc);
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) xv[p][u] = *reinterpret_cast<const f32x4*>(xp[p] + 4 * gc);
+                }
+#pragma unroll
+                for (int p = 0; p < 4; ++p)
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        if (g0 + 8 * u < ng) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const double diff = (double)qv[u][e] - (double)xv[p][u][e];
+                                acc[p] = acc[p] + diff * diff;
+                            }
+                        }
+                    }
+            }
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                acc[p] = acc[p] + __shfl_xor(acc[p], 1);
+                acc[p] = acc[p] + __shfl_xor(acc[p], 2);
+                acc[p] = acc[p] + __shfl_xor(acc[p], 4);
+                const int w = w0 + 8 * p + wl;
+                if (part == 0 && w < k) wd[w] = ok[p] ? acc[p] : __builtin_huge_val();
+            }
+        }
+    } else
     for (int w = lane; w < k; w += kWave) {
         const int j = wi[w];
         double dist = __builtin_huge_val();
