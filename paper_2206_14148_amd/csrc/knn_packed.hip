@@ -40,10 +40,9 @@ namespace {
 
 // The points of a slab rounded to bf16 in A-operand order: step (64 points) -> row block (32) ->
 // chunk of 16 coordinates -> lane: lane (i32, h) holds coordinates 16 c + 8 h .. + 7 of point
-// 32 pb + i32, zero past d and past n.  One thread per (point, chunk, half): the reads of a
-// wave cover whole rows, the 16-byte writes come in runs of four lanes.  `scale` (a power of two:
+// 32 pb + i32, zero past d and past n.  This kernel serves rows that are not 16-byte aligned (one
+// thread per (point, chunk, half), element-wise loads); aligned rows take knn_pack_block_kernel.  `scale` (a power of two:
 // it commutes with the rounding) is 1 for points and -2 for queries packed as B operands.
-template <bool ALIGNED>
 __global__ __launch_bounds__(256) void knn_pack_operands_kernel(const float* __restrict__ X,
                                                                 int64_t ldx, int n, int d, int nch,
                                                                 int j_first, int64_t pieces,
@@ -57,8 +56,8 @@ __global__ __launch_bounds__(256) void knn_pack_operands_kernel(const float* __r
     const int j = j_first + rel;
     const bool ok = j < n;
     const int col = c * 16 + h * 8;
-    const f32x4 v0 = mask_row4(load_row4<ALIGNED>(X, ldx, j, n, col, d), ok, col, d, scale);
-    const f32x4 v1 = mask_row4(load_row4<ALIGNED>(X, ldx, j, n, col + 4, d), ok, col + 4, d, scale);
+    const f32x4 v0 = mask_row4(load_row4<false>(X, ldx, j, n, col, d), ok, col, d, scale);
+    const f32x4 v1 = mask_row4(load_row4<false>(X, ldx, j, n, col + 4, d), ok, col + 4, d, scale);
     const uint4 w = {round_pair(v0[0], v0[1]), round_pair(v0[2], v0[3]), round_pair(v1[0], v1[1]),
                      round_pair(v1[2], v1[3])};
     const int st = rel >> 6, pb = (rel >> 5) & 1, i32 = rel & 31;
@@ -835,7 +834,7 @@ hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, i
     }
     const int64_t pieces = points * nch * 2;
     const dim3 grid((unsigned)((pieces + 255) / 256));
-    knn_pack_operands_kernel<false><<<grid, dim3(256), 0, stream>>>(X, ldx, (int)n, d, nch, (int)j_first,
+    knn_pack_operands_kernel<<<grid, dim3(256), 0, stream>>>(X, ldx, (int)n, d, nch, (int)j_first,
                                                                     pieces, scale, static_cast<uint4*>(xp));
     return hipGetLastError();
 }

@@ -29,36 +29,6 @@ __device__ __forceinline__ double exact_sqdist(const float* __restrict__ q,
     return acc;
 }
 
-// The same sum in the same order (ascending t, one addition per coordinate, no contraction) for
-// rows that are 16-byte aligned with d a multiple of 4: the coordinates arrive four at a time.
-// A lane walks its own row, so every load instruction of the wave touches 64 different cache
-// lines; with 16 bytes per lane and instruction there are four times fewer of them.
-__device__ __forceinline__ double exact_sqdist_aligned(const float* __restrict__ q,
-                                                       const float* __restrict__ x, int d) {
-#pragma clang fp contract(off)
-    double acc = 0.0;
-    for (int t = 0; t < d; t += 8) {
-        const f32x4 x0 = *reinterpret_cast<const f32x4*>(x + t);
-        const f32x4 q0 = *reinterpret_cast<const f32x4*>(q + t);
-        const bool more = t + 4 < d;
-        const f32x4 x1 = *reinterpret_cast<const f32x4*>(x + (more ? t + 4 : t));
-        const f32x4 q1 = *reinterpret_cast<const f32x4*>(q + (more ? t + 4 : t));
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const double diff = (double)q0[e] - (double)x0[e];
-            acc = acc + diff * diff;
-        }
-        if (more) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const double diff = (double)q1[e] - (double)x1[e];
-                acc = acc + diff * diff;
-            }
-        }
-    }
-    return acc;
-}
-
 // Cosine distance in fp64: 1 - <q,x> / (|q| |x|), clamped at 0; 1 if either vector is zero.
 __device__ __forceinline__ double exact_cosdist(const float* __restrict__ q,
                                                 const float* __restrict__ x, int d) {
@@ -199,8 +169,7 @@ __global__ __launch_bounds__(256) void knn_merge_refine_kernel(
             const float* xp = X + (int64_t)j * ldx;
             dist = metric == 1 ? exact_cosdist(qp, xp, d)
                                : (metric == 2 ? exact_l1dist(qp, xp, d)
-                                              : (aligned ? exact_sqdist_aligned(qp, xp, d)
-                                                         : exact_sqdist(qp, xp, d)));
+                                              : exact_sqdist(qp, xp, d));
         }
         wd[w] = dist;
     }
