@@ -75,15 +75,13 @@ constexpr inline int pk_padded_chunks(int d) {
     const int nch = (d + kSpKC - 1) / kSpKC;
     return nch <= 8 ? nch : (nch + 1) / 2 * 2;
 }
-// Waves per workgroup.  Up to 8 chunks (d <= 128) a wave's state fits 256 registers and two waves
-// share a SIMD; above that the A operands alone take up to 128, so a workgroup has four waves of
-// up to 512 registers, one per SIMD.
-constexpr inline int pk_waves(int nch_padded) { return nch_padded <= 8 ? 8 : 4; }
+constexpr int kPkWaves = 8;              // waves per workgroup, two per SIMD, <= 256 registers each (a wave's A
+                                         // operands take up to 128 of them at d = 256)
 // LDS bytes of a workgroup with `sets` query sets: B operands, candidate buffers, seven words of
 // state per query, the merge scratch of each wave, a few control words
 constexpr inline int64_t pk_lds_bytes(int nch_padded, int k, int sets) {
     return (int64_t)sets * nch_padded * 1024 + (int64_t)sets * 32 * (kPkCand * 4 + 28) +
-           (int64_t)pk_waves(nch_padded) * (2 * kWave + 2 * k) * 4 + (int64_t)pk_waves(nch_padded) * 256 + 256;
+           (int64_t)kPkWaves * (2 * kWave + 2 * k) * 4 + (int64_t)kPkWaves * 256 + 256;
 }
 // most query sets a workgroup can hold (0: the shape does not fit)
 constexpr inline int pk_max_sets(int nch_padded, int k) {

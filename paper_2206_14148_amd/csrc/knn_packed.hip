@@ -13,6 +13,9 @@
 //     life; each of its 8 waves walks its own steps of 64 points, and for every step runs
 //     through all query sets: one 1 KB LDS read feeds two MFMAs, and the accumulators start
 //     from the points' squared norms through the MFMA's C operand, held in registers per step.
+//     A step's operands (up to 128 registers at d = 256) are requested when it begins and are
+//     dead when it ends, so two waves of <= 256 registers share a SIMD at every d and one
+//     computes while the other waits for its operands.
 // The eight waves therefore see different points for the same queries.  Pairs that pass the
 // filter go to per-query buffers in LDS that all waves append to (slots reserved with a
 // compare-and-swap, all of a wave's pairs for a query and step or none); when a buffer runs
@@ -347,9 +350,8 @@ struct PkArgs {
 enum { kCtlStop = 16, kCtlCount = 17, kCtlDone = 18, kCtlNext = 19 };
 
 template <int NCH, bool ALIGNED>
-__global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) void knn_packed_kernel(const PkArgs a) {
+__global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkArgs a) {
     constexpr int C = kPkCand;
-    constexpr int kPkWaves = pk_waves(NCH);  // 8 waves of <= 256 registers, or 4 of <= 512
     constexpr int NT = 64 * kPkWaves;
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
@@ -562,9 +564,8 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
             __hip_atomic_store(ctl + kCtlStop, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     };
 
-    // One query set against the wave's 64 points.  roll: this is the step's last use of the A
-    // operands, and the next step's are requested into the registers as they fall free.
-    auto body = [&](int qs, bool roll, const u32x4* xbase, int st, int parity) {
+    // One query set against the wave's 64 points.
+    auto body = [&](int qs, int st, int parity) {
         const int q = qs * 32 + i32;
         const float tq = tauf_l[q];
         const uint4* bq = Bq + (size_t)qs * (NCH * 64) + lane;
@@ -582,17 +583,6 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
                                                            c == 0 ? XN[0] : acc0, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[1][c]), b,
                                                            c == 0 ? XN[1] : acc1, 0, 0, 0);
-            if (roll) {
-                // (kept in this place: moved up by the scheduler, the next step's operands would
-                // be in flight all through the set.  The compiler still gives them registers of
-                // their own beside the current ones - it does not load into a register that an
-                // MFMA has only just read - which is why more than 8 chunks run with four waves
-                // of up to 512 registers.)
-                __builtin_amdgcn_sched_barrier(0);
-                A[0][c] = xbase[c * 64 + lane];
-                A[1][c] = xbase[(NCH + c) * 64 + lane];
-                __builtin_amdgcn_sched_barrier(0);
-            }
         }
         // minima of the eight groups of four registers, then of all 32: the rare path below only
         // looks into groups that hold a key under some lane's threshold
@@ -607,56 +597,6 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
         if (__builtin_amdgcn_ballot_w64(m < tq) != 0) {
             append(q, tq, acc0, acc1, g, st, parity);
         }
-    };
-
-    // The same for the four-wave shape, where a wave has its SIMD to itself and nothing runs
-    // under its MFMAs unless the wave's own instruction stream offers it: the minima and the
-    // vote of the PREVIOUS set (accumulators p0 / p1, query pq, threshold ptq) are interleaved
-    // with this set's MFMAs, two accumulator sets taking turns.  Returns this set's threshold.
-    auto body_pipe = [&](int qs, f32x16& c0, f32x16& c1, const f32x16& p0, const f32x16& p1, int pq,
-                         float ptq, int st, int parity) {
-        const int q = qs * 32 + i32;
-        const float tq = tauf_l[q];
-        const uint4* bq = Bq + (size_t)qs * (NCH * 64) + lane;
-        constexpr int AH = NCH < 4 ? NCH : 4;
-        uint4 bw[AH];
-#pragma unroll
-        for (int c = 0; c < AH; ++c) bw[c] = bq[c * 64];
-        float g[8];
-#pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            const bf16x8 b = __builtin_bit_cast(bf16x8, bw[c % AH]);
-            if (c + AH < NCH) bw[c % AH] = bq[(c + AH) * 64];
-            c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[0][c]), b,
-                                                         c == 0 ? XN[0] : c0, 0, 0, 0);
-            c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[1][c]), b,
-                                                         c == 0 ? XN[1] : c1, 0, 0, 0);
-            // The previous set's group minima, written in among the first chunks.  (Where they end
-            // up is the compiler's choice - mostly under the last MFMAs - and better left to it:
-            // asked through scheduling group barriers for two MFMAs and five vector instructions
-            // a chunk, it also gave up reading the B operands ahead: 60.3 against 57.7 ms at
-            // d = 256.)
-            if (c < 4) {
-                g[c] = fminf(fminf(fminf(p0[4 * c], p0[4 * c + 1]), p0[4 * c + 2]), p0[4 * c + 3]);
-                g[4 + c] = fminf(fminf(fminf(p1[4 * c], p1[4 * c + 1]), p1[4 * c + 2]), p1[4 * c + 3]);
-            }
-        }
-        const float m = fminf(fminf(fminf(fminf(g[0], g[1]), g[2]), fminf(fminf(g[3], g[4]), g[5])),
-                              fminf(g[6], g[7]));
-        if (__builtin_amdgcn_ballot_w64(m < ptq) != 0) append(pq, ptq, p0, p1, g, st, parity);
-        return tq;
-    };
-    // the last set of a step has nobody behind it: its minima and vote on their own
-    auto tail_pipe = [&](int qs, float tq, const f32x16& p0, const f32x16& p1, int st, int parity) {
-        float g[8];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            g[u] = fminf(fminf(fminf(p0[4 * u], p0[4 * u + 1]), p0[4 * u + 2]), p0[4 * u + 3]);
-            g[4 + u] = fminf(fminf(fminf(p1[4 * u], p1[4 * u + 1]), p1[4 * u + 2]), p1[4 * u + 3]);
-        }
-        const float m = fminf(fminf(fminf(fminf(g[0], g[1]), g[2]), fminf(fminf(g[3], g[4]), g[5])),
-                              fminf(g[6], g[7]));
-        if (__builtin_amdgcn_ballot_w64(m < tq) != 0) append(qs * 32 + i32, tq, p0, p1, g, st, parity);
     };
 
     // A stop: every wave of the workgroup is here, nobody appends.  The queries with enough
@@ -734,70 +674,34 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
         __syncthreads();
     };
 
-    // Every path out of a stop loads the A operands and norms again, so that nothing of them is
-    // live across it (a wave that has no step left loads a valid one for nothing).
+    // A step's A operands and norms are requested when the step begins and are live within it
+    // only: the SIMD's other wave has work meanwhile, and registers that carry operands from one
+    // iteration of the loop into the next get copies of their own from the compiler (requesting
+    // the next step's operands during the last set costs 64 - 128 registers that way and gained
+    // nothing measurable at d = 128; at d = 256 it does not fit two waves per SIMD at all).
+    // Nothing of them is live across a stop either.
     const int step_any = a.step_first;
     int step = take_step();
     bool have = step < step_hi;
-    loadA(have ? step : step_any);
-    spread_xn(a.xn[(size_t)(have ? step : step_any) * kPkStep + lane]);
+    float xn_next = a.xn[(size_t)(have ? step : step_any) * kPkStep + lane];
     int parity = 0;
     bool announced = false;
-    float xn_next = 0.f;
     for (;;) {
         if (have) {
+            loadA(step);
+            spread_xn(xn_next);
             if (lane == 0) ctl[wave * 2 + parity] = step;
             const int taken = take_step();
             const bool has_next = taken < step_hi;
             const int nstep = has_next ? taken : step;
             xn_next = a.xn[(size_t)nstep * kPkStep + lane];
-            const u32x4* xnext =
-                reinterpret_cast<const u32x4*>(a.Xp) + (size_t)(nstep - a.step_slab0) * (2 * NCH * 64);
-            int stop;
-            if constexpr (kPkWaves == 4) {
-                // the next step's operands are requested when the step begins (there are registers
-                // for a second set of them); the sets run through the two-stage pipeline above
-                u32x4 A2[2][NCH];
-#pragma unroll
-                for (int pb = 0; pb < 2; ++pb)
-#pragma unroll
-                    for (int c = 0; c < NCH; ++c) A2[pb][c] = xnext[(pb * NCH + c) * 64 + lane];
-                f32x16 a0, a1, b0, b1;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) b0[e] = b1[e] = kInf;  // "the set before the first": nothing passes
-                float tqa = body_pipe(0, a0, a1, b0, b1, i32, -kInf, step, parity), tqb = -kInf;
-                int qs = 1;
-                for (; qs + 1 < sets; qs += 2) {
-                    tqb = body_pipe(qs, b0, b1, a0, a1, (qs - 1) * 32 + i32, tqa, step, parity);
-                    tqa = body_pipe(qs + 1, a0, a1, b0, b1, qs * 32 + i32, tqb, step, parity);
-                }
-                if (qs < sets) {
-                    tqb = body_pipe(qs, b0, b1, a0, a1, (qs - 1) * 32 + i32, tqa, step, parity);
-                    tail_pipe(qs, tqb, b0, b1, step, parity);
-                } else {
-                    tail_pipe(qs - 1, tqa, a0, a1, step, parity);
-                }
-                stop = __builtin_amdgcn_readfirstlane(
-                    __hip_atomic_load(ctl + kCtlStop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-#pragma unroll
-                for (int pb = 0; pb < 2; ++pb)
-#pragma unroll
-                    for (int c = 0; c < NCH; ++c) A[pb][c] = A2[pb][c];
-            } else {
-                for (int qs = 0; qs + 1 < sets; ++qs) body(qs, false, xnext, step, parity);
-                stop = __builtin_amdgcn_readfirstlane(
-                    __hip_atomic_load(ctl + kCtlStop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-                // (the last set always requests the next step's operands as it goes; a stop reloads
-                // them)
-                body(sets - 1, true, xnext, step, parity);
-            }
+            for (int qs = 0; qs < sets; ++qs) body(qs, step, parity);
+            const int stop = __builtin_amdgcn_readfirstlane(
+                __hip_atomic_load(ctl + kCtlStop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
             step = nstep;
             have = has_next;
             parity ^= 1;
-            if (stop == 0) {
-                spread_xn(xn_next);
-                continue;
-            }
+            if (stop == 0) continue;
         } else if (!announced) {
             if (lane == 0) atomicAdd(ctl + kCtlDone, 1);
             announced = true;
@@ -806,8 +710,6 @@ __global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) == 8 ? 2 : 1) voi
         const bool all_done = ctl[kCtlDone] == kPkWaves;
         stop_work(all_done);
         if (all_done) break;
-        loadA(have ? step : step_any);
-        spread_xn(have ? xn_next : 0.f);
     }
 }
 
@@ -932,7 +834,7 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
     do {                                                                                       \
         hipError_t e2 = raise_lds_limit(knn_packed_kernel<N, true>, lds);                      \
         if (e2 != hipSuccess) return e2;                                                       \
-        knn_packed_kernel<N, true><<<grid, dim3(64 * pk_waves(N)), lds, stream>>>(a);          \
+        knn_packed_kernel<N, true><<<grid, dim3(64 * kPkWaves), lds, stream>>>(a);          \
     } while (0)
     switch (nch) {
         case 2: KNN_PACKED_LAUNCH(2); break;
