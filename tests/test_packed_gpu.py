@@ -74,7 +74,7 @@ CASES = [
     (11, 2600, 75000, 256, 32, "normal"),    # 16 chunks
     (12, 2048, 65536, 20, 3, "normal"),      # the fewest points the path takes, d % 16 != 0
     (13, 64, 70000, 128, 10, "normal"),      # the fewest queries the path takes
-    (14, 333, 80000, 256, 40, "clustered"),  # a few hundred queries, four-wave shape
+    (14, 333, 80000, 256, 40, "clustered"),  # a few hundred queries, d = 256
 ]
 
 
