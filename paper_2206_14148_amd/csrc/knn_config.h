@@ -53,7 +53,7 @@ constexpr int kSpRoom = 4;           // a buffer with fewer free slots than this
 // 16 < d <= 256, squared-Euclidean metric, many points, and room in the workspace for the points
 // rounded to bf16 in matrix-core operand order: the same filter with the roles swapped.  A
 // workgroup keeps the B operands of up to 16 sets of 32 queries in LDS for its whole life; each of
-// its 8 waves streams its own steps of 64 points from the packed copy straight into registers.
+// its waves streams its own steps of 64 points from the packed copy straight into registers.
 constexpr int kPkStep = 64;              // points per wave step (two MFMA row blocks)
 constexpr int kPkMaxD = 256;
 constexpr int kPkMaxSets = 16;           // 512 queries: one thread per query in the stops
@@ -75,13 +75,15 @@ constexpr inline int pk_padded_chunks(int d) {
     const int nch = (d + kSpKC - 1) / kSpKC;
     return nch <= 8 ? nch : (nch + 1) / 2 * 2;
 }
-constexpr int kPkWaves = 8;              // waves per workgroup, two per SIMD, <= 256 registers each (a wave's A
-                                         // operands take up to 128 of them at d = 256)
+// Waves per workgroup.  A wave's state is what it holds of a step - A operands (8 registers a
+// chunk), norms, two accumulators - and fits 168 registers up to 8 chunks (d <= 128): three waves
+// per SIMD; above, up to 256: two.
+constexpr inline int pk_waves(int nch_padded) { return nch_padded <= 8 ? 12 : 8; }
 // LDS bytes of a workgroup with `sets` query sets: B operands, candidate buffers, seven words of
 // state per query, the merge scratch of each wave, a few control words
 constexpr inline int64_t pk_lds_bytes(int nch_padded, int k, int sets) {
     return (int64_t)sets * nch_padded * 1024 + (int64_t)sets * 32 * (kPkCand * 4 + 28) +
-           (int64_t)kPkWaves * (2 * kWave + 2 * k) * 4 + (int64_t)kPkWaves * 256 + 256;
+           (int64_t)pk_waves(nch_padded) * (2 * kWave + 2 * k) * 4 + (int64_t)pk_waves(nch_padded) * 256 + 256;
 }
 // most query sets a workgroup can hold (0: the shape does not fit)
 constexpr inline int pk_max_sets(int nch_padded, int k) {

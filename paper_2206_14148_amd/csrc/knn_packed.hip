@@ -10,13 +10,13 @@
 //     operand with one coalesced 1 KB load straight into registers: no conversion, no LDS
 //     staging, no workgroup barrier in the search loop;
 //   - a workgroup keeps the B operands of up to 16 sets of 32 queries in LDS for its whole
-//     life; each of its 8 waves walks its own steps of 64 points, and for every step runs
-//     through all query sets: one 1 KB LDS read feeds two MFMAs, and the accumulators start
+//     life; each of its waves (12 up to d = 128, 8 above) walks its own steps of 64 points, and
+//     for every step runs through all query sets: one 1 KB LDS read feeds two MFMAs, and the accumulators start
 //     from the points' squared norms through the MFMA's C operand, held in registers per step.
 //     A step's operands (up to 128 registers at d = 256) are requested when it begins and are
-//     dead when it ends, so two waves of <= 256 registers share a SIMD at every d and one
-//     computes while the other waits for its operands.
-// The eight waves therefore see different points for the same queries.  Pairs that pass the
+//     dead when it ends, so three waves of <= 168 registers share a SIMD up to d = 128 and two
+//     of <= 256 above, and the others compute while one waits for its operands.
+// The waves therefore see different points for the same queries.  Pairs that pass the
 // filter go to per-query buffers in LDS that all waves append to (slots reserved with a
 // compare-and-swap, all of a wave's pairs for a query and step or none); when a buffer runs
 // full the workgroup stops at the next step boundary, the queries with enough buffered pairs are
@@ -165,7 +165,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 // that at least k points of a sample have f <= t, at least k points have dd <= t + qn + allowance:
 // an upper bound of the query's k-th smallest distance, as valid a starting threshold as +inf and
 // far tighter - without evaluating a single pair exactly.  (Lists that start from +inf accept
-// every pair until they hold k entries; with eight waves feeding one buffer that phase would be
+// every pair until they hold k entries; with all waves feeding one buffer that phase would be
 // spent in stops.)  The sample is `sample_steps` steps of 64 points spread evenly over the packed
 // copy.  One wave per 64 queries, B operands in registers; a first pass finds the lane's lowest
 // and highest filter key, then kSeedIters passes quarter the interval [lo, hi] keeping
@@ -347,10 +347,11 @@ struct PkArgs {
     int j_valid;      // a valid point index for lanes that hold no candidate
 };
 
-enum { kCtlStop = 16, kCtlCount = 17, kCtlDone = 18, kCtlNext = 19 };
+enum { kCtlStop = 32, kCtlCount = 33, kCtlDone = 34, kCtlNext = 35 };
 
 template <int NCH, bool ALIGNED>
-__global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkArgs a) {
+__global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) / 4) void knn_packed_kernel(const PkArgs a) {
+    constexpr int kPkWaves = pk_waves(NCH);
     constexpr int C = kPkCand;
     constexpr int NT = 64 * kPkWaves;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -373,10 +374,14 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
     int* const cand = reinterpret_cast<int*>(Bq + (size_t)sets * NCH * 64);  // [Qw][C]
     float* const qn_l = reinterpret_cast<float*>(cand + Qw * C);     // [Qw] squared norms
     float* const own_l = qn_l + Qw;      // [Qw] k-th key of the query's list in this range
-    float* const tauf_l = own_l + Qw;    // [Qw] filter thresholds
-    int* const alloc_l = reinterpret_cast<int*>(tauf_l + Qw);  // [Qw] buffered pairs
-    int* const ovf_l = alloc_l + Qw;     // [Qw] bit 2 w + p: wave w found no room in its step of parity p
-    int* const queue_l = ovf_l + Qw;     // [Qw] queries a stop has to serve
+    // [Qw][3] what the search loop touches of a query, side by side so that one address serves
+    // all three (an odd stride in words: no bank conflicts): the filter threshold, the number of
+    // buffered pairs, and bit 2 w + p set where wave w found no room in its step of parity p
+    int* const hot_l = reinterpret_cast<int*>(own_l + Qw);
+    auto tauf_at = [&](int q) -> float& { return *reinterpret_cast<float*>(hot_l + 3 * q); };
+    auto alloc_at = [&](int q) -> int& { return hot_l[3 * q + 1]; };
+    auto ovf_at = [&](int q) -> int& { return hot_l[3 * q + 2]; };
+    int* const queue_l = hot_l + 3 * Qw;  // [Qw] queries a stop has to serve
     float* const cross_l = reinterpret_cast<float*>(queue_l + Qw);  // [Qw] allowance for the rounded operands
     float* const scratch = cross_l + Qw;  // [waves][2 * 64 + 2 k]
     float* const xn_stage = scratch + (size_t)kPkWaves * (2 * kWave + 2 * k);  // [waves][64]
@@ -467,9 +472,9 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
                                    __HIP_MEMORY_SCOPE_AGENT);
         }
         own_l[qq] = own;
-        tauf_l[qq] = active ? key_bound(fminf(own, shared_cap(rc)), qn, cross) : -kInf;
-        alloc_l[qq] = 0;
-        ovf_l[qq] = 0;
+        tauf_at(qq) = active ? key_bound(fminf(own, shared_cap(rc)), qn, cross) : -kInf;
+        alloc_at(qq) = 0;
+        ovf_at(qq) = 0;
     }
     if (tid < 64) ctl[tid] = tid == kCtlNext ? a.step_first + s * a.range_steps : 0;
     if (init_mine) {
@@ -542,9 +547,9 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
                 int j = jb;
                 asm volatile("" : "+v"(j));
                 j += off;
-                const int slot = atomicAdd(&alloc_l[q], 1);
+                const int slot = atomicAdd(&alloc_at(q), 1);
                 if (slot < C) cand[q * C + slot] = j;
-                else atomicOr(&ovf_l[q], 1 << (wave * 2 + parity));
+                else atomicOr(&ovf_at(q), 1 << (wave * 2 + parity));
                 call = call || slot >= C - kPkRoom;
             }
         };
@@ -565,10 +570,10 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
     };
 
     // One query set against the wave's 64 points.
-    auto body = [&](int qs, int st, int parity) {
-        const int q = qs * 32 + i32;
-        const float tq = tauf_l[q];
-        const uint4* bq = Bq + (size_t)qs * (NCH * 64) + lane;
+    auto body = [&](int qs, int st, int parity, int ln) {
+        const int q = qs * 32 + (ln & 31);
+        const float tq = tauf_at(q);
+        const uint4* bq = Bq + (size_t)qs * (NCH * 64) + ln;
         f32x16 acc0, acc1;
         // the B operands are read AH chunks ahead of their use
         constexpr int AH = NCH < 4 ? NCH : 4;
@@ -613,15 +618,15 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
         if (tid == 0) ctl[kCtlStop] = 0;
         const int share = everything ? 1 : kPkShareMin;
         for (int qq = tid; qq < Qw; qq += NT)
-            if (alloc_l[qq] >= share || ovf_l[qq] != 0) queue_l[atomicAdd(ctl + kCtlCount, 1)] = qq;
+            if (alloc_at(qq) >= share || ovf_at(qq) != 0) queue_l[atomicAdd(ctl + kCtlCount, 1)] = qq;
         __syncthreads();
         const int nq = ctl[kCtlCount];
         for (int e = wave; e < nq; e += kPkWaves) {
             const int q = __builtin_amdgcn_readfirstlane(queue_l[e]);
             const int r = wg_row0 + q;
             const size_t lb = ((size_t)r * S + s) * k;
-            const int cc = min(C, __builtin_amdgcn_readfirstlane(alloc_l[q]));
-            unsigned rem = (unsigned)__builtin_amdgcn_readfirstlane(ovf_l[q]);
+            const int cc = min(C, __builtin_amdgcn_readfirstlane(alloc_at(q)));
+            unsigned rem = (unsigned)__builtin_amdgcn_readfirstlane(ovf_at(q));
             unsigned t_bits = __float_as_uint(own_l[q]);
             float key_s = kInf;  // the list's key at position pos_s after the last merge
             bool merged = false;
@@ -659,8 +664,8 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
             }
             if (lane == 0) {
                 own_l[q] = __uint_as_float(t_bits);
-                alloc_l[q] = 0;
-                ovf_l[q] = 0;
+                alloc_at(q) = 0;
+                ovf_at(q) = 0;
                 if (merged)
                     __hip_atomic_store(a.tsr + (size_t)r * S + s, key_word(key_s), __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
@@ -670,7 +675,7 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
         if (tid == 0) ctl[kCtlCount] = 0;
         for (int qq = tid; qq < Qw; qq += NT)
             if (wg_row0 + qq < a.rows)
-                tauf_l[qq] = key_bound(fminf(own_l[qq], shared_cap(wg_row0 + qq)), qn_l[qq], cross_l[qq]);
+                tauf_at(qq) = key_bound(fminf(own_l[qq], shared_cap(wg_row0 + qq)), qn_l[qq], cross_l[qq]);
         __syncthreads();
     };
 
@@ -694,8 +699,12 @@ __global__ __launch_bounds__(64 * kPkWaves, 2) void knn_packed_kernel(const PkAr
             const int taken = take_step();
             const bool has_next = taken < step_hi;
             const int nstep = has_next ? taken : step;
-            xn_next = a.xn[(size_t)nstep * kPkStep + lane];
-            for (int qs = 0; qs < sets; ++qs) body(qs, step, parity);
+            // (the lane index through an empty asm: the addresses that depend on it are then formed
+            // here, step by step, instead of being kept in registers from before the loop)
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+            xn_next = (a.xn + (size_t)nstep * kPkStep)[(unsigned)ln];
+            for (int qs = 0; qs < sets; ++qs) body(qs, step, parity, ln);
             const int stop = __builtin_amdgcn_readfirstlane(
                 __hip_atomic_load(ctl + kCtlStop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
             step = nstep;
@@ -821,7 +830,7 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
     a.step_slab0 = (int)(slab_first / kPkStep);
     a.step_first = (int)(j_first / kPkStep);
     a.step_end = (int)((j_end + kPkStep - 1) / kPkStep);
-    // ranges of whole rounds of the eight waves
+    // ranges of a multiple of eight steps
     const int steps = a.step_end - a.step_first;
     int per = (steps + S - 1) / S;
     per = (per + 7) / 8 * 8;
@@ -834,7 +843,7 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
     do {                                                                                       \
         hipError_t e2 = raise_lds_limit(knn_packed_kernel<N, true>, lds);                      \
         if (e2 != hipSuccess) return e2;                                                       \
-        knn_packed_kernel<N, true><<<grid, dim3(64 * kPkWaves), lds, stream>>>(a);          \
+        knn_packed_kernel<N, true><<<grid, dim3(64 * pk_waves(N)), lds, stream>>>(a);          \
     } while (0)
     switch (nch) {
         case 2: KNN_PACKED_LAUNCH(2); break;
