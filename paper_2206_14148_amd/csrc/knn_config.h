@@ -77,13 +77,19 @@ constexpr inline int pk_padded_chunks(int d) {
 }
 // Waves per workgroup.  A wave's state is what it holds of a step - A operands (8 registers a
 // chunk), norms, two accumulators - and fits 168 registers up to 8 chunks (d <= 128): three waves
-// per SIMD; above, up to 256: two.
-constexpr inline int pk_waves(int nch_padded) { return nch_padded <= 8 ? 12 : 8; }
+// per SIMD; above, up to 256: two.  Every wave has its own merge scratch in LDS (2 k + 128 words),
+// which the query sets pay for: where twelve of them would take more than half the LDS (k > 789)
+// the workgroup has eight waves at every d (measured at d = 128, m = 2e4, n = 1e6, ms with 12 / 8
+// waves: k = 10 .. 700 faster with twelve - 21.3 / 23.5, 17.0 / 19.8 at k = 256, 86.7 / 90.8 at
+// k = 700 - but k = 1024, 4 sets instead of 6: 258 / 169).
+constexpr inline int pk_waves(int nch_padded, int k) {
+    return nch_padded <= 8 && 12 * (2 * kWave + 2 * (int64_t)k) * 4 <= kPkLdsBytes / 2 ? 12 : 8;
+}
 // LDS bytes of a workgroup with `sets` query sets: B operands, candidate buffers, seven words of
 // state per query, the merge scratch of each wave, a few control words
 constexpr inline int64_t pk_lds_bytes(int nch_padded, int k, int sets) {
     return (int64_t)sets * nch_padded * 1024 + (int64_t)sets * 32 * (kPkCand * 4 + 28) +
-           (int64_t)pk_waves(nch_padded) * (2 * kWave + 2 * k) * 4 + (int64_t)pk_waves(nch_padded) * 256 + 256;
+           (int64_t)pk_waves(nch_padded, k) * (2 * kWave + 2 * k) * 4 + (int64_t)pk_waves(nch_padded, k) * 256 + 256;
 }
 // most query sets a workgroup can hold (0: the shape does not fit)
 constexpr inline int pk_max_sets(int nch_padded, int k) {

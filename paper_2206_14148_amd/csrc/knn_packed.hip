@@ -349,9 +349,9 @@ struct PkArgs {
 
 enum { kCtlStop = 32, kCtlCount = 33, kCtlDone = 34, kCtlNext = 35 };
 
-template <int NCH, bool ALIGNED>
-__global__ __launch_bounds__(64 * pk_waves(NCH), pk_waves(NCH) / 4) void knn_packed_kernel(const PkArgs a) {
-    constexpr int kPkWaves = pk_waves(NCH);
+template <int NCH, bool ALIGNED, int WV>
+__global__ __launch_bounds__(64 * WV, WV / 4) void knn_packed_kernel(const PkArgs a) {
+    constexpr int kPkWaves = WV;  // 12 or 8 (pk_waves)
     constexpr int C = kPkCand;
     constexpr int NT = 64 * kPkWaves;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -839,11 +839,17 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
     a.j_valid = (int)j_first;
     const size_t lds = (size_t)pk_lds_bytes(nch, k, sets);
     const dim3 grid((unsigned)(a.tiles * S));
+    const int waves = pk_waves(nch, k);
+#define KNN_PACKED_LAUNCH_W(N, W)                                                              \
+    do {                                                                                       \
+        hipError_t e2 = raise_lds_limit(knn_packed_kernel<N, true, W>, lds);                   \
+        if (e2 != hipSuccess) return e2;                                                       \
+        knn_packed_kernel<N, true, W><<<grid, dim3(64 * W), lds, stream>>>(a);                 \
+    } while (0)
 #define KNN_PACKED_LAUNCH(N)                                                                   \
     do {                                                                                       \
-        hipError_t e2 = raise_lds_limit(knn_packed_kernel<N, true>, lds);                      \
-        if (e2 != hipSuccess) return e2;                                                       \
-        knn_packed_kernel<N, true><<<grid, dim3(64 * pk_waves(N)), lds, stream>>>(a);          \
+        if (waves == 12) KNN_PACKED_LAUNCH_W(N, 12);                                           \
+        else KNN_PACKED_LAUNCH_W(N, 8);                                                        \
     } while (0)
     switch (nch) {
         case 2: KNN_PACKED_LAUNCH(2); break;
@@ -853,12 +859,13 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
         case 6: KNN_PACKED_LAUNCH(6); break;
         case 7: KNN_PACKED_LAUNCH(7); break;
         case 8: KNN_PACKED_LAUNCH(8); break;
-        case 10: KNN_PACKED_LAUNCH(10); break;
-        case 12: KNN_PACKED_LAUNCH(12); break;
-        case 14: KNN_PACKED_LAUNCH(14); break;
-        case 16: KNN_PACKED_LAUNCH(16); break;
+        case 10: KNN_PACKED_LAUNCH_W(10, 8); break;
+        case 12: KNN_PACKED_LAUNCH_W(12, 8); break;
+        case 14: KNN_PACKED_LAUNCH_W(14, 8); break;
+        case 16: KNN_PACKED_LAUNCH_W(16, 8); break;
         default: return hipErrorInvalidValue;
     }
+#undef KNN_PACKED_LAUNCH_W
 #undef KNN_PACKED_LAUNCH
     return hipGetLastError();
 }

@@ -218,7 +218,8 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
             seed = (max(8192, 8 * k) + 63) // 64 * 64
             assert 16 < d <= 256 and m >= 64 and n >= 65536 and n >= 4 * seed and p.seed_points == seed
             nch_p = nch if nch <= 8 else (nch + 1) // 2 * 2
-            waves = 12 if nch_p <= 8 else 8  # three waves per SIMD where their registers allow
+            # three waves per SIMD where their registers allow and their merge scratch takes at most half the LDS
+            waves = 12 if nch_p <= 8 and 12 * (128 + 2 * k) * 4 <= 80 * 1024 else 8
             n64 = (n + 63) // 64 * 64
             # the copy holds all points, or a slab of them (a multiple of 8192 points, at least 65536)
             assert p.slab_points == n64 or (p.slab_points % 8192 == 0 and 131072 <= p.slab_points < n64 and p.q_chunks == 1)
