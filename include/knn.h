@@ -71,7 +71,7 @@ typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1, KNN_METRIC_L1 = 2 } k
                                  rounding; exact fp32 test of the pairs that pass.  (Number 1
                                  was this path's fp32 matrix-core predecessor.) */
 
-#define KNN_PATH_MFMA_PACKED 6 /* 16 < d <= 256, squared-Euclidean, m >= 64, n >= 65536 and room for the
+#define KNN_PATH_MFMA_PACKED 6 /* 8 < d <= 256, squared-Euclidean, m >= 64 (2048 up to d = 16), n >= 65536 and room for the
                                   points rounded to bf16 (32 bytes per point and 16 coordinates):
                                   the filter of path 5 with the queries resident in LDS and the
                                   points read from that copy in matrix-core operand order; the

@@ -50,7 +50,7 @@ constexpr int kSpResidentMaxChunks = 16;  // d <= 256: the queries' B operands s
 constexpr int kSpShareMin = 20;      // when the workgroup stops to empty buffers: all with at least this many entries
 constexpr int kSpRoom = 4;           // a buffer with fewer free slots than this is emptied after the tile
 
-// 16 < d <= 256, squared-Euclidean metric, many points, and room in the workspace for the points
+// 8 < d <= 256, squared-Euclidean metric, many points, and room in the workspace for the points
 // rounded to bf16 in matrix-core operand order: the same filter with the roles swapped.  A
 // workgroup keeps the B operands of up to 16 sets of 32 queries in LDS for its whole life; each of
 // its waves streams its own steps of 64 points from the packed copy straight into registers.
@@ -69,7 +69,9 @@ constexpr int64_t kPkMinQueries = 64;    // fewer queries: packing all points co
                                          // (n = 1e6, ms on path 6 against path 5: 64 queries d = 64, k = 10: 1.45 / 1.69;
                                          // d = 128, k = 100: 3.3 / 9.3; d = 256, k = 32: 3.0 / 5.6; 1000 queries: 1.9 / 2.1,
                                          // 4.1 / 15.0, 3.2 / 7.7)
-// the chunk counts the kernel is instantiated for (2 .. 8 and the even ones up to 16); others are
+constexpr int64_t kPkMinQueriesOneChunk = 2048;  // the same for d <= 16 (n = 1e6, d = 16, k = 10, ms on path 6 / path 5:
+                                                 // 1000 queries 1.59 / 1.37, 1e4 2.21 / 3.40, 1e5 8.6 / 23.1)
+// the chunk counts the kernel is instantiated for (1 .. 8 and the even ones up to 16); others are
 // padded up with zero operands
 constexpr inline int pk_padded_chunks(int d) {
     const int nch = (d + kSpKC - 1) / kSpKC;

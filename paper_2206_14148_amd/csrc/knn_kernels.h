@@ -63,7 +63,7 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
                         int64_t rows, int64_t n, int d, int k, int S, float* lk, int* li,
                         hipStream_t stream);
 
-// 16 < d <= 256 with the points rounded to bf16 in the workspace (knn_packed.hip).
+// 8 < d <= 256 with the points rounded to bf16 in the workspace (knn_packed.hip).
 //   launch_pack_operands  xp = `points` points from j_first on (j_first and points multiples of
 //                         64; rows past n are zero), pk_padded_chunks(d) x 32 bytes per point;
 //                         scale = -2 packs queries as B operands (n = their number); xn != null

@@ -1,4 +1,4 @@
-// gfx950 (CDNA4, MI355X) kNN search for 16 < d <= 256 and many points: the bf16 matrix-core
+// gfx950 (CDNA4, MI355X) kNN search for 8 < d <= 256 and many points: the bf16 matrix-core
 // filter of knn_split.hip with the roles of the operands swapped.
 //
 // The expansion sum x^2 - 2 q.x of paper section 4.1 runs on the values rounded to bf16 and only
@@ -766,6 +766,7 @@ hipError_t launch_seed_thresholds(const float* Q, int64_t ldq, const void* xp, c
         static_cast<const unsigned*>(hdr), Q, ldq, static_cast<unsigned*>(tsh), (int)rows, d, nch_real, k, \
         nsteps, sample_steps)
     switch (nch) {
+        case 1: KNN_SEED_LAUNCH(1); break;
         case 2: KNN_SEED_LAUNCH(2); break;
         case 3: KNN_SEED_LAUNCH(3); break;
         case 4: KNN_SEED_LAUNCH(4); break;
@@ -852,6 +853,7 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
         else KNN_PACKED_LAUNCH_W(N, 8);                                                        \
     } while (0)
     switch (nch) {
+        case 1: KNN_PACKED_LAUNCH(1); break;
         case 2: KNN_PACKED_LAUNCH(2); break;
         case 3: KNN_PACKED_LAUNCH(3); break;
         case 4: KNN_PACKED_LAUNCH(4); break;

@@ -225,12 +225,13 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
             }
         }
     }
-    // 16 < d <= 256 and many points: with room for the points rounded to bf16 in operand order
+    // 8 < d <= 256 and many points: with room for the points rounded to bf16 in operand order
     // the search runs with the queries resident in LDS (knn_packed.hip).  Its workspace is that
     // of path 5 plus the packed copy, so a call whose rows turn out not to be 16-byte aligned
     // still runs under this plan, on path 5's kernel.
-    if (split && metric == KNN_METRIC_L2SQ && d > kSpKC && d <= kPkMaxD &&
-        n >= kPkMinPoints && n >= 4 * pk_seed_points(k) && m >= kPkMinQueries) {
+    if (split && metric == KNN_METRIC_L2SQ && d <= kPkMaxD &&
+        n >= kPkMinPoints && n >= 4 * pk_seed_points(k) &&
+        m >= (d <= kSpKC ? kPkMinQueriesOneChunk : kPkMinQueries)) {
         const int nch_p = pk_padded_chunks(d);
         const int sets_max = pk_max_sets(nch_p, k);
         const uint64_t n64 = ((uint64_t)n + kPkStep - 1) / kPkStep * kPkStep;

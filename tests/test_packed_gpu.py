@@ -1,4 +1,4 @@
-"""GPU parity tests of the packed path (16 < d <= 256, at least 64 queries and 65536 points, room for the points
+"""GPU parity tests of the packed path (8 < d <= 256, at least 64 queries - 2048 up to d = 16 - and 65536 points, room for the points
 rounded to bf16): through the C ABI against the CPU oracle on sampled rows, and bit for bit
 against the split path, which the same call takes under a limit too small for the packed copy.
 """
@@ -75,6 +75,9 @@ CASES = [
     (12, 2048, 65536, 20, 3, "normal"),      # the fewest points the path takes, d % 16 != 0
     (13, 64, 70000, 128, 10, "normal"),      # the fewest queries the path takes
     (14, 333, 80000, 256, 40, "clustered"),  # a few hundred queries, d = 256
+    (15, 2500, 70000, 16, 10, "normal"),     # one chunk
+    (16, 2048, 66000, 16, 33, "uniform"),    # one chunk, the fewest queries it takes
+    (17, 2300, 90000, 12, 5, "clustered"),   # one chunk, a quarter of it padding
 ]
 
 

@@ -63,7 +63,7 @@ def test_chunk_rows_floor():
 
 
 # (m, n, d, k, limit, path): d <= 8 with room for the packed points takes the low-d matrix-core
-# filter; 16 < d <= 256 with room for the points rounded to bf16 (32 bytes per point and 16
+# filter; 8 < d <= 256 with room for the points rounded to bf16 (32 bytes per point and 16
 # coordinates: 2.56 GB at d = 128, n = 1e7; 1.02 GB at d = 256, n = 2e6) or of a slab of them (at
 # least 65536 points) the packed path
 CONFIGS = [
@@ -147,7 +147,10 @@ def test_low_d_falls_back_to_the_vector_path_when_packed_points_do_not_fit():
     assert K.knn_plan(m, n, 8, k, 10 ** 9).path == K.KNN_PATH_LOWD_BF16
     assert K.knn_plan(m, n, 8, k, 10 ** 9).norms_bytes == 256 + 64 * n
     assert K.knn_plan(m, n, 8, k, 60 * 10 ** 6).path == K.KNN_PATH_LOWD
-    assert K.knn_plan(m, n, 9, k, 10 ** 9).path == K.KNN_PATH_MFMA_SPLIT
+    assert K.knn_plan(m, n, 9, k, 10 ** 9).path == K.KNN_PATH_MFMA_PACKED  # (one chunk: from 2048 queries)
+    assert K.knn_plan(2047, n, 9, k, 10 ** 9).path == K.KNN_PATH_MFMA_SPLIT
+    assert K.knn_plan(m, n, 9, k, 30 * 10 ** 6).slab_points < n  # a slab of the copy
+    assert K.knn_plan(m, n, 9, k, 12 * 10 ** 6).path == K.KNN_PATH_MFMA_SPLIT  # no room for one
     assert K.knn_plan(m, n, 9, k, 10 ** 9, metric="cosine").path == K.KNN_PATH_MFMA_SPLIT
     assert K.knn_plan(m, n, 3, k, 10 ** 9, metric="cosine").path == K.KNN_PATH_MFMA_SPLIT
 
@@ -193,7 +196,7 @@ def test_threshold_seed_grid_is_sized_from_n_and_k_and_paid_for_under_the_limit(
 def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can():
     # paths 5 and 6 (d > 8, squared-Euclidean): per query 32 bytes per 16 coordinates of bf16 B
     # operands, a squared norm and a shared-threshold word, each array 256-aligned; the chunk is
-    # the longest multiple of the query tile that fits with them.  Path 6 (16 < d <= 256, at least
+    # the longest multiple of the query tile that fits with them.  Path 6 (8 < d <= 256, at least 64 queries - 2048 up to d = 16 -,
     # 65536 points and four times the sample its first thresholds come from) adds the points rounded to bf16, 32 bytes
     # per point and 16 coordinates (the chunk count padded to an even one above 8), and pads the
     # norms to a multiple of 64 points; its query tile is 32 x the query sets of a workgroup.
@@ -216,7 +219,7 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
         seen.add(p.path)
         if p.path == K.KNN_PATH_MFMA_PACKED:
             seed = (max(8192, 8 * k) + 63) // 64 * 64
-            assert 16 < d <= 256 and m >= 64 and n >= 65536 and n >= 4 * seed and p.seed_points == seed
+            assert 8 < d <= 256 and m >= (2048 if d <= 16 else 64) and n >= 65536 and n >= 4 * seed and p.seed_points == seed
             nch_p = nch if nch <= 8 else (nch + 1) // 2 * 2
             # three waves per SIMD where their registers allow and their merge scratch takes at most half the LDS
             waves = 12 if nch_p <= 8 and 12 * (128 + 2 * k) * 4 <= 80 * 1024 else 8
