@@ -41,7 +41,7 @@ PROFILED_TRAFFIC = {
     "c3_imagelike_d784": ("knn_wide_kernel", 51.4e9, "profiles/knn_wide_kernel_c3.md"),
     "c4_clustered_d128": ("knn_packed_kernel", 611.6e9, "profiles/knn_packed_kernel_c4.md"),
     "c5_memsweep_d256": ("knn_packed_kernel", 41.7e9, "profiles/knn_packed_kernel_c5_1GB.md"),  # per launch, two a step
-    "c6_cosine_d100": ("knn_split_kernel", 15.85e9, "profiles/knn_split_kernel_c6.md"),
+    "c6_cosine_d100": ("knn_packed_kernel", 8.44e9, "profiles/knn_packed_kernel_c6.md"),
     "c7_l1_d100": ("knn_l1_kernel", 25.8e9, "profiles/knn_l1_kernel_c7.md"),
     "kmv1_d1": ("kmv_lowd_kernel", 1.84e9, "profiles/kmv_lowd_kernel_kmv1.md"),
     "kmv2_d32": ("kmv_mfma_kernel", 1.47e9, "profiles/kmv_mfma_kernel_kmv2.md"),

@@ -71,7 +71,8 @@ typedef enum { KNN_METRIC_L2SQ = 0, KNN_METRIC_COSINE = 1, KNN_METRIC_L1 = 2 } k
                                  rounding; exact fp32 test of the pairs that pass.  (Number 1
                                  was this path's fp32 matrix-core predecessor.) */
 
-#define KNN_PATH_MFMA_PACKED 6 /* 8 < d <= 256, squared-Euclidean, m >= 64 (2048 up to d = 16), n >= 65536 and room for the
+#define KNN_PATH_MFMA_PACKED 6 /* 8 < d <= 256 squared-Euclidean, d <= 256 cosine (on the rows x / |x|, whole copy
+                                  only), m >= 64 (2048 up to d = 16), n >= 65536 and room for the
                                   points rounded to bf16 (32 bytes per point and 16 coordinates):
                                   the filter of path 5 with the queries resident in LDS and the
                                   points read from that copy in matrix-core operand order; the
@@ -113,7 +114,8 @@ typedef struct {
     uint64_t norms_bytes;     /* workspace: per-point data. path 2: packed points
                                  [x0 x1 x2 |x|^2]; path 5: squared norms (cosine: 1 / norm)
                                  and a 256-byte header; paths 6, 7: the same (norms padded to a
-                                 multiple of 64 points) and slab_points points rounded to bf16; path 4: a 256-byte header, 32 bytes
+                                 multiple of 64 points) and slab_points points rounded to bf16
+                                 (path 6, cosine: and as many words again, zeros); path 4: a 256-byte header, 32 bytes
                                  per point and 16 K slots, and with seed_cells the grid's cell
                                  starts and cursors and the points in cell order (16 bytes each);
                                  paths 0, 3: nothing                                   */

@@ -211,6 +211,12 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
     }
     const int S = plan.n_splits;
     const bool cosine = metric == KNN_METRIC_COSINE;
+    // path 6, cosine metric: xn holds 1 / |x|, the copy the rows x / |x|, and behind the copy lie
+    // the values the filter's sums start from (zeros, +inf from n to the end of the last step)
+    float* const sum0 =
+        (cosine && plan.path == KNN_PATH_MFMA_PACKED)
+            ? reinterpret_cast<float*>(xp + align_up((uint64_t)plan.slab_points * (uint64_t)pk_padded_chunks(d) * 32))
+            : xn;
 
     hipError_t e;
     if (plan.path == KNN_PATH_MFMA_SPLIT || packed_plan) {
@@ -221,12 +227,16 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
         // (one slab: the copy is made here, once for all query chunks, and the pass that makes it
         // takes the norms and the largest rounding residual along)
         const bool copy_now = packed && plan.slab_points >= (int64_t)n64;
-        if (e == hipSuccess && copy_now)
+        if (e == hipSuccess && copy_now && !cosine)
             e = launch_pack_operands(X, ldx, n, d, 0, (int64_t)n64, xp, stream, 1.f, xn, hdr);
-        if (e == hipSuccess && !copy_now)
+        if (e == hipSuccess && (!copy_now || cosine))
             e = launch_row_norms(X, ldx, n, d, cosine, xn, stream, cosine ? nullptr : hdr + 4);
         if (e == hipSuccess) e = launch_max_norm(xn, n, hdr, stream);
-        if (e == hipSuccess && packed) e = launch_pad_norms(xn, n, stream);
+        if (e == hipSuccess && packed && cosine) {  // (plans of the cosine metric hold the whole copy)
+            e = launch_pack_operands(X, ldx, n, d, 0, (int64_t)n64, xp, stream, 1.f, nullptr, hdr, xn);
+            if (e == hipSuccess) e = launch_fill_words(sum0, (int64_t)n64, 0u, stream);
+        }
+        if (e == hipSuccess && packed) e = launch_pad_norms(sum0, n, stream);
         if (e != hipSuccess) {
             drop_bracket(t0);
             return hip_fail(e, "row norms launch");
@@ -298,8 +308,8 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
                         // tighter than a sample of this block would make them; path 7 takes its
                         // first thresholds inside the search kernel)
                         if (e == hipSuccess && !keep_thresholds && !wide_plan)
-                            e = launch_seed_thresholds(Qc, ldq, xp, xn, qs, qn, tsh, hdr, rows, j1, d, k,
-                                                       plan.seed_points, stream);
+                            e = launch_seed_thresholds(Qc, ldq, xp, sum0, qs, qn, tsh, hdr, rows, j1, d, k,
+                                                       plan.seed_points, stream, cosine);
                         if (e == hipSuccess) e = launch_fill_words(tsr, rows * S, 0xff800000u, stream);
                     }
                     if (e != hipSuccess) break;
@@ -309,8 +319,9 @@ knn_status run_search(const knn_plan_t& plan, const float* Q, int64_t ldq, const
                         e = launch_wide(Qc, ldq, X, ldx, xp, j0, pts, qs, qn, tsh, tsr, xn, hdr, rows, n, d, k,
                                         S, j0, j1, j0 == 0 ? 0 : S, lk, li, stream);
                     else
-                        e = launch_packed(Qc, ldq, X, ldx, xp, j0, qs, qn, tsh, tsr, xn, hdr, rows, n, d, k, S,
-                                          plan.tile_q / 32, j0, j1, j0 == 0 ? 0 : S, lk, li, stream);
+                        e = launch_packed(Qc, ldq, X, ldx, xp, j0, qs, qn, tsh, tsr, sum0, hdr, rows, n, d, k, S,
+                                          plan.tile_q / 32, j0, j1, j0 == 0 ? 0 : S, lk, li, stream,
+                                          cosine ? xn : nullptr);
                 }
             }
         } else

@@ -69,7 +69,10 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
 //                         scale = -2 packs queries as B operands (n = their number); xn != null
 //                         (16-byte aligned rows only): the same pass also writes the rows'
 //                         squared norms to xn[j_first ..] and raises hdr word 1 to the largest
-//                         squared norm of a rounding residual, as launch_row_norms would
+//                         squared norm of a rounding residual, as launch_row_norms would;
+//                         row_scale != null (aligned rows, hdr != null): row j is multiplied by
+//                         row_scale[j] before it is rounded (the cosine metric's x / |x|), and
+//                         the residuals (and norms, if xn != null) are those of the scaled rows
 //   launch_pad_norms      xn[n .. next multiple of 64) = +inf
 //   launch_packed         the search of points [j_first, j_end) (j_first a multiple of 64) out of
 //                         the copy xp whose first point is slab_first, for queries whose B
@@ -80,9 +83,12 @@ hipError_t launch_split(const float* Q, int64_t ldq, const float* X, int64_t ldx
 //                         0xff800000 (+inf) beforehand: the key at position ceil(k / S) - 1 of
 //                         every range's list, through which the ranges bound each other.
 //                         Rows must be 16-byte aligned (packed_rows_aligned).
+//                         Cosine metric: rn = 1 / |x| of all points, xp packed with row_scale =
+//                         rn, xn = zeros (+inf from n to the next multiple of 64), and
+//                         launch_seed_thresholds with cosine = true.
 hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, int64_t j_first,
                                 int64_t points, void* xp, hipStream_t stream, float scale = 1.f,
-                                float* xn = nullptr, void* hdr = nullptr);
+                                float* xn = nullptr, void* hdr = nullptr, const float* row_scale = nullptr);
 hipError_t launch_pad_norms(float* xn, int64_t n, hipStream_t stream);
 //   launch_seed_thresholds  tsh[r] = min(tsh[r], an upper bound of query r's k-th smallest distance
 //                         found from the filter keys of seed_points points spread over the packed
@@ -90,13 +96,13 @@ hipError_t launch_pad_norms(float* xn, int64_t n, hipStream_t stream);
 //                         norms and the header
 hipError_t launch_seed_thresholds(const float* Q, int64_t ldq, const void* xp, const float* xn, const void* qs,
                                   const float* qn, void* tsh, const void* hdr, int64_t rows, int64_t n, int d,
-                                  int k, int64_t seed_points, hipStream_t stream);
+                                  int k, int64_t seed_points, hipStream_t stream, bool cosine = false);
 bool packed_rows_aligned(const float* Q, int64_t ldq, const float* X, int64_t ldx, int d);
 hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ldx, const void* xp,
                          int64_t slab_first, const void* qs, const float* qn, void* tsh, void* tsr,
                          const float* xn, const void* hdr, int64_t rows, int64_t n, int d, int k, int S,
                          int sets, int64_t j_first, int64_t j_end, int init_from, float* lk, int* li,
-                         hipStream_t stream);
+                         hipStream_t stream, const float* rn = nullptr);
 // d > 256 with both operands rounded to bf16 in the workspace (knn_wide.hip).
 //   launch_wide   the search of points [j_first, j_end) (j_first a multiple of 64) out of the copy
 //                 xp (launch_pack_operands) that holds slab_points points from slab_first on, for

@@ -74,12 +74,14 @@ __global__ __launch_bounds__(256) void knn_pack_operands_kernel(const float* __r
 // passes.  NORMS: the squared norms of the rows (one fma chain per lane over its pieces, lanes added
 // up by a butterfly: a fixed order) go to xn, and the largest squared norm of a rounding residual
 // x - bf16(x) to hdr[1] - the pass over X that knn_row_norms_kernel would otherwise repeat.
+// (With row_scale both are those of the scaled rows; xn may be null.)
 constexpr int kPbSeg = 32;               // chunks per pass
 constexpr int kPbOperandStride = 64 + 2; // uint4 per operand in LDS (a half of 32 rows + one: no bank conflicts)
 template <bool NORMS>
 __global__ __launch_bounds__(256) void knn_pack_block_kernel(const float* __restrict__ X, int64_t ldx, int n,
                                                              int d, int nch, int j_first, int nblocks,
-                                                             float scale, uint4* __restrict__ Xp,
+                                                             float scale, const float* __restrict__ row_scale,
+                                                             uint4* __restrict__ Xp,
                                                              float* __restrict__ xn, unsigned* __restrict__ hdr) {
     __shared__ uint4 ops[kPbSeg * kPbOperandStride];
     __shared__ float wmax[4];
@@ -102,9 +104,12 @@ __global__ __launch_bounds__(256) void knn_pack_block_kernel(const float* __rest
                 }
 #pragma unroll
                 for (int rr = 0; rr < 8; ++rr) {
-                    const bool ok = j_first + blk * 32 + wave * 8 + rr < n;
-                    const f32x4 a0 = mask_row4(v0[rr], ok, col, d, scale);
-                    const f32x4 a1 = mask_row4(v1[rr], ok, col + 4, d, scale);
+                    const int jr = j_first + blk * 32 + wave * 8 + rr;
+                    const bool ok = jr < n;
+                    // (row_scale: every row times its own factor - the cosine metric's 1 / |x|)
+                    const float sc = row_scale ? row_scale[ok ? jr : 0] : scale;
+                    const f32x4 a0 = mask_row4(v0[rr], ok, col, d, sc);
+                    const f32x4 a1 = mask_row4(v1[rr], ok, col + 4, d, sc);
                     if (NORMS) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
@@ -139,7 +144,7 @@ __global__ __launch_bounds__(256) void knn_pack_block_kernel(const float* __rest
                     r += __shfl_xor(r, sft);
                 }
                 const int j = j_first + blk * 32 + wave * 8 + rr;
-                if (lane == 0 && j < n) xn[j] = a;
+                if (xn && lane == 0 && j < n) xn[j] = a;
                 worst = fmaxf(worst, r);
             }
         }
@@ -171,6 +176,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 // and highest filter key, then kSeedIters passes quarter the interval [lo, hi] keeping
 // count(f <= hi) >= k.  The bound goes into tsh (atomic minimum on the order-preserving word).
 constexpr int kSeedIters = 4;
+constexpr float kCosUnit = 1.0001f;  // cosine metric: the packed rows are x / |x|, of squared norm below this
 constexpr int kSeedSets = 1;  // sets of 32 queries per wave
 template <int NCH>
 __global__ __launch_bounds__(256, 2) void knn_seed_kernel(const uint4* __restrict__ Xp, const float* __restrict__ xn,
@@ -179,7 +185,8 @@ __global__ __launch_bounds__(256, 2) void knn_seed_kernel(const uint4* __restric
                                                        const unsigned* __restrict__ hdr,
                                                        const float* __restrict__ Q, int64_t ldq,
                                                        unsigned* __restrict__ tsh, int rows, int d,
-                                                       int nch_real, int k, int nsteps, int sample_steps) {
+                                                       int nch_real, int k, int nsteps, int sample_steps,
+                                                       int cosine) {
     const int lane = threadIdx.x & 63;
     const int i32 = lane & 31, h = lane >> 5;
     const int row0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * (32 * kSeedSets);
@@ -303,7 +310,7 @@ __global__ __launch_bounds__(256, 2) void knn_seed_kernel(const uint4* __restric
         if (r < rows && h == 0) {
             // the allowance of knn_packed_kernel's filter (see there), with the bound itself in
             // place of tau in the rounding term and that term doubled
-            const float xmax = __uint_as_float(hdr[0]);
+            const float xmax = cosine ? kCosUnit : __uint_as_float(hdr[0]);
             const float rxm = sqrtf(__uint_as_float(hdr[1]));
             const float qn = qnorm[r];
             float rq2 = 0.f;
@@ -317,7 +324,9 @@ __global__ __launch_bounds__(256, 2) void knn_seed_kernel(const uint4* __restric
             const float cross = 1.01f * ((sqrtf(xmax) + rxm) * sqrtf(rq2) + rxm * 2.f * sqrtf(qn)) +
                                 e_acc * sqrtf(xmax * qn);
             const float base = hi[t] + qn;
-            const float bound = base + (cross + 2.f * e_sum * (xmax + qn + fabsf(base) + cross) + 0x1p-126f);
+            // (cosine metric: the key is -2 q.x / |x| itself, see knn_packed_kernel; twice its allowance)
+            const float bound = cosine ? hi[t] + 2.f * (cross + 4.f * e_sum * sqrtf(qn) + 0x1p-126f)
+                                       : base + (cross + 2.f * e_sum * (xmax + qn + fabsf(base) + cross) + 0x1p-126f);
             atomicMin(tsh + r, key_word(bound));
         }
     }
@@ -330,6 +339,8 @@ struct PkArgs {
     int64_t ldx;
     const uint4* Xp;       // packed points of the slab
     const float* xn;       // squared norms of all points, +inf up to the end of the last step
+                           // (cosine metric: zeros, +inf past the points - what the sums start from)
+    const float* rn;       // cosine metric: 1 / |x| of all points; else null
     const uint4* Qs;       // B operands of the chunk's queries (knn_split_queries_kernel)
     const float* qnorm;    // their squared norms
     unsigned* tsh;         // [rows] lowest k-th key any range of the query has reached
@@ -349,7 +360,7 @@ struct PkArgs {
 
 enum { kCtlStop = 32, kCtlCount = 33, kCtlDone = 34, kCtlNext = 35 };
 
-template <int NCH, bool ALIGNED, int WV>
+template <int NCH, bool ALIGNED, int WV, bool COS>
 __global__ __launch_bounds__(64 * WV, WV / 4) void knn_packed_kernel(const PkArgs a) {
     constexpr int kPkWaves = WV;  // 12 or 8 (pk_waves)
     constexpr int C = kPkCand;
@@ -410,12 +421,20 @@ __global__ __launch_bounds__(64 * WV, WV / 4) void knn_packed_kernel(const PkArg
     //                       2.02 |x| |q| in magnitude
     //   roundings of xn, qn, dd   each below (d / 64 + 8) ulps of the value
     // The constants below cover the first in full and are at least twice the others.
-    const float xmax = __uint_as_float(a.hdr[0]);
+    // Cosine metric (COS; a.rn = 1 / |x|): the copy holds the rows x / |x| (scaled in fp32, then rounded),
+    // the sums start from 0, so the filter key is  sum bf16(x^) bf16(-2 q)  and the exact key
+    // -2 (q.x) / |x| from an fp32 dot product (knn_exact.h).  The same two terms bound the rounded
+    // operands with |x^| < 1.0001 in place of sqrt(xmax) and the residuals of the scaled rows in
+    // the header; the roundings of 1 / |x|, of the scaling and of the dot product are ulps of
+    // values below 2.02 |q|: 4 e_sum |q| covers them twice over.  Nothing is subtracted from tau.
+    constexpr bool cosine = COS;
+    const float xmax = cosine ? kCosUnit : __uint_as_float(a.hdr[0]);
     const float rxm = sqrtf(__uint_as_float(a.hdr[1]));
     const float e_acc = (float)(4 * (NCH * 16) + 32) * 0x1p-24f;
     const float e_sum = (float)(a.d + 16) * 0x1p-23f;
     auto key_bound = [&](float t, float qn, float cross) {
-        return (t - qn) + (cross + e_sum * (xmax + qn + t) + 0x1p-126f);
+        return cosine ? t + (cross + 4.f * e_sum * sqrtf(qn) + 0x1p-126f)
+                      : (t - qn) + (cross + e_sum * (xmax + qn + t) + 0x1p-126f);
     };
     // Thresholds.  A query's S ranges run in different workgroups; any upper bound of the k-th
     // smallest key over ALL points may cut every range's candidates:
@@ -657,7 +676,7 @@ __global__ __launch_bounds__(64 * WV, WV / 4) void knn_packed_kernel(const PkArg
                 if (n_c > 0) {
                     t_bits = flush_query_exact<ALIGNED, 8, true>(a.Q + (int64_t)r * a.ldq, a.X, a.ldx, a.d,
                                                            a.j_valid, cbuf, jb, n_c, a.lk + lb, a.li + lb,
-                                                           k, my_scratch, a.tsh + r, nullptr, lane, pos_s,
+                                                           k, my_scratch, a.tsh + r, COS ? a.rn : nullptr, lane, pos_s,
                                                            &key_s);
                     merged = true;
                 }
@@ -726,21 +745,21 @@ __global__ __launch_bounds__(64 * WV, WV / 4) void knn_packed_kernel(const PkArg
 
 hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, int64_t j_first,
                                 int64_t points, void* xp, hipStream_t stream, float scale, float* xn,
-                                void* hdr) {
+                                void* hdr, const float* row_scale) {
     const int nch = pk_padded_chunks(d);
     const bool aligned = (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (ldx % 4 == 0) && (d % 4 == 0);
-    if (xn && (!aligned || !hdr)) return hipErrorInvalidValue;
+    if ((xn || row_scale) && (!aligned || !hdr)) return hipErrorInvalidValue;
     if (aligned) {
         const int nblocks = (int)(points / 32);
         const dim3 grid((unsigned)(nblocks < 16384 ? nblocks : 16384));
-        if (xn)
+        if (xn || row_scale)
             knn_pack_block_kernel<true><<<grid, dim3(256), 0, stream>>>(X, ldx, (int)n, d, nch, (int)j_first, nblocks,
-                                                                         scale, static_cast<uint4*>(xp), xn,
-                                                                         static_cast<unsigned*>(hdr));
+                                                                         scale, row_scale, static_cast<uint4*>(xp),
+                                                                         xn, static_cast<unsigned*>(hdr));
         else
             knn_pack_block_kernel<false><<<grid, dim3(256), 0, stream>>>(X, ldx, (int)n, d, nch, (int)j_first,
-                                                                          nblocks, scale, static_cast<uint4*>(xp),
-                                                                          nullptr, nullptr);
+                                                                          nblocks, scale, nullptr,
+                                                                          static_cast<uint4*>(xp), nullptr, nullptr);
         return hipGetLastError();
     }
     const int64_t pieces = points * nch * 2;
@@ -752,7 +771,7 @@ hipError_t launch_pack_operands(const float* X, int64_t ldx, int64_t n, int d, i
 
 hipError_t launch_seed_thresholds(const float* Q, int64_t ldq, const void* xp, const float* xn, const void* qs,
                                   const float* qn, void* tsh, const void* hdr, int64_t rows, int64_t n, int d,
-                                  int k, int64_t seed_points, hipStream_t stream) {
+                                  int k, int64_t seed_points, hipStream_t stream, bool cosine) {
     const int nch_real = (d + kSpKC - 1) / kSpKC;
     const int nch = pk_padded_chunks(d);
     const int nsteps = (int)((n + kPkStep - 1) / kPkStep);
@@ -764,7 +783,7 @@ hipError_t launch_seed_thresholds(const float* Q, int64_t ldq, const void* xp, c
     knn_seed_kernel<N><<<grid, dim3(256), 0, stream>>>(                                             \
         static_cast<const uint4*>(xp), xn, static_cast<const uint4*>(qs), qn,                       \
         static_cast<const unsigned*>(hdr), Q, ldq, static_cast<unsigned*>(tsh), (int)rows, d, nch_real, k, \
-        nsteps, sample_steps)
+        nsteps, sample_steps, cosine ? 1 : 0)
     switch (nch) {
         case 1: KNN_SEED_LAUNCH(1); break;
         case 2: KNN_SEED_LAUNCH(2); break;
@@ -799,7 +818,7 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
                          int64_t slab_first, const void* qs, const float* qn, void* tsh, void* tsr,
                          const float* xn, const void* hdr, int64_t rows, int64_t n, int d, int k, int S,
                          int sets, int64_t j_first, int64_t j_end, int init_from, float* lk, int* li,
-                         hipStream_t stream) {
+                         hipStream_t stream, const float* rn) {
     const int nch_real = (d + kSpKC - 1) / kSpKC;
     const int nch = pk_padded_chunks(d);
     if (d > kPkMaxD || sets < 1 || sets > pk_max_sets(nch, k) || !packed_rows_aligned(Q, ldq, X, ldx, d) ||
@@ -813,6 +832,7 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
     a.ldx = ldx;
     a.Xp = static_cast<const uint4*>(xp);
     a.xn = xn;
+    a.rn = rn;
     a.Qs = static_cast<const uint4*>(qs);
     a.qnorm = qn;
     a.tsh = static_cast<unsigned*>(tsh);
@@ -843,9 +863,15 @@ hipError_t launch_packed(const float* Q, int64_t ldq, const float* X, int64_t ld
     const int waves = pk_waves(nch, k);
 #define KNN_PACKED_LAUNCH_W(N, W)                                                              \
     do {                                                                                       \
-        hipError_t e2 = raise_lds_limit(knn_packed_kernel<N, true, W>, lds);                   \
-        if (e2 != hipSuccess) return e2;                                                       \
-        knn_packed_kernel<N, true, W><<<grid, dim3(64 * W), lds, stream>>>(a);                 \
+        if (rn) {                                                                              \
+            hipError_t e2 = raise_lds_limit(knn_packed_kernel<N, true, W, true>, lds);         \
+            if (e2 != hipSuccess) return e2;                                                   \
+            knn_packed_kernel<N, true, W, true><<<grid, dim3(64 * W), lds, stream>>>(a);       \
+        } else {                                                                               \
+            hipError_t e2 = raise_lds_limit(knn_packed_kernel<N, true, W, false>, lds);        \
+            if (e2 != hipSuccess) return e2;                                                   \
+            knn_packed_kernel<N, true, W, false><<<grid, dim3(64 * W), lds, stream>>>(a);      \
+        }                                                                                      \
     } while (0)
 #define KNN_PACKED_LAUNCH(N)                                                                   \
     do {                                                                                       \

@@ -229,7 +229,10 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     // the search runs with the queries resident in LDS (knn_packed.hip).  Its workspace is that
     // of path 5 plus the packed copy, so a call whose rows turn out not to be 16-byte aligned
     // still runs under this plan, on path 5's kernel.
-    if (split && metric == KNN_METRIC_L2SQ && d <= kPkMaxD &&
+    // The cosine metric runs there too, on a copy of the rows x / |x|, with one more array of n
+    // words (what the sums start from; the first holds 1 / |x|) and the whole copy only, no slabs.
+    const bool cosine6 = metric == KNN_METRIC_COSINE;
+    if (split && (metric == KNN_METRIC_L2SQ || cosine6) && d <= kPkMaxD &&
         n >= kPkMinPoints && n >= 4 * pk_seed_points(k) &&
         m >= (d <= kSpKC ? kPkMinQueriesOneChunk : kPkMinQueries)) {
         const int nch_p = pk_padded_chunks(d);
@@ -239,12 +242,13 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
         // of the points at a time - all of them if the limit has room, else the largest slab that
         // leaves the lists a place: the point axis is cut by the limit as well (section 4.3), each
         // slab is packed into the same buffer and searched, and the lists carry over.
-        const uint64_t fixed = align_up(n64 * 4) + kAlign;
+        const uint64_t fixed = align_up(n64 * 4) * (cosine6 ? 2 : 1) + kAlign;
         const int64_t min_rows = m < 64 ? m : 64;
         double best = 0.0;
         int best_sets = 0;
         int64_t best_S = 0, best_r = 0, best_slab = 0;
-        for (int64_t slab = (int64_t)n64; sets_max >= 2 && (slab == (int64_t)n64 || slab >= 2 * kPkMinPoints);
+        for (int64_t slab = (int64_t)n64;
+             sets_max >= 2 && (slab == (int64_t)n64 || (slab >= 2 * kPkMinPoints && !cosine6));
              slab = (slab / 2 + kPkSlabGrain - 1) / kPkSlabGrain * kPkSlabGrain) {
             const uint64_t copy = align_up((uint64_t)slab * (uint64_t)nch_p * 32);
             if (mem_limit_bytes >= fixed + copy + lists_bytes_for((uint64_t)min_rows, 1, (uint64_t)k) +

@@ -28,20 +28,20 @@ def K():
     return K
 
 
-def both_paths(K, Qd, Xd, k, big=4 * 10 ** 9):
+def both_paths(K, Qd, Xd, k, big=4 * 10 ** 9, metric="l2"):
     """(idx, dist) on the packed path, after checking that the split path gives the same bits."""
     m, d = Qd.shape
     n = Xd.shape[0]
-    p6 = K.knn_plan(m, n, d, k, big)
+    p6 = K.knn_plan(m, n, d, k, big, metric)
     assert p6.path == K.KNN_PATH_MFMA_PACKED, p6
-    small = K.knn_plan(m, n, d, k, 1 << 44).min_limit_bytes + 10 ** 6
-    p5 = K.knn_plan(m, n, d, k, small)
+    small = K.knn_plan(m, n, d, k, 1 << 44, metric).min_limit_bytes + 10 ** 6
+    p5 = K.knn_plan(m, n, d, k, small, metric)
     assert p5.path == K.KNN_PATH_MFMA_SPLIT, p5
-    i6, d6 = K.knn_search(Qd, Xd, k, big)
+    i6, d6 = K.knn_search(Qd, Xd, k, big, metric=metric)
     torch.cuda.synchronize()
     plan, peak = K.knn_last_stats()
     assert plan.path == K.KNN_PATH_MFMA_PACKED and peak <= big
-    i5, d5 = K.knn_search(Qd, Xd, k, small)
+    i5, d5 = K.knn_search(Qd, Xd, k, small, metric=metric)
     torch.cuda.synchronize()
     same_i = torch.equal(i6, i5)
     same_d = torch.equal(d6.view(torch.int32), d5.view(torch.int32))
@@ -52,8 +52,8 @@ def both_paths(K, Qd, Xd, k, big=4 * 10 ** 9):
     return i6.cpu().numpy(), d6.cpu().numpy()
 
 
-def against_oracle(oracle, Q, X, k, idx, dist, rows):
-    o_idx, o_dist, o_next = oracle.knn(Q, X, k, rows=rows)
+def against_oracle(oracle, Q, X, k, idx, dist, rows, metric="l2"):
+    o_idx, o_dist, o_next = oracle.knn(Q, X, k, rows=rows, metric=metric)
     stats = check(idx[rows], dist[rows], o_idx, o_dist, o_next, X.shape[0])
     say("   parity", stats)
     return stats
@@ -105,6 +105,32 @@ def test_packed_parity(K, oracle, seed, m, n, d, k, kind):
     idx, dist = both_paths(K, Qd, Xd, k)
     rows = np.unique(np.concatenate([np.arange(0, m, max(1, m // 24)), [m - 1]]))
     against_oracle(oracle, Q, X, k, idx, dist, rows)
+
+
+# the cosine metric on the packed path: the copy holds the rows x / |x|
+COSINE_CASES = [
+    (31, 2500, 70001, 100, 10, "clustered"),  # the shape of the embedding rows, three waves per SIMD
+    (32, 2300, 80000, 256, 32, "normal"),     # 16 chunks, two waves per SIMD
+    (33, 2100, 90000, 16, 33, "normal"),      # one chunk
+    (34, 300, 66000, 64, 7, "zeros"),         # zero rows among points and queries: distance 1
+    (35, 2200, 70000, 40, 5, "scales"),       # row lengths over four orders of magnitude
+]
+
+
+@pytest.mark.parametrize("seed,m,n,d,k,kind", COSINE_CASES)
+def test_packed_cosine_parity(K, oracle, seed, m, n, d, k, kind):
+    say(f"packed cosine case seed={seed} m={m} n={n} d={d} k={k} {kind}")
+    Q, X = make(seed, m, n, d, "clustered" if kind == "clustered" else "normal")
+    rng = np.random.default_rng(seed)
+    if kind == "zeros":
+        X[::97] = 0
+        Q[5] = 0
+    if kind == "scales":
+        X *= (10.0 ** rng.uniform(-2, 2, (n, 1))).astype(np.float32)
+        Q *= (10.0 ** rng.uniform(-2, 2, (m, 1))).astype(np.float32)
+    idx, dist = both_paths(K, torch.from_numpy(Q).cuda(), torch.from_numpy(X).cuda(), k, metric="cosine")
+    rows = np.unique(np.concatenate([np.arange(0, m, max(1, m // 24)), [5, m - 1]]))
+    against_oracle(oracle, Q, X, k, idx, dist, rows, metric="cosine")
 
 
 def test_packed_worst_order_stream_overflows_the_buffers(K, oracle):

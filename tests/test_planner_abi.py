@@ -151,8 +151,13 @@ def test_low_d_falls_back_to_the_vector_path_when_packed_points_do_not_fit():
     assert K.knn_plan(2047, n, 9, k, 10 ** 9).path == K.KNN_PATH_MFMA_SPLIT
     assert K.knn_plan(m, n, 9, k, 30 * 10 ** 6).slab_points < n  # a slab of the copy
     assert K.knn_plan(m, n, 9, k, 12 * 10 ** 6).path == K.KNN_PATH_MFMA_SPLIT  # no room for one
-    assert K.knn_plan(m, n, 9, k, 10 ** 9, metric="cosine").path == K.KNN_PATH_MFMA_SPLIT
-    assert K.knn_plan(m, n, 3, k, 10 ** 9, metric="cosine").path == K.KNN_PATH_MFMA_SPLIT
+    # the cosine metric: the packed path at any d <= 256 (the whole copy, and n more words), else path 5
+    for dc in (9, 3):
+        pc = K.knn_plan(m, n, dc, k, 10 ** 9, metric="cosine")
+        assert pc.path == K.KNN_PATH_MFMA_PACKED and pc.slab_points == n
+        assert pc.norms_bytes == 2 * (4 * n) + 256 + 32 * n
+        assert K.knn_plan(m, n, dc, k, 30 * 10 ** 6, metric="cosine").path == K.KNN_PATH_MFMA_SPLIT
+        assert K.knn_plan(2047, n, dc, k, 10 ** 9, metric="cosine").path == K.KNN_PATH_MFMA_SPLIT
 
 
 def test_threshold_seed_grid_is_sized_from_n_and_k_and_paid_for_under_the_limit():
