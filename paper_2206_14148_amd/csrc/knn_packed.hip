@@ -172,7 +172,8 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 // far tighter - without evaluating a single pair exactly.  (Lists that start from +inf accept
 // every pair until they hold k entries; with all waves feeding one buffer that phase would be
 // spent in stops.)  The sample is `sample_steps` steps of 64 points spread evenly over the packed
-// copy.  One wave per 64 queries, B operands in registers; a first pass finds the lane's lowest
+// copy.  One workgroup per 32 queries (B operands in registers, every wave a quarter of the
+// sample); a first pass finds the lane's lowest
 // and highest filter key, then kSeedIters passes quarter the interval [lo, hi] keeping
 // count(f <= hi) >= k.  The bound goes into tsh (atomic minimum on the order-preserving word).
 constexpr int kSeedIters = 4;
@@ -189,8 +190,14 @@ __global__ __launch_bounds__(256, 2) void knn_seed_kernel(const uint4* __restric
                                                        int cosine) {
     const int lane = threadIdx.x & 63;
     const int i32 = lane & 31, h = lane >> 5;
-    const int row0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * (32 * kSeedSets);
-    if (row0 >= rows) return;  // whole wave; no workgroup barrier below
+    // The four waves of a workgroup serve the same 32 queries and take every fourth step of the
+    // sample each; their extremes and counts meet in LDS.  (One wave per 32 queries walking the
+    // whole sample left most of the chip idle below 3e4 queries: 0.94 ms of c6's 4.6.)
+    const int wv = threadIdx.x >> 6;
+    const int row0 = blockIdx.x * (32 * kSeedSets);
+    __shared__ float ex_l[4][2][32];
+    __shared__ int cnt_l[4][3][32];
+    static_assert(kSeedSets == 1, "one query set per workgroup");
     uint4 bq[kSeedSets][NCH];
 #pragma unroll
     for (int t = 0; t < kSeedSets; ++t) {
@@ -246,7 +253,7 @@ __global__ __launch_bounds__(256, 2) void knn_seed_kernel(const uint4* __restric
         lo[t] = kInf;
         hi[t] = -kInf;
     }
-    for (int i = 0; i < sample_steps; ++i) {
+    for (int i = wv; i < sample_steps; i += 4) {
         f32x16 acc[kSeedSets][2];
         keys(step_of(i), acc);
 #pragma unroll
@@ -264,6 +271,13 @@ __global__ __launch_bounds__(256, 2) void knn_seed_kernel(const uint4* __restric
     for (int t = 0; t < kSeedSets; ++t) {
         lo[t] = fminf(lo[t], lane_xor<32>(lo[t]));
         hi[t] = fmaxf(hi[t], lane_xor<32>(hi[t]));
+        if (h == 0) {
+            ex_l[wv][0][i32] = lo[t];
+            ex_l[wv][1][i32] = hi[t];
+        }
+        __syncthreads();
+        lo[t] = fminf(fminf(ex_l[0][0][i32], ex_l[1][0][i32]), fminf(ex_l[2][0][i32], ex_l[3][0][i32]));
+        hi[t] = fmaxf(fmaxf(ex_l[0][1][i32], ex_l[1][1][i32]), fmaxf(ex_l[2][1][i32], ex_l[3][1][i32]));
     }
     // (three thresholds a pass, the quartiles of the interval: two bits of the answer for one
     // walk over the sample, which is what a pass costs - the operands come out of the L2 again)
@@ -277,7 +291,7 @@ __global__ __launch_bounds__(256, 2) void knn_seed_kernel(const uint4* __restric
             q3[t] = lo[t] + 0.75f * (hi[t] - lo[t]);
             c1[t] = c2[t] = c3[t] = 0;
         }
-        for (int i = 0; i < sample_steps; ++i) {
+        for (int i = wv; i < sample_steps; i += 4) {
             f32x16 acc[kSeedSets][2];
             keys(step_of(i), acc);
 #pragma unroll
@@ -297,6 +311,16 @@ __global__ __launch_bounds__(256, 2) void knn_seed_kernel(const uint4* __restric
             c1[t] += lane_xor<32>(c1[t]);
             c2[t] += lane_xor<32>(c2[t]);
             c3[t] += lane_xor<32>(c3[t]);
+            __syncthreads();  // (the previous pass has read its counts)
+            if (h == 0) {
+                cnt_l[wv][0][i32] = c1[t];
+                cnt_l[wv][1][i32] = c2[t];
+                cnt_l[wv][2][i32] = c3[t];
+            }
+            __syncthreads();
+            c1[t] = cnt_l[0][0][i32] + cnt_l[1][0][i32] + cnt_l[2][0][i32] + cnt_l[3][0][i32];
+            c2[t] = cnt_l[0][1][i32] + cnt_l[1][1][i32] + cnt_l[2][1][i32] + cnt_l[3][1][i32];
+            c3[t] = cnt_l[0][2][i32] + cnt_l[1][2][i32] + cnt_l[2][2][i32] + cnt_l[3][2][i32];
             // the lowest quarter whose upper end still has k keys at or below it
             if (c1[t] >= k) hi[t] = q1[t];
             else if (c2[t] >= k) { lo[t] = q1[t]; hi[t] = q2[t]; }
@@ -307,7 +331,7 @@ __global__ __launch_bounds__(256, 2) void knn_seed_kernel(const uint4* __restric
 #pragma unroll
     for (int t = 0; t < kSeedSets; ++t) {
         const int r = row0 + 32 * t + i32;
-        if (r < rows && h == 0) {
+        if (r < rows && h == 0 && wv == 0) {
             // the allowance of knn_packed_kernel's filter (see there), with the bound itself in
             // place of tau in the rounding term and that term doubled
             const float xmax = cosine ? kCosUnit : __uint_as_float(hdr[0]);
@@ -778,7 +802,7 @@ hipError_t launch_seed_thresholds(const float* Q, int64_t ldq, const void* xp, c
     int sample_steps = (int)(seed_points / kPkStep);
     if (sample_steps > nsteps) sample_steps = nsteps;
     if (sample_steps < 1 || (int64_t)sample_steps * kPkStep < k) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)((rows + 4 * 32 * kSeedSets - 1) / (4 * 32 * kSeedSets)));
+    const dim3 grid((unsigned)((rows + 32 * kSeedSets - 1) / (32 * kSeedSets)));
 #define KNN_SEED_LAUNCH(N)                                                                          \
     knn_seed_kernel<N><<<grid, dim3(256), 0, stream>>>(                                             \
         static_cast<const uint4*>(xp), xn, static_cast<const uint4*>(qs), qn,                       \
