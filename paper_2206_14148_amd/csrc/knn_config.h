@@ -99,10 +99,23 @@ constexpr inline int pk_max_sets(int nch_padded, int k) {
     while (sets < kPkMaxSets && pk_lds_bytes(nch_padded, k, sets + 1) <= kPkLdsBytes) ++sets;
     return sets;
 }
-// points whose filter keys give every query its first threshold on path 6 (knn_seed_kernel)
-constexpr inline int64_t pk_seed_points(int k) {
+// Points whose filter keys give every query its first threshold on path 6 (knn_seed_kernel).
+// The path needs n >= 4 x the smallest sample, max(8192, 8 k) points; the sample grows with k up
+// to 160 k (at most a quarter of the points, at most 65536): a list's first threshold passes
+// about k / sample of the points, and c4 (k = 100, ms for preparation + search on one box):
+// 8192 points 4.7 + 218.2, 16000 6.5 + 211.8, 32000 10.2 + 207.2; c5 (k = 32): 4096 1.7 + 45.1,
+// 8192 2.7 + 44.3, 16384 4.6 + 43.7.
+constexpr inline int64_t pk_seed_points_min(int k) {
     const int64_t w = 8 * (int64_t)k;
     return ((w > kPkSeedMin ? w : kPkSeedMin) + kPkStep - 1) / kPkStep * kPkStep;
+}
+constexpr inline int64_t pk_seed_points(int k, int64_t n) {
+    int64_t w = 160 * (int64_t)k;
+    if (w > 65536) w = 65536;
+    if (w > n / 4) w = n / 4;
+    w = w / kPkStep * kPkStep;
+    const int64_t least = pk_seed_points_min(k);
+    return w > least ? w : least;
 }
 
 // d > 256, squared-Euclidean metric, many points, room for the points rounded to bf16:

@@ -233,7 +233,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
     // words (what the sums start from; the first holds 1 / |x|) and the whole copy only, no slabs.
     const bool cosine6 = metric == KNN_METRIC_COSINE;
     if (split && (metric == KNN_METRIC_L2SQ || cosine6) && d <= kPkMaxD &&
-        n >= kPkMinPoints && n >= 4 * pk_seed_points(k) &&
+        n >= kPkMinPoints && n >= 4 * pk_seed_points_min(k) &&
         m >= (d <= kSpKC ? kPkMinQueriesOneChunk : kPkMinQueries)) {
         const int nch_p = pk_padded_chunks(d);
         const int sets_max = pk_max_sets(nch_p, k);
@@ -292,7 +292,7 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
         }
         if (best_sets != 0) {
             out->path = KNN_PATH_MFMA_PACKED;
-            out->seed_points = (int32_t)pk_seed_points(k);
+            out->seed_points = (int32_t)pk_seed_points(k, n);
             out->slab_points = best_slab;
             out->tile_q = 32 * best_sets;
             out->tile_x = kPkStep;

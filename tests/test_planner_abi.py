@@ -202,7 +202,7 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
     # paths 5 and 6 (d > 8, squared-Euclidean): per query 32 bytes per 16 coordinates of bf16 B
     # operands, a squared norm and a shared-threshold word, each array 256-aligned; the chunk is
     # the longest multiple of the query tile that fits with them.  Path 6 (8 < d <= 256, at least 64 queries - 2048 up to d = 16 -,
-    # 65536 points and four times the sample its first thresholds come from) adds the points rounded to bf16, 32 bytes
+    # 65536 points and four times the smallest sample its first thresholds come from) adds the points rounded to bf16, 32 bytes
     # per point and 16 coordinates (the chunk count padded to an even one above 8), and pads the
     # norms to a multiple of 64 points; its query tile is 32 x the query sets of a workgroup.
     import random
@@ -223,8 +223,9 @@ def test_split_paths_account_for_the_per_query_data_and_use_every_byte_they_can(
         nch = (d + 15) // 16
         seen.add(p.path)
         if p.path == K.KNN_PATH_MFMA_PACKED:
-            seed = (max(8192, 8 * k) + 63) // 64 * 64
-            assert 8 < d <= 256 and m >= (2048 if d <= 16 else 64) and n >= 65536 and n >= 4 * seed and p.seed_points == seed
+            seed_min = (max(8192, 8 * k) + 63) // 64 * 64
+            seed = max(seed_min, min(160 * k, 65536, n // 4) // 64 * 64)
+            assert 8 < d <= 256 and m >= (2048 if d <= 16 else 64) and n >= 65536 and n >= 4 * seed_min and p.seed_points == seed
             nch_p = nch if nch <= 8 else (nch + 1) // 2 * 2
             # three waves per SIMD where their registers allow and their merge scratch takes at most half the LDS
             waves = 12 if nch_p <= 8 and 12 * (128 + 2 * k) * 4 <= 80 * 1024 else 8
