@@ -78,6 +78,8 @@ CASES = [
     (15, 2500, 70000, 16, 10, "normal"),     # one chunk
     (16, 2048, 66000, 16, 33, "uniform"),    # one chunk, the fewest queries it takes
     (17, 2300, 90000, 12, 5, "clustered"),   # one chunk, a quarter of it padding
+    (18, 2200, 70000, 64, 1024, "normal"),   # k above 789: eight waves per workgroup at d <= 128 too
+    (19, 2100, 140000, 128, 300, "clustered"),  # a seed sample of 160 k = 48000 > n / 4 points: capped
 ]
 
 
