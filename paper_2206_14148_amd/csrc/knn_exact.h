@@ -67,14 +67,21 @@ __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, con
                 }
             }
         }
+        // A coordinate past the row's end (or a group past it) leaves the sum as it is: its x is
+        // replaced by q (a zero difference), for the dot product by 0, and sum + 0 = sum exactly -
+        // a select on the operand, so that the chain stays one straight run of fused multiply-adds
+        // (a select on the sum was compiled into a branch per coordinate).
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int g = g0 + 2 * u;
+            const bool ok_g = g < ng;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float df = qv[u][e] - xv[u][e];
-                const float next = DOT ? fmaf(qv[u][e], xv[u][e], sum) : fmaf(df, df, sum);
-                sum = (g < ng && 4 * g + e < d) ? next : sum;
+                const bool ok = ALIGNED ? ok_g : (ok_g && 4 * g + e < d);  // (aligned rows: d % 4 == 0)
+                const float qe = qv[u][e];
+                const float xe = ok ? xv[u][e] : (DOT ? 0.f : qe);
+                const float df = qe - xe;
+                sum = DOT ? fmaf(qe, xe, sum) : fmaf(df, df, sum);
             }
         }
     }
