@@ -44,20 +44,24 @@ constexpr unsigned kInfWord = 0xff800000u;  // key_word(+inf)
 // are issued before the first is used (U = 2), or of U groups: more in flight shorten the wait
 // for a long row and cost registers, which the caller may or may not have to spare.  U does not
 // change the order of the additions.
-template <bool ALIGNED, bool DOT, int U>
+// QLATE (aligned rows): the query's groups are read where they are used instead of together with
+// the candidate's - for a query row that the caller has staged in LDS, so that all U groups in
+// flight are the candidate's.
+template <bool ALIGNED, bool DOT, int U, bool QLATE = false>
 __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, const float* __restrict__ xp,
                                                int d, int part) {
+    static_assert(!QLATE || ALIGNED, "late query reads: aligned rows only");
     float sum = 0.f;
     const int ng = (d + 3) >> 2;  // groups of four coordinates (the last may be ragged)
     for (int g0 = part; g0 < ng; g0 += 2 * U) {
-        f32x4 xv[U], qv[U];
+        f32x4 xv[U], qv[QLATE ? 1 : U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int g = g0 + 2 * u;
             const int gc = g < ng ? g : part;  // a valid group; its value is not used
             if (ALIGNED) {
                 xv[u] = *reinterpret_cast<const f32x4*>(xp + 4 * gc);
-                qv[u] = *reinterpret_cast<const f32x4*>(qp + 4 * gc);
+                if (!QLATE) qv[u] = *reinterpret_cast<const f32x4*>(qp + 4 * gc);
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -75,10 +79,11 @@ __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, con
         for (int u = 0; u < U; ++u) {
             const int g = g0 + 2 * u;
             const bool ok_g = g < ng;
+            const f32x4 qg = QLATE ? *reinterpret_cast<const f32x4*>(qp + 4 * (ok_g ? g : part)) : qv[QLATE ? 0 : u];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const bool ok = ALIGNED ? ok_g : (ok_g && 4 * g + e < d);  // (aligned rows: d % 4 == 0)
-                const float qe = qv[u][e];
+                const float qe = qg[e];
                 const float xe = ok ? xv[u][e] : (DOT ? 0.f : qe);
                 const float df = qe - xe;
                 sum = DOT ? fmaf(qe, xe, sum) : fmaf(df, df, sum);
@@ -96,7 +101,7 @@ __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, con
 // minimum on order-preserving words).  rn != null selects the cosine metric: the key of point j
 // is -2 (q . x_j) rn[j] with the dot product summed in the same order.  Returns the list's new
 // k-th key as float bits; with pos2 >= 0, *key2 gets the key at position pos2 of the merged list.
-template <bool ALIGNED, int U, bool HEAD_AHEAD = false>
+template <bool ALIGNED, int U, bool HEAD_AHEAD = false, bool QLATE = false>
 __device__ __forceinline__ unsigned flush_query_exact(const float* __restrict__ qp,
                                                    const float* __restrict__ X, int64_t ldx, int d,
                                                    int jsafe, const int* __restrict__ cbuf, int jbase,
@@ -121,11 +126,11 @@ __device__ __forceinline__ unsigned flush_query_exact(const float* __restrict__ 
     const int jl = j < 0 ? jsafe : j;
     float sum;
     if (rn) {
-        sum = exact_partial<ALIGNED, true, U>(qp, X + (int64_t)jl * ldx, d, part);
+        sum = exact_partial<ALIGNED, true, U, QLATE>(qp, X + (int64_t)jl * ldx, d, part);
         sum += lane_xor<1>(sum);
         sum = (-2.f * sum) * rn[jl];
     } else {
-        sum = exact_partial<ALIGNED, false, U>(qp, X + (int64_t)jl * ldx, d, part);
+        sum = exact_partial<ALIGNED, false, U, QLATE>(qp, X + (int64_t)jl * ldx, d, part);
         sum += lane_xor<1>(sum);
     }
     // candidate c sits in lanes 2c, 2c + 1; the merge wants it in lane c

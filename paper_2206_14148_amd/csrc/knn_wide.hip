@@ -59,6 +59,7 @@ struct WdArgs {
     int j_first, j_end;   // points this launch covers
     int range_len;        // points per range (a multiple of 128)
     int init_from;        // the lists of ranges >= this start empty, the others continue
+    int q_stage;          // 1: the LDS has room for one query row per wave (the stops' exact keys read it there)
 };
 
 __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs a) {
@@ -78,6 +79,8 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
     int* const co_n = co_queue + TQ;                         // [1]
     int* const co_stop = co_n + 1;                           // [3]
     float* const scratch0 = reinterpret_cast<float*>(co_n + 16);  // [waves][2 * 64 + 2 k]
+    // [waves][d] the row of the query a wave is evaluating at a stop (a.q_stage)
+    float* const qstage0 = scratch0 + (size_t)kWdWaves * (2 * kWave + 2 * a.k);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -272,14 +275,30 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
             unsigned t_bits = 0;
             float key_s = kInf;
             bool merged = false;
+            // An exact key is a chain of round trips, one per U groups of four coordinates of the
+            // candidates' rows (98 groups a lane at d = 784), and the query's row would take half
+            // of the registers that are in flight: staged in LDS once per query, it leaves them
+            // all to the candidates - sixteen groups a trip instead of eight, the same sums.
+            const float* qrow = a.Q + (int64_t)r * a.ldq;
+            float* const qst = qstage0 + (size_t)wave * a.d;
+            if (a.q_stage) {
+                for (int g = ln; 4 * g < a.d; g += kWave)
+                    *reinterpret_cast<f32x4*>(qst + 4 * g) = *reinterpret_cast<const f32x4*>(qrow + 4 * g);
+                // (flush_query_exact begins with a wave-level fence)
+            }
             for (int item = 0; item < (o ? 5 : 1); ++item) {
                 const int* cbuf = item == 0 ? ci + q * C : nullptr;
                 const int jb = tile_base + 32 * (item - 1);
                 const int n_c = item == 0 ? cc : min(32, j1 - jb);
                 if (n_c > 0) {
-                    t_bits = flush_query_exact<true, 8, true>(a.Q + (int64_t)r * a.ldq, a.X, a.ldx, a.d, j0, cbuf,
-                                                              jb, n_c, a.lk + lb, a.li + lb, k, my_scratch,
-                                                              a.tsh + r, nullptr, ln, pos_s, &key_s);
+                    if (a.q_stage)
+                        t_bits = flush_query_exact<true, 16, true, true>(qst, a.X, a.ldx, a.d, j0, cbuf, jb, n_c,
+                                                                         a.lk + lb, a.li + lb, k, my_scratch,
+                                                                         a.tsh + r, nullptr, ln, pos_s, &key_s);
+                    else
+                        t_bits = flush_query_exact<true, 8, true>(qrow, a.X, a.ldx, a.d, j0, cbuf, jb, n_c,
+                                                                  a.lk + lb, a.li + lb, k, my_scratch, a.tsh + r,
+                                                                  nullptr, ln, pos_s, &key_s);
                     merged = true;
                 }
             }
@@ -664,7 +683,9 @@ hipError_t launch_wide(const float* Q, int64_t ldq, const float* X, int64_t ldx,
     per = (per + kWdTileX - 1) / kWdTileX * kWdTileX;
     a.range_len = (int)per;
     a.init_from = init_from;
-    const size_t lds = (size_t)wd_lds_bytes(k);
+    // (room left in the LDS for one query row per wave: the stops stage the row they work on)
+    a.q_stage = wd_lds_bytes(k) + (int64_t)kWdWaves * d * 4 <= kPkLdsBytes ? 1 : 0;
+    const size_t lds = (size_t)wd_lds_bytes(k) + (a.q_stage ? (size_t)kWdWaves * d * 4 : 0);
     hipError_t e = raise_lds_limit(knn_wide_kernel, lds);
     if (e != hipSuccess) return e;
     knn_wide_kernel<<<dim3((unsigned)(a.tiles * S)), dim3(64 * kWdWaves), lds, stream>>>(a);
