@@ -44,24 +44,28 @@ constexpr unsigned kInfWord = 0xff800000u;  // key_word(+inf)
 // are issued before the first is used (U = 2), or of U groups: more in flight shorten the wait
 // for a long row and cost registers, which the caller may or may not have to spare.  U does not
 // change the order of the additions.
-// QLATE (aligned rows): the query's groups are read where they are used instead of together with
-// the candidate's - for a query row that the caller has staged in LDS, so that all U groups in
-// flight are the candidate's.
-template <bool ALIGNED, bool DOT, int U, bool QLATE = false>
+// QMODE (aligned rows) 1: the query's groups are read where they are used instead of together with
+// the candidate's - for a query row that the caller has staged in LDS (qp), so that all U groups
+// in flight are the candidate's.  2: the same with the staging done here: the wave copies the
+// row qp to qst (LDS, d floats) behind the requests for the candidate's first U groups, so that
+// the copy shares their round trip.
+template <bool ALIGNED, bool DOT, int U, int QMODE = 0>
 __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, const float* __restrict__ xp,
-                                               int d, int part) {
-    static_assert(!QLATE || ALIGNED, "late query reads: aligned rows only");
+                                               int d, int part, float* qst = nullptr, int lane = 0) {
+    static_assert(QMODE == 0 || ALIGNED, "late query reads: aligned rows only");
     float sum = 0.f;
     const int ng = (d + 3) >> 2;  // groups of four coordinates (the last may be ragged)
-    for (int g0 = part; g0 < ng; g0 += 2 * U) {
-        f32x4 xv[U], qv[QLATE ? 1 : U];
+    const float* const qsrc = QMODE == 2 ? qst : qp;
+    int trip = 0;
+    for (int g0 = part; g0 < ng; g0 += 2 * U, ++trip) {
+        f32x4 xv[U], qv[QMODE ? 1 : U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int g = g0 + 2 * u;
             const int gc = g < ng ? g : part;  // a valid group; its value is not used
             if (ALIGNED) {
                 xv[u] = *reinterpret_cast<const f32x4*>(xp + 4 * gc);
-                if (!QLATE) qv[u] = *reinterpret_cast<const f32x4*>(qp + 4 * gc);
+                if (!QMODE) qv[u] = *reinterpret_cast<const f32x4*>(qp + 4 * gc);
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -71,6 +75,11 @@ __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, con
                 }
             }
         }
+        if (QMODE == 2 && trip == 0) {
+            for (int g = lane; g < ng; g += kWave)
+                *reinterpret_cast<f32x4*>(qst + 4 * g) = *reinterpret_cast<const f32x4*>(qp + 4 * g);
+            wave_sync();
+        }
         // A coordinate past the row's end (or a group past it) leaves the sum as it is: its x is
         // replaced by q (a zero difference), for the dot product by 0, and sum + 0 = sum exactly -
         // a select on the operand, so that the chain stays one straight run of fused multiply-adds
@@ -79,7 +88,7 @@ __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, con
         for (int u = 0; u < U; ++u) {
             const int g = g0 + 2 * u;
             const bool ok_g = g < ng;
-            const f32x4 qg = QLATE ? *reinterpret_cast<const f32x4*>(qp + 4 * (ok_g ? g : part)) : qv[QLATE ? 0 : u];
+            const f32x4 qg = QMODE ? *reinterpret_cast<const f32x4*>(qsrc + 4 * (ok_g ? g : part)) : qv[QMODE ? 0 : u];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const bool ok = ALIGNED ? ok_g : (ok_g && 4 * g + e < d);  // (aligned rows: d % 4 == 0)
@@ -101,7 +110,9 @@ __device__ __forceinline__ float exact_partial(const float* __restrict__ qp, con
 // minimum on order-preserving words).  rn != null selects the cosine metric: the key of point j
 // is -2 (q . x_j) rn[j] with the dot product summed in the same order.  Returns the list's new
 // k-th key as float bits; with pos2 >= 0, *key2 gets the key at position pos2 of the merged list.
-template <bool ALIGNED, int U, bool HEAD_AHEAD = false, bool QLATE = false>
+// QMODE 2: the query's row is staged in LDS first (exact_partial) - in qst, or in the scratch, which
+// must then hold d floats.
+template <bool ALIGNED, int U, bool HEAD_AHEAD = false, int QMODE = 0>
 __device__ __forceinline__ unsigned flush_query_exact(const float* __restrict__ qp,
                                                    const float* __restrict__ X, int64_t ldx, int d,
                                                    int jsafe, const int* __restrict__ cbuf, int jbase,
@@ -109,7 +120,7 @@ __device__ __forceinline__ unsigned flush_query_exact(const float* __restrict__ 
                                                    float* __restrict__ gk, int* __restrict__ gi, int k,
                                                    float* scratch, unsigned* tshr,
                                                    const float* __restrict__ rn, int lane, int pos2 = -1,
-                                                   float* key2 = nullptr) {
+                                                   float* key2 = nullptr, float* qst = nullptr) {
     MergeScratch sc;
     sc.cand_key = scratch;
     sc.cand_idx = reinterpret_cast<int*>(scratch + kWave);
@@ -126,11 +137,11 @@ __device__ __forceinline__ unsigned flush_query_exact(const float* __restrict__ 
     const int jl = j < 0 ? jsafe : j;
     float sum;
     if (rn) {
-        sum = exact_partial<ALIGNED, true, U, QLATE>(qp, X + (int64_t)jl * ldx, d, part);
+        sum = exact_partial<ALIGNED, true, U, QMODE>(qp, X + (int64_t)jl * ldx, d, part, qst ? qst : scratch, lane);
         sum += lane_xor<1>(sum);
         sum = (-2.f * sum) * rn[jl];
     } else {
-        sum = exact_partial<ALIGNED, false, U, QLATE>(qp, X + (int64_t)jl * ldx, d, part);
+        sum = exact_partial<ALIGNED, false, U, QMODE>(qp, X + (int64_t)jl * ldx, d, part, qst ? qst : scratch, lane);
         sum += lane_xor<1>(sum);
     }
     // candidate c sits in lanes 2c, 2c + 1; the merge wants it in lane c

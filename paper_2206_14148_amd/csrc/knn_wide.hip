@@ -277,24 +277,20 @@ __global__ __launch_bounds__(64 * kWdWaves, 1) void knn_wide_kernel(const WdArgs
             bool merged = false;
             // An exact key is a chain of round trips, one per U groups of four coordinates of the
             // candidates' rows (98 groups a lane at d = 784), and the query's row would take half
-            // of the registers that are in flight: staged in LDS once per query, it leaves them
-            // all to the candidates - sixteen groups a trip instead of eight, the same sums.
+            // of the registers that are in flight: staged in LDS (behind the first trip's
+            // requests, knn_exact.h) it leaves them all to the candidates - sixteen groups a trip
+            // instead of eight, the same sums.
             const float* qrow = a.Q + (int64_t)r * a.ldq;
             float* const qst = qstage0 + (size_t)wave * a.d;
-            if (a.q_stage) {
-                for (int g = ln; 4 * g < a.d; g += kWave)
-                    *reinterpret_cast<f32x4*>(qst + 4 * g) = *reinterpret_cast<const f32x4*>(qrow + 4 * g);
-                // (flush_query_exact begins with a wave-level fence)
-            }
             for (int item = 0; item < (o ? 5 : 1); ++item) {
                 const int* cbuf = item == 0 ? ci + q * C : nullptr;
                 const int jb = tile_base + 32 * (item - 1);
                 const int n_c = item == 0 ? cc : min(32, j1 - jb);
                 if (n_c > 0) {
                     if (a.q_stage)
-                        t_bits = flush_query_exact<true, 16, true, true>(qst, a.X, a.ldx, a.d, j0, cbuf, jb, n_c,
-                                                                         a.lk + lb, a.li + lb, k, my_scratch,
-                                                                         a.tsh + r, nullptr, ln, pos_s, &key_s);
+                        t_bits = flush_query_exact<true, 16, true, 2>(qrow, a.X, a.ldx, a.d, j0, cbuf, jb, n_c,
+                                                                      a.lk + lb, a.li + lb, k, my_scratch,
+                                                                      a.tsh + r, nullptr, ln, pos_s, &key_s, qst);
                     else
                         t_bits = flush_query_exact<true, 8, true>(qrow, a.X, a.ldx, a.d, j0, cbuf, jb, n_c,
                                                                   a.lk + lb, a.li + lb, k, my_scratch, a.tsh + r,
