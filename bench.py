@@ -36,12 +36,12 @@ PEAK_HBM_GBS = 8000.0
 # a workload on the kernel named; a run with other sizes, another limit or another kernel reports
 # null.  {workload: (kernel, bytes, profile)}
 PROFILED_TRAFFIC = {
-    "c1_random_d16": ("knn_split_kernel", 12.6e6, "profiles/knn_split_kernel_c1.md"),
+    "c1_random_d16": ("knn_split_kernel", 11.8e6, "profiles/knn_split_kernel_c1.md"),
     "c2_pointcloud_d3": ("knn_lowd_bf16_kernel", 211.4e9, "profiles/knn_lowd_bf16_kernel_c2.md"),
     "c3_imagelike_d784": ("knn_wide_kernel", 50.6e9, "profiles/knn_wide_kernel_c3.md"),
     "c4_clustered_d128": ("knn_packed_kernel", 435.6e9, "profiles/knn_packed_kernel_c4.md"),
     "c5_memsweep_d256": ("knn_packed_kernel", 35.9e9, "profiles/knn_packed_kernel_c5_1GB.md"),  # per launch, two a step
-    "c6_cosine_d100": ("knn_packed_kernel", 8.39e9, "profiles/knn_packed_kernel_c6.md"),
+    "c6_cosine_d100": ("knn_packed_kernel", 8.37e9, "profiles/knn_packed_kernel_c6.md"),
     "c7_l1_d100": ("knn_l1_kernel", 25.8e9, "profiles/knn_l1_kernel_c7.md"),
     "kmv1_d1": ("kmv_lowd_kernel", 1.84e9, "profiles/kmv_lowd_kernel_kmv1.md"),
     "kmv2_d32": ("kmv_mfma_kernel", 1.47e9, "profiles/kmv_mfma_kernel_kmv2.md"),
