@@ -66,6 +66,7 @@ CASES = [
     (7, 100, 5_000, 300, 3, "normal", 4 * W.MB, "l2"),        # streamed-query kernel per block
     (8, 2100, 400_000, 32, 10, "normal", 60 * W.MB, "l2"),    # packed path per block, thresholds carried on
     (9, 2100, 300_000, 272, 10, "normal", 300 * W.MB, "l2"),  # wide path per block (5 blocks), the same
+    (10, 2100, 400_000, 32, 10, "normal", 70 * W.MB, "cosine"),  # cosine on the packed path per block, the same
 ]
 
 
