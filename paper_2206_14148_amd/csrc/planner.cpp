@@ -275,10 +275,19 @@ extern "C" knn_status knn_plan_metric(int64_t m, int64_t n, int32_t d, int32_t k
                         const int64_t rounds = (wgs + kNumCU - 1) / kNumCU;
                         const double range = (double)((slab + S - 1) / S);
                         // larger tiles re-read the points less often: a mild preference
-                        // and fewer ranges mean fewer lists to fill and to merge
+                        // and fewer ranges mean fewer lists to fill and to merge.  One list per
+                        // query in a launch that fits the chip at once (S = 1, one round) always
+                        // works under its own latest threshold and ends with one merge per
+                        // query, which pays with k: measured (ms for search + merge, S = 1 in one
+                        // round against the plan without this term) c5, k = 32: 40.5 + 0.24 / 42.0 +
+                        // 0.75; m = 6e4, n = 2e6, d = 128, k = 50: 26.3 + 0.24 / 27.6 + 0.54; but
+                        // m = 5e4, n = 4e6, d = 128, k = 10: 38.3 + 0.08 / 36.6 + 0.21, and over
+                        // several rounds the choice loses (m = 2e5, n = 1e6, d = 128: 43.5 / 41.3).
+                        const double kk = 0.004 * (double)k;
+                        const double order = (S == 1 && rounds == 1) ? 1.0 - (kk < 0.12 ? kk : 0.12) : 1.0;
                         const double cost = (double)chunks * (double)nslabs * (double)rounds * (double)sets *
                                             (range + 4096.0 + 64.0 * (double)k) * (1.0 + 0.5 / (double)sets) *
-                                            (1.0 + 0.005 * (double)S);
+                                            (1.0 + 0.005 * (double)S) * order;
                         if (best_sets == 0 || cost < best) {
                             best = cost;
                             best_sets = sets;
