@@ -40,7 +40,7 @@ PROFILED_TRAFFIC = {
     "c2_pointcloud_d3": ("knn_lowd_bf16_kernel", 211.4e9, "profiles/knn_lowd_bf16_kernel_c2.md"),
     "c3_imagelike_d784": ("knn_wide_kernel", 50.6e9, "profiles/knn_wide_kernel_c3.md"),
     "c4_clustered_d128": ("knn_packed_kernel", 435.6e9, "profiles/knn_packed_kernel_c4.md"),
-    "c5_memsweep_d256": ("knn_packed_kernel", 35.9e9, "profiles/knn_packed_kernel_c5_1GB.md"),  # per launch, two a step
+    "c5_memsweep_d256": ("knn_packed_kernel", 15.2e9, "profiles/knn_packed_kernel_c5_1GB.md"),  # per launch, two a step
     "c6_cosine_d100": ("knn_packed_kernel", 8.37e9, "profiles/knn_packed_kernel_c6.md"),
     "c7_l1_d100": ("knn_l1_kernel", 25.8e9, "profiles/knn_l1_kernel_c7.md"),
     "kmv1_d1": ("kmv_lowd_kernel", 1.84e9, "profiles/kmv_lowd_kernel_kmv1.md"),
