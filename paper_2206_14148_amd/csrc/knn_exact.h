@@ -1,5 +1,5 @@
 // Exact fp32 keys of the pairs that a bf16 matrix-core filter lets through, and their merge into
-// a query's list: shared by the gfx950 search kernels for d > 8 (knn_split.hip, knn_packed.hip).
+// a query's list: shared by the gfx950 search kernels for d > 8 (knn_split.hip, knn_packed.hip, knn_wide.hip).
 // The expansion of paper section 4.1 only filters there; the keys that enter the lists are the
 // difference form sum_t (q_t - x_t)^2 evaluated here, in one fixed summation order, so that a
 // key is the same bits whichever kernel, tiling or memory limit produced it.
